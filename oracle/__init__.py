@@ -1,0 +1,13 @@
+"""CPU oracle for the HyLRA decode-attention step (test infrastructure only).
+
+Only tests, the smoke check and the benchmark's ``cpu_baseline`` leg may import
+this package.  It shares nothing with the HIP library.
+"""
+from .binding import (  # noqa: F401
+    build,
+    decode_step,
+    full_attn_topk,
+    overlap,
+    reuse_sparse_attn,
+    threads,
+)

@@ -1,0 +1,163 @@
+"""ctypes loader for ``hylra_oracle.c`` (test infrastructure only).
+
+Inputs are numpy arrays, either float64 or uint16 (bf16 bit patterns); a torch
+CPU tensor of dtype bfloat16/float64 is accepted and viewed without copying
+its values.  Outputs are numpy float64 / int32.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+import threading
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "hylra_oracle.c")
+_LIB = os.path.join(_HERE, "libhylra_oracle.so")
+_lock = threading.Lock()
+_lib = None
+
+F64, BF16 = 0, 1
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.run(
+            ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-Wall", "-Wextra",
+             "-o", tmp, _SRC, "-lm"],
+            check=True,
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    with _lock:
+        if _lib is None:
+            build(force=False)
+            lib = ctypes.CDLL(_LIB)
+            vp, i32, i64, f64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_double
+            lib.hylra_oracle_full_attn_topk.argtypes = [i32, i32, i32, i32, i32, i64, i32, f64,
+                                                        vp, vp, vp, vp, vp, vp]
+            lib.hylra_oracle_full_attn_topk.restype = i32
+            lib.hylra_oracle_reuse_sparse_attn.argtypes = [i32, i32, i32, i32, i32, i64, i32, f64,
+                                                           vp, vp, vp, vp, vp]
+            lib.hylra_oracle_reuse_sparse_attn.restype = i32
+            lib.hylra_oracle_decode_step.argtypes = [i32, i32, vp, i32, i32, i32, i32, i64, i32,
+                                                     f64, vp, vp, vp, vp, vp, vp]
+            lib.hylra_oracle_decode_step.restype = i32
+            lib.hylra_oracle_overlap.argtypes = [vp, vp, i32]
+            lib.hylra_oracle_overlap.restype = f64
+            lib.hylra_oracle_threads.restype = i32
+            _lib = lib
+    return _lib
+
+
+def _as_np(x):
+    """numpy view of a float64 / bf16-bit-pattern tensor, C-contiguous."""
+    if not isinstance(x, np.ndarray):  # torch tensor
+        import torch
+
+        x = x.detach().cpu().contiguous()
+        if x.dtype == torch.bfloat16:
+            x = x.view(torch.int16).numpy().view(np.uint16)
+        elif x.dtype == torch.float64:
+            x = x.numpy()
+        else:
+            raise TypeError("oracle takes float64 or bfloat16 tensors, got %s" % x.dtype)
+    if x.dtype == np.float64:
+        kind = F64
+    elif x.dtype == np.uint16:
+        kind = BF16
+    else:
+        raise TypeError("oracle takes float64 or uint16 (bf16 bits) arrays, got %s" % x.dtype)
+    return np.ascontiguousarray(x), kind
+
+
+def _triple(q, K, V):
+    q, kq = _as_np(q)
+    K, kk = _as_np(K)
+    V, kv = _as_np(V)
+    if not (kq == kk == kv):
+        raise TypeError("q, K, V must share one element type")
+    B, Hq, d = q.shape
+    Bk, Hkv, N, dk = K.shape
+    if (Bk, dk) != (B, d) or V.shape != K.shape:
+        raise ValueError("shape mismatch: q %s K %s V %s" % (q.shape, K.shape, V.shape))
+    return q, K, V, kq, B, Hq, Hkv, d, N
+
+
+def _ptr(a):
+    return ctypes.c_void_p(a.ctypes.data) if a is not None else None
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise RuntimeError("%s failed with oracle status %d" % (what, rc))
+
+
+def full_attn_topk(q, K, V, k, scale=0.0, want_out=True, want_idx=True, want_shat=False):
+    """Full layer of Algorithm 2: returns (out [B,Hq,d], idx [B,Hkv,k], shat or None)."""
+    q, K, V, kind, B, Hq, Hkv, d, N = _triple(q, K, V)
+    out = np.empty((B, Hq, d), np.float64) if want_out else None
+    idx = np.empty((B, Hkv, k), np.int32) if want_idx else None
+    shat = np.empty((B, Hkv, N), np.float64) if want_shat else None
+    rc = _load().hylra_oracle_full_attn_topk(kind, B, Hq, Hkv, d, N, int(k), float(scale),
+                                             _ptr(q), _ptr(K), _ptr(V), _ptr(out), _ptr(idx),
+                                             _ptr(shat))
+    _check(rc, "full_attn_topk")
+    return out, idx, shat
+
+
+def reuse_sparse_attn(q, K, V, idx, scale=0.0):
+    """Reuse layer of Algorithm 2: out [B,Hq,d] over the rows named by idx [B,Hkv,k]."""
+    q, K, V, kind, B, Hq, Hkv, d, N = _triple(q, K, V)
+    idx = np.ascontiguousarray(np.asarray(idx, dtype=np.int32))
+    if idx.shape[:2] != (B, Hkv):
+        raise ValueError("idx shape %s does not match [B=%d, Hkv=%d, k]" % (idx.shape, B, Hkv))
+    k = idx.shape[2]
+    out = np.empty((B, Hq, d), np.float64)
+    rc = _load().hylra_oracle_reuse_sparse_attn(kind, B, Hq, Hkv, d, N, k, float(scale),
+                                                _ptr(q), _ptr(K), _ptr(V), _ptr(idx), _ptr(out))
+    _check(rc, "reuse_sparse_attn")
+    return out
+
+
+def decode_step(policy, q_l, K_l, V_l, k, scale=0.0):
+    """Algorithm 2 over all layers.  Returns (outs list, idx_final, idx_trace [L,B,Hkv,k])."""
+    L = len(policy)
+    trip = [_triple(q_l[l], K_l[l], V_l[l]) for l in range(L)]
+    kind, B, Hq, Hkv, d, N = trip[0][3:]
+    for t in trip:
+        if t[3:] != (kind, B, Hq, Hkv, d, N):
+            raise ValueError("all layers must share one shape and element type")
+    pol = np.ascontiguousarray(np.asarray(policy, dtype=np.uint8))
+    outs = [np.empty((B, Hq, d), np.float64) for _ in range(L)]
+    idx = np.full((B, Hkv, k), -1, np.int32)
+    trace = np.empty((L, B, Hkv, k), np.int32)
+    arr = ctypes.c_void_p * L
+    rc = _load().hylra_oracle_decode_step(
+        kind, L, _ptr(pol), B, Hq, Hkv, d, N, int(k), float(scale),
+        arr(*[t[0].ctypes.data for t in trip]), arr(*[t[1].ctypes.data for t in trip]),
+        arr(*[t[2].ctypes.data for t in trip]), arr(*[o.ctypes.data for o in outs]),
+        _ptr(idx), _ptr(trace))
+    _check(rc, "decode_step")
+    return outs, idx, trace
+
+
+def overlap(a, b):
+    """Overlap ratio |a ∩ b| / k of two index sets of equal size (Eq. 2)."""
+    a = np.ascontiguousarray(np.asarray(a, dtype=np.int32).ravel())
+    b = np.ascontiguousarray(np.asarray(b, dtype=np.int32).ravel())
+    if a.size != b.size:
+        raise ValueError("sets must have equal size")
+    return _load().hylra_oracle_overlap(_ptr(a), _ptr(b), a.size)
+
+
+def threads():
+    return _load().hylra_oracle_threads()

@@ -1,0 +1,402 @@
+"""Pins for the CPU oracle: everything here checks ``oracle/`` against something that is
+not the oracle itself -- hand-worked values (tests/golden), an independent pure-Python brute
+force on tiny inputs, closed forms, invariants of softmax attention, and library routines
+(torch SDPA / topk in fp64) as a referee.  No GPU needed.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+LN = {"LN2": math.log(2.0), "LN4": math.log(4.0), "HALF_LN2": 0.5 * math.log(2.0)}
+
+
+def read_golden(name):
+    out = {}
+    with open(os.path.join(GOLD, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, val = line.split(":", 1)
+            rows = [[LN[t] if t in LN else float(t) for t in r.split()] for r in val.split("|")]
+            out[key.strip()] = np.array(rows if len(rows) > 1 else rows[0], dtype=np.float64)
+    return out
+
+
+# --------------------------------------------------------------------------------------
+# 1. hand-worked examples
+# --------------------------------------------------------------------------------------
+def test_golden_single_head():
+    g = read_golden("single_head_4tok.txt")
+    q = g["q"].reshape(1, 1, 4)
+    K = g["K"].reshape(1, 1, 4, 4)
+    V = g["V"].reshape(1, 1, 4, 4)
+    out, idx, shat = oracle.full_attn_topk(q, K, V, 2, want_shat=True)
+    np.testing.assert_allclose(shat[0, 0], g["scores"], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(out[0, 0], g["full_out"], rtol=0, atol=1e-15)
+    for k in (1, 2, 3, 4):
+        _, idx, _ = oracle.full_attn_topk(q, K, V, k)
+        assert idx[0, 0].tolist() == g["top%d" % k].astype(int).reshape(-1).tolist()
+    for rows, key in (((1, 2), "sparse_on_1_2"), ((3,), "sparse_on_3"), ((0, 2), "sparse_on_0_2")):
+        o = oracle.reuse_sparse_attn(q, K, V, np.array(rows, np.int32).reshape(1, 1, -1))
+        np.testing.assert_allclose(o[0, 0], g[key], rtol=0, atol=1e-15)
+    # probabilities: recover them with one-hot V
+    eye = np.eye(4).reshape(1, 1, 4, 4)
+    p, _, _ = oracle.full_attn_topk(q, K, eye, 1)
+    np.testing.assert_allclose(p[0, 0], g["probs"], rtol=0, atol=1e-15)
+
+
+def test_golden_gqa():
+    g = read_golden("gqa_4tok.txt")
+    q = np.stack([g["q0"], g["q1"]]).reshape(1, 2, 4)
+    K = g["K"].reshape(1, 1, 4, 4)
+    V = g["V"].reshape(1, 1, 4, 4)
+    out, _, shat = oracle.full_attn_topk(q, K, V, 1, want_shat=True)
+    np.testing.assert_allclose(shat[0, 0], g["mean_scores"], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(out[0, 0], g["full_out0"], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(out[0, 1], g["full_out1"], rtol=0, atol=1e-15)
+    for k in (1, 2, 3):
+        _, idx, _ = oracle.full_attn_topk(q, K, V, k)
+        assert idx[0, 0].tolist() == g["top%d" % k].astype(int).reshape(-1).tolist()
+    o = oracle.reuse_sparse_attn(q, K, V, np.array([0, 2], np.int32).reshape(1, 1, 2))
+    np.testing.assert_allclose(o[0, 0], g["sparse_on_0_2_out0"], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(o[0, 1], g["sparse_on_0_2_out1"], rtol=0, atol=1e-15)
+
+
+def test_golden_through_bf16_entry():
+    """The bf16 entry point converts bit patterns exactly: an example whose inputs are
+    bf16-exact gives the same hand-worked numbers.  Scores (0,1,2,0) -> weights (1,e,e^2,1)."""
+    q = torch.tensor([[[2.0, 0, 0, 0]]], dtype=torch.bfloat16)
+    K = torch.tensor([[[[0.0, 0, 0, 0], [1, 0, 0, 0], [2, 0, 0, 0], [0, 0, 0, 0]]]], dtype=torch.bfloat16)
+    V = torch.tensor([[[[1.0, 0, 0, 0], [0, 1, 0, 0], [1, 1, 0, 0], [0, 0, 0, 0]]]], dtype=torch.bfloat16)
+    out, idx, _ = oracle.full_attn_topk(q, K, V, 3)
+    e = math.e
+    z = 2 + e + e * e
+    np.testing.assert_allclose(out[0, 0], [(1 + e * e) / z, (e + e * e) / z, 0, 0], rtol=1e-15)
+    assert idx[0, 0].tolist() == [0, 1, 2]
+
+
+# --------------------------------------------------------------------------------------
+# 2. independent brute force (pure Python, exact-ish sums) on tiny inputs
+# --------------------------------------------------------------------------------------
+def brute_full(q, K, V, k):
+    B, Hq, d = q.shape
+    _, Hkv, N, _ = K.shape
+    G = Hq // Hkv
+    out = np.zeros((B, Hq, d))
+    idx = np.zeros((B, Hkv, k), np.int64)
+    for b in range(B):
+        for kv in range(Hkv):
+            heads = [h for h in range(Hq) if h // G == kv]
+            per_head = []
+            for h in heads:
+                s = [math.fsum(float(q[b, h, c]) * float(K[b, kv, j, c]) for c in range(d)) / math.sqrt(d)
+                     for j in range(N)]
+                per_head.append(s)
+                top = max(s)
+                e = [math.exp(x - top) for x in s]
+                z = math.fsum(e)
+                for c in range(d):
+                    out[b, h, c] = math.fsum(e[j] * float(V[b, kv, j, c]) for j in range(N)) / z
+            mean = [math.fsum(s[j] for s in per_head) / G for j in range(N)]
+            order = sorted(range(N), key=lambda j: (-mean[j], j))
+            idx[b, kv] = sorted(order[:k])
+    return out, idx
+
+
+def brute_sparse(q, K, V, idx):
+    B, Hq, d = q.shape
+    _, Hkv, N, _ = K.shape
+    G = Hq // Hkv
+    out = np.zeros((B, Hq, d))
+    for b in range(B):
+        for h in range(Hq):
+            kv = h // G
+            rows = [int(t) for t in idx[b, kv] if t >= 0]
+            s = [math.fsum(float(q[b, h, c]) * float(K[b, kv, j, c]) for c in range(d)) / math.sqrt(d)
+                 for j in rows]
+            top = max(s)
+            e = [math.exp(x - top) for x in s]
+            z = math.fsum(e)
+            for c in range(d):
+                out[b, h, c] = math.fsum(e[i] * float(V[b, kv, j, c]) for i, j in enumerate(rows)) / z
+    return out
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_brute_force_tiny(seed):
+    rng = np.random.RandomState(seed)
+    B = rng.randint(1, 3)
+    Hkv = rng.randint(1, 4)
+    G = rng.randint(1, 4)
+    d = int(rng.choice([2, 3, 8]))
+    N = rng.randint(3, 17)
+    q = rng.randn(B, Hkv * G, d)
+    K = rng.randn(B, Hkv, N, d)
+    V = rng.randn(B, Hkv, N, d)
+    for k in sorted({1, 2, N // 2 + 1, N}):
+        out, idx, _ = oracle.full_attn_topk(q, K, V, k)
+        bo, bi = brute_full(q, K, V, k)
+        np.testing.assert_allclose(out, bo, rtol=1e-12, atol=1e-14)
+        assert np.array_equal(idx, bi)
+        pick = np.stack([[np.sort(rng.permutation(N)[:k]) for _ in range(Hkv)] for _ in range(B)])
+        np.testing.assert_allclose(oracle.reuse_sparse_attn(q, K, V, pick),
+                                   brute_sparse(q, K, V, pick), rtol=1e-12, atol=1e-14)
+
+
+def test_brute_force_with_ties():
+    """Integer-valued keys make many exactly tied scores; lower position must win."""
+    rng = np.random.RandomState(11)
+    q = rng.randint(-1, 2, size=(1, 4, 4)).astype(np.float64)
+    K = rng.randint(-1, 2, size=(1, 2, 24, 4)).astype(np.float64)
+    V = rng.randn(1, 2, 24, 4)
+    for k in range(1, 25):
+        _, idx, _ = oracle.full_attn_topk(q, K, V, k)
+        _, bi = brute_full(q, K, V, k)
+        assert np.array_equal(idx, bi), k
+
+
+# --------------------------------------------------------------------------------------
+# 3. library referee: single-query SDPA and topk in fp64
+# --------------------------------------------------------------------------------------
+@pytest.mark.parametrize("G,d", [(1, 16), (4, 64), (7, 32)])
+def test_against_torch_sdpa_and_topk(G, d):
+    torch.manual_seed(G * 100 + d)
+    B, Hkv, N, k = 2, 3, 200, 17
+    q = torch.randn(B, Hkv * G, d, dtype=torch.float64)
+    K = torch.randn(B, Hkv, N, d, dtype=torch.float64)
+    V = torch.randn(B, Hkv, N, d, dtype=torch.float64)
+    out, idx, shat = oracle.full_attn_topk(q, K, V, k, want_shat=True)
+    # the library's grouped-query convention: consecutive query heads share one KV head
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        q.unsqueeze(2), K.repeat_interleave(G, dim=1), V.repeat_interleave(G, dim=1)).squeeze(2)
+    np.testing.assert_allclose(out, ref.numpy(), rtol=1e-11, atol=1e-13)
+    logits = torch.einsum("bhgd,bhnd->bhgn", q.view(B, Hkv, G, d), K) / math.sqrt(d)
+    mean = logits.mean(dim=2)
+    np.testing.assert_allclose(shat, mean.numpy(), rtol=1e-11, atol=1e-13)
+    tk = torch.topk(mean, k, dim=-1).indices.sort(dim=-1).values
+    assert np.array_equal(idx, tk.numpy())
+    # reuse branch == SDPA over the gathered rows
+    gi = tk.unsqueeze(-1).expand(-1, -1, -1, d)
+    Ks, Vs = K.gather(2, gi), V.gather(2, gi)
+    ref_s = torch.nn.functional.scaled_dot_product_attention(
+        q.unsqueeze(2), Ks.repeat_interleave(G, dim=1), Vs.repeat_interleave(G, dim=1)).squeeze(2)
+    np.testing.assert_allclose(oracle.reuse_sparse_attn(q, K, V, idx), ref_s.numpy(),
+                               rtol=1e-11, atol=1e-13)
+
+
+def test_explicit_scale_argument():
+    rng = np.random.RandomState(5)
+    q, K, V = rng.randn(1, 2, 8), rng.randn(1, 1, 30, 8), rng.randn(1, 1, 30, 8)
+    a, _, sa = oracle.full_attn_topk(q, K, V, 4, scale=0.0, want_shat=True)
+    b, _, sb = oracle.full_attn_topk(q, K, V, 4, scale=1.0 / math.sqrt(8), want_shat=True)
+    np.testing.assert_allclose(a, b, rtol=1e-14)
+    c, _, sc = oracle.full_attn_topk(q * 2.0, K, V, 4, scale=0.5 / math.sqrt(8), want_shat=True)
+    np.testing.assert_allclose(a, c, rtol=1e-13)
+    np.testing.assert_allclose(sa, sc, rtol=1e-13)
+
+
+# --------------------------------------------------------------------------------------
+# 4. invariants and closed forms
+# --------------------------------------------------------------------------------------
+def _rand(seed, B=2, Hkv=2, G=2, N=40, d=8):
+    rng = np.random.RandomState(seed)
+    return rng.randn(B, Hkv * G, d), rng.randn(B, Hkv, N, d), rng.randn(B, Hkv, N, d)
+
+
+def test_weights_sum_to_one_and_constant_values():
+    q, K, V = _rand(1)
+    ones = np.ones_like(V)
+    out, _, _ = oracle.full_attn_topk(q, K, ones * 3.25, 3)
+    np.testing.assert_allclose(out, 3.25, rtol=1e-14)
+    idx = np.tile(np.array([1, 5, 9], np.int32), (2, 2, 1))
+    np.testing.assert_allclose(oracle.reuse_sparse_attn(q, K, ones * -2.5, idx), -2.5, rtol=1e-14)
+
+
+def test_output_in_convex_hull():
+    q, K, V = _rand(2)
+    out, idx, _ = oracle.full_attn_topk(q, K, V, 6)
+    G = 2
+    for b in range(2):
+        for h in range(4):
+            lo, hi = V[b, h // G].min(axis=0), V[b, h // G].max(axis=0)
+            assert np.all(out[b, h] >= lo - 1e-12) and np.all(out[b, h] <= hi + 1e-12)
+    o = oracle.reuse_sparse_attn(q, K, V, idx)
+    for b in range(2):
+        for h in range(4):
+            rows = V[b, h // G][idx[b, h // G]]
+            assert np.all(o[b, h] >= rows.min(axis=0) - 1e-12)
+            assert np.all(o[b, h] <= rows.max(axis=0) + 1e-12)
+
+
+def test_full_equals_sparse_when_k_is_context_length():
+    q, K, V = _rand(3)
+    N = K.shape[2]
+    out, idx, _ = oracle.full_attn_topk(q, K, V, N)
+    assert np.array_equal(idx, np.broadcast_to(np.arange(N), idx.shape))
+    np.testing.assert_allclose(oracle.reuse_sparse_attn(q, K, V, idx), out, rtol=1e-13, atol=1e-15)
+
+
+def test_reuse_invariant_under_index_permutation_and_padding():
+    q, K, V = _rand(4)
+    rng = np.random.RandomState(0)
+    idx = np.stack([[np.sort(rng.permutation(40)[:9]) for _ in range(2)] for _ in range(2)]).astype(np.int32)
+    base = oracle.reuse_sparse_attn(q, K, V, idx)
+    perm = idx[:, :, rng.permutation(9)]
+    np.testing.assert_allclose(oracle.reuse_sparse_attn(q, K, V, perm), base, rtol=1e-13)
+    padded = np.concatenate([np.full((2, 2, 3), -1, np.int32), idx, np.full((2, 2, 2), -1, np.int32)], axis=2)
+    np.testing.assert_allclose(oracle.reuse_sparse_attn(q, K, V, padded), base, rtol=1e-13)
+
+
+def test_cache_row_permutation_equivariance():
+    q, K, V = _rand(5)
+    N = K.shape[2]
+    perm = np.random.RandomState(1).permutation(N)
+    out, idx, _ = oracle.full_attn_topk(q, K, V, 7)
+    out_p, idx_p, _ = oracle.full_attn_topk(q, K[:, :, perm], V[:, :, perm], 7)
+    np.testing.assert_allclose(out_p, out, rtol=1e-12)
+    # scores are distinct with probability one, so the selected SET maps through the permutation
+    for b in range(2):
+        for g in range(2):
+            assert set(perm[idx_p[b, g]].tolist()) == set(idx[b, g].tolist())
+
+
+def test_key_shift_invariance():
+    """Adding one vector u to every key adds q.u/sqrt(d) to every score of a head: softmax
+    and the ranking of the group mean are unchanged."""
+    q, K, V = _rand(6)
+    u = np.random.RandomState(2).randn(8)
+    out, idx, _ = oracle.full_attn_topk(q, K, V, 5)
+    out_s, idx_s, _ = oracle.full_attn_topk(q, K + u, V, 5)
+    np.testing.assert_allclose(out_s, out, rtol=1e-10)
+    assert np.array_equal(idx, idx_s)
+
+
+def test_dominant_key_limit():
+    """One key far along q: softmax collapses onto that row and it is the first pick."""
+    rng = np.random.RandomState(7)
+    d, N = 8, 30
+    q = rng.randn(1, 1, d)
+    K, V = rng.randn(1, 1, N, d), rng.randn(1, 1, N, d)
+    K[0, 0, 17] = 200.0 * q[0, 0] / np.linalg.norm(q[0, 0])
+    out, idx, _ = oracle.full_attn_topk(q, K, V, 1)
+    np.testing.assert_allclose(out[0, 0], V[0, 0, 17], rtol=1e-9, atol=1e-12)
+    assert idx[0, 0, 0] == 17
+
+
+def test_two_token_closed_form():
+    """Two keys: p0 = sigmoid(s0 - s1)."""
+    d = 4
+    q = np.array([[[1.0, -2.0, 0.5, 3.0]]])
+    K = np.array([[[[0.3, 0.1, -1.0, 0.2], [-0.4, 0.6, 0.9, 0.1]]]])
+    V = np.array([[[[1.0, 10.0, 100.0, 1000.0], [2.0, 20.0, 200.0, 2000.0]]]])
+    s = (K[0, 0] @ q[0, 0]) / math.sqrt(d)
+    p0 = 1.0 / (1.0 + math.exp(s[1] - s[0]))
+    out, idx, _ = oracle.full_attn_topk(q, K, V, 1)
+    np.testing.assert_allclose(out[0, 0], p0 * V[0, 0, 0] + (1 - p0) * V[0, 0, 1], rtol=1e-14)
+    assert idx[0, 0, 0] == (0 if s[0] >= s[1] else 1)
+
+
+def test_group_of_one_equals_per_head_algorithm():
+    """G = 1: each head ranks by its own scores (the paper's single-head statement)."""
+    q, K, V = _rand(8, Hkv=3, G=1)
+    out, idx, shat = oracle.full_attn_topk(q, K, V, 5, want_shat=True)
+    for h in range(3):
+        o1, i1, s1 = oracle.full_attn_topk(q[:, h:h + 1], K[:, h:h + 1], V[:, h:h + 1], 5, want_shat=True)
+        np.testing.assert_array_equal(o1[:, 0], out[:, h])
+        np.testing.assert_array_equal(i1[:, 0], idx[:, h])
+
+
+def test_grouping_is_consecutive_heads():
+    """Heads 0..G-1 read KV head 0, the next G read KV head 1: swapping the two KV heads
+    must swap the two halves of the output."""
+    q, K, V = _rand(9, B=1, Hkv=2, G=3)
+    out, idx, _ = oracle.full_attn_topk(q, K, V, 4)
+    qs = np.concatenate([q[:, 3:], q[:, :3]], axis=1)
+    out_s, idx_s, _ = oracle.full_attn_topk(qs, K[:, ::-1], V[:, ::-1], 4)
+    np.testing.assert_array_equal(out_s[:, :3], out[:, 3:])
+    np.testing.assert_array_equal(out_s[:, 3:], out[:, :3])
+    np.testing.assert_array_equal(idx_s[:, 0], idx[:, 1])
+
+
+def test_full_output_is_dense_not_topk_restricted():
+    """The Full branch attends over ALL rows; only the Reuse branch is restricted."""
+    q, K, V = _rand(10)
+    out, idx, _ = oracle.full_attn_topk(q, K, V, 5)
+    sparse = oracle.reuse_sparse_attn(q, K, V, idx)
+    assert np.max(np.abs(out - sparse)) > 1e-3
+
+
+# --------------------------------------------------------------------------------------
+# 5. the layer chain (Alg. 2 outer loop)
+# --------------------------------------------------------------------------------------
+def _layers(L, seed, **kw):
+    data = [_rand(seed + l, **kw) for l in range(L)]
+    return [x[0] for x in data], [x[1] for x in data], [x[2] for x in data]
+
+
+def test_chain_all_full_equals_independent_calls():
+    qs, Ks, Vs = _layers(3, 20)
+    outs, idx, trace = oracle.decode_step([0, 0, 0], qs, Ks, Vs, 6)
+    for l in range(3):
+        o, i, _ = oracle.full_attn_topk(qs[l], Ks[l], Vs[l], 6)
+        np.testing.assert_array_equal(outs[l], o)
+        np.testing.assert_array_equal(trace[l], i)
+    np.testing.assert_array_equal(idx, trace[2])
+
+
+def test_chain_reuse_inherits_from_last_full_layer():
+    qs, Ks, Vs = _layers(5, 30)
+    policy = [0, 1, 1, 0, 1]
+    outs, idx, trace = oracle.decode_step(policy, qs, Ks, Vs, 6)
+    _, i0, _ = oracle.full_attn_topk(qs[0], Ks[0], Vs[0], 6)
+    _, i3, _ = oracle.full_attn_topk(qs[3], Ks[3], Vs[3], 6)
+    for l, src in ((0, i0), (1, i0), (2, i0), (3, i3), (4, i3)):
+        np.testing.assert_array_equal(trace[l], src)
+    for l, src in ((1, i0), (2, i0), (4, i3)):
+        np.testing.assert_array_equal(outs[l], oracle.reuse_sparse_attn(qs[l], Ks[l], Vs[l], src))
+    np.testing.assert_array_equal(idx, i3)
+    assert not np.array_equal(i0, i3)
+
+
+def test_chain_rejects_reuse_at_layer_zero():
+    qs, Ks, Vs = _layers(2, 40)
+    with pytest.raises(RuntimeError):
+        oracle.decode_step([1, 0], qs, Ks, Vs, 4)
+
+
+def test_jump3_and_full_baseline_policies_are_plain_policy_vectors():
+    """The paper's two baselines: all-Full, and a fixed stride of 3 between Full layers."""
+    qs, Ks, Vs = _layers(7, 50)
+    jump3 = [0 if l % 3 == 0 else 1 for l in range(7)]
+    _, _, trace = oracle.decode_step(jump3, qs, Ks, Vs, 5)
+    for l in range(7):
+        src = 3 * (l // 3)
+        np.testing.assert_array_equal(trace[l], trace[src])
+
+
+# --------------------------------------------------------------------------------------
+# 6. overlap ratio (Eq. 2) and the planted-set statistics of the synthetic inputs
+# --------------------------------------------------------------------------------------
+def test_overlap_ratio():
+    assert oracle.overlap([1, 2, 3, 4], [3, 4, 5, 6]) == 0.5
+    assert oracle.overlap([1, 2, 3, 4], [4, 3, 2, 1]) == 1.0
+    assert oracle.overlap([1, 2], [3, 4]) == 0.0
+
+
+def test_argument_errors():
+    q, K, V = _rand(60)
+    with pytest.raises(RuntimeError):
+        oracle.full_attn_topk(q, K, V, 0)
+    with pytest.raises(RuntimeError):
+        oracle.full_attn_topk(q, K, V, K.shape[2] + 1)
+    bad = np.full((2, 2, 3), K.shape[2], np.int32)
+    with pytest.raises(RuntimeError):
+        oracle.reuse_sparse_attn(q, K, V, bad)
