@@ -1,0 +1,214 @@
+#!/usr/bin/env python3
+"""Benchmark of the HyLRA decode-attention hot path on one MI355X.
+
+A "step" is one hylra_decode_step: every layer of the workload, Full layers (streaming
+attention + top-k) and Reuse layers (gather attention) in policy order, for one decode token
+per sequence.  Inputs are synthetic, drawn on the GPU, and resident in HBM before timing.
+
+Prints ONE JSON line: tokens/s over all layers, the roofline position of the dominant kernel
+(measured live with HIP events on the launch stream), and the CPU oracle timed on the host
+cores on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
+
+# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE,
+# scaled by the copy-kernel calibration); see profiles/.  None until measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama3_8b_32k")
+    ap.add_argument("--policy", default="hylra", choices=["hylra", "full", "jump3"],
+                    help="hylra = the workload's policy; full = every layer Full; jump3 = Full every 3rd layer")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--probe", action="store_true", help="also time the plain copy / read kernels")
+    ap.add_argument("--opt", action="append", default=[], help="library option name=value")
+    args = ap.parse_args()
+
+    world = int(os.environ.get("WORLD_SIZE", "1"))
+    if args.gpus != 1 or world != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus %d / WORLD_SIZE %d is not supported" % (args.gpus, world), file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2602_00777_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    w = synth.WORKLOADS[args.workload]
+    policy = w.policy()
+    if args.policy == "full":
+        policy[:] = synth.FULL
+    elif args.policy == "jump3":
+        policy[:] = synth.REUSE
+        policy[::3] = synth.FULL
+    n_full = int((policy == synth.FULL).sum())
+    n_reuse = int((policy == synth.REUSE).sum())
+
+    t0 = time.time()
+    planted = synth.planted_positions(w)
+    data = []
+    for l in range(w.n_layers):
+        data.append(synth.make_layer(w, l, planted[l], dev))
+    torch.cuda.synchronize()
+    log("generated %s: %d layers, %.1f GiB of KV in %.1f s" %
+        (w.name, w.n_layers, w.n_layers * w.kv_bytes_per_layer() / 2**30, time.time() - t0))
+    qs, Ks, Vs = [x[0] for x in data], [x[1] for x in data], [x[2] for x in data]
+
+    ctx = binding.Context(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ctx_len, w.top_k)
+    for o in args.opt:
+        name, val = o.split("=")
+        ctx.set_option(name, int(val))
+    run, outs, idx_buf = ctx.prepare_step(policy, qs, Ks, Vs, w.top_k)
+
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    tokens_per_s = w.batch / (elapsed / args.steps)
+
+    # per-kernel durations: the same steps again, every launch bracketed by HIP events on
+    # the launch stream
+    ctx.profile_enable(True)
+    ctx.profile_reset()
+    prof_steps = max(1, min(args.steps, 4096 // (2 * w.n_layers)))
+    for _ in range(prof_steps):
+        run()
+    torch.cuda.synchronize()
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    kernels = {name: {"launches": n, "avg_us": (1e3 * ms / n if n else None)}
+               for name, (n, ms) in prof.items() if n}
+
+    B, Hq, Hkv, d, N, k = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ctx_len, w.top_k
+    small = B * Hq * d * 2 + B * Hq * d * 4 + B * Hkv * k * 4         # q + out + idx
+    full_bytes = 4 * B * Hkv * N * d + small
+    reuse_bytes = 4 * B * Hkv * k * d + small
+
+    def roof(kernel, nbytes):
+        kk = kernels.get(kernel)
+        if not kk:
+            return None
+        gbs = nbytes / (kk["avg_us"] * 1e-6) / 1e9
+        return {"bound": "hbm", "kernel": kernel, "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
+                "algorithmic_bytes": nbytes, "avg_us": round(kk["avg_us"], 2),
+                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, kernel))}
+
+    full_time = (kernels.get("full_attn", {}).get("avg_us") or 0) * n_full
+    reuse_time = (kernels.get("reuse_attn", {}).get("avg_us") or 0) * n_reuse
+    dominant = ("full_attn", full_bytes) if full_time >= reuse_time else ("reuse_attn", reuse_bytes)
+    roofline = roof(*dominant)
+    other = roof("reuse_attn", reuse_bytes) if dominant[0] == "full_attn" else roof("full_attn", full_bytes)
+
+    probe = None
+    if args.probe:
+        nbytes = 4 << 30
+        src = torch.empty(nbytes, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        sink = torch.empty(16384, dtype=torch.uint8, device=dev)
+        ctx.profile_enable(True)
+        probe = {}
+        for name, fn in (("copy", lambda: ctx.probe_copy(dst, src)), ("read", lambda: ctx.probe_read(src, sink))):
+            fn()
+            torch.cuda.synchronize()
+            ctx.profile_reset()
+            for _ in range(10):
+                fn()
+            torch.cuda.synchronize()
+            n, ms = ctx.profile_read()["probe"]
+            moved = nbytes * (2 if name == "copy" else 1)
+            probe[name + "_GBps"] = round(moved / (ms / n * 1e-3) / 1e9, 1)
+        ctx.profile_enable(False)
+        del src, dst
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(w, policy, qs, Ks, Vs, idx_buf, n_full, n_reuse)
+
+    line = {
+        "metric": "decode-attention tokens/sec (all layers) at 32K ctx" if w.ctx_len == 32768
+                  else "decode-attention tokens/sec (all layers)",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "description": w.description, "policy": args.policy,
+                   "n_layers": w.n_layers, "full_layers": n_full, "reuse_layers": n_reuse,
+                   "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d, "ctx_len": N,
+                   "top_k": k, "kv_dtype": "bf16", "accumulate": "f32"},
+        "roofline": roofline,
+        "roofline_other": other,
+        "kernels_us": {n: round(v["avg_us"], 2) for n, v in kernels.items()},
+        "cpu_baseline": cpu,
+    }
+    if probe:
+        line["probe"] = probe
+    ctx.close()
+    print(json.dumps(line), flush=True)
+
+
+def cpu_baseline(w, policy, qs, Ks, Vs, idx_buf, n_full, n_reuse):
+    """The oracle as it stands, on the host cores, on a bounded sample of the same workload:
+    the first Full layers and the first Reuse layers of the step (up to 3 each, up to 8
+    sequences of the batch), in policy order with the oracle's own index sets; the step time
+    is n_full * mean(t_full) + n_reuse * mean(t_reuse), scaled to the whole batch."""
+    import oracle
+
+    threads = oracle.threads()
+    nb = min(w.batch, 8)
+    t_full, t_reuse, idx = [], [], None
+    for l in range(w.n_layers):
+        is_full = policy[l] == 0
+        if (is_full and len(t_full) >= 3) or (not is_full and (len(t_reuse) >= 3 or idx is None)):
+            continue
+        q, K, V = qs[l][:nb].cpu(), Ks[l][:nb].cpu(), Vs[l][:nb].cpu()
+        t0 = time.perf_counter()
+        if is_full:
+            _, idx, _ = oracle.full_attn_topk(q, K, V, w.top_k)
+            t_full.append(time.perf_counter() - t0)
+        else:
+            oracle.reuse_sparse_attn(q, K, V, idx)
+            t_reuse.append(time.perf_counter() - t0)
+        if len(t_full) >= 3 and (len(t_reuse) >= 3 or n_reuse == 0):
+            break
+    mf = sum(t_full) / len(t_full)
+    mr = sum(t_reuse) / len(t_reuse) if t_reuse else 0.0
+    scale = w.batch / nb
+    step_s = (n_full * mf + n_reuse * mr) * scale
+    return {"value": round(w.batch / step_s, 4), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "%d Full layers (mean %.3f s) and %d Reuse layers (mean %.4f s) on %d of %d "
+                      "sequences; step extrapolated as (%d*t_full + %d*t_reuse) * %g"
+                      % (len(t_full), mf, len(t_reuse), mr, nb, w.batch, n_full, n_reuse, scale)}
+
+
+if __name__ == "__main__":
+    main()

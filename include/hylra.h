@@ -1,0 +1,169 @@
+/*
+ * libhylra -- the per-layer decode-attention step of HyLRA (Hybrid Layer Reuse
+ * Attention) for one MI355X (gfx950), as a C ABI.
+ *
+ * The operations follow the paper's Algorithm 2 ("Hybrid Inter-Layer Top-K Reuse
+ * Attention") with attention as in Eq. 1:
+ *
+ *   Full layer   S = q K^T / sqrt(d);  I = TopK(S, k);  O = Softmax(S) V over ALL rows
+ *   Reuse layer  I inherited from the previous layer;  O = Attention(q, K[I], V[I])
+ *   Step         the layers in order, a policy vector choosing the branch per layer
+ *
+ * The paper states the algorithm for one head.  Here several query heads may
+ * share one KV head (query head h reads KV head h / G, G = n_q_heads /
+ * n_kv_heads) and there is ONE index set per (batch, KV head): positions are
+ * ranked by the mean over the group's G heads of the scaled scores; ties go to
+ * the lower position; the k positions are written in ascending order.
+ *
+ * General conventions
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller unless marked
+ *     HOST.  The library never frees or keeps caller memory.
+ *   - q   bf16 [B, Hq, d] contiguous.   K, V  bf16 [B, Hkv, N, d] addressed through
+ *     the element strides in hylra_shape (innermost dimension contiguous).
+ *     out fp32 [B, Hq, d] contiguous.   idx  int32 [B, Hkv, k] contiguous.
+ *   - K, V, q must be 16-byte aligned and the strides multiples of 8 elements.
+ *   - All work is enqueued on the given HIP stream (a hipStream_t passed as void*,
+ *     NULL = the default stream) and is asynchronous with respect to the host.
+ *     No call below allocates, synchronises or copies to the host, except
+ *     hylra_create / hylra_destroy and the hylra_profile_* / hylra_probe_* aids.
+ *   - A context owns a fixed device workspace sized at creation for a maximum
+ *     shape; calls with a larger shape fail with HYLRA_ERR_WORKSPACE.  A context
+ *     serves one stream at a time: concurrent calls on one context race on the
+ *     workspace.
+ *   - Errors are return codes; arguments are checked before anything is launched.
+ *     hylra_last_error() gives the detail text of the most recent failure.
+ */
+#ifndef HYLRA_H
+#define HYLRA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hylra_ctx hylra_ctx;
+
+typedef enum {
+    HYLRA_OK = 0,
+    HYLRA_ERR_BAD_ARG = 1,     /* null pointer, misaligned tensor, k outside 1..N, ...      */
+    HYLRA_ERR_UNSUPPORTED = 2, /* head_dim not 64/128, group size above 8, ...               */
+    HYLRA_ERR_WORKSPACE = 3,   /* shape or k larger than what the context was created for    */
+    HYLRA_ERR_POLICY = 4,      /* policy[0] is not Full, or an entry is neither 0 nor 1      */
+    HYLRA_ERR_HIP = 5          /* a HIP runtime call failed (text in hylra_last_error)       */
+} hylra_status;
+
+#define HYLRA_FULL 0
+#define HYLRA_REUSE 1
+
+typedef struct {
+    int32_t batch;       /* B                                                              */
+    int32_t n_q_heads;   /* Hq, a multiple of n_kv_heads; Hq / Hkv <= 8                     */
+    int32_t n_kv_heads;  /* Hkv                                                            */
+    int32_t head_dim;    /* d: 64 or 128                                                   */
+    int32_t ctx_len;     /* N: rows in the KV cache (includes the current token)           */
+    int64_t kv_stride_b; /* element strides of K and V; all three 0 => contiguous [B,Hkv,N,d] */
+    int64_t kv_stride_h;
+    int64_t kv_stride_n;
+    float scale;         /* score scale; 0 => 1/sqrt(head_dim) (Eq. 1)                     */
+} hylra_shape;
+
+/* Creates a context on HIP device `device` with a workspace large enough for
+ * any call whose shape is <= max_shape in every extent and whose k <= max_k.
+ * HOST call; allocates device memory; *out is NULL on failure. */
+hylra_status hylra_create(hylra_ctx **out, const hylra_shape *max_shape, int32_t max_k, int device);
+
+/* Frees the workspace.  The caller makes sure no work of this context is still
+ * running.  NULL is accepted. */
+hylra_status hylra_destroy(hylra_ctx *ctx);
+
+/* Static, never NULL. */
+const char *hylra_status_str(hylra_status s);
+
+/* Detail text of the last failing call on this context (owned by the context,
+ * valid until the next call).  "" if none.  With ctx == NULL: the text of the
+ * last failed hylra_create on this thread. */
+const char *hylra_last_error(const hylra_ctx *ctx);
+
+/*
+ * Full layer (Algorithm 2, Full branch; Eq. 1).
+ *   out[b,h,:]  = sum_j softmax_j(scale * q[b,h,:].K[b,h/G,j,:]) * V[b,h/G,j,:]   over all N rows
+ *   idx[b,g,:]  = the k positions j with the largest mean_h-in-group(scale * q.K_j),
+ *                 ties to the lower position, ascending order
+ * One streaming pass over K and V; scores are computed in fp32 from the bf16
+ * inputs (products exact, fp32 accumulation).  Requires 1 <= k <= N.
+ */
+hylra_status hylra_full_attn_topk(hylra_ctx *ctx, const hylra_shape *shape,
+                                  const void *q, const void *K, const void *V, int32_t k,
+                                  float *out, int32_t *idx, void *hip_stream);
+
+/*
+ * Reuse layer (Algorithm 2, Reuse branch): attention restricted to the rows
+ * named by idx[b, g, 0..k-1], shared by the G query heads of KV head g.
+ * Entries that are negative or >= N are skipped (padding); a set with no valid
+ * entry gives a zero output row.  Only the selected rows of K and V are read.
+ */
+hylra_status hylra_reuse_sparse_attn(hylra_ctx *ctx, const hylra_shape *shape,
+                                     const void *q, const void *K, const void *V,
+                                     const int32_t *idx, int32_t k, float *out,
+                                     void *hip_stream);
+
+/*
+ * One decode step over n_layers layers (Algorithm 2, outer loop), in order, on
+ * one stream.  policy is a HOST array: HYLRA_FULL runs hylra_full_attn_topk and
+ * overwrites idx_buf; HYLRA_REUSE runs hylra_reuse_sparse_attn on idx_buf as the
+ * most recent Full layer left it.  policy[0] must be HYLRA_FULL.
+ * q_l, K_l, V_l, out_l are HOST arrays of n_layers DEVICE pointers (read during
+ * the call only).  idx_buf is DEVICE memory of at least B*Hkv*k int32; on return
+ * (stream order) it holds the last Full layer's set.
+ */
+hylra_status hylra_decode_step(hylra_ctx *ctx, const hylra_shape *shape, int32_t n_layers,
+                               const uint8_t *policy, const void *const *q_l,
+                               const void *const *K_l, const void *const *V_l, int32_t k,
+                               float *const *out_l, int32_t *idx_buf, void *hip_stream);
+
+/*
+ * Tuning knobs (HOST call, takes effect for later launches).  Unknown names give
+ * HYLRA_ERR_BAD_ARG.  Names:
+ *   "full_split_rows"   rows of the cache per workgroup of the Full kernel (0 = automatic)
+ *   "reuse_split_rows"  index entries per workgroup of the Reuse kernel    (0 = automatic)
+ *   "full_variant", "reuse_variant"  kernel variant number (0 = default)
+ */
+hylra_status hylra_set_option(hylra_ctx *ctx, const char *name, int32_t value);
+
+/*
+ * Measurement aids (not on the hot path).
+ *
+ * hylra_profile_enable(ctx, 1) makes every later kernel launch of this context
+ * be bracketed by a pair of HIP events on the launch stream; hylra_profile_read
+ * synchronises those events and returns, per kernel class, the number of
+ * launches and the summed duration in milliseconds since the last
+ * hylra_profile_reset.  Classes: 0 = Full attention (split-KV pass),
+ * 1 = Full finalise (combine + top-k), 2 = Reuse attention, 3 = Reuse combine,
+ * 4 = probe kernels.  At most HYLRA_PROFILE_MAX_EVENTS launches are recorded
+ * between resets; later ones run untimed.
+ */
+#define HYLRA_PROFILE_CLASSES 5
+#define HYLRA_PROFILE_MAX_EVENTS 4096
+hylra_status hylra_profile_enable(hylra_ctx *ctx, int32_t on);
+hylra_status hylra_profile_reset(hylra_ctx *ctx);
+hylra_status hylra_profile_read(hylra_ctx *ctx, int32_t kernel_class, int32_t *n_launches,
+                                double *total_ms);
+
+/* Plain device-to-device copy kernel of `bytes` bytes (a multiple of 16; both
+ * pointers 16-byte aligned): the known-size reference against which hardware
+ * traffic counters are scaled. */
+hylra_status hylra_probe_copy(hylra_ctx *ctx, void *dst, const void *src, size_t bytes,
+                              void *hip_stream);
+
+/* Streaming read of `bytes` bytes (multiple of 16) with a trivial reduction;
+ * writes one 32-bit word per workgroup to `sink` (>= 16384 bytes).  Measures the
+ * reachable HBM read rate. */
+hylra_status hylra_probe_read(hylra_ctx *ctx, const void *src, size_t bytes, void *sink,
+                              void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HYLRA_H */

@@ -1,0 +1,235 @@
+"""Thin ctypes binding over ``libhylra.so`` (declared in ``include/hylra.h``).
+
+Argument marshalling only: PyTorch supplies device memory and the current HIP
+stream; every step of the path runs in the library's kernels.  There is no
+fallback: if the library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhylra.so")
+
+FULL, REUSE = 0, 1
+PROFILE_CLASSES = ("full_attn", "full_finalize", "reuse_attn", "reuse_combine", "probe")
+
+EXPORTS = (
+    "hylra_create", "hylra_destroy", "hylra_status_str", "hylra_last_error",
+    "hylra_full_attn_topk", "hylra_reuse_sparse_attn", "hylra_decode_step",
+    "hylra_set_option", "hylra_profile_enable", "hylra_profile_reset", "hylra_profile_read",
+    "hylra_probe_copy", "hylra_probe_read",
+)
+
+
+class HylraError(RuntimeError):
+    def __init__(self, status: int, what: str, detail: str):
+        super().__init__("%s: status %d (%s)" % (what, status, detail))
+        self.status = status
+
+
+class Shape(ctypes.Structure):
+    _fields_ = [
+        ("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("ctx_len", ctypes.c_int32),
+        ("kv_stride_b", ctypes.c_int64), ("kv_stride_h", ctypes.c_int64),
+        ("kv_stride_n", ctypes.c_int64), ("scale", ctypes.c_float),
+    ]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads the built library; raises if it has not been built (no fallback path)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            "%s is missing: build it with `python -m paper_2602_00777_amd.build`" % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32 = ctypes.c_void_p, ctypes.c_int32
+    sp = ctypes.POINTER(Shape)
+    lib.hylra_create.argtypes = [ctypes.POINTER(vp), sp, i32, ctypes.c_int]
+    lib.hylra_destroy.argtypes = [vp]
+    lib.hylra_status_str.argtypes = [ctypes.c_int]
+    lib.hylra_status_str.restype = ctypes.c_char_p
+    lib.hylra_last_error.argtypes = [vp]
+    lib.hylra_last_error.restype = ctypes.c_char_p
+    lib.hylra_full_attn_topk.argtypes = [vp, sp, vp, vp, vp, i32, vp, vp, vp]
+    lib.hylra_reuse_sparse_attn.argtypes = [vp, sp, vp, vp, vp, vp, i32, vp, vp]
+    lib.hylra_decode_step.argtypes = [vp, sp, i32, vp, vp, vp, vp, i32, vp, vp, vp]
+    lib.hylra_set_option.argtypes = [vp, ctypes.c_char_p, i32]
+    lib.hylra_profile_enable.argtypes = [vp, i32]
+    lib.hylra_profile_reset.argtypes = [vp]
+    lib.hylra_profile_read.argtypes = [vp, i32, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_double)]
+    lib.hylra_probe_copy.argtypes = [vp, vp, vp, ctypes.c_size_t, vp]
+    lib.hylra_probe_read.argtypes = [vp, vp, ctypes.c_size_t, vp, vp]
+    for name in EXPORTS:
+        if name not in ("hylra_status_str", "hylra_last_error"):
+            getattr(lib, name).restype = ctypes.c_int
+    _lib = lib
+    return lib
+
+
+def _stream_ptr(device) -> int:
+    return torch.cuda.current_stream(device).cuda_stream
+
+
+def make_shape(q: torch.Tensor, K: torch.Tensor, scale: float = 0.0) -> Shape:
+    """Shape descriptor for q [B,Hq,d] and K [B,Hkv,N,d] (strides taken from K)."""
+    B, Hq, d = q.shape
+    Bk, Hkv, N, dk = K.shape
+    if (Bk, dk) != (B, d):
+        raise ValueError("q %s and K %s disagree" % (tuple(q.shape), tuple(K.shape)))
+    if K.stride(3) != 1:
+        raise ValueError("the innermost dimension of K and V must be contiguous")
+    return Shape(B, Hq, Hkv, d, N, K.stride(0), K.stride(1), K.stride(2), float(scale))
+
+
+class Context:
+    """Owns one ``hylra_ctx`` (a fixed device workspace) on one GPU."""
+
+    def __init__(self, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, ctx_len: int,
+                 max_k: int, device: int = 0):
+        self._lib = load_library()
+        self._h = ctypes.c_void_p()
+        self.device = torch.device("cuda", device)
+        shp = Shape(batch, n_q_heads, n_kv_heads, head_dim, ctx_len, 0, 0, 0, 0.0)
+        rc = self._lib.hylra_create(ctypes.byref(self._h), ctypes.byref(shp), max_k, device)
+        if rc != 0:
+            raise HylraError(rc, "hylra_create", self._lib.hylra_last_error(None).decode())
+
+    def close(self):
+        if getattr(self, "_h", None) and self._h.value:
+            torch.cuda.synchronize(self.device)
+            self._lib.hylra_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def _check(self, rc: int, what: str):
+        if rc != 0:
+            raise HylraError(rc, what, self._lib.hylra_last_error(self._h).decode())
+
+    @staticmethod
+    def _check_inputs(q, K, V):
+        for name, t in (("q", q), ("K", K), ("V", V)):
+            if t.dtype != torch.bfloat16 or not t.is_cuda:
+                raise TypeError("%s must be a bfloat16 CUDA tensor" % name)
+        if not q.is_contiguous():
+            raise ValueError("q must be contiguous")
+        if V.shape != K.shape or V.stride() != K.stride():
+            raise ValueError("K and V must share shape and strides")
+
+    # -- the three calls of the hot path -------------------------------------------------
+    def full_attn_topk(self, q, K, V, k: int, out=None, idx=None, scale: float = 0.0):
+        """hylra_full_attn_topk: returns (out fp32 [B,Hq,d], idx int32 [B,Hkv,k])."""
+        self._check_inputs(q, K, V)
+        shp = make_shape(q, K, scale)
+        if out is None:
+            out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+        if idx is None:
+            idx = torch.empty((shp.batch, shp.n_kv_heads, k), dtype=torch.int32, device=q.device)
+        rc = self._lib.hylra_full_attn_topk(self._h, ctypes.byref(shp), q.data_ptr(), K.data_ptr(),
+                                            V.data_ptr(), k, out.data_ptr(), idx.data_ptr(),
+                                            _stream_ptr(q.device))
+        self._check(rc, "hylra_full_attn_topk")
+        return out, idx
+
+    def reuse_sparse_attn(self, q, K, V, idx, out=None, scale: float = 0.0):
+        """hylra_reuse_sparse_attn: returns out fp32 [B,Hq,d]."""
+        self._check_inputs(q, K, V)
+        if idx.dtype != torch.int32 or not idx.is_cuda or not idx.is_contiguous():
+            raise TypeError("idx must be a contiguous int32 CUDA tensor")
+        shp = make_shape(q, K, scale)
+        if tuple(idx.shape[:2]) != (shp.batch, shp.n_kv_heads):
+            raise ValueError("idx must be [B, Hkv, k]")
+        if out is None:
+            out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+        rc = self._lib.hylra_reuse_sparse_attn(self._h, ctypes.byref(shp), q.data_ptr(),
+                                               K.data_ptr(), V.data_ptr(), idx.data_ptr(),
+                                               idx.shape[2], out.data_ptr(), _stream_ptr(q.device))
+        self._check(rc, "hylra_reuse_sparse_attn")
+        return out
+
+    def prepare_step(self, policy: Sequence[int], q_l, K_l, V_l, k: int, scale: float = 0.0):
+        """Marshals the per-layer pointer arrays of hylra_decode_step once, so that a timed
+        loop contains nothing but the C call.  Returns a zero-argument callable plus the
+        output tensors (outs, idx_buf)."""
+        L = len(policy)
+        for l in range(L):
+            self._check_inputs(q_l[l], K_l[l], V_l[l])
+        shp = make_shape(q_l[0], K_l[0], scale)
+        for l in range(1, L):
+            o = make_shape(q_l[l], K_l[l], scale)
+            if bytes(o) != bytes(shp):
+                raise ValueError("all layers must share one shape and stride set")
+        dev = q_l[0].device
+        outs = [torch.empty(q_l[l].shape, dtype=torch.float32, device=dev) for l in range(L)]
+        idx_buf = torch.empty((shp.batch, shp.n_kv_heads, k), dtype=torch.int32, device=dev)
+        arr = ctypes.c_void_p * L
+        pol = (ctypes.c_uint8 * L)(*[int(p) for p in policy])
+        qa = arr(*[t.data_ptr() for t in q_l])
+        Ka = arr(*[t.data_ptr() for t in K_l])
+        Va = arr(*[t.data_ptr() for t in V_l])
+        oa = arr(*[t.data_ptr() for t in outs])
+        keep = (q_l, K_l, V_l)
+
+        def run():
+            rc = self._lib.hylra_decode_step(self._h, ctypes.byref(shp), L, pol, qa, Ka, Va, k, oa,
+                                             idx_buf.data_ptr(), _stream_ptr(dev))
+            self._check(rc, "hylra_decode_step")
+            return keep is not None
+
+        return run, outs, idx_buf
+
+    def decode_step(self, policy: Sequence[int], q_l, K_l, V_l, k: int, scale: float = 0.0):
+        """hylra_decode_step: returns (list of out per layer, idx of the last Full layer)."""
+        run, outs, idx_buf = self.prepare_step(policy, q_l, K_l, V_l, k, scale)
+        run()
+        return outs, idx_buf
+
+    # -- knobs and measurement aids ----------------------------------------------------------
+    def set_option(self, name: str, value: int):
+        self._check(self._lib.hylra_set_option(self._h, name.encode(), int(value)), "hylra_set_option")
+
+    def profile_enable(self, on: bool = True):
+        self._check(self._lib.hylra_profile_enable(self._h, 1 if on else 0), "hylra_profile_enable")
+
+    def profile_reset(self):
+        self._check(self._lib.hylra_profile_reset(self._h), "hylra_profile_reset")
+
+    def profile_read(self) -> dict:
+        res = {}
+        for c, name in enumerate(PROFILE_CLASSES):
+            n, ms = ctypes.c_int32(), ctypes.c_double()
+            self._check(self._lib.hylra_profile_read(self._h, c, ctypes.byref(n), ctypes.byref(ms)),
+                        "hylra_profile_read")
+            res[name] = (n.value, ms.value)
+        return res
+
+    def probe_copy(self, dst: torch.Tensor, src: torch.Tensor):
+        nbytes = src.numel() * src.element_size()
+        self._check(self._lib.hylra_probe_copy(self._h, dst.data_ptr(), src.data_ptr(), nbytes,
+                                               _stream_ptr(src.device)), "hylra_probe_copy")
+
+    def probe_read(self, src: torch.Tensor, sink: torch.Tensor):
+        nbytes = src.numel() * src.element_size()
+        self._check(self._lib.hylra_probe_read(self._h, src.data_ptr(), nbytes, sink.data_ptr(),
+                                               _stream_ptr(src.device)), "hylra_probe_read")

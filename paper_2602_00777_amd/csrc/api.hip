@@ -1,0 +1,478 @@
+// Host side of libhylra: argument checks, split planning, workspace, launches.
+// Nothing here computes attention; every step of the path runs in the kernels.
+#include "../../include/hylra.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "launch.h"
+
+using namespace hylra;
+
+namespace {
+
+constexpr int kTargetBlocksFull = 2048;   // workgroups the Full kernel aims for (8 per CU)
+constexpr int kMinBlocksReuse = 512;      // below this the Reuse kernel uses a shorter unroll
+constexpr int64_t kMinSlots = 8192;       // partial slots ((batch, KV head, split) triples) kept
+constexpr float LOG2E_HOST = 1.4426950408889634f;
+
+thread_local char g_create_error[256] = "";
+
+int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+int64_t ceil_div(int64_t x, int64_t m) { return (x + m - 1) / m; }
+
+}  // namespace
+
+struct hylra_ctx {
+    int device = 0;
+    hylra_shape max_shape{};
+    int32_t max_k = 0;
+
+    float* part_ml = nullptr;
+    float* part_acc = nullptr;
+    float* part_mm = nullptr;
+    float* scores = nullptr;
+    int64_t slots = 0;          // capacity in (batch, KV head, split) triples
+    int64_t cap_acc = 0;        // floats
+    int64_t cap_ml = 0;
+    int64_t cap_scores = 0;
+
+    int32_t opt_full_split_rows = 0;
+    int32_t opt_reuse_split_rows = 0;
+    int32_t opt_full_variant = 0;
+    int32_t opt_reuse_variant = 0;
+
+    bool prof_on = false;
+    int prof_n = 0;
+    hipEvent_t* prof_ev = nullptr;          // 2 * HYLRA_PROFILE_MAX_EVENTS, created on first enable
+    uint8_t prof_cls[HYLRA_PROFILE_MAX_EVENTS];
+
+    mutable char err[256] = "";
+};
+
+namespace {
+
+hylra_status fail(const hylra_ctx* ctx, hylra_status s, const char* fmt, ...) {
+    char* dst = ctx ? ctx->err : g_create_error;
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(dst, 256, fmt, ap);
+    va_end(ap);
+    return s;
+}
+
+#define HIP_TRY(ctx, expr)                                                                  \
+    do {                                                                                    \
+        hipError_t e_ = (expr);                                                             \
+        if (e_ != hipSuccess)                                                               \
+            return fail(ctx, HYLRA_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));        \
+    } while (0)
+
+struct DeviceGuard {
+    int prev = -1;
+    bool switched = false;
+    explicit DeviceGuard(int dev) {
+        if (hipGetDevice(&prev) == hipSuccess && prev != dev) switched = hipSetDevice(dev) == hipSuccess;
+    }
+    ~DeviceGuard() {
+        if (switched) (void)hipSetDevice(prev);
+    }
+};
+
+struct Strides {
+    int64_t b, h, n;
+};
+
+// Shape checks shared by every entry point.  Fills G and the effective strides.
+hylra_status check_shape(const hylra_ctx* ctx, const hylra_shape* s, int& G, Strides& st, float& scale) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    if (!s) return fail(ctx, HYLRA_ERR_BAD_ARG, "shape is NULL");
+    if (s->batch < 1 || s->n_q_heads < 1 || s->n_kv_heads < 1 || s->ctx_len < 1)
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "batch, head counts and ctx_len must be >= 1");
+    if (s->n_q_heads % s->n_kv_heads != 0)
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "n_q_heads (%d) is not a multiple of n_kv_heads (%d)",
+                    s->n_q_heads, s->n_kv_heads);
+    G = s->n_q_heads / s->n_kv_heads;
+    if (s->head_dim != 64 && s->head_dim != 128)
+        return fail(ctx, HYLRA_ERR_UNSUPPORTED, "head_dim %d: only 64 and 128 are built", s->head_dim);
+    if (G > kMaxGroup)
+        return fail(ctx, HYLRA_ERR_UNSUPPORTED, "group size %d: at most %d query heads per KV head", G, kMaxGroup);
+    if (s->batch > 65535 || s->n_kv_heads > 65535)   // grid.z / grid.y limits
+        return fail(ctx, HYLRA_ERR_UNSUPPORTED, "batch and n_kv_heads must each be <= 65535");
+    const int D = s->head_dim;
+    if (s->kv_stride_b == 0 && s->kv_stride_h == 0 && s->kv_stride_n == 0) {
+        st.n = D;
+        st.h = (int64_t)s->ctx_len * D;
+        st.b = st.h * s->n_kv_heads;
+    } else {
+        st.b = s->kv_stride_b;
+        st.h = s->kv_stride_h;
+        st.n = s->kv_stride_n;
+        if (st.n < D || st.h < 0 || st.b < 0)
+            return fail(ctx, HYLRA_ERR_BAD_ARG, "kv strides must be non-negative and kv_stride_n >= head_dim");
+        if (st.n % 8 || st.h % 8 || st.b % 8)
+            return fail(ctx, HYLRA_ERR_BAD_ARG, "kv strides must be multiples of 8 elements (16 bytes)");
+    }
+    if (!(s->scale >= 0.f) || std::isinf(s->scale))
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "scale must be finite and >= 0");
+    scale = s->scale > 0.f ? s->scale : 1.0f / std::sqrt((float)D);
+    return HYLRA_OK;
+}
+
+hylra_status check_tensors(const hylra_ctx* ctx, const void* q, const void* K, const void* V, const void* out) {
+    if (!q || !K || !V || !out) return fail(ctx, HYLRA_ERR_BAD_ARG, "q, K, V and out must not be NULL");
+    if (((uintptr_t)q | (uintptr_t)K | (uintptr_t)V) & 15)
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "q, K and V must be 16-byte aligned");
+    if ((uintptr_t)out & 3) return fail(ctx, HYLRA_ERR_BAD_ARG, "out must be 4-byte aligned");
+    return HYLRA_OK;
+}
+
+// Runs a launch, bracketed by events when profiling is on.
+template <class F>
+hipError_t launch_timed(hylra_ctx* ctx, int cls, hipStream_t st, F&& f) {
+    if (ctx->prof_on && ctx->prof_n < HYLRA_PROFILE_MAX_EVENTS) {
+        const int n = ctx->prof_n;
+        hipError_t e = hipEventRecord(ctx->prof_ev[2 * n], st);
+        if (e != hipSuccess) return e;
+        e = f();
+        if (e != hipSuccess) return e;
+        e = hipEventRecord(ctx->prof_ev[2 * n + 1], st);
+        if (e != hipSuccess) return e;
+        ctx->prof_cls[n] = (uint8_t)cls;
+        ctx->prof_n = n + 1;
+        return hipSuccess;
+    }
+    return f();
+}
+
+struct FullPlan {
+    int rows_per_split, n_splits, variant;
+};
+
+hylra_status plan_full(const hylra_ctx* ctx, const hylra_shape* s, int G, FullPlan& pl) {
+    pl.variant = ctx->opt_full_variant;
+    const int quantum = full_block_quantum(s->head_dim, G, pl.variant);
+    if (quantum <= 0) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "Full kernel variant %d is not built for d=%d G=%d", pl.variant, s->head_dim, G);
+    const int64_t pairs = (int64_t)s->batch * s->n_kv_heads;
+    int64_t rps = ctx->opt_full_split_rows > 0 ? ctx->opt_full_split_rows
+                                               : ceil_div(pairs * s->ctx_len, kTargetBlocksFull);
+    rps = round_up(rps < quantum ? quantum : rps, quantum);
+    int64_t S = ceil_div(s->ctx_len, rps);
+    while (S > kMaxSplits || pairs * S > ctx->slots) {
+        rps = round_up(rps * 2, quantum);
+        S = ceil_div(s->ctx_len, rps);
+        if (S == 1) break;
+    }
+    if (pairs * S > ctx->slots)
+        return fail(ctx, HYLRA_ERR_WORKSPACE, "batch*n_kv_heads = %lld exceeds the workspace", (long long)pairs);
+    pl.rows_per_split = (int)rps;
+    pl.n_splits = (int)S;
+    return HYLRA_OK;
+}
+
+struct ReusePlan {
+    int rows_per_split, n_splits, variant, R;
+};
+
+hylra_status plan_reuse(const hylra_ctx* ctx, const hylra_shape* s, int G, int k, ReusePlan& pl) {
+    pl.variant = ctx->opt_reuse_variant;
+    const int64_t pairs = (int64_t)s->batch * s->n_kv_heads;
+    pl.R = 0;
+    for (int R = 4; R >= 1; R >>= 1) {
+        const int quantum = reuse_block_quantum(s->head_dim, G, pl.variant, R);
+        if (quantum <= 0) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "Reuse kernel variant %d is not built for d=%d G=%d", pl.variant, s->head_dim, G);
+        pl.R = R;
+        pl.rows_per_split = quantum;
+        if (pairs * ceil_div(k, quantum) >= kMinBlocksReuse) break;
+    }
+    int64_t rps = pl.rows_per_split;
+    if (ctx->opt_reuse_split_rows > 0) rps = round_up(ctx->opt_reuse_split_rows, pl.rows_per_split);
+    int64_t S = ceil_div(k, rps);
+    while (S > kMaxSplits || pairs * S > ctx->slots) {
+        rps = round_up(rps * 2, pl.rows_per_split);
+        S = ceil_div(k, rps);
+        if (S == 1) break;
+    }
+    if (pairs * S > ctx->slots)
+        return fail(ctx, HYLRA_ERR_WORKSPACE, "batch*n_kv_heads = %lld exceeds the workspace", (long long)pairs);
+    pl.rows_per_split = (int)rps;
+    pl.n_splits = (int)S;
+    return HYLRA_OK;
+}
+
+hylra_status check_workspace(const hylra_ctx* ctx, const hylra_shape* s, int S, bool need_scores) {
+    const int64_t heads = (int64_t)s->batch * s->n_q_heads;
+    if (heads * S * s->head_dim > ctx->cap_acc || heads * S * 2 > ctx->cap_ml)
+        return fail(ctx, HYLRA_ERR_WORKSPACE, "shape needs %lld partial floats, workspace holds %lld",
+                    (long long)(heads * S * s->head_dim), (long long)ctx->cap_acc);
+    if (need_scores) {
+        const int64_t need = (int64_t)s->batch * s->n_kv_heads * round_up(s->ctx_len, 4);
+        if (need > ctx->cap_scores)
+            return fail(ctx, HYLRA_ERR_WORKSPACE, "shape needs %lld score floats, workspace holds %lld",
+                        (long long)need, (long long)ctx->cap_scores);
+    }
+    return HYLRA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* hylra_status_str(hylra_status s) {
+    switch (s) {
+        case HYLRA_OK: return "ok";
+        case HYLRA_ERR_BAD_ARG: return "bad argument";
+        case HYLRA_ERR_UNSUPPORTED: return "unsupported shape";
+        case HYLRA_ERR_WORKSPACE: return "workspace too small";
+        case HYLRA_ERR_POLICY: return "invalid policy";
+        case HYLRA_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+const char* hylra_last_error(const hylra_ctx* ctx) { return ctx ? ctx->err : g_create_error; }
+
+hylra_status hylra_create(hylra_ctx** out, const hylra_shape* max_shape, int32_t max_k, int device) {
+    if (!out) return fail(nullptr, HYLRA_ERR_BAD_ARG, "out is NULL");
+    *out = nullptr;
+    hylra_ctx* ctx = new (std::nothrow) hylra_ctx;
+    if (!ctx) return fail(nullptr, HYLRA_ERR_HIP, "out of host memory");
+    int G = 0;
+    Strides st{};
+    float scale = 0.f;
+    hylra_status rc = check_shape(ctx, max_shape, G, st, scale);
+    if (rc == HYLRA_OK && (max_k < 1 || max_k > max_shape->ctx_len))
+        rc = fail(ctx, HYLRA_ERR_BAD_ARG, "max_k must be in 1..ctx_len");
+    int n_dev = 0;
+    if (rc == HYLRA_OK && (hipGetDeviceCount(&n_dev) != hipSuccess || device < 0 || device >= n_dev))
+        rc = fail(ctx, HYLRA_ERR_HIP, "HIP device %d is not available (%d devices visible)", device, n_dev);
+    if (rc != HYLRA_OK) {
+        std::memcpy(g_create_error, ctx->err, sizeof g_create_error);
+        delete ctx;
+        return rc;
+    }
+    ctx->device = device;
+    ctx->max_shape = *max_shape;
+    ctx->max_k = max_k;
+    const int64_t pairs = (int64_t)max_shape->batch * max_shape->n_kv_heads;
+    ctx->slots = pairs * 2 > kMinSlots ? pairs * 2 : kMinSlots;
+    ctx->cap_acc = ctx->slots * G * max_shape->head_dim;
+    ctx->cap_ml = ctx->slots * G * 2;
+    ctx->cap_scores = pairs * round_up(max_shape->ctx_len, 4);
+
+    DeviceGuard guard(device);
+    hipError_t e = hipMalloc((void**)&ctx->part_acc, ctx->cap_acc * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->part_ml, ctx->cap_ml * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->part_mm, ctx->slots * 2 * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->scores, ctx->cap_scores * sizeof(float));
+    if (e != hipSuccess) {
+        fail(nullptr, HYLRA_ERR_HIP, "workspace allocation failed: %s", hipGetErrorString(e));
+        hylra_destroy(ctx);
+        return HYLRA_ERR_HIP;
+    }
+    *out = ctx;
+    return HYLRA_OK;
+}
+
+hylra_status hylra_destroy(hylra_ctx* ctx) {
+    if (!ctx) return HYLRA_OK;
+    DeviceGuard guard(ctx->device);
+    if (ctx->prof_ev) {
+        for (int i = 0; i < 2 * HYLRA_PROFILE_MAX_EVENTS; ++i)
+            if (ctx->prof_ev[i]) (void)hipEventDestroy(ctx->prof_ev[i]);
+        delete[] ctx->prof_ev;
+    }
+    if (ctx->part_acc) (void)hipFree(ctx->part_acc);
+    if (ctx->part_ml) (void)hipFree(ctx->part_ml);
+    if (ctx->part_mm) (void)hipFree(ctx->part_mm);
+    if (ctx->scores) (void)hipFree(ctx->scores);
+    delete ctx;
+    return HYLRA_OK;
+}
+
+hylra_status hylra_set_option(hylra_ctx* ctx, const char* name, int32_t value) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    if (!name || value < 0) return fail(ctx, HYLRA_ERR_BAD_ARG, "option name is NULL or value negative");
+    if (!std::strcmp(name, "full_split_rows")) ctx->opt_full_split_rows = value;
+    else if (!std::strcmp(name, "reuse_split_rows")) ctx->opt_reuse_split_rows = value;
+    else if (!std::strcmp(name, "full_variant")) ctx->opt_full_variant = value;
+    else if (!std::strcmp(name, "reuse_variant")) ctx->opt_reuse_variant = value;
+    else return fail(ctx, HYLRA_ERR_BAD_ARG, "unknown option '%s'", name);
+    return HYLRA_OK;
+}
+
+hylra_status hylra_full_attn_topk(hylra_ctx* ctx, const hylra_shape* shape, const void* q,
+                                  const void* K, const void* V, int32_t k, float* out,
+                                  int32_t* idx, void* hip_stream) {
+    int G = 0;
+    Strides sd{};
+    float scale = 0.f;
+    hylra_status rc = check_shape(ctx, shape, G, sd, scale);
+    if (rc != HYLRA_OK) return rc;
+    if ((rc = check_tensors(ctx, q, K, V, out)) != HYLRA_OK) return rc;
+    if (!idx || ((uintptr_t)idx & 3)) return fail(ctx, HYLRA_ERR_BAD_ARG, "idx must be a 4-byte aligned device pointer");
+    if (k < 1 || k > shape->ctx_len) return fail(ctx, HYLRA_ERR_BAD_ARG, "k = %d is outside 1..ctx_len (%d)", k, shape->ctx_len);
+    if (k > ctx->max_k) return fail(ctx, HYLRA_ERR_WORKSPACE, "k = %d exceeds the context's max_k = %d", k, ctx->max_k);
+    FullPlan pl{};
+    if ((rc = plan_full(ctx, shape, G, pl)) != HYLRA_OK) return rc;
+    if ((rc = check_workspace(ctx, shape, pl.n_splits, true)) != HYLRA_OK) return rc;
+
+    hipStream_t st = (hipStream_t)hip_stream;
+    DeviceGuard guard(ctx->device);
+    FullParams fp{};
+    fp.q = (const uint16_t*)q;
+    fp.K = (const uint16_t*)K;
+    fp.V = (const uint16_t*)V;
+    fp.sb = sd.b, fp.sh = sd.h, fp.sn = sd.n;
+    fp.Hq = shape->n_q_heads, fp.Hkv = shape->n_kv_heads, fp.N = shape->ctx_len;
+    fp.rows_per_split = pl.rows_per_split, fp.n_splits = pl.n_splits;
+    fp.scale_log2 = scale * LOG2E_HOST;
+    fp.scale_mean = scale / (float)G;
+    fp.part_ml = ctx->part_ml, fp.part_acc = ctx->part_acc, fp.part_mm = ctx->part_mm;
+    fp.scores = ctx->scores;
+    fp.score_stride = round_up(shape->ctx_len, 4);
+    HIP_TRY(ctx, launch_timed(ctx, 0, st, [&] {
+                return launch_full_split(fp, shape->batch, shape->head_dim, G, pl.variant, st);
+            }));
+
+    FinalizeParams zp{};
+    zp.part_ml = ctx->part_ml, zp.part_acc = ctx->part_acc, zp.part_mm = ctx->part_mm;
+    zp.scores = ctx->scores, zp.score_stride = fp.score_stride;
+    zp.n_splits = pl.n_splits, zp.Hq = shape->n_q_heads, zp.Hkv = shape->n_kv_heads;
+    zp.G = G, zp.D = shape->head_dim, zp.N = shape->ctx_len, zp.k = k;
+    zp.out = out, zp.idx = idx;
+    HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_full_finalize(zp, shape->batch, st); }));
+    return HYLRA_OK;
+}
+
+hylra_status hylra_reuse_sparse_attn(hylra_ctx* ctx, const hylra_shape* shape, const void* q,
+                                     const void* K, const void* V, const int32_t* idx, int32_t k,
+                                     float* out, void* hip_stream) {
+    int G = 0;
+    Strides sd{};
+    float scale = 0.f;
+    hylra_status rc = check_shape(ctx, shape, G, sd, scale);
+    if (rc != HYLRA_OK) return rc;
+    if ((rc = check_tensors(ctx, q, K, V, out)) != HYLRA_OK) return rc;
+    if (!idx || ((uintptr_t)idx & 3)) return fail(ctx, HYLRA_ERR_BAD_ARG, "idx must be a 4-byte aligned device pointer");
+    if (k < 1) return fail(ctx, HYLRA_ERR_BAD_ARG, "k = %d must be >= 1", k);
+    if (k > ctx->max_k) return fail(ctx, HYLRA_ERR_WORKSPACE, "k = %d exceeds the context's max_k = %d", k, ctx->max_k);
+    ReusePlan pl{};
+    if ((rc = plan_reuse(ctx, shape, G, k, pl)) != HYLRA_OK) return rc;
+    if ((rc = check_workspace(ctx, shape, pl.n_splits, false)) != HYLRA_OK) return rc;
+
+    hipStream_t st = (hipStream_t)hip_stream;
+    DeviceGuard guard(ctx->device);
+    ReuseParams rp{};
+    rp.q = (const uint16_t*)q;
+    rp.K = (const uint16_t*)K;
+    rp.V = (const uint16_t*)V;
+    rp.sb = sd.b, rp.sh = sd.h, rp.sn = sd.n;
+    rp.Hq = shape->n_q_heads, rp.Hkv = shape->n_kv_heads, rp.N = shape->ctx_len, rp.k = k;
+    rp.rows_per_split = pl.rows_per_split, rp.n_splits = pl.n_splits;
+    rp.scale_log2 = scale * LOG2E_HOST;
+    rp.idx = idx;
+    rp.part_ml = ctx->part_ml, rp.part_acc = ctx->part_acc;
+    HIP_TRY(ctx, launch_timed(ctx, 2, st, [&] {
+                return launch_reuse_split(rp, shape->batch, shape->head_dim, G, pl.variant, pl.R, st);
+            }));
+    CombineParams cp{};
+    cp.part_ml = ctx->part_ml, cp.part_acc = ctx->part_acc;
+    cp.n_splits = pl.n_splits, cp.D = shape->head_dim, cp.out = out;
+    HIP_TRY(ctx, launch_timed(ctx, 3, st, [&] {
+                return launch_combine(cp, shape->batch * shape->n_q_heads, st);
+            }));
+    return HYLRA_OK;
+}
+
+hylra_status hylra_decode_step(hylra_ctx* ctx, const hylra_shape* shape, int32_t n_layers,
+                               const uint8_t* policy, const void* const* q_l,
+                               const void* const* K_l, const void* const* V_l, int32_t k,
+                               float* const* out_l, int32_t* idx_buf, void* hip_stream) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    if (n_layers < 1 || !policy || !q_l || !K_l || !V_l || !out_l || !idx_buf)
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "n_layers < 1 or a NULL argument");
+    if (policy[0] != HYLRA_FULL)
+        return fail(ctx, HYLRA_ERR_POLICY, "policy[0] must be Full: layer 0 has no set to inherit");
+    for (int l = 0; l < n_layers; ++l) {
+        if (policy[l] != HYLRA_FULL && policy[l] != HYLRA_REUSE)
+            return fail(ctx, HYLRA_ERR_POLICY, "policy[%d] = %d is neither Full (0) nor Reuse (1)", l, policy[l]);
+        if (!q_l[l] || !K_l[l] || !V_l[l] || !out_l[l])
+            return fail(ctx, HYLRA_ERR_BAD_ARG, "layer %d has a NULL tensor pointer", l);
+    }
+    // Layers run in order on one stream: a layer's query depends on the previous layer's
+    // output in a real model, so nothing here batches across layers.
+    for (int l = 0; l < n_layers; ++l) {
+        hylra_status rc =
+            policy[l] == HYLRA_FULL
+                ? hylra_full_attn_topk(ctx, shape, q_l[l], K_l[l], V_l[l], k, out_l[l], idx_buf, hip_stream)
+                : hylra_reuse_sparse_attn(ctx, shape, q_l[l], K_l[l], V_l[l], idx_buf, k, out_l[l], hip_stream);
+        if (rc != HYLRA_OK) return rc;
+    }
+    return HYLRA_OK;
+}
+
+hylra_status hylra_profile_enable(hylra_ctx* ctx, int32_t on) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    DeviceGuard guard(ctx->device);
+    if (on && !ctx->prof_ev) {
+        ctx->prof_ev = new (std::nothrow) hipEvent_t[2 * HYLRA_PROFILE_MAX_EVENTS]();
+        if (!ctx->prof_ev) return fail(ctx, HYLRA_ERR_HIP, "out of host memory");
+        for (int i = 0; i < 2 * HYLRA_PROFILE_MAX_EVENTS; ++i) HIP_TRY(ctx, hipEventCreate(&ctx->prof_ev[i]));
+    }
+    ctx->prof_on = on != 0;
+    return HYLRA_OK;
+}
+
+hylra_status hylra_profile_reset(hylra_ctx* ctx) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    ctx->prof_n = 0;
+    return HYLRA_OK;
+}
+
+hylra_status hylra_profile_read(hylra_ctx* ctx, int32_t kernel_class, int32_t* n_launches, double* total_ms) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    if (kernel_class < 0 || kernel_class >= HYLRA_PROFILE_CLASSES || !n_launches || !total_ms)
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "kernel_class outside 0..%d or NULL output", HYLRA_PROFILE_CLASSES - 1);
+    DeviceGuard guard(ctx->device);
+    int n = 0;
+    double ms = 0.0;
+    for (int i = 0; i < ctx->prof_n; ++i) {
+        if (ctx->prof_cls[i] != kernel_class) continue;
+        HIP_TRY(ctx, hipEventSynchronize(ctx->prof_ev[2 * i + 1]));
+        float t = 0.f;
+        HIP_TRY(ctx, hipEventElapsedTime(&t, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]));
+        ms += t;
+        ++n;
+    }
+    *n_launches = n;
+    *total_ms = ms;
+    return HYLRA_OK;
+}
+
+hylra_status hylra_probe_copy(hylra_ctx* ctx, void* dst, const void* src, size_t bytes, void* hip_stream) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    if (!dst || !src || bytes == 0 || bytes % 16 || (((uintptr_t)dst | (uintptr_t)src) & 15))
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "probe_copy needs 16-byte aligned pointers and a multiple of 16 bytes");
+    hipStream_t st = (hipStream_t)hip_stream;
+    DeviceGuard guard(ctx->device);
+    HIP_TRY(ctx, launch_timed(ctx, 4, st, [&] { return launch_probe_copy(dst, src, bytes, st); }));
+    return HYLRA_OK;
+}
+
+hylra_status hylra_probe_read(hylra_ctx* ctx, const void* src, size_t bytes, void* sink, void* hip_stream) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    if (!sink || !src || bytes == 0 || bytes % 16 || (((uintptr_t)sink | (uintptr_t)src) & 15))
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "probe_read needs 16-byte aligned pointers and a multiple of 16 bytes");
+    hipStream_t st = (hipStream_t)hip_stream;
+    DeviceGuard guard(ctx->device);
+    HIP_TRY(ctx, launch_timed(ctx, 4, st, [&] { return launch_probe_read(src, bytes, sink, st); }));
+    return HYLRA_OK;
+}
+
+}  // extern "C"

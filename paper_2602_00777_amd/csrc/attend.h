@@ -1,0 +1,225 @@
+// Wave-level core shared by the Full (streaming) and Reuse (gather) kernels.
+//
+// A wave64 works on "row groups": LPR = D / (8*CH) lanes share one KV row, each lane
+// holding CH 16-byte pieces (8 bf16 each) of it, so one wave-wide load instruction reads
+// RPG = 64 / LPR rows.  Every lane keeps an independent online-softmax state (running
+// max m in log2 units, running sum l, unnormalised accumulator acc) per query head of the
+// group for the subsequence of rows it has seen; states are merged once per workgroup.
+//
+// The score of a row is Eq. 1's q.K_j / sqrt(d); the weight update is the usual
+// max-subtracted softmax of Eq. 1 evaluated incrementally (Algorithm 2, "standard full
+// attention output" / "sparse attention output").
+#pragma once
+#include "device_util.h"
+
+namespace hylra {
+
+template <int D_, int G_, int CH_>
+struct Geo {
+    static constexpr int D = D_;               // head_dim
+    static constexpr int G = G_;               // query heads per KV head
+    static constexpr int CH = CH_;             // 16-byte pieces of a row per lane
+    static constexpr int LPR = D / (8 * CH);   // lanes per row
+    static constexpr int RPG = 64 / LPR;       // rows per wave-wide load
+    static constexpr int ACC = 8 * CH;         // accumulator columns per lane per head
+    static_assert(LPR == 4 || LPR == 8 || LPR == 16, "unsupported lane layout");
+};
+
+template <class GEO>
+struct LaneState {
+    float m[GEO::G];
+    float l[GEO::G];
+    float acc[GEO::G][GEO::ACC];
+    DEVI void init() {
+#pragma unroll
+        for (int h = 0; h < GEO::G; ++h) {
+            m[h] = NEG_BIG;
+            l[h] = 0.f;
+#pragma unroll
+            for (int e = 0; e < GEO::ACC; ++e) acc[h][e] = 0.f;
+        }
+    }
+};
+
+// q of the group, as this lane's pieces: qv[h][j] = 8 bf16 at column (chunk + j*LPR)*8.
+template <class GEO>
+DEVI void load_q(uint4 (&qv)[GEO::G][GEO::CH], const uint16_t* __restrict__ q_group, int chunk) {
+#pragma unroll
+    for (int h = 0; h < GEO::G; ++h)
+#pragma unroll
+        for (int j = 0; j < GEO::CH; ++j)
+            qv[h][j] = *reinterpret_cast<const uint4*>(q_group + h * GEO::D + (chunk + j * GEO::LPR) * 8);
+}
+
+// One tile of R row groups.  off[r] is the element offset (from K and from V) of this
+// lane's first piece of its row in group r; valid[r] is consulted only when MASKED.
+// mean_s[r] receives the group-mean scaled score of that row (natural units).
+template <class GEO, int R, bool MASKED>
+DEVI void attend_tile(LaneState<GEO>& st, const uint4 (&qv)[GEO::G][GEO::CH],
+                      const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+                      const int64_t (&off)[R], const bool (&valid)[R], float scale_log2,
+                      float scale_mean, float (&mean_s)[R]) {
+    constexpr int G = GEO::G, CH = GEO::CH, LPR = GEO::LPR;
+    uint4 kr[R][CH], vr[R][CH];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int j = 0; j < CH; ++j)
+            kr[r][j] = *reinterpret_cast<const uint4*>(K + off[r] + j * LPR * 8);
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int j = 0; j < CH; ++j)
+            vr[r][j] = *reinterpret_cast<const uint4*>(V + off[r] + j * LPR * 8);
+
+    float t[R][G];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        float sum_h = 0.f;
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            float s = 0.f;
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+                s = dot2_bf16(kr[r][j].x, qv[h][j].x, s);
+                s = dot2_bf16(kr[r][j].y, qv[h][j].y, s);
+                s = dot2_bf16(kr[r][j].z, qv[h][j].z, s);
+                s = dot2_bf16(kr[r][j].w, qv[h][j].w, s);
+            }
+            s = group_sum<LPR>(s);
+            sum_h += s;
+            t[r][h] = MASKED ? (valid[r] ? s * scale_log2 : NEG_BIG) : s * scale_log2;
+        }
+        mean_s[r] = sum_h * scale_mean;
+    }
+
+    // running maximum; rescale only when some lane of the wave saw a larger score
+    float m_new[G];
+    bool grow = false;
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        float mx = t[0][h];
+#pragma unroll
+        for (int r = 1; r < R; ++r) mx = fmaxf(mx, t[r][h]);
+        m_new[h] = fmaxf(st.m[h], mx);
+        grow |= m_new[h] > st.m[h];
+    }
+    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            const float alpha = fast_exp2(st.m[h] - m_new[h]);
+            st.m[h] = m_new[h];
+            st.l[h] *= alpha;
+#pragma unroll
+            for (int e = 0; e < GEO::ACC; ++e) st.acc[h][e] *= alpha;
+        }
+    }
+
+    float p[R][G];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int h = 0; h < G; ++h) {
+            float w = fast_exp2(t[r][h] - st.m[h]);
+            if (MASKED) w = valid[r] ? w : 0.f;
+            p[r][h] = w;
+            st.l[h] += w;
+        }
+
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            const uint32_t w4[4] = {vr[r][j].x, vr[r][j].y, vr[r][j].z, vr[r][j].w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float v0 = bf16_lo(w4[i]), v1 = bf16_hi(w4[i]);
+#pragma unroll
+                for (int h = 0; h < G; ++h) {
+                    st.acc[h][j * 8 + 2 * i] = fmaf(p[r][h], v0, st.acc[h][j * 8 + 2 * i]);
+                    st.acc[h][j * 8 + 2 * i + 1] = fmaf(p[r][h], v1, st.acc[h][j * 8 + 2 * i + 1]);
+                }
+            }
+        }
+}
+
+// Floats of LDS that block_merge_store needs for a workgroup of NW waves.
+template <class GEO, int NW>
+constexpr int merge_smem_floats() {
+    return NW * GEO::G * (GEO::D + 2);
+}
+
+// Merge the lane states of a whole workgroup (NW waves) into one partial per head and
+// store it:  part_ml[h*ml_stride + {0,1}] = (max in log2 units, sum),
+//            part_acc[h*acc_stride + 0..D-1] = unnormalised accumulator.
+// Every thread of the workgroup must call this.
+template <class GEO, int NW>
+DEVI void block_merge_store(LaneState<GEO>& st, float* smem, float* __restrict__ part_ml,
+                            int64_t ml_stride, float* __restrict__ part_acc, int64_t acc_stride) {
+    constexpr int G = GEO::G, D = GEO::D, LPR = GEO::LPR, ACC = GEO::ACC, CH = GEO::CH;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int chunk = lane % LPR;
+    float* s_max = smem;                    // [NW][G]
+    float* s_l = smem + NW * G;             // [NW][G]
+    float* s_acc = smem + 2 * NW * G;       // [NW][G][D]
+
+    float wmax[G];
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        float v = st.m[h];
+#pragma unroll
+        for (int mask = LPR; mask < 64; mask <<= 1) v = fmaxf(v, __shfl_xor(v, mask, 64));
+        wmax[h] = v;
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int h = 0; h < G; ++h) s_max[wave * G + h] = wmax[h];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        float M = s_max[h];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) M = fmaxf(M, s_max[w * G + h]);
+        const float f = fast_exp2(st.m[h] - M);
+        float lsum = st.l[h] * f;
+#pragma unroll
+        for (int mask = LPR; mask < 64; mask <<= 1) lsum += __shfl_xor(lsum, mask, 64);
+        if (lane == 0) s_l[wave * G + h] = lsum;
+#pragma unroll
+        for (int e = 0; e < ACC; ++e) {
+            float a = st.acc[h][e] * f;
+#pragma unroll
+            for (int mask = LPR; mask < 64; mask <<= 1) a += __shfl_xor(a, mask, 64);
+            st.acc[h][e] = a;
+        }
+        if (lane < LPR) {
+#pragma unroll
+            for (int j = 0; j < CH; ++j)
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    s_acc[(wave * G + h) * D + (chunk + j * LPR) * 8 + e] = st.acc[h][j * 8 + e];
+        }
+        wmax[h] = M;
+    }
+    __syncthreads();
+    for (int i = tid; i < G * D; i += NW * 64) {
+        const int h = i / D, col = i - h * D;
+        float a = s_acc[h * D + col];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) a += s_acc[(w * G + h) * D + col];
+        part_acc[h * acc_stride + col] = a;
+    }
+    if (tid < G) {
+        float lsum = s_l[tid];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) lsum += s_l[w * G + tid];
+        float M = s_max[tid];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) M = fmaxf(M, s_max[w * G + tid]);
+        part_ml[tid * ml_stride] = M;
+        part_ml[tid * ml_stride + 1] = lsum;
+    }
+}
+
+}  // namespace hylra

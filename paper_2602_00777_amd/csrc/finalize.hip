@@ -1,0 +1,354 @@
+// Full layer, second kernel: merge the split partials into the attention output
+// (Algorithm 2, "O <- Softmax(S) V") and select the k positions with the largest
+// group-mean score (Algorithm 2, "I <- TopK(S, B)"), ties to the lower position, written
+// in ascending order.  One workgroup of 1024 threads per (batch, KV head).
+//
+// Selection is exact and works on the fp32 scores the streaming kernel stored:
+//   1. histogram over 4096 equal-width bins spanning [min, max] of the scores (the bin
+//      index is a non-decreasing function of the score, so bins are ordered like keys);
+//   2. the bin T holding the k-th largest score and the count above it;
+//   3. the rows of bin T become candidates; if they fit in LDS their exact rank is
+//      counted pairwise (key descending, position ascending), otherwise a plain 4-pass
+//      radix select over all keys finds the threshold;
+//   4. one ordered sweep emits every row above the threshold key and the first r rows
+//      equal to it.
+// Also here: the partial merge of the Reuse layer and two measurement kernels.
+#include "device_util.h"
+#include "launch.h"
+
+namespace hylra {
+
+constexpr int SEL_THREADS = 1024;
+constexpr int SEL_WAVES = SEL_THREADS / 64;
+constexpr int SEL_BINS = 4096;
+constexpr int SEL_CAP = 1024;
+
+DEVI int wave_incl_scan(int v, int lane) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int n = __shfl_up(v, d, 64);
+        if (lane >= d) v += n;
+    }
+    return v;
+}
+
+// Exclusive prefix over the workgroup in thread order; total receives the sum.
+// s_wave holds SEL_WAVES + 1 ints.  Contains barriers: every thread must call it.
+DEVI int block_excl_scan(int v, int* s_wave, int& total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int incl = wave_incl_scan(v, lane);
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    if (wave == 0) {
+        const int w = lane < SEL_WAVES ? s_wave[lane] : 0;
+        const int wi = wave_incl_scan(w, lane);
+        if (lane < SEL_WAVES) s_wave[lane] = wi - w;
+        if (lane == SEL_WAVES - 1) s_wave[SEL_WAVES] = wi;
+    }
+    __syncthreads();
+    const int base = s_wave[wave];
+    total = s_wave[SEL_WAVES];
+    __syncthreads();
+    return base + incl - v;
+}
+
+DEVI int score_bin(float x, float lo, float inv_w) {
+    const int b = (int)((x - lo) * inv_w);
+    return min(max(b, 0), SEL_BINS - 1);
+}
+
+__global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizeParams p) {
+    __shared__ int s_hist[SEL_BINS];
+    __shared__ uint32_t s_ckey[SEL_CAP];
+    __shared__ int s_cpos[SEL_CAP];
+    __shared__ int s_wave[SEL_WAVES + 1];
+    __shared__ float s_red[2 * SEL_WAVES];
+    __shared__ int s_T, s_above, s_cand, s_gt, s_kr;
+    __shared__ uint32_t s_tau;
+
+    const int g = blockIdx.x, b = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int S = p.n_splits, D = p.D, G = p.G, N = p.N, k = p.k;
+
+    // ---- attention output: log-sum-exp merge of the S partials of each head ----
+    for (int i = tid; i < G * D; i += SEL_THREADS) {
+        const int h = i / D, col = i - h * D;
+        const int64_t head = (int64_t)b * p.Hq + (int64_t)g * G + h;
+        const float* ml = p.part_ml + head * S * 2;
+        const float* acc = p.part_acc + head * S * D + col;
+        float M = ml[0];
+        for (int s = 1; s < S; ++s) M = fmaxf(M, ml[2 * s]);
+        float num = 0.f, den = 0.f;
+        for (int s = 0; s < S; ++s) {
+            const float w = fast_exp2(ml[2 * s] - M);
+            den = fmaf(w, ml[2 * s + 1], den);
+            num = fmaf(w, acc[(int64_t)s * D], num);
+        }
+        p.out[head * D + col] = den > 0.f ? num / den : 0.f;
+    }
+
+    // ---- range of the scores ----
+    const int64_t pair = (int64_t)b * p.Hkv + g;
+    float lo = 3.0e38f, hi = -3.0e38f;
+    for (int s = tid; s < S; s += SEL_THREADS) {
+        lo = fminf(lo, p.part_mm[(pair * S + s) * 2]);
+        hi = fmaxf(hi, p.part_mm[(pair * S + s) * 2 + 1]);
+    }
+#pragma unroll
+    for (int mask = 1; mask < 64; mask <<= 1) {
+        lo = fminf(lo, __shfl_xor(lo, mask, 64));
+        hi = fmaxf(hi, __shfl_xor(hi, mask, 64));
+    }
+    if (lane == 0) {
+        s_red[2 * wave] = lo;
+        s_red[2 * wave + 1] = hi;
+    }
+    for (int i = tid; i < SEL_BINS; i += SEL_THREADS) s_hist[i] = 0;
+    if (tid == 0) s_cand = 0, s_gt = 0;
+    __syncthreads();
+    lo = s_red[0];
+    hi = s_red[1];
+#pragma unroll
+    for (int w = 1; w < SEL_WAVES; ++w) {
+        lo = fminf(lo, s_red[2 * w]);
+        hi = fmaxf(hi, s_red[2 * w + 1]);
+    }
+    const float span = hi - lo;
+    const float inv_w = (span > 0.f && span < 3.0e38f) ? (float)SEL_BINS / span : 0.f;
+
+    const float* __restrict__ sc = p.scores + pair * p.score_stride;
+    const int n4 = (N + 3) >> 2;    // float4 groups; the last may run past N inside the padding
+
+    // ---- 1. histogram ----
+    for (int i = tid; i < n4; i += SEL_THREADS) {
+        const float4 v = reinterpret_cast<const float4*>(sc)[i];
+        const float x[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (4 * i + e < N) atomicAdd(&s_hist[score_bin(x[e], lo, inv_w)], 1);
+    }
+    __syncthreads();
+
+    // ---- 2. threshold bin: thread t owns bins NB-1-4t ... NB-4-4t (top bins first) ----
+    {
+        int h4[4], local = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            h4[e] = s_hist[SEL_BINS - 1 - (4 * tid + e)];
+            local += h4[e];
+        }
+        int total;
+        const int excl = block_excl_scan(local, s_wave, total);
+        if (excl < k && k <= excl + local) {
+            int c = excl;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (c < k && k <= c + h4[e]) {
+                    s_T = SEL_BINS - 1 - (4 * tid + e);
+                    s_above = c;
+                }
+                c += h4[e];
+            }
+        }
+    }
+    __syncthreads();
+    const int T = s_T;
+    const int kr = k - s_above;      // how many of bin T's rows are selected, 1 <= kr <= |bin T|
+
+    // ---- 3. candidates of bin T ----
+    for (int i = tid; i < n4; i += SEL_THREADS) {
+        const float4 v = reinterpret_cast<const float4*>(sc)[i];
+        const float x[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (4 * i + e < N && score_bin(x[e], lo, inv_w) == T) {
+                const int slot = atomicAdd(&s_cand, 1);
+                if (slot < SEL_CAP) {
+                    s_ckey[slot] = ordered_key(x[e]);
+                    s_cpos[slot] = 4 * i + e;
+                }
+            }
+    }
+    __syncthreads();
+    const int n_cand = s_cand;
+
+    uint32_t tau;
+    int r;   // rows equal to tau that are selected (lowest positions first)
+    if (n_cand <= SEL_CAP) {
+        // exact rank of every candidate under (key descending, position ascending)
+        for (int i = tid; i < n_cand; i += SEL_THREADS) {
+            const uint32_t key = s_ckey[i];
+            const int pos = s_cpos[i];
+            int rank = 0;
+            for (int j = 0; j < n_cand; ++j) {
+                const uint32_t kj = s_ckey[j];
+                rank += (kj > key) || (kj == key && s_cpos[j] < pos);
+            }
+            if (rank == kr - 1) s_tau = key;
+        }
+        __syncthreads();
+        tau = s_tau;
+        int gt = 0;
+        for (int i = tid; i < n_cand; i += SEL_THREADS) gt += s_ckey[i] > tau;
+        if (gt) atomicAdd(&s_gt, gt);
+        __syncthreads();
+        r = kr - s_gt;
+    } else {
+        // rare: too many rows share the threshold bin (e.g. massive ties).  Plain radix
+        // select over all keys, 8 bits per pass; s_hist[0..255] is the digit histogram.
+        uint32_t prefix = 0, mask = 0;
+        int want = k;
+        for (int shift = 24; shift >= 0; shift -= 8) {
+            __syncthreads();
+            for (int i = tid; i < 256; i += SEL_THREADS) s_hist[i] = 0;
+            __syncthreads();
+            for (int i = tid; i < n4; i += SEL_THREADS) {
+                const float4 v = reinterpret_cast<const float4*>(sc)[i];
+                const float x[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t key = ordered_key(x[e]);
+                    if (4 * i + e < N && (key & mask) == prefix)
+                        atomicAdd(&s_hist[(key >> shift) & 255], 1);
+                }
+            }
+            __syncthreads();
+            if (tid == 0) {
+                int c = 0, dg = 255;
+                for (; dg > 0; --dg) {
+                    if (c + s_hist[dg] >= want) break;
+                    c += s_hist[dg];
+                }
+                s_kr = want - c;
+                s_tau = prefix | ((uint32_t)dg << shift);
+            }
+            __syncthreads();
+            want = s_kr;
+            prefix = s_tau;
+            mask |= 0xffu << shift;
+        }
+        tau = prefix;
+        r = want;
+    }
+
+    // ---- 4. ordered emission: thread t owns 4 consecutive rows of each 4096-row tile ----
+    int32_t* __restrict__ dst = p.idx + pair * (int64_t)k;
+    int base_gt = 0, base_eq = 0;
+    for (int tile0 = 0; tile0 < n4; tile0 += SEL_THREADS) {
+        const int i = tile0 + tid;
+        uint32_t key[4];
+        bool in[4];
+        int cnt = 0;    // low 16 bits: rows above tau, high 16 bits: rows equal to tau
+        if (i < n4) {
+            const float4 v = reinterpret_cast<const float4*>(sc)[i];
+            const float x[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                in[e] = 4 * i + e < N;
+                key[e] = ordered_key(x[e]);
+                if (in[e]) cnt += (key[e] > tau) ? 1 : ((key[e] == tau) ? 0x10000 : 0);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) in[e] = false, key[e] = 0;
+        }
+        int total;
+        const int excl = block_excl_scan(cnt, s_wave, total);
+        int gt_before = base_gt + (excl & 0xffff);
+        int eq_before = base_eq + (excl >> 16);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (!in[e]) continue;
+            if (key[e] > tau) {
+                const int o = gt_before + min(eq_before, r);
+                if (o < k) dst[o] = 4 * i + e;
+                ++gt_before;
+            } else if (key[e] == tau) {
+                if (eq_before < r) {
+                    const int o = gt_before + eq_before;
+                    if (o < k) dst[o] = 4 * i + e;
+                }
+                ++eq_before;
+            }
+        }
+        base_gt += total & 0xffff;
+        base_eq += total >> 16;
+    }
+}
+
+hipError_t launch_full_finalize(const FinalizeParams& p, int B, hipStream_t st) {
+    hipLaunchKernelGGL(full_finalize_kernel, dim3(p.Hkv, B), dim3(SEL_THREADS), 0, st, p);
+    return hipGetLastError();
+}
+
+// ---- Reuse layer: merge of the split partials, one workgroup per query head ----
+__global__ __launch_bounds__(128) void combine_kernel(CombineParams p) {
+    const int64_t head = blockIdx.x;
+    const int S = p.n_splits, D = p.D;
+    const float* ml = p.part_ml + head * S * 2;
+    float M = ml[0];
+    for (int s = 1; s < S; ++s) M = fmaxf(M, ml[2 * s]);
+    for (int col = threadIdx.x; col < D; col += blockDim.x) {
+        const float* acc = p.part_acc + head * S * D + col;
+        float num = 0.f, den = 0.f;
+        for (int s = 0; s < S; ++s) {
+            const float w = fast_exp2(ml[2 * s] - M);
+            den = fmaf(w, ml[2 * s + 1], den);
+            num = fmaf(w, acc[(int64_t)s * D], num);
+        }
+        p.out[head * D + col] = den > 0.f ? num / den : 0.f;
+    }
+}
+
+hipError_t launch_combine(const CombineParams& p, int n_heads_total, hipStream_t st) {
+    hipLaunchKernelGGL(combine_kernel, dim3(n_heads_total), dim3(128), 0, st, p);
+    return hipGetLastError();
+}
+
+// ---- measurement kernels ----
+__global__ __launch_bounds__(256) void probe_copy_kernel(uint4* __restrict__ dst,
+                                                         const uint4* __restrict__ src, size_t n16) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride)
+        dst[i] = src[i];
+}
+
+__global__ __launch_bounds__(256) void probe_read_kernel(const uint4* __restrict__ src, size_t n16,
+                                                         uint32_t* __restrict__ sink) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    uint32_t acc = 0;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^
+               d.z ^ d.w;
+    }
+    for (; i < n16; i += stride) {
+        const uint4 a = src[i];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w;
+    }
+#pragma unroll
+    for (int mask = 1; mask < 64; mask <<= 1) acc ^= __shfl_xor((int)acc, mask, 64);
+    __shared__ uint32_t s[4];
+    if ((threadIdx.x & 63) == 0) s[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) sink[blockIdx.x] = s[0] ^ s[1] ^ s[2] ^ s[3];
+}
+
+constexpr int kProbeBlocks = 4096;   // sink needs kProbeBlocks words
+
+hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t st) {
+    hipLaunchKernelGGL(probe_copy_kernel, dim3(kProbeBlocks), dim3(256), 0, st,
+                       reinterpret_cast<uint4*>(dst), reinterpret_cast<const uint4*>(src),
+                       bytes / 16);
+    return hipGetLastError();
+}
+
+hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t st) {
+    hipLaunchKernelGGL(probe_read_kernel, dim3(kProbeBlocks), dim3(256), 0, st,
+                       reinterpret_cast<const uint4*>(src), bytes / 16,
+                       reinterpret_cast<uint32_t*>(sink));
+    return hipGetLastError();
+}
+
+}  // namespace hylra

@@ -1,0 +1,72 @@
+// Internal interface between the host API and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hylra {
+
+constexpr int kMaxGroup = 8;        // query heads per KV head
+constexpr int kMaxSplits = 1024;    // partials per (batch, KV head) the finalise kernels accept
+
+struct FullParams {
+    const uint16_t* q;
+    const uint16_t* K;
+    const uint16_t* V;
+    int64_t sb, sh, sn;             // element strides of K and V
+    int Hq, Hkv, N;
+    int rows_per_split, n_splits;
+    float scale_log2;               // scale * log2(e)
+    float scale_mean;               // scale / G
+    float* part_ml;                 // [B*Hq][S][2]   (max in log2 units, sum)
+    float* part_acc;                // [B*Hq][S][D]
+    float* part_mm;                 // [B*Hkv][S][2]  (min, max of the group-mean scores)
+    float* scores;                  // [B*Hkv][score_stride] group-mean scaled scores
+    int64_t score_stride;           // multiple of 4, >= N
+};
+
+struct FinalizeParams {
+    const float* part_ml;
+    const float* part_acc;
+    const float* part_mm;
+    const float* scores;
+    int64_t score_stride;
+    int n_splits, Hq, Hkv, G, D, N, k;
+    float* out;                     // [B][Hq][D]
+    int32_t* idx;                   // [B][Hkv][k]
+};
+
+struct ReuseParams {
+    const uint16_t* q;
+    const uint16_t* K;
+    const uint16_t* V;
+    int64_t sb, sh, sn;
+    int Hq, Hkv, N, k;
+    int rows_per_split, n_splits;
+    float scale_log2;
+    const int32_t* idx;             // [B][Hkv][k]
+    float* part_ml;                 // [B*Hq][S][2]
+    float* part_acc;                // [B*Hq][S][D]
+};
+
+struct CombineParams {
+    const float* part_ml;
+    const float* part_acc;
+    int n_splits, D;
+    float* out;                     // [n_heads_total][D]
+};
+
+// Rows of the cache one workgroup of the Full kernel consumes per sweep of its 4 waves
+// (rows_per_split must be a multiple of it).  0 if (D, G, variant) is not built.
+int full_block_quantum(int D, int G, int variant);
+// Index entries per workgroup sweep of the Reuse kernel for unroll R in {1, 2, 4}.
+int reuse_block_quantum(int D, int G, int variant, int R);
+
+hipError_t launch_full_split(const FullParams& p, int B, int D, int G, int variant, hipStream_t st);
+hipError_t launch_full_finalize(const FinalizeParams& p, int B, hipStream_t st);
+hipError_t launch_reuse_split(const ReuseParams& p, int B, int D, int G, int variant, int R,
+                              hipStream_t st);
+hipError_t launch_combine(const CombineParams& p, int n_heads_total, hipStream_t st);
+hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
+hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t st);
+
+}  // namespace hylra
