@@ -125,10 +125,17 @@ hylra_status hylra_decode_step(hylra_ctx *ctx, const hylra_shape *shape, int32_t
 
 /*
  * Tuning knobs (HOST call, takes effect for later launches).  Unknown names give
- * HYLRA_ERR_BAD_ARG.  Names:
- *   "full_split_rows"   rows of the cache per workgroup of the Full kernel (0 = automatic)
- *   "reuse_split_rows"  index entries per workgroup of the Reuse kernel    (0 = automatic)
- *   "full_variant", "reuse_variant"  kernel variant number (0 = default)
+ * HYLRA_ERR_BAD_ARG; 0 always means "automatic / default".  Names:
+ *   "full_split_rows"   rows of the cache per workgroup of the Full kernel
+ *   "reuse_split_rows"  index entries per workgroup of the Reuse kernel
+ *   "full_variant"      10*mode + unroll of the Full kernel: 4 (plain loads), 14 (streaming
+ *                       loads), 23 (streaming loads, two-deep register pipeline; default),
+ *                       34 / 32 (rows claimed dynamically through a shared counter)
+ *   "reuse_variant"     1 = plain loads instead of streaming loads in the Reuse kernel
+ *   "reuse_unroll"      row groups per wave tile of the Reuse kernel: 1, 2, 4 or 8
+ *   "reuse_unfused"     1 = merge the Reuse partials in a second kernel instead of in the
+ *                       last-arriving workgroup of the Reuse kernel
+ *   "finalize_variant"  1 = the Full finalise kernel re-reads the scores in every pass
  */
 hylra_status hylra_set_option(hylra_ctx *ctx, const char *name, int32_t value);
 
@@ -140,8 +147,8 @@ hylra_status hylra_set_option(hylra_ctx *ctx, const char *name, int32_t value);
  * synchronises those events and returns, per kernel class, the number of
  * launches and the summed duration in milliseconds since the last
  * hylra_profile_reset.  Classes: 0 = Full attention (split-KV pass),
- * 1 = Full finalise (combine + top-k), 2 = Reuse attention, 3 = Reuse combine,
- * 4 = probe kernels.  At most HYLRA_PROFILE_MAX_EVENTS launches are recorded
+ * 1 = Full finalise (combine + top-k), 2 = Reuse attention, 3 = Reuse combine (absent
+ * in the fused mode), 4 = probe kernels.  At most HYLRA_PROFILE_MAX_EVENTS launches are recorded
  * between resets; later ones run untimed.
  */
 #define HYLRA_PROFILE_CLASSES 5

@@ -15,7 +15,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhylra.so")
-SOURCES = ["api.hip", "full_attn.hip", "reuse_attn.hip", "finalize.hip"]
+SOURCES = ["api.hip", "full_attn_d64.hip", "full_attn_d128.hip", "reuse_attn_d64.hip",
+           "reuse_attn_d128.hip", "finalize.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-FP32 code generation is switched off on purpose (device pass only)
@@ -35,12 +36,21 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(jobs: int = 4) -> str:
+def build(jobs: int = 6) -> str:
+    """Compile and link.  HYLRA_EXTRA_FLAGS adds compiler flags and HYLRA_LIB_OUT redirects
+    the output (both only for tuning builds; the product build uses neither)."""
+    global BUILD, LIB
+    extra = os.environ.get("HYLRA_EXTRA_FLAGS", "").split()
+    if extra:
+        FLAGS.extend(extra)
+        LIB = os.environ.get("HYLRA_LIB_OUT", LIB)
+        BUILD = BUILD + "_extra"
     os.makedirs(BUILD, exist_ok=True)
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(_compile, SOURCES))
     tmp = LIB + ".tmp%d" % os.getpid()
-    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs,
+    link_extra = [f for f in extra if f.startswith("-fgpu-rdc")]
+    r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC"] + link_extra + ["-o", tmp] + objs,
                        capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError("link failed:\n" + r.stderr)

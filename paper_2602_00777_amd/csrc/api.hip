@@ -16,7 +16,8 @@ using namespace hylra;
 
 namespace {
 
-constexpr int kTargetBlocksFull = 2048;   // workgroups the Full kernel aims for (8 per CU)
+constexpr int kTargetBlocksFull = 512;    // workgroups the Full kernel aims for: two per CU,
+                                          // all resident at once (measured best on MI355X)
 constexpr int kMinBlocksReuse = 512;      // below this the Reuse kernel uses a shorter unroll
 constexpr int64_t kMinSlots = 8192;       // partial slots ((batch, KV head, split) triples) kept
 constexpr float LOG2E_HOST = 1.4426950408889634f;
@@ -37,6 +38,8 @@ struct hylra_ctx {
     float* part_acc = nullptr;
     float* part_mm = nullptr;
     float* scores = nullptr;
+    int* counters = nullptr;    // one arrival counter per (batch, KV head), zero between launches
+    int* row_ctr = nullptr;     // one row counter per (batch, KV head), zero between launches
     int64_t slots = 0;          // capacity in (batch, KV head, split) triples
     int64_t cap_acc = 0;        // floats
     int64_t cap_ml = 0;
@@ -46,6 +49,9 @@ struct hylra_ctx {
     int32_t opt_reuse_split_rows = 0;
     int32_t opt_full_variant = 0;
     int32_t opt_reuse_variant = 0;
+    int32_t opt_reuse_unroll = 0;
+    int32_t opt_reuse_unfused = 0;
+    int32_t opt_finalize_variant = 0;
 
     bool prof_on = false;
     int prof_n = 0;
@@ -183,12 +189,12 @@ hylra_status plan_reuse(const hylra_ctx* ctx, const hylra_shape* s, int G, int k
     pl.variant = ctx->opt_reuse_variant;
     const int64_t pairs = (int64_t)s->batch * s->n_kv_heads;
     pl.R = 0;
-    for (int R = 4; R >= 1; R >>= 1) {
+    for (int R = ctx->opt_reuse_unroll > 0 ? ctx->opt_reuse_unroll : 8; R >= 1; R >>= 1) {
         const int quantum = reuse_block_quantum(s->head_dim, G, pl.variant, R);
-        if (quantum <= 0) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "Reuse kernel variant %d is not built for d=%d G=%d", pl.variant, s->head_dim, G);
+        if (quantum <= 0) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "Reuse kernel variant %d / unroll %d is not built for d=%d G=%d", pl.variant, R, s->head_dim, G);
         pl.R = R;
         pl.rows_per_split = quantum;
-        if (pairs * ceil_div(k, quantum) >= kMinBlocksReuse) break;
+        if (ctx->opt_reuse_unroll > 0 || pairs * ceil_div(k, quantum) >= kMinBlocksReuse) break;
     }
     int64_t rps = pl.rows_per_split;
     if (ctx->opt_reuse_split_rows > 0) rps = round_up(ctx->opt_reuse_split_rows, pl.rows_per_split);
@@ -270,6 +276,11 @@ hylra_status hylra_create(hylra_ctx** out, const hylra_shape* max_shape, int32_t
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->part_ml, ctx->cap_ml * sizeof(float));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->part_mm, ctx->slots * 2 * sizeof(float));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->scores, ctx->cap_scores * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->counters, ctx->slots * sizeof(int));
+    if (e == hipSuccess) e = hipMemset(ctx->counters, 0, ctx->slots * sizeof(int));
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->row_ctr, ctx->slots * sizeof(int));
+    if (e == hipSuccess) e = hipMemset(ctx->row_ctr, 0, ctx->slots * sizeof(int));
+    if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         fail(nullptr, HYLRA_ERR_HIP, "workspace allocation failed: %s", hipGetErrorString(e));
         hylra_destroy(ctx);
@@ -291,6 +302,8 @@ hylra_status hylra_destroy(hylra_ctx* ctx) {
     if (ctx->part_ml) (void)hipFree(ctx->part_ml);
     if (ctx->part_mm) (void)hipFree(ctx->part_mm);
     if (ctx->scores) (void)hipFree(ctx->scores);
+    if (ctx->counters) (void)hipFree(ctx->counters);
+    if (ctx->row_ctr) (void)hipFree(ctx->row_ctr);
     delete ctx;
     return HYLRA_OK;
 }
@@ -302,6 +315,9 @@ hylra_status hylra_set_option(hylra_ctx* ctx, const char* name, int32_t value) {
     else if (!std::strcmp(name, "reuse_split_rows")) ctx->opt_reuse_split_rows = value;
     else if (!std::strcmp(name, "full_variant")) ctx->opt_full_variant = value;
     else if (!std::strcmp(name, "reuse_variant")) ctx->opt_reuse_variant = value;
+    else if (!std::strcmp(name, "reuse_unroll")) ctx->opt_reuse_unroll = value;
+    else if (!std::strcmp(name, "reuse_unfused")) ctx->opt_reuse_unfused = value;
+    else if (!std::strcmp(name, "finalize_variant")) ctx->opt_finalize_variant = value;
     else return fail(ctx, HYLRA_ERR_BAD_ARG, "unknown option '%s'", name);
     return HYLRA_OK;
 }
@@ -336,6 +352,7 @@ hylra_status hylra_full_attn_topk(hylra_ctx* ctx, const hylra_shape* shape, cons
     fp.part_ml = ctx->part_ml, fp.part_acc = ctx->part_acc, fp.part_mm = ctx->part_mm;
     fp.scores = ctx->scores;
     fp.score_stride = round_up(shape->ctx_len, 4);
+    fp.row_ctr = ctx->row_ctr;
     HIP_TRY(ctx, launch_timed(ctx, 0, st, [&] {
                 return launch_full_split(fp, shape->batch, shape->head_dim, G, pl.variant, st);
             }));
@@ -345,6 +362,8 @@ hylra_status hylra_full_attn_topk(hylra_ctx* ctx, const hylra_shape* shape, cons
     zp.scores = ctx->scores, zp.score_stride = fp.score_stride;
     zp.n_splits = pl.n_splits, zp.Hq = shape->n_q_heads, zp.Hkv = shape->n_kv_heads;
     zp.G = G, zp.D = shape->head_dim, zp.N = shape->ctx_len, zp.k = k;
+    zp.variant = ctx->opt_finalize_variant;
+    zp.row_ctr = ctx->row_ctr;
     zp.out = out, zp.idx = idx;
     HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_full_finalize(zp, shape->batch, st); }));
     return HYLRA_OK;
@@ -378,9 +397,13 @@ hylra_status hylra_reuse_sparse_attn(hylra_ctx* ctx, const hylra_shape* shape, c
     rp.scale_log2 = scale * LOG2E_HOST;
     rp.idx = idx;
     rp.part_ml = ctx->part_ml, rp.part_acc = ctx->part_acc;
+    const bool fused = ctx->opt_reuse_unfused == 0;
+    rp.counters = fused ? ctx->counters : nullptr;
+    rp.out = out;
     HIP_TRY(ctx, launch_timed(ctx, 2, st, [&] {
                 return launch_reuse_split(rp, shape->batch, shape->head_dim, G, pl.variant, pl.R, st);
             }));
+    if (fused) return HYLRA_OK;
     CombineParams cp{};
     cp.part_ml = ctx->part_ml, cp.part_acc = ctx->part_acc;
     cp.n_splits = pl.n_splits, cp.D = shape->head_dim, cp.out = out;

@@ -51,26 +51,52 @@ DEVI void load_q(uint4 (&qv)[GEO::G][GEO::CH], const uint16_t* __restrict__ q_gr
             qv[h][j] = *reinterpret_cast<const uint4*>(q_group + h * GEO::D + (chunk + j * GEO::LPR) * 8);
 }
 
-// One tile of R row groups.  off[r] is the element offset (from K and from V) of this
-// lane's first piece of its row in group r; valid[r] is consulted only when MASKED.
-// mean_s[r] receives the group-mean scaled score of that row (natural units).
+// Register image of one tile: R row groups of K and of V, CH 16-byte pieces each.
+template <class GEO, int R>
+struct TileBuf {
+    uint4 k[R][GEO::CH];
+    uint4 v[R][GEO::CH];
+};
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+// 16-byte load; NT marks the line as streaming (K and V rows are read once and never again,
+// so they should not displace anything in L2 / the memory-side cache).
+template <bool NT>
+DEVI uint4 load16(const uint16_t* __restrict__ p) {
+    if (NT) {
+        const u32x4_t t = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+        return make_uint4(t.x, t.y, t.z, t.w);
+    }
+    return *reinterpret_cast<const uint4*>(p);
+}
+
+// Issue the loads of one tile.  off[r] is the element offset (from K and from V) of this
+// lane's first piece of its row in group r.
+template <class GEO, int R, bool NT>
+DEVI void load_tile(TileBuf<GEO, R>& b, const uint16_t* __restrict__ K,
+                    const uint16_t* __restrict__ V, const int64_t (&off)[R]) {
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int j = 0; j < GEO::CH; ++j)
+            b.k[r][j] = load16<NT>(K + off[r] + j * GEO::LPR * 8);
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int j = 0; j < GEO::CH; ++j)
+            b.v[r][j] = load16<NT>(V + off[r] + j * GEO::LPR * 8);
+}
+
+// Consume one loaded tile.  valid[r] is consulted only when MASKED.  mean_s[r] receives the
+// group-mean scaled score of that row (natural units).
 template <class GEO, int R, bool MASKED>
-DEVI void attend_tile(LaneState<GEO>& st, const uint4 (&qv)[GEO::G][GEO::CH],
-                      const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-                      const int64_t (&off)[R], const bool (&valid)[R], float scale_log2,
-                      float scale_mean, float (&mean_s)[R]) {
+DEVI void compute_tile(LaneState<GEO>& st, const uint4 (&qv)[GEO::G][GEO::CH],
+                       const TileBuf<GEO, R>& b, const bool (&valid)[R], float scale_log2,
+                       float scale_mean, float (&mean_s)[R]) {
     constexpr int G = GEO::G, CH = GEO::CH, LPR = GEO::LPR;
-    uint4 kr[R][CH], vr[R][CH];
-#pragma unroll
-    for (int r = 0; r < R; ++r)
-#pragma unroll
-        for (int j = 0; j < CH; ++j)
-            kr[r][j] = *reinterpret_cast<const uint4*>(K + off[r] + j * LPR * 8);
-#pragma unroll
-    for (int r = 0; r < R; ++r)
-#pragma unroll
-        for (int j = 0; j < CH; ++j)
-            vr[r][j] = *reinterpret_cast<const uint4*>(V + off[r] + j * LPR * 8);
+    const uint4 (&kr)[R][CH] = b.k;
+    const uint4 (&vr)[R][CH] = b.v;
 
     float t[R][G];
 #pragma unroll
@@ -143,6 +169,17 @@ DEVI void attend_tile(LaneState<GEO>& st, const uint4 (&qv)[GEO::G][GEO::CH],
         }
 }
 
+// Load and consume one tile in one go.
+template <class GEO, int R, bool MASKED, bool NT = false>
+DEVI void attend_tile(LaneState<GEO>& st, const uint4 (&qv)[GEO::G][GEO::CH],
+                      const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+                      const int64_t (&off)[R], const bool (&valid)[R], float scale_log2,
+                      float scale_mean, float (&mean_s)[R]) {
+    TileBuf<GEO, R> b;
+    load_tile<GEO, R, NT>(b, K, V, off);
+    compute_tile<GEO, R, MASKED>(st, qv, b, valid, scale_log2, scale_mean, mean_s);
+}
+
 // Floats of LDS that block_merge_store needs for a workgroup of NW waves.
 template <class GEO, int NW>
 constexpr int merge_smem_floats() {
@@ -152,8 +189,10 @@ constexpr int merge_smem_floats() {
 // Merge the lane states of a whole workgroup (NW waves) into one partial per head and
 // store it:  part_ml[h*ml_stride + {0,1}] = (max in log2 units, sum),
 //            part_acc[h*acc_stride + 0..D-1] = unnormalised accumulator.
-// Every thread of the workgroup must call this.
-template <class GEO, int NW>
+// Every thread of the workgroup must call this.  With COHERENT the partial is written with
+// device-scope write-through stores, so that another workgroup can read it in the same
+// launch (see coherent_load) without a full cache write-back.
+template <class GEO, int NW, bool COHERENT = false>
 DEVI void block_merge_store(LaneState<GEO>& st, float* smem, float* __restrict__ part_ml,
                             int64_t ml_stride, float* __restrict__ part_acc, int64_t acc_stride) {
     constexpr int G = GEO::G, D = GEO::D, LPR = GEO::LPR, ACC = GEO::ACC, CH = GEO::CH;
@@ -200,7 +239,6 @@ DEVI void block_merge_store(LaneState<GEO>& st, float* smem, float* __restrict__
                 for (int e = 0; e < 8; ++e)
                     s_acc[(wave * G + h) * D + (chunk + j * LPR) * 8 + e] = st.acc[h][j * 8 + e];
         }
-        wmax[h] = M;
     }
     __syncthreads();
     for (int i = tid; i < G * D; i += NW * 64) {
@@ -208,7 +246,8 @@ DEVI void block_merge_store(LaneState<GEO>& st, float* smem, float* __restrict__
         float a = s_acc[h * D + col];
 #pragma unroll
         for (int w = 1; w < NW; ++w) a += s_acc[(w * G + h) * D + col];
-        part_acc[h * acc_stride + col] = a;
+        if (COHERENT) coherent_store(part_acc + h * acc_stride + col, a);
+        else part_acc[h * acc_stride + col] = a;
     }
     if (tid < G) {
         float lsum = s_l[tid];
@@ -217,8 +256,13 @@ DEVI void block_merge_store(LaneState<GEO>& st, float* smem, float* __restrict__
         float M = s_max[tid];
 #pragma unroll
         for (int w = 1; w < NW; ++w) M = fmaxf(M, s_max[w * G + tid]);
-        part_ml[tid * ml_stride] = M;
-        part_ml[tid * ml_stride + 1] = lsum;
+        if (COHERENT) {
+            coherent_store(part_ml + tid * ml_stride, M);
+            coherent_store(part_ml + tid * ml_stride + 1, lsum);
+        } else {
+            part_ml[tid * ml_stride] = M;
+            part_ml[tid * ml_stride + 1] = lsum;
+        }
     }
 }
 

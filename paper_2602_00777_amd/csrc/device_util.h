@@ -46,6 +46,32 @@ DEVI uint32_t ordered_key(float f) {
     return u ^ ((u >> 31) ? 0xffffffffu : 0x80000000u);
 }
 
+// Device-scope relaxed accesses: performed at the point where all compute units of the GPU
+// agree (each group of compute units has its own L2), so a value written by one workgroup
+// can be read by another during the same launch once the writer's store has completed.
+DEVI void coherent_store(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+DEVI float coherent_load(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Wait until every vector memory operation this wave has issued is complete.
+DEVI void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+// Phase timestamps for kernel tuning; compiled in only with -DHYLRA_TRACE (never in the
+// product build).  Slot s of workgroup w lands in trace[w * 16 + s] (100 MHz wall clock).
+#ifdef HYLRA_TRACE
+extern __device__ long long* g_trace;
+#define HYLRA_TS(slot)                                                                       \
+    do {                                                                                     \
+        if (threadIdx.x == 0 && g_trace)                                                     \
+            g_trace[((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 +  \
+                    (slot)] = wall_clock64();                                                \
+    } while (0)
+#else
+#define HYLRA_TS(slot) do { } while (0)
+#endif
+
 constexpr float NEG_BIG = -1.0e30f;   // "minus infinity" that stays finite under subtraction
 constexpr float LOG2E = 1.4426950408889634f;
 

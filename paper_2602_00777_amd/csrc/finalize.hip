@@ -16,12 +16,22 @@
 #include "device_util.h"
 #include "launch.h"
 
+#ifdef HYLRA_TRACE
+namespace hylra {
+__device__ long long* g_trace = nullptr;
+}
+extern "C" int hylra_debug_set_trace(void* device_buffer) {
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(hylra::g_trace), &device_buffer, sizeof(void*));
+}
+#endif
+
 namespace hylra {
 
 constexpr int SEL_THREADS = 1024;
 constexpr int SEL_WAVES = SEL_THREADS / 64;
 constexpr int SEL_BINS = 4096;
 constexpr int SEL_CAP = 1024;
+constexpr int SEL_ML_CAP = 2048;   // (max, sum) pairs of one KV head's partials staged in LDS
 
 DEVI int wave_incl_scan(int v, int lane) {
 #pragma unroll
@@ -57,38 +67,111 @@ DEVI int score_bin(float x, float lo, float inv_w) {
     return min(max(b, 0), SEL_BINS - 1);
 }
 
+// Where the finalise kernel gets the scores of its (batch, KV head) from.
+//
+// RegScores<E>: thread t keeps float4 groups t, t+1024, ..., t+1024*(E-1) in registers, so the
+// scores are read from memory exactly once (N <= 4096*E).  E = 0: nothing is kept and every
+// pass re-reads the scores (any N).
+template <int E>
+struct RegScores {
+    float4 v[E > 0 ? E : 1];
+    const float* sc;
+    int N, n4;
+    DEVI void init(const float* scores, int n) {
+        sc = scores;
+        N = n;
+        n4 = (n + 3) >> 2;     // float4 groups; the last may run past N inside the padding
+        if (E > 0) {
+#pragma unroll
+            for (int j = 0; j < E; ++j) {
+                const int i = j * SEL_THREADS + (int)threadIdx.x;
+                v[j] = i < n4 ? reinterpret_cast<const float4*>(sc)[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+    }
+    // f(position, score) for every row this thread owns
+    template <class F>
+    DEVI void for_each(F&& f) const {
+        if (E > 0) {
+#pragma unroll
+            for (int j = 0; j < E; ++j) {
+                const int i = j * SEL_THREADS + (int)threadIdx.x;
+                const float x[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (4 * i + e < N) f(4 * i + e, x[e]);
+            }
+        } else {
+            for (int i = threadIdx.x; i < n4; i += SEL_THREADS) {
+                const float4 q = reinterpret_cast<const float4*>(sc)[i];
+                const float x[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (4 * i + e < N) f(4 * i + e, x[e]);
+            }
+        }
+    }
+};
+
+template <int E>
 __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizeParams p) {
     __shared__ int s_hist[SEL_BINS];
     __shared__ uint32_t s_ckey[SEL_CAP];
     __shared__ int s_cpos[SEL_CAP];
     __shared__ int s_wave[SEL_WAVES + 1];
     __shared__ float s_red[2 * SEL_WAVES];
+    __shared__ float s_m[SEL_ML_CAP], s_l[SEL_ML_CAP];
+    __shared__ int s_tot_gt[(E > 0 ? E : 1) * SEL_WAVES + 1];
+    __shared__ int s_tot_eq[(E > 0 ? E : 1) * SEL_WAVES + 1];
     __shared__ int s_T, s_above, s_cand, s_gt, s_kr;
     __shared__ uint32_t s_tau;
 
     const int g = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int S = p.n_splits, D = p.D, G = p.G, N = p.N, k = p.k;
+    const int64_t pair = (int64_t)b * p.Hkv + g;
+
+    HYLRA_TS(0);
+    if (tid == 0) p.row_ctr[pair] = 0;
+    RegScores<E> src;
+    src.init(p.scores + pair * p.score_stride, N);      // loads are in flight from here on
 
     // ---- attention output: log-sum-exp merge of the S partials of each head ----
+    // (max, sum) pairs go through LDS so that all loads are issued at once; the accumulator
+    // columns are then read with independent loads.
+    const int64_t head0 = (int64_t)b * p.Hq + (int64_t)g * G;
+    const bool ml_in_lds = G * S <= SEL_ML_CAP;
+    if (ml_in_lds) {
+        for (int t = tid; t < G * S; t += SEL_THREADS) {
+            const float2 ml = reinterpret_cast<const float2*>(p.part_ml + head0 * S * 2)[t];
+            s_m[t] = ml.x;
+            s_l[t] = ml.y;
+        }
+        __syncthreads();
+    }
     for (int i = tid; i < G * D; i += SEL_THREADS) {
         const int h = i / D, col = i - h * D;
-        const int64_t head = (int64_t)b * p.Hq + (int64_t)g * G + h;
-        const float* ml = p.part_ml + head * S * 2;
-        const float* acc = p.part_acc + head * S * D + col;
-        float M = ml[0];
-        for (int s = 1; s < S; ++s) M = fmaxf(M, ml[2 * s]);
+        const float* ml = p.part_ml + (head0 + h) * S * 2;
+        const float* acc = p.part_acc + (head0 + h) * S * D + col;
+        float M = NEG_BIG;
+        if (ml_in_lds) {
+            for (int s = 0; s < S; ++s) M = fmaxf(M, s_m[h * S + s]);
+        } else {
+#pragma unroll 8
+            for (int s = 0; s < S; ++s) M = fmaxf(M, ml[2 * s]);
+        }
         float num = 0.f, den = 0.f;
+#pragma unroll 8
         for (int s = 0; s < S; ++s) {
-            const float w = fast_exp2(ml[2 * s] - M);
-            den = fmaf(w, ml[2 * s + 1], den);
+            const float w = fast_exp2((ml_in_lds ? s_m[h * S + s] : ml[2 * s]) - M);
+            den = fmaf(w, ml_in_lds ? s_l[h * S + s] : ml[2 * s + 1], den);
             num = fmaf(w, acc[(int64_t)s * D], num);
         }
-        p.out[head * D + col] = den > 0.f ? num / den : 0.f;
+        p.out[(head0 + h) * D + col] = den > 0.f ? num / den : 0.f;
     }
 
+    HYLRA_TS(1);
     // ---- range of the scores ----
-    const int64_t pair = (int64_t)b * p.Hkv + g;
     float lo = 3.0e38f, hi = -3.0e38f;
     for (int s = tid; s < S; s += SEL_THREADS) {
         lo = fminf(lo, p.part_mm[(pair * S + s) * 2]);
@@ -116,19 +199,12 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
     const float span = hi - lo;
     const float inv_w = (span > 0.f && span < 3.0e38f) ? (float)SEL_BINS / span : 0.f;
 
-    const float* __restrict__ sc = p.scores + pair * p.score_stride;
-    const int n4 = (N + 3) >> 2;    // float4 groups; the last may run past N inside the padding
-
+    HYLRA_TS(2);
     // ---- 1. histogram ----
-    for (int i = tid; i < n4; i += SEL_THREADS) {
-        const float4 v = reinterpret_cast<const float4*>(sc)[i];
-        const float x[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (4 * i + e < N) atomicAdd(&s_hist[score_bin(x[e], lo, inv_w)], 1);
-    }
+    src.for_each([&](int, float x) { atomicAdd(&s_hist[score_bin(x, lo, inv_w)], 1); });
     __syncthreads();
 
+    HYLRA_TS(3);
     // ---- 2. threshold bin: thread t owns bins NB-1-4t ... NB-4-4t (top bins first) ----
     {
         int h4[4], local = 0;
@@ -155,23 +231,21 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
     const int T = s_T;
     const int kr = k - s_above;      // how many of bin T's rows are selected, 1 <= kr <= |bin T|
 
+    HYLRA_TS(4);
     // ---- 3. candidates of bin T ----
-    for (int i = tid; i < n4; i += SEL_THREADS) {
-        const float4 v = reinterpret_cast<const float4*>(sc)[i];
-        const float x[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (4 * i + e < N && score_bin(x[e], lo, inv_w) == T) {
-                const int slot = atomicAdd(&s_cand, 1);
-                if (slot < SEL_CAP) {
-                    s_ckey[slot] = ordered_key(x[e]);
-                    s_cpos[slot] = 4 * i + e;
-                }
+    src.for_each([&](int pos, float x) {
+        if (score_bin(x, lo, inv_w) == T) {
+            const int slot = atomicAdd(&s_cand, 1);
+            if (slot < SEL_CAP) {
+                s_ckey[slot] = ordered_key(x);
+                s_cpos[slot] = pos;
             }
-    }
+        }
+    });
     __syncthreads();
     const int n_cand = s_cand;
 
+    HYLRA_TS(5);
     uint32_t tau;
     int r;   // rows equal to tau that are selected (lowest positions first)
     if (n_cand <= SEL_CAP) {
@@ -202,16 +276,10 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
             __syncthreads();
             for (int i = tid; i < 256; i += SEL_THREADS) s_hist[i] = 0;
             __syncthreads();
-            for (int i = tid; i < n4; i += SEL_THREADS) {
-                const float4 v = reinterpret_cast<const float4*>(sc)[i];
-                const float x[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const uint32_t key = ordered_key(x[e]);
-                    if (4 * i + e < N && (key & mask) == prefix)
-                        atomicAdd(&s_hist[(key >> shift) & 255], 1);
-                }
-            }
+            src.for_each([&](int, float x) {
+                const uint32_t key = ordered_key(x);
+                if ((key & mask) == prefix) atomicAdd(&s_hist[(key >> shift) & 255], 1);
+            });
             __syncthreads();
             if (tid == 0) {
                 int c = 0, dg = 255;
@@ -231,39 +299,19 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
         r = want;
     }
 
-    // ---- 4. ordered emission: thread t owns 4 consecutive rows of each 4096-row tile ----
+    HYLRA_TS(6);
+    // ---- 4. ordered emission ----
     int32_t* __restrict__ dst = p.idx + pair * (int64_t)k;
-    int base_gt = 0, base_eq = 0;
-    for (int tile0 = 0; tile0 < n4; tile0 += SEL_THREADS) {
-        const int i = tile0 + tid;
-        uint32_t key[4];
-        bool in[4];
-        int cnt = 0;    // low 16 bits: rows above tau, high 16 bits: rows equal to tau
-        if (i < n4) {
-            const float4 v = reinterpret_cast<const float4*>(sc)[i];
-            const float x[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                in[e] = 4 * i + e < N;
-                key[e] = ordered_key(x[e]);
-                if (in[e]) cnt += (key[e] > tau) ? 1 : ((key[e] == tau) ? 0x10000 : 0);
-            }
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) in[e] = false, key[e] = 0;
-        }
-        int total;
-        const int excl = block_excl_scan(cnt, s_wave, total);
-        int gt_before = base_gt + (excl & 0xffff);
-        int eq_before = base_eq + (excl >> 16);
+    auto emit4 = [&](int i, const float (&x)[4], int gt_before, int eq_before) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            if (!in[e]) continue;
-            if (key[e] > tau) {
+            if (4 * i + e >= N) continue;
+            const uint32_t key = ordered_key(x[e]);
+            if (key > tau) {
                 const int o = gt_before + min(eq_before, r);
                 if (o < k) dst[o] = 4 * i + e;
                 ++gt_before;
-            } else if (key[e] == tau) {
+            } else if (key == tau) {
                 if (eq_before < r) {
                     const int o = gt_before + eq_before;
                     if (o < k) dst[o] = 4 * i + e;
@@ -271,13 +319,98 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
                 ++eq_before;
             }
         }
-        base_gt += total & 0xffff;
-        base_eq += total >> 16;
+    };
+    auto count4 = [&](int i, const float (&x)[4]) {
+        int cnt = 0;    // low 16 bits: rows above tau, high 16 bits: rows equal to tau
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t key = ordered_key(x[e]);
+            if (4 * i + e < N) cnt += (key > tau) ? 1 : ((key == tau) ? 0x10000 : 0);
+        }
+        return cnt;
+    };
+    if (E > 0) {
+        // row order is (group j, thread t, element e): scan all E groups at once
+        int incl[E > 0 ? E : 1], cnt[E > 0 ? E : 1];
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+            const float x[4] = {src.v[j].x, src.v[j].y, src.v[j].z, src.v[j].w};
+            cnt[j] = count4(j * SEL_THREADS + tid, x);
+            incl[j] = wave_incl_scan(cnt[j], lane);
+            if (lane == 63) {
+                s_tot_gt[j * SEL_WAVES + wave] = incl[j] & 0xffff;
+                s_tot_eq[j * SEL_WAVES + wave] = incl[j] >> 16;
+            }
+        }
+        __syncthreads();
+        // exclusive prefix over the E*16 wave totals, in (group, wave) order, by wave 0
+        if (wave == 0) {
+            constexpr int PER = (E * SEL_WAVES + 63) / 64;
+            int a[PER > 0 ? PER : 1], c[PER > 0 ? PER : 1], sa = 0, sc2 = 0;
+#pragma unroll
+            for (int u = 0; u < PER; ++u) {
+                const int q = lane * PER + u;
+                a[u] = q < E * SEL_WAVES ? s_tot_gt[q] : 0;
+                c[u] = q < E * SEL_WAVES ? s_tot_eq[q] : 0;
+                sa += a[u];
+                sc2 += c[u];
+            }
+            int ea = wave_incl_scan(sa, lane) - sa, ec = wave_incl_scan(sc2, lane) - sc2;
+#pragma unroll
+            for (int u = 0; u < PER; ++u) {
+                const int q = lane * PER + u;
+                if (q < E * SEL_WAVES) {
+                    s_tot_gt[q] = ea;
+                    s_tot_eq[q] = ec;
+                }
+                ea += a[u];
+                ec += c[u];
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < E; ++j) {
+            const float x[4] = {src.v[j].x, src.v[j].y, src.v[j].z, src.v[j].w};
+            const int excl = incl[j] - cnt[j];
+            emit4(j * SEL_THREADS + tid, x, s_tot_gt[j * SEL_WAVES + wave] + (excl & 0xffff),
+                  s_tot_eq[j * SEL_WAVES + wave] + (excl >> 16));
+        }
+    } else {
+        // thread t owns 4 consecutive rows of each 4096-row tile; one block scan per tile
+        const float* __restrict__ sc = src.sc;
+        int base_gt = 0, base_eq = 0;
+        for (int tile0 = 0; tile0 < src.n4; tile0 += SEL_THREADS) {
+            const int i = tile0 + tid;
+            float x[4] = {0.f, 0.f, 0.f, 0.f};
+            int cnt = 0;
+            if (i < src.n4) {
+                const float4 q = reinterpret_cast<const float4*>(sc)[i];
+                x[0] = q.x, x[1] = q.y, x[2] = q.z, x[3] = q.w;
+                cnt = count4(i, x);
+            }
+            int total;
+            const int excl = block_excl_scan(cnt, s_wave, total);
+            if (i < src.n4) emit4(i, x, base_gt + (excl & 0xffff), base_eq + (excl >> 16));
+            base_gt += total & 0xffff;
+            base_eq += total >> 16;
+        }
     }
+    HYLRA_TS(7);
 }
 
 hipError_t launch_full_finalize(const FinalizeParams& p, int B, hipStream_t st) {
-    hipLaunchKernelGGL(full_finalize_kernel, dim3(p.Hkv, B), dim3(SEL_THREADS), 0, st, p);
+    const dim3 grid(p.Hkv, B), block(SEL_THREADS);
+    const int n4 = (p.N + 3) >> 2;
+    if (p.variant == 0 && n4 <= 2 * SEL_THREADS)
+        hipLaunchKernelGGL(full_finalize_kernel<2>, grid, block, 0, st, p);
+    else if (p.variant == 0 && n4 <= 4 * SEL_THREADS)
+        hipLaunchKernelGGL(full_finalize_kernel<4>, grid, block, 0, st, p);
+    else if (p.variant == 0 && n4 <= 8 * SEL_THREADS)
+        hipLaunchKernelGGL(full_finalize_kernel<8>, grid, block, 0, st, p);
+    else if (p.variant == 0 && n4 <= 16 * SEL_THREADS)
+        hipLaunchKernelGGL(full_finalize_kernel<16>, grid, block, 0, st, p);
+    else
+        hipLaunchKernelGGL(full_finalize_kernel<0>, grid, block, 0, st, p);
     return hipGetLastError();
 }
 
@@ -286,11 +419,13 @@ __global__ __launch_bounds__(128) void combine_kernel(CombineParams p) {
     const int64_t head = blockIdx.x;
     const int S = p.n_splits, D = p.D;
     const float* ml = p.part_ml + head * S * 2;
-    float M = ml[0];
-    for (int s = 1; s < S; ++s) M = fmaxf(M, ml[2 * s]);
+    float M = NEG_BIG;
+#pragma unroll 16
+    for (int s = 0; s < S; ++s) M = fmaxf(M, ml[2 * s]);
     for (int col = threadIdx.x; col < D; col += blockDim.x) {
         const float* acc = p.part_acc + head * S * D + col;
         float num = 0.f, den = 0.f;
+#pragma unroll 16
         for (int s = 0; s < S; ++s) {
             const float w = fast_exp2(ml[2 * s] - M);
             den = fmaf(w, ml[2 * s + 1], den);

@@ -22,6 +22,7 @@ struct FullParams {
     float* part_mm;                 // [B*Hkv][S][2]  (min, max of the group-mean scores)
     float* scores;                  // [B*Hkv][score_stride] group-mean scaled scores
     int64_t score_stride;           // multiple of 4, >= N
+    int* row_ctr;                   // [B*Hkv] next unclaimed row (dynamic mode); zero at launch
 };
 
 struct FinalizeParams {
@@ -31,6 +32,8 @@ struct FinalizeParams {
     const float* scores;
     int64_t score_stride;
     int n_splits, Hq, Hkv, G, D, N, k;
+    int* row_ctr;                   // [B*Hkv], reset to zero here for the next Full launch
+    int variant;                    // 0: scores kept in registers when they fit; 1: always re-read
     float* out;                     // [B][Hq][D]
     int32_t* idx;                   // [B][Hkv][k]
 };
@@ -46,6 +49,9 @@ struct ReuseParams {
     const int32_t* idx;             // [B][Hkv][k]
     float* part_ml;                 // [B*Hq][S][2]
     float* part_acc;                // [B*Hq][S][D]
+    int* counters;                  // [B*Hkv] arrival counters, all zero between launches;
+                                    // nullptr: do not merge in this kernel
+    float* out;                     // [B][Hq][D], written by the merging workgroup
 };
 
 struct CombineParams {
@@ -56,15 +62,34 @@ struct CombineParams {
 };
 
 // Rows of the cache one workgroup of the Full kernel consumes per sweep of its 4 waves
-// (rows_per_split must be a multiple of it).  0 if (D, G, variant) is not built.
-int full_block_quantum(int D, int G, int variant);
-// Index entries per workgroup sweep of the Reuse kernel for unroll R in {1, 2, 4}.
-int reuse_block_quantum(int D, int G, int variant, int R);
+// (rows_per_split must be a multiple of it).  0 if (G, variant) is not built.  One pair of
+// functions per head_dim, each in its own translation unit.
+int full_block_quantum_d64(int G, int variant);
+int full_block_quantum_d128(int G, int variant);
+hipError_t launch_full_split_d64(const FullParams& p, int B, int G, int variant, hipStream_t st);
+hipError_t launch_full_split_d128(const FullParams& p, int B, int G, int variant, hipStream_t st);
+// Index entries per workgroup sweep of the Reuse kernel for unroll R in {1, 2, 4, 8}.
+int reuse_block_quantum_d64(int G, int variant, int R);
+int reuse_block_quantum_d128(int G, int variant, int R);
+hipError_t launch_reuse_split_d64(const ReuseParams& p, int B, int G, int variant, int R, hipStream_t st);
+hipError_t launch_reuse_split_d128(const ReuseParams& p, int B, int G, int variant, int R, hipStream_t st);
 
-hipError_t launch_full_split(const FullParams& p, int B, int D, int G, int variant, hipStream_t st);
+inline int full_block_quantum(int D, int G, int variant) {
+    return D == 64 ? full_block_quantum_d64(G, variant) : D == 128 ? full_block_quantum_d128(G, variant) : 0;
+}
+inline hipError_t launch_full_split(const FullParams& p, int B, int D, int G, int variant, hipStream_t st) {
+    return D == 64 ? launch_full_split_d64(p, B, G, variant, st)
+         : D == 128 ? launch_full_split_d128(p, B, G, variant, st) : hipErrorInvalidValue;
+}
+inline int reuse_block_quantum(int D, int G, int variant, int R) {
+    return D == 64 ? reuse_block_quantum_d64(G, variant, R) : D == 128 ? reuse_block_quantum_d128(G, variant, R) : 0;
+}
+inline hipError_t launch_reuse_split(const ReuseParams& p, int B, int D, int G, int variant, int R, hipStream_t st) {
+    return D == 64 ? launch_reuse_split_d64(p, B, G, variant, R, st)
+         : D == 128 ? launch_reuse_split_d128(p, B, G, variant, R, st) : hipErrorInvalidValue;
+}
+
 hipError_t launch_full_finalize(const FinalizeParams& p, int B, hipStream_t st);
-hipError_t launch_reuse_split(const ReuseParams& p, int B, int D, int G, int variant, int R,
-                              hipStream_t st);
 hipError_t launch_combine(const CombineParams& p, int n_heads_total, hipStream_t st);
 hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t st);

@@ -1,0 +1,168 @@
+// Reuse layer (Algorithm 2, Reuse branch): attention over only the KV rows named by the
+// inherited index set.  K^sparse / V^sparse are never materialised: each 8- or 16-lane
+// group of a wave fetches one selected row straight from the cache, and the row serves all
+// G query heads of its KV head.  One workgroup handles one slice of the k indices of one
+// (batch, KV head) and leaves an online-softmax partial per head; the workgroup that
+// finishes last for a (batch, KV head) merges the partials into the output (or, in the
+// unfused mode, a separate merge kernel does).
+#pragma once
+#include "attend.h"
+#include "launch.h"
+
+#ifndef HYLRA_BUILD_D
+#error "define HYLRA_BUILD_D to 64 or 128"
+#endif
+
+namespace hylra {
+
+template <int D, int G, int CH, int R, bool NT>
+__global__ __launch_bounds__(256) void reuse_attn_split_kernel(ReuseParams p) {
+    using GEO = Geo<D, G, CH>;
+    constexpr int NW = 4;
+    constexpr int TILE = R * GEO::RPG;
+    __shared__ float smem[merge_smem_floats<GEO, NW>()];
+    __shared__ int s_last;
+
+    const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int chunk = lane % GEO::LPR, slot = lane / GEO::LPR;
+
+    const int i0 = split * p.rows_per_split;
+    const int i1 = min(p.k, i0 + p.rows_per_split);
+    const int64_t pair = (int64_t)b * p.Hkv + g;
+    const int32_t* __restrict__ ib = p.idx + pair * p.k;
+    const uint16_t* __restrict__ Kb = p.K + (int64_t)b * p.sb + (int64_t)g * p.sh;
+    const uint16_t* __restrict__ Vb = p.V + (int64_t)b * p.sb + (int64_t)g * p.sh;
+
+    HYLRA_TS(0);
+    // the index loads head the longest dependent chain (index -> row -> softmax): issue first
+    int t0 = i0 + wave * TILE;
+    int row[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int pos = t0 + r * GEO::RPG + slot;
+        row[r] = pos < i1 ? ib[pos] : -1;
+    }
+    uint4 qv[G][CH];
+    load_q<GEO>(qv, p.q + ((int64_t)b * p.Hq + (int64_t)g * G) * D, chunk);
+    LaneState<GEO> st;
+    st.init();
+
+    while (t0 < i1) {
+        int64_t off[R];
+        bool valid[R];
+        float ms[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            valid[r] = (unsigned)row[r] < (unsigned)p.N;      // negative or >= N: padding, skipped
+            off[r] = (int64_t)(valid[r] ? row[r] : 0) * p.sn + chunk * 8;
+        }
+        HYLRA_TS(1);
+        TileBuf<GEO, R> buf;
+        load_tile<GEO, R, NT>(buf, Kb, Vb, off);
+        t0 += NW * TILE;
+        if (t0 < i1) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int pos = t0 + r * GEO::RPG + slot;
+                row[r] = pos < i1 ? ib[pos] : -1;
+            }
+        }
+        compute_tile<GEO, R, true>(st, qv, buf, valid, p.scale_log2, 0.f, ms);
+        HYLRA_TS(2);
+    }
+
+    const int64_t head0 = (int64_t)b * p.Hq + (int64_t)g * G;
+    float* const my_ml = p.part_ml + (head0 * p.n_splits + split) * 2;
+    float* const my_acc = p.part_acc + (head0 * p.n_splits + split) * D;
+    if (p.counters == nullptr) {            // unfused: a separate kernel merges the partials
+        block_merge_store<GEO, NW, false>(st, smem, my_ml, (int64_t)p.n_splits * 2, my_acc,
+                                          (int64_t)p.n_splits * D);
+        return;
+    }
+
+    // Fused merge: partials go out with device-scope write-through stores; once they are
+    // complete the workgroup bumps the arrival counter of its (batch, KV head); whoever
+    // arrives last reads all partials back with device-scope loads and writes the output.
+    block_merge_store<GEO, NW, true>(st, smem, my_ml, (int64_t)p.n_splits * 2, my_acc,
+                                     (int64_t)p.n_splits * D);
+    HYLRA_TS(3);
+    wait_vmem();
+    __syncthreads();
+    HYLRA_TS(4);
+    if (tid == 0)
+        s_last = __hip_atomic_fetch_add(p.counters + pair, 1, __ATOMIC_RELAXED,
+                                        __HIP_MEMORY_SCOPE_AGENT) == p.n_splits - 1;
+    __syncthreads();
+    HYLRA_TS(5);
+    if (!s_last) return;
+    const int S = p.n_splits;
+    for (int i = tid; i < G * D; i += NW * 64) {
+        const int h = i / D, col = i - h * D;
+        const float* ml = p.part_ml + (head0 + h) * S * 2;
+        const float* acc = p.part_acc + (head0 + h) * S * D + col;
+        float M = NEG_BIG;
+#pragma unroll 8
+        for (int s = 0; s < S; ++s) M = fmaxf(M, coherent_load(ml + 2 * s));
+        float num = 0.f, den = 0.f;
+#pragma unroll 8
+        for (int s = 0; s < S; ++s) {
+            const float w = fast_exp2(coherent_load(ml + 2 * s) - M);
+            den = fmaf(w, coherent_load(ml + 2 * s + 1), den);
+            num = fmaf(w, coherent_load(acc + (int64_t)s * D), num);
+        }
+        p.out[(head0 + h) * D + col] = den > 0.f ? num / den : 0.f;
+    }
+    HYLRA_TS(6);
+    if (tid == 0) __hip_atomic_store(p.counters + pair, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int D, int G>
+struct ReuseCfg {
+    static constexpr int CH = (D == 128 && G <= 4) ? 2 : 1;
+};
+
+template <int D, int G, int R>
+static hipError_t launch_r(const ReuseParams& p, int B, int variant, hipStream_t st) {
+    constexpr int CH = ReuseCfg<D, G>::CH;
+    dim3 grid(p.n_splits, p.Hkv, B);
+    if (variant == 1)
+        hipLaunchKernelGGL((reuse_attn_split_kernel<D, G, CH, R, false>), grid, dim3(256), 0, st, p);
+    else
+        hipLaunchKernelGGL((reuse_attn_split_kernel<D, G, CH, R, true>), grid, dim3(256), 0, st, p);
+    return hipGetLastError();
+}
+
+#define HYLRA_FOR_EACH_G(X, D) X(D, 1) X(D, 2) X(D, 3) X(D, 4) X(D, 5) X(D, 6) X(D, 7) X(D, 8)
+
+#if HYLRA_BUILD_D == 64
+#define HYLRA_SUFFIX(name) name##_d64
+#else
+#define HYLRA_SUFFIX(name) name##_d128
+#endif
+
+// variant 0 = streaming (non-temporal) loads, 1 = plain loads
+int HYLRA_SUFFIX(reuse_block_quantum)(int G, int variant, int R) {
+    if (variant < 0 || variant > 1 || (R != 1 && R != 2 && R != 4 && R != 8)) return 0;
+#define Q(DD, GG) if (G == GG) return 4 * R * Geo<DD, GG, ReuseCfg<DD, GG>::CH>::RPG;
+    HYLRA_FOR_EACH_G(Q, HYLRA_BUILD_D)
+#undef Q
+    return 0;
+}
+
+hipError_t HYLRA_SUFFIX(launch_reuse_split)(const ReuseParams& p, int B, int G, int variant, int R,
+                                            hipStream_t st) {
+    if (variant < 0 || variant > 1) return hipErrorInvalidValue;
+#define L(DD, GG)                                                   \
+    if (G == GG) {                                                  \
+        if (R == 8) return launch_r<DD, GG, 8>(p, B, variant, st);  \
+        if (R == 4) return launch_r<DD, GG, 4>(p, B, variant, st);  \
+        if (R == 2) return launch_r<DD, GG, 2>(p, B, variant, st);  \
+        if (R == 1) return launch_r<DD, GG, 1>(p, B, variant, st);  \
+    }
+    HYLRA_FOR_EACH_G(L, HYLRA_BUILD_D)
+#undef L
+    return hipErrorInvalidValue;
+}
+
+}  // namespace hylra

@@ -1,0 +1,60 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times: the
+first Full layer and the first Reuse layer of every BASELINE workload run at full shape on
+the GPU; the oracle recomputes sampled (batch, KV head) pairs one by one, and properties that
+hold at any size (ascending, distinct, in-range index sets; finite outputs) are checked for
+every pair."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2602_00777_amd import binding, synth
+from tests.parity import assert_idx_valid, assert_out_close
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def sample_pairs(B, Hkv):
+    pairs = {(0, 0), (B - 1, Hkv - 1), (B // 2, Hkv // 2), (0, Hkv - 1)}
+    return sorted(pairs)
+
+
+@pytest.mark.parametrize("name", ["llama3_8b_32k", "long_131k", "serve_b32_16k", "qwen25_7b_64k"])
+def test_full_size_full_then_reuse(name):
+    print("[case] full size %s" % name, flush=True)
+    w = synth.WORKLOADS[name]
+    full_l = int(np.flatnonzero(w.policy() == synth.FULL)[0])
+    reuse_l = int(np.flatnonzero(w.policy() == synth.REUSE)[0])
+    planted = synth.planted_positions(synth.scaled(w, n_layers=reuse_l + 1))
+    G, d, N, k = w.group, w.head_dim, w.ctx_len, w.top_k
+    with binding.Context(w.batch, w.n_q_heads, w.n_kv_heads, d, N, k) as ctx:
+        q, K, V = synth.make_layer(w, full_l, planted[full_l], DEV)
+        out, idx = ctx.full_attn_topk(q, K, V, k)
+        torch.cuda.synchronize()
+        out_h, idx_h = out.cpu().numpy(), idx.cpu().numpy()
+        # any-size properties, all pairs
+        assert np.all(np.isfinite(out_h))
+        assert idx_h.min() >= 0 and idx_h.max() < N
+        assert np.all(np.diff(idx_h.astype(np.int64), axis=-1) > 0)
+        for (b, g) in sample_pairs(w.batch, w.n_kv_heads):
+            qs = q[b:b + 1, g * G:(g + 1) * G].cpu()
+            Ks, Vs = K[b:b + 1, g:g + 1].cpu(), V[b:b + 1, g:g + 1].cpu()
+            ref_out, ref_idx, shat = oracle.full_attn_topk(qs, Ks, Vs, k, want_shat=True)
+            assert_out_close(out_h[b:b + 1, g * G:(g + 1) * G], ref_out, "%s full out (%d,%d)" % (name, b, g))
+            assert_idx_valid(idx_h[b:b + 1, g:g + 1], shat, k, "%s idx (%d,%d)" % (name, b, g), exact_ref=ref_idx)
+        del q, K, V
+        # the Reuse layer on the set the Full layer just produced
+        q, K, V = synth.make_layer(w, reuse_l, planted[reuse_l], DEV)
+        out2 = ctx.reuse_sparse_attn(q, K, V, idx)
+        torch.cuda.synchronize()
+        out2_h = out2.cpu().numpy()
+        assert np.all(np.isfinite(out2_h))
+        for (b, g) in sample_pairs(w.batch, w.n_kv_heads):
+            qs = q[b:b + 1, g * G:(g + 1) * G].cpu()
+            Ks, Vs = K[b:b + 1, g:g + 1].cpu(), V[b:b + 1, g:g + 1].cpu()
+            ref = oracle.reuse_sparse_attn(qs, Ks, Vs, idx_h[b:b + 1, g:g + 1])
+            assert_out_close(out2_h[b:b + 1, g * G:(g + 1) * G], ref, "%s reuse out (%d,%d)" % (name, b, g))
+    # the planted positions are what the selection finds (statistical sanity of the workload)
+    hit = np.mean([np.isin(planted[full_l][b, g], idx_h[b, g]).mean() for (b, g) in sample_pairs(w.batch, w.n_kv_heads)])
+    assert hit > 0.6, hit

@@ -59,6 +59,38 @@ def test_full_attn_topk_matches_oracle(B, Hkv, G, d, N, k):
     assert_idx_valid(idx, shat, k, "full idx", exact_ref=ref_idx)
 
 
+@pytest.mark.parametrize("variant", [4, 14, 23, 34, 32])
+def test_full_kernel_variants(variant):
+    say("full variant=%d" % variant)
+    B, Hkv, G, d, N, k = 2, 2, 4, 128, 5003, 300
+    q, K, V = rand_case(17, B, Hkv, G, d, N)
+    ref_out, ref_idx, shat = oracle.full_attn_topk(q, K, V, k, want_shat=True)
+    with binding.Context(B, Hkv * G, Hkv, d, N, k) as ctx:
+        ctx.set_option("full_variant", variant)
+        ctx.set_option("full_split_rows", 768)
+        for rep in range(3):       # the dynamic variants rely on counters that reset themselves
+            out, idx = run_full(ctx, q, K, V, k)
+            assert_out_close(out, ref_out, "full out")
+            assert_idx_valid(idx, shat, k, "full idx", exact_ref=ref_idx)
+
+
+@pytest.mark.parametrize("unroll", [1, 2, 4, 8])
+def test_reuse_kernel_unrolls(unroll):
+    say("reuse unroll=%d" % unroll)
+    B, Hkv, G, d, N, k = 2, 2, 4, 128, 5003, 700
+    q, K, V = rand_case(18, B, Hkv, G, d, N)
+    rng = np.random.RandomState(unroll)
+    idx = np.stack([[np.sort(rng.permutation(N)[:k]) for _ in range(Hkv)] for _ in range(B)]).astype(np.int32)
+    ref = oracle.reuse_sparse_attn(q, K, V, idx)
+    with binding.Context(B, Hkv * G, Hkv, d, N, k) as ctx:
+        ctx.set_option("reuse_unroll", unroll)
+        for plain in (0, 1):
+            ctx.set_option("reuse_variant", plain)
+            out = ctx.reuse_sparse_attn(q, K, V, torch.from_numpy(idx).to(DEV))
+            torch.cuda.synchronize()
+            assert_out_close(out.cpu().numpy(), ref, "reuse out")
+
+
 @pytest.mark.parametrize("split_rows", [128, 256, 4096])
 def test_full_result_does_not_depend_on_split(split_rows):
     say("full split_rows=%d" % split_rows)
@@ -138,6 +170,30 @@ def test_reuse_sparse_attn_matches_oracle(B, Hkv, G, d, N, k):
         out = ctx.reuse_sparse_attn(q, K, V, torch.from_numpy(idx).to(DEV))
         torch.cuda.synchronize()
     assert_out_close(out.cpu().numpy(), oracle.reuse_sparse_attn(q, K, V, idx), "reuse out")
+
+
+@pytest.mark.parametrize("B,Hkv,G,d,N,k", [(4, 8, 4, 128, 8192, 2048), (2, 4, 7, 128, 6000, 1000), (8, 2, 4, 64, 4096, 1024)])
+def test_reuse_fused_merge_equals_two_kernel_merge(B, Hkv, G, d, N, k):
+    """The in-kernel merge (last-arriving workgroup) must give bit-identical results to the
+    separate merge kernel, launch after launch (the arrival counters reset themselves)."""
+    say("reuse fused merge B=%d Hkv=%d G=%d d=%d N=%d k=%d" % (B, Hkv, G, d, N, k))
+    q, K, V = rand_case(300 + G, B, Hkv, G, d, N)
+    rng = np.random.RandomState(k)
+    idx = np.stack([[np.sort(rng.permutation(N)[:k]) for _ in range(Hkv)] for _ in range(B)]).astype(np.int32)
+    gidx = torch.from_numpy(idx).to(DEV)
+    with binding.Context(B, Hkv * G, Hkv, d, N, k) as ctx:
+        ctx.set_option("reuse_unfused", 1)
+        two = ctx.reuse_sparse_attn(q, K, V, gidx).clone()
+        ctx.set_option("reuse_unfused", 0)
+        outs = []
+        for it in range(40):
+            o = torch.full(q.shape, float("nan"), dtype=torch.float32, device=DEV)
+            ctx.reuse_sparse_attn(q, K, V, gidx, out=o)
+            outs.append(o)
+        torch.cuda.synchronize()
+    for it, o in enumerate(outs):
+        assert torch.equal(o, two), "fused merge differs at launch %d" % it
+    assert_out_close(two.cpu().numpy(), oracle.reuse_sparse_attn(q, K, V, idx), "reuse out")
 
 
 def test_reuse_padding_order_and_out_of_range_entries():
