@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -18,7 +19,6 @@ namespace {
 
 constexpr int kTargetBlocksFull = 512;    // workgroups the Full kernel aims for: two per CU,
                                           // all resident at once (measured best on MI355X)
-constexpr int kMinBlocksReuse = 512;      // below this the Reuse kernel uses a shorter unroll
 constexpr int64_t kMinSlots = 8192;       // partial slots ((batch, KV head, split) triples) kept
 constexpr float LOG2E_HOST = 1.4426950408889634f;
 
@@ -45,6 +45,9 @@ struct hylra_ctx {
     int64_t cap_ml = 0;
     int64_t cap_scores = 0;
 
+    float xcd_weight[8] = {1, 1, 1, 1, 1, 1, 1, 1};   // relative streaming speed of each XCD
+    bool xcd_weighted = false;
+
     int32_t opt_full_split_rows = 0;
     int32_t opt_reuse_split_rows = 0;
     int32_t opt_full_variant = 0;
@@ -52,6 +55,7 @@ struct hylra_ctx {
     int32_t opt_reuse_unroll = 0;
     int32_t opt_reuse_unfused = 0;
     int32_t opt_finalize_variant = 0;
+    int32_t opt_full_equal_split = 0;
 
     bool prof_on = false;
     int prof_n = 0;
@@ -158,6 +162,8 @@ hipError_t launch_timed(hylra_ctx* ctx, int cls, hipStream_t st, F&& f) {
 
 struct FullPlan {
     int rows_per_split, n_splits, variant;
+    int xcd_weighted;
+    int xcd_bound[9];
 };
 
 hylra_status plan_full(const hylra_ctx* ctx, const hylra_shape* s, int G, FullPlan& pl) {
@@ -178,6 +184,20 @@ hylra_status plan_full(const hylra_ctx* ctx, const hylra_shape* s, int G, FullPl
         return fail(ctx, HYLRA_ERR_WORKSPACE, "batch*n_kv_heads = %lld exceeds the workspace", (long long)pairs);
     pl.rows_per_split = (int)rps;
     pl.n_splits = (int)S;
+    // XCD-aware shares: only when the splits of one (batch, KV head) map one-to-one onto XCDs
+    pl.xcd_weighted = ctx->xcd_weighted && S % 8 == 0 && !ctx->opt_full_equal_split;
+    if (pl.xcd_weighted) {
+        double total = 0, run = 0;
+        for (int x = 0; x < 8; ++x) total += ctx->xcd_weight[x];
+        pl.xcd_bound[0] = 0;
+        for (int x = 0; x < 8; ++x) {
+            run += ctx->xcd_weight[x];
+            pl.xcd_bound[x + 1] = (int)round_up((int64_t)(8.0 * rps * run / total + 0.5), quantum / 4);
+        }
+        pl.xcd_bound[8] = (int)(8 * rps);
+        for (int x = 1; x < 8; ++x)
+            if (pl.xcd_bound[x] < pl.xcd_bound[x - 1] || pl.xcd_bound[x] > pl.xcd_bound[8]) pl.xcd_weighted = 0;
+    }
     return HYLRA_OK;
 }
 
@@ -188,14 +208,17 @@ struct ReusePlan {
 hylra_status plan_reuse(const hylra_ctx* ctx, const hylra_shape* s, int G, int k, ReusePlan& pl) {
     pl.variant = ctx->opt_reuse_variant;
     const int64_t pairs = (int64_t)s->batch * s->n_kv_heads;
-    pl.R = 0;
-    for (int R = ctx->opt_reuse_unroll > 0 ? ctx->opt_reuse_unroll : 8; R >= 1; R >>= 1) {
-        const int quantum = reuse_block_quantum(s->head_dim, G, pl.variant, R);
-        if (quantum <= 0) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "Reuse kernel variant %d / unroll %d is not built for d=%d G=%d", pl.variant, R, s->head_dim, G);
-        pl.R = R;
-        pl.rows_per_split = quantum;
-        if (ctx->opt_reuse_unroll > 0 || pairs * ceil_div(k, quantum) >= kMinBlocksReuse) break;
-    }
+    // Unroll: 8 row groups per wave tile (64 rows per wave with 8 lanes per row) keeps the
+    // whole gather of a layer in flight at once and the number of partials per (batch, KV
+    // head) small, which the in-kernel merge needs (its arrival counter serialises).  Smaller
+    // tiles only when a single workgroup still covers all k entries.
+    pl.R = ctx->opt_reuse_unroll > 0 ? ctx->opt_reuse_unroll : 8;
+    while (ctx->opt_reuse_unroll == 0 && pl.R > 1 &&
+           reuse_block_quantum(s->head_dim, G, pl.variant, pl.R / 2) >= k)
+        pl.R /= 2;
+    pl.rows_per_split = reuse_block_quantum(s->head_dim, G, pl.variant, pl.R);
+    if (pl.rows_per_split <= 0)
+        return fail(ctx, HYLRA_ERR_UNSUPPORTED, "Reuse kernel variant %d / unroll %d is not built for d=%d G=%d", pl.variant, pl.R, s->head_dim, G);
     int64_t rps = pl.rows_per_split;
     if (ctx->opt_reuse_split_rows > 0) rps = round_up(ctx->opt_reuse_split_rows, pl.rows_per_split);
     int64_t S = ceil_div(k, rps);
@@ -286,6 +309,13 @@ hylra_status hylra_create(hylra_ctx** out, const hylra_shape* max_shape, int32_t
         hylra_destroy(ctx);
         return HYLRA_ERR_HIP;
     }
+    if (const char* env = std::getenv("HYLRA_XCD_WEIGHTS")) {     // tuning aid: 8 comma-separated speeds
+        float w[8];
+        if (std::sscanf(env, "%f,%f,%f,%f,%f,%f,%f,%f", w, w + 1, w + 2, w + 3, w + 4, w + 5, w + 6, w + 7) == 8) {
+            for (int x = 0; x < 8; ++x) ctx->xcd_weight[x] = w[x];
+            ctx->xcd_weighted = true;
+        }
+    }
     *out = ctx;
     return HYLRA_OK;
 }
@@ -318,6 +348,7 @@ hylra_status hylra_set_option(hylra_ctx* ctx, const char* name, int32_t value) {
     else if (!std::strcmp(name, "reuse_unroll")) ctx->opt_reuse_unroll = value;
     else if (!std::strcmp(name, "reuse_unfused")) ctx->opt_reuse_unfused = value;
     else if (!std::strcmp(name, "finalize_variant")) ctx->opt_finalize_variant = value;
+    else if (!std::strcmp(name, "full_equal_split")) ctx->opt_full_equal_split = value;
     else return fail(ctx, HYLRA_ERR_BAD_ARG, "unknown option '%s'", name);
     return HYLRA_OK;
 }
@@ -353,6 +384,8 @@ hylra_status hylra_full_attn_topk(hylra_ctx* ctx, const hylra_shape* shape, cons
     fp.scores = ctx->scores;
     fp.score_stride = round_up(shape->ctx_len, 4);
     fp.row_ctr = ctx->row_ctr;
+    fp.xcd_weighted = pl.xcd_weighted;
+    for (int x = 0; x < 9; ++x) fp.xcd_bound[x] = pl.xcd_bound[x];
     HIP_TRY(ctx, launch_timed(ctx, 0, st, [&] {
                 return launch_full_split(fp, shape->batch, shape->head_dim, G, pl.variant, st);
             }));

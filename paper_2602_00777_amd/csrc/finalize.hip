@@ -62,6 +62,58 @@ DEVI int block_excl_scan(int v, int* s_wave, int& total) {
     return base + incl - v;
 }
 
+// Inclusive prefix sum over the 64 lanes of a wave with DPP only (row_shr 1/2/4/8 inside
+// each 16-lane row, then row_bcast15 / row_bcast31 carry the row totals forward).
+DEVI int wave_incl_scan_dpp(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, true);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);
+    return v;
+}
+
+// E independent exclusive prefix sums at once.  Value j of thread t precedes value j' of
+// thread t' iff (j, t) < (j', t') lexicographically -- the row order of the register-resident
+// scores.  s_tot holds E * SEL_WAVES + 1 ints.  Returns the grand total.  Contains barriers:
+// every thread must call it.
+template <int E>
+DEVI int multi_scan(const int (&cnt)[E], int (&base)[E], int* s_tot) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int incl[E];
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+        incl[j] = wave_incl_scan_dpp(cnt[j]);
+        if (lane == 63) s_tot[j * SEL_WAVES + wave] = incl[j];
+    }
+    __syncthreads();
+    if (wave == 0) {
+        constexpr int PER = (E * SEL_WAVES + 63) / 64;
+        int a[PER], sum = 0;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int q = lane * PER + u;
+            a[u] = q < E * SEL_WAVES ? s_tot[q] : 0;
+            sum += a[u];
+        }
+        int run = wave_incl_scan_dpp(sum) - sum;
+#pragma unroll
+        for (int u = 0; u < PER; ++u) {
+            const int q = lane * PER + u;
+            if (q < E * SEL_WAVES) s_tot[q] = run;
+            run += a[u];
+        }
+        if (lane == 63) s_tot[E * SEL_WAVES] = run;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < E; ++j) base[j] = s_tot[j * SEL_WAVES + wave] + incl[j] - cnt[j];
+    const int total = s_tot[E * SEL_WAVES];
+    __syncthreads();
+    return total;
+}
+
 DEVI int score_bin(float x, float lo, float inv_w) {
     const int b = (int)((x - lo) * inv_w);
     return min(max(b, 0), SEL_BINS - 1);
@@ -102,12 +154,24 @@ struct RegScores {
                     if (4 * i + e < N) f(4 * i + e, x[e]);
             }
         } else {
-            for (int i = threadIdx.x; i < n4; i += SEL_THREADS) {
-                const float4 q = reinterpret_cast<const float4*>(sc)[i];
-                const float x[4] = {q.x, q.y, q.z, q.w};
+            // eight independent loads per trip, so the pass is not bound by one memory
+            // latency per float4
+            constexpr int U = 8;
+            for (int i0 = threadIdx.x; i0 < n4; i0 += U * SEL_THREADS) {
+                float4 q[U];
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (4 * i + e < N) f(4 * i + e, x[e]);
+                for (int u = 0; u < U; ++u) {
+                    const int i = i0 + u * SEL_THREADS;
+                    q[u] = i < n4 ? reinterpret_cast<const float4*>(sc)[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int i = i0 + u * SEL_THREADS;
+                    const float x[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (4 * i + e < N) f(4 * i + e, x[e]);
+                }
             }
         }
     }
@@ -121,8 +185,8 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
     __shared__ int s_wave[SEL_WAVES + 1];
     __shared__ float s_red[2 * SEL_WAVES];
     __shared__ float s_m[SEL_ML_CAP], s_l[SEL_ML_CAP];
-    __shared__ int s_tot_gt[(E > 0 ? E : 1) * SEL_WAVES + 1];
-    __shared__ int s_tot_eq[(E > 0 ? E : 1) * SEL_WAVES + 1];
+    __shared__ int s_tot[(E > 0 ? E : 4) * SEL_WAVES + 1];
+    __shared__ unsigned long long s_sel[E > 0 ? SEL_THREADS : 1];   // rows of bin T that made the cut
     __shared__ int s_T, s_above, s_cand, s_gt, s_kr;
     __shared__ uint32_t s_tau;
 
@@ -187,6 +251,7 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
         s_red[2 * wave + 1] = hi;
     }
     for (int i = tid; i < SEL_BINS; i += SEL_THREADS) s_hist[i] = 0;
+    if (E > 0) s_sel[tid] = 0;
     if (tid == 0) s_cand = 0, s_gt = 0;
     __syncthreads();
     lo = s_red[0];
@@ -232,24 +297,52 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
     const int kr = k - s_above;      // how many of bin T's rows are selected, 1 <= kr <= |bin T|
 
     HYLRA_TS(4);
-    // ---- 3. candidates of bin T ----
-    src.for_each([&](int pos, float x) {
-        if (score_bin(x, lo, inv_w) == T) {
-            const int slot = atomicAdd(&s_cand, 1);
-            if (slot < SEL_CAP) {
-                s_ckey[slot] = ordered_key(x);
-                s_cpos[slot] = pos;
+    int32_t* __restrict__ dst = p.idx + pair * (int64_t)k;
+    constexpr int EE = E > 0 ? E : 1;
+
+    // ---- 3. classify: rows in bins above T are selected, rows of bin T are candidates ----
+    // bit 4*j + e of a thread's mask stands for element e of its j-th float4 group
+    unsigned long long gt_mask = 0;
+    if (E > 0) {
+#pragma unroll
+        for (int j = 0; j < EE; ++j) {
+            const int i = j * SEL_THREADS + tid;
+            const float x[4] = {src.v[j].x, src.v[j].y, src.v[j].z, src.v[j].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (4 * i + e >= N) continue;
+                const int bn = score_bin(x[e], lo, inv_w);
+                if (bn > T) gt_mask |= 1ull << (4 * j + e);
+                else if (bn == T) {
+                    const int slot = atomicAdd(&s_cand, 1);
+                    if (slot < SEL_CAP) {
+                        s_ckey[slot] = ordered_key(x[e]);
+                        s_cpos[slot] = 4 * i + e;
+                    }
+                }
             }
         }
-    });
+    } else {
+        src.for_each([&](int pos, float x) {
+            if (score_bin(x, lo, inv_w) == T) {
+                const int slot = atomicAdd(&s_cand, 1);
+                if (slot < SEL_CAP) {
+                    s_ckey[slot] = ordered_key(x);
+                    s_cpos[slot] = pos;
+                }
+            }
+        });
+    }
     __syncthreads();
     const int n_cand = s_cand;
 
     HYLRA_TS(5);
-    uint32_t tau;
-    int r;   // rows equal to tau that are selected (lowest positions first)
-    if (n_cand <= SEL_CAP) {
-        // exact rank of every candidate under (key descending, position ascending)
+    uint32_t tau = 0;
+    int r = 0;   // rows equal to tau that are selected (lowest positions first)
+    const bool ranked = n_cand <= SEL_CAP;
+    if (ranked) {
+        // exact rank of every candidate under (key descending, position ascending); the kr
+        // best are selected
         for (int i = tid; i < n_cand; i += SEL_THREADS) {
             const uint32_t key = s_ckey[i];
             const int pos = s_cpos[i];
@@ -258,15 +351,25 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
                 const uint32_t kj = s_ckey[j];
                 rank += (kj > key) || (kj == key && s_cpos[j] < pos);
             }
-            if (rank == kr - 1) s_tau = key;
+            if (E > 0) {
+                if (rank < kr) {
+                    const int grp = pos >> 2;       // float4 group: owner thread grp % 1024, slot grp / 1024
+                    atomicOr(&s_sel[grp & (SEL_THREADS - 1)],
+                             1ull << (4 * (grp >> 10) + (pos & 3)));
+                }
+            } else if (rank == kr - 1) {
+                s_tau = key;
+            }
         }
         __syncthreads();
-        tau = s_tau;
-        int gt = 0;
-        for (int i = tid; i < n_cand; i += SEL_THREADS) gt += s_ckey[i] > tau;
-        if (gt) atomicAdd(&s_gt, gt);
-        __syncthreads();
-        r = kr - s_gt;
+        if (E == 0) {
+            tau = s_tau;
+            int gt = 0;
+            for (int i = tid; i < n_cand; i += SEL_THREADS) gt += s_ckey[i] > tau;
+            if (gt) atomicAdd(&s_gt, gt);
+            __syncthreads();
+            r = kr - s_gt;
+        }
     } else {
         // rare: too many rows share the threshold bin (e.g. massive ties).  Plain radix
         // select over all keys, 8 bits per pass; s_hist[0..255] is the digit histogram.
@@ -301,96 +404,105 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
 
     HYLRA_TS(6);
     // ---- 4. ordered emission ----
-    int32_t* __restrict__ dst = p.idx + pair * (int64_t)k;
-    auto emit4 = [&](int i, const float (&x)[4], int gt_before, int eq_before) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if (4 * i + e >= N) continue;
-            const uint32_t key = ordered_key(x[e]);
-            if (key > tau) {
-                const int o = gt_before + min(eq_before, r);
-                if (o < k) dst[o] = 4 * i + e;
-                ++gt_before;
-            } else if (key == tau) {
-                if (eq_before < r) {
-                    const int o = gt_before + eq_before;
-                    if (o < k) dst[o] = 4 * i + e;
-                }
-                ++eq_before;
-            }
-        }
-    };
-    auto count4 = [&](int i, const float (&x)[4]) {
-        int cnt = 0;    // low 16 bits: rows above tau, high 16 bits: rows equal to tau
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            const uint32_t key = ordered_key(x[e]);
-            if (4 * i + e < N) cnt += (key > tau) ? 1 : ((key == tau) ? 0x10000 : 0);
-        }
-        return cnt;
-    };
     if (E > 0) {
-        // row order is (group j, thread t, element e): scan all E groups at once
-        int incl[E > 0 ? E : 1], cnt[E > 0 ? E : 1];
+        unsigned long long sel;
+        if (ranked) {
+            sel = gt_mask | s_sel[tid];
+        } else {
+            // masks by key; the first r rows equal to tau (in row order) join the set
+            unsigned long long eq_mask = 0;
+            gt_mask = 0;
+            int eq_cnt[EE], eq_base[EE];
 #pragma unroll
-        for (int j = 0; j < E; ++j) {
-            const float x[4] = {src.v[j].x, src.v[j].y, src.v[j].z, src.v[j].w};
-            cnt[j] = count4(j * SEL_THREADS + tid, x);
-            incl[j] = wave_incl_scan(cnt[j], lane);
-            if (lane == 63) {
-                s_tot_gt[j * SEL_WAVES + wave] = incl[j] & 0xffff;
-                s_tot_eq[j * SEL_WAVES + wave] = incl[j] >> 16;
-            }
-        }
-        __syncthreads();
-        // exclusive prefix over the E*16 wave totals, in (group, wave) order, by wave 0
-        if (wave == 0) {
-            constexpr int PER = (E * SEL_WAVES + 63) / 64;
-            int a[PER > 0 ? PER : 1], c[PER > 0 ? PER : 1], sa = 0, sc2 = 0;
+            for (int j = 0; j < EE; ++j) {
+                const int i = j * SEL_THREADS + tid;
+                const float x[4] = {src.v[j].x, src.v[j].y, src.v[j].z, src.v[j].w};
+                eq_cnt[j] = 0;
 #pragma unroll
-            for (int u = 0; u < PER; ++u) {
-                const int q = lane * PER + u;
-                a[u] = q < E * SEL_WAVES ? s_tot_gt[q] : 0;
-                c[u] = q < E * SEL_WAVES ? s_tot_eq[q] : 0;
-                sa += a[u];
-                sc2 += c[u];
-            }
-            int ea = wave_incl_scan(sa, lane) - sa, ec = wave_incl_scan(sc2, lane) - sc2;
-#pragma unroll
-            for (int u = 0; u < PER; ++u) {
-                const int q = lane * PER + u;
-                if (q < E * SEL_WAVES) {
-                    s_tot_gt[q] = ea;
-                    s_tot_eq[q] = ec;
+                for (int e = 0; e < 4; ++e) {
+                    if (4 * i + e >= N) continue;
+                    const uint32_t key = ordered_key(x[e]);
+                    if (key > tau) gt_mask |= 1ull << (4 * j + e);
+                    else if (key == tau) eq_mask |= 1ull << (4 * j + e), ++eq_cnt[j];
                 }
-                ea += a[u];
-                ec += c[u];
+            }
+            multi_scan<EE>(eq_cnt, eq_base, s_tot);
+            sel = gt_mask;
+#pragma unroll
+            for (int j = 0; j < EE; ++j) {
+                int seen = eq_base[j];
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if ((eq_mask >> (4 * j + e)) & 1) {
+                        if (seen < r) sel |= 1ull << (4 * j + e);
+                        ++seen;
+                    }
             }
         }
-        __syncthreads();
+        int cnt[EE], base[EE];
 #pragma unroll
-        for (int j = 0; j < E; ++j) {
-            const float x[4] = {src.v[j].x, src.v[j].y, src.v[j].z, src.v[j].w};
-            const int excl = incl[j] - cnt[j];
-            emit4(j * SEL_THREADS + tid, x, s_tot_gt[j * SEL_WAVES + wave] + (excl & 0xffff),
-                  s_tot_eq[j * SEL_WAVES + wave] + (excl >> 16));
+        for (int j = 0; j < EE; ++j) cnt[j] = __popc((unsigned)(sel >> (4 * j)) & 0xFu);
+        multi_scan<EE>(cnt, base, s_tot);
+#pragma unroll
+        for (int j = 0; j < EE; ++j) {
+            unsigned nib = (unsigned)(sel >> (4 * j)) & 0xFu;
+            int o = base[j];
+            const int pos0 = 4 * (j * SEL_THREADS + tid);
+            while (nib) {
+                const int e = __ffs(nib) - 1;
+                nib &= nib - 1;
+                if (o < k) dst[o] = pos0 + e;
+                ++o;
+            }
         }
     } else {
-        // thread t owns 4 consecutive rows of each 4096-row tile; one block scan per tile
+        // thread t owns 4 consecutive rows of each 4096-row tile; four tiles per trip, their
+        // (above tau, equal to tau) counts packed 16 + 16 bits and scanned together
+        constexpr int U = 4;
         const float* __restrict__ sc = src.sc;
         int base_gt = 0, base_eq = 0;
-        for (int tile0 = 0; tile0 < src.n4; tile0 += SEL_THREADS) {
-            const int i = tile0 + tid;
-            float x[4] = {0.f, 0.f, 0.f, 0.f};
-            int cnt = 0;
-            if (i < src.n4) {
-                const float4 q = reinterpret_cast<const float4*>(sc)[i];
-                x[0] = q.x, x[1] = q.y, x[2] = q.z, x[3] = q.w;
-                cnt = count4(i, x);
+        for (int tile0 = 0; tile0 < src.n4; tile0 += U * SEL_THREADS) {
+            uint32_t key[U][4];
+            int cnt[U], base[U];
+            float4 q[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = tile0 + u * SEL_THREADS + tid;
+                q[u] = i < src.n4 ? reinterpret_cast<const float4*>(sc)[i] : make_float4(0.f, 0.f, 0.f, 0.f);
             }
-            int total;
-            const int excl = block_excl_scan(cnt, s_wave, total);
-            if (i < src.n4) emit4(i, x, base_gt + (excl & 0xffff), base_eq + (excl >> 16));
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = tile0 + u * SEL_THREADS + tid;
+                const float x[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
+                cnt[u] = 0;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    key[u][e] = ordered_key(x[e]);
+                    if (4 * i + e < N) cnt[u] += (key[u][e] > tau) ? 1 : ((key[u][e] == tau) ? 0x10000 : 0);
+                }
+            }
+            const int total = multi_scan<U>(cnt, base, s_tot);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = tile0 + u * SEL_THREADS + tid;
+                int gt_before = base_gt + (base[u] & 0xffff);
+                int eq_before = base_eq + (base[u] >> 16);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (4 * i + e >= N) continue;
+                    if (key[u][e] > tau) {
+                        const int o = gt_before + min(eq_before, r);
+                        if (o < k) dst[o] = 4 * i + e;
+                        ++gt_before;
+                    } else if (key[u][e] == tau) {
+                        if (eq_before < r) {
+                            const int o = gt_before + eq_before;
+                            if (o < k) dst[o] = 4 * i + e;
+                        }
+                        ++eq_before;
+                    }
+                }
+            }
             base_gt += total & 0xffff;
             base_eq += total >> 16;
         }

@@ -23,6 +23,11 @@ struct FullParams {
     float* scores;                  // [B*Hkv][score_stride] group-mean scaled scores
     int64_t score_stride;           // multiple of 4, >= N
     int* row_ctr;                   // [B*Hkv] next unclaimed row (dynamic mode); zero at launch
+    // XCD-aware split: when xcd_weighted, every run of 8 consecutive splits (one per XCD:
+    // workgroups go to the 8 XCDs round-robin) shares 8*rows_per_split rows, split x taking
+    // rows [xcd_bound[x], xcd_bound[x+1]) of the run instead of an equal eighth.
+    int xcd_weighted;
+    int xcd_bound[9];
 };
 
 struct FinalizeParams {

@@ -48,18 +48,26 @@ __global__ __launch_bounds__(256) void reuse_attn_split_kernel(ReuseParams p) {
     LaneState<GEO> st;
     st.init();
 
+    // A tile is issued as SUB sub-tiles of RS row groups (K rows then V rows of each), all
+    // loads up front, and consumed sub-tile by sub-tile: the softmax of the first rows runs
+    // while the later rows are still in flight.
+    constexpr int RS = R < 2 ? R : 2;
+    constexpr int SUB = R / RS;
     while (t0 < i1) {
-        int64_t off[R];
-        bool valid[R];
-        float ms[R];
-#pragma unroll
-        for (int r = 0; r < R; ++r) {
-            valid[r] = (unsigned)row[r] < (unsigned)p.N;      // negative or >= N: padding, skipped
-            off[r] = (int64_t)(valid[r] ? row[r] : 0) * p.sn + chunk * 8;
-        }
         HYLRA_TS(1);
-        TileBuf<GEO, R> buf;
-        load_tile<GEO, R, NT>(buf, Kb, Vb, off);
+        TileBuf<GEO, RS> buf[SUB];
+        bool valid[SUB][RS];
+#pragma unroll
+        for (int u = 0; u < SUB; ++u) {
+            int64_t off[RS];
+#pragma unroll
+            for (int r = 0; r < RS; ++r) {
+                const int rr = row[u * RS + r];
+                valid[u][r] = (unsigned)rr < (unsigned)p.N;     // negative or >= N: padding, skipped
+                off[r] = (int64_t)(valid[u][r] ? rr : 0) * p.sn + chunk * 8;
+            }
+            load_tile<GEO, RS, NT>(buf[u], Kb, Vb, off);
+        }
         t0 += NW * TILE;
         if (t0 < i1) {
 #pragma unroll
@@ -68,7 +76,11 @@ __global__ __launch_bounds__(256) void reuse_attn_split_kernel(ReuseParams p) {
                 row[r] = pos < i1 ? ib[pos] : -1;
             }
         }
-        compute_tile<GEO, R, true>(st, qv, buf, valid, p.scale_log2, 0.f, ms);
+#pragma unroll
+        for (int u = 0; u < SUB; ++u) {
+            float ms[RS];
+            compute_tile<GEO, RS, true>(st, qv, buf[u], valid[u], p.scale_log2, 0.f, ms);
+        }
         HYLRA_TS(2);
     }
 
@@ -101,15 +113,33 @@ __global__ __launch_bounds__(256) void reuse_attn_split_kernel(ReuseParams p) {
         const int h = i / D, col = i - h * D;
         const float* ml = p.part_ml + (head0 + h) * S * 2;
         const float* acc = p.part_acc + (head0 + h) * S * D + col;
-        float M = NEG_BIG;
+        float M = NEG_BIG, num = 0.f, den = 0.f;
+        if (S <= 16) {          // the usual case: every load of the merge is issued at once
+            float m_s[16], l_s[16], a_s[16];
+#pragma unroll
+            for (int s = 0; s < 16; ++s) {
+                const bool on = s < S;
+                m_s[s] = on ? coherent_load(ml + 2 * s) : NEG_BIG;
+                l_s[s] = on ? coherent_load(ml + 2 * s + 1) : 0.f;
+                a_s[s] = on ? coherent_load(acc + (int64_t)s * D) : 0.f;
+            }
+#pragma unroll
+            for (int s = 0; s < 16; ++s) M = fmaxf(M, m_s[s]);
+#pragma unroll
+            for (int s = 0; s < 16; ++s) {
+                const float w = fast_exp2(m_s[s] - M);
+                den = fmaf(w, l_s[s], den);
+                num = fmaf(w, a_s[s], num);
+            }
+        } else {
 #pragma unroll 8
-        for (int s = 0; s < S; ++s) M = fmaxf(M, coherent_load(ml + 2 * s));
-        float num = 0.f, den = 0.f;
+            for (int s = 0; s < S; ++s) M = fmaxf(M, coherent_load(ml + 2 * s));
 #pragma unroll 8
-        for (int s = 0; s < S; ++s) {
-            const float w = fast_exp2(coherent_load(ml + 2 * s) - M);
-            den = fmaf(w, coherent_load(ml + 2 * s + 1), den);
-            num = fmaf(w, coherent_load(acc + (int64_t)s * D), num);
+            for (int s = 0; s < S; ++s) {
+                const float w = fast_exp2(coherent_load(ml + 2 * s) - M);
+                den = fmaf(w, coherent_load(ml + 2 * s + 1), den);
+                num = fmaf(w, coherent_load(acc + (int64_t)s * D), num);
+            }
         }
         p.out[(head0 + h) * D + col] = den > 0.f ? num / den : 0.f;
     }

@@ -74,6 +74,31 @@ def test_full_kernel_variants(variant):
             assert_idx_valid(idx, shat, k, "full idx", exact_ref=ref_idx)
 
 
+@pytest.mark.parametrize("N,k", [(5003, 300), (20000, 1500), (40000, 3000)])
+def test_finalize_paths(N, k):
+    """Both score sources of the finalise kernel (registers / re-read per pass), including the
+    many-ties fallback, at sizes that use different register-resident group counts."""
+    say("finalize paths N=%d k=%d" % (N, k))
+    B, Hkv, G, d = 1, 2, 4, 64
+    q, K, V = rand_case(19 + N, B, Hkv, G, d, N)
+    gen = torch.Generator().manual_seed(N)
+    Kt = torch.randint(-1, 2, K.shape, generator=gen).to(torch.bfloat16).to(DEV)     # heavy exact ties
+    qt = torch.randint(-1, 2, q.shape, generator=gen).to(torch.bfloat16).to(DEV)
+    Kz = torch.zeros_like(K)                                                          # one giant tie
+    ref = [oracle.full_attn_topk(q, K, V, k, want_shat=True),
+           oracle.full_attn_topk(qt, Kt, V, k, want_shat=True),
+           oracle.full_attn_topk(q, Kz, V, k, want_shat=True)]
+    with binding.Context(B, Hkv * G, Hkv, d, N, k) as ctx:
+        for variant in (0, 1):
+            ctx.set_option("finalize_variant", variant)
+            for (qq, KK), (ro, ri, rs), exact in (((q, K), ref[0], False), ((qt, Kt), ref[1], True), ((q, Kz), ref[2], True)):
+                out, idx = run_full(ctx, qq, KK, V, k)
+                assert_out_close(out, ro, "out")
+                assert_idx_valid(idx, rs, k, "idx", exact_ref=ri)
+                if exact:      # d = 64 and integer inputs: scores are exact, sets must be equal
+                    assert np.array_equal(idx, ri)
+
+
 @pytest.mark.parametrize("unroll", [1, 2, 4, 8])
 def test_reuse_kernel_unrolls(unroll):
     say("reuse unroll=%d" % unroll)
