@@ -135,7 +135,13 @@ hylra_status hylra_decode_step(hylra_ctx *ctx, const hylra_shape *shape, int32_t
  *   "reuse_unroll"      row groups per wave tile of the Reuse kernel: 1, 2, 4 or 8
  *   "reuse_unfused"     1 = merge the Reuse partials in a second kernel instead of in the
  *                       last-arriving workgroup of the Reuse kernel
- *   "finalize_variant"  1 = the Full finalise kernel re-reads the scores in every pass
+ *   "finalize_variant"  how the Full layer is finalised (merge of partials + top-k):
+ *                       1 = one launch, one workgroup per (batch, KV head), scores held in
+ *                       registers when they fit (default up to 32768 rows of context);
+ *                       2 = as 1 but re-reading the scores in every pass;
+ *                       3 = three launches with several workgroups per (batch, KV head)
+ *                       (default beyond 32768 rows)
+ *   "finalize_groups"   rows per workgroup of the three-launch finalise, in units of 4096: 2 or 8
  */
 hylra_status hylra_set_option(hylra_ctx *ctx, const char *name, int32_t value);
 
@@ -147,7 +153,7 @@ hylra_status hylra_set_option(hylra_ctx *ctx, const char *name, int32_t value);
  * synchronises those events and returns, per kernel class, the number of
  * launches and the summed duration in milliseconds since the last
  * hylra_profile_reset.  Classes: 0 = Full attention (split-KV pass),
- * 1 = Full finalise (combine + top-k), 2 = Reuse attention, 3 = Reuse combine (absent
+ * 1 = Full finalise (combine + top-k; all its launches), 2 = Reuse attention, 3 = Reuse combine (absent
  * in the fused mode), 4 = probe kernels.  At most HYLRA_PROFILE_MAX_EVENTS launches are recorded
  * between resets; later ones run untimed.
  */

@@ -7,7 +7,6 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
-#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -40,13 +39,13 @@ struct hylra_ctx {
     float* scores = nullptr;
     int* counters = nullptr;    // one arrival counter per (batch, KV head), zero between launches
     int* row_ctr = nullptr;     // one row counter per (batch, KV head), zero between launches
+    int* sel_ws = nullptr;      // selection scratch: histogram, candidates, counts (see SelectParams)
+    int64_t pairs_cap = 0;      // (batch, KV head) pairs the selection scratch is sized for
+    int max_chunks = 0;         // chunks of 8192 rows per (batch, KV head) at the maximum context
     int64_t slots = 0;          // capacity in (batch, KV head, split) triples
     int64_t cap_acc = 0;        // floats
     int64_t cap_ml = 0;
     int64_t cap_scores = 0;
-
-    float xcd_weight[8] = {1, 1, 1, 1, 1, 1, 1, 1};   // relative streaming speed of each XCD
-    bool xcd_weighted = false;
 
     int32_t opt_full_split_rows = 0;
     int32_t opt_reuse_split_rows = 0;
@@ -55,7 +54,7 @@ struct hylra_ctx {
     int32_t opt_reuse_unroll = 0;
     int32_t opt_reuse_unfused = 0;
     int32_t opt_finalize_variant = 0;
-    int32_t opt_full_equal_split = 0;
+    int32_t opt_finalize_groups = 0;
 
     bool prof_on = false;
     int prof_n = 0;
@@ -162,8 +161,6 @@ hipError_t launch_timed(hylra_ctx* ctx, int cls, hipStream_t st, F&& f) {
 
 struct FullPlan {
     int rows_per_split, n_splits, variant;
-    int xcd_weighted;
-    int xcd_bound[9];
 };
 
 hylra_status plan_full(const hylra_ctx* ctx, const hylra_shape* s, int G, FullPlan& pl) {
@@ -184,20 +181,6 @@ hylra_status plan_full(const hylra_ctx* ctx, const hylra_shape* s, int G, FullPl
         return fail(ctx, HYLRA_ERR_WORKSPACE, "batch*n_kv_heads = %lld exceeds the workspace", (long long)pairs);
     pl.rows_per_split = (int)rps;
     pl.n_splits = (int)S;
-    // XCD-aware shares: only when the splits of one (batch, KV head) map one-to-one onto XCDs
-    pl.xcd_weighted = ctx->xcd_weighted && S % 8 == 0 && !ctx->opt_full_equal_split;
-    if (pl.xcd_weighted) {
-        double total = 0, run = 0;
-        for (int x = 0; x < 8; ++x) total += ctx->xcd_weight[x];
-        pl.xcd_bound[0] = 0;
-        for (int x = 0; x < 8; ++x) {
-            run += ctx->xcd_weight[x];
-            pl.xcd_bound[x + 1] = (int)round_up((int64_t)(8.0 * rps * run / total + 0.5), quantum / 4);
-        }
-        pl.xcd_bound[8] = (int)(8 * rps);
-        for (int x = 1; x < 8; ++x)
-            if (pl.xcd_bound[x] < pl.xcd_bound[x - 1] || pl.xcd_bound[x] > pl.xcd_bound[8]) pl.xcd_weighted = 0;
-    }
     return HYLRA_OK;
 }
 
@@ -301,6 +284,11 @@ hylra_status hylra_create(hylra_ctx** out, const hylra_shape* max_shape, int32_t
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->scores, ctx->cap_scores * sizeof(float));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->counters, ctx->slots * sizeof(int));
     if (e == hipSuccess) e = hipMemset(ctx->counters, 0, ctx->slots * sizeof(int));
+    ctx->pairs_cap = pairs;
+    ctx->max_chunks = (int)ceil_div(max_shape->ctx_len, select_chunk_rows(2));
+    const int64_t sel_ints = pairs * (4096 + 1 + 1024 + 1024 + 2 + ctx->max_chunks);
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->sel_ws, sel_ints * sizeof(int));
+    if (e == hipSuccess) e = hipMemset(ctx->sel_ws, 0, sel_ints * sizeof(int));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->row_ctr, ctx->slots * sizeof(int));
     if (e == hipSuccess) e = hipMemset(ctx->row_ctr, 0, ctx->slots * sizeof(int));
     if (e == hipSuccess) e = hipDeviceSynchronize();
@@ -308,13 +296,6 @@ hylra_status hylra_create(hylra_ctx** out, const hylra_shape* max_shape, int32_t
         fail(nullptr, HYLRA_ERR_HIP, "workspace allocation failed: %s", hipGetErrorString(e));
         hylra_destroy(ctx);
         return HYLRA_ERR_HIP;
-    }
-    if (const char* env = std::getenv("HYLRA_XCD_WEIGHTS")) {     // tuning aid: 8 comma-separated speeds
-        float w[8];
-        if (std::sscanf(env, "%f,%f,%f,%f,%f,%f,%f,%f", w, w + 1, w + 2, w + 3, w + 4, w + 5, w + 6, w + 7) == 8) {
-            for (int x = 0; x < 8; ++x) ctx->xcd_weight[x] = w[x];
-            ctx->xcd_weighted = true;
-        }
     }
     *out = ctx;
     return HYLRA_OK;
@@ -334,6 +315,7 @@ hylra_status hylra_destroy(hylra_ctx* ctx) {
     if (ctx->scores) (void)hipFree(ctx->scores);
     if (ctx->counters) (void)hipFree(ctx->counters);
     if (ctx->row_ctr) (void)hipFree(ctx->row_ctr);
+    if (ctx->sel_ws) (void)hipFree(ctx->sel_ws);
     delete ctx;
     return HYLRA_OK;
 }
@@ -348,7 +330,10 @@ hylra_status hylra_set_option(hylra_ctx* ctx, const char* name, int32_t value) {
     else if (!std::strcmp(name, "reuse_unroll")) ctx->opt_reuse_unroll = value;
     else if (!std::strcmp(name, "reuse_unfused")) ctx->opt_reuse_unfused = value;
     else if (!std::strcmp(name, "finalize_variant")) ctx->opt_finalize_variant = value;
-    else if (!std::strcmp(name, "full_equal_split")) ctx->opt_full_equal_split = value;
+    else if (!std::strcmp(name, "finalize_groups")) {
+        if (value != 0 && value != 2 && value != 8) return fail(ctx, HYLRA_ERR_BAD_ARG, "finalize_groups must be 0, 2 or 8");
+        ctx->opt_finalize_groups = value;
+    }
     else return fail(ctx, HYLRA_ERR_BAD_ARG, "unknown option '%s'", name);
     return HYLRA_OK;
 }
@@ -384,18 +369,47 @@ hylra_status hylra_full_attn_topk(hylra_ctx* ctx, const hylra_shape* shape, cons
     fp.scores = ctx->scores;
     fp.score_stride = round_up(shape->ctx_len, 4);
     fp.row_ctr = ctx->row_ctr;
-    fp.xcd_weighted = pl.xcd_weighted;
-    for (int x = 0; x < 9; ++x) fp.xcd_bound[x] = pl.xcd_bound[x];
     HIP_TRY(ctx, launch_timed(ctx, 0, st, [&] {
                 return launch_full_split(fp, shape->batch, shape->head_dim, G, pl.variant, st);
             }));
 
+    const int64_t pairs = (int64_t)shape->batch * shape->n_kv_heads;
+    // One workgroup per (batch, KV head) keeps up to 32768 scores in registers and needs a
+    // single launch; beyond that the three-launch, several-workgroups form is faster.
+    const bool multi = ctx->opt_finalize_variant == 3 ||
+                       (ctx->opt_finalize_variant == 0 && shape->ctx_len > 32768);
+    if (multi) {
+        // finalise spread over several workgroups per (batch, KV head): three launches
+        int E = 2;
+        if (pairs * ceil_div(shape->ctx_len, select_chunk_rows(2)) > 4096) E = 8;
+        if (ctx->opt_finalize_groups) E = ctx->opt_finalize_groups;
+        const int64_t chunks = ceil_div(shape->ctx_len, select_chunk_rows(E));
+        if (pairs > ctx->pairs_cap || chunks > ctx->max_chunks)
+            return fail(ctx, HYLRA_ERR_WORKSPACE, "batch*n_kv_heads = %lld or ctx_len = %d exceeds the selection workspace", (long long)pairs, shape->ctx_len);
+        SelectParams sp{};
+        sp.part_ml = ctx->part_ml, sp.part_acc = ctx->part_acc, sp.part_mm = ctx->part_mm;
+        sp.scores = ctx->scores, sp.score_stride = fp.score_stride;
+        sp.n_splits = pl.n_splits, sp.Hq = shape->n_q_heads, sp.Hkv = shape->n_kv_heads;
+        sp.G = G, sp.D = shape->head_dim, sp.N = shape->ctx_len, sp.k = k;
+        sp.out = out, sp.idx = idx, sp.row_ctr = ctx->row_ctr;
+        int* w = ctx->sel_ws;
+        sp.ghist = w, w += ctx->pairs_cap * 4096;
+        sp.cand_n = w, w += ctx->pairs_cap;
+        sp.cand_key = (uint32_t*)w, w += ctx->pairs_cap * 1024;
+        sp.cand_pos = w, w += ctx->pairs_cap * 1024;
+        sp.sel_info = w, w += ctx->pairs_cap * 2;
+        sp.chunk_gt = w;
+        sp.max_chunks = ctx->max_chunks;
+        for (int step = 0; step < 3; ++step)
+            HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_select(sp, shape->batch, E, step, st); }));
+        return HYLRA_OK;
+    }
     FinalizeParams zp{};
     zp.part_ml = ctx->part_ml, zp.part_acc = ctx->part_acc, zp.part_mm = ctx->part_mm;
     zp.scores = ctx->scores, zp.score_stride = fp.score_stride;
     zp.n_splits = pl.n_splits, zp.Hq = shape->n_q_heads, zp.Hkv = shape->n_kv_heads;
     zp.G = G, zp.D = shape->head_dim, zp.N = shape->ctx_len, zp.k = k;
-    zp.variant = ctx->opt_finalize_variant;
+    zp.variant = ctx->opt_finalize_variant == 2 ? 1 : 0;
     zp.row_ctr = ctx->row_ctr;
     zp.out = out, zp.idx = idx;
     HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_full_finalize(zp, shape->batch, st); }));

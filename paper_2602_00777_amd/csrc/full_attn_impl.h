@@ -40,13 +40,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
 
     LaneState<GEO> st;
     st.init();
-    int row0 = MODE == 3 ? 0 : split * p.rows_per_split;
-    int row1 = MODE == 3 ? p.N : min(p.N, row0 + p.rows_per_split);
-    if (MODE != 3 && p.xcd_weighted) {
-        const int run0 = (split >> 3) * 8 * p.rows_per_split;
-        row0 = min(p.N, run0 + p.xcd_bound[split & 7]);
-        row1 = min(p.N, run0 + p.xcd_bound[(split & 7) + 1]);
-    }
+    const int row0 = MODE == 3 ? 0 : split * p.rows_per_split;
+    const int row1 = MODE == 3 ? p.N : min(p.N, row0 + p.rows_per_split);
     float* __restrict__ srow = p.scores + ((int64_t)b * p.Hkv + g) * p.score_stride;
     float smin = 3.0e38f, smax = -3.0e38f;
 

@@ -23,11 +23,6 @@ struct FullParams {
     float* scores;                  // [B*Hkv][score_stride] group-mean scaled scores
     int64_t score_stride;           // multiple of 4, >= N
     int* row_ctr;                   // [B*Hkv] next unclaimed row (dynamic mode); zero at launch
-    // XCD-aware split: when xcd_weighted, every run of 8 consecutive splits (one per XCD:
-    // workgroups go to the 8 XCDs round-robin) shares 8*rows_per_split rows, split x taking
-    // rows [xcd_bound[x], xcd_bound[x+1]) of the run instead of an equal eighth.
-    int xcd_weighted;
-    int xcd_bound[9];
 };
 
 struct FinalizeParams {
@@ -41,6 +36,27 @@ struct FinalizeParams {
     int variant;                    // 0: scores kept in registers when they fit; 1: always re-read
     float* out;                     // [B][Hq][D]
     int32_t* idx;                   // [B][Hkv][k]
+};
+
+// Multi-workgroup finalise (select.hip): same inputs as FinalizeParams plus per-(batch, KV
+// head) scratch that is zero between launches where noted.
+struct SelectParams {
+    const float* part_ml;
+    const float* part_acc;
+    const float* part_mm;
+    const float* scores;
+    int64_t score_stride;
+    int n_splits, Hq, Hkv, G, D, N, k;
+    float* out;                     // [B][Hq][D]
+    int32_t* idx;                   // [B][Hkv][k]
+    int* row_ctr;                   // [B*Hkv], reset to zero for the next Full launch
+    int* ghist;                     // [B*Hkv][4096] score histogram; zero between launches
+    int* cand_n;                    // [B*Hkv] rows in the threshold bin found so far
+    uint32_t* cand_key;             // [B*Hkv][1024] their keys ...
+    int* cand_pos;                  // ... and positions (arrival order)
+    int* sel_info;                  // [B*Hkv][2] threshold bin, rows above it
+    int* chunk_gt;                  // [B*Hkv][max_chunks] rows above the threshold bin per chunk
+    int max_chunks;
 };
 
 struct ReuseParams {
@@ -95,6 +111,9 @@ inline hipError_t launch_reuse_split(const ReuseParams& p, int B, int D, int G, 
 }
 
 hipError_t launch_full_finalize(const FinalizeParams& p, int B, hipStream_t st);
+// step 0, 1, 2 = histogram, classify, emit; E = float4 groups per thread (2 or 8)
+int select_chunk_rows(int E);
+hipError_t launch_select(const SelectParams& p, int B, int E, int step, hipStream_t st);
 hipError_t launch_combine(const CombineParams& p, int n_heads_total, hipStream_t st);
 hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t st);

@@ -76,8 +76,8 @@ def test_full_kernel_variants(variant):
 
 @pytest.mark.parametrize("N,k", [(5003, 300), (20000, 1500), (40000, 3000)])
 def test_finalize_paths(N, k):
-    """Both score sources of the finalise kernel (registers / re-read per pass), including the
-    many-ties fallback, at sizes that use different register-resident group counts."""
+    """Every finalise path (multi-workgroup; single workgroup with scores in registers / re-read
+    per pass), including the many-ties fallback, at sizes that span one to several chunks."""
     say("finalize paths N=%d k=%d" % (N, k))
     B, Hkv, G, d = 1, 2, 4, 64
     q, K, V = rand_case(19 + N, B, Hkv, G, d, N)
@@ -89,8 +89,9 @@ def test_finalize_paths(N, k):
            oracle.full_attn_topk(qt, Kt, V, k, want_shat=True),
            oracle.full_attn_topk(q, Kz, V, k, want_shat=True)]
     with binding.Context(B, Hkv * G, Hkv, d, N, k) as ctx:
-        for variant in (0, 1):
+        for variant, groups in ((3, 2), (3, 8), (1, 0), (2, 0), (0, 0)):
             ctx.set_option("finalize_variant", variant)
+            ctx.set_option("finalize_groups", groups)
             for (qq, KK), (ro, ri, rs), exact in (((q, K), ref[0], False), ((qt, Kt), ref[1], True), ((q, Kz), ref[2], True)):
                 out, idx = run_full(ctx, qq, KK, V, k)
                 assert_out_close(out, ro, "out")
