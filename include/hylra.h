@@ -128,10 +128,13 @@ hylra_status hylra_decode_step(hylra_ctx *ctx, const hylra_shape *shape, int32_t
  * HYLRA_ERR_BAD_ARG; 0 always means "automatic / default".  Names:
  *   "full_split_rows"   rows of the cache per workgroup of the Full kernel
  *   "reuse_split_rows"  index entries per workgroup of the Reuse kernel
- *   "full_variant"      10*mode + unroll of the Full kernel: 4 (plain loads), 14 (streaming
- *                       loads), 23 (streaming loads, two-deep register pipeline; default),
- *                       34 / 32 (rows claimed dynamically through a shared counter)
- *   "reuse_variant"     1 = plain loads instead of streaming loads in the Reuse kernel
+ *   "full_variant"      Full streaming kernel.  Vector-ALU kernels, 10*mode + unroll: 4 (plain
+ *                       loads), 14 (streaming loads), 23 (streaming loads, two-deep register
+ *                       pipeline; default up to 4 heads per KV head), 34 / 32 (rows claimed
+ *                       dynamically through a shared counter).  Matrix-core kernels: 54, 52
+ *                       (default from 5 heads per KV head), 62, 61 (pipelined)
+ *   "reuse_variant"     Reuse gather kernel: 1 / 2 = vector-ALU kernel with streaming / plain
+ *                       loads, 3 / 4 = matrix-core kernel with streaming / plain loads (default 4)
  *   "reuse_unroll"      row groups per wave tile of the Reuse kernel: 1, 2, 4 or 8
  *   "reuse_unfused"     1 = merge the Reuse partials in a second kernel instead of in the
  *                       last-arriving workgroup of the Reuse kernel

@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhylra.so")
 SOURCES = ["api.hip", "full_attn_d64.hip", "full_attn_d128.hip", "reuse_attn_d64.hip",
-           "reuse_attn_d128.hip", "finalize.hip", "select.hip"]
+           "reuse_attn_d128.hip", "finalize.hip", "select.hip", "reuse_mfma.hip", "full_mfma.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-FP32 code generation is switched off on purpose (device pass only)
@@ -36,7 +36,7 @@ def _compile(src: str) -> str:
     return obj
 
 
-def build(jobs: int = 6) -> str:
+def build(jobs: int = 8) -> str:
     """Compile and link.  HYLRA_EXTRA_FLAGS adds compiler flags and HYLRA_LIB_OUT redirects
     the output (both only for tuning builds; the product build uses neither)."""
     global BUILD, LIB

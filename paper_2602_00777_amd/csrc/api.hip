@@ -164,7 +164,9 @@ struct FullPlan {
 };
 
 hylra_status plan_full(const hylra_ctx* ctx, const hylra_shape* s, int G, FullPlan& pl) {
-    pl.variant = ctx->opt_full_variant;
+    // automatic: the vector kernel is HBM-bound up to 4 heads per group; beyond that its own
+    // arithmetic limits it and the matrix-core kernel is faster (measured at G = 7)
+    pl.variant = ctx->opt_full_variant > 0 ? ctx->opt_full_variant : (G > 4 ? 52 : 23);
     const int quantum = full_block_quantum(s->head_dim, G, pl.variant);
     if (quantum <= 0) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "Full kernel variant %d is not built for d=%d G=%d", pl.variant, s->head_dim, G);
     const int64_t pairs = (int64_t)s->batch * s->n_kv_heads;
@@ -189,17 +191,22 @@ struct ReusePlan {
 };
 
 hylra_status plan_reuse(const hylra_ctx* ctx, const hylra_shape* s, int G, int k, ReusePlan& pl) {
-    pl.variant = ctx->opt_reuse_variant;
+    // public ids 1..4 = vector kernel (streaming / plain loads), matrix-core kernel (streaming /
+    // plain loads); automatic = matrix cores with plain loads (fastest on 3 of the 4 large
+    // benchmark shapes, within 2 % on the fourth)
+    pl.variant = (ctx->opt_reuse_variant >= 1 && ctx->opt_reuse_variant <= 4) ? ctx->opt_reuse_variant - 1 : 3;
     const int64_t pairs = (int64_t)s->batch * s->n_kv_heads;
     // Unroll: 8 row groups per wave tile (64 rows per wave with 8 lanes per row) keeps the
     // whole gather of a layer in flight at once and the number of partials per (batch, KV
     // head) small, which the in-kernel merge needs (its arrival counter serialises).  Smaller
     // tiles only when a single workgroup still covers all k entries.
     pl.R = ctx->opt_reuse_unroll > 0 ? ctx->opt_reuse_unroll : 8;
-    while (ctx->opt_reuse_unroll == 0 && pl.R > 1 &&
-           reuse_block_quantum(s->head_dim, G, pl.variant, pl.R / 2) >= k)
-        pl.R /= 2;
-    pl.rows_per_split = reuse_block_quantum(s->head_dim, G, pl.variant, pl.R);
+    const bool mfma = pl.variant >= 2;
+    auto quantum_of = [&](int R) {
+        return mfma ? reuse_mfma_quantum(R / 2) : reuse_block_quantum(s->head_dim, G, pl.variant, R);
+    };
+    while (ctx->opt_reuse_unroll == 0 && pl.R > (mfma ? 2 : 1) && quantum_of(pl.R / 2) >= k) pl.R /= 2;
+    pl.rows_per_split = quantum_of(pl.R);
     if (pl.rows_per_split <= 0)
         return fail(ctx, HYLRA_ERR_UNSUPPORTED, "Reuse kernel variant %d / unroll %d is not built for d=%d G=%d", pl.variant, pl.R, s->head_dim, G);
     int64_t rps = pl.rows_per_split;
@@ -448,6 +455,8 @@ hylra_status hylra_reuse_sparse_attn(hylra_ctx* ctx, const hylra_shape* shape, c
     rp.counters = fused ? ctx->counters : nullptr;
     rp.out = out;
     HIP_TRY(ctx, launch_timed(ctx, 2, st, [&] {
+                if (pl.variant >= 2)
+                    return launch_reuse_mfma(rp, shape->batch, shape->head_dim, G, pl.R / 2, pl.variant == 2, st);
                 return launch_reuse_split(rp, shape->batch, shape->head_dim, G, pl.variant, pl.R, st);
             }));
     if (fused) return HYLRA_OK;

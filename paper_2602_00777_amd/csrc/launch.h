@@ -95,10 +95,16 @@ int reuse_block_quantum_d128(int G, int variant, int R);
 hipError_t launch_reuse_split_d64(const ReuseParams& p, int B, int G, int variant, int R, hipStream_t st);
 hipError_t launch_reuse_split_d128(const ReuseParams& p, int B, int G, int variant, int R, hipStream_t st);
 
+// Matrix-core Full kernel (full_mfma.hip): variants 54, 52 (one tile at a time), 62, 61 (pipelined)
+int full_mfma_quantum(int variant);
+hipError_t launch_full_mfma(const FullParams& p, int B, int D, int G, int variant, hipStream_t st);
+
 inline int full_block_quantum(int D, int G, int variant) {
+    if (variant >= 50) return (D == 64 || D == 128) ? full_mfma_quantum(variant) : 0;
     return D == 64 ? full_block_quantum_d64(G, variant) : D == 128 ? full_block_quantum_d128(G, variant) : 0;
 }
 inline hipError_t launch_full_split(const FullParams& p, int B, int D, int G, int variant, hipStream_t st) {
+    if (variant >= 50) return launch_full_mfma(p, B, D, G, variant, st);
     return D == 64 ? launch_full_split_d64(p, B, G, variant, st)
          : D == 128 ? launch_full_split_d128(p, B, G, variant, st) : hipErrorInvalidValue;
 }
@@ -109,6 +115,10 @@ inline hipError_t launch_reuse_split(const ReuseParams& p, int B, int D, int G, 
     return D == 64 ? launch_reuse_split_d64(p, B, G, variant, R, st)
          : D == 128 ? launch_reuse_split_d128(p, B, G, variant, R, st) : hipErrorInvalidValue;
 }
+
+// Matrix-core Reuse kernel: NB blocks of 16 rows per wave tile (1, 2 or 4)
+int reuse_mfma_quantum(int NB);
+hipError_t launch_reuse_mfma(const ReuseParams& p, int B, int D, int G, int NB, bool nt, hipStream_t st);
 
 hipError_t launch_full_finalize(const FinalizeParams& p, int B, hipStream_t st);
 // step 0, 1, 2 = histogram, classify, emit; E = float4 groups per thread (2 or 8)

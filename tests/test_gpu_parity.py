@@ -59,7 +59,7 @@ def test_full_attn_topk_matches_oracle(B, Hkv, G, d, N, k):
     assert_idx_valid(idx, shat, k, "full idx", exact_ref=ref_idx)
 
 
-@pytest.mark.parametrize("variant", [4, 14, 23, 34, 32])
+@pytest.mark.parametrize("variant", [4, 14, 23, 34, 32, 54, 52, 62, 61])
 def test_full_kernel_variants(variant):
     say("full variant=%d" % variant)
     B, Hkv, G, d, N, k = 2, 2, 4, 128, 5003, 300
@@ -110,8 +110,10 @@ def test_reuse_kernel_unrolls(unroll):
     ref = oracle.reuse_sparse_attn(q, K, V, idx)
     with binding.Context(B, Hkv * G, Hkv, d, N, k) as ctx:
         ctx.set_option("reuse_unroll", unroll)
-        for plain in (0, 1):
-            ctx.set_option("reuse_variant", plain)
+        for variant in (1, 2, 3, 4):        # vector kernel (streaming / plain loads), matrix-core kernel
+            if variant >= 3 and unroll == 1:
+                continue
+            ctx.set_option("reuse_variant", variant)
             out = ctx.reuse_sparse_attn(q, K, V, torch.from_numpy(idx).to(DEV))
             torch.cuda.synchronize()
             assert_out_close(out.cpu().numpy(), ref, "reuse out")
