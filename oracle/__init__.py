@@ -7,6 +7,8 @@ from .binding import (  # noqa: F401
     build,
     decode_step,
     full_attn_topk,
+    full_attn_topk_blocks,
+    reuse_block_attn,
     overlap,
     reuse_sparse_attn,
     threads,

@@ -51,6 +51,12 @@ def _load():
             lib.hylra_oracle_decode_step.argtypes = [i32, i32, vp, i32, i32, i32, i32, i64, i32,
                                                      f64, vp, vp, vp, vp, vp, vp]
             lib.hylra_oracle_decode_step.restype = i32
+            lib.hylra_oracle_full_attn_topk_blocks.argtypes = [i32, i32, i32, i32, i32, i64, i32, i32, f64,
+                                                               vp, vp, vp, vp, vp, vp]
+            lib.hylra_oracle_full_attn_topk_blocks.restype = i32
+            lib.hylra_oracle_reuse_block_attn.argtypes = [i32, i32, i32, i32, i32, i64, i32, i32, f64,
+                                                          vp, vp, vp, vp, vp]
+            lib.hylra_oracle_reuse_block_attn.restype = i32
             lib.hylra_oracle_overlap.argtypes = [vp, vp, i32]
             lib.hylra_oracle_overlap.restype = f64
             lib.hylra_oracle_threads.restype = i32
@@ -125,6 +131,34 @@ def reuse_sparse_attn(q, K, V, idx, scale=0.0):
     rc = _load().hylra_oracle_reuse_sparse_attn(kind, B, Hq, Hkv, d, N, k, float(scale),
                                                 _ptr(q), _ptr(K), _ptr(V), _ptr(idx), _ptr(out))
     _check(rc, "reuse_sparse_attn")
+    return out
+
+
+def full_attn_topk_blocks(q, K, V, block, kb, scale=0.0, want_bscore=False):
+    """Full layer, block-level TopK: returns (out [B,Hq,d], bidx [B,Hkv,kb], bscore or None)."""
+    q, K, V, kind, B, Hq, Hkv, d, N = _triple(q, K, V)
+    nblk = -(-N // int(block))
+    out = np.empty((B, Hq, d), np.float64)
+    bidx = np.empty((B, Hkv, int(kb)), np.int32)
+    bscore = np.empty((B, Hkv, nblk), np.float64) if want_bscore else None
+    rc = _load().hylra_oracle_full_attn_topk_blocks(kind, B, Hq, Hkv, d, N, int(block), int(kb),
+                                                    float(scale), _ptr(q), _ptr(K), _ptr(V),
+                                                    _ptr(out), _ptr(bidx), _ptr(bscore))
+    _check(rc, "full_attn_topk_blocks")
+    return out, bidx, bscore
+
+
+def reuse_block_attn(q, K, V, bidx, block, scale=0.0):
+    """Reuse layer on inherited block numbers bidx [B,Hkv,kb]: out [B,Hq,d]."""
+    q, K, V, kind, B, Hq, Hkv, d, N = _triple(q, K, V)
+    bidx = np.ascontiguousarray(np.asarray(bidx, dtype=np.int32))
+    if bidx.shape[:2] != (B, Hkv):
+        raise ValueError("bidx shape %s does not match [B=%d, Hkv=%d, kb]" % (bidx.shape, B, Hkv))
+    out = np.empty((B, Hq, d), np.float64)
+    rc = _load().hylra_oracle_reuse_block_attn(kind, B, Hq, Hkv, d, N, int(block), bidx.shape[2],
+                                               float(scale), _ptr(q), _ptr(K), _ptr(V), _ptr(bidx),
+                                               _ptr(out))
+    _check(rc, "reuse_block_attn")
     return out
 
 

@@ -256,6 +256,77 @@ int hylra_oracle_decode_step(int kind, int L, const uint8_t *policy, int B, int 
     return ORACLE_OK;
 }
 
+/*
+ * Block-level variant (paper, "Adaptation to block-level sparsity"): consecutive tokens are
+ * grouped into blocks of `block` positions (the last block may be short) and TopK selects
+ * BLOCKS, which the following Reuse layers inherit.  The paper does not say how a block is
+ * scored from its tokens; the reading taken here is the MAXIMUM over the block's tokens of
+ * the group-mean token score (a block matters if it holds a critical token).  Ties go to the
+ * lower block; the kb block numbers come out ascending.  The Full layer's output stays the
+ * dense attention over all N rows.
+ *   bidx   [B, Hkv, kb] int32        bscore (optional) [B, Hkv, ceil(N / block)] double
+ */
+int hylra_oracle_full_attn_topk_blocks(int kind, int B, int Hq, int Hkv, int d, long N, int block,
+                                       int kb, double scale, const void *q, const void *K,
+                                       const void *V, double *out, int32_t *bidx, double *bscore)
+{
+    if (!shape_ok(B, Hq, Hkv, d, N) || block < 1 || !bidx) return ORACLE_BAD_ARG;
+    const long nblk = (N + block - 1) / block;
+    if (kb < 1 || kb > nblk) return ORACLE_BAD_ARG;
+    double *shat = malloc((size_t)B * Hkv * N * sizeof *shat);
+    if (!shat) return ORACLE_NOMEM;
+    int rc = hylra_oracle_full_attn_topk(kind, B, Hq, Hkv, d, N, 1, scale, q, K, V, out, NULL, shat);
+    if (rc != ORACLE_OK) { free(shat); return rc; }
+    ranked *r = malloc((size_t)nblk * sizeof *r);
+    if (!r) { free(shat); return ORACLE_NOMEM; }
+    for (int p = 0; p < B * Hkv; ++p) {
+        const double *s = shat + (size_t)p * N;
+        for (long c = 0; c < nblk; ++c) {
+            const long lo = c * block, hi = lo + block < N ? lo + block : N;
+            double m = s[lo];
+            for (long j = lo + 1; j < hi; ++j) if (s[j] > m) m = s[j];
+            r[c].score = m;
+            r[c].pos = (int32_t)c;
+            if (bscore) bscore[(size_t)p * nblk + c] = m;
+        }
+        qsort(r, (size_t)nblk, sizeof *r, by_score_then_pos);
+        int32_t *dst = bidx + (size_t)p * kb;
+        for (int t = 0; t < kb; ++t) dst[t] = r[t].pos;
+        qsort(dst, (size_t)kb, sizeof *dst, by_pos);
+    }
+    free(r);
+    free(shat);
+    return ORACLE_OK;
+}
+
+/*
+ * Reuse layer on inherited BLOCK numbers: attention restricted to every existing token of
+ * the named blocks.  Negative block numbers are padding; numbers >= ceil(N / block) are an
+ * error.
+ */
+int hylra_oracle_reuse_block_attn(int kind, int B, int Hq, int Hkv, int d, long N, int block, int kb,
+                                  double scale, const void *q, const void *K, const void *V,
+                                  const int32_t *bidx, double *out)
+{
+    if (!shape_ok(B, Hq, Hkv, d, N) || block < 1 || kb < 1 || !bidx || !out) return ORACLE_BAD_ARG;
+    const long nblk = (N + block - 1) / block;
+    const size_t per = (size_t)kb * block;
+    int32_t *tok = malloc((size_t)B * Hkv * per * sizeof *tok);
+    if (!tok) return ORACLE_NOMEM;
+    for (size_t p = 0; p < (size_t)B * Hkv; ++p)
+        for (int t = 0; t < kb; ++t) {
+            const int32_t c = bidx[p * kb + t];
+            if (c >= nblk) { free(tok); return ORACLE_BAD_ARG; }
+            for (int j = 0; j < block; ++j) {
+                const long pos = (long)c * block + j;
+                tok[p * per + (size_t)t * block + j] = (c < 0 || pos >= N) ? -1 : (int32_t)pos;
+            }
+        }
+    int rc = hylra_oracle_reuse_sparse_attn(kind, B, Hq, Hkv, d, N, (int)per, scale, q, K, V, tok, out);
+    free(tok);
+    return rc;
+}
+
 /* |S_i ∩ S_j| / k for two index sets of size k (overlap ratio, Eq. 2) */
 double hylra_oracle_overlap(const int32_t *a, const int32_t *b, int k)
 {

@@ -400,3 +400,70 @@ def test_argument_errors():
     bad = np.full((2, 2, 3), K.shape[2], np.int32)
     with pytest.raises(RuntimeError):
         oracle.reuse_sparse_attn(q, K, V, bad)
+
+
+# --------------------------------------------------------------------------------------
+# 7. block-level variant (block TopK, block reuse)
+# --------------------------------------------------------------------------------------
+def test_block_variant_hand_worked():
+    """The single-head golden example with blocks of 2: token scores (0, ln2, ln4, 0) give block
+    scores (ln2, ln4): top-1 block is block 1 = tokens {2,3}, weights (4,1)/5."""
+    g = read_golden("single_head_4tok.txt")
+    q = g["q"].reshape(1, 1, 4)
+    K = g["K"].reshape(1, 1, 4, 4)
+    V = g["V"].reshape(1, 1, 4, 4)
+    out, bidx, bs = oracle.full_attn_topk_blocks(q, K, V, 2, 1, want_bscore=True)
+    np.testing.assert_allclose(out[0, 0], g["full_out"], rtol=0, atol=1e-15)     # dense output unchanged
+    np.testing.assert_allclose(bs[0, 0], [math.log(2.0), math.log(4.0)], rtol=0, atol=1e-15)
+    assert bidx[0, 0].tolist() == [1]
+    o = oracle.reuse_block_attn(q, K, V, bidx, 2)
+    np.testing.assert_allclose(o[0, 0], [0.8, 0.8, 0, 0], rtol=0, atol=1e-15)   # (4*V2 + 1*V3)/5
+    _, both, _ = oracle.full_attn_topk_blocks(q, K, V, 2, 2)
+    assert both[0, 0].tolist() == [0, 1]
+    np.testing.assert_allclose(oracle.reuse_block_attn(q, K, V, both, 2)[0, 0], g["full_out"], atol=1e-15)
+
+
+def test_block_variant_against_brute_force_and_token_level():
+    rng = np.random.RandomState(70)
+    B, Hkv, G, d, N = 2, 2, 3, 8, 29          # 29 is not a multiple of the block sizes below
+    q, K, V = rng.randn(B, Hkv * G, d), rng.randn(B, Hkv, N, d), rng.randn(B, Hkv, N, d)
+    dense, _, shat = oracle.full_attn_topk(q, K, V, 1, want_shat=True)
+    for block in (1, 4, 5, 29, 40):
+        nblk = -(-N // block)
+        for kb in sorted({1, nblk // 2 + 1, nblk}):
+            out, bidx, bs = oracle.full_attn_topk_blocks(q, K, V, block, kb, want_bscore=True)
+            np.testing.assert_array_equal(out, dense)
+            for b in range(B):
+                for g in range(Hkv):
+                    ref = [max(shat[b, g, c * block:min(N, (c + 1) * block)]) for c in range(nblk)]
+                    np.testing.assert_allclose(bs[b, g], ref, rtol=0, atol=0)
+                    order = sorted(range(nblk), key=lambda c: (-ref[c], c))
+                    assert bidx[b, g].tolist() == sorted(order[:kb])
+            # block reuse == token reuse over the tokens of the blocks
+            tok = np.full((B, Hkv, kb * block), -1, np.int32)
+            for b in range(B):
+                for g in range(Hkv):
+                    t = [c * block + j for c in bidx[b, g] for j in range(block) if c * block + j < N]
+                    tok[b, g, :len(t)] = t
+            np.testing.assert_allclose(oracle.reuse_block_attn(q, K, V, bidx, block),
+                                       oracle.reuse_sparse_attn(q, K, V, tok), rtol=1e-13, atol=1e-15)
+            if block == 1:   # blocks of one token are the token-level algorithm
+                _, idx, _ = oracle.full_attn_topk(q, K, V, kb)
+                np.testing.assert_array_equal(bidx, idx)
+    # padding blocks are skipped; all blocks selected = dense attention
+    _, allb, _ = oracle.full_attn_topk_blocks(q, K, V, 4, 8)
+    padded = np.concatenate([np.full((B, Hkv, 2), -1, np.int32), allb], axis=2)
+    np.testing.assert_allclose(oracle.reuse_block_attn(q, K, V, padded, 4), dense, rtol=1e-13, atol=1e-15)
+    with pytest.raises(RuntimeError):
+        oracle.full_attn_topk_blocks(q, K, V, 4, 9)
+    with pytest.raises(RuntimeError):
+        oracle.reuse_block_attn(q, K, V, np.full((B, Hkv, 1), 8, np.int32), 4)
+
+
+def test_block_variant_ties_go_to_lower_block():
+    q = np.zeros((1, 1, 4)); q[0, 0, 0] = 2.0
+    K = np.zeros((1, 1, 8, 4)); K[0, 0, :, 0] = [1, 0, 0, 1, 0, 0, 1, 0]     # blocks of 2: scores 1,1,0,1
+    V = np.random.RandomState(1).randn(1, 1, 8, 4)
+    _, bidx, bs = oracle.full_attn_topk_blocks(q, K, V, 2, 2, want_bscore=True)
+    assert bs[0, 0].tolist() == [1.0, 1.0, 0.0, 1.0]
+    assert bidx[0, 0].tolist() == [0, 1]
