@@ -124,6 +124,38 @@ hylra_status hylra_decode_step(hylra_ctx *ctx, const hylra_shape *shape, int32_t
                                float *const *out_l, int32_t *idx_buf, void *hip_stream);
 
 /*
+ * Block-level variant (paper, section on hardware-efficient optimizations, adaptation to
+ * block-level sparsity): consecutive rows of the cache form blocks of `block` rows (the last
+ * block may be short) and TopK ranks BLOCKS; Reuse layers inherit the block numbers and
+ * attend to every row of the named blocks.  The paper does not fix how a block is scored
+ * from its rows; here a block scores the MAXIMUM of its rows' group-mean scaled logits.
+ * Ties go to the lower block; numbers come out ascending.  The Full layer's output is the
+ * dense attention over all ctx_len rows, as in hylra_full_attn_topk.
+ *
+ *   block   rows per block, 1..65536 (1 = the token-level calls above); any value, not only
+ *           powers of two
+ *   kb      blocks selected per (batch, KV head): 1..ceil(ctx_len / block), and
+ *           kb * block <= max_k of hylra_create rounded up to a multiple of block
+ *   bidx    DEVICE [batch, n_kv_heads, kb] int32: written by the Full call, read by the
+ *           Reuse call.  For the Reuse call, entries < 0 or >= ceil(ctx_len / block) are
+ *           padding and skipped, as are the rows of the last block beyond ctx_len.
+ *   bidx_buf  DEVICE, at least batch * n_kv_heads * kb int32 (as idx_buf above)
+ * All other arguments, ownership, stream order and error behaviour are those of the
+ * token-level calls of the same name.
+ */
+hylra_status hylra_full_attn_topk_blocks(hylra_ctx *ctx, const hylra_shape *shape, const void *q,
+                                         const void *K, const void *V, int32_t block, int32_t kb,
+                                         float *out, int32_t *bidx, void *hip_stream);
+hylra_status hylra_reuse_block_attn(hylra_ctx *ctx, const hylra_shape *shape, const void *q,
+                                    const void *K, const void *V, const int32_t *bidx,
+                                    int32_t block, int32_t kb, float *out, void *hip_stream);
+hylra_status hylra_decode_step_blocks(hylra_ctx *ctx, const hylra_shape *shape, int32_t n_layers,
+                                      const uint8_t *policy, const void *const *q_l,
+                                      const void *const *K_l, const void *const *V_l, int32_t block,
+                                      int32_t kb, float *const *out_l, int32_t *bidx_buf,
+                                      void *hip_stream);
+
+/*
  * Tuning knobs (HOST call, takes effect for later launches).  Unknown names give
  * HYLRA_ERR_BAD_ARG; 0 always means "automatic / default".  Names:
  *   "full_split_rows"   rows of the cache per workgroup of the Full kernel

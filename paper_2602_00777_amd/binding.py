@@ -21,6 +21,7 @@ PROFILE_CLASSES = ("full_attn", "full_finalize", "reuse_attn", "reuse_combine", 
 EXPORTS = (
     "hylra_create", "hylra_destroy", "hylra_status_str", "hylra_last_error",
     "hylra_full_attn_topk", "hylra_reuse_sparse_attn", "hylra_decode_step",
+    "hylra_full_attn_topk_blocks", "hylra_reuse_block_attn", "hylra_decode_step_blocks",
     "hylra_set_option", "hylra_profile_enable", "hylra_profile_reset", "hylra_profile_read",
     "hylra_probe_copy", "hylra_probe_read",
 )
@@ -64,6 +65,9 @@ def load_library() -> ctypes.CDLL:
     lib.hylra_full_attn_topk.argtypes = [vp, sp, vp, vp, vp, i32, vp, vp, vp]
     lib.hylra_reuse_sparse_attn.argtypes = [vp, sp, vp, vp, vp, vp, i32, vp, vp]
     lib.hylra_decode_step.argtypes = [vp, sp, i32, vp, vp, vp, vp, i32, vp, vp, vp]
+    lib.hylra_full_attn_topk_blocks.argtypes = [vp, sp, vp, vp, vp, i32, i32, vp, vp, vp]
+    lib.hylra_reuse_block_attn.argtypes = [vp, sp, vp, vp, vp, vp, i32, i32, vp, vp]
+    lib.hylra_decode_step_blocks.argtypes = [vp, sp, i32, vp, vp, vp, vp, i32, i32, vp, vp, vp]
     lib.hylra_set_option.argtypes = [vp, ctypes.c_char_p, i32]
     lib.hylra_profile_enable.argtypes = [vp, i32]
     lib.hylra_profile_reset.argtypes = [vp]
@@ -168,10 +172,44 @@ class Context:
         self._check(rc, "hylra_reuse_sparse_attn")
         return out
 
-    def prepare_step(self, policy: Sequence[int], q_l, K_l, V_l, k: int, scale: float = 0.0):
+    # -- block-level variant ---------------------------------------------------------------
+    def full_attn_topk_blocks(self, q, K, V, block: int, kb: int, out=None, bidx=None, scale: float = 0.0):
+        """hylra_full_attn_topk_blocks: returns (out fp32 [B,Hq,d], bidx int32 [B,Hkv,kb])."""
+        self._check_inputs(q, K, V)
+        shp = make_shape(q, K, scale)
+        if out is None:
+            out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+        if bidx is None:
+            bidx = torch.empty((shp.batch, shp.n_kv_heads, kb), dtype=torch.int32, device=q.device)
+        rc = self._lib.hylra_full_attn_topk_blocks(self._h, ctypes.byref(shp), q.data_ptr(),
+                                                   K.data_ptr(), V.data_ptr(), block, kb,
+                                                   out.data_ptr(), bidx.data_ptr(),
+                                                   _stream_ptr(q.device))
+        self._check(rc, "hylra_full_attn_topk_blocks")
+        return out, bidx
+
+    def reuse_block_attn(self, q, K, V, bidx, block: int, out=None, scale: float = 0.0):
+        """hylra_reuse_block_attn: returns out fp32 [B,Hq,d]."""
+        self._check_inputs(q, K, V)
+        if bidx.dtype != torch.int32 or not bidx.is_cuda or not bidx.is_contiguous():
+            raise TypeError("bidx must be a contiguous int32 CUDA tensor")
+        shp = make_shape(q, K, scale)
+        if tuple(bidx.shape[:2]) != (shp.batch, shp.n_kv_heads):
+            raise ValueError("bidx must be [B, Hkv, kb]")
+        if out is None:
+            out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+        rc = self._lib.hylra_reuse_block_attn(self._h, ctypes.byref(shp), q.data_ptr(),
+                                              K.data_ptr(), V.data_ptr(), bidx.data_ptr(), block,
+                                              bidx.shape[2], out.data_ptr(), _stream_ptr(q.device))
+        self._check(rc, "hylra_reuse_block_attn")
+        return out
+
+    def prepare_step(self, policy: Sequence[int], q_l, K_l, V_l, k: int, scale: float = 0.0,
+                     block: int = 0):
         """Marshals the per-layer pointer arrays of hylra_decode_step once, so that a timed
         loop contains nothing but the C call.  Returns a zero-argument callable plus the
-        output tensors (outs, idx_buf)."""
+        output tensors (outs, idx_buf).  block > 0 selects hylra_decode_step_blocks, with k
+        counting blocks."""
         L = len(policy)
         for l in range(L):
             self._check_inputs(q_l[l], K_l[l], V_l[l])
@@ -192,16 +230,24 @@ class Context:
         keep = (q_l, K_l, V_l)
 
         def run():
-            rc = self._lib.hylra_decode_step(self._h, ctypes.byref(shp), L, pol, qa, Ka, Va, k, oa,
-                                             idx_buf.data_ptr(), _stream_ptr(dev))
-            self._check(rc, "hylra_decode_step")
+            if block > 0:
+                rc = self._lib.hylra_decode_step_blocks(self._h, ctypes.byref(shp), L, pol, qa, Ka, Va,
+                                                        block, k, oa, idx_buf.data_ptr(),
+                                                        _stream_ptr(dev))
+                self._check(rc, "hylra_decode_step_blocks")
+            else:
+                rc = self._lib.hylra_decode_step(self._h, ctypes.byref(shp), L, pol, qa, Ka, Va, k, oa,
+                                                 idx_buf.data_ptr(), _stream_ptr(dev))
+                self._check(rc, "hylra_decode_step")
             return keep is not None
 
         return run, outs, idx_buf
 
-    def decode_step(self, policy: Sequence[int], q_l, K_l, V_l, k: int, scale: float = 0.0):
-        """hylra_decode_step: returns (list of out per layer, idx of the last Full layer)."""
-        run, outs, idx_buf = self.prepare_step(policy, q_l, K_l, V_l, k, scale)
+    def decode_step(self, policy: Sequence[int], q_l, K_l, V_l, k: int, scale: float = 0.0,
+                    block: int = 0):
+        """hylra_decode_step (or _blocks when block > 0): returns (list of out per layer, idx of
+        the last Full layer)."""
+        run, outs, idx_buf = self.prepare_step(policy, q_l, K_l, V_l, k, scale, block)
         run()
         return outs, idx_buf
 

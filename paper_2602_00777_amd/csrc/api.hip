@@ -19,6 +19,8 @@ namespace {
 constexpr int kTargetBlocksFull = 512;    // workgroups the Full kernel aims for: two per CU,
                                           // all resident at once (measured best on MI355X)
 constexpr int64_t kMinSlots = 8192;       // partial slots ((batch, KV head, split) triples) kept
+constexpr int kMaxBlock = 65536;           // rows per block of the block-level variant
+constexpr int kMaxCtx = 1 << 30;
 constexpr float LOG2E_HOST = 1.4426950408889634f;
 
 thread_local char g_create_error[256] = "";
@@ -37,6 +39,7 @@ struct hylra_ctx {
     float* part_acc = nullptr;
     float* part_mm = nullptr;
     float* scores = nullptr;
+    float* bscores = nullptr;   // block scores of the block-level variant (blocks of >= 2 rows)
     int* counters = nullptr;    // one arrival counter per (batch, KV head), zero between launches
     int* row_ctr = nullptr;     // one row counter per (batch, KV head), zero between launches
     int* sel_ws = nullptr;      // selection scratch: histogram, candidates, counts (see SelectParams)
@@ -46,6 +49,7 @@ struct hylra_ctx {
     int64_t cap_acc = 0;        // floats
     int64_t cap_ml = 0;
     int64_t cap_scores = 0;
+    int64_t cap_bscores = 0;
 
     int32_t opt_full_split_rows = 0;
     int32_t opt_reuse_split_rows = 0;
@@ -103,6 +107,7 @@ hylra_status check_shape(const hylra_ctx* ctx, const hylra_shape* s, int& G, Str
     if (!s) return fail(ctx, HYLRA_ERR_BAD_ARG, "shape is NULL");
     if (s->batch < 1 || s->n_q_heads < 1 || s->n_kv_heads < 1 || s->ctx_len < 1)
         return fail(ctx, HYLRA_ERR_BAD_ARG, "batch, head counts and ctx_len must be >= 1");
+    if (s->ctx_len > kMaxCtx) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "ctx_len must be <= %d", kMaxCtx);
     if (s->n_q_heads % s->n_kv_heads != 0)
         return fail(ctx, HYLRA_ERR_BAD_ARG, "n_q_heads (%d) is not a multiple of n_kv_heads (%d)",
                     s->n_q_heads, s->n_kv_heads);
@@ -283,12 +288,14 @@ hylra_status hylra_create(hylra_ctx** out, const hylra_shape* max_shape, int32_t
     ctx->cap_acc = ctx->slots * G * max_shape->head_dim;
     ctx->cap_ml = ctx->slots * G * 2;
     ctx->cap_scores = pairs * round_up(max_shape->ctx_len, 4);
+    ctx->cap_bscores = pairs * round_up(ceil_div(max_shape->ctx_len, 2), 4);
 
     DeviceGuard guard(device);
     hipError_t e = hipMalloc((void**)&ctx->part_acc, ctx->cap_acc * sizeof(float));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->part_ml, ctx->cap_ml * sizeof(float));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->part_mm, ctx->slots * 2 * sizeof(float));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->scores, ctx->cap_scores * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->bscores, ctx->cap_bscores * sizeof(float));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->counters, ctx->slots * sizeof(int));
     if (e == hipSuccess) e = hipMemset(ctx->counters, 0, ctx->slots * sizeof(int));
     ctx->pairs_cap = pairs;
@@ -320,6 +327,7 @@ hylra_status hylra_destroy(hylra_ctx* ctx) {
     if (ctx->part_ml) (void)hipFree(ctx->part_ml);
     if (ctx->part_mm) (void)hipFree(ctx->part_mm);
     if (ctx->scores) (void)hipFree(ctx->scores);
+    if (ctx->bscores) (void)hipFree(ctx->bscores);
     if (ctx->counters) (void)hipFree(ctx->counters);
     if (ctx->row_ctr) (void)hipFree(ctx->row_ctr);
     if (ctx->sel_ws) (void)hipFree(ctx->sel_ws);
@@ -345,9 +353,15 @@ hylra_status hylra_set_option(hylra_ctx* ctx, const char* name, int32_t value) {
     return HYLRA_OK;
 }
 
-hylra_status hylra_full_attn_topk(hylra_ctx* ctx, const hylra_shape* shape, const void* q,
-                                  const void* K, const void* V, int32_t k, float* out,
-                                  int32_t* idx, void* hip_stream) {
+}  // extern "C"
+
+namespace {
+
+// Full layer.  block == 1: idx receives the k best rows.  block >= 2: idx receives the k best
+// blocks of `block` rows (a block scores the maximum of its rows).
+hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const void* q, const void* K,
+                       const void* V, int32_t block, int32_t k, float* out, int32_t* idx,
+                       void* hip_stream) {
     int G = 0;
     Strides sd{};
     float scale = 0.f;
@@ -355,8 +369,13 @@ hylra_status hylra_full_attn_topk(hylra_ctx* ctx, const hylra_shape* shape, cons
     if (rc != HYLRA_OK) return rc;
     if ((rc = check_tensors(ctx, q, K, V, out)) != HYLRA_OK) return rc;
     if (!idx || ((uintptr_t)idx & 3)) return fail(ctx, HYLRA_ERR_BAD_ARG, "idx must be a 4-byte aligned device pointer");
-    if (k < 1 || k > shape->ctx_len) return fail(ctx, HYLRA_ERR_BAD_ARG, "k = %d is outside 1..ctx_len (%d)", k, shape->ctx_len);
-    if (k > ctx->max_k) return fail(ctx, HYLRA_ERR_WORKSPACE, "k = %d exceeds the context's max_k = %d", k, ctx->max_k);
+    if (block < 1 || block > kMaxBlock) return fail(ctx, HYLRA_ERR_BAD_ARG, "block = %d is outside 1..%d", block, kMaxBlock);
+    // what TopK ranks: rows, or blocks of rows
+    const int n_sel = (int)ceil_div(shape->ctx_len, block);
+    if (k < 1 || k > n_sel)
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "k = %d is outside 1..%d (%s)", k, n_sel, block == 1 ? "ctx_len" : "number of blocks");
+    if ((int64_t)k * block > round_up(ctx->max_k, block))
+        return fail(ctx, HYLRA_ERR_WORKSPACE, "k = %d (x block %d) exceeds the context's max_k = %d", k, block, ctx->max_k);
     FullPlan pl{};
     if ((rc = plan_full(ctx, shape, G, pl)) != HYLRA_OK) return rc;
     if ((rc = check_workspace(ctx, shape, pl.n_splits, true)) != HYLRA_OK) return rc;
@@ -381,23 +400,38 @@ hylra_status hylra_full_attn_topk(hylra_ctx* ctx, const hylra_shape* shape, cons
             }));
 
     const int64_t pairs = (int64_t)shape->batch * shape->n_kv_heads;
+    const float* sel_scores = ctx->scores;
+    int64_t sel_stride = fp.score_stride;
+    if (block > 1) {
+        BlockMaxParams bp{};
+        bp.scores = ctx->scores, bp.score_stride = fp.score_stride;
+        bp.bscores = ctx->bscores, bp.bscore_stride = round_up(n_sel, 4);
+        bp.N = shape->ctx_len, bp.block = block, bp.n_blocks = n_sel;
+        if (pairs * bp.bscore_stride > ctx->cap_bscores)
+            return fail(ctx, HYLRA_ERR_WORKSPACE, "shape needs %lld block-score floats, workspace holds %lld",
+                        (long long)(pairs * bp.bscore_stride), (long long)ctx->cap_bscores);
+        HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_block_max(bp, shape->batch, shape->n_kv_heads, st); }));
+        sel_scores = ctx->bscores;
+        sel_stride = bp.bscore_stride;
+    }
     // One workgroup per (batch, KV head) keeps up to 32768 scores in registers and needs a
     // single launch; beyond that the three-launch, several-workgroups form is faster.
+    // (The score range the streaming kernel recorded also bounds the block maxima.)
     const bool multi = ctx->opt_finalize_variant == 3 ||
-                       (ctx->opt_finalize_variant == 0 && shape->ctx_len > 32768);
+                       (ctx->opt_finalize_variant == 0 && n_sel > 32768);
     if (multi) {
         // finalise spread over several workgroups per (batch, KV head): three launches
         int E = 2;
-        if (pairs * ceil_div(shape->ctx_len, select_chunk_rows(2)) > 4096) E = 8;
+        if (pairs * ceil_div(n_sel, select_chunk_rows(2)) > 4096) E = 8;
         if (ctx->opt_finalize_groups) E = ctx->opt_finalize_groups;
-        const int64_t chunks = ceil_div(shape->ctx_len, select_chunk_rows(E));
+        const int64_t chunks = ceil_div(n_sel, select_chunk_rows(E));
         if (pairs > ctx->pairs_cap || chunks > ctx->max_chunks)
             return fail(ctx, HYLRA_ERR_WORKSPACE, "batch*n_kv_heads = %lld or ctx_len = %d exceeds the selection workspace", (long long)pairs, shape->ctx_len);
         SelectParams sp{};
         sp.part_ml = ctx->part_ml, sp.part_acc = ctx->part_acc, sp.part_mm = ctx->part_mm;
-        sp.scores = ctx->scores, sp.score_stride = fp.score_stride;
+        sp.scores = sel_scores, sp.score_stride = sel_stride;
         sp.n_splits = pl.n_splits, sp.Hq = shape->n_q_heads, sp.Hkv = shape->n_kv_heads;
-        sp.G = G, sp.D = shape->head_dim, sp.N = shape->ctx_len, sp.k = k;
+        sp.G = G, sp.D = shape->head_dim, sp.N = n_sel, sp.k = k;
         sp.out = out, sp.idx = idx, sp.row_ctr = ctx->row_ctr;
         int* w = ctx->sel_ws;
         sp.ghist = w, w += ctx->pairs_cap * 4096;
@@ -413,9 +447,9 @@ hylra_status hylra_full_attn_topk(hylra_ctx* ctx, const hylra_shape* shape, cons
     }
     FinalizeParams zp{};
     zp.part_ml = ctx->part_ml, zp.part_acc = ctx->part_acc, zp.part_mm = ctx->part_mm;
-    zp.scores = ctx->scores, zp.score_stride = fp.score_stride;
+    zp.scores = sel_scores, zp.score_stride = sel_stride;
     zp.n_splits = pl.n_splits, zp.Hq = shape->n_q_heads, zp.Hkv = shape->n_kv_heads;
-    zp.G = G, zp.D = shape->head_dim, zp.N = shape->ctx_len, zp.k = k;
+    zp.G = G, zp.D = shape->head_dim, zp.N = n_sel, zp.k = k;
     zp.variant = ctx->opt_finalize_variant == 2 ? 1 : 0;
     zp.row_ctr = ctx->row_ctr;
     zp.out = out, zp.idx = idx;
@@ -423,9 +457,10 @@ hylra_status hylra_full_attn_topk(hylra_ctx* ctx, const hylra_shape* shape, cons
     return HYLRA_OK;
 }
 
-hylra_status hylra_reuse_sparse_attn(hylra_ctx* ctx, const hylra_shape* shape, const void* q,
-                                     const void* K, const void* V, const int32_t* idx, int32_t k,
-                                     float* out, void* hip_stream) {
+// Reuse layer over n_idx inherited entries per (batch, KV head): rows (block == 1) or blocks.
+hylra_status reuse_impl(hylra_ctx* ctx, const hylra_shape* shape, const void* q, const void* K,
+                        const void* V, const int32_t* idx, int32_t block, int32_t n_idx, float* out,
+                        void* hip_stream) {
     int G = 0;
     Strides sd{};
     float scale = 0.f;
@@ -433,8 +468,11 @@ hylra_status hylra_reuse_sparse_attn(hylra_ctx* ctx, const hylra_shape* shape, c
     if (rc != HYLRA_OK) return rc;
     if ((rc = check_tensors(ctx, q, K, V, out)) != HYLRA_OK) return rc;
     if (!idx || ((uintptr_t)idx & 3)) return fail(ctx, HYLRA_ERR_BAD_ARG, "idx must be a 4-byte aligned device pointer");
-    if (k < 1) return fail(ctx, HYLRA_ERR_BAD_ARG, "k = %d must be >= 1", k);
-    if (k > ctx->max_k) return fail(ctx, HYLRA_ERR_WORKSPACE, "k = %d exceeds the context's max_k = %d", k, ctx->max_k);
+    if (block < 1 || block > kMaxBlock) return fail(ctx, HYLRA_ERR_BAD_ARG, "block = %d is outside 1..%d", block, kMaxBlock);
+    if (n_idx < 1) return fail(ctx, HYLRA_ERR_BAD_ARG, "k = %d must be >= 1", n_idx);
+    if ((int64_t)n_idx * block > round_up(ctx->max_k, block))
+        return fail(ctx, HYLRA_ERR_WORKSPACE, "k = %d (x block %d) exceeds the context's max_k = %d", n_idx, block, ctx->max_k);
+    const int k = n_idx * block;            // row slots; fits: max_k <= ctx_len < 2^31 - block is checked at create
     ReusePlan pl{};
     if ((rc = plan_reuse(ctx, shape, G, k, pl)) != HYLRA_OK) return rc;
     if ((rc = check_workspace(ctx, shape, pl.n_splits, false)) != HYLRA_OK) return rc;
@@ -450,6 +488,9 @@ hylra_status hylra_reuse_sparse_attn(hylra_ctx* ctx, const hylra_shape* shape, c
     rp.rows_per_split = pl.rows_per_split, rp.n_splits = pl.n_splits;
     rp.scale_log2 = scale * LOG2E_HOST;
     rp.idx = idx;
+    rp.idx_stride = n_idx, rp.block = block;
+    rp.block_magic = block > 1 ? (uint32_t)((0x100000000ull + (uint32_t)block - 1) / (uint32_t)block) : 0u;
+    rp.n_blocks = (int)ceil_div(shape->ctx_len, block);
     rp.part_ml = ctx->part_ml, rp.part_acc = ctx->part_acc;
     const bool fused = ctx->opt_reuse_unfused == 0;
     rp.counters = fused ? ctx->counters : nullptr;
@@ -469,10 +510,11 @@ hylra_status hylra_reuse_sparse_attn(hylra_ctx* ctx, const hylra_shape* shape, c
     return HYLRA_OK;
 }
 
-hylra_status hylra_decode_step(hylra_ctx* ctx, const hylra_shape* shape, int32_t n_layers,
-                               const uint8_t* policy, const void* const* q_l,
-                               const void* const* K_l, const void* const* V_l, int32_t k,
-                               float* const* out_l, int32_t* idx_buf, void* hip_stream) {
+// Algorithm 2 over the layers of one decode step; block == 1 is the token-level form.
+hylra_status step_impl(hylra_ctx* ctx, const hylra_shape* shape, int32_t n_layers,
+                       const uint8_t* policy, const void* const* q_l, const void* const* K_l,
+                       const void* const* V_l, int32_t block, int32_t k, float* const* out_l,
+                       int32_t* idx_buf, void* hip_stream) {
     if (!ctx) return HYLRA_ERR_BAD_ARG;
     if (n_layers < 1 || !policy || !q_l || !K_l || !V_l || !out_l || !idx_buf)
         return fail(ctx, HYLRA_ERR_BAD_ARG, "n_layers < 1 or a NULL argument");
@@ -489,11 +531,54 @@ hylra_status hylra_decode_step(hylra_ctx* ctx, const hylra_shape* shape, int32_t
     for (int l = 0; l < n_layers; ++l) {
         hylra_status rc =
             policy[l] == HYLRA_FULL
-                ? hylra_full_attn_topk(ctx, shape, q_l[l], K_l[l], V_l[l], k, out_l[l], idx_buf, hip_stream)
-                : hylra_reuse_sparse_attn(ctx, shape, q_l[l], K_l[l], V_l[l], idx_buf, k, out_l[l], hip_stream);
+                ? full_impl(ctx, shape, q_l[l], K_l[l], V_l[l], block, k, out_l[l], idx_buf, hip_stream)
+                : reuse_impl(ctx, shape, q_l[l], K_l[l], V_l[l], idx_buf, block, k, out_l[l], hip_stream);
         if (rc != HYLRA_OK) return rc;
     }
     return HYLRA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+hylra_status hylra_full_attn_topk(hylra_ctx* ctx, const hylra_shape* shape, const void* q,
+                                  const void* K, const void* V, int32_t k, float* out,
+                                  int32_t* idx, void* hip_stream) {
+    return full_impl(ctx, shape, q, K, V, 1, k, out, idx, hip_stream);
+}
+
+hylra_status hylra_reuse_sparse_attn(hylra_ctx* ctx, const hylra_shape* shape, const void* q,
+                                     const void* K, const void* V, const int32_t* idx, int32_t k,
+                                     float* out, void* hip_stream) {
+    return reuse_impl(ctx, shape, q, K, V, idx, 1, k, out, hip_stream);
+}
+
+hylra_status hylra_decode_step(hylra_ctx* ctx, const hylra_shape* shape, int32_t n_layers,
+                               const uint8_t* policy, const void* const* q_l,
+                               const void* const* K_l, const void* const* V_l, int32_t k,
+                               float* const* out_l, int32_t* idx_buf, void* hip_stream) {
+    return step_impl(ctx, shape, n_layers, policy, q_l, K_l, V_l, 1, k, out_l, idx_buf, hip_stream);
+}
+
+hylra_status hylra_full_attn_topk_blocks(hylra_ctx* ctx, const hylra_shape* shape, const void* q,
+                                         const void* K, const void* V, int32_t block, int32_t kb,
+                                         float* out, int32_t* bidx, void* hip_stream) {
+    return full_impl(ctx, shape, q, K, V, block, kb, out, bidx, hip_stream);
+}
+
+hylra_status hylra_reuse_block_attn(hylra_ctx* ctx, const hylra_shape* shape, const void* q,
+                                    const void* K, const void* V, const int32_t* bidx,
+                                    int32_t block, int32_t kb, float* out, void* hip_stream) {
+    return reuse_impl(ctx, shape, q, K, V, bidx, block, kb, out, hip_stream);
+}
+
+hylra_status hylra_decode_step_blocks(hylra_ctx* ctx, const hylra_shape* shape, int32_t n_layers,
+                                      const uint8_t* policy, const void* const* q_l,
+                                      const void* const* K_l, const void* const* V_l, int32_t block,
+                                      int32_t kb, float* const* out_l, int32_t* bidx_buf,
+                                      void* hip_stream) {
+    return step_impl(ctx, shape, n_layers, policy, q_l, K_l, V_l, block, kb, out_l, bidx_buf, hip_stream);
 }
 
 hylra_status hylra_profile_enable(hylra_ctx* ctx, int32_t on) {

@@ -435,6 +435,38 @@ hipError_t launch_full_finalize(const FinalizeParams& p, int B, hipStream_t st) 
     return hipGetLastError();
 }
 
+// ---- block-level TopK: score of a block = maximum of its rows' group-mean scores ----
+// A group of L lanes (L = largest power of two <= min(64, block)) reduces one block; a
+// workgroup of 256 threads covers 256 / L blocks per sweep.
+constexpr int kBlockMaxThreads = 256;
+constexpr int kBlockMaxSweeps = 4;
+
+__global__ __launch_bounds__(kBlockMaxThreads) void block_max_kernel(BlockMaxParams p, int L) {
+    const int64_t pair = (int64_t)blockIdx.z * gridDim.y + blockIdx.y;
+    const float* __restrict__ sc = p.scores + pair * p.score_stride;
+    float* __restrict__ dst = p.bscores + pair * p.bscore_stride;
+    const int sub = threadIdx.x & (L - 1), grp = threadIdx.x / L, groups = kBlockMaxThreads / L;
+    for (int s = 0; s < kBlockMaxSweeps; ++s) {
+        const int c = (blockIdx.x * kBlockMaxSweeps + s) * groups + grp;     // uniform per lane group
+        float m = -3.0e38f;
+        if (c < p.n_blocks) {
+            const int lo = c * p.block, hi = min(p.N, lo + p.block);
+            for (int j = lo + sub; j < hi; j += L) m = fmaxf(m, sc[j]);
+        }
+        for (int mask = 1; mask < L; mask <<= 1) m = fmaxf(m, __shfl_xor(m, mask, 64));
+        if (c < p.n_blocks && sub == 0) dst[c] = m;
+    }
+}
+
+hipError_t launch_block_max(const BlockMaxParams& p, int B, int Hkv, hipStream_t st) {
+    int L = 1;
+    while (2 * L <= 64 && 2 * L <= p.block) L *= 2;
+    const int per_wg = kBlockMaxSweeps * (kBlockMaxThreads / L);
+    const dim3 grid((p.n_blocks + per_wg - 1) / per_wg, Hkv, B);
+    hipLaunchKernelGGL(block_max_kernel, grid, dim3(kBlockMaxThreads), 0, st, p, L);
+    return hipGetLastError();
+}
+
 // ---- Reuse layer: merge of the split partials, one workgroup per query head ----
 __global__ __launch_bounds__(128) void combine_kernel(CombineParams p) {
     const int64_t head = blockIdx.x;

@@ -64,15 +64,28 @@ struct ReuseParams {
     const uint16_t* K;
     const uint16_t* V;
     int64_t sb, sh, sn;
-    int Hq, Hkv, N, k;
+    int Hq, Hkv, N, k;              // k = row slots per (batch, KV head) = idx_stride * block
     int rows_per_split, n_splits;
     float scale_log2;
-    const int32_t* idx;             // [B][Hkv][k]
+    const int32_t* idx;             // [B][Hkv][idx_stride]: rows (block == 1) or block numbers
+    int idx_stride;                 // entries of idx per (batch, KV head): k / block
+    int block;                      // tokens per block; 1 = idx names rows directly
+    uint32_t block_magic;           // ceil(2^32 / block), for the division by block
+    int n_blocks;                   // ceil(N / block)
     float* part_ml;                 // [B*Hq][S][2]
     float* part_acc;                // [B*Hq][S][D]
     int* counters;                  // [B*Hkv] arrival counters, all zero between launches;
                                     // nullptr: do not merge in this kernel
     float* out;                     // [B][Hq][D], written by the merging workgroup
+};
+
+// Block-level TopK: scores of blocks of `block` consecutive rows = maximum of the rows' scores.
+struct BlockMaxParams {
+    const float* scores;            // [B*Hkv][score_stride] row scores
+    int64_t score_stride;
+    float* bscores;                 // [B*Hkv][bscore_stride] block scores
+    int64_t bscore_stride;
+    int N, block, n_blocks;
 };
 
 struct CombineParams {
@@ -124,6 +137,7 @@ hipError_t launch_full_finalize(const FinalizeParams& p, int B, hipStream_t st);
 // step 0, 1, 2 = histogram, classify, emit; E = float4 groups per thread (2 or 8)
 int select_chunk_rows(int E);
 hipError_t launch_select(const SelectParams& p, int B, int E, int step, hipStream_t st);
+hipError_t launch_block_max(const BlockMaxParams& p, int B, int Hkv, hipStream_t st);
 hipError_t launch_combine(const CombineParams& p, int n_heads_total, hipStream_t st);
 hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t st);

@@ -31,7 +31,7 @@ __global__ __launch_bounds__(256) void reuse_attn_split_kernel(ReuseParams p) {
     const int i0 = split * p.rows_per_split;
     const int i1 = min(p.k, i0 + p.rows_per_split);
     const int64_t pair = (int64_t)b * p.Hkv + g;
-    const int32_t* __restrict__ ib = p.idx + pair * p.k;
+    const int32_t* __restrict__ ib = p.idx + pair * p.idx_stride;
     const uint16_t* __restrict__ Kb = p.K + (int64_t)b * p.sb + (int64_t)g * p.sh;
     const uint16_t* __restrict__ Vb = p.V + (int64_t)b * p.sb + (int64_t)g * p.sh;
 
@@ -42,7 +42,7 @@ __global__ __launch_bounds__(256) void reuse_attn_split_kernel(ReuseParams p) {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
         const int pos = t0 + r * GEO::RPG + slot;
-        row[r] = pos < i1 ? ib[pos] : -1;
+        row[r] = pos < i1 ? reuse_row(p, ib, pos) : -1;
     }
     uint4 qv[G][CH];
     load_q<GEO>(qv, p.q + ((int64_t)b * p.Hq + (int64_t)g * G) * D, chunk);
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void reuse_attn_split_kernel(ReuseParams p) {
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const int pos = t0 + r * GEO::RPG + slot;
-                row[r] = pos < i1 ? ib[pos] : -1;
+                row[r] = pos < i1 ? reuse_row(p, ib, pos) : -1;
             }
         }
 #pragma unroll

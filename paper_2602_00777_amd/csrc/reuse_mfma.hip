@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void r
     const int i1 = min(p.k, i0 + p.rows_per_split);
     const int64_t pair = (int64_t)b * p.Hkv + g;
     const int64_t head0 = (int64_t)b * p.Hq + (int64_t)g * G;
-    const int32_t* __restrict__ ib = p.idx + pair * p.k;
+    const int32_t* __restrict__ ib = p.idx + pair * p.idx_stride;
     const uint16_t* __restrict__ Kb = p.K + (int64_t)b * p.sb + (int64_t)g * p.sh;
     const uint16_t* __restrict__ Vb = p.V + (int64_t)b * p.sb + (int64_t)g * p.sh;
 
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void r
 #pragma unroll
     for (int blk = 0; blk < NB; ++blk) {
         const int pos = t0 + 16 * blk + n;
-        row[blk] = pos < i1 ? ib[pos] : -1;
+        row[blk] = pos < i1 ? reuse_row(p, ib, pos) : -1;
     }
     uint4 qb[KI], sel[2];
     mfma_load_q<D, G>(qb, p.q + head0 * D, n, gq);
@@ -81,7 +81,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void r
 #pragma unroll
             for (int blk = 0; blk < NB; ++blk) {
                 const int pos = t0 + 16 * blk + n;
-                row[blk] = pos < i1 ? ib[pos] : -1;
+                row[blk] = pos < i1 ? reuse_row(p, ib, pos) : -1;
             }
         }
 #pragma unroll

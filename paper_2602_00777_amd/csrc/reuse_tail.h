@@ -9,6 +9,19 @@
 
 namespace hylra {
 
+// Cache row behind slot `pos` of a (batch, KV head)'s selection.  Token level: the entry
+// itself.  Block level (paper, block-level sparsity): slot pos is row pos % block of the
+// block named by entry pos / block; the quotient comes from a multiply-high with
+// ceil(2^32 / block), which is at most one too large for pos < 2^31.  Anything that is not a
+// row of the cache comes back negative or >= N and is skipped by the caller.
+DEVI int reuse_row(const ReuseParams& p, const int32_t* __restrict__ ib, int pos) {
+    if (p.block == 1) return ib[pos];
+    int t = (int)__umulhi((uint32_t)pos, p.block_magic);
+    if (t * p.block > pos) --t;
+    const int c = ib[t];
+    return (unsigned)c < (unsigned)p.n_blocks ? c * p.block + (pos - t * p.block) : -1;
+}
+
 // Every thread of the workgroup (NT threads) calls this after its partial stores were issued.
 template <int G, int D, int NT>
 DEVI void reuse_merge_tail(const ReuseParams& p, int64_t pair, int64_t head0, int* s_last) {

@@ -371,3 +371,35 @@ def test_error_codes():
     with pytest.raises(binding.HylraError) as e:
         binding.Context(1, 18, 2, 128, 128, 8)            # group of 9
     assert e.value.status == 2
+
+
+def test_profile_and_probe_aids():
+    """Event-based kernel timing and the two measurement kernels of the C ABI."""
+    say("profile / probe")
+    B, Hkv, G, d, N, k = 1, 2, 4, 128, 4096, 256
+    q, K, V = rand_case(21, B, Hkv, G, d, N)
+    with binding.Context(B, Hkv * G, Hkv, d, N, k) as ctx:
+        ctx.profile_enable(True)
+        ctx.profile_reset()
+        out, idx = ctx.full_attn_topk(q, K, V, k)
+        for _ in range(3):
+            ctx.reuse_sparse_attn(q, K, V, idx)
+        torch.cuda.synchronize()
+        prof = ctx.profile_read()
+        assert prof["full_attn"][0] == 1 and prof["full_finalize"][0] == 1
+        assert prof["reuse_attn"][0] == 3 and prof["reuse_combine"][0] == 0
+        for name in ("full_attn", "full_finalize", "reuse_attn"):
+            assert 0.0 < prof[name][1] < 50.0          # milliseconds
+        ctx.profile_reset()
+        assert ctx.profile_read()["full_attn"] == (0, 0.0)
+        src = torch.randint(0, 255, (1 << 20,), dtype=torch.uint8, device=DEV)
+        dst = torch.zeros_like(src)
+        sink = torch.zeros(16384, dtype=torch.uint8, device=DEV)
+        ctx.probe_copy(dst, src)
+        ctx.probe_read(src, sink)
+        torch.cuda.synchronize()
+        assert torch.equal(dst, src)
+        assert ctx.profile_read()["probe"][0] == 2
+        ctx.profile_enable(False)
+        with pytest.raises(binding.HylraError):
+            ctx.set_option("no_such_option", 1)
