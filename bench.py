@@ -41,6 +41,8 @@ def main():
     ap.add_argument("--workload", default="llama3_8b_32k")
     ap.add_argument("--policy", default="hylra", choices=["hylra", "full", "jump3"],
                     help="hylra = the workload's policy; full = every layer Full; jump3 = Full every 3rd layer")
+    ap.add_argument("--block", type=int, default=0,
+                    help="block-level variant: rows per block (TopK keeps top_k / block blocks); 0 = token level")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--probe", action="store_true", help="also time the plain copy / read kernels")
     ap.add_argument("--opt", action="append", default=[], help="library option name=value")
@@ -85,7 +87,11 @@ def main():
     for o in args.opt:
         name, val = o.split("=")
         ctx.set_option(name, int(val))
-    run, outs, idx_buf = ctx.prepare_step(policy, qs, Ks, Vs, w.top_k)
+    if args.block < 0 or (args.block and w.top_k % args.block):
+        print("bench.py: --block must divide the workload's top_k (%d)" % w.top_k, file=sys.stderr)
+        sys.exit(2)
+    k_sel = w.top_k // args.block if args.block else w.top_k
+    run, outs, idx_buf = ctx.prepare_step(policy, qs, Ks, Vs, k_sel, block=args.block)
 
     for _ in range(args.warmup):
         run()
@@ -112,7 +118,7 @@ def main():
                for name, (n, ms) in prof.items() if n}
 
     B, Hq, Hkv, d, N, k = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ctx_len, w.top_k
-    small = B * Hq * d * 2 + B * Hq * d * 4 + B * Hkv * k * 4         # q + out + idx
+    small = B * Hq * d * 2 + B * Hq * d * 4 + B * Hkv * k_sel * 4     # q + out + idx
     full_bytes = 4 * B * Hkv * N * d + small
     reuse_bytes = 4 * B * Hkv * k * d + small
 
@@ -155,7 +161,7 @@ def main():
 
     cpu = None
     if not args.no_cpu_baseline:
-        cpu = cpu_baseline(w, policy, qs, Ks, Vs, idx_buf, n_full, n_reuse)
+        cpu = cpu_baseline(w, policy, qs, Ks, Vs, n_full, n_reuse, args.block)
 
     line = {
         "metric": "decode-attention tokens/sec (all layers) at 32K ctx" if w.ctx_len == 32768
@@ -167,7 +173,7 @@ def main():
         "config": {"workload": w.name, "description": w.description, "policy": args.policy,
                    "n_layers": w.n_layers, "full_layers": n_full, "reuse_layers": n_reuse,
                    "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d, "ctx_len": N,
-                   "top_k": k, "kv_dtype": "bf16", "accumulate": "f32"},
+                   "top_k": k, "block": args.block or 1, "kv_dtype": "bf16", "accumulate": "f32"},
         "roofline": roofline,
         "roofline_other": other,
         "kernels_us": {n: round(v["avg_us"], 2) for n, v in kernels.items()},
@@ -179,7 +185,7 @@ def main():
     print(json.dumps(line), flush=True)
 
 
-def cpu_baseline(w, policy, qs, Ks, Vs, idx_buf, n_full, n_reuse):
+def cpu_baseline(w, policy, qs, Ks, Vs, n_full, n_reuse, block=0):
     """The oracle as it stands, on the host cores, on a bounded sample of the same workload:
     the first Full layers and the first Reuse layers of the step (up to 3 each, up to 8
     sequences of the batch), in policy order with the oracle's own index sets; the step time
@@ -196,10 +202,16 @@ def cpu_baseline(w, policy, qs, Ks, Vs, idx_buf, n_full, n_reuse):
         q, K, V = qs[l][:nb].cpu(), Ks[l][:nb].cpu(), Vs[l][:nb].cpu()
         t0 = time.perf_counter()
         if is_full:
-            _, idx, _ = oracle.full_attn_topk(q, K, V, w.top_k)
+            if block:
+                _, idx, _ = oracle.full_attn_topk_blocks(q, K, V, block, w.top_k // block)
+            else:
+                _, idx, _ = oracle.full_attn_topk(q, K, V, w.top_k)
             t_full.append(time.perf_counter() - t0)
         else:
-            oracle.reuse_sparse_attn(q, K, V, idx)
+            if block:
+                oracle.reuse_block_attn(q, K, V, idx, block)
+            else:
+                oracle.reuse_sparse_attn(q, K, V, idx)
             t_reuse.append(time.perf_counter() - t0)
         if len(t_full) >= 3 and (len(t_reuse) >= 3 or n_reuse == 0):
             break

@@ -58,3 +58,40 @@ def test_full_size_full_then_reuse(name):
     # the planted positions are what the selection finds (statistical sanity of the workload)
     hit = np.mean([np.isin(planted[full_l][b, g], idx_h[b, g]).mean() for (b, g) in sample_pairs(w.batch, w.n_kv_heads)])
     assert hit > 0.6, hit
+
+
+@pytest.mark.parametrize("name,block", [("llama3_8b_32k", 128), ("long_131k", 16), ("long_131k", 2)])
+def test_full_size_block_variant(name, block):
+    """The block-level variant at full shape: block TopK then block reuse, sampled pairs."""
+    print("[case] full size blocks %s block=%d" % (name, block), flush=True)
+    w = synth.WORKLOADS[name]
+    full_l = int(np.flatnonzero(w.policy() == synth.FULL)[0])
+    reuse_l = int(np.flatnonzero(w.policy() == synth.REUSE)[0])
+    planted = synth.planted_positions(synth.scaled(w, n_layers=reuse_l + 1))
+    G, d, N, kb = w.group, w.head_dim, w.ctx_len, w.top_k // block
+    nblk = -(-N // block)
+    with binding.Context(w.batch, w.n_q_heads, w.n_kv_heads, d, N, w.top_k) as ctx:
+        q, K, V = synth.make_layer(w, full_l, planted[full_l], DEV)
+        out, bidx = ctx.full_attn_topk_blocks(q, K, V, block, kb)
+        torch.cuda.synchronize()
+        out_h, bidx_h = out.cpu().numpy(), bidx.cpu().numpy()
+        assert np.all(np.isfinite(out_h))
+        assert bidx_h.min() >= 0 and bidx_h.max() < nblk
+        assert np.all(np.diff(bidx_h.astype(np.int64), axis=-1) > 0)
+        for (b, g) in sample_pairs(w.batch, w.n_kv_heads):
+            qs = q[b:b + 1, g * G:(g + 1) * G].cpu()
+            Ks, Vs = K[b:b + 1, g:g + 1].cpu(), V[b:b + 1, g:g + 1].cpu()
+            ref_out, ref_bidx, bs = oracle.full_attn_topk_blocks(qs, Ks, Vs, block, kb, want_bscore=True)
+            assert_out_close(out_h[b:b + 1, g * G:(g + 1) * G], ref_out, "%s full out (%d,%d)" % (name, b, g))
+            assert_idx_valid(bidx_h[b:b + 1, g:g + 1], bs, kb, "%s bidx (%d,%d)" % (name, b, g), exact_ref=ref_bidx)
+        del q, K, V
+        q, K, V = synth.make_layer(w, reuse_l, planted[reuse_l], DEV)
+        out2 = ctx.reuse_block_attn(q, K, V, bidx, block)
+        torch.cuda.synchronize()
+        out2_h = out2.cpu().numpy()
+        assert np.all(np.isfinite(out2_h))
+        for (b, g) in sample_pairs(w.batch, w.n_kv_heads):
+            qs = q[b:b + 1, g * G:(g + 1) * G].cpu()
+            Ks, Vs = K[b:b + 1, g:g + 1].cpu(), V[b:b + 1, g:g + 1].cpu()
+            ref = oracle.reuse_block_attn(qs, Ks, Vs, bidx_h[b:b + 1, g:g + 1], block)
+            assert_out_close(out2_h[b:b + 1, g * G:(g + 1) * G], ref, "%s reuse out (%d,%d)" % (name, b, g))
