@@ -158,12 +158,12 @@ hylra_status hylra_decode_step_blocks(hylra_ctx *ctx, const hylra_shape *shape, 
 /*
  * Tuning knobs (HOST call, takes effect for later launches).  Unknown names give
  * HYLRA_ERR_BAD_ARG; 0 always means "automatic / default".  Names:
- *   "full_split_rows"   rows of the cache per workgroup of the Full kernel
+ *   "full_split_rows"   rows of the cache per workgroup of the Full kernel (the vector-ALU
+ *                       kernels take at most 8192 and clamp larger values)
  *   "reuse_split_rows"  index entries per workgroup of the Reuse kernel
  *   "full_variant"      Full streaming kernel.  Vector-ALU kernels, 10*mode + unroll: 4 (plain
  *                       loads), 14 (streaming loads), 23 (streaming loads, two-deep register
- *                       pipeline; default up to 4 heads per KV head), 34 / 32 (rows claimed
- *                       dynamically through a shared counter).  Matrix-core kernels: 54, 52
+ *                       pipeline; default up to 4 heads per KV head).  Matrix-core kernels: 54, 52
  *                       (default from 5 heads per KV head), 62, 61 (pipelined)
  *   "reuse_variant"     Reuse gather kernel: 1 / 2 = vector-ALU kernel with streaming / plain
  *                       loads, 3 / 4 = matrix-core kernel with streaming / plain loads (default 4)

@@ -41,7 +41,6 @@ struct hylra_ctx {
     float* scores = nullptr;
     float* bscores = nullptr;   // block scores of the block-level variant (blocks of >= 2 rows)
     int* counters = nullptr;    // one arrival counter per (batch, KV head), zero between launches
-    int* row_ctr = nullptr;     // one row counter per (batch, KV head), zero between launches
     int* sel_ws = nullptr;      // selection scratch: histogram, candidates, counts (see SelectParams)
     int64_t pairs_cap = 0;      // (batch, KV head) pairs the selection scratch is sized for
     int max_chunks = 0;         // chunks of 8192 rows per (batch, KV head) at the maximum context
@@ -54,6 +53,7 @@ struct hylra_ctx {
     int32_t opt_full_split_rows = 0;
     int32_t opt_reuse_split_rows = 0;
     int32_t opt_full_variant = 0;
+    int32_t opt_full_split_rot = 0;
     int32_t opt_reuse_variant = 0;
     int32_t opt_reuse_unroll = 0;
     int32_t opt_reuse_unfused = 0;
@@ -178,12 +178,18 @@ hylra_status plan_full(const hylra_ctx* ctx, const hylra_shape* s, int G, FullPl
     int64_t rps = ctx->opt_full_split_rows > 0 ? ctx->opt_full_split_rows
                                                : ceil_div(pairs * s->ctx_len, kTargetBlocksFull);
     rps = round_up(rps < quantum ? quantum : rps, quantum);
+    // the vector kernel stages the scores of its split in LDS
+    const int64_t rps_cap = pl.variant < 50 ? kMaxFullSplitRows / quantum * quantum : (int64_t)1 << 40;
+    if (rps > rps_cap) rps = rps_cap;
     int64_t S = ceil_div(s->ctx_len, rps);
-    while (S > kMaxSplits || pairs * S > ctx->slots) {
+    while ((S > kMaxSplits || pairs * S > ctx->slots) && rps < rps_cap) {
         rps = round_up(rps * 2, quantum);
+        if (rps > rps_cap) rps = rps_cap;
         S = ceil_div(s->ctx_len, rps);
         if (S == 1) break;
     }
+    if (S > kMaxSplits)
+        return fail(ctx, HYLRA_ERR_UNSUPPORTED, "ctx_len = %d needs %lld splits per KV head, at most %d are supported", s->ctx_len, (long long)S, kMaxSplits);
     if (pairs * S > ctx->slots)
         return fail(ctx, HYLRA_ERR_WORKSPACE, "batch*n_kv_heads = %lld exceeds the workspace", (long long)pairs);
     pl.rows_per_split = (int)rps;
@@ -284,7 +290,10 @@ hylra_status hylra_create(hylra_ctx** out, const hylra_shape* max_shape, int32_t
     ctx->max_shape = *max_shape;
     ctx->max_k = max_k;
     const int64_t pairs = (int64_t)max_shape->batch * max_shape->n_kv_heads;
-    ctx->slots = pairs * 2 > kMinSlots ? pairs * 2 : kMinSlots;
+    // enough partial slots for the Full kernel's smallest split count at the maximum context
+    const int64_t min_splits = ceil_div(max_shape->ctx_len, kMaxFullSplitRows - 256);
+    ctx->slots = pairs * (min_splits > 2 ? min_splits : 2);
+    if (ctx->slots < kMinSlots) ctx->slots = kMinSlots;
     ctx->cap_acc = ctx->slots * G * max_shape->head_dim;
     ctx->cap_ml = ctx->slots * G * 2;
     ctx->cap_scores = pairs * round_up(max_shape->ctx_len, 4);
@@ -303,8 +312,6 @@ hylra_status hylra_create(hylra_ctx** out, const hylra_shape* max_shape, int32_t
     const int64_t sel_ints = pairs * (4096 + 1 + 1024 + 1024 + 2 + ctx->max_chunks);
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->sel_ws, sel_ints * sizeof(int));
     if (e == hipSuccess) e = hipMemset(ctx->sel_ws, 0, sel_ints * sizeof(int));
-    if (e == hipSuccess) e = hipMalloc((void**)&ctx->row_ctr, ctx->slots * sizeof(int));
-    if (e == hipSuccess) e = hipMemset(ctx->row_ctr, 0, ctx->slots * sizeof(int));
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         fail(nullptr, HYLRA_ERR_HIP, "workspace allocation failed: %s", hipGetErrorString(e));
@@ -329,7 +336,6 @@ hylra_status hylra_destroy(hylra_ctx* ctx) {
     if (ctx->scores) (void)hipFree(ctx->scores);
     if (ctx->bscores) (void)hipFree(ctx->bscores);
     if (ctx->counters) (void)hipFree(ctx->counters);
-    if (ctx->row_ctr) (void)hipFree(ctx->row_ctr);
     if (ctx->sel_ws) (void)hipFree(ctx->sel_ws);
     delete ctx;
     return HYLRA_OK;
@@ -341,6 +347,7 @@ hylra_status hylra_set_option(hylra_ctx* ctx, const char* name, int32_t value) {
     if (!std::strcmp(name, "full_split_rows")) ctx->opt_full_split_rows = value;
     else if (!std::strcmp(name, "reuse_split_rows")) ctx->opt_reuse_split_rows = value;
     else if (!std::strcmp(name, "full_variant")) ctx->opt_full_variant = value;
+    else if (!std::strcmp(name, "full_split_rot")) ctx->opt_full_split_rot = value;
     else if (!std::strcmp(name, "reuse_variant")) ctx->opt_reuse_variant = value;
     else if (!std::strcmp(name, "reuse_unroll")) ctx->opt_reuse_unroll = value;
     else if (!std::strcmp(name, "reuse_unfused")) ctx->opt_reuse_unfused = value;
@@ -389,12 +396,12 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const void* q, 
     fp.sb = sd.b, fp.sh = sd.h, fp.sn = sd.n;
     fp.Hq = shape->n_q_heads, fp.Hkv = shape->n_kv_heads, fp.N = shape->ctx_len;
     fp.rows_per_split = pl.rows_per_split, fp.n_splits = pl.n_splits;
+    fp.split_rot = ctx->opt_full_split_rot % pl.n_splits;
     fp.scale_log2 = scale * LOG2E_HOST;
     fp.scale_mean = scale / (float)G;
     fp.part_ml = ctx->part_ml, fp.part_acc = ctx->part_acc, fp.part_mm = ctx->part_mm;
     fp.scores = ctx->scores;
     fp.score_stride = round_up(shape->ctx_len, 4);
-    fp.row_ctr = ctx->row_ctr;
     HIP_TRY(ctx, launch_timed(ctx, 0, st, [&] {
                 return launch_full_split(fp, shape->batch, shape->head_dim, G, pl.variant, st);
             }));
@@ -432,7 +439,7 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const void* q, 
         sp.scores = sel_scores, sp.score_stride = sel_stride;
         sp.n_splits = pl.n_splits, sp.Hq = shape->n_q_heads, sp.Hkv = shape->n_kv_heads;
         sp.G = G, sp.D = shape->head_dim, sp.N = n_sel, sp.k = k;
-        sp.out = out, sp.idx = idx, sp.row_ctr = ctx->row_ctr;
+        sp.out = out, sp.idx = idx;
         int* w = ctx->sel_ws;
         sp.ghist = w, w += ctx->pairs_cap * 4096;
         sp.cand_n = w, w += ctx->pairs_cap;
@@ -451,7 +458,6 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const void* q, 
     zp.n_splits = pl.n_splits, zp.Hq = shape->n_q_heads, zp.Hkv = shape->n_kv_heads;
     zp.G = G, zp.D = shape->head_dim, zp.N = n_sel, zp.k = k;
     zp.variant = ctx->opt_finalize_variant == 2 ? 1 : 0;
-    zp.row_ctr = ctx->row_ctr;
     zp.out = out, zp.idx = idx;
     HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_full_finalize(zp, shape->batch, st); }));
     return HYLRA_OK;

@@ -192,70 +192,90 @@ constexpr int merge_smem_floats() {
 // Every thread of the workgroup must call this.  With COHERENT the partial is written with
 // device-scope write-through stores, so that another workgroup can read it in the same
 // launch (see coherent_load) without a full cache write-back.
+//
+// All workgroups of a launch reach this point at about the same time, so nothing overlaps
+// it: it is kept short.  Within a wave the lanes that hold the same columns (one per row
+// slot) are summed with register exchanges only: a halving butterfly over the four 16-lane
+// rows (each step hands half of the values to the partner rows, so the work halves too),
+// then rotations inside a row.  The waves meet once, in LDS, each with its own maximum.
 template <class GEO, int NW, bool COHERENT = false>
 DEVI void block_merge_store(LaneState<GEO>& st, float* smem, float* __restrict__ part_ml,
                             int64_t ml_stride, float* __restrict__ part_acc, int64_t acc_stride) {
-    constexpr int G = GEO::G, D = GEO::D, LPR = GEO::LPR, ACC = GEO::ACC, CH = GEO::CH;
+    constexpr int G = GEO::G, D = GEO::D, LPR = GEO::LPR, ACC = GEO::ACC;
+    constexpr int PER = ACC + 1;                       // summed values per head: accumulators, l
+    constexpr int NV = (G * PER + 3) / 4 * 4;          // padded so that it halves twice
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int chunk = lane % LPR;
     float* s_max = smem;                    // [NW][G]
     float* s_l = smem + NW * G;             // [NW][G]
     float* s_acc = smem + 2 * NW * G;       // [NW][G][D]
 
+    // the wave's maximum per head; every lane rescales its state to it
+    float v[NV];
     float wmax[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-        float v = st.m[h];
+        wmax[h] = strided_minmax<LPR, true>(st.m[h]);
+        const float f = fast_exp2(st.m[h] - wmax[h]);
 #pragma unroll
-        for (int mask = LPR; mask < 64; mask <<= 1) v = fmaxf(v, __shfl_xor(v, mask, 64));
-        wmax[h] = v;
+        for (int e = 0; e < ACC; ++e) v[h * PER + e] = st.acc[h][e] * f;
+        v[h * PER + ACC] = st.l[h] * f;
+    }
+#pragma unroll
+    for (int i = G * PER; i < NV; ++i) v[i] = 0.f;
+
+    // rows 0,1 keep values [0, NV/2), rows 2,3 take [NV/2, NV); then even rows keep the lower
+    // half of what they hold and odd rows the upper half
+#pragma unroll
+    for (int i = 0; i < NV / 2; ++i) {
+        swap_rows32(v[i], v[i + NV / 2]);
+        v[i] += v[i + NV / 2];
+    }
+#pragma unroll
+    for (int i = 0; i < NV / 4; ++i) {
+        swap_rows16(v[i], v[i + NV / 4]);
+        v[i] += v[i + NV / 4];
+        if (LPR <= 8) v[i] += dpp_move<0x128>(v[i]);       // row_ror:8
+        if (LPR <= 4) v[i] += dpp_move<0x124>(v[i]);       // row_ror:4
+    }
+    // lane row r now holds values i + first, i < NV/4, summed over the whole wave
+    const int row = lane >> 4;
+    const int first = (row & 1) * (NV / 4) + (row >> 1) * (NV / 2);
+    if ((lane & 15) < LPR) {
+#pragma unroll
+        for (int i = 0; i < NV / 4; ++i) {
+            const int j = first + i;
+            const int h = j / PER, e = j - h * PER;
+            if (j < G * PER) {
+                if (e < ACC) s_acc[(wave * G + h) * D + ((e >> 3) * LPR + chunk) * 8 + (e & 7)] = v[i];
+                else if (chunk == 0) s_l[wave * G + h] = v[i];
+            }
+        }
     }
     if (lane == 0) {
 #pragma unroll
         for (int h = 0; h < G; ++h) s_max[wave * G + h] = wmax[h];
     }
     __syncthreads();
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
+
+    for (int i = tid; i < G * D; i += NW * 64) {
+        const int h = i / D, col = i - h * D;
         float M = s_max[h];
 #pragma unroll
         for (int w = 1; w < NW; ++w) M = fmaxf(M, s_max[w * G + h]);
-        const float f = fast_exp2(st.m[h] - M);
-        float lsum = st.l[h] * f;
+        float a = 0.f;
 #pragma unroll
-        for (int mask = LPR; mask < 64; mask <<= 1) lsum += __shfl_xor(lsum, mask, 64);
-        if (lane == 0) s_l[wave * G + h] = lsum;
-#pragma unroll
-        for (int e = 0; e < ACC; ++e) {
-            float a = st.acc[h][e] * f;
-#pragma unroll
-            for (int mask = LPR; mask < 64; mask <<= 1) a += __shfl_xor(a, mask, 64);
-            st.acc[h][e] = a;
-        }
-        if (lane < LPR) {
-#pragma unroll
-            for (int j = 0; j < CH; ++j)
-#pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    s_acc[(wave * G + h) * D + (chunk + j * LPR) * 8 + e] = st.acc[h][j * 8 + e];
-        }
-    }
-    __syncthreads();
-    for (int i = tid; i < G * D; i += NW * 64) {
-        const int h = i / D, col = i - h * D;
-        float a = s_acc[h * D + col];
-#pragma unroll
-        for (int w = 1; w < NW; ++w) a += s_acc[(w * G + h) * D + col];
+        for (int w = 0; w < NW; ++w) a = fmaf(fast_exp2(s_max[w * G + h] - M), s_acc[(w * G + h) * D + col], a);
         if (COHERENT) coherent_store(part_acc + h * acc_stride + col, a);
         else part_acc[h * acc_stride + col] = a;
     }
     if (tid < G) {
-        float lsum = s_l[tid];
-#pragma unroll
-        for (int w = 1; w < NW; ++w) lsum += s_l[w * G + tid];
         float M = s_max[tid];
 #pragma unroll
         for (int w = 1; w < NW; ++w) M = fmaxf(M, s_max[w * G + tid]);
+        float lsum = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) lsum = fmaf(fast_exp2(s_max[w * G + tid] - M), s_l[w * G + tid], lsum);
         if (COHERENT) {
             coherent_store(part_ml + tid * ml_stride, M);
             coherent_store(part_ml + tid * ml_stride + 1, lsum);

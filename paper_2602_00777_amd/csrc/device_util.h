@@ -40,6 +40,41 @@ DEVI float group_sum(float v) {
     return v;
 }
 
+// Register exchanges between the four 16-lane rows of a wave (gfx950 VALU, no LDS traffic).
+// swap_rows16(a, b): rows 1 and 3 of a trade places with rows 0 and 2 of b.
+// swap_rows32(a, b): rows 2 and 3 of a trade places with rows 0 and 1 of b.
+// With a == b on entry, a and b leave holding the two partners of an xor-16 (xor-32) lane
+// exchange; with different values, a + b afterwards is a's pair sum on the lower partner
+// rows and b's on the upper ones, i.e. one step of a halving butterfly.
+DEVI void swap_rows16(float& a, float& b) {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    a = __uint_as_float(r[0]);
+    b = __uint_as_float(r[1]);
+}
+DEVI void swap_rows32(float& a, float& b) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    a = __uint_as_float(r[0]);
+    b = __uint_as_float(r[1]);
+}
+
+// Maximum / minimum over the lanes that share (lane % LANES) in a wave, LANES in {1, 4, 8, 16}
+// (LANES = 1: over the whole wave); every lane ends with the result.  row_ror:n rotates within
+// a 16-lane row, so rotations by 8 and 4 (and 2, 1) reach every lane of a row.
+template <int LANES, bool MAX>
+DEVI float strided_minmax(float v) {
+    auto op = [](float a, float b) { return MAX ? fmaxf(a, b) : fminf(a, b); };
+    if (LANES <= 8) v = op(v, dpp_move<0x128>(v));
+    if (LANES <= 4) v = op(v, dpp_move<0x124>(v));
+    if (LANES <= 2) v = op(v, dpp_move<0x122>(v));
+    if (LANES <= 1) v = op(v, dpp_move<0x121>(v));
+    float a = v, b = v;
+    swap_rows16(a, b);
+    v = op(a, b);
+    a = v, b = v;
+    swap_rows32(a, b);
+    return op(a, b);
+}
+
 // Unsigned key with the same order as the float (negative zero below positive zero).
 DEVI uint32_t ordered_key(float f) {
     uint32_t u = __float_as_uint(f);

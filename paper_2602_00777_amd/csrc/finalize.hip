@@ -105,7 +105,6 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
     const int64_t pair = (int64_t)b * p.Hkv + g;
 
     HYLRA_TS(0);
-    if (tid == 0) p.row_ctr[pair] = 0;
     RegScores<E> src;
     src.init(p.scores + pair * p.score_stride, N);      // loads are in flight from here on
 

@@ -14,11 +14,16 @@ namespace hylra {
 
 // MODE 0: plain loads, one tile at a time.  MODE 1: streaming (non-temporal) loads.
 // MODE 2: streaming loads and a two-deep register pipeline -- the loads of tile i+1 are
-// issued before tile i is consumed, so every wave always has a full tile in flight.
-// MODE 3: streaming loads, and rows are handed out dynamically: the workgroups of one
-// (batch, KV head) share a row counter and every wave claims the next chunk of rows when it
-// runs dry, so compute units that get a larger share of the memory bandwidth simply stream
-// more rows and all waves finish together.  rows_per_split is ignored in this mode.
+// issued before tile i is consumed, so every wave always has one to two tiles in flight.
+//
+// The group-mean scores of the split are staged in LDS (rows_per_split floats of dynamic
+// shared memory) and written out once, after the loop.  Besides turning them into full
+// 16-byte stores this keeps vector stores out of the loop: loads and stores share one
+// completion counter on this architecture and do not complete in order with respect to each
+// other, so with a store pending every wait for a tile would have to drain the counter to
+// zero, i.e. also wait for the tile that was only just requested.  For the same reason the
+// pipelined loop issues its look-ahead loads unconditionally (rows past the split are
+// clamped to its last row): the number of younger loads at each wait is then a constant.
 template <int D, int G, int CH, int R, int MODE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void full_attn_split_kernel(FullParams p) {
     using GEO = Geo<D, G, CH>;
@@ -27,8 +32,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     constexpr bool NT = MODE >= 1;
     __shared__ float smem[merge_smem_floats<GEO, NW>()];
     __shared__ float s_mm[2 * NW];
+    extern __shared__ float s_scores[];          // [rows_per_split]
 
-    const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int split = (blockIdx.x + p.split_rot) % p.n_splits, g = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int chunk = lane % GEO::LPR, slot = lane / GEO::LPR;
 
@@ -40,9 +46,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
 
     LaneState<GEO> st;
     st.init();
-    const int row0 = MODE == 3 ? 0 : split * p.rows_per_split;
-    const int row1 = MODE == 3 ? p.N : min(p.N, row0 + p.rows_per_split);
-    float* __restrict__ srow = p.scores + ((int64_t)b * p.Hkv + g) * p.score_stride;
+    const int row0 = split * p.rows_per_split;
+    const int row1 = min(p.N, row0 + p.rows_per_split);
     float smin = 3.0e38f, smax = -3.0e38f;
 
     // element offsets of this lane's rows in the tile starting at row t0 (rows past the end
@@ -52,7 +57,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         for (int r = 0; r < R; ++r)
             off[r] = (int64_t)min(t0 + r * GEO::RPG + slot, row1 - 1) * p.sn + chunk * 8;
     };
-    // softmax/accumulate a loaded tile, store its group-mean scores, track their range
+    // softmax/accumulate a loaded tile, stage its group-mean scores, track their range
     auto consume = [&](const TileBuf<GEO, R>& buf, int t0) {
         bool valid[R];
         float ms[R];
@@ -63,7 +68,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const float v = fminf(fmaxf(ms[r], -3.0e38f), 3.0e38f);   // also maps NaN to a number
-                if (chunk == 0) srow[t0 + r * GEO::RPG + slot] = v;
+                if (chunk == 0) s_scores[t0 - row0 + r * GEO::RPG + slot] = v;
                 smin = fminf(smin, v);
                 smax = fmaxf(smax, v);
             }
@@ -75,7 +80,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
             for (int r = 0; r < R; ++r) {
                 const float v = fminf(fmaxf(ms[r], -3.0e38f), 3.0e38f);
                 if (valid[r]) {
-                    if (chunk == 0) srow[t0 + r * GEO::RPG + slot] = v;
+                    if (chunk == 0) s_scores[t0 - row0 + r * GEO::RPG + slot] = v;
                     smin = fminf(smin, v);
                     smax = fmaxf(smax, v);
                 }
@@ -84,36 +89,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     };
 
     constexpr int STEP = NW * TILE;
-    if (MODE == 3) {
-        constexpr int CHUNK = 4 * TILE;            // rows claimed per atomic
-        int* ctr = p.row_ctr + ((int64_t)b * p.Hkv + g);
-        auto claim = [&]() {
-            int v = 0;
-            if (lane == 0) v = __hip_atomic_fetch_add(ctr, CHUNK, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            return v;
-        };
-        // The claimed row is the same in every lane, but it is passed on with a shuffle and
-        // not as a scalar: the compiler then keeps the loop in its compact form (as a
-        // provably uniform value it restructures the loop and runs out of registers).
-        int cur = __shfl(claim(), 0, 64);
-        int nxt_v = claim();                       // in flight while this chunk is processed
-        int i = 0;
-#pragma unroll 1
-        while (true) {
-            const int t0 = cur + i * TILE;
-            if (t0 >= row1) break;                 // claims only grow: nothing is left
-            int64_t off[R];
-            TileBuf<GEO, R> buf;
-            offsets(t0, off);
-            load_tile<GEO, R, NT>(buf, Kb, Vb, off);
-            consume(buf, t0);
-            if (++i == 4) {
-                i = 0;
-                cur = __shfl(nxt_v, 0, 64);
-                nxt_v = claim();
-            }
-        }
-    } else if (MODE < 2) {
+    if (MODE < 2) {
         for (int t0 = row0 + wave * TILE; t0 < row1; t0 += STEP) {
             int64_t off[R];
             TileBuf<GEO, R> buf;
@@ -125,22 +101,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         TileBuf<GEO, R> bufA, bufB;
         int64_t off[R];
         int t0 = row0 + wave * TILE;
-        if (t0 < row1) {
-            offsets(t0, off);
-            load_tile<GEO, R, NT>(bufA, Kb, Vb, off);
-        }
+        offsets(t0, off);
+        load_tile<GEO, R, NT>(bufA, Kb, Vb, off);
         while (t0 < row1) {
-            if (t0 + STEP < row1) {
-                offsets(t0 + STEP, off);
-                load_tile<GEO, R, NT>(bufB, Kb, Vb, off);
-            }
+            offsets(t0 + STEP, off);
+            load_tile<GEO, R, NT>(bufB, Kb, Vb, off);
             consume(bufA, t0);
             t0 += STEP;
             if (t0 >= row1) break;
-            if (t0 + STEP < row1) {
-                offsets(t0 + STEP, off);
-                load_tile<GEO, R, NT>(bufA, Kb, Vb, off);
-            }
+            offsets(t0 + STEP, off);
+            load_tile<GEO, R, NT>(bufA, Kb, Vb, off);
             consume(bufB, t0);
             t0 += STEP;
         }
@@ -148,16 +118,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
 
     HYLRA_TS(1);
     // range of this split's group-mean scores (the finalise kernel bins on it)
-#pragma unroll
-    for (int mask = 1; mask < 64; mask <<= 1) {
-        smin = fminf(smin, __shfl_xor(smin, mask, 64));
-        smax = fmaxf(smax, __shfl_xor(smax, mask, 64));
-    }
+    smin = strided_minmax<1, false>(smin);
+    smax = strided_minmax<1, true>(smax);
     if (lane == 0) {
         s_mm[2 * wave] = smin;
         s_mm[2 * wave + 1] = smax;
     }
-    __syncthreads();
+    __syncthreads();                             // also: every score of the split is in LDS
     if (tid == 0) {
 #pragma unroll
         for (int w = 1; w < NW; ++w) {
@@ -167,6 +134,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         float* mm = p.part_mm + (((int64_t)b * p.Hkv + g) * p.n_splits + split) * 2;
         mm[0] = smin;
         mm[1] = smax;
+    }
+    {
+        // row0 and the score stride are multiples of 4 floats: 16-byte stores are aligned
+        float* __restrict__ dst = p.scores + ((int64_t)b * p.Hkv + g) * p.score_stride + row0;
+        const int n = row1 - row0;
+        for (int i = 4 * tid; i < n; i += 4 * NW * 64) {
+            if (i + 4 <= n) {
+                *reinterpret_cast<float4*>(dst + i) = *reinterpret_cast<const float4*>(s_scores + i);
+            } else {
+                for (int e = i; e < n; ++e) dst[e] = s_scores[e];
+            }
+        }
     }
 
     const int64_t head0 = (int64_t)b * p.Hq + (int64_t)g * G;
@@ -185,7 +164,7 @@ struct FullCfg {
 };
 
 // variant = 10 * MODE + R  (R = row groups per tile)
-#define HYLRA_FULL_VARIANTS(X) X(0, 4) X(1, 4) X(2, 3) X(3, 4) X(3, 2)
+#define HYLRA_FULL_VARIANTS(X) X(0, 4) X(1, 4) X(2, 3)
 constexpr int kDefaultFullVariant = 23;
 
 template <int D, int G>
@@ -194,7 +173,8 @@ static hipError_t launch_one(const FullParams& p, int B, int variant, hipStream_
     dim3 grid(p.n_splits, p.Hkv, B);
 #define V(MODE, R)                                                                              \
     if (variant == 10 * MODE + R) {                                                             \
-        hipLaunchKernelGGL((full_attn_split_kernel<D, G, CH, R, MODE>), grid, dim3(256), 0, st, p); \
+        hipLaunchKernelGGL((full_attn_split_kernel<D, G, CH, R, MODE>), grid, dim3(256),        \
+                           p.rows_per_split * sizeof(float), st, p);                            \
         return hipGetLastError();                                                               \
     }
     HYLRA_FULL_VARIANTS(V)

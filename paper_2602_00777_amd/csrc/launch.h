@@ -7,6 +7,7 @@ namespace hylra {
 
 constexpr int kMaxGroup = 8;        // query heads per KV head
 constexpr int kMaxSplits = 1024;    // partials per (batch, KV head) the finalise kernels accept
+constexpr int kMaxFullSplitRows = 8192;   // rows per workgroup of the vector Full kernel (its scores sit in LDS)
 
 struct FullParams {
     const uint16_t* q;
@@ -15,6 +16,7 @@ struct FullParams {
     int64_t sb, sh, sn;             // element strides of K and V
     int Hq, Hkv, N;
     int rows_per_split, n_splits;
+    int split_rot;                  // workgroup x handles split (x + split_rot) % n_splits
     float scale_log2;               // scale * log2(e)
     float scale_mean;               // scale / G
     float* part_ml;                 // [B*Hq][S][2]   (max in log2 units, sum)
@@ -22,7 +24,6 @@ struct FullParams {
     float* part_mm;                 // [B*Hkv][S][2]  (min, max of the group-mean scores)
     float* scores;                  // [B*Hkv][score_stride] group-mean scaled scores
     int64_t score_stride;           // multiple of 4, >= N
-    int* row_ctr;                   // [B*Hkv] next unclaimed row (dynamic mode); zero at launch
 };
 
 struct FinalizeParams {
@@ -32,7 +33,6 @@ struct FinalizeParams {
     const float* scores;
     int64_t score_stride;
     int n_splits, Hq, Hkv, G, D, N, k;
-    int* row_ctr;                   // [B*Hkv], reset to zero here for the next Full launch
     int variant;                    // 0: scores kept in registers when they fit; 1: always re-read
     float* out;                     // [B][Hq][D]
     int32_t* idx;                   // [B][Hkv][k]
@@ -49,7 +49,6 @@ struct SelectParams {
     int n_splits, Hq, Hkv, G, D, N, k;
     float* out;                     // [B][Hq][D]
     int32_t* idx;                   // [B][Hkv][k]
-    int* row_ctr;                   // [B*Hkv], reset to zero for the next Full launch
     int* ghist;                     // [B*Hkv][4096] score histogram; zero between launches
     int* cand_n;                    // [B*Hkv] rows in the threshold bin found so far
     uint32_t* cand_key;             // [B*Hkv][1024] their keys ...

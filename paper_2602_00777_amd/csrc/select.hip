@@ -91,7 +91,6 @@ __global__ __launch_bounds__(SEL_THREADS) void select_hist_kernel(SelectParams p
     for (int i = tid; i < SEL_BINS; i += SEL_THREADS) s_hist[i] = 0;
     if (c == 0 && tid == 0) {
         p.cand_n[pair] = 0;
-        p.row_ctr[pair] = 0;
     }
 
     // attention output: this workgroup's share of the G*D outputs of the KV head
