@@ -166,8 +166,11 @@ hylra_status hylra_decode_step_blocks(hylra_ctx *ctx, const hylra_shape *shape, 
  *                       pipeline; default up to 4 heads per KV head).  Matrix-core kernels: 54, 52
  *                       (default from 5 heads per KV head), 62, 61 (pipelined)
  *   "reuse_variant"     Reuse gather kernel: 1 / 2 = vector-ALU kernel with streaming / plain
- *                       loads, 3 / 4 = matrix-core kernel with streaming / plain loads (default 4)
+ *                       loads, 3 / 4 = first matrix-core kernel with streaming / plain loads
+ *                       (default for head_dim 64: 4), 5 / 6 = second matrix-core kernel
+ *                       (head_dim 128 only; default there: 5)
  *   "reuse_unroll"      row groups per wave tile of the Reuse kernel: 1, 2, 4 or 8
+ *   "reuse_waves"       waves per workgroup of the matrix-core Reuse kernel: 4 or 8
  *   "reuse_unfused"     1 = merge the Reuse partials in a second kernel instead of in the
  *                       last-arriving workgroup of the Reuse kernel
  *   "finalize_variant"  how the Full layer is finalised (merge of partials + top-k):

@@ -56,6 +56,7 @@ struct hylra_ctx {
     int32_t opt_full_split_rot = 0;
     int32_t opt_reuse_variant = 0;
     int32_t opt_reuse_unroll = 0;
+    int32_t opt_reuse_waves = 0;
     int32_t opt_reuse_unfused = 0;
     int32_t opt_finalize_variant = 0;
     int32_t opt_finalize_groups = 0;
@@ -198,14 +199,17 @@ hylra_status plan_full(const hylra_ctx* ctx, const hylra_shape* s, int G, FullPl
 }
 
 struct ReusePlan {
-    int rows_per_split, n_splits, variant, R;
+    int rows_per_split, n_splits, variant, R, NW;
 };
 
 hylra_status plan_reuse(const hylra_ctx* ctx, const hylra_shape* s, int G, int k, ReusePlan& pl) {
-    // public ids 1..4 = vector kernel (streaming / plain loads), matrix-core kernel (streaming /
-    // plain loads); automatic = matrix cores with plain loads (fastest on 3 of the 4 large
-    // benchmark shapes, within 2 % on the fourth)
-    pl.variant = (ctx->opt_reuse_variant >= 1 && ctx->opt_reuse_variant <= 4) ? ctx->opt_reuse_variant - 1 : 3;
+    // public ids 1..6 = vector kernel (streaming / plain loads), first matrix-core kernel
+    // (streaming / plain loads), second matrix-core kernel (streaming / plain loads).
+    // Automatic: the second matrix-core kernel with streaming loads for head_dim 128 (it is
+    // built for that only), else the first one with plain loads.
+    pl.variant = (ctx->opt_reuse_variant >= 1 && ctx->opt_reuse_variant <= 6) ? ctx->opt_reuse_variant - 1
+                 : s->head_dim == 128 ? 4 : 3;
+    if (pl.variant >= 4 && s->head_dim != 128) pl.variant -= 2;
     const int64_t pairs = (int64_t)s->batch * s->n_kv_heads;
     // Unroll: 8 row groups per wave tile (64 rows per wave with 8 lanes per row) keeps the
     // whole gather of a layer in flight at once and the number of partials per (batch, KV
@@ -213,10 +217,17 @@ hylra_status plan_reuse(const hylra_ctx* ctx, const hylra_shape* s, int G, int k
     // tiles only when a single workgroup still covers all k entries.
     pl.R = ctx->opt_reuse_unroll > 0 ? ctx->opt_reuse_unroll : 8;
     const bool mfma = pl.variant >= 2;
+    const bool mfma2 = pl.variant >= 4;
+    if (mfma2) pl.R = 8;
+    // matrix-core kernels: workgroups of 8 waves when asked for, or when k fills them
+    pl.NW = 4;
+    if (mfma && pl.R == 8 && (ctx->opt_reuse_waves == 8 || (ctx->opt_reuse_waves == 0 && k >= 512 && k % 512 == 0)))
+        pl.NW = 8;
     auto quantum_of = [&](int R) {
-        return mfma ? reuse_mfma_quantum(R / 2) : reuse_block_quantum(s->head_dim, G, pl.variant, R);
+        if (mfma2) return R == 8 ? reuse_mfma2_quantum(s->head_dim, pl.NW) : 0;
+        return mfma ? reuse_mfma_quantum(R / 2, pl.NW) : reuse_block_quantum(s->head_dim, G, pl.variant, R);
     };
-    while (ctx->opt_reuse_unroll == 0 && pl.R > (mfma ? 2 : 1) && quantum_of(pl.R / 2) >= k) pl.R /= 2;
+    while (ctx->opt_reuse_unroll == 0 && !mfma2 && pl.R > (mfma ? 2 : 1) && quantum_of(pl.R / 2) >= k) pl.R /= 2;
     pl.rows_per_split = quantum_of(pl.R);
     if (pl.rows_per_split <= 0)
         return fail(ctx, HYLRA_ERR_UNSUPPORTED, "Reuse kernel variant %d / unroll %d is not built for d=%d G=%d", pl.variant, pl.R, s->head_dim, G);
@@ -350,6 +361,7 @@ hylra_status hylra_set_option(hylra_ctx* ctx, const char* name, int32_t value) {
     else if (!std::strcmp(name, "full_split_rot")) ctx->opt_full_split_rot = value;
     else if (!std::strcmp(name, "reuse_variant")) ctx->opt_reuse_variant = value;
     else if (!std::strcmp(name, "reuse_unroll")) ctx->opt_reuse_unroll = value;
+    else if (!std::strcmp(name, "reuse_waves")) ctx->opt_reuse_waves = value;
     else if (!std::strcmp(name, "reuse_unfused")) ctx->opt_reuse_unfused = value;
     else if (!std::strcmp(name, "finalize_variant")) ctx->opt_finalize_variant = value;
     else if (!std::strcmp(name, "finalize_groups")) {
@@ -502,8 +514,10 @@ hylra_status reuse_impl(hylra_ctx* ctx, const hylra_shape* shape, const void* q,
     rp.counters = fused ? ctx->counters : nullptr;
     rp.out = out;
     HIP_TRY(ctx, launch_timed(ctx, 2, st, [&] {
+                if (pl.variant >= 4)
+                    return launch_reuse_mfma2(rp, shape->batch, G, pl.variant == 4, pl.NW, st);
                 if (pl.variant >= 2)
-                    return launch_reuse_mfma(rp, shape->batch, shape->head_dim, G, pl.R / 2, pl.variant == 2, st);
+                    return launch_reuse_mfma(rp, shape->batch, shape->head_dim, G, pl.R / 2, pl.variant == 2, pl.NW, st);
                 return launch_reuse_split(rp, shape->batch, shape->head_dim, G, pl.variant, pl.R, st);
             }));
     if (fused) return HYLRA_OK;

@@ -128,9 +128,14 @@ inline hipError_t launch_reuse_split(const ReuseParams& p, int B, int D, int G, 
          : D == 128 ? launch_reuse_split_d128(p, B, G, variant, R, st) : hipErrorInvalidValue;
 }
 
-// Matrix-core Reuse kernel: NB blocks of 16 rows per wave tile (1, 2 or 4)
-int reuse_mfma_quantum(int NB);
-hipError_t launch_reuse_mfma(const ReuseParams& p, int B, int D, int G, int NB, bool nt, hipStream_t st);
+// Matrix-core Reuse kernel: NB blocks of 16 rows per wave tile (1, 2 or 4), NW waves per
+// workgroup (4; 8 with NB = 4)
+int reuse_mfma_quantum(int NB, int NW);
+hipError_t launch_reuse_mfma(const ReuseParams& p, int B, int D, int G, int NB, bool nt, int NW, hipStream_t st);
+
+// Second matrix-core Reuse kernel (head_dim 128): 64 index entries per wave, NW = 4 or 8 waves
+int reuse_mfma2_quantum(int D, int NW);
+hipError_t launch_reuse_mfma2(const ReuseParams& p, int B, int G, bool nt, int NW, hipStream_t st);
 
 hipError_t launch_full_finalize(const FinalizeParams& p, int B, hipStream_t st);
 // step 0, 1, 2 = histogram, classify, emit; E = float4 groups per thread (2 or 8)

@@ -25,10 +25,12 @@
 
 namespace hylra {
 
-// NB blocks of 16 rows per wave tile.
-template <int D, int G, int NB, bool NT>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void reuse_mfma_kernel(ReuseParams p) {
-    constexpr int NW = 4;
+// NB blocks of 16 rows per wave tile, NW waves per workgroup.  With 8 waves one workgroup fills
+// a compute unit (two waves per SIMD), so all waves of the unit start together and issue their
+// index loads before any row load is queued in the unit's memory pipeline; with 4 waves the
+// second workgroup of a unit can find its index loads queued behind the first one's rows.
+template <int D, int G, int NB, bool NT, int NW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) void reuse_mfma_kernel(ReuseParams p) {
     constexpr int KI = D / 32;          // 32-column steps of the score contraction
     constexpr int ROWS_W = 16 * NB;
     __shared__ float s_m[NW][16];
@@ -105,29 +107,33 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void r
 }
 
 template <int D, int G>
-static hipError_t launch_g(const ReuseParams& p, int B, int NB, bool nt, hipStream_t st) {
+static hipError_t launch_g(const ReuseParams& p, int B, int NB, bool nt, int NW, hipStream_t st) {
     dim3 grid(p.n_splits, p.Hkv, B);
-#define HYLRA_MFMA_CASE(NBV)                                                                        \
-    if (NB == NBV) {                                                                                \
-        if (nt) hipLaunchKernelGGL((reuse_mfma_kernel<D, G, NBV, true>), grid, dim3(256), 0, st, p); \
-        else hipLaunchKernelGGL((reuse_mfma_kernel<D, G, NBV, false>), grid, dim3(256), 0, st, p);   \
-        return hipGetLastError();                                                                   \
+#define HYLRA_MFMA_CASE(NBV, NWV)                                                                              \
+    if (NB == NBV && NW == NWV) {                                                                              \
+        if (nt) hipLaunchKernelGGL((reuse_mfma_kernel<D, G, NBV, true, NWV>), grid, dim3(NWV * 64), 0, st, p); \
+        else hipLaunchKernelGGL((reuse_mfma_kernel<D, G, NBV, false, NWV>), grid, dim3(NWV * 64), 0, st, p);   \
+        return hipGetLastError();                                                                              \
     }
-    HYLRA_MFMA_CASE(4)
-    HYLRA_MFMA_CASE(2)
-    HYLRA_MFMA_CASE(1)
+    HYLRA_MFMA_CASE(4, 4)
+    HYLRA_MFMA_CASE(2, 4)
+    HYLRA_MFMA_CASE(1, 4)
+    HYLRA_MFMA_CASE(4, 8)
 #undef HYLRA_MFMA_CASE
     return hipErrorInvalidValue;
 }
 
-// rows per workgroup sweep with NB blocks of 16 rows per wave
-int reuse_mfma_quantum(int NB) { return (NB == 1 || NB == 2 || NB == 4) ? 4 * 16 * NB : 0; }
+// rows per workgroup sweep with NB blocks of 16 rows per wave and NW waves
+int reuse_mfma_quantum(int NB, int NW) {
+    const bool ok = (NW == 4 && (NB == 1 || NB == 2 || NB == 4)) || (NW == 8 && NB == 4);
+    return ok ? NW * 16 * NB : 0;
+}
 
-hipError_t launch_reuse_mfma(const ReuseParams& p, int B, int D, int G, int NB, bool nt, hipStream_t st) {
-#define HYLRA_G(GG)                                                      \
-    if (G == GG) {                                                       \
-        if (D == 128) return launch_g<128, GG>(p, B, NB, nt, st);        \
-        if (D == 64) return launch_g<64, GG>(p, B, NB, nt, st);          \
+hipError_t launch_reuse_mfma(const ReuseParams& p, int B, int D, int G, int NB, bool nt, int NW, hipStream_t st) {
+#define HYLRA_G(GG)                                                          \
+    if (G == GG) {                                                           \
+        if (D == 128) return launch_g<128, GG>(p, B, NB, nt, NW, st);        \
+        if (D == 64) return launch_g<64, GG>(p, B, NB, nt, NW, st);          \
     }
     HYLRA_G(1) HYLRA_G(2) HYLRA_G(3) HYLRA_G(4) HYLRA_G(5) HYLRA_G(6) HYLRA_G(7) HYLRA_G(8)
 #undef HYLRA_G

@@ -1,0 +1,290 @@
+// Reuse layer (Algorithm 2, Reuse branch; attention as in Eq. 1) for head_dim 128, second
+// matrix-core form.  Same decomposition and cross-workgroup merge as reuse_mfma.hip; what
+// differs is the V side of a wave's work:
+//
+//   K rows   loaded as before, lane = row of a 16-row block, and contracted with q by
+//            v_mfma_f32_16x16x32_bf16; the scores of a block come back as lane = head,
+//            registers = rows 4 gq .. 4 gq + 3 of the block.
+//   V rows   loaded with 16 lanes per row (one instruction reads four whole 256-byte rows):
+//            lane (n, gq) fetches, for the two blocks a, b of a 32-row group, columns
+//            8 n .. 8 n + 7 of rows 4 gq + j of a (j < 4) and of b (j >= 4) -- the same eight
+//            rows, in the same order, that its score registers cover.  An 8 x 8 transpose
+//            inside the lane (32 byte permutes, no cross-lane traffic) turns these into, per
+//            column 8 n + e, eight rows packed in one register quad: the B operand of
+//            out[h][8 n + e] += P[h][rows] V[rows][8 n + e]  on v_mfma_f32_16x16x32_bf16.
+//   weights  fp32, split into a high and a low bf16 half (two MFMAs per column set), so they
+//            carry 16 mantissa bits.
+//
+// Per 32 rows this needs 8 + 16 MFMAs where the first form needs 56 (it transposes V through
+// the matrix cores, 16 rows at a time, and contracts with the 16-deep instruction).
+#include "launch.h"
+#include "mfma_core.h"
+#include "reuse_tail.h"
+
+namespace hylra {
+
+namespace {
+
+// (lo half of x) | (lo half of y) << 16   and the same for the high halves
+DEVI uint32_t pack_lo(uint32_t x, uint32_t y) { return __builtin_amdgcn_perm(y, x, 0x05040100u); }
+DEVI uint32_t pack_hi(uint32_t x, uint32_t y) { return __builtin_amdgcn_perm(y, x, 0x07060302u); }
+
+DEVI uint32_t dword_of(const uint4& v, int w) { return w == 0 ? v.x : w == 1 ? v.y : w == 2 ? v.z : v.w; }
+
+// v[j] = eight consecutive bf16 columns of row j (j = 0..7).  t[e] = column e of the eight rows.
+DEVI void transpose8x8(const uint4 (&v)[8], uint4 (&t)[8]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        uint32_t w[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const uint32_t x = dword_of(v[2 * r], e >> 1), y = dword_of(v[2 * r + 1], e >> 1);
+            w[r] = (e & 1) ? pack_hi(x, y) : pack_lo(x, y);
+        }
+        t[e] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
+// Online-softmax state of a wave: m, l belong to head n (identical in the 4 lanes of a head);
+// register j of acc[e] in lane (n, gq) holds out[head 4 gq + j][column 8 n + e].
+struct State2 {
+    float m, l;
+    float4_t acc[8];
+    DEVI void init() {
+        m = NEG_BIG;
+        l = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = float4_t{0.f, 0.f, 0.f, 0.f};
+    }
+};
+
+// One group of 32 rows (blocks a and b).  ka / kb: this lane's pieces of its row of K in each
+// block; v: its eight V pieces (rows 4 gq + j of a, then of b); mask_a / mask_b: bit r set if
+// row r of the block takes part.
+template <int G>
+DEVI void group32(State2& st, const uint4 (&ka)[4], const uint4 (&kb)[4], const uint4 (&v)[8],
+                  const uint4 (&qb)[4], uint32_t mask_a, uint32_t mask_b, float scale_log2, int n, int gq) {
+    float4_t Sa = {0.f, 0.f, 0.f, 0.f}, Sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        Sa = mfma_k32(ka[i], qb[i], Sa);
+        Sb = mfma_k32(kb[i], qb[i], Sb);
+    }
+    float t[8];
+    bool ok[8];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        ok[j] = n < G && ((mask_a >> (4 * gq + j)) & 1u);
+        ok[4 + j] = n < G && ((mask_b >> (4 * gq + j)) & 1u);
+        t[j] = ok[j] ? Sa[j] * scale_log2 : NEG_BIG;
+        t[4 + j] = ok[4 + j] ? Sb[j] * scale_log2 : NEG_BIG;
+    }
+    float mx = fmaxf(fmaxf(fmaxf(t[0], t[1]), fmaxf(t[2], t[3])), fmaxf(fmaxf(t[4], t[5]), fmaxf(t[6], t[7])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(st.m, mx);
+    if (__builtin_amdgcn_ballot_w64(m_new > st.m) != 0) {
+        const float alpha = fast_exp2(st.m - m_new);
+        st.m = m_new;
+        st.l *= alpha;
+        // register j of this lane accumulates head 4 gq + j, whose factor is in lane 4 gq + j
+        float a4[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) a4[j] = __shfl(alpha, 4 * gq + j, 64);
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) st.acc[e][j] *= a4[j];
+    }
+    float hi[8], lo[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float w = ok[j] ? fast_exp2(t[j] - st.m) : 0.f;
+        st.l += w;
+        hi[j] = __uint_as_float(__float_as_uint(w) & 0xffff0000u);
+        lo[j] = w - hi[j];
+    }
+    const uint4 p_hi = make_uint4(pack_hi16(hi[0], hi[1]), pack_hi16(hi[2], hi[3]),
+                                  pack_hi16(hi[4], hi[5]), pack_hi16(hi[6], hi[7]));
+    const uint4 p_lo = make_uint4(pack_hi16(lo[0], lo[1]), pack_hi16(lo[2], lo[3]),
+                                  pack_hi16(lo[4], lo[5]), pack_hi16(lo[6], lo[7]));
+    uint4 vt[8];
+    transpose8x8(v, vt);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        st.acc[e] = mfma_k32(p_hi, vt[e], st.acc[e]);
+        st.acc[e] = mfma_k32(p_lo, vt[e], st.acc[e]);
+    }
+}
+
+// Merge the wave states of a workgroup into one partial per head, as mfma_block_merge_store
+// does for the first form (only the accumulator layout differs).  s_acc: [NW][G][128].
+template <int G, int NW, bool COHERENT>
+DEVI void merge_store2(State2& st, float (*s_m)[16], float (*s_l)[16], float* s_acc,
+                       float* __restrict__ part_ml, int64_t ml_stride, float* __restrict__ part_acc,
+                       int64_t acc_stride, int n, int gq) {
+    constexpr int D = 128;
+    const int tid = threadIdx.x, wave = tid >> 6;
+    float l = st.l;
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    if (gq == 0) {
+        s_m[wave][n] = st.m;
+        s_l[wave][n] = l;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int h = 4 * gq + j;
+        if (h < G) {
+            float4* dst = reinterpret_cast<float4*>(s_acc + (wave * G + h) * D + 8 * n);
+            dst[0] = make_float4(st.acc[0][j], st.acc[1][j], st.acc[2][j], st.acc[3][j]);
+            dst[1] = make_float4(st.acc[4][j], st.acc[5][j], st.acc[6][j], st.acc[7][j]);
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < G * D; i += NW * 64) {
+        const int h = i / D, col = i - h * D;
+        float M = s_m[0][h];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) M = fmaxf(M, s_m[w][h]);
+        float a = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) a = fmaf(fast_exp2(s_m[w][h] - M), s_acc[(w * G + h) * D + col], a);
+        if (COHERENT) coherent_store(part_acc + h * acc_stride + col, a);
+        else part_acc[h * acc_stride + col] = a;
+    }
+    if (tid < G) {
+        float M = s_m[0][tid];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) M = fmaxf(M, s_m[w][tid]);
+        float ls = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) ls = fmaf(fast_exp2(s_m[w][tid] - M), s_l[w][tid], ls);
+        if (COHERENT) {
+            coherent_store(part_ml + tid * ml_stride, M);
+            coherent_store(part_ml + tid * ml_stride + 1, ls);
+        } else {
+            part_ml[tid * ml_stride] = M;
+            part_ml[tid * ml_stride + 1] = ls;
+        }
+    }
+}
+
+}  // namespace
+
+// A wave takes 64 index entries (4 blocks of 16 = 2 groups of 32) per sweep; NW waves per
+// workgroup.
+template <int G, bool NT, int NW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) void reuse_mfma2_kernel(ReuseParams p) {
+    constexpr int D = 128, NB = 4, ROWS_W = 16 * NB;
+    __shared__ float s_m[NW][16];
+    __shared__ float s_l[NW][16];
+    __shared__ __attribute__((aligned(16))) float s_acc[NW * G * D];
+    __shared__ int s_last;
+
+    const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, gq = lane >> 4;
+
+    const int i0 = split * p.rows_per_split;
+    const int i1 = min(p.k, i0 + p.rows_per_split);
+    const int64_t pair = (int64_t)b * p.Hkv + g;
+    const int64_t head0 = (int64_t)b * p.Hq + (int64_t)g * G;
+    const int32_t* __restrict__ ib = p.idx + pair * p.idx_stride;
+    const uint16_t* __restrict__ Kb = p.K + (int64_t)b * p.sb + (int64_t)g * p.sh;
+    const uint16_t* __restrict__ Vb = p.V + (int64_t)b * p.sb + (int64_t)g * p.sh;
+
+    HYLRA_TS(0);
+    // the index loads head the longest dependent chain (index -> row -> softmax): issue first
+    int t0 = i0 + wave * ROWS_W;
+    int row[NB];
+#pragma unroll
+    for (int blk = 0; blk < NB; ++blk) {
+        const int pos = t0 + 16 * blk + n;
+        row[blk] = pos < i1 ? reuse_row(p, ib, pos) : -1;
+    }
+    uint4 qb[4];
+    mfma_load_q<D, G>(qb, p.q + head0 * D, n, gq);
+    State2 st;
+    st.init();
+
+    while (t0 < i1) {
+        HYLRA_TS(1);
+        uint4 kb[NB][4], vb[NB][4];
+        bool valid[NB];
+#pragma unroll
+        for (int blk = 0; blk < NB; ++blk) {
+            valid[blk] = (unsigned)row[blk] < (unsigned)p.N;       // negative or >= N: padding
+            const int64_t off = (int64_t)(valid[blk] ? row[blk] : 0) * p.sn + 8 * gq;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) kb[blk][i] = ld16<NT>(Kb + off + 32 * i);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                // row 4 gq + j of the block: its number sits in lane 4 gq + j
+                const int rv = __shfl(row[blk], 4 * gq + j, 64);
+                const int64_t voff = (int64_t)((unsigned)rv < (unsigned)p.N ? rv : 0) * p.sn + 8 * n;
+                vb[blk][j] = ld16<NT>(Vb + voff);
+            }
+        }
+        t0 += NW * ROWS_W;
+        if (t0 < i1) {
+#pragma unroll
+            for (int blk = 0; blk < NB; ++blk) {
+                const int pos = t0 + 16 * blk + n;
+                row[blk] = pos < i1 ? reuse_row(p, ib, pos) : -1;
+            }
+        }
+#pragma unroll
+        for (int gp = 0; gp < NB / 2; ++gp) {
+            // lanes 0..15 carry the 16 rows' validity
+            const uint32_t mask_a = (uint32_t)__builtin_amdgcn_ballot_w64(valid[2 * gp]) & 0xffffu;
+            const uint32_t mask_b = (uint32_t)__builtin_amdgcn_ballot_w64(valid[2 * gp + 1]) & 0xffffu;
+            uint4 v8[8];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                v8[j] = vb[2 * gp][j];
+                v8[4 + j] = vb[2 * gp + 1][j];
+            }
+            group32<G>(st, kb[2 * gp], kb[2 * gp + 1], v8, qb, mask_a, mask_b, p.scale_log2, n, gq);
+        }
+        HYLRA_TS(2);
+    }
+
+    float* const my_ml = p.part_ml + (head0 * p.n_splits + split) * 2;
+    float* const my_acc = p.part_acc + (head0 * p.n_splits + split) * D;
+    const int64_t ml_stride = (int64_t)p.n_splits * 2, acc_stride = (int64_t)p.n_splits * D;
+    if (p.counters == nullptr) {            // unfused: a separate kernel merges the partials
+        merge_store2<G, NW, false>(st, s_m, s_l, s_acc, my_ml, ml_stride, my_acc, acc_stride, n, gq);
+        return;
+    }
+    merge_store2<G, NW, true>(st, s_m, s_l, s_acc, my_ml, ml_stride, my_acc, acc_stride, n, gq);
+    reuse_merge_tail<G, D, NW * 64>(p, pair, head0, &s_last);
+}
+
+template <int G>
+static hipError_t launch2_g(const ReuseParams& p, int B, bool nt, int NW, hipStream_t st) {
+    dim3 grid(p.n_splits, p.Hkv, B);
+#define HYLRA_CASE(NWV)                                                                              \
+    if (NW == NWV) {                                                                                 \
+        if (nt) hipLaunchKernelGGL((reuse_mfma2_kernel<G, true, NWV>), grid, dim3(NWV * 64), 0, st, p); \
+        else hipLaunchKernelGGL((reuse_mfma2_kernel<G, false, NWV>), grid, dim3(NWV * 64), 0, st, p);   \
+        return hipGetLastError();                                                                    \
+    }
+    HYLRA_CASE(4)
+    HYLRA_CASE(8)
+#undef HYLRA_CASE
+    return hipErrorInvalidValue;
+}
+
+// index entries per workgroup sweep; 0 if the shape is not built
+int reuse_mfma2_quantum(int D, int NW) { return (D == 128 && (NW == 4 || NW == 8)) ? NW * 64 : 0; }
+
+hipError_t launch_reuse_mfma2(const ReuseParams& p, int B, int G, bool nt, int NW, hipStream_t st) {
+#define HYLRA_G(GG) \
+    if (G == GG) return launch2_g<GG>(p, B, nt, NW, st);
+    HYLRA_G(1) HYLRA_G(2) HYLRA_G(3) HYLRA_G(4) HYLRA_G(5) HYLRA_G(6) HYLRA_G(7) HYLRA_G(8)
+#undef HYLRA_G
+    return hipErrorInvalidValue;
+}
+
+}  // namespace hylra

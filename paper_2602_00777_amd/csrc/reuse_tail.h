@@ -22,6 +22,35 @@ DEVI int reuse_row(const ReuseParams& p, const int32_t* __restrict__ ib, int pos
     return (unsigned)c < (unsigned)p.n_blocks ? c * p.block + (pos - t * p.block) : -1;
 }
 
+// Merge of SB >= n_splits partials for output element i of the KV head's G*D outputs, with
+// every load of the merge in flight at once (the loads are device-scope and each is a trip to
+// memory: issued one after the other they would add up).  Slots s >= S are read from the
+// last real partial and weighted zero.
+template <int D, int SB>
+DEVI float merge_partials(const ReuseParams& p, int64_t head0, int i, int S) {
+    const int h = i / D, col = i - h * D;
+    const float* ml = p.part_ml + (head0 + h) * S * 2;
+    const float* acc = p.part_acc + (head0 + h) * S * D + col;
+    float m_s[SB], l_s[SB], a_s[SB];
+#pragma unroll
+    for (int s = 0; s < SB; ++s) {
+        const int sc = min(s, S - 1);
+        m_s[s] = coherent_load(ml + 2 * sc);
+        l_s[s] = coherent_load(ml + 2 * sc + 1);
+        a_s[s] = coherent_load(acc + (int64_t)sc * D);
+    }
+    float M = NEG_BIG, num = 0.f, den = 0.f;
+#pragma unroll
+    for (int s = 0; s < SB; ++s) M = fmaxf(M, m_s[s]);
+#pragma unroll
+    for (int s = 0; s < SB; ++s) {
+        const float w = s < S ? fast_exp2(m_s[s] - M) : 0.f;
+        den = fmaf(w, l_s[s], den);
+        num = fmaf(w, a_s[s], num);
+    }
+    return den > 0.f ? num / den : 0.f;
+}
+
 // Every thread of the workgroup (NT threads) calls this after its partial stores were issued.
 template <int G, int D, int NT>
 DEVI void reuse_merge_tail(const ReuseParams& p, int64_t pair, int64_t head0, int* s_last) {
@@ -37,29 +66,30 @@ DEVI void reuse_merge_tail(const ReuseParams& p, int64_t pair, int64_t head0, in
     HYLRA_TS(5);
     if (!*s_last) return;
     const int S = p.n_splits;
-    for (int i = tid; i < G * D; i += NT) {
-        const int h = i / D, col = i - h * D;
-        const float* ml = p.part_ml + (head0 + h) * S * 2;
-        const float* acc = p.part_acc + (head0 + h) * S * D + col;
-        float M = NEG_BIG, num = 0.f, den = 0.f;
-        if (S <= 16) {          // the usual case: every load of the merge is issued at once
-            float m_s[16], l_s[16], a_s[16];
+    constexpr int ITER = (G * D + NT - 1) / NT;      // output elements per thread
+    if (S <= 16) {
+        // the usual case.  All elements of a thread are merged in one go (clamped index,
+        // guarded store) so that their loads overlap too.
+        float r[ITER];
 #pragma unroll
-            for (int s = 0; s < 16; ++s) {
-                const bool on = s < S;
-                m_s[s] = on ? coherent_load(ml + 2 * s) : NEG_BIG;
-                l_s[s] = on ? coherent_load(ml + 2 * s + 1) : 0.f;
-                a_s[s] = on ? coherent_load(acc + (int64_t)s * D) : 0.f;
-            }
+        for (int it = 0; it < ITER; ++it) {
+            const int i = min(tid + it * NT, G * D - 1);
+            r[it] = S <= 2 ? merge_partials<D, 2>(p, head0, i, S)
+                  : S <= 4 ? merge_partials<D, 4>(p, head0, i, S)
+                  : S <= 8 ? merge_partials<D, 8>(p, head0, i, S)
+                           : merge_partials<D, 16>(p, head0, i, S);
+        }
 #pragma unroll
-            for (int s = 0; s < 16; ++s) M = fmaxf(M, m_s[s]);
-#pragma unroll
-            for (int s = 0; s < 16; ++s) {
-                const float w = fast_exp2(m_s[s] - M);
-                den = fmaf(w, l_s[s], den);
-                num = fmaf(w, a_s[s], num);
-            }
-        } else {
+        for (int it = 0; it < ITER; ++it) {
+            const int i = tid + it * NT;
+            if (i < G * D) p.out[head0 * D + i] = r[it];
+        }
+    } else {
+        for (int i = tid; i < G * D; i += NT) {
+            const int h = i / D, col = i - h * D;
+            const float* ml = p.part_ml + (head0 + h) * S * 2;
+            const float* acc = p.part_acc + (head0 + h) * S * D + col;
+            float M = NEG_BIG, num = 0.f, den = 0.f;
 #pragma unroll 8
             for (int s = 0; s < S; ++s) M = fmaxf(M, coherent_load(ml + 2 * s));
 #pragma unroll 8
@@ -68,8 +98,8 @@ DEVI void reuse_merge_tail(const ReuseParams& p, int64_t pair, int64_t head0, in
                 den = fmaf(w, coherent_load(ml + 2 * s + 1), den);
                 num = fmaf(w, coherent_load(acc + (int64_t)s * D), num);
             }
+            p.out[(head0 + h) * D + col] = den > 0.f ? num / den : 0.f;
         }
-        p.out[(head0 + h) * D + col] = den > 0.f ? num / den : 0.f;
     }
     HYLRA_TS(6);
     if (tid == 0) __hip_atomic_store(p.counters + pair, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

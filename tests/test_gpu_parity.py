@@ -119,6 +119,29 @@ def test_reuse_kernel_unrolls(unroll):
             assert_out_close(out.cpu().numpy(), ref, "reuse out")
 
 
+@pytest.mark.parametrize("variant,waves", [(3, 4), (4, 8), (5, 4), (5, 8), (6, 4), (6, 8)])
+def test_reuse_matrix_core_kernels(variant, waves):
+    """Both matrix-core Reuse kernels, with workgroups of 4 and of 8 waves, for every group size,
+    with padding entries, several sweeps per workgroup and a ragged tail."""
+    say("reuse matrix-core variant=%d waves=%d" % (variant, waves))
+    for G, (B, Hkv, N, k) in zip(range(1, 9), [(1, 2, 3000, 700), (2, 1, 2000, 513), (1, 1, 1500, 64), (2, 2, 5003, 1100),
+                                                (1, 1, 900, 31), (1, 2, 4000, 1024), (2, 1, 2500, 900), (1, 1, 1300, 1300)]):
+        q, K, V = rand_case(40 + G, B, Hkv, G, 128, N)
+        rng = np.random.RandomState(10 * variant + G)
+        idx = np.stack([[np.sort(rng.permutation(N)[:k]) for _ in range(Hkv)] for _ in range(B)]).astype(np.int32)
+        idx[:, :, ::7] = -1                      # padding entries
+        idx[:, :, 5::41] = N + 3
+        ref = oracle.reuse_sparse_attn(q, K, V, np.where(idx >= N, -1, idx))
+        with binding.Context(B, Hkv * G, Hkv, 128, N, k) as ctx:
+            ctx.set_option("reuse_variant", variant)
+            ctx.set_option("reuse_waves", waves)
+            for split_rows in (0, 2048):
+                ctx.set_option("reuse_split_rows", split_rows)
+                out = ctx.reuse_sparse_attn(q, K, V, torch.from_numpy(idx).to(DEV))
+                torch.cuda.synchronize()
+                assert_out_close(out.cpu().numpy(), ref, "reuse out G=%d split_rows=%d" % (G, split_rows))
+
+
 @pytest.mark.parametrize("split_rows", [128, 256, 4096])
 def test_full_result_does_not_depend_on_split(split_rows):
     say("full split_rows=%d" % split_rows)
