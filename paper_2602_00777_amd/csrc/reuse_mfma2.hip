@@ -1,9 +1,12 @@
 // Reuse layer (Algorithm 2, Reuse branch; attention as in Eq. 1) for head_dim 128, second
 // matrix-core form.  Same decomposition and cross-workgroup merge as reuse_mfma.hip; what
-// differs is the V side of a wave's work:
+// differs is how the rows are fetched and how V is contracted:
 //
-//   K rows   loaded as before, lane = row of a 16-row block, and contracted with q by
-//            v_mfma_f32_16x16x32_bf16; the scores of a block come back as lane = head,
+//   K rows   contracted with q by v_mfma_f32_16x16x32_bf16 with lane = row of a 16-row block,
+//            which taken literally makes every load instruction touch 16 rows with only 64
+//            bytes each.  Instead lanes n and n ^ 8 fetch the two halves of one 128-byte line
+//            of the same row, and a row_ror:8 register move per loaded dword then gives every
+//            lane the pieces of its own row.  The scores of a block come back as lane = head,
 //            registers = rows 4 gq .. 4 gq + 3 of the block.
 //   V rows   loaded with 16 lanes per row (one instruction reads four whole 256-byte rows):
 //            lane (n, gq) fetches, for the two blocks a, b of a 32-row group, columns
@@ -30,6 +33,22 @@ DEVI uint32_t pack_lo(uint32_t x, uint32_t y) { return __builtin_amdgcn_perm(y, 
 DEVI uint32_t pack_hi(uint32_t x, uint32_t y) { return __builtin_amdgcn_perm(y, x, 0x07060302u); }
 
 DEVI uint32_t dword_of(const uint4& v, int w) { return w == 0 ? v.x : w == 1 ? v.y : w == 2 ? v.z : v.w; }
+
+// Within every 16-lane row: the lanes of the banks in MASK (bit b = lanes 4b .. 4b+3) receive
+// src from the lane 8 places away, the others keep old (v_mov_b32 with row_ror:8).
+template <int MASK>
+DEVI int rotate_in(int old, int src) { return __builtin_amdgcn_update_dpp(old, src, 0x128, 0xF, MASK, false); }
+
+// k[2L], k[2L+1]: the two loads of line L as issued (see the K loads of the kernel).  On
+// return k[s] is the lane's own row n, columns 32 s + 8 gq .. + 7, for s = 0..3.
+DEVI void own_row(uint4 (&k)[4]) {
+#pragma unroll
+    for (int L = 0; L < 2; ++L) {
+        const uint4 a = k[2 * L], b = k[2 * L + 1];
+        k[2 * L] = make_uint4(rotate_in<0xC>(a.x, b.x), rotate_in<0xC>(a.y, b.y), rotate_in<0xC>(a.z, b.z), rotate_in<0xC>(a.w, b.w));
+        k[2 * L + 1] = make_uint4(rotate_in<0x3>(b.x, a.x), rotate_in<0x3>(b.y, a.y), rotate_in<0x3>(b.z, a.z), rotate_in<0x3>(b.w, a.w));
+    }
+}
 
 // v[j] = eight consecutive bf16 columns of row j (j = 0..7).  t[e] = column e of the eight rows.
 DEVI void transpose8x8(const uint4 (&v)[8], uint4 (&t)[8]) {
@@ -215,9 +234,19 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 #pragma unroll
         for (int blk = 0; blk < NB; ++blk) {
             valid[blk] = (unsigned)row[blk] < (unsigned)p.N;       // negative or >= N: padding
-            const int64_t off = (int64_t)(valid[blk] ? row[blk] : 0) * p.sn + 8 * gq;
+            // K: lanes n and n ^ 8 read the two halves of a 128-byte line of one row (row n & 7
+            // of the block in the first load of a line, row 8 + (n & 7) in the second), so that
+            // eight lanes cover a whole line; own_row() afterwards hands every lane the pieces of
+            // its own row n.
+            const int ra = rotate_in<0xC>(row[blk], row[blk]);      // lanes 8..15: from lane n - 8
+            const int rb = rotate_in<0x3>(row[blk], row[blk]);      // lanes 0..7: from lane n + 8
+            const int64_t offa = (int64_t)((unsigned)ra < (unsigned)p.N ? ra : 0) * p.sn + 32 * (n >> 3) + 8 * gq;
+            const int64_t offb = (int64_t)((unsigned)rb < (unsigned)p.N ? rb : 0) * p.sn + 32 * (n >> 3) + 8 * gq;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) kb[blk][i] = ld16<NT>(Kb + off + 32 * i);
+            for (int L = 0; L < 2; ++L) {
+                kb[blk][2 * L] = ld16<NT>(Kb + offa + 64 * L);
+                kb[blk][2 * L + 1] = ld16<NT>(Kb + offb + 64 * L);
+            }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 // row 4 gq + j of the block: its number sits in lane 4 gq + j
@@ -245,6 +274,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
                 v8[j] = vb[2 * gp][j];
                 v8[4 + j] = vb[2 * gp + 1][j];
             }
+            own_row(kb[2 * gp]);
+            own_row(kb[2 * gp + 1]);
             group32<G>(st, kb[2 * gp], kb[2 * gp + 1], v8, qb, mask_a, mask_b, p.scale_log2, n, gq);
         }
         HYLRA_TS(2);
