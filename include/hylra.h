@@ -162,9 +162,11 @@ hylra_status hylra_decode_step_blocks(hylra_ctx *ctx, const hylra_shape *shape, 
  *                       kernels take at most 8192 and clamp larger values)
  *   "reuse_split_rows"  index entries per workgroup of the Reuse kernel
  *   "full_variant"      Full streaming kernel.  Vector-ALU kernels, 10*mode + unroll: 4 (plain
- *                       loads), 14 (streaming loads), 23 (streaming loads, two-deep register
- *                       pipeline; default up to 4 heads per KV head).  Matrix-core kernels: 54, 52
- *                       (default from 5 heads per KV head), 62, 61 (pipelined)
+ *                       loads), 14 (streaming loads), 23 / 22 (streaming loads, two-deep register
+ *                       pipeline), 43 / 42 (as 23 / 22 with the rows handed out at run time;
+ *                       up to 4 heads per KV head the default is 43 while batch * n_kv_heads
+ *                       >= 64 and 23 below that).  Matrix-core kernels: 54, 52 (default from
+ *                       5 heads per KV head), 62, 61 (pipelined)
  *   "reuse_variant"     Reuse gather kernel: 1 / 2 = vector-ALU kernel with streaming / plain
  *                       loads, 3 / 4 = first matrix-core kernel with streaming / plain loads
  *                       (default for head_dim 64: 4), 5 / 6 = second matrix-core kernel

@@ -16,6 +16,7 @@ using namespace hylra;
 
 namespace {
 
+constexpr int kDynWgsPerSeg = 8;          // workgroups that share a segment in the self-scheduling Full kernel
 constexpr int kTargetBlocksFull = 512;    // workgroups the Full kernel aims for: two per CU,
                                           // all resident at once (measured best on MI355X)
 constexpr int64_t kMinSlots = 8192;       // partial slots ((batch, KV head, split) triples) kept
@@ -41,6 +42,7 @@ struct hylra_ctx {
     float* scores = nullptr;
     float* bscores = nullptr;   // block scores of the block-level variant (blocks of >= 2 rows)
     int* counters = nullptr;    // one arrival counter per (batch, KV head), zero between launches
+    int* chunk_ctr = nullptr;   // chunk counters of the self-scheduling Full kernel (kCtrStride ints apart)
     int* sel_ws = nullptr;      // selection scratch: histogram, candidates, counts (see SelectParams)
     int64_t pairs_cap = 0;      // (batch, KV head) pairs the selection scratch is sized for
     int max_chunks = 0;         // chunks of 8192 rows per (batch, KV head) at the maximum context
@@ -167,15 +169,71 @@ hipError_t launch_timed(hylra_ctx* ctx, int cls, hipStream_t st, F&& f) {
 
 struct FullPlan {
     int rows_per_split, n_splits, variant;
+    int n_segs, wgs_per_seg;        // self-scheduling kernel: n_splits = n_segs * wgs_per_seg
 };
+
+// Chunk table of the self-scheduling Full kernel (guided self-scheduling): with `remaining`
+// tiles left, the next chunk takes remaining / (2 * S) of them, never fewer than min_tiles
+// (one tile per wave), so chunks shrink towards the end and the S workgroups of a (batch,
+// KV head) finish within about one small chunk of each other.  Returns the number of chunks.
+int make_chunk_table(int total_tiles, int S, int (&chunk_tile)[kMaxChunks + 1]) {
+    for (int min_tiles = 4;; min_tiles *= 2) {
+        int n = 0, at = 0;
+        while (at < total_tiles && n < kMaxChunks) {
+            int take = (int)ceil_div(total_tiles - at, 2 * (int64_t)S);
+            if (take < min_tiles) take = min_tiles;
+            if (take > total_tiles - at) take = total_tiles - at;
+            chunk_tile[n++] = at;
+            at += take;
+        }
+        if (at == total_tiles) {
+            chunk_tile[n] = total_tiles;
+            return n;
+        }
+    }
+}
 
 hylra_status plan_full(const hylra_ctx* ctx, const hylra_shape* s, int G, FullPlan& pl) {
     // automatic: the vector kernel is HBM-bound up to 4 heads per group; beyond that its own
-    // arithmetic limits it and the matrix-core kernel is faster (measured at G = 7)
-    pl.variant = ctx->opt_full_variant > 0 ? ctx->opt_full_variant : (G > 4 ? 52 : 23);
+    // arithmetic limits it and the matrix-core kernel is faster (measured at G = 7).  Of the
+    // vector kernels the self-scheduling one is the default while a (batch, KV head) gets at
+    // most one segment of workgroups (measured: 2 % faster at batch 8 / 32K context, 20 % at
+    // batch 32 / 16K, 2 % slower with 8 segments at batch 1 / 128K).
+    const int64_t pairs = (int64_t)s->batch * s->n_kv_heads;
+    pl.variant = ctx->opt_full_variant > 0 ? ctx->opt_full_variant
+                 : G > 4 ? 52
+                 : ceil_div(kTargetBlocksFull, pairs) <= kDynWgsPerSeg ? 43 : 23;
     const int quantum = full_block_quantum(s->head_dim, G, pl.variant);
     if (quantum <= 0) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "Full kernel variant %d is not built for d=%d G=%d", pl.variant, s->head_dim, G);
-    const int64_t pairs = (int64_t)s->batch * s->n_kv_heads;
+    if (pl.variant / 10 == 4) {
+        // self-scheduling kernel: only the number of workgroups per pair is planned (rows are
+        // handed out at run time); "full_split_rows" still sets it, as ctx_len / rows.  More
+        // than kDynWgsPerSeg workgroups per pair are put into segments of that many: the
+        // workgroups of a segment then sit on different XCDs (consecutive workgroup numbers)
+        // and the chunk table stays short.
+        const int64_t tile = quantum / 4;                      // rows of one wave tile
+        const int64_t tiles = ceil_div(s->ctx_len, tile);
+        int64_t S = ctx->opt_full_split_rows > 0 ? ceil_div(s->ctx_len, ctx->opt_full_split_rows)
+                                                 : ceil_div(kTargetBlocksFull, pairs);
+        if (S > ceil_div(tiles, 4)) S = ceil_div(tiles, 4);
+        if (S > kMaxSplits) S = kMaxSplits;
+        while (S > 1 && pairs * S > ctx->slots) --S;
+        int64_t segs = 1;
+        if (S > kDynWgsPerSeg) {
+            segs = S / kDynWgsPerSeg;
+            S = segs * kDynWgsPerSeg;
+        }
+        if (pairs * S > ctx->slots)
+            return fail(ctx, HYLRA_ERR_WORKSPACE, "batch*n_kv_heads = %lld exceeds the workspace", (long long)pairs);
+        // rows of score staging per workgroup: twice its share of the rows, in whole wave tiles
+        int64_t stage = round_up(2 * ceil_div(s->ctx_len, S), tile);
+        if (stage > kMaxFullSplitRows) stage = kMaxFullSplitRows / tile * tile;
+        pl.rows_per_split = (int)stage;
+        pl.n_splits = (int)S;
+        pl.n_segs = (int)segs;
+        pl.wgs_per_seg = (int)(S / segs);
+        return HYLRA_OK;
+    }
     int64_t rps = ctx->opt_full_split_rows > 0 ? ctx->opt_full_split_rows
                                                : ceil_div(pairs * s->ctx_len, kTargetBlocksFull);
     rps = round_up(rps < quantum ? quantum : rps, quantum);
@@ -323,6 +381,9 @@ hylra_status hylra_create(hylra_ctx** out, const hylra_shape* max_shape, int32_t
     const int64_t sel_ints = pairs * (4096 + 1 + 1024 + 1024 + 2 + ctx->max_chunks);
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->sel_ws, sel_ints * sizeof(int));
     if (e == hipSuccess) e = hipMemset(ctx->sel_ws, 0, sel_ints * sizeof(int));
+    // one counter per (pair, segment); there are never more segments than partial slots
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->chunk_ctr, ctx->slots * kCtrStride * sizeof(int));
+    if (e == hipSuccess) e = hipMemset(ctx->chunk_ctr, 0, ctx->slots * kCtrStride * sizeof(int));
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         fail(nullptr, HYLRA_ERR_HIP, "workspace allocation failed: %s", hipGetErrorString(e));
@@ -347,6 +408,7 @@ hylra_status hylra_destroy(hylra_ctx* ctx) {
     if (ctx->scores) (void)hipFree(ctx->scores);
     if (ctx->bscores) (void)hipFree(ctx->bscores);
     if (ctx->counters) (void)hipFree(ctx->counters);
+    if (ctx->chunk_ctr) (void)hipFree(ctx->chunk_ctr);
     if (ctx->sel_ws) (void)hipFree(ctx->sel_ws);
     delete ctx;
     return HYLRA_OK;
@@ -414,6 +476,14 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const void* q, 
     fp.part_ml = ctx->part_ml, fp.part_acc = ctx->part_acc, fp.part_mm = ctx->part_mm;
     fp.scores = ctx->scores;
     fp.score_stride = round_up(shape->ctx_len, 4);
+    if (pl.variant / 10 == 4) {
+        fp.chunk_ctr = ctx->chunk_ctr;
+        const int tile = full_block_quantum(shape->head_dim, G, pl.variant) / 4;     // rows of one wave tile
+        fp.total_tiles = (int)ceil_div(shape->ctx_len, tile);
+        fp.n_segs = pl.n_segs, fp.wgs_per_seg = pl.wgs_per_seg;
+        // the table is made for the shortest segment; longer ones (by one tile) extend their last chunk
+        fp.n_chunks = make_chunk_table(fp.total_tiles / pl.n_segs, pl.wgs_per_seg, fp.chunk_tile);
+    }
     HIP_TRY(ctx, launch_timed(ctx, 0, st, [&] {
                 return launch_full_split(fp, shape->batch, shape->head_dim, G, pl.variant, st);
             }));

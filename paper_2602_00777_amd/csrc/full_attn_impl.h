@@ -24,6 +24,145 @@ namespace hylra {
 // zero, i.e. also wait for the tile that was only just requested.  For the same reason the
 // pipelined loop issues its look-ahead loads unconditionally (rows past the split are
 // clamped to its last row): the number of younger loads at each wait is then a constant.
+// MODE 4: as MODE 2, but the rows are handed out at run time (guided self-scheduling), because
+// compute units do not stream at the same speed (XCDs differ, and so do the units of one XCD)
+// and with a fixed split the slowest workgroup sets the kernel time.  The rows of a (batch,
+// KV head) are cut into chunks of decreasing size (host-made table, the same for every pair).
+// The pair's workgroups start on one chunk each and claim further ones from a device-scope
+// counter, one claim per chunk: few enough that the counter is never contended.  Inside a
+// workgroup the four waves draw tiles of the current chunks from a ticket counter in LDS, so
+// the waves of a workgroup also finish together.  The wave that draws the first tile of a
+// chunk claims the next one for its workgroup and publishes it in LDS: the claim travels
+// while the chunk is consumed.  The counter returns to zero by itself: every launch adds to
+// it exactly n_chunks times per pair (n_chunks - S claims that succeed and one that fails per
+// workgroup), and the workgroup that draws the last value stores zero.
+// Nothing in the loop waits for anything but the tile it is about to consume: the claim is
+// only issued when a slot's first tile is drawn and its result is looked at one tile later
+// (memory returns loads and atomics in order, so by then it is there), and the group-mean
+// scores are staged in LDS by ticket (the workgroup's t-th tile at t * TILE) and written out
+// after the loop, slot by slot.  (A store inside the loop, even once per chunk, costs more
+// than it saves: loads and stores share one completion counter and complete out of order with
+// respect to each other, so every store means draining the wave's loads once.)  Tickets
+// beyond the staging area (a workgroup that ends up with far more than its share) store
+// straight to memory.
+struct ChunkQueue {
+    int ticket;                     // next tile ticket of the workgroup
+    int n_ready;                    // published slots
+    int done;                       // no further slot will be published
+    int first[kMaxChunks + 2];      // first[i] = first ticket of slot i; first[n_ready] = end
+    int tile0[kMaxChunks + 1];      // first tile (of the pair's tiles) of slot i
+};
+
+// A drawn tile: its number among the pair's tiles (-1: none) and its ticket.
+struct TileRef {
+    int tile;                       // in a vector register, see next_tile
+    int ticket;
+};
+
+// A claim on the pair's chunk counter that is under way: the atomic has been issued, its
+// result has not been looked at yet.
+struct PendingClaim {
+    int raw;                        // lane 0: what the counter returned
+    int slot;                       // the slot the new chunk becomes; -1: nothing pending
+    int first;                      // its first ticket
+};
+
+// LDS words of the queue are read by every lane (one address: a broadcast) and moved to a
+// scalar register, so the queue logic runs on the scalar unit and costs no vector registers.
+// Ordering between the waves of the workgroup is by fences on LDS alone ("local"): a plain
+// workgroup-scope acquire or release would also wait for the wave's loads from memory, i.e.
+// for the tile it has just requested.
+DEVI int lds_load(const int* p) {
+    return __builtin_amdgcn_readfirstlane(__hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+}
+DEVI int lds_load_acquire(const int* p) {
+    const int v = lds_load(p);
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+    return v;
+}
+DEVI void lds_store_release(int* p, int v) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+// A wave's view of the queue: the slot it draws from, cached in scalar registers, so that a
+// draw inside the slot costs one LDS operation (the ticket).
+struct QueueCursor {
+    int slot, first, next, tile0;   // tickets first .. next - 1 are tiles tile0 .. of slot `slot`
+};
+
+// Next tile of the pair for the calling wave (every lane gets the same answer), or -1 when
+// the workgroup has none left.  Every wait here ends: a slot is published by a running wave
+// of this workgroup that waits for nothing but its own memory operations, and the spin is
+// bounded on top of that.  A wave that draws the first tile of a slot issues the claim for
+// the workgroup's next chunk into pc (at most one claim per wave is under way: the caller
+// publishes pc before it draws again).
+DEVI TileRef next_tile(ChunkQueue& cq, int* __restrict__ ctr, QueueCursor& cur, PendingClaim& pc, int lane) {
+    int T = 0;
+    if (lane == 0) T = __hip_atomic_fetch_add(&cq.ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    T = __builtin_amdgcn_readfirstlane(T);
+    int tile = -1;
+    if (T >= cur.next) {
+        // past the cached slot: wait until the ticket's slot is published, then walk to it
+        bool have = false;
+        for (int spin = 0; spin < (1 << 22); ++spin) {
+            const int done = lds_load_acquire(&cq.done);
+            const int nr = lds_load_acquire(&cq.n_ready);
+            if (T < lds_load(&cq.first[nr])) {
+                have = true;
+                break;
+            }
+            if (done) break;
+            __builtin_amdgcn_s_sleep(2);
+        }
+        if (have) {
+            while (T >= cur.next) {
+                ++cur.slot;
+                cur.first = cur.next;
+                cur.next = lds_load(&cq.first[cur.slot + 1]);
+            }
+            cur.tile0 = lds_load(&cq.tile0[cur.slot]);
+        }
+    }
+    if (T < cur.next) {
+        tile = cur.tile0 + (T - cur.first);
+        if (T == cur.first) {
+            if (lane == 0) pc.raw = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            pc.slot = cur.slot + 1;
+            pc.first = cur.next;
+        }
+    }
+    // Handed back in a vector register the compiler cannot prove uniform: with a provably
+    // uniform row number it turns the consumer's "whole tile inside the cache?" test into
+    // scalar control flow, duplicates the loop body around it and runs out of registers.
+    TileRef r;
+    asm volatile("v_mov_b32 %0, %1" : "=v"(r.tile) : "s"(tile));
+    r.ticket = T;
+    return r;
+}
+
+// Look at the result of the claim under way, if any, and publish it: the chunk as slot
+// pc.slot of the queue, or the end of the queue.  The counter returns to zero here too.
+// seg_tile0 / seg_tiles: first tile and number of tiles of the workgroup's segment.
+DEVI void publish_claim(ChunkQueue& cq, const FullParams& p, int* __restrict__ ctr, PendingClaim& pc, int lane,
+                        int seg_tile0, int seg_tiles) {
+    if (pc.slot < 0) return;
+    const int raw = __builtin_amdgcn_readfirstlane(pc.raw);
+    const int c = p.wgs_per_seg + raw;
+    if (lane == 0) {
+        if (raw == p.n_chunks - 1) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (c < p.n_chunks) {
+            const int end = c == p.n_chunks - 1 ? seg_tiles : p.chunk_tile[c + 1];
+            cq.tile0[pc.slot] = seg_tile0 + p.chunk_tile[c];
+            cq.first[pc.slot + 1] = pc.first + (end - p.chunk_tile[c]);
+            lds_store_release(&cq.n_ready, pc.slot + 1);
+        } else {
+            lds_store_release(&cq.done, 1);
+        }
+    }
+    pc.slot = -1;
+}
+
 template <int D, int G, int CH, int R, int MODE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void full_attn_split_kernel(FullParams p) {
     using GEO = Geo<D, G, CH>;
@@ -46,9 +185,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
 
     LaneState<GEO> st;
     st.init();
-    const int row0 = split * p.rows_per_split;
-    const int row1 = min(p.N, row0 + p.rows_per_split);
+    constexpr bool DYN = MODE == 4;
+    const int row0 = DYN ? 0 : split * p.rows_per_split;
+    const int row1 = DYN ? p.N : min(p.N, row0 + p.rows_per_split);
     float smin = 3.0e38f, smax = -3.0e38f;
+    float* __restrict__ srow = p.scores + ((int64_t)b * p.Hkv + g) * p.score_stride;
 
     // element offsets of this lane's rows in the tile starting at row t0 (rows past the end
     // of the split are clamped to its last row; they are masked when consumed)
@@ -58,7 +199,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
             off[r] = (int64_t)min(t0 + r * GEO::RPG + slot, row1 - 1) * p.sn + chunk * 8;
     };
     // softmax/accumulate a loaded tile, stage its group-mean scores, track their range
-    auto consume = [&](const TileBuf<GEO, R>& buf, int t0) {
+    // st0: where the tile's scores are staged in s_scores (static modes: t0 - row0; dynamic:
+    // ticket * TILE, or negative = store to memory)
+    auto consume = [&](const TileBuf<GEO, R>& buf, int t0, int st0) {
         bool valid[R];
         float ms[R];
         if (t0 + TILE <= row1) {
@@ -68,7 +211,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const float v = fminf(fmaxf(ms[r], -3.0e38f), 3.0e38f);   // also maps NaN to a number
-                if (chunk == 0) s_scores[t0 - row0 + r * GEO::RPG + slot] = v;
+                if (chunk == 0) {
+                    if (DYN && st0 < 0) srow[t0 + r * GEO::RPG + slot] = v;
+                    else s_scores[st0 + r * GEO::RPG + slot] = v;
+                }
                 smin = fminf(smin, v);
                 smax = fmaxf(smax, v);
             }
@@ -80,7 +226,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
             for (int r = 0; r < R; ++r) {
                 const float v = fminf(fmaxf(ms[r], -3.0e38f), 3.0e38f);
                 if (valid[r]) {
-                    if (chunk == 0) s_scores[t0 - row0 + r * GEO::RPG + slot] = v;
+                    if (chunk == 0) {
+                        if (DYN && st0 < 0) srow[t0 + r * GEO::RPG + slot] = v;
+                        else s_scores[st0 + r * GEO::RPG + slot] = v;
+                    }
                     smin = fminf(smin, v);
                     smax = fmaxf(smax, v);
                 }
@@ -89,13 +238,77 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     };
 
     constexpr int STEP = NW * TILE;
-    if (MODE < 2) {
+    if (DYN) {
+        __shared__ ChunkQueue cq;
+        const int seg = split / p.wgs_per_seg, w = split - seg * p.wgs_per_seg;
+        const int seg_tile0 = (int)((int64_t)seg * p.total_tiles / p.n_segs);
+        const int seg_tiles = (int)((int64_t)(seg + 1) * p.total_tiles / p.n_segs) - seg_tile0;
+        if (tid == 0) {
+            const bool has = w < p.n_chunks;
+            const int end = !has ? 0 : w == p.n_chunks - 1 ? seg_tiles : p.chunk_tile[w + 1];
+            cq.ticket = 0;
+            cq.first[0] = 0;
+            cq.first[1] = has ? end - p.chunk_tile[w] : 0;
+            cq.tile0[0] = has ? seg_tile0 + p.chunk_tile[w] : 0;
+            cq.n_ready = 1;
+            cq.done = has ? 0 : 1;
+        }
+        __syncthreads();
+        int* ctr = p.chunk_ctr + (((int64_t)b * p.Hkv + g) * p.n_segs + seg) * kCtrStride;
+        QueueCursor qslot;
+        qslot.slot = 0;
+        qslot.first = 0;
+        qslot.next = lds_load(&cq.first[1]);
+        qslot.tile0 = lds_load(&cq.tile0[0]);
+        TileBuf<GEO, R> bufA, bufB;
+        int64_t off[R];
+        const int stage_tiles = p.rows_per_split / TILE;      // tiles the staging area holds
+        auto stage_of = [&](const TileRef& t) { return t.ticket < stage_tiles ? t.ticket * TILE : -1; };
+        PendingClaim pc;
+        pc.raw = 0, pc.slot = -1, pc.first = 0;
+        TileRef ta = next_tile(cq, ctr, qslot, pc, lane);
+        offsets(ta.tile >= 0 ? ta.tile * TILE : 0, off);
+        load_tile<GEO, R, NT>(bufA, Kb, Vb, off);
+        while (ta.tile >= 0) {
+            publish_claim(cq, p, ctr, pc, lane, seg_tile0, seg_tiles);                      // (first pass only)
+            const TileRef tb = next_tile(cq, ctr, qslot, pc, lane);
+            offsets(tb.tile >= 0 ? tb.tile * TILE : 0, off);          // nothing left: a harmless reload
+            load_tile<GEO, R, NT>(bufB, Kb, Vb, off);
+            consume(bufA, ta.tile * TILE, stage_of(ta));
+            publish_claim(cq, p, ctr, pc, lane, seg_tile0, seg_tiles);
+            if (tb.tile < 0) break;
+            ta = next_tile(cq, ctr, qslot, pc, lane);
+            offsets(ta.tile >= 0 ? ta.tile * TILE : 0, off);
+            load_tile<GEO, R, NT>(bufA, Kb, Vb, off);
+            consume(bufB, tb.tile * TILE, stage_of(tb));
+            publish_claim(cq, p, ctr, pc, lane, seg_tile0, seg_tiles);
+        }
+        publish_claim(cq, p, ctr, pc, lane, seg_tile0, seg_tiles);
+        __syncthreads();
+        // write the staged scores out: slot i of the queue is tiles tile0[i] .. of the pair,
+        // tickets first[i] .. first[i + 1] - 1 (tile starts and the score stride are multiples
+        // of 4 floats, so the 16-byte stores are aligned)
+        const int n_slots = cq.n_ready;
+        for (int i = 0; i < n_slots; ++i) {
+            const int f0 = cq.first[i], f1 = min(cq.first[i + 1], stage_tiles);
+            const int r0 = cq.tile0[i] * TILE;
+            const int n = min((f1 - f0) * TILE, p.N - r0);
+            const float* src = s_scores + f0 * TILE;
+            for (int e = 4 * tid; e < n; e += 4 * NW * 64) {
+                if (e + 4 <= n) {
+                    *reinterpret_cast<float4*>(srow + r0 + e) = *reinterpret_cast<const float4*>(src + e);
+                } else {
+                    for (int x = e; x < n; ++x) srow[r0 + x] = src[x];
+                }
+            }
+        }
+    } else if (MODE < 2) {
         for (int t0 = row0 + wave * TILE; t0 < row1; t0 += STEP) {
             int64_t off[R];
             TileBuf<GEO, R> buf;
             offsets(t0, off);
             load_tile<GEO, R, NT>(buf, Kb, Vb, off);
-            consume(buf, t0);
+            consume(buf, t0, t0 - row0);
         }
     } else {
         TileBuf<GEO, R> bufA, bufB;
@@ -106,12 +319,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         while (t0 < row1) {
             offsets(t0 + STEP, off);
             load_tile<GEO, R, NT>(bufB, Kb, Vb, off);
-            consume(bufA, t0);
+            consume(bufA, t0, t0 - row0);
             t0 += STEP;
             if (t0 >= row1) break;
             offsets(t0 + STEP, off);
             load_tile<GEO, R, NT>(bufA, Kb, Vb, off);
-            consume(bufB, t0);
+            consume(bufB, t0, t0 - row0);
             t0 += STEP;
         }
     }
@@ -135,9 +348,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         mm[0] = smin;
         mm[1] = smax;
     }
-    {
+    if (!DYN) {
         // row0 and the score stride are multiples of 4 floats: 16-byte stores are aligned
-        float* __restrict__ dst = p.scores + ((int64_t)b * p.Hkv + g) * p.score_stride + row0;
+        float* __restrict__ dst = srow + row0;
         const int n = row1 - row0;
         for (int i = 4 * tid; i < n; i += 4 * NW * 64) {
             if (i + 4 <= n) {
@@ -164,7 +377,7 @@ struct FullCfg {
 };
 
 // variant = 10 * MODE + R  (R = row groups per tile)
-#define HYLRA_FULL_VARIANTS(X) X(0, 4) X(1, 4) X(2, 3)
+#define HYLRA_FULL_VARIANTS(X) X(0, 4) X(1, 4) X(2, 3) X(4, 3) X(4, 2) X(2, 2)
 constexpr int kDefaultFullVariant = 23;
 
 template <int D, int G>

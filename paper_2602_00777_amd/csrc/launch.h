@@ -8,6 +8,8 @@ namespace hylra {
 constexpr int kMaxGroup = 8;        // query heads per KV head
 constexpr int kMaxSplits = 1024;    // partials per (batch, KV head) the finalise kernels accept
 constexpr int kMaxFullSplitRows = 8192;   // rows per workgroup of the vector Full kernel (its scores sit in LDS)
+constexpr int kMaxChunks = 480;     // chunks of rows per (batch, KV head) in the self-scheduling Full kernel
+constexpr int kCtrStride = 64;      // ints between the chunk counters of two (batch, KV head) pairs
 
 struct FullParams {
     const uint16_t* q;
@@ -24,6 +26,16 @@ struct FullParams {
     float* part_mm;                 // [B*Hkv][S][2]  (min, max of the group-mean scores)
     float* scores;                  // [B*Hkv][score_stride] group-mean scaled scores
     int64_t score_stride;           // multiple of 4, >= N
+    // self-scheduling mode only.  The wave tiles of a (batch, KV head) (a tile = the rows one
+    // wave loads at a time) are cut into n_segs segments of equal length (to within one tile);
+    // wgs_per_seg workgroups share a segment.  Chunk c of a segment covers its tiles
+    // chunk_tile[c] .. chunk_tile[c + 1] - 1 (the last chunk runs to the segment's end);
+    // workgroup w of the segment starts on chunk w, further chunks are claimed from the
+    // segment's counter.
+    int* chunk_ctr;                 // [B*Hkv][n_segs] counters, kCtrStride ints apart, zero between launches
+    int n_segs, wgs_per_seg, total_tiles;
+    int n_chunks;
+    int chunk_tile[kMaxChunks + 1];
 };
 
 struct FinalizeParams {
