@@ -189,13 +189,14 @@ hylra_status hylra_set_option(hylra_ctx *ctx, const char *name, int32_t value);
  * Measurement aids (not on the hot path).
  *
  * hylra_profile_enable(ctx, 1) makes every later kernel launch of this context
- * be bracketed by a pair of HIP events on the launch stream; hylra_profile_read
- * synchronises those events and returns, per kernel class, the number of
- * launches and the summed duration in milliseconds since the last
- * hylra_profile_reset.  Classes: 0 = Full attention (split-KV pass),
+ * be bracketed by a pair of HIP events on the launch stream (consecutive
+ * launches of one class on one stream share one pair, so a launch is charged
+ * what it costs back to back); hylra_profile_read synchronises those events
+ * and returns, per kernel class, the number of launches and the summed
+ * duration in milliseconds since the last hylra_profile_reset.  Classes: 0 = Full attention (split-KV pass),
  * 1 = Full finalise (combine + top-k; all its launches), 2 = Reuse attention, 3 = Reuse combine (absent
- * in the fused mode), 4 = probe kernels.  At most HYLRA_PROFILE_MAX_EVENTS launches are recorded
- * between resets; later ones run untimed.
+ * in the fused mode), 4 = probe kernels.  At most HYLRA_PROFILE_MAX_EVENTS event pairs are recorded
+ * between resets; later launches run untimed.
  */
 #define HYLRA_PROFILE_CLASSES 5
 #define HYLRA_PROFILE_MAX_EVENTS 4096

@@ -67,6 +67,9 @@ struct hylra_ctx {
     int prof_n = 0;
     hipEvent_t* prof_ev = nullptr;          // 2 * HYLRA_PROFILE_MAX_EVENTS, created on first enable
     uint8_t prof_cls[HYLRA_PROFILE_MAX_EVENTS];
+    int32_t prof_cnt[HYLRA_PROFILE_MAX_EVENTS];      // launches inside bracket i
+    bool prof_open = false;                          // the last bracket still lacks its end event
+    hipStream_t prof_stream = nullptr;               // stream of the open bracket
 
     mutable char err[256] = "";
 };
@@ -149,22 +152,38 @@ hylra_status check_tensors(const hylra_ctx* ctx, const void* q, const void* K, c
     return HYLRA_OK;
 }
 
-// Runs a launch, bracketed by events when profiling is on.
+// Ends the open event bracket, if any, on the stream it was opened on.
+hipError_t close_bracket(hylra_ctx* ctx) {
+    if (!ctx->prof_open) return hipSuccess;
+    ctx->prof_open = false;
+    return hipEventRecord(ctx->prof_ev[2 * (ctx->prof_n - 1) + 1], ctx->prof_stream);
+}
+
+// Runs a launch, timed by events when profiling is on.  Consecutive launches of one class on
+// one stream share a bracket (start event before the first, end event after the last): the
+// events then cost nothing between the launches, and the bracket's time divided by its
+// launches is what one launch costs back to back, gaps included.
 template <class F>
 hipError_t launch_timed(hylra_ctx* ctx, int cls, hipStream_t st, F&& f) {
-    if (ctx->prof_on && ctx->prof_n < HYLRA_PROFILE_MAX_EVENTS) {
-        const int n = ctx->prof_n;
-        hipError_t e = hipEventRecord(ctx->prof_ev[2 * n], st);
-        if (e != hipSuccess) return e;
-        e = f();
-        if (e != hipSuccess) return e;
-        e = hipEventRecord(ctx->prof_ev[2 * n + 1], st);
-        if (e != hipSuccess) return e;
-        ctx->prof_cls[n] = (uint8_t)cls;
-        ctx->prof_n = n + 1;
-        return hipSuccess;
+    if (!ctx->prof_on) return f();
+    if (ctx->prof_open && ctx->prof_cls[ctx->prof_n - 1] == cls && ctx->prof_stream == st) {
+        ++ctx->prof_cnt[ctx->prof_n - 1];
+        return f();
     }
-    return f();
+    hipError_t e = close_bracket(ctx);
+    if (e != hipSuccess) return e;
+    if (ctx->prof_n >= HYLRA_PROFILE_MAX_EVENTS) return f();
+    const int n = ctx->prof_n;
+    e = hipEventRecord(ctx->prof_ev[2 * n], st);
+    if (e != hipSuccess) return e;
+    e = f();
+    if (e != hipSuccess) return e;
+    ctx->prof_cls[n] = (uint8_t)cls;
+    ctx->prof_cnt[n] = 1;
+    ctx->prof_n = n + 1;
+    ctx->prof_open = true;
+    ctx->prof_stream = st;
+    return hipSuccess;
 }
 
 struct FullPlan {
@@ -679,12 +698,17 @@ hylra_status hylra_profile_enable(hylra_ctx* ctx, int32_t on) {
         if (!ctx->prof_ev) return fail(ctx, HYLRA_ERR_HIP, "out of host memory");
         for (int i = 0; i < 2 * HYLRA_PROFILE_MAX_EVENTS; ++i) HIP_TRY(ctx, hipEventCreate(&ctx->prof_ev[i]));
     }
+    if (!on) HIP_TRY(ctx, close_bracket(ctx));
     ctx->prof_on = on != 0;
     return HYLRA_OK;
 }
 
 hylra_status hylra_profile_reset(hylra_ctx* ctx) {
     if (!ctx) return HYLRA_ERR_BAD_ARG;
+    {
+        DeviceGuard guard(ctx->device);
+        HIP_TRY(ctx, close_bracket(ctx));
+    }
     ctx->prof_n = 0;
     return HYLRA_OK;
 }
@@ -694,6 +718,7 @@ hylra_status hylra_profile_read(hylra_ctx* ctx, int32_t kernel_class, int32_t* n
     if (kernel_class < 0 || kernel_class >= HYLRA_PROFILE_CLASSES || !n_launches || !total_ms)
         return fail(ctx, HYLRA_ERR_BAD_ARG, "kernel_class outside 0..%d or NULL output", HYLRA_PROFILE_CLASSES - 1);
     DeviceGuard guard(ctx->device);
+    HIP_TRY(ctx, close_bracket(ctx));
     int n = 0;
     double ms = 0.0;
     for (int i = 0; i < ctx->prof_n; ++i) {
@@ -702,7 +727,7 @@ hylra_status hylra_profile_read(hylra_ctx* ctx, int32_t kernel_class, int32_t* n
         float t = 0.f;
         HIP_TRY(ctx, hipEventElapsedTime(&t, ctx->prof_ev[2 * i], ctx->prof_ev[2 * i + 1]));
         ms += t;
-        ++n;
+        n += ctx->prof_cnt[i];
     }
     *n_launches = n;
     *total_ms = ms;
