@@ -43,6 +43,10 @@ def main():
                     help="hylra = the workload's policy; full = every layer Full; jump3 = Full every 3rd layer")
     ap.add_argument("--block", type=int, default=0,
                     help="block-level variant: rows per block (TopK keeps top_k / block blocks); 0 = token level")
+    ap.add_argument("--paged", type=int, default=0,
+                    help="paged KV cache: rows per page (pages scattered over a pool by a random block table); 0 = contiguous")
+    ap.add_argument("--ragged", action="store_true",
+                    help="with --paged: sequence lengths uniform in [N/4, N] instead of all N")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--probe", action="store_true", help="also time the plain copy / read kernels")
     ap.add_argument("--opt", action="append", default=[], help="library option name=value")
@@ -82,6 +86,22 @@ def main():
     log("generated %s: %d layers, %.1f GiB of KV in %.1f s" %
         (w.name, w.n_layers, w.n_layers * w.kv_bytes_per_layer() / 2**30, time.time() - t0))
     qs, Ks, Vs = [x[0] for x in data], [x[1] for x in data], [x[2] for x in data]
+    paged, lens = None, None
+    if args.paged:
+        if args.block:
+            print("bench.py: --paged and --block exclude each other", file=sys.stderr)
+            sys.exit(2)
+        table = synth.page_table(w.batch, w.ctx_len, args.paged, w.seed)
+        n_pages = int(table.max()) + 1
+        for l in range(w.n_layers):             # layer by layer, so that only one extra copy is alive
+            Ks[l] = synth.to_pool(Ks[l], table, args.paged, n_pages)
+            Vs[l] = synth.to_pool(Vs[l], table, args.paged, n_pages)
+            data[l] = None
+        lens = synth.ragged_lengths(w.batch, w.ctx_len, w.seed) if args.ragged else None
+        paged = binding.PagedCache(torch.from_numpy(table).to(dev), args.paged, w.ctx_len,
+                                   torch.from_numpy(lens).to(dev) if lens is not None else None)
+        torch.cuda.synchronize()
+        log("paged: %d pages of %d rows%s" % (n_pages, args.paged, ", ragged lengths %s" % lens.tolist() if lens is not None else ""))
 
     ctx = binding.Context(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ctx_len, w.top_k)
     for o in args.opt:
@@ -91,7 +111,7 @@ def main():
         print("bench.py: --block must divide the workload's top_k (%d)" % w.top_k, file=sys.stderr)
         sys.exit(2)
     k_sel = w.top_k // args.block if args.block else w.top_k
-    run, outs, idx_buf = ctx.prepare_step(policy, qs, Ks, Vs, k_sel, block=args.block)
+    run, outs, idx_buf = ctx.prepare_step(policy, qs, Ks, Vs, k_sel, block=args.block, paged=paged)
 
     for _ in range(args.warmup):
         run()
@@ -119,8 +139,10 @@ def main():
 
     B, Hq, Hkv, d, N, k = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ctx_len, w.top_k
     small = B * Hq * d * 2 + B * Hq * d * 4 + B * Hkv * k_sel * 4     # q + out + idx
-    full_bytes = 4 * B * Hkv * N * d + small
-    reuse_bytes = 4 * B * Hkv * k * d + small
+    rows_total = int(lens.sum()) if lens is not None else B * N        # rows a Full layer attends to
+    sel_total = int(np.minimum(lens, k).sum()) if lens is not None else B * k
+    full_bytes = 4 * Hkv * rows_total * d + small
+    reuse_bytes = 4 * Hkv * sel_total * d + small
 
     def roof(kernel, nbytes):
         kk = kernels.get(kernel)
@@ -130,7 +152,7 @@ def main():
         return {"bound": "hbm", "kernel": kernel, "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
                 "algorithmic_bytes": nbytes, "avg_us": round(kk["avg_us"], 2),
-                "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, kernel))}
+                "traffic": None if args.paged or args.block else MEASURED_TRAFFIC_BYTES.get((w.name, kernel))}
 
     full_time = (kernels.get("full_attn", {}).get("avg_us") or 0) * n_full
     reuse_time = (kernels.get("reuse_attn", {}).get("avg_us") or 0) * n_reuse
@@ -160,7 +182,7 @@ def main():
         del src, dst
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.paged:
         cpu = cpu_baseline(w, policy, qs, Ks, Vs, n_full, n_reuse, args.block)
 
     line = {
@@ -173,7 +195,9 @@ def main():
         "config": {"workload": w.name, "description": w.description, "policy": args.policy,
                    "n_layers": w.n_layers, "full_layers": n_full, "reuse_layers": n_reuse,
                    "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d, "ctx_len": N,
-                   "top_k": k, "block": args.block or 1, "kv_dtype": "bf16", "accumulate": "f32"},
+                   "top_k": k, "block": args.block or 1, "page_size": args.paged or None,
+                   "seq_lens": lens.tolist() if lens is not None else None,
+                   "kv_dtype": "bf16", "accumulate": "f32"},
         "roofline": roofline,
         "roofline_other": other,
         "kernels_us": {n: round(v["avg_us"], 2) for n, v in kernels.items()},

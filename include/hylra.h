@@ -156,6 +156,57 @@ hylra_status hylra_decode_step_blocks(hylra_ctx *ctx, const hylra_shape *shape, 
                                       void *hip_stream);
 
 /*
+ * Paged KV cache and per-sequence lengths: the same three operations for the cache
+ * layout of a serving engine (the method keeps the full KV cache and only changes
+ * what is read from it; it says nothing about the cache's layout or about batches
+ * of sequences of different lengths, so the reading is: sequence b attends to and
+ * ranks its own first n_b rows).
+ *
+ * K_pool, V_pool: bf16 pools of pages; page p, KV head g, token slot s starts at
+ * element  p * stride_page + g * stride_head + s * stride_row  (innermost
+ * dimension contiguous; strides multiples of 8 elements, stride_row >= head_dim).
+ * block_table[b][t] (DEVICE, int32, max_pages columns) names the page holding rows
+ * t * page_size .. (t + 1) * page_size - 1 of sequence b; only the entries that
+ * cover rows 0 .. n_b - 1 are read.  seq_lens[b] (DEVICE, int32) is n_b, clamped
+ * to 0 .. shape->ctx_len; NULL means n_b = shape->ctx_len for every sequence.
+ * shape->ctx_len is the largest length a sequence of the call may have (it sizes
+ * the launch); shape's kv strides are ignored.  One table serves K and V, and in
+ * hylra_decode_step_paged every layer (each layer has its own pools).
+ *
+ * Full layer: sequence b selects min(k, n_b) rows; idx[b, g, min(k, n_b) .. k-1]
+ * = -1.  A sequence with n_b = 0 gets a zero output row and no index.  Requires
+ * 1 <= k <= shape->ctx_len.  Reuse layer: entries < 0 or >= n_b are padding.
+ */
+typedef struct {
+    int32_t page_size;          /* rows per page: a power of two, 1 .. 65536                */
+    int32_t max_pages;          /* columns of block_table; >= ceil(ctx_len / page_size)     */
+    int64_t stride_page;        /* element strides of the pools, see above                  */
+    int64_t stride_head;
+    int64_t stride_row;
+    const int32_t *block_table; /* DEVICE [batch][max_pages]                                */
+    const int32_t *seq_lens;    /* DEVICE [batch], or NULL                                  */
+} hylra_paged;
+
+hylra_status hylra_full_attn_topk_paged(hylra_ctx *ctx, const hylra_shape *shape,
+                                        const hylra_paged *cache, const void *q,
+                                        const void *K_pool, const void *V_pool, int32_t k,
+                                        float *out, int32_t *idx, void *hip_stream);
+
+hylra_status hylra_reuse_sparse_attn_paged(hylra_ctx *ctx, const hylra_shape *shape,
+                                           const hylra_paged *cache, const void *q,
+                                           const void *K_pool, const void *V_pool,
+                                           const int32_t *idx, int32_t k, float *out,
+                                           void *hip_stream);
+
+/* As hylra_decode_step, with K_pool_l[l] / V_pool_l[l] the pools of layer l. */
+hylra_status hylra_decode_step_paged(hylra_ctx *ctx, const hylra_shape *shape,
+                                     const hylra_paged *cache, int32_t n_layers,
+                                     const uint8_t *policy, const void *const *q_l,
+                                     const void *const *K_pool_l, const void *const *V_pool_l,
+                                     int32_t k, float *const *out_l, int32_t *idx_buf,
+                                     void *hip_stream);
+
+/*
  * Tuning knobs (HOST call, takes effect for later launches).  Unknown names give
  * HYLRA_ERR_BAD_ARG; 0 always means "automatic / default".  Names:
  *   "full_split_rows"   rows of the cache per workgroup of the Full kernel (the vector-ALU

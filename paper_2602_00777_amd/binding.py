@@ -22,6 +22,7 @@ EXPORTS = (
     "hylra_create", "hylra_destroy", "hylra_status_str", "hylra_last_error",
     "hylra_full_attn_topk", "hylra_reuse_sparse_attn", "hylra_decode_step",
     "hylra_full_attn_topk_blocks", "hylra_reuse_block_attn", "hylra_decode_step_blocks",
+    "hylra_full_attn_topk_paged", "hylra_reuse_sparse_attn_paged", "hylra_decode_step_paged",
     "hylra_set_option", "hylra_profile_enable", "hylra_profile_reset", "hylra_profile_read",
     "hylra_probe_copy", "hylra_probe_read",
 )
@@ -39,6 +40,14 @@ class Shape(ctypes.Structure):
         ("head_dim", ctypes.c_int32), ("ctx_len", ctypes.c_int32),
         ("kv_stride_b", ctypes.c_int64), ("kv_stride_h", ctypes.c_int64),
         ("kv_stride_n", ctypes.c_int64), ("scale", ctypes.c_float),
+    ]
+
+
+class Paged(ctypes.Structure):
+    _fields_ = [
+        ("page_size", ctypes.c_int32), ("max_pages", ctypes.c_int32),
+        ("stride_page", ctypes.c_int64), ("stride_head", ctypes.c_int64), ("stride_row", ctypes.c_int64),
+        ("block_table", ctypes.c_void_p), ("seq_lens", ctypes.c_void_p),
     ]
 
 
@@ -68,6 +77,10 @@ def load_library() -> ctypes.CDLL:
     lib.hylra_full_attn_topk_blocks.argtypes = [vp, sp, vp, vp, vp, i32, i32, vp, vp, vp]
     lib.hylra_reuse_block_attn.argtypes = [vp, sp, vp, vp, vp, vp, i32, i32, vp, vp]
     lib.hylra_decode_step_blocks.argtypes = [vp, sp, i32, vp, vp, vp, vp, i32, i32, vp, vp, vp]
+    pp = ctypes.POINTER(Paged)
+    lib.hylra_full_attn_topk_paged.argtypes = [vp, sp, pp, vp, vp, vp, i32, vp, vp, vp]
+    lib.hylra_reuse_sparse_attn_paged.argtypes = [vp, sp, pp, vp, vp, vp, vp, i32, vp, vp]
+    lib.hylra_decode_step_paged.argtypes = [vp, sp, pp, i32, vp, vp, vp, vp, i32, vp, vp, vp]
     lib.hylra_set_option.argtypes = [vp, ctypes.c_char_p, i32]
     lib.hylra_profile_enable.argtypes = [vp, i32]
     lib.hylra_profile_reset.argtypes = [vp]
@@ -94,6 +107,35 @@ def make_shape(q: torch.Tensor, K: torch.Tensor, scale: float = 0.0) -> Shape:
     if K.stride(3) != 1:
         raise ValueError("the innermost dimension of K and V must be contiguous")
     return Shape(B, Hq, Hkv, d, N, K.stride(0), K.stride(1), K.stride(2), float(scale))
+
+
+class PagedCache:
+    """Describes a paged KV cache for the ``*_paged`` calls: ``block_table`` int32 [B, max_pages]
+    (device), optional ``seq_lens`` int32 [B] (device), ``ctx_len`` = the largest sequence
+    length of the call.  Pools are bf16 tensors [pages, Hkv, page_size, d] (any strides with a
+    contiguous innermost dimension); K and V pools of a layer share shape and strides."""
+
+    def __init__(self, block_table: torch.Tensor, page_size: int, ctx_len: int,
+                 seq_lens: Optional[torch.Tensor] = None):
+        for name, t in (("block_table", block_table), ("seq_lens", seq_lens)):
+            if t is not None and (t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous()):
+                raise TypeError("%s must be a contiguous int32 CUDA tensor" % name)
+        if block_table.dim() != 2 or (seq_lens is not None and tuple(seq_lens.shape) != (block_table.shape[0],)):
+            raise ValueError("block_table must be [B, max_pages] and seq_lens [B]")
+        self.block_table, self.seq_lens = block_table, seq_lens
+        self.page_size, self.ctx_len = int(page_size), int(ctx_len)
+
+    def describe(self, q: torch.Tensor, pool: torch.Tensor, scale: float = 0.0) -> Tuple[Shape, Paged]:
+        B, Hq, d = q.shape
+        P, Hkv, ps, dk = pool.shape
+        if dk != d or ps != self.page_size or self.block_table.shape[0] != B:
+            raise ValueError("q %s, pool %s and the block table disagree" % (tuple(q.shape), tuple(pool.shape)))
+        if pool.stride(3) != 1:
+            raise ValueError("the innermost dimension of the pools must be contiguous")
+        shp = Shape(B, Hq, Hkv, d, self.ctx_len, 0, 0, 0, float(scale))
+        pg = Paged(self.page_size, self.block_table.shape[1], pool.stride(0), pool.stride(1), pool.stride(2),
+                   self.block_table.data_ptr(), self.seq_lens.data_ptr() if self.seq_lens is not None else None)
+        return shp, pg
 
 
 class Context:
@@ -172,6 +214,38 @@ class Context:
         self._check(rc, "hylra_reuse_sparse_attn")
         return out
 
+    # -- paged cache, per-sequence lengths -------------------------------------------------
+    def full_attn_topk_paged(self, q, K_pool, V_pool, cache: PagedCache, k: int, out=None, idx=None,
+                             scale: float = 0.0):
+        """hylra_full_attn_topk_paged: returns (out fp32 [B,Hq,d], idx int32 [B,Hkv,k])."""
+        self._check_inputs(q, K_pool, V_pool)
+        shp, pg = cache.describe(q, K_pool, scale)
+        if out is None:
+            out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+        if idx is None:
+            idx = torch.empty((shp.batch, shp.n_kv_heads, k), dtype=torch.int32, device=q.device)
+        rc = self._lib.hylra_full_attn_topk_paged(self._h, ctypes.byref(shp), ctypes.byref(pg), q.data_ptr(),
+                                                  K_pool.data_ptr(), V_pool.data_ptr(), k, out.data_ptr(),
+                                                  idx.data_ptr(), _stream_ptr(q.device))
+        self._check(rc, "hylra_full_attn_topk_paged")
+        return out, idx
+
+    def reuse_sparse_attn_paged(self, q, K_pool, V_pool, cache: PagedCache, idx, out=None, scale: float = 0.0):
+        """hylra_reuse_sparse_attn_paged: returns out fp32 [B,Hq,d]."""
+        self._check_inputs(q, K_pool, V_pool)
+        if idx.dtype != torch.int32 or not idx.is_cuda or not idx.is_contiguous():
+            raise TypeError("idx must be a contiguous int32 CUDA tensor")
+        shp, pg = cache.describe(q, K_pool, scale)
+        if tuple(idx.shape[:2]) != (shp.batch, shp.n_kv_heads):
+            raise ValueError("idx must be [B, Hkv, k]")
+        if out is None:
+            out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+        rc = self._lib.hylra_reuse_sparse_attn_paged(self._h, ctypes.byref(shp), ctypes.byref(pg), q.data_ptr(),
+                                                     K_pool.data_ptr(), V_pool.data_ptr(), idx.data_ptr(),
+                                                     idx.shape[2], out.data_ptr(), _stream_ptr(q.device))
+        self._check(rc, "hylra_reuse_sparse_attn_paged")
+        return out
+
     # -- block-level variant ---------------------------------------------------------------
     def full_attn_topk_blocks(self, q, K, V, block: int, kb: int, out=None, bidx=None, scale: float = 0.0):
         """hylra_full_attn_topk_blocks: returns (out fp32 [B,Hq,d], bidx int32 [B,Hkv,kb])."""
@@ -205,16 +279,26 @@ class Context:
         return out
 
     def prepare_step(self, policy: Sequence[int], q_l, K_l, V_l, k: int, scale: float = 0.0,
-                     block: int = 0):
+                     block: int = 0, paged: Optional[PagedCache] = None):
         """Marshals the per-layer pointer arrays of hylra_decode_step once, so that a timed
         loop contains nothing but the C call.  Returns a zero-argument callable plus the
         output tensors (outs, idx_buf).  block > 0 selects hylra_decode_step_blocks, with k
-        counting blocks."""
+        counting blocks; paged selects hylra_decode_step_paged, with K_l / V_l the pools."""
         L = len(policy)
         for l in range(L):
             self._check_inputs(q_l[l], K_l[l], V_l[l])
-        shp = make_shape(q_l[0], K_l[0], scale)
-        for l in range(1, L):
+        pg = None
+        if paged is not None:
+            if block:
+                raise ValueError("the block-level variant is not built for paged caches")
+            shp, pg = paged.describe(q_l[0], K_l[0], scale)
+            for l in range(1, L):
+                o, og = paged.describe(q_l[l], K_l[l], scale)
+                if bytes(o) != bytes(shp) or bytes(og) != bytes(pg):
+                    raise ValueError("all layers must share one shape and stride set")
+        else:
+            shp = make_shape(q_l[0], K_l[0], scale)
+        for l in range(1, L if paged is None else 0):
             o = make_shape(q_l[l], K_l[l], scale)
             if bytes(o) != bytes(shp):
                 raise ValueError("all layers must share one shape and stride set")
@@ -227,10 +311,14 @@ class Context:
         Ka = arr(*[t.data_ptr() for t in K_l])
         Va = arr(*[t.data_ptr() for t in V_l])
         oa = arr(*[t.data_ptr() for t in outs])
-        keep = (q_l, K_l, V_l)
+        keep = (q_l, K_l, V_l, paged)
 
         def run():
-            if block > 0:
+            if pg is not None:
+                rc = self._lib.hylra_decode_step_paged(self._h, ctypes.byref(shp), ctypes.byref(pg), L, pol,
+                                                       qa, Ka, Va, k, oa, idx_buf.data_ptr(), _stream_ptr(dev))
+                self._check(rc, "hylra_decode_step_paged")
+            elif block > 0:
                 rc = self._lib.hylra_decode_step_blocks(self._h, ctypes.byref(shp), L, pol, qa, Ka, Va,
                                                         block, k, oa, idx_buf.data_ptr(),
                                                         _stream_ptr(dev))
@@ -244,10 +332,10 @@ class Context:
         return run, outs, idx_buf
 
     def decode_step(self, policy: Sequence[int], q_l, K_l, V_l, k: int, scale: float = 0.0,
-                    block: int = 0):
+                    block: int = 0, paged: Optional[PagedCache] = None):
         """hylra_decode_step (or _blocks when block > 0): returns (list of out per layer, idx of
         the last Full layer)."""
-        run, outs, idx_buf = self.prepare_step(policy, q_l, K_l, V_l, k, scale, block)
+        run, outs, idx_buf = self.prepare_step(policy, q_l, K_l, V_l, k, scale, block, paged)
         run()
         return outs, idx_buf
 

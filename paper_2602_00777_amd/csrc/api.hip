@@ -152,6 +152,39 @@ hylra_status check_tensors(const hylra_ctx* ctx, const void* q, const void* K, c
     return HYLRA_OK;
 }
 
+// Paged cache description -> row map and strides.  pg == nullptr: contiguous cache.
+hylra_status check_paged(const hylra_ctx* ctx, const hylra_shape* s, const hylra_paged* pg, Strides& st, RowMap& map) {
+    map = RowMap{};
+    if (!pg) return HYLRA_OK;
+    if (pg->page_size < 1 || pg->page_size > 65536 || (pg->page_size & (pg->page_size - 1)))
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "page_size = %d is not a power of two in 1..65536", pg->page_size);
+    if ((int64_t)pg->max_pages * pg->page_size < s->ctx_len)
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "max_pages = %d pages of %d rows do not cover ctx_len = %d", pg->max_pages, pg->page_size, s->ctx_len);
+    if (!pg->block_table || ((uintptr_t)pg->block_table & 3) || ((uintptr_t)pg->seq_lens & 3))
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "block_table must be a 4-byte aligned device pointer (seq_lens too, or NULL)");
+    if (pg->stride_row < s->head_dim || pg->stride_head < 0 || pg->stride_page < 0)
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "pool strides must be non-negative and stride_row >= head_dim");
+    if (pg->stride_row % 8 || pg->stride_head % 8 || pg->stride_page % 8)
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "pool strides must be multiples of 8 elements (16 bytes)");
+    st.b = 0, st.h = pg->stride_head, st.n = pg->stride_row;
+    map.table = pg->block_table;
+    map.seq_lens = pg->seq_lens;
+    map.table_stride = pg->max_pages;
+    map.page_shift = 0;
+    while ((1 << map.page_shift) < pg->page_size) ++map.page_shift;
+    map.stride_page = pg->stride_page;
+    return HYLRA_OK;
+}
+
+// Page-table entries a workgroup that touches `rows` consecutive rows may have to stage in
+// LDS, given that `other_lds` bytes of dynamic LDS are taken already; 0 (= look the table up
+// in memory) if that would not fit.
+int table_capacity(const RowMap& map, int64_t rows, int64_t other_lds) {
+    if (!map.table) return 0;
+    const int64_t n = (rows >> map.page_shift) + 3;
+    return other_lds + n * 4 <= 48 * 1024 ? (int)n : 0;
+}
+
 // Ends the open event bracket, if any, on the stream it was opened on.
 hipError_t close_bracket(hylra_ctx* ctx) {
     if (!ctx->prof_open) return hipSuccess;
@@ -459,14 +492,17 @@ namespace {
 
 // Full layer.  block == 1: idx receives the k best rows.  block >= 2: idx receives the k best
 // blocks of `block` rows (a block scores the maximum of its rows).
-hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const void* q, const void* K,
-                       const void* V, int32_t block, int32_t k, float* out, int32_t* idx,
+hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* pg, const void* q,
+                       const void* K, const void* V, int32_t block, int32_t k, float* out, int32_t* idx,
                        void* hip_stream) {
     int G = 0;
     Strides sd{};
     float scale = 0.f;
+    RowMap map{};
     hylra_status rc = check_shape(ctx, shape, G, sd, scale);
     if (rc != HYLRA_OK) return rc;
+    if ((rc = check_paged(ctx, shape, pg, sd, map)) != HYLRA_OK) return rc;
+    if (pg && block != 1) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "the block-level variant is not built for paged caches");
     if ((rc = check_tensors(ctx, q, K, V, out)) != HYLRA_OK) return rc;
     if (!idx || ((uintptr_t)idx & 3)) return fail(ctx, HYLRA_ERR_BAD_ARG, "idx must be a 4-byte aligned device pointer");
     if (block < 1 || block > kMaxBlock) return fail(ctx, HYLRA_ERR_BAD_ARG, "block = %d is outside 1..%d", block, kMaxBlock);
@@ -487,8 +523,12 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const void* q, 
     fp.K = (const uint16_t*)K;
     fp.V = (const uint16_t*)V;
     fp.sb = sd.b, fp.sh = sd.h, fp.sn = sd.n;
+    fp.map = map;
     fp.Hq = shape->n_q_heads, fp.Hkv = shape->n_kv_heads, fp.N = shape->ctx_len;
     fp.rows_per_split = pl.rows_per_split, fp.n_splits = pl.n_splits;
+    // rows whose pages one workgroup can touch: its split, or (self-scheduling) its segment
+    fp.tbl_cap = table_capacity(map, pl.variant / 10 == 4 ? ceil_div(shape->ctx_len, pl.n_segs) + 64 : pl.rows_per_split,
+                                pl.variant >= 50 ? 0 : (int64_t)pl.rows_per_split * 4);
     fp.split_rot = ctx->opt_full_split_rot % pl.n_splits;
     fp.scale_log2 = scale * LOG2E_HOST;
     fp.scale_mean = scale / (float)G;
@@ -540,6 +580,7 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const void* q, 
         sp.scores = sel_scores, sp.score_stride = sel_stride;
         sp.n_splits = pl.n_splits, sp.Hq = shape->n_q_heads, sp.Hkv = shape->n_kv_heads;
         sp.G = G, sp.D = shape->head_dim, sp.N = n_sel, sp.k = k;
+        sp.seq_lens = map.seq_lens;
         sp.out = out, sp.idx = idx;
         int* w = ctx->sel_ws;
         sp.ghist = w, w += ctx->pairs_cap * 4096;
@@ -558,6 +599,7 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const void* q, 
     zp.scores = sel_scores, zp.score_stride = sel_stride;
     zp.n_splits = pl.n_splits, zp.Hq = shape->n_q_heads, zp.Hkv = shape->n_kv_heads;
     zp.G = G, zp.D = shape->head_dim, zp.N = n_sel, zp.k = k;
+    zp.seq_lens = map.seq_lens;
     zp.variant = ctx->opt_finalize_variant == 2 ? 1 : 0;
     zp.out = out, zp.idx = idx;
     HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_full_finalize(zp, shape->batch, st); }));
@@ -565,14 +607,17 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const void* q, 
 }
 
 // Reuse layer over n_idx inherited entries per (batch, KV head): rows (block == 1) or blocks.
-hylra_status reuse_impl(hylra_ctx* ctx, const hylra_shape* shape, const void* q, const void* K,
-                        const void* V, const int32_t* idx, int32_t block, int32_t n_idx, float* out,
-                        void* hip_stream) {
+hylra_status reuse_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* pg, const void* q,
+                        const void* K, const void* V, const int32_t* idx, int32_t block, int32_t n_idx,
+                        float* out, void* hip_stream) {
     int G = 0;
     Strides sd{};
     float scale = 0.f;
+    RowMap map{};
     hylra_status rc = check_shape(ctx, shape, G, sd, scale);
     if (rc != HYLRA_OK) return rc;
+    if ((rc = check_paged(ctx, shape, pg, sd, map)) != HYLRA_OK) return rc;
+    if (pg && block != 1) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "the block-level variant is not built for paged caches");
     if ((rc = check_tensors(ctx, q, K, V, out)) != HYLRA_OK) return rc;
     if (!idx || ((uintptr_t)idx & 3)) return fail(ctx, HYLRA_ERR_BAD_ARG, "idx must be a 4-byte aligned device pointer");
     if (block < 1 || block > kMaxBlock) return fail(ctx, HYLRA_ERR_BAD_ARG, "block = %d is outside 1..%d", block, kMaxBlock);
@@ -591,6 +636,7 @@ hylra_status reuse_impl(hylra_ctx* ctx, const hylra_shape* shape, const void* q,
     rp.K = (const uint16_t*)K;
     rp.V = (const uint16_t*)V;
     rp.sb = sd.b, rp.sh = sd.h, rp.sn = sd.n;
+    rp.map = map;
     rp.Hq = shape->n_q_heads, rp.Hkv = shape->n_kv_heads, rp.N = shape->ctx_len, rp.k = k;
     rp.rows_per_split = pl.rows_per_split, rp.n_splits = pl.n_splits;
     rp.scale_log2 = scale * LOG2E_HOST;
@@ -620,7 +666,7 @@ hylra_status reuse_impl(hylra_ctx* ctx, const hylra_shape* shape, const void* q,
 }
 
 // Algorithm 2 over the layers of one decode step; block == 1 is the token-level form.
-hylra_status step_impl(hylra_ctx* ctx, const hylra_shape* shape, int32_t n_layers,
+hylra_status step_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* pg, int32_t n_layers,
                        const uint8_t* policy, const void* const* q_l, const void* const* K_l,
                        const void* const* V_l, int32_t block, int32_t k, float* const* out_l,
                        int32_t* idx_buf, void* hip_stream) {
@@ -640,8 +686,8 @@ hylra_status step_impl(hylra_ctx* ctx, const hylra_shape* shape, int32_t n_layer
     for (int l = 0; l < n_layers; ++l) {
         hylra_status rc =
             policy[l] == HYLRA_FULL
-                ? full_impl(ctx, shape, q_l[l], K_l[l], V_l[l], block, k, out_l[l], idx_buf, hip_stream)
-                : reuse_impl(ctx, shape, q_l[l], K_l[l], V_l[l], idx_buf, block, k, out_l[l], hip_stream);
+                ? full_impl(ctx, shape, pg, q_l[l], K_l[l], V_l[l], block, k, out_l[l], idx_buf, hip_stream)
+                : reuse_impl(ctx, shape, pg, q_l[l], K_l[l], V_l[l], idx_buf, block, k, out_l[l], hip_stream);
         if (rc != HYLRA_OK) return rc;
     }
     return HYLRA_OK;
@@ -654,32 +700,32 @@ extern "C" {
 hylra_status hylra_full_attn_topk(hylra_ctx* ctx, const hylra_shape* shape, const void* q,
                                   const void* K, const void* V, int32_t k, float* out,
                                   int32_t* idx, void* hip_stream) {
-    return full_impl(ctx, shape, q, K, V, 1, k, out, idx, hip_stream);
+    return full_impl(ctx, shape, nullptr, q, K, V, 1, k, out, idx, hip_stream);
 }
 
 hylra_status hylra_reuse_sparse_attn(hylra_ctx* ctx, const hylra_shape* shape, const void* q,
                                      const void* K, const void* V, const int32_t* idx, int32_t k,
                                      float* out, void* hip_stream) {
-    return reuse_impl(ctx, shape, q, K, V, idx, 1, k, out, hip_stream);
+    return reuse_impl(ctx, shape, nullptr, q, K, V, idx, 1, k, out, hip_stream);
 }
 
 hylra_status hylra_decode_step(hylra_ctx* ctx, const hylra_shape* shape, int32_t n_layers,
                                const uint8_t* policy, const void* const* q_l,
                                const void* const* K_l, const void* const* V_l, int32_t k,
                                float* const* out_l, int32_t* idx_buf, void* hip_stream) {
-    return step_impl(ctx, shape, n_layers, policy, q_l, K_l, V_l, 1, k, out_l, idx_buf, hip_stream);
+    return step_impl(ctx, shape, nullptr, n_layers, policy, q_l, K_l, V_l, 1, k, out_l, idx_buf, hip_stream);
 }
 
 hylra_status hylra_full_attn_topk_blocks(hylra_ctx* ctx, const hylra_shape* shape, const void* q,
                                          const void* K, const void* V, int32_t block, int32_t kb,
                                          float* out, int32_t* bidx, void* hip_stream) {
-    return full_impl(ctx, shape, q, K, V, block, kb, out, bidx, hip_stream);
+    return full_impl(ctx, shape, nullptr, q, K, V, block, kb, out, bidx, hip_stream);
 }
 
 hylra_status hylra_reuse_block_attn(hylra_ctx* ctx, const hylra_shape* shape, const void* q,
                                     const void* K, const void* V, const int32_t* bidx,
                                     int32_t block, int32_t kb, float* out, void* hip_stream) {
-    return reuse_impl(ctx, shape, q, K, V, bidx, block, kb, out, hip_stream);
+    return reuse_impl(ctx, shape, nullptr, q, K, V, bidx, block, kb, out, hip_stream);
 }
 
 hylra_status hylra_decode_step_blocks(hylra_ctx* ctx, const hylra_shape* shape, int32_t n_layers,
@@ -687,7 +733,32 @@ hylra_status hylra_decode_step_blocks(hylra_ctx* ctx, const hylra_shape* shape, 
                                       const void* const* K_l, const void* const* V_l, int32_t block,
                                       int32_t kb, float* const* out_l, int32_t* bidx_buf,
                                       void* hip_stream) {
-    return step_impl(ctx, shape, n_layers, policy, q_l, K_l, V_l, block, kb, out_l, bidx_buf, hip_stream);
+    return step_impl(ctx, shape, nullptr, n_layers, policy, q_l, K_l, V_l, block, kb, out_l, bidx_buf, hip_stream);
+}
+
+hylra_status hylra_full_attn_topk_paged(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* cache,
+                                        const void* q, const void* K_pool, const void* V_pool, int32_t k,
+                                        float* out, int32_t* idx, void* hip_stream) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    if (!cache) return fail(ctx, HYLRA_ERR_BAD_ARG, "cache is NULL");
+    return full_impl(ctx, shape, cache, q, K_pool, V_pool, 1, k, out, idx, hip_stream);
+}
+
+hylra_status hylra_reuse_sparse_attn_paged(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* cache,
+                                           const void* q, const void* K_pool, const void* V_pool,
+                                           const int32_t* idx, int32_t k, float* out, void* hip_stream) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    if (!cache) return fail(ctx, HYLRA_ERR_BAD_ARG, "cache is NULL");
+    return reuse_impl(ctx, shape, cache, q, K_pool, V_pool, idx, 1, k, out, hip_stream);
+}
+
+hylra_status hylra_decode_step_paged(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* cache,
+                                     int32_t n_layers, const uint8_t* policy, const void* const* q_l,
+                                     const void* const* K_pool_l, const void* const* V_pool_l, int32_t k,
+                                     float* const* out_l, int32_t* idx_buf, void* hip_stream) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    if (!cache) return fail(ctx, HYLRA_ERR_BAD_ARG, "cache is NULL");
+    return step_impl(ctx, shape, cache, n_layers, policy, q_l, K_pool_l, V_pool_l, 1, k, out_l, idx_buf, hip_stream);
 }
 
 hylra_status hylra_profile_enable(hylra_ctx* ctx, int32_t on) {

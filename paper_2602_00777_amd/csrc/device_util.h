@@ -93,6 +93,21 @@ DEVI float coherent_load(const float* p) {
 // Wait until every vector memory operation this wave has issued is complete.
 DEVI void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
+// Rows of sequence b (see RowMap): clamped to 0..N.
+template <class MAP>
+DEVI int seq_rows(const MAP& m, int b, int N) {
+    return m.seq_lens ? min(max(m.seq_lens[b], 0), N) : N;
+}
+DEVI int seq_rows(const int32_t* seq_lens, int b, int N) {
+    return seq_lens ? min(max(seq_lens[b], 0), N) : N;
+}
+// Element offset of row `row` of sequence b from the (batch-independent) base of a paged pool;
+// tbl points at the sequence's row of the page table (in memory or staged in LDS).
+template <class MAP>
+DEVI int64_t paged_row_offset(const MAP& m, const int32_t* tbl, int row, int64_t sn) {
+    return (int64_t)tbl[row >> m.page_shift] * m.stride_page + (int64_t)(row & ((1 << m.page_shift) - 1)) * sn;
+}
+
 // Phase timestamps for kernel tuning; compiled in only with -DHYLRA_TRACE (never in the
 // product build).  Slot s of workgroup w lands in trace[w * 16 + s] (100 MHz wall clock).
 #ifdef HYLRA_TRACE

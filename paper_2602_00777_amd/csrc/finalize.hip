@@ -101,8 +101,12 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
 
     const int g = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int S = p.n_splits, D = p.D, G = p.G, N = p.N, k = p.k;
+    const int S = p.n_splits, D = p.D, G = p.G;
+    // this sequence ranks its first N rows and selects k of them (all of them if it has fewer)
+    const int N = seq_rows(p.seq_lens, b, p.N), k = min(p.k, N);
     const int64_t pair = (int64_t)b * p.Hkv + g;
+    int32_t* __restrict__ dst = p.idx + pair * (int64_t)p.k;
+    for (int i = k + tid; i < p.k; i += SEL_THREADS) dst[i] = -1;      // entries beyond a short sequence
 
     HYLRA_TS(0);
     RegScores<E> src;
@@ -160,7 +164,7 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
     }
     for (int i = tid; i < SEL_BINS; i += SEL_THREADS) s_hist[i] = 0;
     if (E > 0) s_sel[tid] = 0;
-    if (tid == 0) s_cand = 0, s_gt = 0;
+    if (tid == 0) s_cand = 0, s_gt = 0, s_T = SEL_BINS, s_above = 0;      // (k = 0: nothing is selected)
     __syncthreads();
     lo = s_red[0];
     hi = s_red[1];
@@ -205,7 +209,6 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
     const int kr = k - s_above;      // how many of bin T's rows are selected, 1 <= kr <= |bin T|
 
     HYLRA_TS(4);
-    int32_t* __restrict__ dst = p.idx + pair * (int64_t)k;
     constexpr int EE = E > 0 ? E : 1;
 
     // ---- 3. classify: rows in bins above T are selected, rows of bin T are candidates ----

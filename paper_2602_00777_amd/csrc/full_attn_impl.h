@@ -141,20 +141,49 @@ DEVI TileRef next_tile(ChunkQueue& cq, int* __restrict__ ctr, QueueCursor& cur, 
     return r;
 }
 
+// The workgroup's segment for its sequence: first tile, number of tiles, and the number of
+// tiles the host's chunk table was made for (a full-length sequence has that many or one
+// more; a shorter one has fewer, and the table is scaled down to it).
+struct SegInfo {
+    int tile0, tiles, made_for;
+};
+
+// First tile (within the segment) of chunk c; chunk c is [chunk_bound(c), chunk_bound(c + 1)).
+DEVI int chunk_bound(const FullParams& p, const SegInfo& sg, int c) {
+    if (c >= p.n_chunks) return sg.tiles;
+    const int t = p.chunk_tile[c];
+    return sg.tiles >= sg.made_for ? t : (int)((int64_t)t * sg.tiles / sg.made_for);
+}
+
+// One lane only.  raw: what the segment's counter returned to a claim of this workgroup.
+// Returns the claimed chunk and its bounds, or -1 if the counter has run out.  A chunk can be
+// empty when the sequence is much shorter than the table was made for; then the lane claims
+// again (and waits for it) until a chunk has tiles or the counter runs out, so that every
+// workgroup still ends with exactly one failed claim.  The counter returns to zero here: the
+// claim that draws the last value of the launch stores zero.
+DEVI int settle_claim(const FullParams& p, const SegInfo& sg, int* __restrict__ ctr, int raw, int& lo, int& hi) {
+    for (;;) {
+        if (raw == p.n_chunks - 1) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int c = p.wgs_per_seg + raw;
+        if (c >= p.n_chunks) return -1;
+        lo = chunk_bound(p, sg, c);
+        hi = chunk_bound(p, sg, c + 1);
+        if (hi > lo) return c;
+        raw = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
 // Look at the result of the claim under way, if any, and publish it: the chunk as slot
-// pc.slot of the queue, or the end of the queue.  The counter returns to zero here too.
-// seg_tile0 / seg_tiles: first tile and number of tiles of the workgroup's segment.
+// pc.slot of the queue, or the end of the queue.
 DEVI void publish_claim(ChunkQueue& cq, const FullParams& p, int* __restrict__ ctr, PendingClaim& pc, int lane,
-                        int seg_tile0, int seg_tiles) {
+                        const SegInfo& sg) {
     if (pc.slot < 0) return;
     const int raw = __builtin_amdgcn_readfirstlane(pc.raw);
-    const int c = p.wgs_per_seg + raw;
     if (lane == 0) {
-        if (raw == p.n_chunks - 1) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (c < p.n_chunks) {
-            const int end = c == p.n_chunks - 1 ? seg_tiles : p.chunk_tile[c + 1];
-            cq.tile0[pc.slot] = seg_tile0 + p.chunk_tile[c];
-            cq.first[pc.slot + 1] = pc.first + (end - p.chunk_tile[c]);
+        int lo = 0, hi = 0;
+        if (settle_claim(p, sg, ctr, raw, lo, hi) >= 0) {
+            cq.tile0[pc.slot] = sg.tile0 + lo;
+            cq.first[pc.slot + 1] = pc.first + (hi - lo);
             lds_store_release(&cq.n_ready, pc.slot + 1);
         } else {
             lds_store_release(&cq.done, 1);
@@ -178,25 +207,56 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     const int chunk = lane % GEO::LPR, slot = lane / GEO::LPR;
 
     HYLRA_TS(0);
-    const uint16_t* __restrict__ Kb = p.K + (int64_t)b * p.sb + (int64_t)g * p.sh;
-    const uint16_t* __restrict__ Vb = p.V + (int64_t)b * p.sb + (int64_t)g * p.sh;
+    const bool paged = p.map.table != nullptr;
+    const int64_t base = (paged ? 0 : (int64_t)b * p.sb) + (int64_t)g * p.sh;
+    const uint16_t* __restrict__ Kb = p.K + base;
+    const uint16_t* __restrict__ Vb = p.V + base;
     uint4 qv[G][CH];
     load_q<GEO>(qv, p.q + ((int64_t)b * p.Hq + (int64_t)g * G) * D, chunk);
 
     LaneState<GEO> st;
     st.init();
     constexpr bool DYN = MODE == 4;
-    const int row0 = DYN ? 0 : split * p.rows_per_split;
-    const int row1 = DYN ? p.N : min(p.N, row0 + p.rows_per_split);
+    constexpr int STEP = NW * TILE;
+    // rows of this sequence; a shorter sequence is cut into the same number of (shorter) splits
+    const int n_rows = seq_rows(p.map, b, p.N);
+    const int rps = DYN || n_rows == p.N ? p.rows_per_split
+                                         : (n_rows + p.n_splits * STEP - 1) / (p.n_splits * STEP) * STEP;
+    const int row0 = DYN ? 0 : split * rps;
+    const int row1 = DYN ? n_rows : min(n_rows, row0 + rps);
     float smin = 3.0e38f, smax = -3.0e38f;
     float* __restrict__ srow = p.scores + ((int64_t)b * p.Hkv + g) * p.score_stride;
+
+    // Paged cache: the part of the sequence's page table this workgroup can touch is staged in
+    // LDS behind the score staging area (a lookup from memory in the loop would put a load
+    // between the tiles' loads, whose result the address arithmetic would have to wait for).
+    // If it does not fit there (tiny pages, long contexts) the table is read from memory.
+    int* const s_tbl = reinterpret_cast<int*>(s_scores + p.rows_per_split);
+    const int32_t* __restrict__ tbl = p.map.table + (int64_t)b * p.map.table_stride;     // unused unless paged
+    int tbl_page0 = -1;                                                     // first staged page; -1: not staged
+    auto stage_table = [&](int first_row, int last_row) {                   // every thread; rows of this sequence
+        const int page0 = first_row >> p.map.page_shift, n_pages = (last_row >> p.map.page_shift) - page0 + 1;
+        if (n_pages <= p.tbl_cap) {
+            for (int i = tid; i < n_pages; i += NW * 64) s_tbl[i] = tbl[page0 + i];
+            tbl_page0 = page0;
+        }
+        __syncthreads();
+    };
+    auto row_offset = [&](int row) -> int64_t {
+        if (!paged) return (int64_t)row * p.sn;
+        const int t = row >> p.map.page_shift;
+        const int page = tbl_page0 >= 0 ? s_tbl[t - tbl_page0] : tbl[t];
+        return (int64_t)page * p.map.stride_page + (int64_t)(row & ((1 << p.map.page_shift) - 1)) * p.sn;
+    };
 
     // element offsets of this lane's rows in the tile starting at row t0 (rows past the end
     // of the split are clamped to its last row; they are masked when consumed)
     auto offsets = [&](int t0, int64_t (&off)[R]) {
 #pragma unroll
-        for (int r = 0; r < R; ++r)
-            off[r] = (int64_t)min(t0 + r * GEO::RPG + slot, row1 - 1) * p.sn + chunk * 8;
+        for (int r = 0; r < R; ++r) {
+            const int row = min(t0 + r * GEO::RPG + slot, row1 - 1);
+            off[r] = row_offset(row) + chunk * 8;
+        }
     };
     // softmax/accumulate a loaded tile, stage its group-mean scores, track their range
     // st0: where the tile's scores are staged in s_scores (static modes: t0 - row0; dynamic:
@@ -237,24 +297,38 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         }
     };
 
-    constexpr int STEP = NW * TILE;
-    if (DYN) {
+    if (DYN && n_rows > 0) {
         __shared__ ChunkQueue cq;
         const int seg = split / p.wgs_per_seg, w = split - seg * p.wgs_per_seg;
-        const int seg_tile0 = (int)((int64_t)seg * p.total_tiles / p.n_segs);
-        const int seg_tiles = (int)((int64_t)(seg + 1) * p.total_tiles / p.n_segs) - seg_tile0;
+        const int tiles_b = (n_rows + TILE - 1) / TILE;            // tiles of this sequence
+        SegInfo sg;
+        sg.tile0 = (int)((int64_t)seg * tiles_b / p.n_segs);
+        sg.tiles = (int)((int64_t)(seg + 1) * tiles_b / p.n_segs) - sg.tile0;
+        sg.made_for = p.chunk_tile[p.n_chunks];
+        int* ctr = p.chunk_ctr + (((int64_t)b * p.Hkv + g) * p.n_segs + seg) * kCtrStride;
+        // a row of the segment that exists: where a wave with nothing left points its loads
+        const int idle_row = min(sg.tile0 * TILE, n_rows - 1);
+        if (paged) stage_table(idle_row, max(idle_row, min((sg.tile0 + sg.tiles) * TILE, n_rows) - 1));
         if (tid == 0) {
-            const bool has = w < p.n_chunks;
-            const int end = !has ? 0 : w == p.n_chunks - 1 ? seg_tiles : p.chunk_tile[w + 1];
+            int lo = 0, hi = 0;
+            bool has = false;
+            if (w < p.n_chunks) {
+                lo = chunk_bound(p, sg, w);
+                hi = chunk_bound(p, sg, w + 1);
+                has = hi > lo;
+                if (!has) {
+                    const int raw = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    has = settle_claim(p, sg, ctr, raw, lo, hi) >= 0;
+                }
+            }
             cq.ticket = 0;
             cq.first[0] = 0;
-            cq.first[1] = has ? end - p.chunk_tile[w] : 0;
-            cq.tile0[0] = has ? seg_tile0 + p.chunk_tile[w] : 0;
+            cq.first[1] = has ? hi - lo : 0;
+            cq.tile0[0] = has ? sg.tile0 + lo : 0;
             cq.n_ready = 1;
             cq.done = has ? 0 : 1;
         }
         __syncthreads();
-        int* ctr = p.chunk_ctr + (((int64_t)b * p.Hkv + g) * p.n_segs + seg) * kCtrStride;
         QueueCursor qslot;
         qslot.slot = 0;
         qslot.first = 0;
@@ -267,23 +341,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         PendingClaim pc;
         pc.raw = 0, pc.slot = -1, pc.first = 0;
         TileRef ta = next_tile(cq, ctr, qslot, pc, lane);
-        offsets(ta.tile >= 0 ? ta.tile * TILE : 0, off);
+        offsets(ta.tile >= 0 ? ta.tile * TILE : idle_row, off);
         load_tile<GEO, R, NT>(bufA, Kb, Vb, off);
         while (ta.tile >= 0) {
-            publish_claim(cq, p, ctr, pc, lane, seg_tile0, seg_tiles);                      // (first pass only)
+            publish_claim(cq, p, ctr, pc, lane, sg);                      // (first pass only)
             const TileRef tb = next_tile(cq, ctr, qslot, pc, lane);
-            offsets(tb.tile >= 0 ? tb.tile * TILE : 0, off);          // nothing left: a harmless reload
+            offsets(tb.tile >= 0 ? tb.tile * TILE : idle_row, off);   // nothing left: a harmless reload
             load_tile<GEO, R, NT>(bufB, Kb, Vb, off);
             consume(bufA, ta.tile * TILE, stage_of(ta));
-            publish_claim(cq, p, ctr, pc, lane, seg_tile0, seg_tiles);
+            publish_claim(cq, p, ctr, pc, lane, sg);
             if (tb.tile < 0) break;
             ta = next_tile(cq, ctr, qslot, pc, lane);
-            offsets(ta.tile >= 0 ? ta.tile * TILE : 0, off);
+            offsets(ta.tile >= 0 ? ta.tile * TILE : idle_row, off);
             load_tile<GEO, R, NT>(bufA, Kb, Vb, off);
             consume(bufB, tb.tile * TILE, stage_of(tb));
-            publish_claim(cq, p, ctr, pc, lane, seg_tile0, seg_tiles);
+            publish_claim(cq, p, ctr, pc, lane, sg);
         }
-        publish_claim(cq, p, ctr, pc, lane, seg_tile0, seg_tiles);
+        publish_claim(cq, p, ctr, pc, lane, sg);
         __syncthreads();
         // write the staged scores out: slot i of the queue is tiles tile0[i] .. of the pair,
         // tickets first[i] .. first[i + 1] - 1 (tile starts and the score stride are multiples
@@ -292,7 +366,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         for (int i = 0; i < n_slots; ++i) {
             const int f0 = cq.first[i], f1 = min(cq.first[i + 1], stage_tiles);
             const int r0 = cq.tile0[i] * TILE;
-            const int n = min((f1 - f0) * TILE, p.N - r0);
+            const int n = min((f1 - f0) * TILE, n_rows - r0);
             const float* src = s_scores + f0 * TILE;
             for (int e = 4 * tid; e < n; e += 4 * NW * 64) {
                 if (e + 4 <= n) {
@@ -302,7 +376,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
                 }
             }
         }
+    } else if (DYN || row0 >= row1) {
+        // nothing to stream: an empty sequence, or a split past the end of a short one
     } else if (MODE < 2) {
+        if (paged) stage_table(row0, row1 - 1);
         for (int t0 = row0 + wave * TILE; t0 < row1; t0 += STEP) {
             int64_t off[R];
             TileBuf<GEO, R> buf;
@@ -311,6 +388,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
             consume(buf, t0, t0 - row0);
         }
     } else {
+        if (paged) stage_table(row0, row1 - 1);
         TileBuf<GEO, R> bufA, bufB;
         int64_t off[R];
         int t0 = row0 + wave * TILE;
@@ -351,7 +429,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     if (!DYN) {
         // row0 and the score stride are multiples of 4 floats: 16-byte stores are aligned
         float* __restrict__ dst = srow + row0;
-        const int n = row1 - row0;
+        const int n = max(row1 - row0, 0);
         for (int i = 4 * tid; i < n; i += 4 * NW * 64) {
             if (i + 4 <= n) {
                 *reinterpret_cast<float4*>(dst + i) = *reinterpret_cast<const float4*>(s_scores + i);
@@ -387,7 +465,7 @@ static hipError_t launch_one(const FullParams& p, int B, int variant, hipStream_
 #define V(MODE, R)                                                                              \
     if (variant == 10 * MODE + R) {                                                             \
         hipLaunchKernelGGL((full_attn_split_kernel<D, G, CH, R, MODE>), grid, dim3(256),        \
-                           p.rows_per_split * sizeof(float), st, p);                            \
+                           p.rows_per_split * sizeof(float) + p.tbl_cap * sizeof(int), st, p);  \
         return hipGetLastError();                                                               \
     }
     HYLRA_FULL_VARIANTS(V)

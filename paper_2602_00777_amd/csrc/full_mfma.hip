@@ -31,8 +31,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, gq = lane >> 4;
 
-    const uint16_t* __restrict__ Kb = p.K + (int64_t)b * p.sb + (int64_t)g * p.sh;
-    const uint16_t* __restrict__ Vb = p.V + (int64_t)b * p.sb + (int64_t)g * p.sh;
+    const bool paged = p.map.table != nullptr;
+    const int64_t base = (paged ? 0 : (int64_t)b * p.sb) + (int64_t)g * p.sh;
+    const uint16_t* __restrict__ Kb = p.K + base;
+    const uint16_t* __restrict__ Vb = p.V + base;
     const int64_t head0 = (int64_t)b * p.Hq + (int64_t)g * G;
     uint4 qb[KI], sel[2];
     mfma_load_q<D, G>(qb, p.q + head0 * D, n, gq);
@@ -40,16 +42,42 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     MfmaState<D> st;
     st.init();
 
-    const int row0 = split * p.rows_per_split;
-    const int row1 = min(p.N, row0 + p.rows_per_split);
+    constexpr int STEP = NW * TILE;
+    // rows of this sequence; a shorter sequence is cut into the same number of (shorter) splits
+    const int n_rows = seq_rows(p.map, b, p.N);
+    const int rps = n_rows == p.N ? p.rows_per_split
+                                  : (n_rows + p.n_splits * STEP - 1) / (p.n_splits * STEP) * STEP;
+    const int row0 = split * rps;
+    const int row1 = min(n_rows, row0 + rps);
     float* __restrict__ srow = p.scores + ((int64_t)b * p.Hkv + g) * p.score_stride;
     float smin = 3.0e38f, smax = -3.0e38f;
+
+    // paged cache: the split's part of the sequence's page table, staged in LDS
+    extern __shared__ int s_tbl[];
+    // (read from memory if it does not fit there)
+    const int32_t* __restrict__ tbl = p.map.table + (int64_t)b * p.map.table_stride;     // unused unless paged
+    int tbl_page0 = -1;                                                     // first staged page; -1: not staged
+    if (paged && row0 < row1) {
+        const int page0 = row0 >> p.map.page_shift, n_pages = ((row1 - 1) >> p.map.page_shift) - page0 + 1;
+        if (n_pages <= p.tbl_cap) {
+            for (int i = tid; i < n_pages; i += NW * 64) s_tbl[i] = tbl[page0 + i];
+            tbl_page0 = page0;
+        }
+        __syncthreads();
+    }
+    auto row_offset = [&](int row) -> int64_t {
+        if (!paged) return (int64_t)row * p.sn;
+        const int t = row >> p.map.page_shift;
+        const int page = tbl_page0 >= 0 ? s_tbl[t - tbl_page0] : tbl[t];
+        return (int64_t)page * p.map.stride_page + (int64_t)(row & ((1 << p.map.page_shift) - 1)) * p.sn;
+    };
 
     // rows past the end of the split are clamped to its last row and masked when consumed
     auto issue = [&](MfmaTile<D, NB>& buf, int t0) {
 #pragma unroll
         for (int blk = 0; blk < NB; ++blk) {
-            const int64_t off = (int64_t)min(t0 + 16 * blk + n, row1 - 1) * p.sn + 8 * gq;
+            const int row = min(t0 + 16 * blk + n, row1 - 1);
+            const int64_t off = row_offset(row) + 8 * gq;
 #pragma unroll
             for (int i = 0; i < KI; ++i) buf.k[blk][i] = ld16<true>(Kb + off + 32 * i);
 #pragma unroll
@@ -89,7 +117,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         }
     };
 
-    constexpr int STEP = NW * TILE;
     if (!PIPE) {
         for (int t0 = row0 + wave * TILE; t0 < row1; t0 += STEP) {
             MfmaTile<D, NB> buf;
@@ -147,7 +174,8 @@ static hipError_t launch_g(const FullParams& p, int B, int variant, hipStream_t 
     dim3 grid(p.n_splits, p.Hkv, B);
 #define V(MODE, NB, PIPE)                                                                        \
     if (variant == 10 * MODE + NB) {                                                             \
-        hipLaunchKernelGGL((full_mfma_kernel<D, G, NB, PIPE>), grid, dim3(256), 0, st, p);       \
+        hipLaunchKernelGGL((full_mfma_kernel<D, G, NB, PIPE>), grid, dim3(256),                  \
+                           p.tbl_cap * sizeof(int), st, p);                                      \
         return hipGetLastError();                                                                \
     }
     HYLRA_FULL_MFMA_VARIANTS(V)

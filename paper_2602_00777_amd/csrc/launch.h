@@ -11,11 +11,25 @@ constexpr int kMaxFullSplitRows = 8192;   // rows per workgroup of the vector Fu
 constexpr int kMaxChunks = 480;     // chunks of rows per (batch, KV head) in the self-scheduling Full kernel
 constexpr int kCtrStride = 64;      // ints between the chunk counters of two (batch, KV head) pairs
 
+// Where the rows of the cache live and how many a sequence has (paged caches and
+// per-sequence lengths; a serving engine keeps the cache in fixed-size pages and batches
+// sequences of different lengths).  table == nullptr: sequence b is the contiguous range of
+// rows starting at b * sb.  Otherwise rows t * 2^page_shift .. of sequence b are the rows of
+// page table[b * table_stride + t], and sb is unused.
+struct RowMap {
+    const int32_t* table;
+    const int32_t* seq_lens;        // [B] rows of sequence b, clamped to 0..N; nullptr: N everywhere
+    int table_stride, page_shift;
+    int64_t stride_page;            // elements between two pages of a pool
+};
+
 struct FullParams {
     const uint16_t* q;
     const uint16_t* K;
     const uint16_t* V;
-    int64_t sb, sh, sn;             // element strides of K and V
+    int64_t sb, sh, sn;             // element strides of K and V (sn: between rows, also inside a page)
+    RowMap map;
+    int tbl_cap;                    // page-table entries a workgroup can stage in LDS (0 if not paged)
     int Hq, Hkv, N;
     int rows_per_split, n_splits;
     int split_rot;                  // workgroup x handles split (x + split_rot) % n_splits
@@ -45,6 +59,8 @@ struct FinalizeParams {
     const float* scores;
     int64_t score_stride;
     int n_splits, Hq, Hkv, G, D, N, k;
+    const int32_t* seq_lens;        // [B] or nullptr: sequence b ranks its first n_b rows and selects
+                                    // min(k, n_b) of them; the rest of its k index entries are -1
     int variant;                    // 0: scores kept in registers when they fit; 1: always re-read
     float* out;                     // [B][Hq][D]
     int32_t* idx;                   // [B][Hkv][k]
@@ -59,6 +75,7 @@ struct SelectParams {
     const float* scores;
     int64_t score_stride;
     int n_splits, Hq, Hkv, G, D, N, k;
+    const int32_t* seq_lens;        // as in FinalizeParams
     float* out;                     // [B][Hq][D]
     int32_t* idx;                   // [B][Hkv][k]
     int* ghist;                     // [B*Hkv][4096] score histogram; zero between launches
@@ -75,6 +92,7 @@ struct ReuseParams {
     const uint16_t* K;
     const uint16_t* V;
     int64_t sb, sh, sn;
+    RowMap map;
     int Hq, Hkv, N, k;              // k = row slots per (batch, KV head) = idx_stride * block
     int rows_per_split, n_splits;
     float scale_log2;

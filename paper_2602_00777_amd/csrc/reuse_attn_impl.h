@@ -28,12 +28,17 @@ __global__ __launch_bounds__(256) void reuse_attn_split_kernel(ReuseParams p) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int chunk = lane % GEO::LPR, slot = lane / GEO::LPR;
 
+    // rows of this sequence (entries that name a row beyond them are padding); with none,
+    // nothing is loaded
+    const int n_rows = seq_rows(p.map, b, p.N);
     const int i0 = split * p.rows_per_split;
-    const int i1 = min(p.k, i0 + p.rows_per_split);
+    const int i1 = n_rows > 0 ? min(p.k, i0 + p.rows_per_split) : i0;
     const int64_t pair = (int64_t)b * p.Hkv + g;
     const int32_t* __restrict__ ib = p.idx + pair * p.idx_stride;
-    const uint16_t* __restrict__ Kb = p.K + (int64_t)b * p.sb + (int64_t)g * p.sh;
-    const uint16_t* __restrict__ Vb = p.V + (int64_t)b * p.sb + (int64_t)g * p.sh;
+    const int32_t* __restrict__ tbl = p.map.table ? p.map.table + (int64_t)b * p.map.table_stride : nullptr;
+    const int64_t base = (tbl ? 0 : (int64_t)b * p.sb) + (int64_t)g * p.sh;
+    const uint16_t* __restrict__ Kb = p.K + base;
+    const uint16_t* __restrict__ Vb = p.V + base;
 
     HYLRA_TS(0);
     // the index loads head the longest dependent chain (index -> row -> softmax): issue first
@@ -64,8 +69,8 @@ __global__ __launch_bounds__(256) void reuse_attn_split_kernel(ReuseParams p) {
 #pragma unroll
             for (int r = 0; r < RS; ++r) {
                 const int rr = row[u * RS + r];
-                valid[u][r] = (unsigned)rr < (unsigned)p.N;     // negative or >= N: padding, skipped
-                off[r] = (int64_t)(valid[u][r] ? rr : 0) * p.sn + chunk * 8;
+                valid[u][r] = (unsigned)rr < (unsigned)n_rows;  // negative or past the sequence: padding, skipped
+                off[r] = reuse_row_offset(p, tbl, valid[u][r] ? rr : 0) + chunk * 8;
             }
             load_tile<GEO, RS, NT>(buf[u], Kb, Vb, off);
         }

@@ -42,13 +42,18 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, gq = lane >> 4;
 
+    // rows of this sequence (entries that name a row beyond them are padding); with none,
+    // nothing is loaded
+    const int n_rows = seq_rows(p.map, b, p.N);
     const int i0 = split * p.rows_per_split;
-    const int i1 = min(p.k, i0 + p.rows_per_split);
+    const int i1 = n_rows > 0 ? min(p.k, i0 + p.rows_per_split) : i0;
     const int64_t pair = (int64_t)b * p.Hkv + g;
     const int64_t head0 = (int64_t)b * p.Hq + (int64_t)g * G;
     const int32_t* __restrict__ ib = p.idx + pair * p.idx_stride;
-    const uint16_t* __restrict__ Kb = p.K + (int64_t)b * p.sb + (int64_t)g * p.sh;
-    const uint16_t* __restrict__ Vb = p.V + (int64_t)b * p.sb + (int64_t)g * p.sh;
+    const int32_t* __restrict__ tbl = p.map.table ? p.map.table + (int64_t)b * p.map.table_stride : nullptr;
+    const int64_t base = (tbl ? 0 : (int64_t)b * p.sb) + (int64_t)g * p.sh;
+    const uint16_t* __restrict__ Kb = p.K + base;
+    const uint16_t* __restrict__ Vb = p.V + base;
 
     HYLRA_TS(0);
     // the index loads head the longest dependent chain (index -> row -> softmax): issue first
@@ -71,8 +76,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
         bool valid[NB];
 #pragma unroll
         for (int blk = 0; blk < NB; ++blk) {
-            valid[blk] = (unsigned)row[blk] < (unsigned)p.N;       // negative or >= N: padding
-            const int64_t off = (int64_t)(valid[blk] ? row[blk] : 0) * p.sn + 8 * gq;
+            valid[blk] = (unsigned)row[blk] < (unsigned)n_rows;    // negative or past the sequence: padding
+            const int64_t off = reuse_row_offset(p, tbl, valid[blk] ? row[blk] : 0) + 8 * gq;
 #pragma unroll
             for (int i = 0; i < KI; ++i) kb[blk][i] = ld16<NT>(Kb + off + 32 * i);
 #pragma unroll

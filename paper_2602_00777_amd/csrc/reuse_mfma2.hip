@@ -205,13 +205,25 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = lane & 15, gq = lane >> 4;
 
+    // rows of this sequence (entries that name a row beyond them are padding); with none,
+    // nothing is loaded
+    const int n_rows = seq_rows(p.map, b, p.N);
     const int i0 = split * p.rows_per_split;
-    const int i1 = min(p.k, i0 + p.rows_per_split);
+    const int i1 = n_rows > 0 ? min(p.k, i0 + p.rows_per_split) : i0;
     const int64_t pair = (int64_t)b * p.Hkv + g;
     const int64_t head0 = (int64_t)b * p.Hq + (int64_t)g * G;
     const int32_t* __restrict__ ib = p.idx + pair * p.idx_stride;
-    const uint16_t* __restrict__ Kb = p.K + (int64_t)b * p.sb + (int64_t)g * p.sh;
-    const uint16_t* __restrict__ Vb = p.V + (int64_t)b * p.sb + (int64_t)g * p.sh;
+    const int32_t* __restrict__ tbl = p.map.table ? p.map.table + (int64_t)b * p.map.table_stride : nullptr;
+    const int64_t base = (tbl ? 0 : (int64_t)b * p.sb) + (int64_t)g * p.sh;
+    const uint16_t* __restrict__ Kb = p.K + base;
+    const uint16_t* __restrict__ Vb = p.V + base;
+
+    const int page_mask = (1 << p.map.page_shift) - 1;
+    // element offset of a row given its place (see below)
+    auto place = [&](int pr) -> int64_t {
+        return tbl ? (int64_t)(pr >> p.map.page_shift) * p.map.stride_page + (int64_t)(pr & page_mask) * p.sn
+                   : (int64_t)pr * p.sn;
+    };
 
     HYLRA_TS(0);
     // the index loads head the longest dependent chain (index -> row -> softmax): issue first
@@ -233,15 +245,20 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
         bool valid[NB];
 #pragma unroll
         for (int blk = 0; blk < NB; ++blk) {
-            valid[blk] = (unsigned)row[blk] < (unsigned)p.N;       // negative or >= N: padding
+            valid[blk] = (unsigned)row[blk] < (unsigned)n_rows;    // negative or past the sequence: padding
+            // Where the lane's row lives: its number in a contiguous cache, page * page_size +
+            // slot in a paged one (one page-table lookup per row; the lanes below that fetch
+            // pieces of other lanes' rows get this number from them, not from the table).
+            const int r = valid[blk] ? row[blk] : 0;
+            const int pr = tbl ? (tbl[r >> p.map.page_shift] << p.map.page_shift) | (r & page_mask) : r;
             // K: lanes n and n ^ 8 read the two halves of a 128-byte line of one row (row n & 7
             // of the block in the first load of a line, row 8 + (n & 7) in the second), so that
             // eight lanes cover a whole line; own_row() afterwards hands every lane the pieces of
             // its own row n.
-            const int ra = rotate_in<0xC>(row[blk], row[blk]);      // lanes 8..15: from lane n - 8
-            const int rb = rotate_in<0x3>(row[blk], row[blk]);      // lanes 0..7: from lane n + 8
-            const int64_t offa = (int64_t)((unsigned)ra < (unsigned)p.N ? ra : 0) * p.sn + 32 * (n >> 3) + 8 * gq;
-            const int64_t offb = (int64_t)((unsigned)rb < (unsigned)p.N ? rb : 0) * p.sn + 32 * (n >> 3) + 8 * gq;
+            const int ra = rotate_in<0xC>(pr, pr);                  // lanes 8..15: from lane n - 8
+            const int rb = rotate_in<0x3>(pr, pr);                  // lanes 0..7: from lane n + 8
+            const int64_t offa = place(ra) + 32 * (n >> 3) + 8 * gq;
+            const int64_t offb = place(rb) + 32 * (n >> 3) + 8 * gq;
 #pragma unroll
             for (int L = 0; L < 2; ++L) {
                 kb[blk][2 * L] = ld16<NT>(Kb + offa + 64 * L);
@@ -249,10 +266,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                // row 4 gq + j of the block: its number sits in lane 4 gq + j
-                const int rv = __shfl(row[blk], 4 * gq + j, 64);
-                const int64_t voff = (int64_t)((unsigned)rv < (unsigned)p.N ? rv : 0) * p.sn + 8 * n;
-                vb[blk][j] = ld16<NT>(Vb + voff);
+                // row 4 gq + j of the block: its place sits in lane 4 gq + j
+                const int rv = __shfl(pr, 4 * gq + j, 64);
+                vb[blk][j] = ld16<NT>(Vb + place(rv) + 8 * n);
             }
         }
         t0 += NW * ROWS_W;

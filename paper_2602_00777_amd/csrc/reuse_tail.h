@@ -51,6 +51,13 @@ DEVI float merge_partials(const ReuseParams& p, int64_t head0, int i, int S) {
     return den > 0.f ? num / den : 0.f;
 }
 
+// Element offset of cache row `row` of the workgroup's sequence from the kernel's K / V base
+// (which already holds the KV head, and the batch for a contiguous cache).  tbl: the
+// sequence's row of the page table, or nullptr for a contiguous cache.
+DEVI int64_t reuse_row_offset(const ReuseParams& p, const int32_t* __restrict__ tbl, int row) {
+    return tbl ? paged_row_offset(p.map, tbl, row, p.sn) : (int64_t)row * p.sn;
+}
+
 // Every thread of the workgroup (NT threads) calls this after its partial stores were issued.
 template <int G, int D, int NT>
 DEVI void reuse_merge_tail(const ReuseParams& p, int64_t pair, int64_t head0, int* s_last) {

@@ -86,8 +86,9 @@ __global__ __launch_bounds__(SEL_THREADS) void select_hist_kernel(SelectParams p
     const int64_t pair = (int64_t)b * p.Hkv + g;
     const int S = p.n_splits, D = p.D, G = p.G;
 
+    const int N = seq_rows(p.seq_lens, b, p.N);             // rows this sequence ranks
     Chunk<E> ch;
-    ch.load(p.scores + pair * p.score_stride, p.N, c);      // in flight during the merge below
+    ch.load(p.scores + pair * p.score_stride, N, c);        // in flight during the merge below
     for (int i = tid; i < SEL_BINS; i += SEL_THREADS) s_hist[i] = 0;
     if (c == 0 && tid == 0) {
         p.cand_n[pair] = 0;
@@ -119,7 +120,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_hist_kernel(SelectParams p
     for (int j = 0; j < E; ++j)
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            if (ch.pos(j, e) < p.N) atomicAdd(&s_hist[score_bin(ch.at(j, e), lo, inv_w)], 1);
+            if (ch.pos(j, e) < N) atomicAdd(&s_hist[score_bin(ch.at(j, e), lo, inv_w)], 1);
     __syncthreads();
     int* gh = p.ghist + pair * SEL_BINS;
     for (int i = tid; i < SEL_BINS; i += SEL_THREADS) {
@@ -166,20 +167,21 @@ __global__ __launch_bounds__(SEL_THREADS) void select_classify_kernel(SelectPara
     const int tid = threadIdx.x;
     const int64_t pair = (int64_t)b * p.Hkv + g;
 
+    const int N = seq_rows(p.seq_lens, b, p.N), k = min(p.k, N);
     Chunk<E> ch;
-    ch.load(p.scores + pair * p.score_stride, p.N, c);
-    if (tid == 0) s_gt = 0;
+    ch.load(p.scores + pair * p.score_stride, N, c);
+    if (tid == 0) s_gt = 0, s_pick[0] = SEL_BINS, s_pick[1] = 0;      // (k = 0: nothing is selected)
     float lo, inv_w;
     score_range(p, pair, s_red, lo, inv_w);
     int T, above;
-    threshold_bin(p.ghist + pair * SEL_BINS, p.k, s_wave, s_pick, T, above);
+    threshold_bin(p.ghist + pair * SEL_BINS, k, s_wave, s_pick, T, above);
 
     int gt = 0;
 #pragma unroll
     for (int j = 0; j < E; ++j)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            if (ch.pos(j, e) >= p.N) continue;
+            if (ch.pos(j, e) >= N) continue;
             const float x = ch.at(j, e);
             const int bn = score_bin(x, lo, inv_w);
             if (bn > T) ++gt;
@@ -217,8 +219,11 @@ __global__ __launch_bounds__(SEL_THREADS) void select_emit_kernel(SelectParams p
     const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z, C = gridDim.x;
     const int tid = threadIdx.x;
     const int64_t pair = (int64_t)b * p.Hkv + g;
-    const int N = p.N, k = p.k;
+    const int N = seq_rows(p.seq_lens, b, p.N), k = min(p.k, N);
     const float* __restrict__ sc = p.scores + pair * p.score_stride;
+    int32_t* __restrict__ dst = p.idx + pair * (int64_t)p.k;
+    if (c == 0)
+        for (int i = k + tid; i < p.k; i += SEL_THREADS) dst[i] = -1;  // entries beyond a short sequence
 
     Chunk<E> ch;
     ch.load(sc, N, c);
@@ -360,7 +365,6 @@ __global__ __launch_bounds__(SEL_THREADS) void select_emit_kernel(SelectParams p
     }
 
     // ordered emission of the chunk's selected rows
-    int32_t* __restrict__ dst = p.idx + pair * (int64_t)k;
     int cnt[E], base[E];
 #pragma unroll
     for (int j = 0; j < E; ++j) cnt[j] = __popc((unsigned)(sel >> (4 * j)) & 0xFu);

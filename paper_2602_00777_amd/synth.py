@@ -157,3 +157,39 @@ def make_workload(w: Workload, device="cpu", layers: Optional[Sequence[int]] = N
     which = range(w.n_layers) if layers is None else layers
     data = [make_layer(w, l, planted[l], device) for l in which]
     return w.policy(), planted, data
+
+
+# ---- paged caches and ragged batches (layout only) ------------------------------------------
+
+def page_table(batch: int, ctx_len: int, page_size: int, seed: int = 0, spare_pages: int = 3) -> np.ndarray:
+    """A block table int32 [B, ceil(N / page_size)] that scatters the pages of every sequence
+    over a pool of B * pages + spare_pages pages (a random permutation, as a serving engine's
+    allocator would leave them after many requests)."""
+    per_seq = -(-ctx_len // page_size)
+    rng = np.random.RandomState(seed + 104729)
+    perm = rng.permutation(batch * per_seq + spare_pages)[:batch * per_seq]
+    return perm.reshape(batch, per_seq).astype(np.int32)
+
+
+def to_pool(x: torch.Tensor, table: np.ndarray, page_size: int, n_pages: Optional[int] = None) -> torch.Tensor:
+    """Copies a contiguous cache tensor x [B,Hkv,N,d] into a pool [pages, Hkv, page_size, d]
+    laid out by ``table`` (rows past N in a sequence's last page are zero)."""
+    B, H, N, d = x.shape
+    per_seq = table.shape[1]
+    if n_pages is None:
+        n_pages = int(table.max()) + 1
+    pad = per_seq * page_size - N
+    if pad:
+        x = torch.cat([x, torch.zeros((B, H, pad, d), dtype=x.dtype, device=x.device)], dim=2)
+    pages = x.view(B, H, per_seq, page_size, d).permute(0, 2, 1, 3, 4).reshape(B * per_seq, H, page_size, d)
+    pool = torch.zeros((n_pages, H, page_size, d), dtype=x.dtype, device=x.device)
+    pool[torch.as_tensor(table.reshape(-1).astype(np.int64), device=x.device)] = pages
+    return pool
+
+
+def ragged_lengths(batch: int, ctx_len: int, seed: int = 0, shortest: float = 0.25) -> np.ndarray:
+    """Sequence lengths int32 [B]: uniform in [shortest * N, N], the first one exactly N."""
+    rng = np.random.RandomState(seed + 15485863)
+    lens = rng.randint(max(1, int(shortest * ctx_len)), ctx_len + 1, size=batch)
+    lens[0] = ctx_len
+    return lens.astype(np.int32)
