@@ -10,6 +10,9 @@ from .binding import (  # noqa: F401
     full_attn_topk_blocks,
     reuse_block_attn,
     overlap,
+    overlap_counts,
+    policy_search,
+    similarity_matrix,
     reuse_sparse_attn,
     threads,
 )

@@ -59,6 +59,10 @@ def _load():
             lib.hylra_oracle_reuse_block_attn.restype = i32
             lib.hylra_oracle_overlap.argtypes = [vp, vp, i32]
             lib.hylra_oracle_overlap.restype = f64
+            lib.hylra_oracle_overlap_counts.argtypes = [i32, i32, i32, i32, vp, vp]
+            lib.hylra_oracle_overlap_counts.restype = None
+            lib.hylra_oracle_policy_search.argtypes = [i32, vp, f64, vp, vp]
+            lib.hylra_oracle_policy_search.restype = i32
             lib.hylra_oracle_threads.restype = i32
             _lib = lib
     return _lib
@@ -191,6 +195,42 @@ def overlap(a, b):
     if a.size != b.size:
         raise ValueError("sets must have equal size")
     return _load().hylra_oracle_overlap(_ptr(a), _ptr(b), a.size)
+
+
+def overlap_counts(idx_l):
+    """Pooled overlap counts of the layers' index sets: int64 [L, L], entries i <= j filled
+    (sum over all (batch, KV head) sets of |S_i ∩ S_j|), the rest zero."""
+    arrs = [np.ascontiguousarray(np.asarray(a, dtype=np.int32)) for a in idx_l]
+    L = len(arrs)
+    B, H, k = arrs[0].shape
+    for a in arrs:
+        if a.shape != (B, H, k):
+            raise ValueError("all layers must share one idx shape")
+    counts = np.zeros((L, L), np.int64)
+    ptrs = (ctypes.c_void_p * L)(*[a.ctypes.data for a in arrs])
+    _load().hylra_oracle_overlap_counts(L, B, H, k, ptrs, _ptr(counts))
+    return counts
+
+
+def similarity_matrix(counts):
+    """M[i][j] = counts[i][j] / counts[j][j] for i <= j (diagonal 1), zero below the diagonal."""
+    counts = np.asarray(counts, dtype=np.float64)
+    L = counts.shape[0]
+    M = np.zeros((L, L))
+    for j in range(L):
+        for i in range(j + 1):
+            M[i, j] = counts[i, j] / counts[j, j] if counts[j, j] > 0 else (1.0 if i == j else 0.0)
+    return M
+
+
+def policy_search(M, theta):
+    """Algorithm 1: returns (policy uint8 [L] with 0 = Full, 1 = Reuse; C* Full layers; S*)."""
+    M = np.ascontiguousarray(np.asarray(M, dtype=np.float64))
+    L = M.shape[0]
+    policy = np.empty(L, np.uint8)
+    s = ctypes.c_double()
+    c = _load().hylra_oracle_policy_search(L, _ptr(M), float(theta), _ptr(policy), ctypes.byref(s))
+    return policy, int(c), float(s.value)
 
 
 def threads():

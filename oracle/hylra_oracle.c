@@ -33,6 +33,9 @@
  *   q   [B, Hq, d]        K, V [B, Hkv, N, d]
  *   out [B, Hq, d] double idx  [B, Hkv, k] int32     shat [B, Hkv, N] double
  *
+ * Also here, for the offline profiling step that produces the policy (Eq. 2, Algorithm 1):
+ * the pooled overlap counts between the layers' index sets and the policy search.
+ *
  * Parity pins for every function here live in tests/test_oracle_pins.py.
  */
 #include <math.h>
@@ -335,6 +338,96 @@ double hylra_oracle_overlap(const int32_t *a, const int32_t *b, int k)
         for (int j = 0; j < k; ++j)
             if (a[i] >= 0 && a[i] == b[j]) { ++common; break; }
     return (double)common / (double)k;
+}
+
+/*
+ * Similarity matrix of the offline profiling step (paper: "Inter-Layer Similarity", Eq. 2, and
+ * "Similarity Matrix Construction"): for layers i <= j, counts[i * L + j] = the sum over all
+ * (batch, KV head) sets of |S_i ∩ S_j|, where S_l is the index set idx_l[l] [B, H, k] of layer
+ * l (negative entries are padding).  counts[j * L + i] is left untouched for i < j.
+ * Reading (the paper states Eq. 2 for one set per layer): the sets of all sequences and KV
+ * heads are pooled, and M[i][j] = counts[i][j] / counts[j][j], so that the diagonal is 1 as
+ * the paper sets it.  Plain nested loops.
+ */
+void hylra_oracle_overlap_counts(int L, int B, int H, int k, const int32_t *const *idx_l, int64_t *counts)
+{
+    for (int i = 0; i < L; ++i)
+        for (int j = i; j < L; ++j) {
+            int64_t total = 0;
+            for (int s = 0; s < B * H; ++s) {
+                const int32_t *a = idx_l[i] + (size_t)s * k, *b = idx_l[j] + (size_t)s * k;
+                for (int x = 0; x < k; ++x) {
+                    if (a[x] < 0) continue;
+                    for (int y = 0; y < k; ++y)
+                        if (a[x] == b[y]) { ++total; break; }
+                }
+            }
+            counts[(size_t)i * L + j] = total;
+        }
+}
+
+/*
+ * Offline policy search (paper: Algorithm 1 "Offline Policy Optimization via Dynamic
+ * Programming" and the section of that name).  M [L][L] row-major, M[i][j] for source layer
+ * i <= target layer j; theta the similarity threshold.
+ *
+ * A state (i, j), i <= j, means layer j uses the index set of layer i (i == j: full
+ * attention at j).  Every state keeps its best path value (C, S): C = number of
+ * full-attention layers on the path, S = sum of M over the path's states; better means
+ * smaller C, then larger S.  The path starts at (0, 0) with C = 1, S = M[0][0] (layer 0
+ * computes full attention; reading: it counts).  From (i, j): the vertical move to (i, j+1)
+ * is allowed if M[i][j+1] >= theta and adds M[i][j+1] to S; the reset jump to (j+1, j+1)
+ * adds 1 to C and M[j+1][j+1] to S.  A candidate replaces the state's value only if it is
+ * strictly better, and candidates arrive in the order of the algorithm's loops (j ascending,
+ * i ascending, vertical move before reset jump), so among equal values the first one stays
+ * (the paper does not say; reading).  The answer is the best state of the last layer (first
+ * one among equals), traced back: policy[l] = 0 (Full) for diagonal states, 1 (Reuse) else.
+ * Returns the number of Full layers C*, and S* through sum_sim.
+ */
+int hylra_oracle_policy_search(int L, const double *M, double theta, uint8_t *policy, double *sum_sim)
+{
+    /* value and predecessor (source index at layer j-1) of state (i, j) */
+    int *C = malloc(sizeof(int) * L * L), *prev = malloc(sizeof(int) * L * L);
+    double *S = malloc(sizeof(double) * L * L);
+    char *reach = calloc((size_t)L * L, 1);
+    C[0] = 1, S[0] = M[0], prev[0] = -1, reach[0] = 1;
+    for (int j = 0; j + 1 < L; ++j)
+        for (int i = 0; i <= j; ++i) {
+            if (!reach[i * L + j]) continue;
+            const int c = C[i * L + j];
+            const double s = S[i * L + j];
+            /* vertical move: index reuse */
+            if (M[i * L + j + 1] >= theta) {
+                const int t = i * L + j + 1;
+                const double cs = s + M[i * L + j + 1];
+                if (!reach[t] || c < C[t] || (c == C[t] && cs > S[t])) {
+                    reach[t] = 1, C[t] = c, S[t] = cs, prev[t] = i;
+                }
+            }
+            /* reset jump: full attention */
+            {
+                const int t = (j + 1) * L + j + 1;
+                const double cs = s + M[t];
+                if (!reach[t] || c + 1 < C[t] || (c + 1 == C[t] && cs > S[t])) {
+                    reach[t] = 1, C[t] = c + 1, S[t] = cs, prev[t] = i;
+                }
+            }
+        }
+    int best = -1;
+    for (int i = 0; i < L; ++i) {
+        const int t = i * L + L - 1;
+        if (!reach[t]) continue;
+        if (best < 0 || C[t] < C[best * L + L - 1] || (C[t] == C[best * L + L - 1] && S[t] > S[best * L + L - 1]))
+            best = i;
+    }
+    const int c_star = best >= 0 ? C[best * L + L - 1] : 0;   /* (the last layer is always reachable by reset jumps) */
+    if (sum_sim) *sum_sim = S[best * L + L - 1];
+    for (int j = L - 1, i = best; j >= 0; --j) {
+        policy[j] = (i == j) ? 0 : 1;
+        i = prev[i * L + j];
+    }
+    free(C), free(prev), free(S), free(reach);
+    return c_star;
 }
 
 int hylra_oracle_threads(void)

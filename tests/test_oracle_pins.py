@@ -467,3 +467,96 @@ def test_block_variant_ties_go_to_lower_block():
     _, bidx, bs = oracle.full_attn_topk_blocks(q, K, V, 2, 2, want_bscore=True)
     assert bs[0, 0].tolist() == [1.0, 1.0, 0.0, 1.0]
     assert bidx[0, 0].tolist() == [0, 1]
+
+
+# ---- offline profiling step: overlap counts (Eq. 2) and policy search (Algorithm 1) ----------
+
+def test_overlap_counts_against_python_sets():
+    """Pooled |S_i ∩ S_j| against Python set intersections; padding (-1) is no member."""
+    rng = np.random.RandomState(3)
+    L, B, H, k, N = 5, 2, 3, 20, 60
+    idx = [np.stack([[np.sort(rng.permutation(N)[:k]) for _ in range(H)] for _ in range(B)]).astype(np.int32)
+           for _ in range(L)]
+    idx[2][:, :, -4:] = -1
+    counts = oracle.overlap_counts(idx)
+    for i in range(L):
+        for j in range(L):
+            if i > j:
+                assert counts[i, j] == 0
+                continue
+            want = sum(len((set(idx[i][b, h].tolist()) - {-1}) & set(idx[j][b, h].tolist()))
+                       for b in range(B) for h in range(H))
+            assert counts[i, j] == want
+    M = oracle.similarity_matrix(counts)
+    assert np.allclose(np.diag(M), 1.0)
+    assert counts[2, 2] == B * H * (k - 4)
+    # one set per layer: the pooled ratio is the pairwise overlap ratio of Eq. 2
+    one = [a[:1, :1] for a in idx[:2]]
+    assert oracle.similarity_matrix(oracle.overlap_counts(one))[0, 1] == oracle.overlap(one[0], one[1])
+
+
+def _policy_value(M, policy, theta):
+    """(C, S) of a policy vector under the path rules of Algorithm 1, or None if a reused layer
+    falls below the threshold."""
+    src, C, S = 0, 0, 0.0
+    for j, a in enumerate(policy):
+        if a == 0:
+            src, C = j, C + 1
+        elif M[src, j] < theta:
+            return None
+        S += M[src, j]
+    return C, S
+
+
+def _brute_force_policy(M, theta):
+    L = M.shape[0]
+    best = None
+    for bits in itertools.product((0, 1), repeat=L - 1):
+        pol = (0,) + bits
+        v = _policy_value(M, pol, theta)
+        if v is None:
+            continue
+        if best is None or v[0] < best[0][0] or (v[0] == best[0][0] and v[1] > best[0][1]):
+            best = (v, pol)
+    return best
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_policy_search_against_exhaustive_search(seed):
+    """Algorithm 1 against all 2^(L-1) policies on random similarity matrices (generic values:
+    no ties, so the optimal policy is unique)."""
+    rng = np.random.RandomState(seed)
+    L = 4 + seed
+    M = np.triu(rng.uniform(0.2, 1.0, size=(L, L)))
+    np.fill_diagonal(M, 1.0)
+    for theta in (0.0, 0.4, 0.7, 0.95):
+        pol, C, S = oracle.policy_search(M, theta)
+        (bc, bs), bpol = _brute_force_policy(M, theta)
+        assert C == bc and S == pytest.approx(bs, abs=1e-12)
+        assert tuple(pol.tolist()) == bpol
+        assert _policy_value(M, pol, theta) == (C, pytest.approx(S, abs=1e-12))
+
+
+def test_policy_search_closed_forms():
+    L = 10
+    ones = np.triu(np.ones((L, L)))
+    # threshold above every off-diagonal entry: every layer is Full
+    M = np.triu(np.full((L, L), 0.5)); np.fill_diagonal(M, 1.0)
+    pol, C, S = oracle.policy_search(M, 0.6)
+    assert pol.tolist() == [0] * L and C == L and S == L
+    # threshold below everything: only layer 0 is Full
+    pol, C, S = oracle.policy_search(M, 0.1)
+    assert pol.tolist() == [0] + [1] * (L - 1) and C == 1 and S == pytest.approx(1 + 0.5 * (L - 1))
+    # similarity above the threshold only up to two layers back: a Full layer every third
+    # layer (the "Jump3" baseline of the paper's evaluation), and no cheaper policy exists
+    band = np.zeros((L, L))
+    for i in range(L):
+        for j in range(i, L):
+            band[i, j] = 1.0 if i == j else (0.9 - 0.1 * (j - i) if j - i <= 2 else 0.1)
+    pol, C, S = oracle.policy_search(band, 0.5)
+    assert C == math.ceil(L / 3)
+    assert _policy_value(band, pol, 0.5) == (C, pytest.approx(S))
+    assert all(sum(1 for _ in grp) <= 2 for key, grp in itertools.groupby(pol.tolist()) if key == 1)
+    # all similarities equal to 1: every policy with one Full layer ties; the value is what is fixed
+    pol, C, S = oracle.policy_search(ones, 1.0)
+    assert C == 1 and S == L and pol[0] == 0
