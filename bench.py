@@ -39,8 +39,11 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama3_8b_32k")
-    ap.add_argument("--policy", default="hylra", choices=["hylra", "full", "jump3"],
-                    help="hylra = the workload's policy; full = every layer Full; jump3 = Full every 3rd layer")
+    ap.add_argument("--policy", default="hylra", choices=["hylra", "full", "jump3", "search"],
+                    help="hylra = the workload's policy; full = every layer Full; jump3 = Full every 3rd layer; "
+                         "search = profile an all-Full pass on the synthetic data and run the policy search")
+    ap.add_argument("--theta", type=float, default=-1.0,
+                    help="--policy search: similarity threshold; negative = the median similarity of adjacent layers")
     ap.add_argument("--block", type=int, default=0,
                     help="block-level variant: rows per block (TopK keeps top_k / block blocks); 0 = token level")
     ap.add_argument("--paged", type=int, default=0,
@@ -111,6 +114,31 @@ def main():
         print("bench.py: --block must divide the workload's top_k (%d)" % w.top_k, file=sys.stderr)
         sys.exit(2)
     k_sel = w.top_k // args.block if args.block else w.top_k
+    searched = None
+    if args.policy == "search":
+        if args.block or args.paged:
+            print("bench.py: --policy search runs on the contiguous token-level layout", file=sys.stderr)
+            sys.exit(2)
+        # offline profiling as in the paper: full attention at every layer, top-k sets, pairwise
+        # overlap, path search (on synthetic data, so the policy says nothing about a real model)
+        t0 = time.time()
+        sets = [ctx.full_attn_topk(qs[l], Ks[l], Vs[l], w.top_k)[1] for l in range(w.n_layers)]
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        counts = ctx.overlap_counts(sets, w.ctx_len)
+        e1.record()
+        torch.cuda.synchronize()
+        M = binding.similarity_matrix(counts.cpu().numpy())
+        theta = args.theta if args.theta >= 0 else float(np.median(np.diag(M, 1)))
+        policy, n_full_found, sim = binding.policy_search(M, theta)
+        searched = {"theta": round(theta, 4), "adjacent_similarity_median": round(float(np.median(np.diag(M, 1))), 4),
+                    "overlap_counts_us": round(1e3 * e0.elapsed_time(e1), 1), "sum_similarity": round(sim, 3),
+                    "policy": "".join("F" if a == synth.FULL else "r" for a in policy)}
+        log("policy search: theta %.4f -> %s (%d Full), profiling %.1f s" % (theta, searched["policy"], n_full_found, time.time() - t0))
+        n_full = int((policy == synth.FULL).sum())
+        n_reuse = int((policy == synth.REUSE).sum())
+        del sets
     run, outs, idx_buf = ctx.prepare_step(policy, qs, Ks, Vs, k_sel, block=args.block, paged=paged)
 
     for _ in range(args.warmup):
@@ -205,6 +233,8 @@ def main():
     }
     if probe:
         line["probe"] = probe
+    if searched:
+        line["config"]["policy_search"] = searched
     ctx.close()
     print(json.dumps(line), flush=True)
 

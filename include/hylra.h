@@ -207,6 +207,37 @@ hylra_status hylra_decode_step_paged(hylra_ctx *ctx, const hylra_shape *shape,
                                      void *hip_stream);
 
 /*
+ * Offline profiling: from the index sets of an all-Full run to the layer policy
+ * ("Inter-Layer Similarity", Eq. 2; "Offline Optimal Policy via Dynamic
+ * Programming", Algorithm 1).
+ *
+ * hylra_overlap_counts: idx_l is a HOST array of n_layers (<= 256) DEVICE
+ * pointers, idx_l[l] = the int32 [batch, n_kv_heads, k] index set layer l's Full
+ * attention produced (entries < 0 or >= ctx_len are padding; ctx_len <= 524288).
+ * counts (DEVICE, int64 [n_layers][n_layers]) receives, for i <= j,
+ * counts[i][j] = the sum over all (batch, KV head) sets of |S_i ∩ S_j|; entries
+ * below the diagonal are set to zero.  Enqueued on the stream.
+ *
+ * hylra_similarity_matrix (HOST arrays): M[i][j] = counts[i][j] / counts[j][j] for
+ * i <= j (the diagonal is 1, as the paper sets it; a layer without valid entries
+ * gets 0 off the diagonal), 0 below the diagonal.
+ *
+ * hylra_policy_search (HOST arrays, no GPU work, ctx may be NULL): the path
+ * search of Algorithm 1 over M [n_layers][n_layers] (source layer i <= target
+ * layer j) with threshold theta: fewest Full layers first, then the largest sum of
+ * similarities along the path; layer 0 is Full and counts; among equal values the
+ * candidate met first in the order of the algorithm's loops is kept.  policy[l]
+ * receives HYLRA_FULL or HYLRA_REUSE; n_full and sum_sim (either may be NULL) the
+ * value of the chosen path.
+ */
+hylra_status hylra_overlap_counts(hylra_ctx *ctx, int32_t n_layers, const int32_t *const *idx_l,
+                                  int32_t batch, int32_t n_kv_heads, int32_t k, int32_t ctx_len,
+                                  int64_t *counts, void *hip_stream);
+hylra_status hylra_similarity_matrix(int32_t n_layers, const int64_t *counts, double *M);
+hylra_status hylra_policy_search(hylra_ctx *ctx, int32_t n_layers, const double *M, double theta,
+                                 uint8_t *policy, int32_t *n_full, double *sum_sim);
+
+/*
  * Tuning knobs (HOST call, takes effect for later launches).  Unknown names give
  * HYLRA_ERR_BAD_ARG; 0 always means "automatic / default".  Names:
  *   "full_split_rows"   rows of the cache per workgroup of the Full kernel (the vector-ALU

@@ -23,6 +23,7 @@ EXPORTS = (
     "hylra_full_attn_topk", "hylra_reuse_sparse_attn", "hylra_decode_step",
     "hylra_full_attn_topk_blocks", "hylra_reuse_block_attn", "hylra_decode_step_blocks",
     "hylra_full_attn_topk_paged", "hylra_reuse_sparse_attn_paged", "hylra_decode_step_paged",
+    "hylra_overlap_counts", "hylra_similarity_matrix", "hylra_policy_search",
     "hylra_set_option", "hylra_profile_enable", "hylra_profile_reset", "hylra_profile_read",
     "hylra_probe_copy", "hylra_probe_read",
 )
@@ -81,6 +82,10 @@ def load_library() -> ctypes.CDLL:
     lib.hylra_full_attn_topk_paged.argtypes = [vp, sp, pp, vp, vp, vp, i32, vp, vp, vp]
     lib.hylra_reuse_sparse_attn_paged.argtypes = [vp, sp, pp, vp, vp, vp, vp, i32, vp, vp]
     lib.hylra_decode_step_paged.argtypes = [vp, sp, pp, i32, vp, vp, vp, vp, i32, vp, vp, vp]
+    lib.hylra_overlap_counts.argtypes = [vp, i32, vp, i32, i32, i32, i32, vp, vp]
+    lib.hylra_similarity_matrix.argtypes = [i32, vp, vp]
+    lib.hylra_policy_search.argtypes = [vp, i32, vp, ctypes.c_double, vp, ctypes.POINTER(i32),
+                                        ctypes.POINTER(ctypes.c_double)]
     lib.hylra_set_option.argtypes = [vp, ctypes.c_char_p, i32]
     lib.hylra_profile_enable.argtypes = [vp, i32]
     lib.hylra_profile_reset.argtypes = [vp]
@@ -136,6 +141,36 @@ class PagedCache:
         pg = Paged(self.page_size, self.block_table.shape[1], pool.stride(0), pool.stride(1), pool.stride(2),
                    self.block_table.data_ptr(), self.seq_lens.data_ptr() if self.seq_lens is not None else None)
         return shp, pg
+
+
+def similarity_matrix(counts) -> "numpy.ndarray":
+    """hylra_similarity_matrix on a host int64 [L, L] array of overlap counts."""
+    import numpy as np
+
+    counts = np.ascontiguousarray(np.asarray(counts, dtype=np.int64))
+    L = counts.shape[0]
+    M = np.empty((L, L), np.float64)
+    rc = load_library().hylra_similarity_matrix(L, counts.ctypes.data, M.ctypes.data)
+    if rc != 0:
+        raise HylraError(rc, "hylra_similarity_matrix", "bad argument")
+    return M
+
+
+def policy_search(M, theta: float):
+    """hylra_policy_search (host only): returns (policy uint8 [L], n_full, sum_sim)."""
+    import numpy as np
+
+    M = np.ascontiguousarray(np.asarray(M, dtype=np.float64))
+    L = M.shape[0]
+    if M.shape != (L, L):
+        raise ValueError("M must be square")
+    policy = np.empty(L, np.uint8)
+    n_full, s = ctypes.c_int32(), ctypes.c_double()
+    rc = load_library().hylra_policy_search(None, L, M.ctypes.data, float(theta), policy.ctypes.data,
+                                            ctypes.byref(n_full), ctypes.byref(s))
+    if rc != 0:
+        raise HylraError(rc, "hylra_policy_search", "bad argument")
+    return policy, n_full.value, s.value
 
 
 class Context:
@@ -245,6 +280,21 @@ class Context:
                                                      idx.shape[2], out.data_ptr(), _stream_ptr(q.device))
         self._check(rc, "hylra_reuse_sparse_attn_paged")
         return out
+
+    # -- offline profiling ------------------------------------------------------------------
+    def overlap_counts(self, idx_l: Sequence[torch.Tensor], ctx_len: int) -> torch.Tensor:
+        """hylra_overlap_counts: int64 [L, L] device tensor of pooled |S_i ∩ S_j| (i <= j)."""
+        L = len(idx_l)
+        B, H, k = idx_l[0].shape
+        for t in idx_l:
+            if t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != (B, H, k):
+                raise TypeError("every idx must be a contiguous int32 CUDA tensor of one shape [B, Hkv, k]")
+        counts = torch.empty((L, L), dtype=torch.int64, device=idx_l[0].device)
+        ptrs = (ctypes.c_void_p * L)(*[t.data_ptr() for t in idx_l])
+        rc = self._lib.hylra_overlap_counts(self._h, L, ptrs, B, H, k, int(ctx_len), counts.data_ptr(),
+                                            _stream_ptr(idx_l[0].device))
+        self._check(rc, "hylra_overlap_counts")
+        return counts
 
     # -- block-level variant ---------------------------------------------------------------
     def full_attn_topk_blocks(self, q, K, V, block: int, kb: int, out=None, bidx=None, scale: float = 0.0):

@@ -761,6 +761,49 @@ hylra_status hylra_decode_step_paged(hylra_ctx* ctx, const hylra_shape* shape, c
     return step_impl(ctx, shape, cache, n_layers, policy, q_l, K_pool_l, V_pool_l, 1, k, out_l, idx_buf, hip_stream);
 }
 
+hylra_status hylra_overlap_counts(hylra_ctx* ctx, int32_t n_layers, const int32_t* const* idx_l, int32_t batch,
+                                  int32_t n_kv_heads, int32_t k, int32_t ctx_len, int64_t* counts,
+                                  void* hip_stream) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    if (n_layers < 1 || !idx_l || !counts || ((uintptr_t)counts & 7))
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "n_layers < 1, a NULL argument, or counts not 8-byte aligned");
+    if (n_layers > kMaxProfileLayers) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "at most %d layers", kMaxProfileLayers);
+    if (batch < 1 || n_kv_heads < 1 || k < 1 || ctx_len < 1 || batch > 65535 || n_kv_heads > 65535)
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "batch, n_kv_heads (each 1..65535), k and ctx_len must be >= 1");
+    if (ctx_len > (1 << 19)) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "ctx_len must be <= %d here", 1 << 19);
+    OverlapParams op{};
+    for (int l = 0; l < n_layers; ++l) {
+        if (!idx_l[l] || ((uintptr_t)idx_l[l] & 3))
+            return fail(ctx, HYLRA_ERR_BAD_ARG, "idx_l[%d] must be a 4-byte aligned device pointer", l);
+        op.idx[l] = idx_l[l];
+    }
+    op.L = n_layers, op.Hkv = n_kv_heads, op.k = k, op.N = ctx_len;
+    op.counts = reinterpret_cast<unsigned long long*>(counts);
+    DeviceGuard guard(ctx->device);
+    HIP_TRY(ctx, launch_overlap_counts(op, batch, (hipStream_t)hip_stream));
+    return HYLRA_OK;
+}
+
+hylra_status hylra_similarity_matrix(int32_t n_layers, const int64_t* counts, double* M) {
+    if (n_layers < 1 || !counts || !M) return HYLRA_ERR_BAD_ARG;
+    const int64_t L = n_layers;
+    for (int64_t i = 0; i < L; ++i)
+        for (int64_t j = 0; j < L; ++j) {
+            const int64_t d = counts[j * L + j];
+            M[i * L + j] = i > j ? 0.0 : i == j ? 1.0 : d > 0 ? (double)counts[i * L + j] / (double)d : 0.0;
+        }
+    return HYLRA_OK;
+}
+
+hylra_status hylra_policy_search(hylra_ctx* ctx, int32_t n_layers, const double* M, double theta, uint8_t* policy,
+                                 int32_t* n_full, double* sum_sim) {
+    if (n_layers < 1 || !M || !policy) return fail(ctx, HYLRA_ERR_BAD_ARG, "n_layers < 1 or a NULL argument");
+    if (!(theta == theta)) return fail(ctx, HYLRA_ERR_BAD_ARG, "theta is not a number");
+    const int c = policy_search_host(n_layers, M, theta, policy, sum_sim);
+    if (n_full) *n_full = c;
+    return HYLRA_OK;
+}
+
 hylra_status hylra_profile_enable(hylra_ctx* ctx, int32_t on) {
     if (!ctx) return HYLRA_ERR_BAD_ARG;
     DeviceGuard guard(ctx->device);

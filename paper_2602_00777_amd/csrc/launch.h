@@ -117,6 +117,14 @@ struct BlockMaxParams {
     int N, block, n_blocks;
 };
 
+// Pooled overlap counts between the index sets of the layers (policy.hip).
+constexpr int kMaxProfileLayers = 256;
+struct OverlapParams {
+    const int32_t* idx[kMaxProfileLayers];   // per layer: [B][Hkv][k]
+    int L, Hkv, k, N;
+    unsigned long long* counts;               // [L][L]; entries i <= j are written
+};
+
 struct CombineParams {
     const float* part_ml;
     const float* part_acc;
@@ -166,6 +174,9 @@ hipError_t launch_reuse_mfma(const ReuseParams& p, int B, int D, int G, int NB, 
 // Second matrix-core Reuse kernel (head_dim 128): 64 index entries per wave, NW = 4 or 8 waves
 int reuse_mfma2_quantum(int D, int NW);
 hipError_t launch_reuse_mfma2(const ReuseParams& p, int B, int G, bool nt, int NW, hipStream_t st);
+
+hipError_t launch_overlap_counts(const OverlapParams& p, int B, hipStream_t st);
+int policy_search_host(int L, const double* M, double theta, uint8_t* policy, double* sum_sim);
 
 hipError_t launch_full_finalize(const FinalizeParams& p, int B, hipStream_t st);
 // step 0, 1, 2 = histogram, classify, emit; E = float4 groups per thread (2 or 8)
