@@ -50,6 +50,8 @@ def main():
                     help="paged KV cache: rows per page (pages scattered over a pool by a random block table); 0 = contiguous")
     ap.add_argument("--ragged", action="store_true",
                     help="with --paged: sequence lengths uniform in [N/4, N] instead of all N")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one decode step in a HIP graph (through torch) and time its replays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--probe", action="store_true", help="also time the plain copy / read kernels")
     ap.add_argument("--opt", action="append", default=[], help="library option name=value")
@@ -141,12 +143,22 @@ def main():
         del sets
     run, outs, idx_buf = ctx.prepare_step(policy, qs, Ks, Vs, k_sel, block=args.block, paged=paged)
 
-    for _ in range(args.warmup):
+    step = run
+    if args.graph:
+        # the step is kernel launches on the current stream and nothing else (no allocation, no
+        # host synchronisation, no memset), so it can be captured as it is
         run()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            run()
+        step = graph.replay
+    for _ in range(args.warmup):
+        step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        run()
+        step()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = 1e3 * elapsed / args.steps
@@ -224,7 +236,7 @@ def main():
                    "n_layers": w.n_layers, "full_layers": n_full, "reuse_layers": n_reuse,
                    "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d, "ctx_len": N,
                    "top_k": k, "block": args.block or 1, "page_size": args.paged or None,
-                   "seq_lens": lens.tolist() if lens is not None else None,
+                   "seq_lens": lens.tolist() if lens is not None else None, "hip_graph": bool(args.graph),
                    "kv_dtype": "bf16", "accumulate": "f32"},
         "roofline": roofline,
         "roofline_other": other,

@@ -358,17 +358,63 @@ def test_decode_step_longer_chain_and_baseline_policies():
                              top_k=150, full_layers=(0, 1)))              # group of 7, sink prefix
 
 
-def test_results_are_deterministic():
-    say("determinism")
+def test_decode_step_replayed_from_a_hip_graph():
+    """hylra_decode_step only launches kernels on the caller's stream, so a caller may capture
+    it in a HIP graph.  Replays (with eager launches and synchronisations in between) must give
+    the eager result: this covers the counters the kernels reset themselves.  Index sets and the
+    Reuse layers' outputs must be bit-identical; a Full layer's output may differ in the last
+    bits, because the self-scheduling kernel groups the rows into partial sums differently from
+    run to run (the row scores, and hence the index sets, do not depend on the grouping)."""
+    say("decode step under graph capture")
+    w = synth.scaled(synth.WORKLOADS["toy"], n_layers=6, full_layers=(0, 3), batch=16, n_q_heads=32, n_kv_heads=8,
+                     head_dim=128, ctx_len=3000, top_k=512)      # batch * n_kv_heads >= 64: the self-scheduling Full kernel
+    policy, _, data = synth.make_workload(w, DEV)
+    qs, Ks, Vs = [x[0] for x in data], [x[1] for x in data], [x[2] for x in data]
+    with binding.Context(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ctx_len, w.top_k) as ctx:
+        run, outs, idx_buf = ctx.prepare_step(policy, qs, Ks, Vs, w.top_k)
+        run()
+        torch.cuda.synchronize()
+        want = [o.clone() for o in outs] + [idx_buf.clone()]
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            run()
+        for rep in range(4):
+            for o in outs:
+                o.fill_(float("nan"))
+            idx_buf.fill_(-7)
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(idx_buf, want[-1]), "replay %d: index sets differ from the eager step" % rep
+            for l, (got, ref) in enumerate(zip(outs, want)):
+                if policy[l] == synth.REUSE:
+                    assert torch.equal(got, ref), "replay %d: Reuse layer %d differs from the eager step" % (rep, l)
+                else:
+                    err = (got - ref).abs().max().item() / ref.abs().max().item()
+                    assert err < 1e-5, "replay %d: Full layer %d differs from the eager step by %.2e" % (rep, l, err)
+            run()                                   # eager work between replays
+            torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("variant", [23, 43])
+def test_results_are_deterministic(variant):
+    """Run to run, index sets and Reuse outputs are bit-identical with every kernel; the Full
+    output is too with the statically split kernels.  (The self-scheduling Full kernel hands
+    rows to workgroups at run time, so its partial sums group differently from run to run and
+    the output can move in the last bits; the row scores and the index sets cannot.)"""
+    say("determinism variant=%d" % variant)
     B, Hkv, G, d, N, k = 2, 2, 4, 128, 6000, 400
     q, K, V = rand_case(12, B, Hkv, G, d, N)
     with binding.Context(B, Hkv * G, Hkv, d, N, k) as ctx:
+        ctx.set_option("full_variant", variant)
         a_out, a_idx = run_full(ctx, q, K, V, k)
         b_out, b_idx = run_full(ctx, q, K, V, k)
         ra = ctx.reuse_sparse_attn(q, K, V, torch.from_numpy(a_idx).to(DEV)).cpu().numpy()
         rb = ctx.reuse_sparse_attn(q, K, V, torch.from_numpy(a_idx).to(DEV)).cpu().numpy()
     assert np.array_equal(a_idx, b_idx)
-    assert np.array_equal(a_out, b_out)
+    if variant == 23:
+        assert np.array_equal(a_out, b_out)
+    else:
+        assert np.max(np.abs(a_out - b_out)) <= 1e-5 * np.max(np.abs(a_out))
     assert np.array_equal(ra, rb)
 
 
