@@ -116,7 +116,9 @@ hylra_status hylra_reuse_sparse_attn(hylra_ctx *ctx, const hylra_shape *shape,
  * most recent Full layer left it.  policy[0] must be HYLRA_FULL.
  * q_l, K_l, V_l, out_l are HOST arrays of n_layers DEVICE pointers (read during
  * the call only).  idx_buf is DEVICE memory of at least B*Hkv*k int32; on return
- * (stream order) it holds the last Full layer's set.
+ * (stream order) it holds the last Full layer's set.  A Full layer directly
+ * followed by another Full layer hands its set to no one; its TopK is skipped
+ * (its output is computed as always).
  */
 hylra_status hylra_decode_step(hylra_ctx *ctx, const hylra_shape *shape, int32_t n_layers,
                                const uint8_t *policy, const void *const *q_l,

@@ -492,9 +492,11 @@ namespace {
 
 // Full layer.  block == 1: idx receives the k best rows.  block >= 2: idx receives the k best
 // blocks of `block` rows (a block scores the maximum of its rows).
+// want_idx == false (only from the layer chain): the layer's index set would never be read, so
+// only the attention output is produced and idx is left untouched.
 hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* pg, const void* q,
                        const void* K, const void* V, int32_t block, int32_t k, float* out, int32_t* idx,
-                       void* hip_stream) {
+                       void* hip_stream, bool want_idx = true) {
     int G = 0;
     Strides sd{};
     float scale = 0.f;
@@ -550,7 +552,7 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
     const int64_t pairs = (int64_t)shape->batch * shape->n_kv_heads;
     const float* sel_scores = ctx->scores;
     int64_t sel_stride = fp.score_stride;
-    if (block > 1) {
+    if (block > 1 && want_idx) {
         BlockMaxParams bp{};
         bp.scores = ctx->scores, bp.score_stride = fp.score_stride;
         bp.bscores = ctx->bscores, bp.bscore_stride = round_up(n_sel, 4);
@@ -581,7 +583,7 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
         sp.n_splits = pl.n_splits, sp.Hq = shape->n_q_heads, sp.Hkv = shape->n_kv_heads;
         sp.G = G, sp.D = shape->head_dim, sp.N = n_sel, sp.k = k;
         sp.seq_lens = map.seq_lens;
-        sp.out = out, sp.idx = idx;
+        sp.out = out, sp.idx = want_idx ? idx : nullptr;
         int* w = ctx->sel_ws;
         sp.ghist = w, w += ctx->pairs_cap * 4096;
         sp.cand_n = w, w += ctx->pairs_cap;
@@ -590,7 +592,7 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
         sp.sel_info = w, w += ctx->pairs_cap * 2;
         sp.chunk_gt = w;
         sp.max_chunks = ctx->max_chunks;
-        for (int step = 0; step < 3; ++step)
+        for (int step = 0; step < (want_idx ? 3 : 1); ++step)
             HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_select(sp, shape->batch, E, step, st); }));
         return HYLRA_OK;
     }
@@ -601,7 +603,7 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
     zp.G = G, zp.D = shape->head_dim, zp.N = n_sel, zp.k = k;
     zp.seq_lens = map.seq_lens;
     zp.variant = ctx->opt_finalize_variant == 2 ? 1 : 0;
-    zp.out = out, zp.idx = idx;
+    zp.out = out, zp.idx = want_idx ? idx : nullptr;
     HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_full_finalize(zp, shape->batch, st); }));
     return HYLRA_OK;
 }
@@ -682,11 +684,15 @@ hylra_status step_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
             return fail(ctx, HYLRA_ERR_BAD_ARG, "layer %d has a NULL tensor pointer", l);
     }
     // Layers run in order on one stream: a layer's query depends on the previous layer's
-    // output in a real model, so nothing here batches across layers.
+    // output in a real model, so nothing here batches across layers.  A Full layer that is
+    // followed by another Full layer hands its index set to nobody (a Reuse layer inherits from
+    // the most recent Full layer), so its TopK is skipped; the last layer's set is kept because
+    // idx_buf is documented to hold the last Full layer's set on return.
     for (int l = 0; l < n_layers; ++l) {
+        const bool want_idx = l + 1 == n_layers || policy[l + 1] == HYLRA_REUSE;
         hylra_status rc =
             policy[l] == HYLRA_FULL
-                ? full_impl(ctx, shape, pg, q_l[l], K_l[l], V_l[l], block, k, out_l[l], idx_buf, hip_stream)
+                ? full_impl(ctx, shape, pg, q_l[l], K_l[l], V_l[l], block, k, out_l[l], idx_buf, hip_stream, want_idx)
                 : reuse_impl(ctx, shape, pg, q_l[l], K_l[l], V_l[l], idx_buf, block, k, out_l[l], hip_stream);
         if (rc != HYLRA_OK) return rc;
     }

@@ -106,11 +106,12 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
     const int N = seq_rows(p.seq_lens, b, p.N), k = min(p.k, N);
     const int64_t pair = (int64_t)b * p.Hkv + g;
     int32_t* __restrict__ dst = p.idx + pair * (int64_t)p.k;
-    for (int i = k + tid; i < p.k; i += SEL_THREADS) dst[i] = -1;      // entries beyond a short sequence
+    if (p.idx)
+        for (int i = k + tid; i < p.k; i += SEL_THREADS) dst[i] = -1;  // entries beyond a short sequence
 
     HYLRA_TS(0);
     RegScores<E> src;
-    src.init(p.scores + pair * p.score_stride, N);      // loads are in flight from here on
+    if (p.idx) src.init(p.scores + pair * p.score_stride, N);      // loads are in flight from here on
 
     // ---- attention output: log-sum-exp merge of the S partials of each head ----
     // (max, sum) pairs go through LDS so that all loads are issued at once; the accumulator
@@ -147,6 +148,8 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
     }
 
     HYLRA_TS(1);
+    if (!p.idx) return;         // merge only: nobody will read this layer's index set
+
     // ---- range of the scores ----
     float lo = 3.0e38f, hi = -3.0e38f;
     for (int s = tid; s < S; s += SEL_THREADS) {

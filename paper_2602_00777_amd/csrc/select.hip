@@ -86,7 +86,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_hist_kernel(SelectParams p
     const int64_t pair = (int64_t)b * p.Hkv + g;
     const int S = p.n_splits, D = p.D, G = p.G;
 
-    const int N = seq_rows(p.seq_lens, b, p.N);             // rows this sequence ranks
+    const int N = p.idx ? seq_rows(p.seq_lens, b, p.N) : 0; // rows this sequence ranks (none: merge only)
     Chunk<E> ch;
     ch.load(p.scores + pair * p.score_stride, N, c);        // in flight during the merge below
     for (int i = tid; i < SEL_BINS; i += SEL_THREADS) s_hist[i] = 0;
@@ -114,6 +114,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_hist_kernel(SelectParams p
         p.out[(head0 + h) * D + col] = den > 0.f ? num / den : 0.f;
     }
 
+    if (!p.idx) return;         // merge only: nobody will read this layer's index set
     float lo, inv_w;
     score_range(p, pair, s_red, lo, inv_w);     // its barriers also cover the zeroing above
 #pragma unroll
