@@ -50,6 +50,9 @@ def main():
                     help="paged KV cache: rows per page (pages scattered over a pool by a random block table); 0 = contiguous")
     ap.add_argument("--ragged", action="store_true",
                     help="with --paged: sequence lengths uniform in [N/4, N] instead of all N")
+    ap.add_argument("--offload", type=int, default=0,
+                    help="index-guided prefetch: keep the Reuse layers' caches in pinned host memory and fetch only "
+                         "the selected rows over PCIe into this many staging slots (0 = everything resident)")
     ap.add_argument("--graph", action="store_true",
                     help="capture one decode step in a HIP graph (through torch) and time its replays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -141,7 +144,21 @@ def main():
         n_full = int((policy == synth.FULL).sum())
         n_reuse = int((policy == synth.REUSE).sum())
         del sets
-    run, outs, idx_buf = ctx.prepare_step(policy, qs, Ks, Vs, k_sel, block=args.block, paged=paged)
+    if args.offload:
+        if args.block or args.paged or args.graph:
+            print("bench.py: --offload runs on the contiguous token-level layout, launched eagerly", file=sys.stderr)
+            sys.exit(2)
+        t0 = time.time()
+        for l in range(w.n_layers):
+            if policy[l] == synth.REUSE:
+                Ks[l] = Ks[l].cpu().pin_memory()
+                Vs[l] = Vs[l].cpu().pin_memory()
+                data[l] = None
+        log("offloaded %d Reuse layers (%.1f GiB) to pinned host memory in %.1f s" %
+            (n_reuse, n_reuse * w.kv_bytes_per_layer() / 2**30, time.time() - t0))
+        run, outs, idx_buf, _copy_stream = ctx.prepare_step_offloaded(policy, qs, Ks, Vs, k_sel, n_slots=args.offload)
+    else:
+        run, outs, idx_buf = ctx.prepare_step(policy, qs, Ks, Vs, k_sel, block=args.block, paged=paged)
 
     step = run
     if args.graph:
@@ -247,6 +264,15 @@ def main():
         line["probe"] = probe
     if searched:
         line["config"]["policy_search"] = searched
+    if args.offload:
+        g = kernels.get("reuse_combine")        # class 3 = the gather launches in this mode
+        moved = 4 * B * Hkv * k * d
+        line["config"]["offload"] = {
+            "slots": args.offload, "host_resident_GiB": round(n_reuse * w.kv_bytes_per_layer() / 2**30, 1),
+            "gather_us": round(g["avg_us"], 1) if g else None,
+            "gather_GBps": round(moved / (g["avg_us"] * 1e-6) / 1e9, 1) if g else None,
+            "pcie_peak_GBps": 64.0,
+            "full_cache_transfer_ms_at_peak": round(w.kv_bytes_per_layer() / 64e9 * 1e3, 1)}
     ctx.close()
     print(json.dumps(line), flush=True)
 

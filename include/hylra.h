@@ -209,6 +209,40 @@ hylra_status hylra_decode_step_paged(hylra_ctx *ctx, const hylra_shape *shape,
                                      void *hip_stream);
 
 /*
+ * Index-guided prefetch ("Bandwidth reduction via index-guided offloading"): when
+ * a tolerant layer's cache lives in memory the GPU reads slowly (pinned host memory
+ * across PCIe), its index set is known as soon as the preceding Full layer has
+ * run, so only the selected rows are fetched, ahead of time.
+ *
+ * hylra_gather_rows: K_src / V_src are addressed as K and V of shape (any memory
+ * the device can read); idx DEVICE int32 [B, Hkv, k].  Writes, in DEVICE memory,
+ *   K_dst[b,g,t,:] = K_src[b,g,idx[b,g,t],:]   (bf16 [B,Hkv,k,d] contiguous; likewise V_dst;
+ *                                               zero rows where idx holds padding)
+ *   idx_dst[b,g,t] = t, or -1 where idx[b,g,t] is < 0 or >= ctx_len
+ * so that hylra_reuse_sparse_attn over (K_dst, V_dst, idx_dst) with ctx_len = k
+ * equals hylra_reuse_sparse_attn over (K_src, V_src, idx).
+ *
+ * hylra_decode_step_offloaded: hylra_decode_step with the Reuse layers' K_l[l] /
+ * V_l[l] in such slow memory (Full layers' caches in device memory).  Gathers run
+ * on copy_stream into slots of a DEVICE staging buffer and overlap the attention
+ * kernels on compute_stream; the two are ordered by events the context owns.
+ * staging holds staging_bytes / hylra_offload_slot_bytes(shape, k) >= 1 slots; with
+ * s slots up to s layers are prefetched ahead.  The streams may be the same (no
+ * overlap then).  On return both streams have the work enqueued; results are
+ * complete when compute_stream has drained.  n_layers <= 256.
+ */
+size_t hylra_offload_slot_bytes(const hylra_shape *shape, int32_t k);
+hylra_status hylra_gather_rows(hylra_ctx *ctx, const hylra_shape *shape, const void *K_src,
+                               const void *V_src, const int32_t *idx, int32_t k, void *K_dst,
+                               void *V_dst, int32_t *idx_dst, void *hip_stream);
+hylra_status hylra_decode_step_offloaded(hylra_ctx *ctx, const hylra_shape *shape, int32_t n_layers,
+                                         const uint8_t *policy, const void *const *q_l,
+                                         const void *const *K_l, const void *const *V_l, int32_t k,
+                                         float *const *out_l, int32_t *idx_buf, void *staging,
+                                         size_t staging_bytes, void *compute_stream,
+                                         void *copy_stream);
+
+/*
  * Offline profiling: from the index sets of an all-Full run to the layer policy
  * ("Inter-Layer Similarity", Eq. 2; "Offline Optimal Policy via Dynamic
  * Programming", Algorithm 1).

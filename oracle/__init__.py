@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     decode_step,
     full_attn_topk,
     full_attn_topk_blocks,
+    gather_rows,
     reuse_block_attn,
     overlap,
     overlap_counts,

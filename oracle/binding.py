@@ -233,5 +233,28 @@ def policy_search(M, theta):
     return policy, int(c), float(s.value)
 
 
+def gather_rows(K, V, idx):
+    """Index-guided prefetch, plain definition (paper: "index-guided offloading"; Algorithm 2,
+    K^sparse = K^cache[I], V^sparse = V^cache[I]): returns (K_sparse, V_sparse, idx_compact)
+    with K_sparse[b,g,t] = K[b,g,idx[b,g,t]] (zero rows for padding entries, i.e. < 0 or >= N)
+    and idx_compact[b,g,t] = t, or -1 for padding.  Element type is kept."""
+    K, _ = _as_np(K)
+    V, _ = _as_np(V)
+    idx = np.asarray(idx, dtype=np.int64)
+    B, H, N, d = K.shape
+    k = idx.shape[2]
+    Ks, Vs = np.zeros((B, H, k, d), K.dtype), np.zeros((B, H, k, d), V.dtype)
+    ic = np.full((B, H, k), -1, np.int32)
+    for b in range(B):
+        for g in range(H):
+            for t in range(k):
+                j = idx[b, g, t]
+                if 0 <= j < N:
+                    Ks[b, g, t] = K[b, g, j]
+                    Vs[b, g, t] = V[b, g, j]
+                    ic[b, g, t] = t
+    return Ks, Vs, ic
+
+
 def threads():
     return _load().hylra_oracle_threads()

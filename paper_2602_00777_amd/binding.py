@@ -24,6 +24,7 @@ EXPORTS = (
     "hylra_full_attn_topk_blocks", "hylra_reuse_block_attn", "hylra_decode_step_blocks",
     "hylra_full_attn_topk_paged", "hylra_reuse_sparse_attn_paged", "hylra_decode_step_paged",
     "hylra_overlap_counts", "hylra_similarity_matrix", "hylra_policy_search",
+    "hylra_offload_slot_bytes", "hylra_gather_rows", "hylra_decode_step_offloaded",
     "hylra_set_option", "hylra_profile_enable", "hylra_profile_reset", "hylra_profile_read",
     "hylra_probe_copy", "hylra_probe_read",
 )
@@ -82,6 +83,9 @@ def load_library() -> ctypes.CDLL:
     lib.hylra_full_attn_topk_paged.argtypes = [vp, sp, pp, vp, vp, vp, i32, vp, vp, vp]
     lib.hylra_reuse_sparse_attn_paged.argtypes = [vp, sp, pp, vp, vp, vp, vp, i32, vp, vp]
     lib.hylra_decode_step_paged.argtypes = [vp, sp, pp, i32, vp, vp, vp, vp, i32, vp, vp, vp]
+    lib.hylra_offload_slot_bytes.argtypes = [sp, i32]
+    lib.hylra_gather_rows.argtypes = [vp, sp, vp, vp, vp, i32, vp, vp, vp, vp]
+    lib.hylra_decode_step_offloaded.argtypes = [vp, sp, i32, vp, vp, vp, vp, i32, vp, vp, vp, ctypes.c_size_t, vp, vp]
     lib.hylra_overlap_counts.argtypes = [vp, i32, vp, i32, i32, i32, i32, vp, vp]
     lib.hylra_similarity_matrix.argtypes = [i32, vp, vp]
     lib.hylra_policy_search.argtypes = [vp, i32, vp, ctypes.c_double, vp, ctypes.POINTER(i32),
@@ -93,8 +97,9 @@ def load_library() -> ctypes.CDLL:
     lib.hylra_probe_copy.argtypes = [vp, vp, vp, ctypes.c_size_t, vp]
     lib.hylra_probe_read.argtypes = [vp, vp, ctypes.c_size_t, vp, vp]
     for name in EXPORTS:
-        if name not in ("hylra_status_str", "hylra_last_error"):
+        if name not in ("hylra_status_str", "hylra_last_error", "hylra_offload_slot_bytes"):
             getattr(lib, name).restype = ctypes.c_int
+    lib.hylra_offload_slot_bytes.restype = ctypes.c_size_t
     _lib = lib
     return lib
 
@@ -280,6 +285,65 @@ class Context:
                                                      idx.shape[2], out.data_ptr(), _stream_ptr(q.device))
         self._check(rc, "hylra_reuse_sparse_attn_paged")
         return out
+
+    # -- index-guided prefetch (offloaded caches) -------------------------------------------
+    def gather_rows(self, K_src, V_src, idx, device=None):
+        """hylra_gather_rows: K_src / V_src bf16 [B,Hkv,N,d] in device or pinned host memory;
+        returns (K_dst, V_dst bf16 [B,Hkv,k,d], idx_dst int32 [B,Hkv,k]) on the GPU."""
+        dev = idx.device if device is None else device
+        B, Hkv, N, d = K_src.shape
+        if K_src.dtype != torch.bfloat16 or V_src.shape != K_src.shape or V_src.stride() != K_src.stride():
+            raise TypeError("K_src and V_src must be bfloat16 tensors of one shape and stride set")
+        if not (K_src.is_cuda or K_src.is_pinned()) or not (V_src.is_cuda or V_src.is_pinned()):
+            raise TypeError("the source caches must be in device or pinned host memory")
+        k = idx.shape[2]
+        shp = Shape(B, Hkv, Hkv, d, N, K_src.stride(0), K_src.stride(1), K_src.stride(2), 0.0)
+        Kd = torch.empty((B, Hkv, k, d), dtype=torch.bfloat16, device=dev)
+        Vd = torch.empty_like(Kd)
+        idd = torch.empty((B, Hkv, k), dtype=torch.int32, device=dev)
+        rc = self._lib.hylra_gather_rows(self._h, ctypes.byref(shp), K_src.data_ptr(), V_src.data_ptr(),
+                                         idx.data_ptr(), k, Kd.data_ptr(), Vd.data_ptr(), idd.data_ptr(),
+                                         _stream_ptr(dev))
+        self._check(rc, "hylra_gather_rows")
+        return Kd, Vd, idd
+
+    def prepare_step_offloaded(self, policy: Sequence[int], q_l, K_l, V_l, k: int, n_slots: int = 2,
+                               copy_stream: Optional[torch.cuda.Stream] = None, scale: float = 0.0):
+        """hylra_decode_step_offloaded: K_l[l] / V_l[l] of Reuse layers may be pinned host tensors.
+        Returns (run, outs, idx_buf, copy_stream); run() enqueues one step on the current stream
+        (attention) and the copy stream (gathers)."""
+        L = len(policy)
+        dev = q_l[0].device
+        shp = make_shape(q_l[0], K_l[0], scale)
+        for l in range(L):
+            o = make_shape(q_l[l], K_l[l], scale)
+            if bytes(o) != bytes(shp) or V_l[l].stride() != K_l[l].stride():
+                raise ValueError("all layers must share one shape and stride set")
+            if policy[l] == FULL and not K_l[l].is_cuda:
+                raise TypeError("the caches of Full layers must be in device memory")
+            if not (K_l[l].is_cuda or K_l[l].is_pinned()):
+                raise TypeError("offloaded caches must be in pinned host memory")
+        outs = [torch.empty(q_l[l].shape, dtype=torch.float32, device=dev) for l in range(L)]
+        idx_buf = torch.empty((shp.batch, shp.n_kv_heads, k), dtype=torch.int32, device=dev)
+        slot = self._lib.hylra_offload_slot_bytes(ctypes.byref(shp), k)
+        staging = torch.empty(slot * n_slots + 256, dtype=torch.uint8, device=dev)
+        base = (staging.data_ptr() + 255) // 256 * 256
+        if copy_stream is None:
+            copy_stream = torch.cuda.Stream(device=dev)
+        arr = ctypes.c_void_p * L
+        pol = (ctypes.c_uint8 * L)(*[int(p) for p in policy])
+        qa, Ka, Va = (arr(*[t.data_ptr() for t in ts]) for ts in (q_l, K_l, V_l))
+        oa = arr(*[t.data_ptr() for t in outs])
+        keep = (q_l, K_l, V_l, staging)
+
+        def run():
+            rc = self._lib.hylra_decode_step_offloaded(self._h, ctypes.byref(shp), L, pol, qa, Ka, Va, k, oa,
+                                                       idx_buf.data_ptr(), base, slot * n_slots,
+                                                       _stream_ptr(dev), copy_stream.cuda_stream)
+            self._check(rc, "hylra_decode_step_offloaded")
+            return keep is not None
+
+        return run, outs, idx_buf, copy_stream
 
     # -- offline profiling ------------------------------------------------------------------
     def overlap_counts(self, idx_l: Sequence[torch.Tensor], ctx_len: int) -> torch.Tensor:

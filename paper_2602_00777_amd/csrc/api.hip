@@ -9,6 +9,7 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "launch.h"
 
@@ -16,6 +17,7 @@ using namespace hylra;
 
 namespace {
 
+constexpr int kMaxOffloadLayers = 256;    // layers hylra_decode_step_offloaded accepts (and staging slots it uses)
 constexpr int kDynWgsPerSeg = 8;          // workgroups that share a segment in the self-scheduling Full kernel
 constexpr int kTargetBlocksFull = 512;    // workgroups the Full kernel aims for: two per CU,
                                           // all resident at once (measured best on MI355X)
@@ -70,6 +72,10 @@ struct hylra_ctx {
     int32_t prof_cnt[HYLRA_PROFILE_MAX_EVENTS];      // launches inside bracket i
     bool prof_open = false;                          // the last bracket still lacks its end event
     hipStream_t prof_stream = nullptr;               // stream of the open bracket
+
+    // index-guided prefetch: events that order the copy stream and the compute stream
+    hipEvent_t* off_ev = nullptr;           // [0]: index set ready; [1 .. kMaxOffloadLayers]: layer l gathered;
+                                            // then one per staging slot: slot consumed
 
     mutable char err[256] = "";
 };
@@ -449,6 +455,11 @@ hylra_status hylra_create(hylra_ctx** out, const hylra_shape* max_shape, int32_t
 hylra_status hylra_destroy(hylra_ctx* ctx) {
     if (!ctx) return HYLRA_OK;
     DeviceGuard guard(ctx->device);
+    if (ctx->off_ev) {
+        for (int i = 0; i < 1 + 2 * kMaxOffloadLayers; ++i)
+            if (ctx->off_ev[i]) (void)hipEventDestroy(ctx->off_ev[i]);
+        delete[] ctx->off_ev;
+    }
     if (ctx->prof_ev) {
         for (int i = 0; i < 2 * HYLRA_PROFILE_MAX_EVENTS; ++i)
             if (ctx->prof_ev[i]) (void)hipEventDestroy(ctx->prof_ev[i]);
@@ -765,6 +776,149 @@ hylra_status hylra_decode_step_paged(hylra_ctx* ctx, const hylra_shape* shape, c
     if (!ctx) return HYLRA_ERR_BAD_ARG;
     if (!cache) return fail(ctx, HYLRA_ERR_BAD_ARG, "cache is NULL");
     return step_impl(ctx, shape, cache, n_layers, policy, q_l, K_pool_l, V_pool_l, 1, k, out_l, idx_buf, hip_stream);
+}
+
+size_t hylra_offload_slot_bytes(const hylra_shape* shape, int32_t k) {
+    if (!shape || k < 1 || shape->batch < 1 || shape->n_kv_heads < 1 || shape->head_dim < 1) return 0;
+    const size_t rows = (size_t)shape->batch * shape->n_kv_heads * (size_t)k;
+    const size_t kv = (rows * shape->head_dim * 2 + 255) / 256 * 256;          // one of K, V (bf16)
+    return 2 * kv + (rows * 4 + 255) / 256 * 256;
+}
+
+namespace {
+struct Slot {
+    void* K;
+    void* V;
+    int32_t* idx;
+};
+Slot slot_at(void* staging, const hylra_shape* shape, int32_t k, int i) {
+    const size_t rows = (size_t)shape->batch * shape->n_kv_heads * (size_t)k;
+    const size_t kv = (rows * shape->head_dim * 2 + 255) / 256 * 256;
+    char* base = (char*)staging + (size_t)i * hylra_offload_slot_bytes(shape, k);
+    return Slot{base, base + kv, (int32_t*)(base + 2 * kv)};
+}
+
+hylra_status gather_impl(hylra_ctx* ctx, const hylra_shape* shape, const void* K_src, const void* V_src,
+                         const int32_t* idx, int32_t k, void* K_dst, void* V_dst, int32_t* idx_dst,
+                         void* hip_stream) {
+    int G = 0;
+    Strides sd{};
+    float scale = 0.f;
+    hylra_status rc = check_shape(ctx, shape, G, sd, scale);
+    if (rc != HYLRA_OK) return rc;
+    if (!K_src || !V_src || !idx || !K_dst || !V_dst || !idx_dst)
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "a NULL argument");
+    if ((((uintptr_t)K_src | (uintptr_t)V_src | (uintptr_t)K_dst | (uintptr_t)V_dst) & 15) ||
+        (((uintptr_t)idx | (uintptr_t)idx_dst) & 3))
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "caches must be 16-byte aligned, index sets 4-byte aligned");
+    if (k < 1) return fail(ctx, HYLRA_ERR_BAD_ARG, "k = %d must be >= 1", k);
+    GatherParams gp{};
+    gp.K = (const uint16_t*)K_src, gp.V = (const uint16_t*)V_src;
+    gp.sb = sd.b, gp.sh = sd.h, gp.sn = sd.n;
+    gp.Hkv = shape->n_kv_heads, gp.D = shape->head_dim, gp.N = shape->ctx_len, gp.k = k;
+    gp.idx = idx;
+    gp.K_dst = (uint16_t*)K_dst, gp.V_dst = (uint16_t*)V_dst, gp.idx_dst = idx_dst;
+    DeviceGuard guard(ctx->device);
+    HIP_TRY(ctx, launch_timed(ctx, 3, (hipStream_t)hip_stream, [&] { return launch_gather_rows(gp, shape->batch, (hipStream_t)hip_stream); }));
+    return HYLRA_OK;
+}
+}  // namespace
+
+hylra_status hylra_gather_rows(hylra_ctx* ctx, const hylra_shape* shape, const void* K_src, const void* V_src,
+                               const int32_t* idx, int32_t k, void* K_dst, void* V_dst, int32_t* idx_dst,
+                               void* hip_stream) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    return gather_impl(ctx, shape, K_src, V_src, idx, k, K_dst, V_dst, idx_dst, hip_stream);
+}
+
+hylra_status hylra_decode_step_offloaded(hylra_ctx* ctx, const hylra_shape* shape, int32_t n_layers,
+                                         const uint8_t* policy, const void* const* q_l, const void* const* K_l,
+                                         const void* const* V_l, int32_t k, float* const* out_l, int32_t* idx_buf,
+                                         void* staging, size_t staging_bytes, void* compute_stream,
+                                         void* copy_stream) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    if (n_layers < 1 || !policy || !q_l || !K_l || !V_l || !out_l || !idx_buf || !staging || !shape)
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "n_layers < 1 or a NULL argument");
+    if (n_layers > kMaxOffloadLayers) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "at most %d layers", kMaxOffloadLayers);
+    if (policy[0] != HYLRA_FULL)
+        return fail(ctx, HYLRA_ERR_POLICY, "policy[0] must be Full: layer 0 has no set to inherit");
+    for (int l = 0; l < n_layers; ++l) {
+        if (policy[l] != HYLRA_FULL && policy[l] != HYLRA_REUSE)
+            return fail(ctx, HYLRA_ERR_POLICY, "policy[%d] = %d is neither Full (0) nor Reuse (1)", l, policy[l]);
+        if (!q_l[l] || !K_l[l] || !V_l[l] || !out_l[l])
+            return fail(ctx, HYLRA_ERR_BAD_ARG, "layer %d has a NULL tensor pointer", l);
+    }
+    if ((uintptr_t)staging & 255) return fail(ctx, HYLRA_ERR_BAD_ARG, "staging must be 256-byte aligned");
+    const size_t slot_bytes = hylra_offload_slot_bytes(shape, k);
+    if (slot_bytes == 0 || staging_bytes < slot_bytes)
+        return fail(ctx, HYLRA_ERR_WORKSPACE, "staging holds %zu bytes, one slot needs %zu", staging_bytes, slot_bytes);
+    int n_slots = (int)(staging_bytes / slot_bytes < (size_t)kMaxOffloadLayers ? staging_bytes / slot_bytes : kMaxOffloadLayers);
+    if (k > shape->ctx_len) return fail(ctx, HYLRA_ERR_BAD_ARG, "k = %d exceeds ctx_len = %d", k, shape->ctx_len);
+
+    DeviceGuard guard(ctx->device);
+    if (!ctx->off_ev) {
+        ctx->off_ev = new (std::nothrow) hipEvent_t[1 + 2 * kMaxOffloadLayers]();
+        if (!ctx->off_ev) return fail(ctx, HYLRA_ERR_HIP, "out of host memory");
+        for (int i = 0; i < 1 + 2 * kMaxOffloadLayers; ++i)
+            HIP_TRY(ctx, hipEventCreateWithFlags(&ctx->off_ev[i], hipEventDisableTiming));
+    }
+    hipEvent_t& ev_idx = ctx->off_ev[0];
+    hipEvent_t* ev_gathered = ctx->off_ev + 1;                       // per layer
+    hipEvent_t* ev_consumed = ctx->off_ev + 1 + kMaxOffloadLayers;   // per slot
+    hipStream_t cs = (hipStream_t)compute_stream, xs = (hipStream_t)copy_stream;
+
+    // the compacted cache of a Reuse layer: k rows per (batch, KV head), contiguous
+    hylra_shape compact = *shape;
+    compact.ctx_len = k;
+    compact.kv_stride_b = compact.kv_stride_h = compact.kv_stride_n = 0;
+
+    std::vector<int> slot_of(n_layers, -1);
+    std::vector<char> slot_used(n_slots, 0);
+    int next_slot = 0;
+    // enqueue the gather of Reuse layer r into the next slot (after whoever used the slot last)
+    auto prefetch = [&](int r) -> hylra_status {
+        const int s = next_slot;
+        next_slot = (next_slot + 1) % n_slots;
+        if (slot_used[s]) HIP_TRY(ctx, hipStreamWaitEvent(xs, ev_consumed[s], 0));
+        const Slot sl = slot_at(staging, shape, k, s);
+        hylra_status rc = gather_impl(ctx, shape, K_l[r], V_l[r], idx_buf, k, sl.K, sl.V, sl.idx, xs);
+        if (rc != HYLRA_OK) return rc;
+        HIP_TRY(ctx, hipEventRecord(ev_gathered[r], xs));
+        slot_of[r] = s;
+        slot_used[s] = 1;
+        return HYLRA_OK;
+    };
+
+    int run_end = 0, next_fetch = 0;      // the Reuse layers of the current run are [.., run_end); next to prefetch
+    for (int l = 0; l < n_layers; ++l) {
+        if (policy[l] == HYLRA_FULL) {
+            const bool want_idx = l + 1 == n_layers || policy[l + 1] == HYLRA_REUSE;
+            hylra_status rc = full_impl(ctx, shape, nullptr, q_l[l], K_l[l], V_l[l], 1, k, out_l[l], idx_buf, cs, want_idx);
+            if (rc != HYLRA_OK) return rc;
+            run_end = l + 1;
+            while (run_end < n_layers && policy[run_end] == HYLRA_REUSE) ++run_end;
+            next_fetch = l + 1;
+            if (next_fetch < run_end) {
+                // the run's gathers read this layer's index set
+                HIP_TRY(ctx, hipEventRecord(ev_idx, cs));
+                HIP_TRY(ctx, hipStreamWaitEvent(xs, ev_idx, 0));
+                for (int i = 0; i < n_slots && next_fetch < run_end; ++i, ++next_fetch)
+                    if ((rc = prefetch(next_fetch)) != HYLRA_OK) return rc;
+            }
+        } else {
+            const int s = slot_of[l];
+            const Slot sl = slot_at(staging, shape, k, s);
+            HIP_TRY(ctx, hipStreamWaitEvent(cs, ev_gathered[l], 0));
+            hylra_status rc = reuse_impl(ctx, &compact, nullptr, q_l[l], sl.K, sl.V, sl.idx, 1, k, out_l[l], cs);
+            if (rc != HYLRA_OK) return rc;
+            HIP_TRY(ctx, hipEventRecord(ev_consumed[s], cs));
+            if (next_fetch < run_end) {
+                if ((rc = prefetch(next_fetch)) != HYLRA_OK) return rc;
+                ++next_fetch;
+            }
+        }
+    }
+    return HYLRA_OK;
 }
 
 hylra_status hylra_overlap_counts(hylra_ctx* ctx, int32_t n_layers, const int32_t* const* idx_l, int32_t batch,

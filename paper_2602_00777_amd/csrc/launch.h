@@ -125,6 +125,18 @@ struct OverlapParams {
     unsigned long long* counts;               // [L][L]; entries i <= j are written
 };
 
+// Index-guided prefetch (offload.hip): selected rows of a (slow) cache into compact buffers.
+struct GatherParams {
+    const uint16_t* K;              // source cache, addressed through sb / sh / sn (elements)
+    const uint16_t* V;
+    int64_t sb, sh, sn;
+    int Hkv, D, N, k;
+    const int32_t* idx;             // [B][Hkv][k]
+    uint16_t* K_dst;                // [B][Hkv][k][D]
+    uint16_t* V_dst;
+    int32_t* idx_dst;               // [B][Hkv][k]: t, or -1 where idx holds padding
+};
+
 struct CombineParams {
     const float* part_ml;
     const float* part_acc;
@@ -175,6 +187,7 @@ hipError_t launch_reuse_mfma(const ReuseParams& p, int B, int D, int G, int NB, 
 int reuse_mfma2_quantum(int D, int NW);
 hipError_t launch_reuse_mfma2(const ReuseParams& p, int B, int G, bool nt, int NW, hipStream_t st);
 
+hipError_t launch_gather_rows(const GatherParams& p, int B, hipStream_t st);
 hipError_t launch_overlap_counts(const OverlapParams& p, int B, hipStream_t st);
 int policy_search_host(int L, const double* M, double theta, uint8_t* policy, double* sum_sim);
 
