@@ -281,10 +281,15 @@ hylra_status hylra_policy_search(hylra_ctx *ctx, int32_t n_layers, const double 
  *   "reuse_split_rows"  index entries per workgroup of the Reuse kernel
  *   "full_variant"      Full streaming kernel.  Vector-ALU kernels, 10*mode + unroll: 4 (plain
  *                       loads), 14 (streaming loads), 23 / 22 (streaming loads, two-deep register
- *                       pipeline), 43 / 42 (as 23 / 22 with the rows handed out at run time;
- *                       up to 4 heads per KV head the default is 43 while batch * n_kv_heads
- *                       >= 64 and 23 below that).  Matrix-core kernels: 54, 52 (default from
- *                       5 heads per KV head), 62, 61 (pipelined)
+ *                       pipeline), 43 / 42 (as 23 / 22 with the rows handed out at run time).
+ *                       First matrix-core kernel: 54, 52, 62, 61 (pipelined).  Second
+ *                       matrix-core kernel (head_dim 128): 72 (even splits), 74 (rows handed
+ *                       out at run time).  Defaults: head_dim 128: 72 from 5 heads per KV head,
+ *                       else 74 while batch * n_kv_heads >= 64 and 23 below that; head_dim 64:
+ *                       52 from 5 heads per KV head, else 43 / 23 likewise.  The kernels that
+ *                       hand out rows at run time give outputs that can differ in the last
+ *                       bits from run to run (index sets never do); the others are
+ *                       bit-reproducible.
  *   "reuse_variant"     Reuse gather kernel: 1 / 2 = vector-ALU kernel with streaming / plain
  *                       loads, 3 / 4 = first matrix-core kernel with streaming / plain loads
  *                       (default for head_dim 64: 4), 5 / 6 = second matrix-core kernel

@@ -225,6 +225,9 @@ hipError_t launch_timed(hylra_ctx* ctx, int cls, hipStream_t st, F&& f) {
     return hipSuccess;
 }
 
+// Full kernels that hand out rows at run time: 4x (vector) and 74 (matrix cores)
+bool is_self_scheduling(int variant) { return variant / 10 == 4 || variant == 74; }
+
 struct FullPlan {
     int rows_per_split, n_splits, variant;
     int n_segs, wgs_per_seg;        // self-scheduling kernel: n_splits = n_segs * wgs_per_seg
@@ -252,18 +255,21 @@ int make_chunk_table(int total_tiles, int S, int (&chunk_tile)[kMaxChunks + 1]) 
 }
 
 hylra_status plan_full(const hylra_ctx* ctx, const hylra_shape* s, int G, FullPlan& pl) {
-    // automatic: the vector kernel is HBM-bound up to 4 heads per group; beyond that its own
-    // arithmetic limits it and the matrix-core kernel is faster (measured at G = 7).  Of the
-    // vector kernels the self-scheduling one is the default while a (batch, KV head) gets at
-    // most one segment of workgroups (measured: 2 % faster at batch 8 / 32K context, 20 % at
-    // batch 32 / 16K, 2 % slower with 8 segments at batch 1 / 128K).
+    // automatic (measured on the benchmark shapes): for head_dim 128 the second matrix-core
+    // kernel, evenly split from 5 heads per group (there the vector kernel is bound by its own
+    // arithmetic: 121 us against 91 us at G = 7) and self-scheduling below that while a
+    // (batch, KV head) gets at most one segment of workgroups (2 % faster than the
+    // self-scheduling vector kernel at batch 8 / 32K, equal at batch 32 / 16K); with several
+    // segments per pair (small batches) the evenly split vector kernel is still 2 % faster.
+    // head_dim 64: the vector kernels up to 4 heads per group, the first matrix-core kernel above.
     const int64_t pairs = (int64_t)s->batch * s->n_kv_heads;
+    const bool one_segment = ceil_div(kTargetBlocksFull, pairs) <= kDynWgsPerSeg;
     pl.variant = ctx->opt_full_variant > 0 ? ctx->opt_full_variant
-                 : G > 4 ? 52
-                 : ceil_div(kTargetBlocksFull, pairs) <= kDynWgsPerSeg ? 43 : 23;
+                 : s->head_dim == 128 ? (G > 4 ? 72 : one_segment ? 74 : 23)
+                 : G > 4 ? 52 : one_segment ? 43 : 23;
     const int quantum = full_block_quantum(s->head_dim, G, pl.variant);
     if (quantum <= 0) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "Full kernel variant %d is not built for d=%d G=%d", pl.variant, s->head_dim, G);
-    if (pl.variant / 10 == 4) {
+    if (is_self_scheduling(pl.variant)) {
         // self-scheduling kernel: only the number of workgroups per pair is planned (rows are
         // handed out at run time); "full_split_rows" still sets it, as ctx_len / rows.  More
         // than kDynWgsPerSeg workgroups per pair are put into segments of that many: the
@@ -296,7 +302,8 @@ hylra_status plan_full(const hylra_ctx* ctx, const hylra_shape* s, int G, FullPl
                                                : ceil_div(pairs * s->ctx_len, kTargetBlocksFull);
     rps = round_up(rps < quantum ? quantum : rps, quantum);
     // the vector kernel stages the scores of its split in LDS
-    const int64_t rps_cap = pl.variant < 50 ? kMaxFullSplitRows / quantum * quantum : (int64_t)1 << 40;
+    const bool stages = pl.variant < 50 || pl.variant >= 70;          // kernels that stage the split's scores in LDS
+    const int64_t rps_cap = stages ? kMaxFullSplitRows / quantum * quantum : (int64_t)1 << 40;
     if (rps > rps_cap) rps = rps_cap;
     int64_t S = ceil_div(s->ctx_len, rps);
     while ((S > kMaxSplits || pairs * S > ctx->slots) && rps < rps_cap) {
@@ -540,15 +547,15 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
     fp.Hq = shape->n_q_heads, fp.Hkv = shape->n_kv_heads, fp.N = shape->ctx_len;
     fp.rows_per_split = pl.rows_per_split, fp.n_splits = pl.n_splits;
     // rows whose pages one workgroup can touch: its split, or (self-scheduling) its segment
-    fp.tbl_cap = table_capacity(map, pl.variant / 10 == 4 ? ceil_div(shape->ctx_len, pl.n_segs) + 64 : pl.rows_per_split,
-                                pl.variant >= 50 ? 0 : (int64_t)pl.rows_per_split * 4);
+    fp.tbl_cap = table_capacity(map, is_self_scheduling(pl.variant) ? ceil_div(shape->ctx_len, pl.n_segs) + 64 : pl.rows_per_split,
+                                pl.variant >= 50 && pl.variant < 70 ? 0 : (int64_t)pl.rows_per_split * 4);
     fp.split_rot = ctx->opt_full_split_rot % pl.n_splits;
     fp.scale_log2 = scale * LOG2E_HOST;
     fp.scale_mean = scale / (float)G;
     fp.part_ml = ctx->part_ml, fp.part_acc = ctx->part_acc, fp.part_mm = ctx->part_mm;
     fp.scores = ctx->scores;
     fp.score_stride = round_up(shape->ctx_len, 4);
-    if (pl.variant / 10 == 4) {
+    if (is_self_scheduling(pl.variant)) {
         fp.chunk_ctr = ctx->chunk_ctr;
         const int tile = full_block_quantum(shape->head_dim, G, pl.variant) / 4;     // rows of one wave tile
         fp.total_tiles = (int)ceil_div(shape->ctx_len, tile);

@@ -4,6 +4,7 @@
 // (the quantity TopK ranks) for the finalise kernel.
 #pragma once
 #include "attend.h"
+#include "chunk_queue.h"
 #include "launch.h"
 
 #ifndef HYLRA_BUILD_D
@@ -24,174 +25,13 @@ namespace hylra {
 // zero, i.e. also wait for the tile that was only just requested.  For the same reason the
 // pipelined loop issues its look-ahead loads unconditionally (rows past the split are
 // clamped to its last row): the number of younger loads at each wait is then a constant.
-// MODE 4: as MODE 2, but the rows are handed out at run time (guided self-scheduling), because
-// compute units do not stream at the same speed (XCDs differ, and so do the units of one XCD)
-// and with a fixed split the slowest workgroup sets the kernel time.  The rows of a (batch,
-// KV head) are cut into chunks of decreasing size (host-made table, the same for every pair).
-// The pair's workgroups start on one chunk each and claim further ones from a device-scope
-// counter, one claim per chunk: few enough that the counter is never contended.  Inside a
-// workgroup the four waves draw tiles of the current chunks from a ticket counter in LDS, so
-// the waves of a workgroup also finish together.  The wave that draws the first tile of a
-// chunk claims the next one for its workgroup and publishes it in LDS: the claim travels
-// while the chunk is consumed.  The counter returns to zero by itself: every launch adds to
-// it exactly n_chunks times per pair (n_chunks - S claims that succeed and one that fails per
-// workgroup), and the workgroup that draws the last value stores zero.
-// Nothing in the loop waits for anything but the tile it is about to consume: the claim is
-// only issued when a slot's first tile is drawn and its result is looked at one tile later
-// (memory returns loads and atomics in order, so by then it is there), and the group-mean
+// MODE 4: as MODE 2, but the rows are handed out at run time (chunk_queue.h).  Group-mean
 // scores are staged in LDS by ticket (the workgroup's t-th tile at t * TILE) and written out
 // after the loop, slot by slot.  (A store inside the loop, even once per chunk, costs more
 // than it saves: loads and stores share one completion counter and complete out of order with
 // respect to each other, so every store means draining the wave's loads once.)  Tickets
 // beyond the staging area (a workgroup that ends up with far more than its share) store
 // straight to memory.
-struct ChunkQueue {
-    int ticket;                     // next tile ticket of the workgroup
-    int n_ready;                    // published slots
-    int done;                       // no further slot will be published
-    int first[kMaxChunks + 2];      // first[i] = first ticket of slot i; first[n_ready] = end
-    int tile0[kMaxChunks + 1];      // first tile (of the pair's tiles) of slot i
-};
-
-// A drawn tile: its number among the pair's tiles (-1: none) and its ticket.
-struct TileRef {
-    int tile;                       // in a vector register, see next_tile
-    int ticket;
-};
-
-// A claim on the pair's chunk counter that is under way: the atomic has been issued, its
-// result has not been looked at yet.
-struct PendingClaim {
-    int raw;                        // lane 0: what the counter returned
-    int slot;                       // the slot the new chunk becomes; -1: nothing pending
-    int first;                      // its first ticket
-};
-
-// LDS words of the queue are read by every lane (one address: a broadcast) and moved to a
-// scalar register, so the queue logic runs on the scalar unit and costs no vector registers.
-// Ordering between the waves of the workgroup is by fences on LDS alone ("local"): a plain
-// workgroup-scope acquire or release would also wait for the wave's loads from memory, i.e.
-// for the tile it has just requested.
-DEVI int lds_load(const int* p) {
-    return __builtin_amdgcn_readfirstlane(__hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
-}
-DEVI int lds_load_acquire(const int* p) {
-    const int v = lds_load(p);
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-    return v;
-}
-DEVI void lds_store_release(int* p, int v) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-}
-
-// A wave's view of the queue: the slot it draws from, cached in scalar registers, so that a
-// draw inside the slot costs one LDS operation (the ticket).
-struct QueueCursor {
-    int slot, first, next, tile0;   // tickets first .. next - 1 are tiles tile0 .. of slot `slot`
-};
-
-// Next tile of the pair for the calling wave (every lane gets the same answer), or -1 when
-// the workgroup has none left.  Every wait here ends: a slot is published by a running wave
-// of this workgroup that waits for nothing but its own memory operations, and the spin is
-// bounded on top of that.  A wave that draws the first tile of a slot issues the claim for
-// the workgroup's next chunk into pc (at most one claim per wave is under way: the caller
-// publishes pc before it draws again).
-DEVI TileRef next_tile(ChunkQueue& cq, int* __restrict__ ctr, QueueCursor& cur, PendingClaim& pc, int lane) {
-    int T = 0;
-    if (lane == 0) T = __hip_atomic_fetch_add(&cq.ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    T = __builtin_amdgcn_readfirstlane(T);
-    int tile = -1;
-    if (T >= cur.next) {
-        // past the cached slot: wait until the ticket's slot is published, then walk to it
-        bool have = false;
-        for (int spin = 0; spin < (1 << 22); ++spin) {
-            const int done = lds_load_acquire(&cq.done);
-            const int nr = lds_load_acquire(&cq.n_ready);
-            if (T < lds_load(&cq.first[nr])) {
-                have = true;
-                break;
-            }
-            if (done) break;
-            __builtin_amdgcn_s_sleep(2);
-        }
-        if (have) {
-            while (T >= cur.next) {
-                ++cur.slot;
-                cur.first = cur.next;
-                cur.next = lds_load(&cq.first[cur.slot + 1]);
-            }
-            cur.tile0 = lds_load(&cq.tile0[cur.slot]);
-        }
-    }
-    if (T < cur.next) {
-        tile = cur.tile0 + (T - cur.first);
-        if (T == cur.first) {
-            if (lane == 0) pc.raw = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            pc.slot = cur.slot + 1;
-            pc.first = cur.next;
-        }
-    }
-    // Handed back in a vector register the compiler cannot prove uniform: with a provably
-    // uniform row number it turns the consumer's "whole tile inside the cache?" test into
-    // scalar control flow, duplicates the loop body around it and runs out of registers.
-    TileRef r;
-    asm volatile("v_mov_b32 %0, %1" : "=v"(r.tile) : "s"(tile));
-    r.ticket = T;
-    return r;
-}
-
-// The workgroup's segment for its sequence: first tile, number of tiles, and the number of
-// tiles the host's chunk table was made for (a full-length sequence has that many or one
-// more; a shorter one has fewer, and the table is scaled down to it).
-struct SegInfo {
-    int tile0, tiles, made_for;
-};
-
-// First tile (within the segment) of chunk c; chunk c is [chunk_bound(c), chunk_bound(c + 1)).
-DEVI int chunk_bound(const FullParams& p, const SegInfo& sg, int c) {
-    if (c >= p.n_chunks) return sg.tiles;
-    const int t = p.chunk_tile[c];
-    return sg.tiles >= sg.made_for ? t : (int)((int64_t)t * sg.tiles / sg.made_for);
-}
-
-// One lane only.  raw: what the segment's counter returned to a claim of this workgroup.
-// Returns the claimed chunk and its bounds, or -1 if the counter has run out.  A chunk can be
-// empty when the sequence is much shorter than the table was made for; then the lane claims
-// again (and waits for it) until a chunk has tiles or the counter runs out, so that every
-// workgroup still ends with exactly one failed claim.  The counter returns to zero here: the
-// claim that draws the last value of the launch stores zero.
-DEVI int settle_claim(const FullParams& p, const SegInfo& sg, int* __restrict__ ctr, int raw, int& lo, int& hi) {
-    for (;;) {
-        if (raw == p.n_chunks - 1) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const int c = p.wgs_per_seg + raw;
-        if (c >= p.n_chunks) return -1;
-        lo = chunk_bound(p, sg, c);
-        hi = chunk_bound(p, sg, c + 1);
-        if (hi > lo) return c;
-        raw = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-}
-
-// Look at the result of the claim under way, if any, and publish it: the chunk as slot
-// pc.slot of the queue, or the end of the queue.
-DEVI void publish_claim(ChunkQueue& cq, const FullParams& p, int* __restrict__ ctr, PendingClaim& pc, int lane,
-                        const SegInfo& sg) {
-    if (pc.slot < 0) return;
-    const int raw = __builtin_amdgcn_readfirstlane(pc.raw);
-    if (lane == 0) {
-        int lo = 0, hi = 0;
-        if (settle_claim(p, sg, ctr, raw, lo, hi) >= 0) {
-            cq.tile0[pc.slot] = sg.tile0 + lo;
-            cq.first[pc.slot + 1] = pc.first + (hi - lo);
-            lds_store_release(&cq.n_ready, pc.slot + 1);
-        } else {
-            lds_store_release(&cq.done, 1);
-        }
-    }
-    pc.slot = -1;
-}
-
 template <int D, int G, int CH, int R, int MODE>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void full_attn_split_kernel(FullParams p) {
     using GEO = Geo<D, G, CH>;
@@ -249,12 +89,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         return (int64_t)page * p.map.stride_page + (int64_t)(row & ((1 << p.map.page_shift) - 1)) * p.sn;
     };
 
-    // element offsets of this lane's rows in the tile starting at row t0 (rows past the end
-    // of the split are clamped to its last row; they are masked when consumed)
-    auto offsets = [&](int t0, int64_t (&off)[R]) {
+    // element offsets of this lane's rows in the tile starting at row t0; rows past `last`
+    // (the split's last row by default) are clamped to it and masked when consumed
+    auto offsets = [&](int t0, int64_t (&off)[R], int last = -1) {
+        if (last < 0) last = row1 - 1;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            const int row = min(t0 + r * GEO::RPG + slot, row1 - 1);
+            const int row = min(t0 + r * GEO::RPG + slot, last);
             off[r] = row_offset(row) + chunk * 8;
         }
     };
@@ -307,6 +148,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         sg.made_for = p.chunk_tile[p.n_chunks];
         int* ctr = p.chunk_ctr + (((int64_t)b * p.Hkv + g) * p.n_segs + seg) * kCtrStride;
         // a row of the segment that exists: where a wave with nothing left points its loads
+        // (all of them at this one row: the rows after it may lie outside the staged table)
         const int idle_row = min(sg.tile0 * TILE, n_rows - 1);
         if (paged) stage_table(idle_row, max(idle_row, min((sg.tile0 + sg.tiles) * TILE, n_rows) - 1));
         if (tid == 0) {
@@ -341,18 +183,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         PendingClaim pc;
         pc.raw = 0, pc.slot = -1, pc.first = 0;
         TileRef ta = next_tile(cq, ctr, qslot, pc, lane);
-        offsets(ta.tile >= 0 ? ta.tile * TILE : idle_row, off);
+        offsets(ta.tile >= 0 ? ta.tile * TILE : idle_row, off, ta.tile >= 0 ? -1 : idle_row);
         load_tile<GEO, R, NT>(bufA, Kb, Vb, off);
         while (ta.tile >= 0) {
             publish_claim(cq, p, ctr, pc, lane, sg);                      // (first pass only)
             const TileRef tb = next_tile(cq, ctr, qslot, pc, lane);
-            offsets(tb.tile >= 0 ? tb.tile * TILE : idle_row, off);   // nothing left: a harmless reload
+            offsets(tb.tile >= 0 ? tb.tile * TILE : idle_row, off, tb.tile >= 0 ? -1 : idle_row);   // nothing left: a harmless reload
             load_tile<GEO, R, NT>(bufB, Kb, Vb, off);
             consume(bufA, ta.tile * TILE, stage_of(ta));
             publish_claim(cq, p, ctr, pc, lane, sg);
             if (tb.tile < 0) break;
             ta = next_tile(cq, ctr, qslot, pc, lane);
-            offsets(ta.tile >= 0 ? ta.tile * TILE : idle_row, off);
+            offsets(ta.tile >= 0 ? ta.tile * TILE : idle_row, off, ta.tile >= 0 ? -1 : idle_row);
             load_tile<GEO, R, NT>(bufA, Kb, Vb, off);
             consume(bufB, tb.tile * TILE, stage_of(tb));
             publish_claim(cq, p, ctr, pc, lane, sg);

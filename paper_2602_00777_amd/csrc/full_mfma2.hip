@@ -1,0 +1,267 @@
+// Full layer, streaming pass (Algorithm 2, Full branch) for head_dim 128 with a wave's work in
+// the second matrix-core form (mfma2_core.h): whole-line K loads by lane pairs, whole-row V
+// loads transposed inside the lane, both contractions of Eq. 1 on v_mfma_f32_16x16x32_bf16.
+// Same role, outputs and launch geometry as the vector kernel (full_attn_impl.h) and the first
+// matrix-core kernel (full_mfma.hip): per-head online-softmax partials, the group-mean score of
+// every row, their range per split.  Loop shape as in the vector kernel's pipelined mode: a
+// wave tile is 32 rows, the loads of tile i+1 are issued (unconditionally, rows clamped to the
+// split's last row) before tile i is consumed, and the scores are staged in LDS and written
+// once after the loop, so that no vector store sits between the loads.  DYN: the rows are
+// handed out at run time (chunk_queue.h) instead of split evenly; scores are then staged by
+// ticket as in the vector kernel.
+#include "chunk_queue.h"
+#include "launch.h"
+#include "mfma2_core.h"
+
+namespace hylra {
+
+struct Tile32 {
+    uint4 k[2][4];      // blocks a, b: the lane-pair loads of K (see own_row)
+    uint4 v[8];         // rows 4 gq + j of a (j < 4) and of b (j >= 4), columns 8 n ..
+};
+
+template <int G, bool DYN>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void full_mfma2_kernel(FullParams p) {
+    constexpr int D = 128, NW = 4, TILE = 32, STEP = NW * TILE;
+    __shared__ float s_m[NW][16];
+    __shared__ float s_l[NW][16];
+    __shared__ __attribute__((aligned(16))) float s_acc[NW * G * D];
+    __shared__ float s_mm[2 * NW];
+    extern __shared__ float s_scores[];          // [rows_per_split], then the staged page table
+
+    const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = lane & 15, gq = lane >> 4;
+
+    const bool paged = p.map.table != nullptr;
+    const int64_t base = (paged ? 0 : (int64_t)b * p.sb) + (int64_t)g * p.sh;
+    const uint16_t* __restrict__ Kb = p.K + base;
+    const uint16_t* __restrict__ Vb = p.V + base;
+    const int64_t head0 = (int64_t)b * p.Hq + (int64_t)g * G;
+    uint4 qb[4];
+    mfma_load_q<D, G>(qb, p.q + head0 * D, n, gq);
+    State2 st;
+    st.init();
+
+    // rows of this sequence; a shorter sequence is cut into the same number of (shorter) splits
+    const int n_rows = seq_rows(p.map, b, p.N);
+    const int rps = DYN || n_rows == p.N ? p.rows_per_split
+                                         : (n_rows + p.n_splits * STEP - 1) / (p.n_splits * STEP) * STEP;
+    const int row0 = DYN ? 0 : split * rps;
+    const int row1 = DYN ? n_rows : min(n_rows, row0 + rps);
+    float* __restrict__ srow = p.scores + ((int64_t)b * p.Hkv + g) * p.score_stride;
+    float smin = 3.0e38f, smax = -3.0e38f;
+
+    // paged cache: the split's part of the sequence's page table, staged in LDS (read from
+    // memory if it does not fit there)
+    int* const s_tbl = reinterpret_cast<int*>(s_scores + p.rows_per_split);
+    const int32_t* __restrict__ tbl = p.map.table + (int64_t)b * p.map.table_stride;     // unused unless paged
+    int tbl_page0 = -1;
+    auto stage_table = [&](int first_row, int last_row) {                   // every thread; rows of this sequence
+        const int page0 = first_row >> p.map.page_shift, n_pages = (last_row >> p.map.page_shift) - page0 + 1;
+        if (n_pages <= p.tbl_cap) {
+            for (int i = tid; i < n_pages; i += NW * 64) s_tbl[i] = tbl[page0 + i];
+            tbl_page0 = page0;
+        }
+        __syncthreads();
+    };
+    if (!DYN && paged && row0 < row1) stage_table(row0, row1 - 1);
+    auto row_offset = [&](int row) -> int64_t {
+        if (!paged) return (int64_t)row * p.sn;
+        const int t = row >> p.map.page_shift;
+        const int page = tbl_page0 >= 0 ? s_tbl[t - tbl_page0] : tbl[t];
+        return (int64_t)page * p.map.stride_page + (int64_t)(row & ((1 << p.map.page_shift) - 1)) * p.sn;
+    };
+
+    // rows past `last` (the split's last row by default) are clamped to it and masked later
+    auto issue = [&](Tile32& buf, int t0, int last = -1) {
+        if (last < 0) last = row1 - 1;
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk) {
+            const int r0 = t0 + 16 * blk;
+            const int64_t offa = row_offset(min(r0 + (n & 7), last)) + 32 * (n >> 3) + 8 * gq;
+            const int64_t offb = row_offset(min(r0 + 8 + (n & 7), last)) + 32 * (n >> 3) + 8 * gq;
+#pragma unroll
+            for (int L = 0; L < 2; ++L) {
+                buf.k[blk][2 * L] = ld16<true>(Kb + offa + 64 * L);
+                buf.k[blk][2 * L + 1] = ld16<true>(Kb + offb + 64 * L);
+            }
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                buf.v[4 * blk + j] = ld16<true>(Vb + row_offset(min(r0 + 4 * gq + j, last)) + 8 * n);
+        }
+    };
+    // st0: where the tile's scores are staged in s_scores (negative: store to memory)
+    auto consume = [&](Tile32& buf, int t0, int st0) {
+        own_row(buf.k[0]);
+        own_row(buf.k[1]);
+        const int left = row1 - t0;                          // rows of this tile inside the split
+        const uint32_t mask_a = left >= 16 ? 0xffffu : left > 0 ? (1u << left) - 1u : 0u;
+        const uint32_t mask_b = left >= 32 ? 0xffffu : left > 16 ? (1u << (left - 16)) - 1u : 0u;
+        float4_t Sa, Sb;
+        group32<G>(st, buf.k[0], buf.k[1], buf.v, qb, mask_a, mask_b, p.scale_log2, n, gq, Sa, Sb);
+        // group-mean score of rows 4 gq + j of each block: sum over the 16 head lanes (padding
+        // heads hold 0); staged in LDS at the row's place in the split
+#pragma unroll
+        for (int blk = 0; blk < 2; ++blk)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float v = group_sum<16>(blk ? Sb[j] : Sa[j]) * p.scale_mean;
+                v = fminf(fmaxf(v, -3.0e38f), 3.0e38f);      // also maps NaN to a number
+                const int r = 16 * blk + 4 * gq + j;
+                if (r < left) {
+                    if (n == 0) {
+                        if (DYN && st0 < 0) srow[t0 + r] = v;
+                        else s_scores[st0 + r] = v;
+                    }
+                    smin = fminf(smin, v);
+                    smax = fmaxf(smax, v);
+                }
+            }
+    };
+
+    if (DYN && n_rows > 0) {
+        __shared__ ChunkQueue cq;
+        const int seg = split / p.wgs_per_seg, w = split - seg * p.wgs_per_seg;
+        const int tiles_b = (n_rows + TILE - 1) / TILE;            // tiles of this sequence
+        SegInfo sg;
+        sg.tile0 = (int)((int64_t)seg * tiles_b / p.n_segs);
+        sg.tiles = (int)((int64_t)(seg + 1) * tiles_b / p.n_segs) - sg.tile0;
+        sg.made_for = p.chunk_tile[p.n_chunks];
+        int* ctr = p.chunk_ctr + (((int64_t)b * p.Hkv + g) * p.n_segs + seg) * kCtrStride;
+        // a row of the segment that exists: where a wave with nothing left points its loads
+        // (all of them at this one row: the rows after it may lie outside the staged table)
+        const int idle_row = min(sg.tile0 * TILE, n_rows - 1);
+        if (paged) stage_table(idle_row, max(idle_row, min((sg.tile0 + sg.tiles) * TILE, n_rows) - 1));
+        if (tid == 0) {
+            int lo = 0, hi = 0;
+            bool has = false;
+            if (w < p.n_chunks) {
+                lo = chunk_bound(p, sg, w);
+                hi = chunk_bound(p, sg, w + 1);
+                has = hi > lo;
+                if (!has) {
+                    const int raw = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    has = settle_claim(p, sg, ctr, raw, lo, hi) >= 0;
+                }
+            }
+            cq.ticket = 0;
+            cq.first[0] = 0;
+            cq.first[1] = has ? hi - lo : 0;
+            cq.tile0[0] = has ? sg.tile0 + lo : 0;
+            cq.n_ready = 1;
+            cq.done = has ? 0 : 1;
+        }
+        __syncthreads();
+        QueueCursor cur;
+        cur.slot = 0;
+        cur.first = 0;
+        cur.next = lds_load(&cq.first[1]);
+        cur.tile0 = lds_load(&cq.tile0[0]);
+        const int stage_tiles = p.rows_per_split / TILE;      // tiles the staging area holds
+        auto stage_of = [&](const TileRef& t) { return t.ticket < stage_tiles ? t.ticket * TILE : -1; };
+        PendingClaim pc;
+        pc.raw = 0, pc.slot = -1, pc.first = 0;
+        Tile32 bufA, bufB;
+        TileRef ta = next_tile(cq, ctr, cur, pc, lane);
+        issue(bufA, ta.tile >= 0 ? ta.tile * TILE : idle_row, ta.tile >= 0 ? -1 : idle_row);
+        while (ta.tile >= 0) {
+            publish_claim(cq, p, ctr, pc, lane, sg);                  // (first pass only)
+            const TileRef tb = next_tile(cq, ctr, cur, pc, lane);
+            issue(bufB, tb.tile >= 0 ? tb.tile * TILE : idle_row, tb.tile >= 0 ? -1 : idle_row);    // nothing left: a harmless reload
+            consume(bufA, ta.tile * TILE, stage_of(ta));
+            publish_claim(cq, p, ctr, pc, lane, sg);
+            if (tb.tile < 0) break;
+            ta = next_tile(cq, ctr, cur, pc, lane);
+            issue(bufA, ta.tile >= 0 ? ta.tile * TILE : idle_row, ta.tile >= 0 ? -1 : idle_row);
+            consume(bufB, tb.tile * TILE, stage_of(tb));
+            publish_claim(cq, p, ctr, pc, lane, sg);
+        }
+        publish_claim(cq, p, ctr, pc, lane, sg);
+        __syncthreads();
+        // write the staged scores out, slot by slot (tile starts and the score stride are
+        // multiples of 4 floats, so the 16-byte stores are aligned)
+        const int n_slots = cq.n_ready;
+        for (int i = 0; i < n_slots; ++i) {
+            const int f0 = cq.first[i], f1 = min(cq.first[i + 1], stage_tiles);
+            const int r0 = cq.tile0[i] * TILE;
+            const int cnt = min((f1 - f0) * TILE, n_rows - r0);
+            const float* src = s_scores + f0 * TILE;
+            for (int e = 4 * tid; e < cnt; e += 4 * NW * 64) {
+                if (e + 4 <= cnt) {
+                    *reinterpret_cast<float4*>(srow + r0 + e) = *reinterpret_cast<const float4*>(src + e);
+                } else {
+                    for (int x = e; x < cnt; ++x) srow[r0 + x] = src[x];
+                }
+            }
+        }
+    } else if (!DYN && row0 < row1) {
+        Tile32 bufA, bufB;
+        int t0 = row0 + wave * TILE;
+        issue(bufA, t0);
+        while (t0 < row1) {
+            issue(bufB, t0 + STEP);
+            consume(bufA, t0, t0 - row0);
+            t0 += STEP;
+            if (t0 >= row1) break;
+            issue(bufA, t0 + STEP);
+            consume(bufB, t0, t0 - row0);
+            t0 += STEP;
+        }
+    }
+
+    // range of this split's group-mean scores (the finalise kernels bin on it)
+    smin = strided_minmax<1, false>(smin);
+    smax = strided_minmax<1, true>(smax);
+    if (lane == 0) {
+        s_mm[2 * wave] = smin;
+        s_mm[2 * wave + 1] = smax;
+    }
+    __syncthreads();                             // also: every score of the split is in LDS
+    if (tid == 0) {
+#pragma unroll
+        for (int w = 1; w < NW; ++w) {
+            smin = fminf(smin, s_mm[2 * w]);
+            smax = fmaxf(smax, s_mm[2 * w + 1]);
+        }
+        float* mm = p.part_mm + (((int64_t)b * p.Hkv + g) * p.n_splits + split) * 2;
+        mm[0] = smin;
+        mm[1] = smax;
+    }
+    if (!DYN) {
+        // row0 and the score stride are multiples of 4 floats: 16-byte stores are aligned
+        float* __restrict__ dst = srow + row0;
+        const int cnt = max(row1 - row0, 0);
+        for (int i = 4 * tid; i < cnt; i += 4 * NW * 64) {
+            if (i + 4 <= cnt) {
+                *reinterpret_cast<float4*>(dst + i) = *reinterpret_cast<const float4*>(s_scores + i);
+            } else {
+                for (int e = i; e < cnt; ++e) dst[e] = s_scores[e];
+            }
+        }
+    }
+    merge_store2<G, NW, false>(st, s_m, s_l, s_acc, p.part_ml + (head0 * p.n_splits + split) * 2,
+                               (int64_t)p.n_splits * 2, p.part_acc + (head0 * p.n_splits + split) * D,
+                               (int64_t)p.n_splits * D, n, gq);
+}
+
+// rows a workgroup consumes per sweep of its 4 waves; variant 72 = even splits, 74 = rows handed
+// out at run time
+int full_mfma2_quantum(int D, int variant) { return (D == 128 && (variant == 72 || variant == 74)) ? 128 : 0; }
+
+hipError_t launch_full_mfma2(const FullParams& p, int B, int G, int variant, hipStream_t st) {
+    if (variant != 72 && variant != 74) return hipErrorInvalidValue;
+    dim3 grid(p.n_splits, p.Hkv, B);
+    const size_t lds = p.rows_per_split * sizeof(float) + p.tbl_cap * sizeof(int);
+#define HYLRA_G(GG)                                                                                   \
+    if (G == GG) {                                                                                    \
+        if (variant == 74) hipLaunchKernelGGL((full_mfma2_kernel<GG, true>), grid, dim3(256), lds, st, p);  \
+        else hipLaunchKernelGGL((full_mfma2_kernel<GG, false>), grid, dim3(256), lds, st, p);         \
+        return hipGetLastError();                                                                     \
+    }
+    HYLRA_G(1) HYLRA_G(2) HYLRA_G(3) HYLRA_G(4) HYLRA_G(5) HYLRA_G(6) HYLRA_G(7) HYLRA_G(8)
+#undef HYLRA_G
+    return hipErrorInvalidValue;
+}
+
+}  // namespace hylra

@@ -161,11 +161,17 @@ hipError_t launch_reuse_split_d128(const ReuseParams& p, int B, int G, int varia
 int full_mfma_quantum(int variant);
 hipError_t launch_full_mfma(const FullParams& p, int B, int D, int G, int variant, hipStream_t st);
 
+// Second matrix-core Full kernel (full_mfma2.hip; head_dim 128): variant 72
+int full_mfma2_quantum(int D, int variant);
+hipError_t launch_full_mfma2(const FullParams& p, int B, int G, int variant, hipStream_t st);
+
 inline int full_block_quantum(int D, int G, int variant) {
+    if (variant >= 70) return full_mfma2_quantum(D, variant);
     if (variant >= 50) return (D == 64 || D == 128) ? full_mfma_quantum(variant) : 0;
     return D == 64 ? full_block_quantum_d64(G, variant) : D == 128 ? full_block_quantum_d128(G, variant) : 0;
 }
 inline hipError_t launch_full_split(const FullParams& p, int B, int D, int G, int variant, hipStream_t st) {
+    if (variant >= 70) return D == 128 ? launch_full_mfma2(p, B, G, variant, st) : hipErrorInvalidValue;
     if (variant >= 50) return launch_full_mfma(p, B, D, G, variant, st);
     return D == 64 ? launch_full_split_d64(p, B, G, variant, st)
          : D == 128 ? launch_full_split_d128(p, B, G, variant, st) : hipErrorInvalidValue;
