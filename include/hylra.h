@@ -174,6 +174,9 @@ hylra_status hylra_decode_step_blocks(hylra_ctx *ctx, const hylra_shape *shape, 
  * shape->ctx_len is the largest length a sequence of the call may have (it sizes
  * the launch); shape's kv strides are ignored.  One table serves K and V, and in
  * hylra_decode_step_paged every layer (each layer has its own pools).
+ * block_table == NULL means a contiguous cache with per-sequence lengths only:
+ * K_pool / V_pool are then K and V addressed through shape's strides, as in the
+ * calls above, and page_size, max_pages and the pool strides are ignored.
  *
  * Full layer: sequence b selects min(k, n_b) rows; idx[b, g, min(k, n_b) .. k-1]
  * = -1.  A sequence with n_b = 0 gets a zero output row and no index.  Requires
@@ -185,7 +188,7 @@ typedef struct {
     int64_t stride_page;        /* element strides of the pools, see above                  */
     int64_t stride_head;
     int64_t stride_row;
-    const int32_t *block_table; /* DEVICE [batch][max_pages]                                */
+    const int32_t *block_table; /* DEVICE [batch][max_pages]; NULL: contiguous cache           */
     const int32_t *seq_lens;    /* DEVICE [batch], or NULL                                  */
 } hylra_paged;
 

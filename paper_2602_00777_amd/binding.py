@@ -125,17 +125,25 @@ class PagedCache:
     length of the call.  Pools are bf16 tensors [pages, Hkv, page_size, d] (any strides with a
     contiguous innermost dimension); K and V pools of a layer share shape and strides."""
 
-    def __init__(self, block_table: torch.Tensor, page_size: int, ctx_len: int,
+    def __init__(self, block_table: Optional[torch.Tensor], page_size: int, ctx_len: int,
                  seq_lens: Optional[torch.Tensor] = None):
         for name, t in (("block_table", block_table), ("seq_lens", seq_lens)):
             if t is not None and (t.dtype != torch.int32 or not t.is_cuda or not t.is_contiguous()):
                 raise TypeError("%s must be a contiguous int32 CUDA tensor" % name)
-        if block_table.dim() != 2 or (seq_lens is not None and tuple(seq_lens.shape) != (block_table.shape[0],)):
+        if block_table is not None and (block_table.dim() != 2 or (seq_lens is not None and tuple(seq_lens.shape) != (block_table.shape[0],))):
             raise ValueError("block_table must be [B, max_pages] and seq_lens [B]")
+        if block_table is None and seq_lens is None:
+            raise ValueError("a contiguous cache without seq_lens needs no PagedCache")
         self.block_table, self.seq_lens = block_table, seq_lens
         self.page_size, self.ctx_len = int(page_size), int(ctx_len)
 
     def describe(self, q: torch.Tensor, pool: torch.Tensor, scale: float = 0.0) -> Tuple[Shape, Paged]:
+        if self.block_table is None:
+            # contiguous cache [B, Hkv, N, d] with per-sequence lengths only
+            shp = make_shape(q, pool, scale)
+            if shp.ctx_len != self.ctx_len or tuple(self.seq_lens.shape) != (shp.batch,):
+                raise ValueError("cache %s disagrees with ctx_len = %d or seq_lens" % (tuple(pool.shape), self.ctx_len))
+            return shp, Paged(0, 0, 0, 0, 0, None, self.seq_lens.data_ptr())
         B, Hq, d = q.shape
         P, Hkv, ps, dk = pool.shape
         if dk != d or ps != self.page_size or self.block_table.shape[0] != B:

@@ -162,12 +162,18 @@ hylra_status check_tensors(const hylra_ctx* ctx, const void* q, const void* K, c
 hylra_status check_paged(const hylra_ctx* ctx, const hylra_shape* s, const hylra_paged* pg, Strides& st, RowMap& map) {
     map = RowMap{};
     if (!pg) return HYLRA_OK;
+    if (!pg->block_table) {
+        // per-sequence lengths over a contiguous cache (addressed through the shape's strides)
+        if ((uintptr_t)pg->seq_lens & 3) return fail(ctx, HYLRA_ERR_BAD_ARG, "seq_lens must be 4-byte aligned");
+        map.seq_lens = pg->seq_lens;
+        return HYLRA_OK;
+    }
     if (pg->page_size < 1 || pg->page_size > 65536 || (pg->page_size & (pg->page_size - 1)))
         return fail(ctx, HYLRA_ERR_BAD_ARG, "page_size = %d is not a power of two in 1..65536", pg->page_size);
     if ((int64_t)pg->max_pages * pg->page_size < s->ctx_len)
         return fail(ctx, HYLRA_ERR_BAD_ARG, "max_pages = %d pages of %d rows do not cover ctx_len = %d", pg->max_pages, pg->page_size, s->ctx_len);
-    if (!pg->block_table || ((uintptr_t)pg->block_table & 3) || ((uintptr_t)pg->seq_lens & 3))
-        return fail(ctx, HYLRA_ERR_BAD_ARG, "block_table must be a 4-byte aligned device pointer (seq_lens too, or NULL)");
+    if (((uintptr_t)pg->block_table & 3) || ((uintptr_t)pg->seq_lens & 3))
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "block_table and seq_lens must be 4-byte aligned device pointers");
     if (pg->stride_row < s->head_dim || pg->stride_head < 0 || pg->stride_page < 0)
         return fail(ctx, HYLRA_ERR_BAD_ARG, "pool strides must be non-negative and stride_row >= head_dim");
     if (pg->stride_row % 8 || pg->stride_head % 8 || pg->stride_page % 8)
@@ -522,7 +528,7 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
     hylra_status rc = check_shape(ctx, shape, G, sd, scale);
     if (rc != HYLRA_OK) return rc;
     if ((rc = check_paged(ctx, shape, pg, sd, map)) != HYLRA_OK) return rc;
-    if (pg && block != 1) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "the block-level variant is not built for paged caches");
+    if (pg && block != 1) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "the block-level variant is not built for paged caches or per-sequence lengths");
     if ((rc = check_tensors(ctx, q, K, V, out)) != HYLRA_OK) return rc;
     if (!idx || ((uintptr_t)idx & 3)) return fail(ctx, HYLRA_ERR_BAD_ARG, "idx must be a 4-byte aligned device pointer");
     if (block < 1 || block > kMaxBlock) return fail(ctx, HYLRA_ERR_BAD_ARG, "block = %d is outside 1..%d", block, kMaxBlock);
@@ -637,7 +643,7 @@ hylra_status reuse_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pa
     hylra_status rc = check_shape(ctx, shape, G, sd, scale);
     if (rc != HYLRA_OK) return rc;
     if ((rc = check_paged(ctx, shape, pg, sd, map)) != HYLRA_OK) return rc;
-    if (pg && block != 1) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "the block-level variant is not built for paged caches");
+    if (pg && block != 1) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "the block-level variant is not built for paged caches or per-sequence lengths");
     if ((rc = check_tensors(ctx, q, K, V, out)) != HYLRA_OK) return rc;
     if (!idx || ((uintptr_t)idx & 3)) return fail(ctx, HYLRA_ERR_BAD_ARG, "idx must be a 4-byte aligned device pointer");
     if (block < 1 || block > kMaxBlock) return fail(ctx, HYLRA_ERR_BAD_ARG, "block = %d is outside 1..%d", block, kMaxBlock);

@@ -155,6 +155,29 @@ def test_paged_decode_step_chain():
         assert np.array_equal(idx_buf.cpu().numpy(), cur)
 
 
+@pytest.mark.parametrize("B,Hkv,G,d,N,k", [(4, 2, 4, 128, 5003, 300), (16, 8, 4, 128, 1500, 64), (3, 2, 7, 128, 3001, 256),
+                                          (2, 2, 2, 64, 2048, 128)])
+def test_sequence_lengths_on_a_contiguous_cache(B, Hkv, G, d, N, k):
+    """block_table == NULL: per-sequence lengths over the ordinary [B,Hkv,N,d] cache."""
+    say("ragged contiguous B=%d Hkv=%d G=%d d=%d N=%d k=%d" % (B, Hkv, G, d, N, k))
+    w = synth.Workload("case", 1, Hkv * G, Hkv, d, B, N, 1, (0,), 0.02, 3.0, 1.0, seed=N)
+    q, K, V = synth.make_layer(w, 0, synth.planted_positions(w)[0], DEV)
+    lens = synth.ragged_lengths(B, N, N)
+    lens[-1] = min(N, 29)
+    cache = binding.PagedCache(None, 0, N, torch.from_numpy(lens).to(DEV))
+    refs = oracle_full(q, K, V, lens, k)
+    with binding.Context(B, Hkv * G, Hkv, d, N, k) as ctx:
+        out, idx = ctx.full_attn_topk_paged(q, K, V, cache, k)
+        sparse = ctx.reuse_sparse_attn_paged(q, K, V, cache, idx)
+        torch.cuda.synchronize()
+        out, idx, sparse = out.cpu().numpy(), idx.cpu().numpy(), sparse.cpu().numpy()
+    check_full(out, idx, refs, lens, k, "ragged contiguous")
+    for b in range(B):
+        n = int(lens[b])
+        ref = oracle.reuse_sparse_attn(q[b:b + 1], K[b:b + 1, :, :n], V[b:b + 1, :, :n], idx[b:b + 1])
+        assert_out_close(sparse[b:b + 1], ref, "ragged contiguous reuse b=%d" % b)
+
+
 def test_paged_zero_length_sequence_and_errors():
     say("paged zero length, errors")
     B, Hkv, G, d, N, k, page = 3, 2, 4, 128, 1000, 100, 16
