@@ -49,7 +49,7 @@ def main():
     ap.add_argument("--paged", type=int, default=0,
                     help="paged KV cache: rows per page (pages scattered over a pool by a random block table); 0 = contiguous")
     ap.add_argument("--ragged", action="store_true",
-                    help="with --paged: sequence lengths uniform in [N/4, N] instead of all N")
+                    help="sequence lengths uniform in [N/4, N] instead of all N (with or without --paged)")
     ap.add_argument("--offload", type=int, default=0,
                     help="index-guided prefetch: keep the Reuse layers' caches in pinned host memory and fetch only "
                          "the selected rows over PCIe into this many staging slots (0 = everything resident)")
@@ -96,9 +96,6 @@ def main():
     qs, Ks, Vs = [x[0] for x in data], [x[1] for x in data], [x[2] for x in data]
     paged, lens = None, None
     if args.paged:
-        if args.block:
-            print("bench.py: --paged and --block exclude each other", file=sys.stderr)
-            sys.exit(2)
         table = synth.page_table(w.batch, w.ctx_len, args.paged, w.seed)
         n_pages = int(table.max()) + 1
         for l in range(w.n_layers):             # layer by layer, so that only one extra copy is alive
@@ -110,6 +107,10 @@ def main():
                                    torch.from_numpy(lens).to(dev) if lens is not None else None)
         torch.cuda.synchronize()
         log("paged: %d pages of %d rows%s" % (n_pages, args.paged, ", ragged lengths %s" % lens.tolist() if lens is not None else ""))
+    elif args.ragged:
+        lens = synth.ragged_lengths(w.batch, w.ctx_len, w.seed)
+        paged = binding.PagedCache(None, 0, w.ctx_len, torch.from_numpy(lens).to(dev))
+        log("contiguous cache, ragged lengths %s" % lens.tolist())
 
     ctx = binding.Context(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ctx_len, w.top_k)
     for o in args.opt:
@@ -121,7 +122,7 @@ def main():
     k_sel = w.top_k // args.block if args.block else w.top_k
     searched = None
     if args.policy == "search":
-        if args.block or args.paged:
+        if args.block or args.paged or args.ragged:
             print("bench.py: --policy search runs on the contiguous token-level layout", file=sys.stderr)
             sys.exit(2)
         # offline profiling as in the paper: full attention at every layer, top-k sets, pairwise
@@ -145,7 +146,7 @@ def main():
         n_reuse = int((policy == synth.REUSE).sum())
         del sets
     if args.offload:
-        if args.block or args.paged or args.graph:
+        if args.block or args.paged or args.ragged or args.graph:
             print("bench.py: --offload runs on the contiguous token-level layout, launched eagerly", file=sys.stderr)
             sys.exit(2)
         t0 = time.time()
@@ -209,7 +210,7 @@ def main():
         return {"bound": "hbm", "kernel": kernel, "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
                 "algorithmic_bytes": nbytes, "avg_us": round(kk["avg_us"], 2),
-                "traffic": None if args.paged or args.block else MEASURED_TRAFFIC_BYTES.get((w.name, kernel))}
+                "traffic": None if args.paged or args.block or args.ragged else MEASURED_TRAFFIC_BYTES.get((w.name, kernel))}
 
     full_time = (kernels.get("full_attn", {}).get("avg_us") or 0) * n_full
     reuse_time = (kernels.get("reuse_attn", {}).get("avg_us") or 0) * n_reuse
@@ -239,7 +240,7 @@ def main():
         del src, dst
 
     cpu = None
-    if not args.no_cpu_baseline and not args.paged:
+    if not args.no_cpu_baseline and not args.paged and not args.ragged:
         cpu = cpu_baseline(w, policy, qs, Ks, Vs, n_full, n_reuse, args.block)
 
     line = {

@@ -212,6 +212,28 @@ hylra_status hylra_decode_step_paged(hylra_ctx *ctx, const hylra_shape *shape,
                                      void *hip_stream);
 
 /*
+ * The block-level variant on a paged cache or with per-sequence lengths: blocks are
+ * `block` consecutive rows of a sequence (they need not line up with pages); sequence b
+ * has ceil(n_b / block) of them, the last one possibly short, selects
+ * min(kb, ceil(n_b / block)) and pads its index entries with -1.  Arguments as in the
+ * calls of the same names above.
+ */
+hylra_status hylra_full_attn_topk_blocks_paged(hylra_ctx *ctx, const hylra_shape *shape,
+                                               const hylra_paged *cache, const void *q,
+                                               const void *K_pool, const void *V_pool, int32_t block,
+                                               int32_t kb, float *out, int32_t *bidx, void *hip_stream);
+hylra_status hylra_reuse_block_attn_paged(hylra_ctx *ctx, const hylra_shape *shape,
+                                          const hylra_paged *cache, const void *q,
+                                          const void *K_pool, const void *V_pool, const int32_t *bidx,
+                                          int32_t block, int32_t kb, float *out, void *hip_stream);
+hylra_status hylra_decode_step_blocks_paged(hylra_ctx *ctx, const hylra_shape *shape,
+                                            const hylra_paged *cache, int32_t n_layers,
+                                            const uint8_t *policy, const void *const *q_l,
+                                            const void *const *K_pool_l, const void *const *V_pool_l,
+                                            int32_t block, int32_t kb, float *const *out_l,
+                                            int32_t *bidx_buf, void *hip_stream);
+
+/*
  * Index-guided prefetch ("Bandwidth reduction via index-guided offloading"): when
  * a tolerant layer's cache lives in memory the GPU reads slowly (pinned host memory
  * across PCIe), its index set is known as soon as the preceding Full layer has

@@ -23,6 +23,7 @@ EXPORTS = (
     "hylra_full_attn_topk", "hylra_reuse_sparse_attn", "hylra_decode_step",
     "hylra_full_attn_topk_blocks", "hylra_reuse_block_attn", "hylra_decode_step_blocks",
     "hylra_full_attn_topk_paged", "hylra_reuse_sparse_attn_paged", "hylra_decode_step_paged",
+    "hylra_full_attn_topk_blocks_paged", "hylra_reuse_block_attn_paged", "hylra_decode_step_blocks_paged",
     "hylra_overlap_counts", "hylra_similarity_matrix", "hylra_policy_search",
     "hylra_offload_slot_bytes", "hylra_gather_rows", "hylra_decode_step_offloaded",
     "hylra_set_option", "hylra_profile_enable", "hylra_profile_reset", "hylra_profile_read",
@@ -83,6 +84,9 @@ def load_library() -> ctypes.CDLL:
     lib.hylra_full_attn_topk_paged.argtypes = [vp, sp, pp, vp, vp, vp, i32, vp, vp, vp]
     lib.hylra_reuse_sparse_attn_paged.argtypes = [vp, sp, pp, vp, vp, vp, vp, i32, vp, vp]
     lib.hylra_decode_step_paged.argtypes = [vp, sp, pp, i32, vp, vp, vp, vp, i32, vp, vp, vp]
+    lib.hylra_full_attn_topk_blocks_paged.argtypes = [vp, sp, pp, vp, vp, vp, i32, i32, vp, vp, vp]
+    lib.hylra_reuse_block_attn_paged.argtypes = [vp, sp, pp, vp, vp, vp, vp, i32, i32, vp, vp]
+    lib.hylra_decode_step_blocks_paged.argtypes = [vp, sp, pp, i32, vp, vp, vp, vp, i32, i32, vp, vp, vp]
     lib.hylra_offload_slot_bytes.argtypes = [sp, i32]
     lib.hylra_gather_rows.argtypes = [vp, sp, vp, vp, vp, i32, vp, vp, vp, vp]
     lib.hylra_decode_step_offloaded.argtypes = [vp, sp, i32, vp, vp, vp, vp, i32, vp, vp, vp, ctypes.c_size_t, vp, vp]
@@ -294,6 +298,39 @@ class Context:
         self._check(rc, "hylra_reuse_sparse_attn_paged")
         return out
 
+    def full_attn_topk_blocks_paged(self, q, K_pool, V_pool, cache: PagedCache, block: int, kb: int,
+                                    out=None, bidx=None, scale: float = 0.0):
+        """hylra_full_attn_topk_blocks_paged: returns (out fp32 [B,Hq,d], bidx int32 [B,Hkv,kb])."""
+        self._check_inputs(q, K_pool, V_pool)
+        shp, pg = cache.describe(q, K_pool, scale)
+        if out is None:
+            out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+        if bidx is None:
+            bidx = torch.empty((shp.batch, shp.n_kv_heads, kb), dtype=torch.int32, device=q.device)
+        rc = self._lib.hylra_full_attn_topk_blocks_paged(self._h, ctypes.byref(shp), ctypes.byref(pg),
+                                                         q.data_ptr(), K_pool.data_ptr(), V_pool.data_ptr(),
+                                                         block, kb, out.data_ptr(), bidx.data_ptr(),
+                                                         _stream_ptr(q.device))
+        self._check(rc, "hylra_full_attn_topk_blocks_paged")
+        return out, bidx
+
+    def reuse_block_attn_paged(self, q, K_pool, V_pool, cache: PagedCache, bidx, block: int, out=None,
+                               scale: float = 0.0):
+        """hylra_reuse_block_attn_paged: returns out fp32 [B,Hq,d]."""
+        self._check_inputs(q, K_pool, V_pool)
+        if bidx.dtype != torch.int32 or not bidx.is_cuda or not bidx.is_contiguous():
+            raise TypeError("bidx must be a contiguous int32 CUDA tensor")
+        shp, pg = cache.describe(q, K_pool, scale)
+        if tuple(bidx.shape[:2]) != (shp.batch, shp.n_kv_heads):
+            raise ValueError("bidx must be [B, Hkv, kb]")
+        if out is None:
+            out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+        rc = self._lib.hylra_reuse_block_attn_paged(self._h, ctypes.byref(shp), ctypes.byref(pg), q.data_ptr(),
+                                                    K_pool.data_ptr(), V_pool.data_ptr(), bidx.data_ptr(),
+                                                    block, bidx.shape[2], out.data_ptr(), _stream_ptr(q.device))
+        self._check(rc, "hylra_reuse_block_attn_paged")
+        return out
+
     # -- index-guided prefetch (offloaded caches) -------------------------------------------
     def gather_rows(self, K_src, V_src, idx, device=None):
         """hylra_gather_rows: K_src / V_src bf16 [B,Hkv,N,d] in device or pinned host memory;
@@ -405,14 +442,13 @@ class Context:
         """Marshals the per-layer pointer arrays of hylra_decode_step once, so that a timed
         loop contains nothing but the C call.  Returns a zero-argument callable plus the
         output tensors (outs, idx_buf).  block > 0 selects hylra_decode_step_blocks, with k
-        counting blocks; paged selects hylra_decode_step_paged, with K_l / V_l the pools."""
+        counting blocks; paged selects hylra_decode_step_paged (hylra_decode_step_blocks_paged
+        with block > 0), with K_l / V_l the pools."""
         L = len(policy)
         for l in range(L):
             self._check_inputs(q_l[l], K_l[l], V_l[l])
         pg = None
         if paged is not None:
-            if block:
-                raise ValueError("the block-level variant is not built for paged caches")
             shp, pg = paged.describe(q_l[0], K_l[0], scale)
             for l in range(1, L):
                 o, og = paged.describe(q_l[l], K_l[l], scale)
@@ -436,7 +472,12 @@ class Context:
         keep = (q_l, K_l, V_l, paged)
 
         def run():
-            if pg is not None:
+            if pg is not None and block > 0:
+                rc = self._lib.hylra_decode_step_blocks_paged(self._h, ctypes.byref(shp), ctypes.byref(pg), L, pol,
+                                                              qa, Ka, Va, block, k, oa, idx_buf.data_ptr(),
+                                                              _stream_ptr(dev))
+                self._check(rc, "hylra_decode_step_blocks_paged")
+            elif pg is not None:
                 rc = self._lib.hylra_decode_step_paged(self._h, ctypes.byref(shp), ctypes.byref(pg), L, pol,
                                                        qa, Ka, Va, k, oa, idx_buf.data_ptr(), _stream_ptr(dev))
                 self._check(rc, "hylra_decode_step_paged")

@@ -528,7 +528,6 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
     hylra_status rc = check_shape(ctx, shape, G, sd, scale);
     if (rc != HYLRA_OK) return rc;
     if ((rc = check_paged(ctx, shape, pg, sd, map)) != HYLRA_OK) return rc;
-    if (pg && block != 1) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "the block-level variant is not built for paged caches or per-sequence lengths");
     if ((rc = check_tensors(ctx, q, K, V, out)) != HYLRA_OK) return rc;
     if (!idx || ((uintptr_t)idx & 3)) return fail(ctx, HYLRA_ERR_BAD_ARG, "idx must be a 4-byte aligned device pointer");
     if (block < 1 || block > kMaxBlock) return fail(ctx, HYLRA_ERR_BAD_ARG, "block = %d is outside 1..%d", block, kMaxBlock);
@@ -581,6 +580,7 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
         bp.scores = ctx->scores, bp.score_stride = fp.score_stride;
         bp.bscores = ctx->bscores, bp.bscore_stride = round_up(n_sel, 4);
         bp.N = shape->ctx_len, bp.block = block, bp.n_blocks = n_sel;
+        bp.seq_lens = map.seq_lens;
         if (pairs * bp.bscore_stride > ctx->cap_bscores)
             return fail(ctx, HYLRA_ERR_WORKSPACE, "shape needs %lld block-score floats, workspace holds %lld",
                         (long long)(pairs * bp.bscore_stride), (long long)ctx->cap_bscores);
@@ -606,7 +606,7 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
         sp.scores = sel_scores, sp.score_stride = sel_stride;
         sp.n_splits = pl.n_splits, sp.Hq = shape->n_q_heads, sp.Hkv = shape->n_kv_heads;
         sp.G = G, sp.D = shape->head_dim, sp.N = n_sel, sp.k = k;
-        sp.seq_lens = map.seq_lens;
+        sp.seq_lens = map.seq_lens, sp.sel_block = block;
         sp.out = out, sp.idx = want_idx ? idx : nullptr;
         int* w = ctx->sel_ws;
         sp.ghist = w, w += ctx->pairs_cap * 4096;
@@ -625,7 +625,7 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
     zp.scores = sel_scores, zp.score_stride = sel_stride;
     zp.n_splits = pl.n_splits, zp.Hq = shape->n_q_heads, zp.Hkv = shape->n_kv_heads;
     zp.G = G, zp.D = shape->head_dim, zp.N = n_sel, zp.k = k;
-    zp.seq_lens = map.seq_lens;
+    zp.seq_lens = map.seq_lens, zp.sel_block = block;
     zp.variant = ctx->opt_finalize_variant == 2 ? 1 : 0;
     zp.out = out, zp.idx = want_idx ? idx : nullptr;
     HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_full_finalize(zp, shape->batch, st); }));
@@ -643,7 +643,6 @@ hylra_status reuse_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pa
     hylra_status rc = check_shape(ctx, shape, G, sd, scale);
     if (rc != HYLRA_OK) return rc;
     if ((rc = check_paged(ctx, shape, pg, sd, map)) != HYLRA_OK) return rc;
-    if (pg && block != 1) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "the block-level variant is not built for paged caches or per-sequence lengths");
     if ((rc = check_tensors(ctx, q, K, V, out)) != HYLRA_OK) return rc;
     if (!idx || ((uintptr_t)idx & 3)) return fail(ctx, HYLRA_ERR_BAD_ARG, "idx must be a 4-byte aligned device pointer");
     if (block < 1 || block > kMaxBlock) return fail(ctx, HYLRA_ERR_BAD_ARG, "block = %d is outside 1..%d", block, kMaxBlock);
@@ -789,6 +788,34 @@ hylra_status hylra_decode_step_paged(hylra_ctx* ctx, const hylra_shape* shape, c
     if (!ctx) return HYLRA_ERR_BAD_ARG;
     if (!cache) return fail(ctx, HYLRA_ERR_BAD_ARG, "cache is NULL");
     return step_impl(ctx, shape, cache, n_layers, policy, q_l, K_pool_l, V_pool_l, 1, k, out_l, idx_buf, hip_stream);
+}
+
+hylra_status hylra_full_attn_topk_blocks_paged(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* cache,
+                                               const void* q, const void* K_pool, const void* V_pool,
+                                               int32_t block, int32_t kb, float* out, int32_t* bidx,
+                                               void* hip_stream) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    if (!cache) return fail(ctx, HYLRA_ERR_BAD_ARG, "cache is NULL");
+    return full_impl(ctx, shape, cache, q, K_pool, V_pool, block, kb, out, bidx, hip_stream);
+}
+
+hylra_status hylra_reuse_block_attn_paged(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* cache,
+                                          const void* q, const void* K_pool, const void* V_pool,
+                                          const int32_t* bidx, int32_t block, int32_t kb, float* out,
+                                          void* hip_stream) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    if (!cache) return fail(ctx, HYLRA_ERR_BAD_ARG, "cache is NULL");
+    return reuse_impl(ctx, shape, cache, q, K_pool, V_pool, bidx, block, kb, out, hip_stream);
+}
+
+hylra_status hylra_decode_step_blocks_paged(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* cache,
+                                            int32_t n_layers, const uint8_t* policy, const void* const* q_l,
+                                            const void* const* K_pool_l, const void* const* V_pool_l,
+                                            int32_t block, int32_t kb, float* const* out_l, int32_t* bidx_buf,
+                                            void* hip_stream) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    if (!cache) return fail(ctx, HYLRA_ERR_BAD_ARG, "cache is NULL");
+    return step_impl(ctx, shape, cache, n_layers, policy, q_l, K_pool_l, V_pool_l, block, kb, out_l, bidx_buf, hip_stream);
 }
 
 size_t hylra_offload_slot_bytes(const hylra_shape* shape, int32_t k) {

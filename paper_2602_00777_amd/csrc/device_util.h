@@ -101,6 +101,12 @@ DEVI int seq_rows(const MAP& m, int b, int N) {
 DEVI int seq_rows(const int32_t* seq_lens, int b, int N) {
     return seq_lens ? min(max(seq_lens[b], 0), N) : N;
 }
+// Units of `block` rows (the last one may be short) that sequence b has, out of at most n_units.
+DEVI int seq_units(const int32_t* seq_lens, int b, int n_units, int block) {
+    if (!seq_lens) return n_units;
+    const int len = seq_lens[b];
+    return len <= 0 ? 0 : min((len - 1) / block + 1, n_units);
+}
 // Element offset of row `row` of sequence b from the (batch-independent) base of a paged pool;
 // tbl points at the sequence's row of the page table (in memory or staged in LDS).
 template <class MAP>

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int S = p.n_splits, D = p.D, G = p.G;
     // this sequence ranks its first N rows and selects k of them (all of them if it has fewer)
-    const int N = seq_rows(p.seq_lens, b, p.N), k = min(p.k, N);
+    const int N = seq_units(p.seq_lens, b, p.N, p.sel_block), k = min(p.k, N);
     const int64_t pair = (int64_t)b * p.Hkv + g;
     int32_t* __restrict__ dst = p.idx + pair * (int64_t)p.k;
     if (p.idx)
@@ -451,15 +451,17 @@ __global__ __launch_bounds__(kBlockMaxThreads) void block_max_kernel(BlockMaxPar
     const float* __restrict__ sc = p.scores + pair * p.score_stride;
     float* __restrict__ dst = p.bscores + pair * p.bscore_stride;
     const int sub = threadIdx.x & (L - 1), grp = threadIdx.x / L, groups = kBlockMaxThreads / L;
+    const int n_rows = seq_rows(p.seq_lens, (int)blockIdx.z, p.N);
+    const int n_blocks = seq_units(p.seq_lens, (int)blockIdx.z, p.n_blocks, p.block);
     for (int s = 0; s < kBlockMaxSweeps; ++s) {
         const int c = (blockIdx.x * kBlockMaxSweeps + s) * groups + grp;     // uniform per lane group
         float m = -3.0e38f;
-        if (c < p.n_blocks) {
-            const int lo = c * p.block, hi = min(p.N, lo + p.block);
+        if (c < n_blocks) {
+            const int lo = c * p.block, hi = min(n_rows, lo + p.block);
             for (int j = lo + sub; j < hi; j += L) m = fmaxf(m, sc[j]);
         }
         for (int mask = 1; mask < L; mask <<= 1) m = fmaxf(m, __shfl_xor(m, mask, 64));
-        if (c < p.n_blocks && sub == 0) dst[c] = m;
+        if (c < n_blocks && sub == 0) dst[c] = m;
     }
 }
 

@@ -73,22 +73,42 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         return (int64_t)page * p.map.stride_page + (int64_t)(row & ((1 << p.map.page_shift) - 1)) * p.sn;
     };
 
-    // rows past `last` (the split's last row by default) are clamped to it and masked later
+    // Rows past `last` (the split's last row by default) are clamped to it and masked later.
+    // A block of 16 rows starts at a multiple of 16, so with pages of 16 rows or more it lies
+    // inside one page (as it trivially does in a contiguous cache): one 64-bit offset per block
+    // (one page-table lookup) and 32-bit distances from it for the lanes' rows.  Smaller pages:
+    // every row is looked up (also with row strides so large that 16 of them overflow 32 bits).
+    const bool by_block = (!paged || p.map.page_shift >= 4) && p.sn < (1 << 26);
+    const int sn = (int)p.sn;
     auto issue = [&](Tile32& buf, int t0, int last = -1) {
         if (last < 0) last = row1 - 1;
 #pragma unroll
         for (int blk = 0; blk < 2; ++blk) {
             const int r0 = t0 + 16 * blk;
-            const int64_t offa = row_offset(min(r0 + (n & 7), last)) + 32 * (n >> 3) + 8 * gq;
-            const int64_t offb = row_offset(min(r0 + 8 + (n & 7), last)) + 32 * (n >> 3) + 8 * gq;
+            const int ra = min(r0 + (n & 7), last), rb = min(r0 + 8 + (n & 7), last);
+            int64_t offa, offb, offv[4];
+            if (by_block) {
+                const int rc = min(r0, last);                    // <= every clamped row of the block
+                const int64_t blk_base = row_offset(rc);
+                offa = blk_base + (ra - rc) * sn;
+                offb = blk_base + (rb - rc) * sn;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) offv[j] = blk_base + (min(r0 + 4 * gq + j, last) - rc) * sn;
+            } else {
+                offa = row_offset(ra);
+                offb = row_offset(rb);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) offv[j] = row_offset(min(r0 + 4 * gq + j, last));
+            }
+            offa += 32 * (n >> 3) + 8 * gq;
+            offb += 32 * (n >> 3) + 8 * gq;
 #pragma unroll
             for (int L = 0; L < 2; ++L) {
                 buf.k[blk][2 * L] = ld16<true>(Kb + offa + 64 * L);
                 buf.k[blk][2 * L + 1] = ld16<true>(Kb + offb + 64 * L);
             }
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                buf.v[4 * blk + j] = ld16<true>(Vb + row_offset(min(r0 + 4 * gq + j, last)) + 8 * n);
+            for (int j = 0; j < 4; ++j) buf.v[4 * blk + j] = ld16<true>(Vb + offv[j] + 8 * n);
         }
     };
     // st0: where the tile's scores are staged in s_scores (negative: store to memory)

@@ -61,6 +61,7 @@ struct FinalizeParams {
     int n_splits, Hq, Hkv, G, D, N, k;
     const int32_t* seq_lens;        // [B] or nullptr: sequence b ranks its first n_b rows and selects
                                     // min(k, n_b) of them; the rest of its k index entries are -1
+    int sel_block;                  // rows per ranked unit (N and k count units): n_b = ceil(len / sel_block)
     int variant;                    // 0: scores kept in registers when they fit; 1: always re-read
     float* out;                     // [B][Hq][D]
     int32_t* idx;                   // [B][Hkv][k]
@@ -76,6 +77,7 @@ struct SelectParams {
     int64_t score_stride;
     int n_splits, Hq, Hkv, G, D, N, k;
     const int32_t* seq_lens;        // as in FinalizeParams
+    int sel_block;
     float* out;                     // [B][Hq][D]
     int32_t* idx;                   // [B][Hkv][k]
     int* ghist;                     // [B*Hkv][4096] score histogram; zero between launches
@@ -115,6 +117,7 @@ struct BlockMaxParams {
     float* bscores;                 // [B*Hkv][bscore_stride] block scores
     int64_t bscore_stride;
     int N, block, n_blocks;
+    const int32_t* seq_lens;        // [B] or nullptr: only the blocks that hold rows of sequence b are written
 };
 
 // Pooled overlap counts between the index sets of the layers (policy.hip).

@@ -86,7 +86,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_hist_kernel(SelectParams p
     const int64_t pair = (int64_t)b * p.Hkv + g;
     const int S = p.n_splits, D = p.D, G = p.G;
 
-    const int N = p.idx ? seq_rows(p.seq_lens, b, p.N) : 0; // rows this sequence ranks (none: merge only)
+    const int N = p.idx ? seq_units(p.seq_lens, b, p.N, p.sel_block) : 0; // rows this sequence ranks (none: merge only)
     Chunk<E> ch;
     ch.load(p.scores + pair * p.score_stride, N, c);        // in flight during the merge below
     for (int i = tid; i < SEL_BINS; i += SEL_THREADS) s_hist[i] = 0;
@@ -168,7 +168,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_classify_kernel(SelectPara
     const int tid = threadIdx.x;
     const int64_t pair = (int64_t)b * p.Hkv + g;
 
-    const int N = seq_rows(p.seq_lens, b, p.N), k = min(p.k, N);
+    const int N = seq_units(p.seq_lens, b, p.N, p.sel_block), k = min(p.k, N);
     Chunk<E> ch;
     ch.load(p.scores + pair * p.score_stride, N, c);
     if (tid == 0) s_gt = 0, s_pick[0] = SEL_BINS, s_pick[1] = 0;      // (k = 0: nothing is selected)
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_emit_kernel(SelectParams p
     const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z, C = gridDim.x;
     const int tid = threadIdx.x;
     const int64_t pair = (int64_t)b * p.Hkv + g;
-    const int N = seq_rows(p.seq_lens, b, p.N), k = min(p.k, N);
+    const int N = seq_units(p.seq_lens, b, p.N, p.sel_block), k = min(p.k, N);
     const float* __restrict__ sc = p.scores + pair * p.score_stride;
     int32_t* __restrict__ dst = p.idx + pair * (int64_t)p.k;
     if (c == 0)

@@ -155,6 +155,41 @@ def test_paged_decode_step_chain():
         assert np.array_equal(idx_buf.cpu().numpy(), cur)
 
 
+def test_paged_block_decode_step_chain():
+    """The layer chain with block indices on a paged, ragged batch: equal to the single calls."""
+    say("paged block decode step")
+    B, Hkv, G, d, N, block, kb, page, L = 4, 2, 4, 128, 3000, 32, 8, 16, 5
+    w = synth.Workload("chain", L, Hkv * G, Hkv, d, B, N, kb * block, (0, 3), 0.02, 3.0, 0.8, seed=6)
+    policy, _, data = synth.make_workload(w, DEV)
+    table = synth.page_table(B, N, page, 6)
+    lens = synth.ragged_lengths(B, N, 6)
+    pools = [(synth.to_pool(K, table, page), synth.to_pool(V, table, page)) for _, K, V in data]
+    cache = binding.PagedCache(torch.from_numpy(table).to(DEV), page, N, torch.from_numpy(lens).to(DEV))
+    qs = [x[0] for x in data]
+    with binding.Context(B, Hkv * G, Hkv, d, N, kb * block) as ctx:
+        outs, idx_buf = ctx.decode_step(policy, qs, [p[0] for p in pools], [p[1] for p in pools], kb,
+                                        block=block, paged=cache)
+        torch.cuda.synchronize()
+        cur = None
+        for l in range(L):
+            if policy[l] == synth.FULL:
+                o, cur = ctx.full_attn_topk_blocks_paged(qs[l], pools[l][0], pools[l][1], cache, block, kb)
+            else:
+                o = ctx.reuse_block_attn_paged(qs[l], pools[l][0], pools[l][1], cache, cur, block)
+            torch.cuda.synchronize()
+            assert torch.allclose(o, outs[l], rtol=1e-5, atol=1e-6), "layer %d" % l
+        assert torch.equal(idx_buf, cur)
+        # and the first Full layer against the oracle, per sequence
+        q, K, V = data[0]
+        first = ctx.full_attn_topk_blocks_paged(q, pools[0][0], pools[0][1], cache, block, kb)[1].cpu().numpy()
+        for b in range(B):
+            n = int(lens[b])
+            kk = min(kb, -(-n // block))
+            _, ref_bidx, bs = oracle.full_attn_topk_blocks(q[b:b + 1], K[b:b + 1, :, :n], V[b:b + 1, :, :n], block, kk,
+                                                           want_bscore=True)
+            assert_idx_valid(first[b:b + 1, :, :kk], bs, kk, "b=%d" % b, exact_ref=ref_bidx)
+
+
 @pytest.mark.parametrize("B,Hkv,G,d,N,k", [(4, 2, 4, 128, 5003, 300), (16, 8, 4, 128, 1500, 64), (3, 2, 7, 128, 3001, 256),
                                           (2, 2, 2, 64, 2048, 128)])
 def test_sequence_lengths_on_a_contiguous_cache(B, Hkv, G, d, N, k):
@@ -176,6 +211,53 @@ def test_sequence_lengths_on_a_contiguous_cache(B, Hkv, G, d, N, k):
         n = int(lens[b])
         ref = oracle.reuse_sparse_attn(q[b:b + 1], K[b:b + 1, :, :n], V[b:b + 1, :, :n], idx[b:b + 1])
         assert_out_close(sparse[b:b + 1], ref, "ragged contiguous reuse b=%d" % b)
+
+
+BLOCK_CASES = [
+    # B, Hkv, G, d,   N,  block, kb, page (0: contiguous with lengths)
+    (4, 2, 4, 128, 4099, 128, 7, 16),       # blocks of 8 pages
+    (3, 2, 4, 128, 3000, 48, 20, 32),       # blocks that straddle pages
+    (3, 1, 7, 128, 3001, 100, 11, 0),
+    (4, 2, 2, 64, 2048, 16, 40, 64),        # several blocks per page
+    (16, 8, 4, 128, 1500, 32, 8, 16),       # self-scheduling Full kernel
+    (2, 1, 4, 128, 36000, 8, 300, 16),      # three-launch selection over 4500 blocks
+]
+
+
+@pytest.mark.parametrize("B,Hkv,G,d,N,block,kb,page", BLOCK_CASES)
+def test_paged_block_level_variant(B, Hkv, G, d, N, block, kb, page):
+    """Block TopK and block reuse per sequence: sequence b has ceil(n_b / block) blocks."""
+    say("paged blocks B=%d Hkv=%d G=%d d=%d N=%d block=%d kb=%d page=%d" % (B, Hkv, G, d, N, block, kb, page))
+    q, K, V, Kp, Vp, cache, lens = make_case(900 + N + block, B, Hkv, G, d, N, page or 16, True)
+    lens[0] = N                                     # one sequence of full length ...
+    lens[-1] = max(1, N - block // 2 - 1)           # ... and one whose last block is short
+    dlens = torch.from_numpy(lens).to(DEV)
+    if page:
+        cache = binding.PagedCache(cache.block_table, page, N, dlens)
+    else:
+        cache, Kp, Vp = binding.PagedCache(None, 0, N, dlens), K, V
+    q2 = torch.roll(q, 1, dims=1).contiguous()      # another query for the Reuse layer
+    with binding.Context(B, Hkv * G, Hkv, d, N, min(N, kb * block)) as ctx:
+        out, bidx = ctx.full_attn_topk_blocks_paged(q, Kp, Vp, cache, block, kb)
+        sparse = {}
+        for variant in (1, 4):
+            ctx.set_option("reuse_variant", variant)
+            sparse[variant] = ctx.reuse_block_attn_paged(q2, Kp, Vp, cache, bidx, block)
+        torch.cuda.synchronize()
+        out, bidx = out.cpu().numpy(), bidx.cpu().numpy()
+        sparse = {v: o.cpu().numpy() for v, o in sparse.items()}
+    for b in range(B):
+        n = int(lens[b])
+        nb = -(-n // block)
+        kk = min(kb, nb)
+        Kb, Vb = K[b:b + 1, :, :n], V[b:b + 1, :, :n]
+        ref_out, ref_bidx, bs = oracle.full_attn_topk_blocks(q[b:b + 1], Kb, Vb, block, kk, want_bscore=True)
+        assert_out_close(out[b:b + 1], ref_out, "full out b=%d" % b)
+        assert np.all(bidx[b, :, kk:] == -1), "entries past min(kb, blocks of the sequence) must be -1 (b=%d)" % b
+        assert_idx_valid(bidx[b:b + 1, :, :kk], bs, kk, "block idx b=%d" % b, exact_ref=ref_bidx)
+        ref = oracle.reuse_block_attn(q2[b:b + 1], Kb, Vb, bidx[b:b + 1, :, :kk], block)
+        for v, o in sparse.items():
+            assert_out_close(o[b:b + 1], ref, "reuse v%d b=%d" % (v, b))
 
 
 def test_paged_zero_length_sequence_and_errors():
