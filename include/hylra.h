@@ -330,6 +330,9 @@ hylra_status hylra_policy_search(hylra_ctx *ctx, int32_t n_layers, const double 
  *                       3 = three launches with several workgroups per (batch, KV head)
  *                       (default beyond 32768 rows)
  *   "finalize_groups"   rows per workgroup of the three-launch finalise, in units of 4096: 2 or 8
+ *   "ragged_even"       1 = with seq_lens, give every (batch, KV head) the same number of
+ *                       workgroups of the self-scheduling Full kernel instead of a number in
+ *                       proportion to its rows
  */
 hylra_status hylra_set_option(hylra_ctx *ctx, const char *name, int32_t value);
 

@@ -46,6 +46,10 @@ struct hylra_ctx {
     int* counters = nullptr;    // one arrival counter per (batch, KV head), zero between launches
     int* chunk_ctr = nullptr;   // chunk counters of the self-scheduling Full kernel (kCtrStride ints apart)
     int* sel_ws = nullptr;      // selection scratch: histogram, candidates, counts (see SelectParams)
+    int4* wg_map = nullptr;     // deal of the Full kernel's workgroups to sequences of different lengths
+    int2* pair_map = nullptr;   // (see RaggedPlanParams): `slots` and `pairs_cap` entries
+    bool in_step = false;       // inside hylra_decode_step*: the lengths are the same for every layer,
+    bool step_planned = false;  // so the deal is made once per step
     int64_t pairs_cap = 0;      // (batch, KV head) pairs the selection scratch is sized for
     int max_chunks = 0;         // chunks of 8192 rows per (batch, KV head) at the maximum context
     int64_t slots = 0;          // capacity in (batch, KV head, split) triples
@@ -64,6 +68,7 @@ struct hylra_ctx {
     int32_t opt_reuse_unfused = 0;
     int32_t opt_finalize_variant = 0;
     int32_t opt_finalize_groups = 0;
+    int32_t opt_ragged_even = 0;
 
     bool prof_on = false;
     int prof_n = 0;
@@ -455,6 +460,8 @@ hylra_status hylra_create(hylra_ctx** out, const hylra_shape* max_shape, int32_t
     // one counter per (pair, segment); there are never more segments than partial slots
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->chunk_ctr, ctx->slots * kCtrStride * sizeof(int));
     if (e == hipSuccess) e = hipMemset(ctx->chunk_ctr, 0, ctx->slots * kCtrStride * sizeof(int));
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->wg_map, ctx->slots * sizeof(int4));
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->pair_map, pairs * sizeof(int2));
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         fail(nullptr, HYLRA_ERR_HIP, "workspace allocation failed: %s", hipGetErrorString(e));
@@ -486,6 +493,8 @@ hylra_status hylra_destroy(hylra_ctx* ctx) {
     if (ctx->counters) (void)hipFree(ctx->counters);
     if (ctx->chunk_ctr) (void)hipFree(ctx->chunk_ctr);
     if (ctx->sel_ws) (void)hipFree(ctx->sel_ws);
+    if (ctx->wg_map) (void)hipFree(ctx->wg_map);
+    if (ctx->pair_map) (void)hipFree(ctx->pair_map);
     delete ctx;
     return HYLRA_OK;
 }
@@ -502,6 +511,7 @@ hylra_status hylra_set_option(hylra_ctx* ctx, const char* name, int32_t value) {
     else if (!std::strcmp(name, "reuse_waves")) ctx->opt_reuse_waves = value;
     else if (!std::strcmp(name, "reuse_unfused")) ctx->opt_reuse_unfused = value;
     else if (!std::strcmp(name, "finalize_variant")) ctx->opt_finalize_variant = value;
+    else if (!std::strcmp(name, "ragged_even")) ctx->opt_ragged_even = value;
     else if (!std::strcmp(name, "finalize_groups")) {
         if (value != 0 && value != 2 && value != 8) return fail(ctx, HYLRA_ERR_BAD_ARG, "finalize_groups must be 0, 2 or 8");
         ctx->opt_finalize_groups = value;
@@ -543,6 +553,7 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
 
     hipStream_t st = (hipStream_t)hip_stream;
     DeviceGuard guard(ctx->device);
+    const int2* pair_map = nullptr;
     FullParams fp{};
     fp.q = (const uint16_t*)q;
     fp.K = (const uint16_t*)K;
@@ -567,6 +578,25 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
         fp.n_segs = pl.n_segs, fp.wgs_per_seg = pl.wgs_per_seg;
         // the table is made for the shortest segment; longer ones (by one tile) extend their last chunk
         fp.n_chunks = make_chunk_table(fp.total_tiles / pl.n_segs, pl.wgs_per_seg, fp.chunk_tile);
+        // Sequences of different lengths: the workgroups are dealt out in proportion to the rows
+        // (the lengths live on the device, so a small kernel makes the deal; once per decode step).
+        if (map.seq_lens && pl.n_segs == 1 && pl.wgs_per_seg > 1 && shape->batch > 1 &&
+            shape->batch <= kMaxRaggedBatch && (int64_t)shape->batch * pl.wgs_per_seg <= kMaxRaggedWgs &&
+            (int64_t)shape->batch * shape->n_kv_heads <= ctx->pairs_cap &&
+            !ctx->opt_ragged_even) {
+            if (!(ctx->in_step && ctx->step_planned)) {
+                RaggedPlanParams gp{};
+                gp.seq_lens = map.seq_lens;
+                gp.B = shape->batch, gp.Hkv = shape->n_kv_heads, gp.S = pl.wgs_per_seg;
+                gp.N = shape->ctx_len, gp.tile = tile;
+                gp.wg_map = ctx->wg_map, gp.pair_map = ctx->pair_map;
+                HIP_TRY(ctx, close_bracket(ctx));                // (the deal belongs to no profiling class)
+                HIP_TRY(ctx, launch_ragged_plan(gp, st));
+                ctx->step_planned = true;
+            }
+            fp.wg_map = ctx->wg_map;
+            pair_map = ctx->pair_map;
+        }
     }
     HIP_TRY(ctx, launch_timed(ctx, 0, st, [&] {
                 return launch_full_split(fp, shape->batch, shape->head_dim, G, pl.variant, st);
@@ -607,6 +637,7 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
         sp.n_splits = pl.n_splits, sp.Hq = shape->n_q_heads, sp.Hkv = shape->n_kv_heads;
         sp.G = G, sp.D = shape->head_dim, sp.N = n_sel, sp.k = k;
         sp.seq_lens = map.seq_lens, sp.sel_block = block;
+        sp.pair_map = pair_map;
         sp.out = out, sp.idx = want_idx ? idx : nullptr;
         int* w = ctx->sel_ws;
         sp.ghist = w, w += ctx->pairs_cap * 4096;
@@ -626,6 +657,7 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
     zp.n_splits = pl.n_splits, zp.Hq = shape->n_q_heads, zp.Hkv = shape->n_kv_heads;
     zp.G = G, zp.D = shape->head_dim, zp.N = n_sel, zp.k = k;
     zp.seq_lens = map.seq_lens, zp.sel_block = block;
+    zp.pair_map = pair_map;
     zp.variant = ctx->opt_finalize_variant == 2 ? 1 : 0;
     zp.out = out, zp.idx = want_idx ? idx : nullptr;
     HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_full_finalize(zp, shape->batch, st); }));
@@ -711,15 +743,16 @@ hylra_status step_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
     // followed by another Full layer hands its index set to nobody (a Reuse layer inherits from
     // the most recent Full layer), so its TopK is skipped; the last layer's set is kept because
     // idx_buf is documented to hold the last Full layer's set on return.
-    for (int l = 0; l < n_layers; ++l) {
+    ctx->in_step = true, ctx->step_planned = false;
+    hylra_status rc = HYLRA_OK;
+    for (int l = 0; l < n_layers && rc == HYLRA_OK; ++l) {
         const bool want_idx = l + 1 == n_layers || policy[l + 1] == HYLRA_REUSE;
-        hylra_status rc =
-            policy[l] == HYLRA_FULL
-                ? full_impl(ctx, shape, pg, q_l[l], K_l[l], V_l[l], block, k, out_l[l], idx_buf, hip_stream, want_idx)
-                : reuse_impl(ctx, shape, pg, q_l[l], K_l[l], V_l[l], idx_buf, block, k, out_l[l], hip_stream);
-        if (rc != HYLRA_OK) return rc;
+        rc = policy[l] == HYLRA_FULL
+                 ? full_impl(ctx, shape, pg, q_l[l], K_l[l], V_l[l], block, k, out_l[l], idx_buf, hip_stream, want_idx)
+                 : reuse_impl(ctx, shape, pg, q_l[l], K_l[l], V_l[l], idx_buf, block, k, out_l[l], hip_stream);
     }
-    return HYLRA_OK;
+    ctx->in_step = false;
+    return rc;
 }
 
 }  // namespace

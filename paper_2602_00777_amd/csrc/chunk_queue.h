@@ -12,9 +12,10 @@
 // draws the first tile of a chunk issues the claim for the workgroup's next chunk and looks at
 // the result one tile later (memory returns loads and atomics in order, so by then it is
 // there): nothing in the streaming loop waits for anything but the tile to be consumed.  The
-// counter returns to zero by itself: every launch adds to it exactly n_chunks times per
-// segment (n_chunks - S claims that succeed and one that fails per workgroup), and the claim
-// that draws the last value stores zero.
+// counter returns to zero by itself: every launch adds to it exactly n times per segment, n
+// being the segment's chunks (n - S claims that succeed and one that fails per workgroup; with
+// more than n workgroups, the first n fail once and the others neither start on a chunk nor
+// claim), and the claim that draws the last value stores zero.
 #pragma once
 #include "device_util.h"
 #include "launch.h"
@@ -118,30 +119,69 @@ DEVI TileRef next_tile(ChunkQueue& cq, int* __restrict__ ctr, QueueCursor& cur, 
 }
 
 // The workgroup's segment for its sequence: first tile, number of tiles, and the number of
-// tiles the host's chunk table was made for (a full-length sequence has that many or one
-// more; a shorter one has fewer, and the table is scaled down to it).
+// tiles the host's chunk table was made for.  A full-length sequence has that many or one more
+// (the last chunk then runs to the segment's end).  A shorter one uses the end of the table:
+// guided self-scheduling cuts the next chunk from what remains, so the table's chunks from the
+// one that holds tile `off` = made_for - tiles on are the table of a segment of `tiles` tiles
+// (its first chunk clipped), with the same smallest chunk; the segment has n_eff chunks,
+// table entries c0 .. n_chunks - 1.
 struct SegInfo {
     int tile0, tiles, made_for;
+    int wgs;                        // workgroups that serve the segment
+    int off, c0, n_eff;             // set by seg_chunks()
 };
 
-// First tile (within the segment) of chunk c; chunk c is [chunk_bound(c), chunk_bound(c + 1)).
+// Every thread calls this (the result is the same for all and lives in scalar registers).
+DEVI void seg_chunks(const FullParams& p, SegInfo& sg) {
+    sg.off = max(sg.made_for - sg.tiles, 0);
+    int lo = 0, hi = p.n_chunks;                    // largest c with chunk_tile[c] <= off
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (p.chunk_tile[mid] <= sg.off) lo = mid;
+        else hi = mid - 1;
+    }
+    sg.c0 = lo;
+    sg.n_eff = p.n_chunks - lo;
+}
+
+// A pair that was dealt n workgroups of its own (sequences of different lengths): they form
+// max(1, n / S) segments of S .. 2 S - 1 workgroups each (fewer than S only when n < S), S being
+// the number of workgroups the chunk table was made for, so that a workgroup's first chunk
+// (1 / (2 S) of its segment) stays below its fair share.  For workgroup w of the pair: its
+// segment, its rank in it, the segment's workgroups and the rank of the segment's first one.
+struct PairSeg {
+    int seg, w, wgs, wg0;
+};
+DEVI PairSeg pair_segment(int n, int S, int w) {
+    const int n_seg = max(1, n / S), base = n / n_seg, extra = n - base * n_seg;   // `extra` segments have one more
+    PairSeg r;
+    if (w < extra * (base + 1)) {
+        r.seg = w / (base + 1), r.wgs = base + 1, r.wg0 = r.seg * (base + 1);
+    } else {
+        const int v = w - extra * (base + 1);
+        r.seg = extra + v / base, r.wgs = base, r.wg0 = extra * (base + 1) + (r.seg - extra) * base;
+    }
+    r.w = w - r.wg0;
+    return r;
+}
+
+// First tile (within the segment) of the segment's chunk c (0 .. n_eff - 1); chunk c is
+// [chunk_bound(c), chunk_bound(c + 1)).
 DEVI int chunk_bound(const FullParams& p, const SegInfo& sg, int c) {
-    if (c >= p.n_chunks) return sg.tiles;
-    const int t = p.chunk_tile[c];
-    return sg.tiles >= sg.made_for ? t : (int)((int64_t)t * sg.tiles / sg.made_for);
+    if (c >= sg.n_eff) return sg.tiles;
+    return max(p.chunk_tile[sg.c0 + c] - sg.off, 0);
 }
 
 // One lane only.  raw: what the segment's counter returned to a claim of this workgroup.
-// Returns the claimed chunk and its bounds, or -1 if the counter has run out.  A chunk can be
-// empty when the sequence is much shorter than the table was made for; then the lane claims
-// again (and waits for it) until a chunk has tiles or the counter runs out, so that every
-// workgroup still ends with exactly one failed claim.  The counter returns to zero here: the
+// Returns the claimed chunk and its bounds, or -1 if the counter has run out.  Should a chunk
+// be empty, the lane claims again (and waits for it) until a chunk has tiles or the counter
+// runs out, so that every workgroup still ends with exactly one failed claim.  The counter returns to zero here: the
 // claim that draws the last value of the launch stores zero.
 DEVI int settle_claim(const FullParams& p, const SegInfo& sg, int* __restrict__ ctr, int raw, int& lo, int& hi) {
     for (;;) {
-        if (raw == p.n_chunks - 1) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const int c = p.wgs_per_seg + raw;
-        if (c >= p.n_chunks) return -1;
+        if (raw == sg.n_eff - 1) __hip_atomic_store(ctr, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int c = sg.wgs + raw;
+        if (c >= sg.n_eff) return -1;
         lo = chunk_bound(p, sg, c);
         hi = chunk_bound(p, sg, c + 1);
         if (hi > lo) return c;

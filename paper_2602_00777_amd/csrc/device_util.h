@@ -101,6 +101,23 @@ DEVI int seq_rows(const MAP& m, int b, int N) {
 DEVI int seq_rows(const int32_t* seq_lens, int b, int N) {
     return seq_lens ? min(max(seq_lens[b], 0), N) : N;
 }
+// The partials of a (batch, KV head) pair: S of them per head, head h's at entries
+// base + h * S .. base + (h + 1) * S - 1 of the partial arrays; their score ranges at entries
+// first .. first + S - 1 of the range array.
+struct PartView {
+    int64_t first;
+    int S;
+};
+DEVI PartView part_view(const int2* pair_map, int64_t pair, int n_splits) {
+    PartView v;
+    v.first = pair * n_splits, v.S = n_splits;
+    if (pair_map) {
+        const int2 m = pair_map[pair];
+        v.first = m.x, v.S = m.y;
+    }
+    return v;
+}
+
 // Units of `block` rows (the last one may be short) that sequence b has, out of at most n_units.
 DEVI int seq_units(const int32_t* seq_lens, int b, int n_units, int block) {
     if (!seq_lens) return n_units;

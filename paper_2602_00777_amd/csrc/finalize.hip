@@ -101,10 +101,13 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
 
     const int g = blockIdx.x, b = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int S = p.n_splits, D = p.D, G = p.G;
+    const int D = p.D, G = p.G;
     // this sequence ranks its first N rows and selects k of them (all of them if it has fewer)
     const int N = seq_units(p.seq_lens, b, p.N, p.sel_block), k = min(p.k, N);
     const int64_t pair = (int64_t)b * p.Hkv + g;
+    const PartView pv = part_view(p.pair_map, pair, p.n_splits);
+    const int S = pv.S;
+    const int64_t hb = pv.first * G;              // first partial of the pair's first head
     int32_t* __restrict__ dst = p.idx + pair * (int64_t)p.k;
     if (p.idx)
         for (int i = k + tid; i < p.k; i += SEL_THREADS) dst[i] = -1;  // entries beyond a short sequence
@@ -120,7 +123,7 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
     const bool ml_in_lds = G * S <= SEL_ML_CAP;
     if (ml_in_lds) {
         for (int t = tid; t < G * S; t += SEL_THREADS) {
-            const float2 ml = reinterpret_cast<const float2*>(p.part_ml + head0 * S * 2)[t];
+            const float2 ml = reinterpret_cast<const float2*>(p.part_ml + hb * 2)[t];
             s_m[t] = ml.x;
             s_l[t] = ml.y;
         }
@@ -128,8 +131,8 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
     }
     for (int i = tid; i < G * D; i += SEL_THREADS) {
         const int h = i / D, col = i - h * D;
-        const float* ml = p.part_ml + (head0 + h) * S * 2;
-        const float* acc = p.part_acc + (head0 + h) * S * D + col;
+        const float* ml = p.part_ml + (hb + (int64_t)h * S) * 2;
+        const float* acc = p.part_acc + (hb + (int64_t)h * S) * D + col;
         float M = NEG_BIG;
         if (ml_in_lds) {
             for (int s = 0; s < S; ++s) M = fmaxf(M, s_m[h * S + s]);
@@ -153,8 +156,8 @@ __global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizePara
     // ---- range of the scores ----
     float lo = 3.0e38f, hi = -3.0e38f;
     for (int s = tid; s < S; s += SEL_THREADS) {
-        lo = fminf(lo, p.part_mm[(pair * S + s) * 2]);
-        hi = fmaxf(hi, p.part_mm[(pair * S + s) * 2 + 1]);
+        lo = fminf(lo, p.part_mm[(pv.first + s) * 2]);
+        hi = fmaxf(hi, p.part_mm[(pv.first + s) * 2 + 1]);
     }
 #pragma unroll
     for (int mask = 1; mask < 64; mask <<= 1) {

@@ -42,7 +42,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     __shared__ float s_mm[2 * NW];
     extern __shared__ float s_scores[];          // [rows_per_split]
 
-    const int split = (blockIdx.x + p.split_rot) % p.n_splits, g = blockIdx.y, b = blockIdx.z;
+    int split = (blockIdx.x + p.split_rot) % p.n_splits, g = blockIdx.y, b = blockIdx.z;
+    int my_wgs = p.wgs_per_seg;                              // workgroups of this pair (self-scheduling mode)
+    int64_t slot0 = ((int64_t)b * p.Hkv + g) * p.n_splits;   // the pair's first partial slot
+    int mapped_rows = -1;
+    if (MODE == 4 && p.wg_map) {
+        // sequences of different lengths: the pairs' shares of the workgroups were dealt out before the launch
+        const int4 m = p.wg_map[slot0 + split];
+        if ((m.y >> 16) == 0) return;
+        b = m.x / p.Hkv, g = m.x - b * p.Hkv;
+        split = m.y & 0xffff, my_wgs = m.y >> 16, slot0 = m.z, mapped_rows = m.w;
+    }
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int chunk = lane % GEO::LPR, slot = lane / GEO::LPR;
 
@@ -59,7 +69,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     constexpr bool DYN = MODE == 4;
     constexpr int STEP = NW * TILE;
     // rows of this sequence; a shorter sequence is cut into the same number of (shorter) splits
-    const int n_rows = seq_rows(p.map, b, p.N);
+    const int n_rows = mapped_rows >= 0 ? mapped_rows : seq_rows(p.map, b, p.N);
     const int rps = DYN || n_rows == p.N ? p.rows_per_split
                                          : (n_rows + p.n_splits * STEP - 1) / (p.n_splits * STEP) * STEP;
     const int row0 = DYN ? 0 : split * rps;
@@ -140,13 +150,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
 
     if (DYN && n_rows > 0) {
         __shared__ ChunkQueue cq;
-        const int seg = split / p.wgs_per_seg, w = split - seg * p.wgs_per_seg;
         const int tiles_b = (n_rows + TILE - 1) / TILE;            // tiles of this sequence
         SegInfo sg;
-        sg.tile0 = (int)((int64_t)seg * tiles_b / p.n_segs);
-        sg.tiles = (int)((int64_t)(seg + 1) * tiles_b / p.n_segs) - sg.tile0;
         sg.made_for = p.chunk_tile[p.n_chunks];
-        int* ctr = p.chunk_ctr + (((int64_t)b * p.Hkv + g) * p.n_segs + seg) * kCtrStride;
+        int w;
+        int* ctr;
+        if (mapped_rows >= 0) {
+            // the pair's own number of workgroups, in segments of their own (counters: the pair's partial slots)
+            const PairSeg ps = pair_segment(my_wgs, p.wgs_per_seg, split);
+            w = ps.w;
+            sg.wgs = ps.wgs;
+            sg.tile0 = (int)((int64_t)tiles_b * ps.wg0 / my_wgs);
+            sg.tiles = (int)((int64_t)tiles_b * (ps.wg0 + ps.wgs) / my_wgs) - sg.tile0;
+            ctr = p.chunk_ctr + (slot0 + ps.seg) * kCtrStride;
+        } else {
+            const int seg = split / my_wgs;
+            w = split - seg * my_wgs;
+            sg.wgs = my_wgs;
+            sg.tile0 = (int)((int64_t)seg * tiles_b / p.n_segs);
+            sg.tiles = (int)((int64_t)(seg + 1) * tiles_b / p.n_segs) - sg.tile0;
+            ctr = p.chunk_ctr + (((int64_t)b * p.Hkv + g) * p.n_segs + seg) * kCtrStride;
+        }
+        seg_chunks(p, sg);
         // a row of the segment that exists: where a wave with nothing left points its loads
         // (all of them at this one row: the rows after it may lie outside the staged table)
         const int idle_row = min(sg.tile0 * TILE, n_rows - 1);
@@ -154,7 +179,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         if (tid == 0) {
             int lo = 0, hi = 0;
             bool has = false;
-            if (w < p.n_chunks) {
+            if (w < sg.n_eff) {
                 lo = chunk_bound(p, sg, w);
                 hi = chunk_bound(p, sg, w + 1);
                 has = hi > lo;
@@ -264,7 +289,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
             smin = fminf(smin, s_mm[2 * w]);
             smax = fmaxf(smax, s_mm[2 * w + 1]);
         }
-        float* mm = p.part_mm + (((int64_t)b * p.Hkv + g) * p.n_splits + split) * 2;
+        float* mm = p.part_mm + (slot0 + split) * 2;
         mm[0] = smin;
         mm[1] = smax;
     }
@@ -281,11 +306,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         }
     }
 
-    const int64_t head0 = (int64_t)b * p.Hq + (int64_t)g * G;
-    block_merge_store<GEO, NW>(st, smem, p.part_ml + (head0 * p.n_splits + split) * 2,
-                               (int64_t)p.n_splits * 2,
-                               p.part_acc + (head0 * p.n_splits + split) * D,
-                               (int64_t)p.n_splits * D);
+    // the pair's partials: [head of the group][partial] from slot0 * G on
+    const int n_part = DYN ? my_wgs * p.n_segs : p.n_splits;
+    block_merge_store<GEO, NW>(st, smem, p.part_ml + (slot0 * G + split) * 2, (int64_t)n_part * 2,
+                               p.part_acc + (slot0 * G + split) * D, (int64_t)n_part * D);
     HYLRA_TS(2);
 }
 

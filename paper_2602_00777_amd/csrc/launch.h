@@ -48,6 +48,14 @@ struct FullParams {
     // segment's counter.
     int* chunk_ctr;                 // [B*Hkv][n_segs] counters, kCtrStride ints apart, zero between launches
     int n_segs, wgs_per_seg, total_tiles;
+    // Sequences of different lengths (n_segs == 1 only): the workgroups of the launch are
+    // dealt out to the (batch, KV head) pairs in proportion to their rows by a small kernel
+    // that runs first (ragged_plan.hip).  wg_map[x] for workgroup x of the grid (x counted
+    // with the split fastest, then the KV head, then the batch): its pair, its rank w among
+    // the pair's n workgroups, the pair's first partial slot and the rows of the pair's
+    // sequence; n == 0: nothing to do.
+    // nullptr: workgroup x serves pair x / n_splits as number x % n_splits of n_splits.
+    const int4* wg_map;             // {pair, w | n << 16, first, rows}
     int n_chunks;
     int chunk_tile[kMaxChunks + 1];
 };
@@ -62,6 +70,9 @@ struct FinalizeParams {
     const int32_t* seq_lens;        // [B] or nullptr: sequence b ranks its first n_b rows and selects
                                     // min(k, n_b) of them; the rest of its k index entries are -1
     int sel_block;                  // rows per ranked unit (N and k count units): n_b = ceil(len / sel_block)
+    const int2* pair_map;           // [B*Hkv] {first partial slot, partials} of the pair; nullptr:
+                                    // {pair * n_splits, n_splits}.  The pair's partials are laid out
+                                    // [head of the group][partial] from slot `first` on (see part_base).
     int variant;                    // 0: scores kept in registers when they fit; 1: always re-read
     float* out;                     // [B][Hq][D]
     int32_t* idx;                   // [B][Hkv][k]
@@ -78,6 +89,7 @@ struct SelectParams {
     int n_splits, Hq, Hkv, G, D, N, k;
     const int32_t* seq_lens;        // as in FinalizeParams
     int sel_block;
+    const int2* pair_map;
     float* out;                     // [B][Hq][D]
     int32_t* idx;                   // [B][Hkv][k]
     int* ghist;                     // [B*Hkv][4096] score histogram; zero between launches
@@ -119,6 +131,20 @@ struct BlockMaxParams {
     int N, block, n_blocks;
     const int32_t* seq_lens;        // [B] or nullptr: only the blocks that hold rows of sequence b are written
 };
+
+// Deal of the Full kernel's workgroups to sequences of different lengths (ragged_plan.hip).
+// Per KV head the batch shares S * B workgroups: sequence b gets max(1, ceil(T_b / L)) of them,
+// T_b being its wave tiles and L the smallest load per workgroup the S * B workgroups can
+// carry; the few left over stay idle.
+struct RaggedPlanParams {
+    const int32_t* seq_lens;        // [B]
+    int B, Hkv, S, N, tile;         // S: workgroups per pair of the launch; tile: rows per wave tile
+    int4* wg_map;                   // [B*Hkv*S], see FullParams
+    int2* pair_map;                 // [B*Hkv], see FinalizeParams
+};
+constexpr int kMaxRaggedBatch = 4096;
+constexpr int kMaxRaggedWgs = 32767;   // S * B
+hipError_t launch_ragged_plan(const RaggedPlanParams& p, hipStream_t st);
 
 // Pooled overlap counts between the index sets of the layers (policy.hip).
 constexpr int kMaxProfileLayers = 256;

@@ -50,9 +50,10 @@ struct Chunk {
 DEVI void score_range(const SelectParams& p, int64_t pair, float* s_red, float& lo, float& inv_w) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     float a = 3.0e38f, b = -3.0e38f;
-    for (int s = tid; s < p.n_splits; s += SEL_THREADS) {
-        a = fminf(a, p.part_mm[(pair * p.n_splits + s) * 2]);
-        b = fmaxf(b, p.part_mm[(pair * p.n_splits + s) * 2 + 1]);
+    const PartView pv = part_view(p.pair_map, pair, p.n_splits);
+    for (int s = tid; s < pv.S; s += SEL_THREADS) {
+        a = fminf(a, p.part_mm[(pv.first + s) * 2]);
+        b = fmaxf(b, p.part_mm[(pv.first + s) * 2 + 1]);
     }
 #pragma unroll
     for (int mask = 1; mask < 64; mask <<= 1) {
@@ -84,7 +85,9 @@ __global__ __launch_bounds__(SEL_THREADS) void select_hist_kernel(SelectParams p
     const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z, C = gridDim.x;
     const int tid = threadIdx.x;
     const int64_t pair = (int64_t)b * p.Hkv + g;
-    const int S = p.n_splits, D = p.D, G = p.G;
+    const PartView pv = part_view(p.pair_map, pair, p.n_splits);
+    const int S = pv.S, D = p.D, G = p.G;
+    const int64_t hb = pv.first * G;              // first partial of the pair's first head
 
     const int N = p.idx ? seq_units(p.seq_lens, b, p.N, p.sel_block) : 0; // rows this sequence ranks (none: merge only)
     Chunk<E> ch;
@@ -99,8 +102,8 @@ __global__ __launch_bounds__(SEL_THREADS) void select_hist_kernel(SelectParams p
     const int64_t head0 = (int64_t)b * p.Hq + (int64_t)g * G;
     for (int i = c * share + tid; i < min(G * D, (c + 1) * share); i += SEL_THREADS) {
         const int h = i / D, col = i - h * D;
-        const float* ml = p.part_ml + (head0 + h) * S * 2;
-        const float* acc = p.part_acc + (head0 + h) * S * D + col;
+        const float* ml = p.part_ml + (hb + (int64_t)h * S) * 2;
+        const float* acc = p.part_acc + (hb + (int64_t)h * S) * D + col;
         float M = NEG_BIG;
 #pragma unroll 8
         for (int s = 0; s < S; ++s) M = fmaxf(M, ml[2 * s]);

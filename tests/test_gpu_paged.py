@@ -260,6 +260,51 @@ def test_paged_block_level_variant(B, Hkv, G, d, N, block, kb, page):
             assert_out_close(o[b:b + 1], ref, "reuse v%d b=%d" % (v, b))
 
 
+SKEWED = [
+    # B, Hkv, G, d,   N,   k, page, lengths of the first sequences (the rest: 1 + 13 b rows)
+    (16, 4, 4, 128, 6000, 128, 16, (6000, 0, 1, 750, 40)),      # one long sequence gets most workgroups
+    (16, 4, 4, 128, 6000, 128, 0, (33, 6000, 5999, 0, 0)),      # contiguous cache
+    (32, 2, 2, 64, 4000, 64, 32, (4000, 7, 0, 2100)),           # head_dim 64: the vector self-scheduling kernel
+    (64, 1, 4, 128, 3000, 32, 16, (3000, 3000, 1)),
+]
+
+
+@pytest.mark.parametrize("B,Hkv,G,d,N,k,page,head", SKEWED)
+def test_skewed_lengths_deal_workgroups_by_rows(B, Hkv, G, d, N, k, page, head):
+    """Very unequal lengths: the self-scheduling Full kernels give every (batch, KV head) a share
+    of the workgroups in proportion to its rows (several segments for a long sequence, one
+    workgroup for an empty one); with the even deal switched on the result is the same."""
+    say("skewed B=%d Hkv=%d G=%d d=%d N=%d k=%d page=%d" % (B, Hkv, G, d, N, k, page))
+    q, K, V, Kp, Vp, cache, _ = make_case(1300 + B + N, B, Hkv, G, d, N, page or 16, False)
+    lens = np.array([1 + 13 * b for b in range(B)], np.int32)
+    lens[:len(head)] = head
+    dlens = torch.from_numpy(lens).to(DEV)
+    if page:
+        cache = binding.PagedCache(cache.block_table, page, N, dlens)
+    else:
+        cache, Kp, Vp = binding.PagedCache(None, 0, N, dlens), K, V
+    outs, idxs, shats = oracle_full(q, K, V, np.maximum(lens, 1), k)       # (the oracle wants a row; see below)
+    with binding.Context(B, Hkv * G, Hkv, d, N, k) as ctx:
+        res = {}
+        for even in (0, 1):
+            ctx.set_option("ragged_even", even)
+            for rep in range(2):                                           # twice: counters and maps are reused
+                out, idx = ctx.full_attn_topk_paged(q, Kp, Vp, cache, k)
+                torch.cuda.synchronize()
+            res[even] = (out.cpu().numpy(), idx.cpu().numpy())
+    for even, (out, idx) in res.items():
+        for b in range(B):
+            n = int(lens[b])
+            if n == 0:
+                assert np.all(out[b] == 0) and np.all(idx[b] == -1), "empty sequence b=%d (even=%d)" % (b, even)
+                continue
+            kk = min(k, n)
+            assert_out_close(out[b:b + 1], outs[b][None], "out b=%d even=%d" % (b, even))
+            assert np.all(idx[b, :, kk:] == -1)
+            assert_idx_valid(idx[b:b + 1, :, :kk], shats[b][None], kk, "idx b=%d even=%d" % (b, even), exact_ref=idxs[b][None])
+    assert np.array_equal(res[0][1], res[1][1])
+
+
 def test_paged_zero_length_sequence_and_errors():
     say("paged zero length, errors")
     B, Hkv, G, d, N, k, page = 3, 2, 4, 128, 1000, 100, 16
