@@ -330,6 +330,8 @@ hylra_status hylra_policy_search(hylra_ctx *ctx, int32_t n_layers, const double 
  *                       3 = three launches with several workgroups per (batch, KV head)
  *                       (default beyond 32768 rows)
  *   "finalize_groups"   rows per workgroup of the three-launch finalise, in units of 4096: 2 or 8
+ *   "full_unpaired"     1 = the self-scheduling Full kernels group their workgroups by number
+ *                       instead of mixing early and late arrivals on the compute units
  *   "ragged_even"       1 = with seq_lens, give every (batch, KV head) the same number of
  *                       workgroups of the self-scheduling Full kernel instead of a number in
  *                       proportion to its rows

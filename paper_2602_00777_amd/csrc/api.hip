@@ -48,6 +48,7 @@ struct hylra_ctx {
     int* sel_ws = nullptr;      // selection scratch: histogram, candidates, counts (see SelectParams)
     int4* wg_map = nullptr;     // deal of the Full kernel's workgroups to sequences of different lengths
     int2* pair_map = nullptr;   // (see RaggedPlanParams): `slots` and `pairs_cap` entries
+    int n_cus = 0;              // compute units of the device
     bool in_step = false;       // inside hylra_decode_step*: the lengths are the same for every layer,
     bool step_planned = false;  // so the deal is made once per step
     int64_t pairs_cap = 0;      // (batch, KV head) pairs the selection scratch is sized for
@@ -69,6 +70,7 @@ struct hylra_ctx {
     int32_t opt_finalize_variant = 0;
     int32_t opt_finalize_groups = 0;
     int32_t opt_ragged_even = 0;
+    int32_t opt_full_unpaired = 0;
 
     bool prof_on = false;
     int prof_n = 0;
@@ -265,39 +267,60 @@ int make_chunk_table(int total_tiles, int S, int (&chunk_tile)[kMaxChunks + 1]) 
     }
 }
 
+// Workgroups per (batch, KV head) of a self-scheduling Full kernel whose wave tile has `tile`
+// rows, and the segments they form.  Only the number of workgroups is planned (rows are handed
+// out at run time); "full_split_rows" still sets it, as ctx_len / rows.  More than
+// kDynWgsPerSeg workgroups per pair are put into segments of that many: the workgroups of a
+// segment then sit on different XCDs and the chunk table stays short.
+void plan_dyn_groups(const hylra_ctx* ctx, const hylra_shape* s, int64_t tile, int64_t& S, int64_t& segs) {
+    const int64_t pairs = (int64_t)s->batch * s->n_kv_heads;
+    const int64_t tiles = ceil_div(s->ctx_len, tile);
+    S = ctx->opt_full_split_rows > 0 ? ceil_div(s->ctx_len, ctx->opt_full_split_rows)
+                                     : ceil_div(kTargetBlocksFull, pairs);
+    if (S > ceil_div(tiles, 4)) S = ceil_div(tiles, 4);
+    if (S > kMaxSplits) S = kMaxSplits;
+    while (S > 1 && pairs * S > ctx->slots) --S;
+    segs = 1;
+    if (S > kDynWgsPerSeg) {
+        segs = S / kDynWgsPerSeg;
+        S = segs * kDynWgsPerSeg;
+    }
+}
+
+// Exactly two workgroups per compute unit and groups of an even number of workgroups: every
+// group of a self-scheduling kernel can then be made of early and late arrivals on the
+// compute units in equal parts (FullParams::gen_half).
+bool pairs_generations(const hylra_ctx* ctx, const hylra_shape* s, int64_t S, int64_t segs) {
+    const int64_t grid = (int64_t)s->batch * s->n_kv_heads * S;
+    return grid == 2 * (int64_t)ctx->n_cus && (S / segs) % 2 == 0 && !ctx->opt_full_unpaired;
+}
+
 hylra_status plan_full(const hylra_ctx* ctx, const hylra_shape* s, int G, FullPlan& pl) {
-    // automatic (measured on the benchmark shapes): for head_dim 128 the second matrix-core
-    // kernel, evenly split from 5 heads per group (there the vector kernel is bound by its own
-    // arithmetic: 121 us against 91 us at G = 7) and self-scheduling below that while a
-    // (batch, KV head) gets at most one segment of workgroups (2 % faster than the
-    // self-scheduling vector kernel at batch 8 / 32K, equal at batch 32 / 16K); with several
-    // segments per pair (small batches) the evenly split vector kernel is still 2 % faster.
+    // automatic (measured on the benchmark shapes).  head_dim 128: the second matrix-core
+    // kernel.  Self-scheduling while a (batch, KV head) gets at most one segment of workgroups
+    // (2 % faster than the self-scheduling vector kernel at batch 8 / 32K, equal at batch 32 /
+    // 16K) or whenever its groups can mix early and late workgroups (then also 1 .. 2 % ahead
+    // of the even split at batch 1 / 131K and at G = 7); else evenly split from 5 heads per
+    // group (there the vector kernel is bound by its own arithmetic: 121 us against 91 us at
+    // G = 7) and the evenly split vector kernel below that.
     // head_dim 64: the vector kernels up to 4 heads per group, the first matrix-core kernel above.
     const int64_t pairs = (int64_t)s->batch * s->n_kv_heads;
     const bool one_segment = ceil_div(kTargetBlocksFull, pairs) <= kDynWgsPerSeg;
+    bool mixes = false;
+    if (s->head_dim == 128) {
+        int64_t S, segs;
+        plan_dyn_groups(ctx, s, full_block_quantum(128, G, 74) / 4, S, segs);
+        mixes = pairs_generations(ctx, s, S, segs);
+    }
     pl.variant = ctx->opt_full_variant > 0 ? ctx->opt_full_variant
-                 : s->head_dim == 128 ? (G > 4 ? 72 : one_segment ? 74 : 23)
+                 : s->head_dim == 128 ? (one_segment && G <= 4 ? 74 : mixes ? 74 : G > 4 ? 72 : 23)
                  : G > 4 ? 52 : one_segment ? 43 : 23;
     const int quantum = full_block_quantum(s->head_dim, G, pl.variant);
     if (quantum <= 0) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "Full kernel variant %d is not built for d=%d G=%d", pl.variant, s->head_dim, G);
     if (is_self_scheduling(pl.variant)) {
-        // self-scheduling kernel: only the number of workgroups per pair is planned (rows are
-        // handed out at run time); "full_split_rows" still sets it, as ctx_len / rows.  More
-        // than kDynWgsPerSeg workgroups per pair are put into segments of that many: the
-        // workgroups of a segment then sit on different XCDs (consecutive workgroup numbers)
-        // and the chunk table stays short.
         const int64_t tile = quantum / 4;                      // rows of one wave tile
-        const int64_t tiles = ceil_div(s->ctx_len, tile);
-        int64_t S = ctx->opt_full_split_rows > 0 ? ceil_div(s->ctx_len, ctx->opt_full_split_rows)
-                                                 : ceil_div(kTargetBlocksFull, pairs);
-        if (S > ceil_div(tiles, 4)) S = ceil_div(tiles, 4);
-        if (S > kMaxSplits) S = kMaxSplits;
-        while (S > 1 && pairs * S > ctx->slots) --S;
-        int64_t segs = 1;
-        if (S > kDynWgsPerSeg) {
-            segs = S / kDynWgsPerSeg;
-            S = segs * kDynWgsPerSeg;
-        }
+        int64_t S, segs;
+        plan_dyn_groups(ctx, s, tile, S, segs);
         if (pairs * S > ctx->slots)
             return fail(ctx, HYLRA_ERR_WORKSPACE, "batch*n_kv_heads = %lld exceeds the workspace", (long long)pairs);
         // rows of score staging per workgroup: twice its share of the rows, in whole wave tiles
@@ -435,6 +458,7 @@ hylra_status hylra_create(hylra_ctx** out, const hylra_shape* max_shape, int32_t
         return rc;
     }
     ctx->device = device;
+    (void)hipDeviceGetAttribute(&ctx->n_cus, hipDeviceAttributeMultiprocessorCount, device);
     ctx->max_shape = *max_shape;
     ctx->max_k = max_k;
     const int64_t pairs = (int64_t)max_shape->batch * max_shape->n_kv_heads;
@@ -515,6 +539,7 @@ hylra_status hylra_set_option(hylra_ctx* ctx, const char* name, int32_t value) {
     else if (!std::strcmp(name, "reuse_unfused")) ctx->opt_reuse_unfused = value;
     else if (!std::strcmp(name, "finalize_variant")) ctx->opt_finalize_variant = value;
     else if (!std::strcmp(name, "ragged_even")) ctx->opt_ragged_even = value;
+    else if (!std::strcmp(name, "full_unpaired")) ctx->opt_full_unpaired = value;
     else if (!std::strcmp(name, "finalize_groups")) {
         if (value != 0 && value != 2 && value != 8) return fail(ctx, HYLRA_ERR_BAD_ARG, "finalize_groups must be 0, 2 or 8");
         ctx->opt_finalize_groups = value;
@@ -581,6 +606,9 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
         fp.n_segs = pl.n_segs, fp.wgs_per_seg = pl.wgs_per_seg;
         // the table is made for the shortest segment; longer ones (by one tile) extend their last chunk
         fp.n_chunks = make_chunk_table(fp.total_tiles / pl.n_segs, pl.wgs_per_seg, fp.chunk_tile);
+        // exactly two workgroups per compute unit: mix the early and the late ones in every group
+        if (pairs_generations(ctx, shape, pl.n_splits, pl.n_segs))
+            fp.gen_half = (int)((int64_t)shape->batch * shape->n_kv_heads * pl.n_splits / 2);
         // Sequences of different lengths: the workgroups are dealt out in proportion to the rows
         // (the lengths live on the device, so a small kernel makes the deal; once per decode step).
         if (map.seq_lens && pl.n_segs == 1 && pl.wgs_per_seg > 1 && shape->batch > 1 &&

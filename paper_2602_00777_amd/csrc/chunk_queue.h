@@ -144,6 +144,19 @@ DEVI void seg_chunks(const FullParams& p, SegInfo& sg) {
     sg.n_eff = p.n_chunks - lo;
 }
 
+// Workgroup x of a grid of 2 * half workgroups -> the group of S workgroups (S even) it belongs
+// to and its rank there: group u is made of the S / 2 workgroups u * S / 2 .. of the first half
+// and of the S / 2 workgroups of the second half that sit one group further on (so that its
+// workgroups of the second half land on other XCDs than those of the first half).
+DEVI void paired_unit(int x, int half, int S, int& unit, int& w) {
+    const int h = S >> 1;
+    const int late = x >= half;
+    int r = x - (late ? half : 0);
+    if (late) r = r >= h ? r - h : r - h + half;
+    unit = r / h;
+    w = (late ? h : 0) + (r - unit * h);
+}
+
 // A pair that was dealt n workgroups of its own (sequences of different lengths): they form
 // max(1, n / S) segments of S .. 2 S - 1 workgroups each (fewer than S only when n < S), S being
 // the number of workgroups the chunk table was made for, so that a workgroup's first chunk

@@ -46,6 +46,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     int my_wgs = p.wgs_per_seg;                              // workgroups of this pair (self-scheduling mode)
     int64_t slot0 = ((int64_t)b * p.Hkv + g) * p.n_splits;   // the pair's first partial slot
     int mapped_rows = -1;
+    if (MODE == 4 && !p.wg_map && p.gen_half) {
+        // early and late arrivals on the compute units are mixed in every group of workgroups
+        int unit, w;
+        paired_unit((int)(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z)), p.gen_half, p.wgs_per_seg,
+                    unit, w);
+        const int pair = unit / p.n_segs;
+        b = pair / p.Hkv, g = pair - b * p.Hkv;
+        split = (unit - pair * p.n_segs) * p.wgs_per_seg + w;
+        slot0 = (int64_t)pair * p.n_splits;
+    }
     if (MODE == 4 && p.wg_map) {
         // sequences of different lengths: the pairs' shares of the workgroups were dealt out before the launch
         const int4 m = p.wg_map[slot0 + split];

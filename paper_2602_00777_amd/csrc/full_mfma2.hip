@@ -33,6 +33,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     int my_wgs = p.wgs_per_seg;                              // workgroups of this pair (DYN)
     int64_t slot0 = ((int64_t)b * p.Hkv + g) * p.n_splits;   // the pair's first partial slot
     int mapped_rows = -1;
+    if (DYN && !p.wg_map && p.gen_half) {
+        // early and late arrivals on the compute units are mixed in every group of workgroups
+        int unit, w;
+        paired_unit((int)(blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z)), p.gen_half, p.wgs_per_seg,
+                    unit, w);
+        const int pair = unit / p.n_segs;
+        b = pair / p.Hkv, g = pair - b * p.Hkv;
+        split = (unit - pair * p.n_segs) * p.wgs_per_seg + w;
+        slot0 = (int64_t)pair * p.n_splits;
+    }
     if (DYN && p.wg_map) {
         // sequences of different lengths: the pairs' shares of the workgroups were dealt out before the launch
         const int4 m = p.wg_map[slot0 + split];
@@ -48,6 +58,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     const uint16_t* __restrict__ Kb = p.K + base;
     const uint16_t* __restrict__ Vb = p.V + base;
     const int64_t head0 = (int64_t)b * p.Hq + (int64_t)g * G;
+    HYLRA_TS(0);
     uint4 qb[4];
     mfma_load_q<D, G>(qb, p.q + head0 * D, n, gq);
     State2 st;
@@ -223,7 +234,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
             publish_claim(cq, p, ctr, pc, lane, sg);
         }
         publish_claim(cq, p, ctr, pc, lane, sg);
+        HYLRA_TS(1);
         __syncthreads();
+        HYLRA_TS(2);
         // write the staged scores out, slot by slot (tile starts and the score stride are
         // multiples of 4 floats, so the 16-byte stores are aligned)
         const int n_slots = cq.n_ready;
@@ -255,6 +268,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         }
     }
 
+    HYLRA_TS(3);
     // range of this split's group-mean scores (the finalise kernels bin on it)
     smin = strided_minmax<1, false>(smin);
     smax = strided_minmax<1, true>(smax);
@@ -290,6 +304,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     merge_store2<G, NW, false>(st, s_m, s_l, s_acc, p.part_ml + (slot0 * G + split) * 2,
                                (int64_t)n_part * 2, p.part_acc + (slot0 * G + split) * D,
                                (int64_t)n_part * D, n, gq);
+    HYLRA_TS(4);
 }
 
 // rows a workgroup consumes per sweep of its 4 waves; variant 72 = even splits, 74 = rows handed

@@ -56,6 +56,13 @@ struct FullParams {
     // sequence; n == 0: nothing to do.
     // nullptr: workgroup x serves pair x / n_splits as number x % n_splits of n_splits.
     const int4* wg_map;             // {pair, w | n << 16, first, rows}
+    // Two workgroups share a compute unit, and the one that arrived first streams about 10 %
+    // faster (the unit serves its older waves first).  Workgroups are placed in the order of
+    // their numbers, so with gen_half = half the grid > 0 the first half of the grid are the
+    // early arrivals.  Every group of wgs_per_seg workgroups that shares a chunk counter is then
+    // made of wgs_per_seg / 2 workgroups from each half (see paired_unit), so that the groups
+    // finish together.  0: workgroup x belongs to group x / wgs_per_seg.
+    int gen_half;
     int n_chunks;
     int chunk_tile[kMaxChunks + 1];
 };

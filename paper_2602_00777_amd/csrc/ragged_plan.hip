@@ -101,8 +101,12 @@ __global__ __launch_bounds__(256) void ragged_plan_kernel(RaggedPlanParams p) {
             n = s_n[a] - begin;
             rows = seq_rows(p.seq_lens, a, p.N);
         }
-        for (int g = 0; g < p.Hkv; ++g)
-            p.wg_map[(int64_t)g * per_head + j] = make_int4(seq * p.Hkv + g, w | (n << 16), g * per_head + begin, rows);
+        for (int g = 0; g < p.Hkv; ++g) {
+            // (slot = workgroup of the grid.  Spreading a pair's slots over the two halves of the grid, as
+            // the kernels do for equal lengths, measured 2 % slower at batch 8 and no faster at batch 32.)
+            const int x = g * per_head + j;
+            p.wg_map[x] = make_int4(seq * p.Hkv + g, w | (n << 16), g * per_head + begin, rows);
+        }
     }
 }
 
