@@ -266,6 +266,7 @@ SKEWED = [
     (16, 4, 4, 128, 6000, 128, 0, (33, 6000, 5999, 0, 0)),      # contiguous cache
     (32, 2, 2, 64, 4000, 64, 32, (4000, 7, 0, 2100)),           # head_dim 64: the vector self-scheduling kernel
     (64, 1, 4, 128, 3000, 32, 16, (3000, 3000, 1)),
+    (300, 1, 4, 128, 700, 32, 16, (700, 0, 1, 699)),            # more sequences than threads in the deal's workgroup
 ]
 
 
@@ -276,7 +277,7 @@ def test_skewed_lengths_deal_workgroups_by_rows(B, Hkv, G, d, N, k, page, head):
     workgroup for an empty one); with the even deal switched on the result is the same."""
     say("skewed B=%d Hkv=%d G=%d d=%d N=%d k=%d page=%d" % (B, Hkv, G, d, N, k, page))
     q, K, V, Kp, Vp, cache, _ = make_case(1300 + B + N, B, Hkv, G, d, N, page or 16, False)
-    lens = np.array([1 + 13 * b for b in range(B)], np.int32)
+    lens = np.array([(1 + 13 * b) % (N + 1) for b in range(B)], np.int32)
     lens[:len(head)] = head
     dlens = torch.from_numpy(lens).to(DEV)
     if page:
