@@ -597,7 +597,8 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
     fp.scale_log2 = scale * LOG2E_HOST;
     fp.scale_mean = scale / (float)G;
     fp.part_ml = ctx->part_ml, fp.part_acc = ctx->part_acc, fp.part_mm = ctx->part_mm;
-    fp.scores = ctx->scores;
+    // (the second matrix-core kernel leaves the scores out when the layer's index set is not wanted)
+    fp.scores = !want_idx && pl.variant >= 70 ? nullptr : ctx->scores;
     fp.score_stride = round_up(shape->ctx_len, 4);
     if (is_self_scheduling(pl.variant)) {
         fp.chunk_ctr = ctx->chunk_ctr;

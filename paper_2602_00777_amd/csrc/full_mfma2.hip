@@ -70,7 +70,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
                                          : (n_rows + p.n_splits * STEP - 1) / (p.n_splits * STEP) * STEP;
     const int row0 = DYN ? 0 : split * rps;
     const int row1 = DYN ? n_rows : min(n_rows, row0 + rps);
-    float* __restrict__ srow = p.scores + ((int64_t)b * p.Hkv + g) * p.score_stride;
+    // p.scores == nullptr: nobody will rank this layer's rows (its index set is not wanted), so
+    // the group-mean scores are neither formed nor written, nor is their range
+    const bool want_scores = p.scores != nullptr;
+    float* __restrict__ srow = want_scores ? p.scores + ((int64_t)b * p.Hkv + g) * p.score_stride : nullptr;
     float smin = 3.0e38f, smax = -3.0e38f;
 
     // paged cache: the split's part of the sequence's page table, staged in LDS (read from
@@ -141,6 +144,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         const uint32_t mask_b = left >= 32 ? 0xffffu : left > 16 ? (1u << (left - 16)) - 1u : 0u;
         float4_t Sa, Sb;
         group32<G>(st, buf.k[0], buf.k[1], buf.v, qb, mask_a, mask_b, p.scale_log2, n, gq, Sa, Sb);
+        if (!want_scores) return;
         // group-mean score of rows 4 gq + j of each block: sum over the 16 head lanes (padding
         // heads hold 0); staged in LDS at the row's place in the split
 #pragma unroll
@@ -239,7 +243,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         HYLRA_TS(2);
         // write the staged scores out, slot by slot (tile starts and the score stride are
         // multiples of 4 floats, so the 16-byte stores are aligned)
-        const int n_slots = cq.n_ready;
+        const int n_slots = want_scores ? cq.n_ready : 0;
         for (int i = 0; i < n_slots; ++i) {
             const int f0 = cq.first[i], f1 = min(cq.first[i + 1], stage_tiles);
             const int r0 = cq.tile0[i] * TILE;
@@ -277,7 +281,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         s_mm[2 * wave + 1] = smax;
     }
     __syncthreads();                             // also: every score of the split is in LDS
-    if (tid == 0) {
+    if (tid == 0 && want_scores) {
 #pragma unroll
         for (int w = 1; w < NW; ++w) {
             smin = fminf(smin, s_mm[2 * w]);
@@ -290,7 +294,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     if (!DYN) {
         // row0 and the score stride are multiples of 4 floats: 16-byte stores are aligned
         float* __restrict__ dst = srow + row0;
-        const int cnt = max(row1 - row0, 0);
+        const int cnt = want_scores ? max(row1 - row0, 0) : 0;
         for (int i = 4 * tid; i < cnt; i += 4 * NW * 64) {
             if (i + 4 <= cnt) {
                 *reinterpret_cast<float4*>(dst + i) = *reinterpret_cast<const float4*>(s_scores + i);

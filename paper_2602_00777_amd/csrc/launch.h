@@ -38,7 +38,8 @@ struct FullParams {
     float* part_ml;                 // [B*Hq][S][2]   (max in log2 units, sum)
     float* part_acc;                // [B*Hq][S][D]
     float* part_mm;                 // [B*Hkv][S][2]  (min, max of the group-mean scores)
-    float* scores;                  // [B*Hkv][score_stride] group-mean scaled scores
+    float* scores;                  // [B*Hkv][score_stride] group-mean scaled scores (second matrix-core
+                                    // kernel: nullptr = not wanted, then part_mm is not written either)
     int64_t score_stride;           // multiple of 4, >= N
     // self-scheduling mode only.  The wave tiles of a (batch, KV head) (a tile = the rows one
     // wave loads at a time) are cut into n_segs segments of equal length (to within one tile);
