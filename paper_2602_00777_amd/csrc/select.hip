@@ -97,24 +97,36 @@ __global__ __launch_bounds__(SEL_THREADS) void select_hist_kernel(SelectParams p
         p.cand_n[pair] = 0;
     }
 
-    // attention output: this workgroup's share of the G*D outputs of the KV head
+    // attention output: this workgroup's share of the G*D outputs of the KV head.  16 lanes per
+    // output element, each merging every 16th partial (with many partials per head, one thread
+    // per element would walk them one after the other while most of the workgroup idles).
     const int share = (G * D + C - 1) / C;
     const int64_t head0 = (int64_t)b * p.Hq + (int64_t)g * G;
-    for (int i = c * share + tid; i < min(G * D, (c + 1) * share); i += SEL_THREADS) {
-        const int h = i / D, col = i - h * D;
-        const float* ml = p.part_ml + (hb + (int64_t)h * S) * 2;
-        const float* acc = p.part_acc + (hb + (int64_t)h * S) * D + col;
-        float M = NEG_BIG;
-#pragma unroll 8
-        for (int s = 0; s < S; ++s) M = fmaxf(M, ml[2 * s]);
-        float num = 0.f, den = 0.f;
-#pragma unroll 8
-        for (int s = 0; s < S; ++s) {
-            const float w = fast_exp2(ml[2 * s] - M);
-            den = fmaf(w, ml[2 * s + 1], den);
-            num = fmaf(w, acc[(int64_t)s * D], num);
+    {
+        constexpr int L = 16;
+        const int sub = tid & (L - 1), grp = tid / L;
+        const int end = min(G * D, (c + 1) * share);
+        for (int i = c * share + grp; i < end; i += SEL_THREADS / L) {
+            const int h = i / D, col = i - h * D;
+            const float* ml = p.part_ml + (hb + (int64_t)h * S) * 2;
+            const float* acc = p.part_acc + (hb + (int64_t)h * S) * D + col;
+            float M = NEG_BIG;
+            for (int s = sub; s < S; s += L) M = fmaxf(M, ml[2 * s]);
+#pragma unroll
+            for (int m = 1; m < L; m <<= 1) M = fmaxf(M, __shfl_xor(M, m, 64));
+            float num = 0.f, den = 0.f;
+            for (int s = sub; s < S; s += L) {
+                const float w = fast_exp2(ml[2 * s] - M);
+                den = fmaf(w, ml[2 * s + 1], den);
+                num = fmaf(w, acc[(int64_t)s * D], num);
+            }
+#pragma unroll
+            for (int m = 1; m < L; m <<= 1) {
+                num += __shfl_xor(num, m, 64);
+                den += __shfl_xor(den, m, 64);
+            }
+            if (sub == 0) p.out[(head0 + h) * D + col] = den > 0.f ? num / den : 0.f;
         }
-        p.out[(head0 + h) * D + col] = den > 0.f ? num / den : 0.f;
     }
 
     if (!p.idx) return;         // merge only: nobody will read this layer's index set
