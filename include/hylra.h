@@ -169,7 +169,9 @@ hylra_status hylra_decode_step_blocks(hylra_ctx *ctx, const hylra_shape *shape, 
  * dimension contiguous; strides multiples of 8 elements, stride_row >= head_dim).
  * block_table[b][t] (DEVICE, int32, max_pages columns) names the page holding rows
  * t * page_size .. (t + 1) * page_size - 1 of sequence b; only the entries that
- * cover rows 0 .. n_b - 1 are read.  seq_lens[b] (DEVICE, int32) is n_b, clamped
+ * cover rows 0 .. n_b - 1 are read, and those must name pages inside the pools
+ * (the library cannot check device-resident page numbers before it launches).
+ * seq_lens[b] (DEVICE, int32) is n_b, clamped
  * to 0 .. shape->ctx_len; NULL means n_b = shape->ctx_len for every sequence.
  * shape->ctx_len is the largest length a sequence of the call may have (it sizes
  * the launch); shape's kv strides are ignored.  One table serves K and V, and in
