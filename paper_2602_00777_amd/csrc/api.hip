@@ -393,6 +393,11 @@ hylra_status plan_reuse(const hylra_ctx* ctx, const hylra_shape* s, int G, int k
         return fail(ctx, HYLRA_ERR_UNSUPPORTED, "Reuse kernel variant %d / unroll %d is not built for d=%d G=%d", pl.variant, pl.R, s->head_dim, G);
     int64_t rps = pl.rows_per_split;
     if (ctx->opt_reuse_split_rows > 0) rps = round_up(ctx->opt_reuse_split_rows, pl.rows_per_split);
+    // workgroups of 8 waves: one per compute unit is enough to keep the whole gather in flight, so
+    // with many (batch, KV head) pairs a workgroup takes more than one sweep and fewer partials
+    // cross workgroups (batch 32, k = 1024: one workgroup per pair and no merge, 27.2 vs 29.1 us)
+    else if (pl.NW == 8 && ctx->n_cus > 0)
+        rps = round_up(ceil_div(pairs * k, ctx->n_cus), pl.rows_per_split);
     int64_t S = ceil_div(k, rps);
     while (S > kMaxSplits || pairs * S > ctx->slots) {
         rps = round_up(rps * 2, pl.rows_per_split);
