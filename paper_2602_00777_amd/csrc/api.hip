@@ -306,18 +306,22 @@ hylra_status plan_full(const hylra_ctx* ctx, const hylra_shape* s, int G, FullPl
     // 16K) or whenever its groups can mix early and late workgroups (then also 1 .. 2 % ahead
     // of the even split at batch 1 / 131K and at G = 7); else evenly split from 5 heads per
     // group (there the vector kernel is bound by its own arithmetic: 121 us against 91 us at
-    // G = 7) and the evenly split vector kernel below that.
+    // G = 7) and the evenly split vector kernel below that.  Small problems (under 2048 rows per
+    // workgroup): evenly split.
     // head_dim 64: the vector kernels up to 4 heads per group, the first matrix-core kernel above.
     const int64_t pairs = (int64_t)s->batch * s->n_kv_heads;
     const bool one_segment = kTargetBlocksFull / pairs <= kDynWgsPerSeg;
-    bool mixes = false;
+    bool mixes = false, small = false;
     if (s->head_dim == 128) {
         int64_t S, segs;
         plan_dyn_groups(ctx, s, full_block_quantum(128, G, 74) / 4, S, segs);
         mixes = pairs_generations(ctx, s, S, segs);
+        // below about 2048 rows per workgroup the run-time hand-out costs more at the start than
+        // it balances (batch 1 / 32K: 33 us against 27.5 us evenly split; batch 8 / 8K: 52 vs 48.5)
+        small = s->ctx_len / S < 2048;
     }
     pl.variant = ctx->opt_full_variant > 0 ? ctx->opt_full_variant
-                 : s->head_dim == 128 ? (one_segment && G <= 4 ? 74 : mixes ? 74 : G > 4 ? 72 : 23)
+                 : s->head_dim == 128 ? (small ? 72 : one_segment && G <= 4 ? 74 : mixes ? 74 : G > 4 ? 72 : 23)
                  : G > 4 ? 52 : one_segment ? 43 : 23;
     const int quantum = full_block_quantum(s->head_dim, G, pl.variant);
     if (quantum <= 0) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "Full kernel variant %d is not built for d=%d G=%d", pl.variant, s->head_dim, G);
