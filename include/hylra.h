@@ -313,9 +313,9 @@ hylra_status hylra_policy_search(hylra_ctx *ctx, int32_t n_layers, const double 
  *                       matrix-core kernel (head_dim 128): 72 (even splits), 74 (rows handed
  *                       out at run time).  Defaults: head_dim 128: 74 while batch * n_kv_heads
  *                       >= 64 (up to 4 heads per KV head) or whenever the launch has exactly two
- *                       workgroups per compute unit, else 72 from 5 heads per KV head and 23
- *                       below that; head_dim 64: 52 from 5 heads per KV head, else 43 while
- *                       batch * n_kv_heads >= 64 and 23 below that.  The kernels that
+ *                       workgroups per compute unit, 72 otherwise and for small problems (under
+ *                       2048 rows per workgroup); head_dim 64: 52 from 5 heads per KV head, else
+ *                       43 while batch * n_kv_heads >= 64 and 23 below that.  The kernels that
  *                       hand out rows at run time give outputs that can differ in the last
  *                       bits from run to run (index sets never do); the others are
  *                       bit-reproducible.

@@ -271,8 +271,8 @@ int make_chunk_table(int total_tiles, int S, int (&chunk_tile)[kMaxChunks + 1]) 
 // Workgroups per (batch, KV head) of a self-scheduling Full kernel whose wave tile has `tile`
 // rows, and the segments they form.  Only the number of workgroups is planned (rows are handed
 // out at run time); "full_split_rows" still sets it, as ctx_len / rows.  More than
-// kDynWgsPerSeg workgroups per pair are put into segments of that many: the workgroups of a
-// segment then sit on different XCDs and the chunk table stays short.
+// kDynWgsPerSeg workgroups per pair are put into equal segments of at most that many: the
+// workgroups of a segment then sit on different XCDs and the chunk table stays short.
 void plan_dyn_groups(const hylra_ctx* ctx, const hylra_shape* s, int64_t tile, int64_t& S, int64_t& segs) {
     const int64_t pairs = (int64_t)s->batch * s->n_kv_heads;
     const int64_t tiles = ceil_div(s->ctx_len, tile);
@@ -284,11 +284,8 @@ void plan_dyn_groups(const hylra_ctx* ctx, const hylra_shape* s, int64_t tile, i
     if (S > ceil_div(tiles, 4)) S = ceil_div(tiles, 4);
     if (S > kMaxSplits) S = kMaxSplits;
     while (S > 1 && pairs * S > ctx->slots) --S;
-    segs = 1;
-    if (S > kDynWgsPerSeg) {
-        segs = S / kDynWgsPerSeg;
-        S = segs * kDynWgsPerSeg;
-    }
+    segs = ceil_div(S, kDynWgsPerSeg);
+    S = segs * (S / segs);
 }
 
 // Exactly two workgroups per compute unit and groups of an even number of workgroups: every
@@ -303,11 +300,10 @@ hylra_status plan_full(const hylra_ctx* ctx, const hylra_shape* s, int G, FullPl
     // automatic (measured on the benchmark shapes).  head_dim 128: the second matrix-core
     // kernel.  Self-scheduling while a (batch, KV head) gets at most one segment of workgroups
     // (2 % faster than the self-scheduling vector kernel at batch 8 / 32K, equal at batch 32 /
-    // 16K) or whenever its groups can mix early and late workgroups (then also 1 .. 2 % ahead
-    // of the even split at batch 1 / 131K and at G = 7); else evenly split from 5 heads per
-    // group (there the vector kernel is bound by its own arithmetic: 121 us against 91 us at
-    // G = 7) and the evenly split vector kernel below that.  Small problems (under 2048 rows per
-    // workgroup): evenly split.
+    // 16K; up to 4 heads per group) or whenever its groups can mix early and late workgroups
+    // (then also 1 .. 2 % ahead of the even split at batch 1 / 131K and at G = 7); evenly split
+    // otherwise (batch 3 / 50K: 98 us against 101 us for the vector kernel and for the
+    // self-scheduling form without mixing) and for small problems (under 2048 rows per workgroup).
     // head_dim 64: the vector kernels up to 4 heads per group, the first matrix-core kernel above.
     const int64_t pairs = (int64_t)s->batch * s->n_kv_heads;
     const bool one_segment = kTargetBlocksFull / pairs <= kDynWgsPerSeg;
@@ -321,7 +317,7 @@ hylra_status plan_full(const hylra_ctx* ctx, const hylra_shape* s, int G, FullPl
         small = s->ctx_len / S < 2048;
     }
     pl.variant = ctx->opt_full_variant > 0 ? ctx->opt_full_variant
-                 : s->head_dim == 128 ? (small ? 72 : one_segment && G <= 4 ? 74 : mixes ? 74 : G > 4 ? 72 : 23)
+                 : s->head_dim == 128 ? (small ? 72 : one_segment && G <= 4 ? 74 : mixes ? 74 : 72)
                  : G > 4 ? 52 : one_segment ? 43 : 23;
     const int quantum = full_block_quantum(s->head_dim, G, pl.variant);
     if (quantum <= 0) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "Full kernel variant %d is not built for d=%d G=%d", pl.variant, s->head_dim, G);
