@@ -115,18 +115,17 @@ DEVI void group32(State2& st, const uint4 (&ka)[4], const uint4 (&kb)[4], const 
 #pragma unroll
             for (int j = 0; j < 4; ++j) st.acc[e][j] *= a4[j];
     }
-    float hi[8], lo[8];
+    float w[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        const float w = ok[j] ? fast_exp2(t[j] - st.m) : 0.f;
-        st.l += w;
-        hi[j] = __uint_as_float(__float_as_uint(w) & 0xffff0000u);
-        lo[j] = w - hi[j];
+        w[j] = ok[j] ? fast_exp2(t[j] - st.m) : 0.f;
+        st.l += w[j];
     }
-    const uint4 p_hi = make_uint4(pack_hi16(hi[0], hi[1]), pack_hi16(hi[2], hi[3]),
-                                  pack_hi16(hi[4], hi[5]), pack_hi16(hi[6], hi[7]));
-    const uint4 p_lo = make_uint4(pack_hi16(lo[0], lo[1]), pack_hi16(lo[2], lo[3]),
-                                  pack_hi16(lo[4], lo[5]), pack_hi16(lo[6], lo[7]));
+    uint4 p_hi, p_lo;
+    split_weights(w[0], w[1], p_hi.x, p_lo.x);
+    split_weights(w[2], w[3], p_hi.y, p_lo.y);
+    split_weights(w[4], w[5], p_hi.z, p_lo.z);
+    split_weights(w[6], w[7], p_hi.w, p_lo.w);
     uint4 vt[8];
     transpose8x8(v, vt);
 #pragma unroll
