@@ -134,7 +134,7 @@ struct SegInfo {
 // Every thread calls this (the result is the same for all and lives in scalar registers).
 DEVI void seg_chunks(const FullParams& p, SegInfo& sg) {
     sg.off = max(sg.made_for - sg.tiles, 0);
-    int lo = 0, hi = p.n_chunks;                    // largest c with chunk_tile[c] <= off
+    int lo = 0, hi = sg.off ? p.n_chunks : 0;       // largest c with chunk_tile[c] <= off (0 for a full-length sequence)
     while (lo < hi) {
         const int mid = (lo + hi + 1) >> 1;
         if (p.chunk_tile[mid] <= sg.off) lo = mid;
