@@ -617,6 +617,7 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
         fp.n_segs = pl.n_segs, fp.wgs_per_seg = pl.wgs_per_seg;
         // the table is made for the shortest segment; longer ones (by one tile) extend their last chunk
         fp.n_chunks = make_chunk_table(fp.total_tiles / pl.n_segs, pl.wgs_per_seg, fp.chunk_tile);
+        fp.made_for = fp.chunk_tile[fp.n_chunks];
         // exactly two workgroups per compute unit: mix the early and the late ones in every group
         if (pairs_generations(ctx, shape, pl.n_splits, pl.n_segs))
             fp.gen_half = (int)((int64_t)shape->batch * shape->n_kv_heads * pl.n_splits / 2);

@@ -162,7 +162,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         __shared__ ChunkQueue cq;
         const int tiles_b = (n_rows + TILE - 1) / TILE;            // tiles of this sequence
         SegInfo sg;
-        sg.made_for = p.chunk_tile[p.n_chunks];
+        sg.made_for = p.made_for;
         int w;
         int* ctr;
         if (mapped_rows >= 0) {
@@ -177,8 +177,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
             const int seg = split / my_wgs;
             w = split - seg * my_wgs;
             sg.wgs = my_wgs;
-            sg.tile0 = (int)((int64_t)seg * tiles_b / p.n_segs);
-            sg.tiles = (int)((int64_t)(seg + 1) * tiles_b / p.n_segs) - sg.tile0;
+            sg.tile0 = 0, sg.tiles = tiles_b;
+            if (p.n_segs > 1) {             // (the 64-bit divisions are left out of the common case)
+                sg.tile0 = (int)((int64_t)seg * tiles_b / p.n_segs);
+                sg.tiles = (int)((int64_t)(seg + 1) * tiles_b / p.n_segs) - sg.tile0;
+            }
             ctr = p.chunk_ctr + (((int64_t)b * p.Hkv + g) * p.n_segs + seg) * kCtrStride;
         }
         seg_chunks(p, sg);

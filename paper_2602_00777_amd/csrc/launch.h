@@ -65,6 +65,9 @@ struct FullParams {
     // finish together.  0: workgroup x belongs to group x / wgs_per_seg.
     int gen_half;
     int n_chunks;
+    int made_for;                   // = chunk_tile[n_chunks]: the tiles the table was made for (kept beside the
+                                    // other scalars: read through the table it would be a second, dependent
+                                    // fetch of kernel arguments in front of the first tile's loads)
     int chunk_tile[kMaxChunks + 1];
 };
 
