@@ -79,6 +79,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     // paged cache: the split's part of the sequence's page table, staged in LDS (read from
     // memory if it does not fit there)
     int* const s_tbl = reinterpret_cast<int*>(s_scores + p.rows_per_split);
+    int* const s_tile_of = s_tbl + p.tbl_cap;    // DYN: the tile whose scores staging slot t (= ticket t) holds
     const int32_t* __restrict__ tbl = p.map.table + (int64_t)b * p.map.table_stride;     // unused unless paged
     int tbl_page0 = -1;
     auto stage_table = [&](int first_row, int last_row) {                   // every thread; rows of this sequence
@@ -222,7 +223,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         cur.next = lds_load(&cq.first[1]);
         cur.tile0 = lds_load(&cq.tile0[0]);
         const int stage_tiles = p.rows_per_split / TILE;      // tiles the staging area holds
-        auto stage_of = [&](const TileRef& t) { return t.ticket < stage_tiles ? t.ticket * TILE : -1; };
+        auto stage_of = [&](const TileRef& t) {
+            if (t.ticket >= stage_tiles) return -1;
+            if (lane == 0) s_tile_of[t.ticket] = t.tile;
+            return t.ticket * TILE;
+        };
         PendingClaim pc;
         pc.raw = 0, pc.slot = -1, pc.first = 0;
         Tile32 bufA, bufB;
@@ -245,20 +250,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         HYLRA_TS(1);
         __syncthreads();
         HYLRA_TS(2);
-        // write the staged scores out, slot by slot (tile starts and the score stride are
-        // multiples of 4 floats, so the 16-byte stores are aligned)
-        const int n_slots = want_scores ? cq.n_ready : 0;
-        for (int i = 0; i < n_slots; ++i) {
-            const int f0 = cq.first[i], f1 = min(cq.first[i + 1], stage_tiles);
-            const int r0 = cq.tile0[i] * TILE;
-            const int cnt = min((f1 - f0) * TILE, n_rows - r0);
-            const float* src = s_scores + f0 * TILE;
-            for (int e = 4 * tid; e < cnt; e += 4 * NW * 64) {
-                if (e + 4 <= cnt) {
-                    *reinterpret_cast<float4*>(srow + r0 + e) = *reinterpret_cast<const float4*>(src + e);
-                } else {
-                    for (int x = e; x < cnt; ++x) srow[r0 + x] = src[x];
-                }
+        // write the staged scores out: 8 threads per staged tile, 16 bytes each (tile starts and
+        // the score stride are multiples of 4 floats, so the stores are aligned)
+        const int n_staged = want_scores ? min(cq.first[cq.n_ready], stage_tiles) : 0;
+        for (int i = tid; i < n_staged * (TILE / 4); i += NW * 64) {
+            const int t = i >> 3, part = i & 7;
+            const int r = s_tile_of[t] * TILE + 4 * part;
+            const float* src = s_scores + t * TILE + 4 * part;
+            if (r + 4 <= n_rows) {
+                *reinterpret_cast<float4*>(srow + r) = *reinterpret_cast<const float4*>(src);
+            } else {
+                for (int x = 0; x < 4; ++x)
+                    if (r + x < n_rows) srow[r + x] = src[x];
             }
         }
     } else if (!DYN && row0 < row1) {
@@ -322,7 +325,9 @@ int full_mfma2_quantum(int D, int variant) { return (D == 128 && (variant == 72 
 hipError_t launch_full_mfma2(const FullParams& p, int B, int G, int variant, hipStream_t st) {
     if (variant != 72 && variant != 74) return hipErrorInvalidValue;
     dim3 grid(p.n_splits, p.Hkv, B);
-    const size_t lds = p.rows_per_split * sizeof(float) + p.tbl_cap * sizeof(int);
+    // scores of the split (or staging area), staged page table, and (variant 74) a tile number per staged tile
+    const size_t lds = p.rows_per_split * sizeof(float) + p.tbl_cap * sizeof(int) +
+                       (variant == 74 ? p.rows_per_split / 32 * sizeof(int) : 0);
 #define HYLRA_G(GG)                                                                                   \
     if (G == GG) {                                                                                    \
         if (variant == 74) hipLaunchKernelGGL((full_mfma2_kernel<GG, true>), grid, dim3(256), lds, st, p);  \
