@@ -66,3 +66,19 @@ def test_null_arguments_are_rejected_without_touching_a_gpu(lib):
     assert lib.hylra_create(ctypes.byref(h), ctypes.byref(bad), 1, 0) == 1
     bad = binding.Shape(1, 8, 2, 96, 64, 0, 0, 0, 0.0)       # head_dim 96
     assert lib.hylra_create(ctypes.byref(h), ctypes.byref(bad), 1, 0) == 2
+
+
+@pytest.mark.parametrize("compiler,std,ext", [("gcc", "-std=c99", ".c"), ("g++", "-std=c++17", ".cpp")])
+def test_header_is_plain_c_and_cxx(tmp_path, compiler, std, ext):
+    """include/hylra.h must be usable from C and from C++ with nothing but the standard headers."""
+    import shutil
+    import subprocess
+    if shutil.which(compiler) is None:
+        pytest.skip(compiler + " is not installed")
+    src = tmp_path / ("use_header" + ext)
+    src.write_text('#include "hylra.h"\n'
+                   "int main(void) { hylra_shape s; hylra_paged p; (void)s; (void)p; return (int)HYLRA_OK; }\n")
+    inc = os.path.join(ROOT, "include")
+    r = subprocess.run([compiler, std, "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, "-c", str(src),
+                        "-o", str(tmp_path / "use_header.o")], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
