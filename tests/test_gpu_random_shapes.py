@@ -20,25 +20,38 @@ def say(msg):
     print("[case] " + msg, flush=True)
 
 
-def draw(seed):
-    """A shape whose oracle run stays around a second: batch * n_kv_heads * ctx_len <= 600K rows."""
+def draw(seed, big_batch=False):
+    """A shape whose oracle run stays around a second: batch * n_kv_heads * ctx_len <= 600K rows
+    (1.5M for the large batches of short sequences)."""
     rng = np.random.RandomState(1000003 * seed + 17)
     d = int(rng.choice([64, 128]))
     G = int(rng.choice([1, 2, 3, 4, 5, 7, 8]))
     Hkv = int(rng.choice([1, 2, 4, 8]))
-    B = int(rng.choice([1, 2, 3, 5, 8, 16, 40]))
-    cap = max(300, 600000 // (B * Hkv))
+    B = int(rng.choice([64, 100, 128, 256, 300] if big_batch else [1, 2, 3, 5, 8, 16, 40]))
+    cap = max(300, (1500000 if big_batch else 600000) // (B * Hkv))
     N = int(rng.randint(200, min(cap, 50000) + 1))
     k = int(rng.randint(1, min(N, 3000) + 1))
-    mode = str(rng.choice(["plain", "plain", "paged", "ragged", "paged+ragged", "blocks", "blocks+paged+ragged"]))
+    modes = (["ragged", "paged+ragged", "blocks+paged+ragged", "plain"] if big_batch else
+             ["plain", "plain", "paged", "ragged", "paged+ragged", "blocks", "blocks+paged+ragged"])
+    mode = str(rng.choice(modes))
     page = int(rng.choice([1, 8, 16, 64, 256]))
     block = int(rng.choice([2, 16, 33, 128]))
     return rng, B, Hkv, G, d, N, k, mode, page, block
 
 
+@pytest.mark.parametrize("seed", range(1000, 1016))
+def test_random_large_batch(seed):
+    """Batches of 64 to 300 short sequences, mostly of unequal lengths."""
+    check_shape(seed, True)
+
+
 @pytest.mark.parametrize("seed", range(96))
 def test_random_shape(seed):
-    rng, B, Hkv, G, d, N, k, mode, page, block = draw(seed)
+    check_shape(seed, False)
+
+
+def check_shape(seed, big_batch):
+    rng, B, Hkv, G, d, N, k, mode, page, block = draw(seed, big_batch)
     say("seed %d: B=%d Hkv=%d G=%d d=%d N=%d k=%d mode=%s page=%d block=%d" % (seed, B, Hkv, G, d, N, k, mode, page, block))
     w = synth.Workload("case", 1, Hkv * G, Hkv, d, B, N, 1, (0,), 0.02, 3.0, 1.0, seed=5000 + seed)
     q, K, V = synth.make_layer(w, 0, synth.planted_positions(w)[0], DEV)
