@@ -24,8 +24,8 @@ HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 # HBM traffic per launch of the dominant kernel from rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE,
 # scaled by the copy-kernel calibration); see profiles/.  None until measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("llama3_8b_32k", "full_attn"): 1081256683,    # profiles/hbm_traffic_llama3_8b_32k.txt
-    ("llama3_8b_32k", "reuse_attn"): 69413116,
+    ("llama3_8b_32k", "full_attn"): 1081263987,    # profiles/hbm_traffic_llama3_8b_32k.txt
+    ("llama3_8b_32k", "reuse_attn"): 69417440,
 }
 
 
