@@ -256,5 +256,58 @@ def gather_rows(K, V, idx):
     return Ks, Vs, ic
 
 
+def gather_blocks(K, V, bidx, block, lens=None):
+    """Index-guided prefetch at block granularity (paper: "selective prefetching of only the
+    critical KV blocks"; blocks as in the block-level variant: `block` consecutive rows, the last
+    block of a sequence possibly short).  Slot t * block + r of the compact cache holds row
+    bidx[b,g,t] * block + r of sequence b when that row exists (block number in range and row
+    below the sequence's length), else zeros.  Returns (K_sparse, V_sparse [B,H,kb*block,d],
+    idx_compact [B,H,kb*block] = the slot's own number, or -1 where the slot holds no row)."""
+    K, _ = _as_np(K)
+    V, _ = _as_np(V)
+    bidx = np.asarray(bidx, dtype=np.int64)
+    B, H, N, d = K.shape
+    kb = bidx.shape[2]
+    block = int(block)
+    Ks, Vs = np.zeros((B, H, kb * block, d), K.dtype), np.zeros((B, H, kb * block, d), V.dtype)
+    ic = np.full((B, H, kb * block), -1, np.int32)
+    for b in range(B):
+        n = N if lens is None else int(lens[b])
+        for g in range(H):
+            for t in range(kb):
+                c = bidx[b, g, t]
+                if c < 0:
+                    continue
+                for r in range(block):
+                    j = c * block + r
+                    if j < n:
+                        Ks[b, g, t * block + r] = K[b, g, j]
+                        Vs[b, g, t * block + r] = V[b, g, j]
+                        ic[b, g, t * block + r] = t * block + r
+    return Ks, Vs, ic
+
+
+def append_rows(K, V, k_new, v_new, lens):
+    """Decode-time cache update that precedes Algorithm 2 (its K^cache, V^cache hold the
+    current token): the token's key and value of every (batch, KV head), k_new / v_new
+    [B,Hkv,d], become row lens[b] of sequence b.  Returns copies (K', V', lens + 1)."""
+    K, _ = _as_np(K)
+    V, _ = _as_np(V)
+    k_new, _ = _as_np(k_new)
+    v_new, _ = _as_np(v_new)
+    lens = np.asarray(lens, dtype=np.int64)
+    B, H, N, d = K.shape
+    if k_new.shape != (B, H, d) or v_new.shape != (B, H, d) or lens.shape != (B,):
+        raise ValueError("k_new / v_new must be [B,Hkv,d] and lens [B]")
+    if lens.min() < 0 or lens.max() >= N:
+        raise ValueError("a sequence has no free row left")
+    K2, V2 = K.copy(), V.copy()
+    for b in range(B):
+        for g in range(H):
+            K2[b, g, lens[b]] = k_new[b, g]
+            V2[b, g, lens[b]] = v_new[b, g]
+    return K2, V2, (lens + 1).astype(np.int32)
+
+
 def threads():
     return _load().hylra_oracle_threads()

@@ -1,8 +1,10 @@
-"""Parity at the benchmark's full sizes, in the launch configuration bench.py times: the
-first Full layer and the first Reuse layer of every BASELINE workload run at full shape on
-the GPU; the oracle recomputes sampled (batch, KV head) pairs one by one, and properties that
-hold at any size (ascending, distinct, in-range index sets; finite outputs) are checked for
-every pair."""
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+test_full_size_decode_step_all_pairs: the benchmarked call itself, hylra_decode_step with the
+workload's own policy at full shape, every layer and every (batch, KV head) pair against the
+oracle (tests/step_check.py).  The per-call tests below it run the first Full and the first
+Reuse layer through the single-layer entry points on sampled pairs, plus properties that hold
+at any size (ascending, distinct, in-range index sets; finite outputs) on every pair."""
 import numpy as np
 import pytest
 import torch
@@ -13,6 +15,29 @@ from tests.parity import assert_idx_valid, assert_out_close
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
+
+
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["llama3_8b_32k", "long_131k", "serve_b32_16k", "qwen25_7b_64k"])
+def test_full_size_decode_step_all_pairs(name):
+    from tests.step_check import check_step
+
+    print("[case] full size decode step, all layers, all pairs: %s" % name, flush=True)
+    w = synth.WORKLOADS[name]
+    policy = w.policy()
+    planted = synth.planted_positions(w)
+    data = [synth.make_layer(w, l, planted[l], DEV) for l in range(w.n_layers)]
+    qs, Ks, Vs = [x[0] for x in data], [x[1] for x in data], [x[2] for x in data]
+    del data
+    with binding.Context(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ctx_len, w.top_k) as ctx:
+        run, outs, idx_buf = ctx.prepare_step(policy, qs, Ks, Vs, w.top_k)
+        run()
+        run()                    # the benchmark times repeated steps on one context
+        torch.cuda.synchronize()
+        res = check_step(ctx, policy, qs, Ks, Vs, w.top_k, outs, idx_buf,
+                         say=lambda m: print("  " + m, flush=True))
+    print("  %s" % res, flush=True)
+    assert res["layers"] == w.n_layers and res["pairs"] == w.n_layers * w.batch * w.n_kv_heads
 
 
 def sample_pairs(B, Hkv):

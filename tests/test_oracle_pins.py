@@ -560,3 +560,89 @@ def test_policy_search_closed_forms():
     # all similarities equal to 1: every policy with one Full layer ties; the value is what is fixed
     pol, C, S = oracle.policy_search(ones, 1.0)
     assert C == 1 and S == L and pol[0] == 0
+
+
+# --------------------------------------------------------------------------------------
+# 8. index-guided prefetch (compacted caches) and the decode-time cache update
+# --------------------------------------------------------------------------------------
+def test_gather_rows_hand_written():
+    """Three rows of two columns, one head: entries (2, padding, 0, one past the cache)."""
+    K = np.array([[[[1., 2.], [3., 4.], [5., 6.]]]])
+    V = -K
+    idx = np.array([[[2, -1, 0, 3]]], np.int32)
+    Ks, Vs, ic = oracle.gather_rows(K, V, idx)
+    assert Ks.tolist() == [[[[5., 6.], [0., 0.], [1., 2.], [0., 0.]]]]
+    assert Vs.tolist() == [[[[-5., -6.], [0., 0.], [-1., -2.], [0., 0.]]]]
+    assert ic.tolist() == [[[0, -1, 2, -1]]]
+
+
+def test_gather_rows_against_fancy_indexing_and_reuse_identity():
+    q, K, V = _rand(21, B=2, Hkv=3, G=2, N=50, d=8)
+    rng = np.random.RandomState(5)
+    idx = np.stack([[rng.permutation(50)[:12] for _ in range(3)] for _ in range(2)]).astype(np.int32)
+    Ks, Vs, ic = oracle.gather_rows(K, V, idx)
+    assert np.array_equal(Ks, np.take_along_axis(K, idx[..., None].astype(np.int64), axis=2))
+    assert np.array_equal(Vs, np.take_along_axis(V, idx[..., None].astype(np.int64), axis=2))
+    assert np.array_equal(ic, np.broadcast_to(np.arange(12), ic.shape))
+    # with padding and out-of-range entries: attention over the compacted cache with the compact
+    # set is attention over the source cache with the original set
+    idx[:, :, ::4] = -1
+    idx[:, :, 5] = 50
+    Ks, Vs, ic = oracle.gather_rows(K, V, idx)
+    assert np.all(ic[:, :, ::4] == -1) and np.all(ic[:, :, 5] == -1) and np.all(Ks[:, :, 5] == 0)
+    want = oracle.reuse_sparse_attn(q, K, V, np.where(idx >= 50, -1, idx))
+    np.testing.assert_allclose(oracle.reuse_sparse_attn(q, Ks, Vs, ic), want, rtol=1e-13, atol=1e-15)
+    # bf16 bit patterns keep their element type and their bits
+    Kb = (rng.randint(0, 1 << 16, size=K.shape)).astype(np.uint16)
+    Ksb, _, _ = oracle.gather_rows(Kb, Kb, idx)
+    assert Ksb.dtype == np.uint16 and np.array_equal(Ksb[0, 1, 1], Kb[0, 1, idx[0, 1, 1]])
+
+
+def test_gather_blocks_hand_written_and_identity():
+    """Five rows in blocks of two (the last block has one row): blocks (2, 0, padding)."""
+    K = np.arange(10, dtype=np.float64).reshape(1, 1, 5, 2) + 1.0
+    V = 10.0 * K
+    bidx = np.array([[[2, 0, -1]]], np.int32)
+    Ks, Vs, ic = oracle.gather_blocks(K, V, bidx, 2)
+    assert Ks[0, 0].tolist() == [[9., 10.], [0., 0.], [1., 2.], [3., 4.], [0., 0.], [0., 0.]]
+    assert np.array_equal(Vs, 10.0 * Ks)
+    assert ic.tolist() == [[[0, -1, 2, 3, -1, -1]]]
+    # a shorter sequence: rows at or past its length are no rows
+    _, _, ic4 = oracle.gather_blocks(K, V, np.array([[[1, 0]]], np.int32), 2, lens=[3])
+    assert ic4.tolist() == [[[0, -1, 2, 3]]]
+    # block of one row is the row-level gather
+    idx = np.array([[[4, -1, 1]]], np.int32)
+    for a, b in zip(oracle.gather_blocks(K, V, idx, 1), oracle.gather_rows(K, V, idx)):
+        assert np.array_equal(a, b)
+    # attention over the compacted cache equals block attention over the source cache
+    q, K, V = _rand(22, B=2, Hkv=2, G=3, N=43, d=8)
+    rng = np.random.RandomState(6)
+    for block in (4, 5, 16):
+        nblk = -(-43 // block)
+        kb = min(3, nblk)
+        bidx = np.stack([[rng.permutation(nblk)[:kb] for _ in range(2)] for _ in range(2)]).astype(np.int32)
+        bidx[0, 0, 0] = -1
+        Ks, Vs, ic = oracle.gather_blocks(K, V, bidx, block)
+        want = oracle.reuse_block_attn(q, K, V, bidx, block)
+        np.testing.assert_allclose(oracle.reuse_sparse_attn(q, Ks, Vs, ic), want, rtol=1e-13, atol=1e-15)
+
+
+def test_append_rows_then_attend_equals_attention_on_the_longer_cache():
+    # hand-written: the new rows land at each sequence's own length, nothing else moves
+    K = np.zeros((2, 1, 4, 2)); V = np.zeros((2, 1, 4, 2))
+    K2, V2, n2 = oracle.append_rows(K, V, np.array([[[1., 2.]], [[3., 4.]]]), np.array([[[5., 6.]], [[7., 8.]]]), [3, 0])
+    assert n2.tolist() == [4, 1]
+    assert K2[0, 0].tolist() == [[0., 0.], [0., 0.], [0., 0.], [1., 2.]] and K2[1, 0].tolist() == [[3., 4.], [0., 0.], [0., 0.], [0., 0.]]
+    assert V2[0, 0, 3].tolist() == [5., 6.] and V2[1, 0, 0].tolist() == [7., 8.] and not K.any()
+    with pytest.raises(ValueError):
+        oracle.append_rows(K, V, np.zeros((2, 1, 2)), np.zeros((2, 1, 2)), [4, 0])
+    # a cache of N + 1 rows, its last row handed over as the new token
+    q, K, V = _rand(23, B=2, Hkv=2, G=2, N=31, d=8)
+    Kc, Vc = K.copy(), V.copy()
+    Kc[:, :, 30] = 99.0          # stale contents of the free row must not matter
+    Vc[:, :, 30] = -99.0
+    K2, V2, n2 = oracle.append_rows(Kc, Vc, K[:, :, 30], V[:, :, 30], [30, 30])
+    assert np.array_equal(K2, K) and np.array_equal(V2, V) and n2.tolist() == [31, 31]
+    a, ia, _ = oracle.full_attn_topk(q, K2, V2, 9)
+    b, ib, _ = oracle.full_attn_topk(q, K, V, 9)
+    assert np.array_equal(a, b) and np.array_equal(ia, ib)
