@@ -110,6 +110,27 @@ hylra_status hylra_reuse_sparse_attn(hylra_ctx *ctx, const hylra_shape *shape,
                                      void *hip_stream);
 
 /*
+ * hylra_reuse_sparse_attn for callers that cannot allocate device memory at all (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): no context, and
+ * no allocation inside -- neither hipMalloc / hipFree nor any allocating library routine.
+ * The split partials and arrival counters that the other entry points keep in a context's
+ * workspace live in a fixed array inside the library's device image instead (about 2.1 MB,
+ * held by every GPU the library has been loaded on until the process ends).  Runs on the
+ * CURRENT HIP device; hip_stream must belong to it.  Arguments, results and numerics are those
+ * of hylra_reuse_sparse_attn (same kernels, same split plan).
+ * Limits: batch * n_kv_heads <= 2048 and batch * n_q_heads * splits <= 4096, where splits is
+ * the number of workgroups the plan gives one (batch, KV head) (every BASELINE shape fits);
+ * anything larger fails with HYLRA_ERR_WORKSPACE before a kernel is launched.  Failures leave
+ * their text in hylra_last_error(NULL) (per thread).
+ * All calls on one GPU share the one array: calls that overlap in time on one GPU (two
+ * streams, two threads) race on it; calls on one stream, or otherwise ordered, do not.  The
+ * array keeps the previous call's contents; the call clears what it needs cleared.
+ */
+hylra_status hylra_reuse_sparse_attn_static(const hylra_shape *shape, const void *q, const void *K,
+                                            const void *V, const int32_t *idx, int32_t k,
+                                            float *out, void *hip_stream);
+
+/*
  * One decode step over n_layers layers (Algorithm 2, outer loop), in order, on
  * one stream.  policy is a HOST array: HYLRA_FULL runs hylra_full_attn_topk and
  * overwrites idx_buf; HYLRA_REUSE runs hylra_reuse_sparse_attn on idx_buf as the

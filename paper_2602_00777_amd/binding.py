@@ -21,6 +21,7 @@ PROFILE_CLASSES = ("full_attn", "full_finalize", "reuse_attn", "reuse_combine", 
 EXPORTS = (
     "hylra_create", "hylra_destroy", "hylra_status_str", "hylra_last_error",
     "hylra_full_attn_topk", "hylra_reuse_sparse_attn", "hylra_decode_step",
+    "hylra_reuse_sparse_attn_static",
     "hylra_full_attn_topk_blocks", "hylra_reuse_block_attn", "hylra_decode_step_blocks",
     "hylra_full_attn_topk_paged", "hylra_reuse_sparse_attn_paged", "hylra_decode_step_paged",
     "hylra_full_attn_topk_blocks_paged", "hylra_reuse_block_attn_paged", "hylra_decode_step_blocks_paged",
@@ -77,6 +78,7 @@ def load_library() -> ctypes.CDLL:
     lib.hylra_full_attn_topk.argtypes = [vp, sp, vp, vp, vp, i32, vp, vp, vp]
     lib.hylra_reuse_sparse_attn.argtypes = [vp, sp, vp, vp, vp, vp, i32, vp, vp]
     lib.hylra_decode_step.argtypes = [vp, sp, i32, vp, vp, vp, vp, i32, vp, vp, vp]
+    lib.hylra_reuse_sparse_attn_static.argtypes = [sp, vp, vp, vp, vp, i32, vp, vp]
     lib.hylra_full_attn_topk_blocks.argtypes = [vp, sp, vp, vp, vp, i32, i32, vp, vp, vp]
     lib.hylra_reuse_block_attn.argtypes = [vp, sp, vp, vp, vp, vp, i32, i32, vp, vp]
     lib.hylra_decode_step_blocks.argtypes = [vp, sp, i32, vp, vp, vp, vp, i32, i32, vp, vp, vp]
@@ -188,6 +190,26 @@ def policy_search(M, theta: float):
     if rc != 0:
         raise HylraError(rc, "hylra_policy_search", "bad argument")
     return policy, n_full.value, s.value
+
+
+def reuse_sparse_attn_static(q, K, V, idx, out, scale: float = 0.0):
+    """hylra_reuse_sparse_attn_static: the Reuse layer without a context and without any
+    allocation (the caller passes ``out``); runs on the current device."""
+    Context._check_inputs(q, K, V)
+    if idx.dtype != torch.int32 or not idx.is_cuda or not idx.is_contiguous():
+        raise TypeError("idx must be a contiguous int32 CUDA tensor")
+    if out.dtype != torch.float32 or not out.is_cuda or not out.is_contiguous() or out.shape != q.shape:
+        raise TypeError("out must be a contiguous float32 CUDA tensor shaped like q")
+    shp = make_shape(q, K, scale)
+    if tuple(idx.shape[:2]) != (shp.batch, shp.n_kv_heads):
+        raise ValueError("idx must be [B, Hkv, k]")
+    lib = load_library()
+    with torch.cuda.device(q.device):
+        rc = lib.hylra_reuse_sparse_attn_static(ctypes.byref(shp), q.data_ptr(), K.data_ptr(), V.data_ptr(),
+                                                idx.data_ptr(), idx.shape[2], out.data_ptr(), _stream_ptr(q.device))
+    if rc != 0:
+        raise HylraError(rc, "hylra_reuse_sparse_attn_static", lib.hylra_last_error(None).decode())
+    return out
 
 
 class Context:

@@ -9,6 +9,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -28,6 +29,52 @@ constexpr int kMaxCtx = 1 << 30;
 constexpr float LOG2E_HOST = 1.4426950408889634f;
 
 thread_local char g_create_error[256] = "";
+
+// Workspace of hylra_reuse_sparse_attn_static, the entry point that allocates nothing: the
+// split partials and arrival counters of the Reuse kernels, laid out as
+//   acc  float [kStaticHeadSplits][128]   partial outputs per (query head, split)
+//   ml   float [kStaticHeadSplits][2]     their (max, sum)
+//   ctr  int   [kStaticPairs]             arrival counter per (batch, KV head)
+// Every GPU the library runs on holds its own copy of this array at its own address until the
+// process ends.  In host code the array's NAME is only a handle for hipGetSymbolAddress: the
+// device address it yields (kept per device in g_scratch_ptr) is what kernels, fills and
+// copies are given.
+constexpr int64_t kStaticHeadSplits = 4096;
+constexpr int64_t kStaticPairs = 2048;
+constexpr int64_t kStaticAccBytes = kStaticHeadSplits * 128 * sizeof(float);
+constexpr int64_t kStaticMlBytes = kStaticHeadSplits * 2 * sizeof(float);
+constexpr int64_t kStaticCtrBytes = kStaticPairs * sizeof(int);
+constexpr int64_t kStaticScratchBytes = kStaticAccBytes + kStaticMlBytes + kStaticCtrBytes;
+constexpr int kMaxDevices = 64;
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+int g_scratch_cus[kMaxDevices] = {};
+
+// Device address of `scratch` on device dev (which must be the current device) and the
+// device's compute units; looked up once per device.
+hipError_t scratch_on_device(int dev, void** ptr, int* n_cus) {
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        int cus = 0;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        g_scratch_cus[dev] = cus;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    *n_cus = g_scratch_cus[dev];
+    return hipSuccess;
+}
 
 int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 int64_t ceil_div(int64_t x, int64_t m) { return (x + m - 1) / m; }
@@ -710,7 +757,7 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
 // Reuse layer over n_idx inherited entries per (batch, KV head): rows (block == 1) or blocks.
 hylra_status reuse_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* pg, const void* q,
                         const void* K, const void* V, const int32_t* idx, int32_t block, int32_t n_idx,
-                        float* out, void* hip_stream) {
+                        float* out, void* hip_stream, bool clear_counters = false) {
     int G = 0;
     Strides sd{};
     float scale = 0.f;
@@ -748,6 +795,9 @@ hylra_status reuse_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pa
     const bool fused = ctx->opt_reuse_unfused == 0;
     rp.counters = fused ? ctx->counters : nullptr;
     rp.out = out;
+    // (a workspace that other calls may have left in any state: the arrival counters must start
+    // at zero; a fill kernel, not a memset, since the caller may be capturing the stream)
+    if (clear_counters && fused) HIP_TRY(ctx, launch_fill_zero(ctx->counters, shape->batch * shape->n_kv_heads, st));
     HIP_TRY(ctx, launch_timed(ctx, 2, st, [&] {
                 if (pl.variant >= 4)
                     return launch_reuse_mfma2(rp, shape->batch, G, pl.variant == 4, pl.NW, st);
@@ -812,6 +862,42 @@ hylra_status hylra_reuse_sparse_attn(hylra_ctx* ctx, const hylra_shape* shape, c
                                      const void* K, const void* V, const int32_t* idx, int32_t k,
                                      float* out, void* hip_stream) {
     return reuse_impl(ctx, shape, nullptr, q, K, V, idx, 1, k, out, hip_stream);
+}
+
+hylra_status hylra_reuse_sparse_attn_static(const hylra_shape* shape, const void* q, const void* K,
+                                            const void* V, const int32_t* idx, int32_t k, float* out,
+                                            void* hip_stream) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess)
+        return fail(nullptr, HYLRA_ERR_HIP, "no current HIP device");
+    void* base = nullptr;
+    int n_cus = 0;
+    const hipError_t e = scratch_on_device(dev, &base, &n_cus);
+    if (e != hipSuccess)
+        return fail(nullptr, HYLRA_ERR_HIP, "address of the static workspace on device %d: %s", dev, hipGetErrorString(e));
+    if (!shape) return fail(nullptr, HYLRA_ERR_BAD_ARG, "shape is NULL");
+    // a context that owns nothing: its workspace pointers name parts of the static array
+    hylra_ctx tmp;
+    tmp.device = dev;
+    tmp.n_cus = n_cus;
+    tmp.max_shape = *shape;
+    tmp.max_k = k;
+    char* b = static_cast<char*>(base);
+    tmp.part_acc = reinterpret_cast<float*>(b);
+    tmp.part_ml = reinterpret_cast<float*>(b + kStaticAccBytes);
+    tmp.counters = reinterpret_cast<int*>(b + kStaticAccBytes + kStaticMlBytes);
+    tmp.slots = kStaticPairs;
+    tmp.cap_acc = kStaticHeadSplits * 128;
+    tmp.cap_ml = kStaticHeadSplits * 2;
+    hylra_status rc = HYLRA_OK;
+    const int64_t pairs = (int64_t)shape->batch * shape->n_kv_heads;
+    if (shape->batch < 1 || shape->n_kv_heads < 1 || pairs > kStaticPairs)
+        rc = fail(&tmp, HYLRA_ERR_WORKSPACE, "batch * n_kv_heads = %lld exceeds the static workspace's %lld pairs",
+                  (long long)pairs, (long long)kStaticPairs);
+    // the array keeps what the last call left, so reuse_impl clears the counters it will use
+    if (rc == HYLRA_OK) rc = reuse_impl(&tmp, shape, nullptr, q, K, V, idx, 1, k, out, hip_stream, true);
+    if (rc != HYLRA_OK) std::memcpy(g_create_error, tmp.err, sizeof g_create_error);
+    return rc;
 }
 
 hylra_status hylra_decode_step(hylra_ctx* ctx, const hylra_shape* shape, int32_t n_layers,

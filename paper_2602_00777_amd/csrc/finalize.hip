@@ -503,6 +503,18 @@ hipError_t launch_combine(const CombineParams& p, int n_heads_total, hipStream_t
     return hipGetLastError();
 }
 
+// ---- zero fill of small integer arrays ----
+__global__ __launch_bounds__(256) void fill_zero_kernel(int* __restrict__ p, int n) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+hipError_t launch_fill_zero(int* p, int n, hipStream_t st) {
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((n + 255) / 256), dim3(256), 0, st, p, n);
+    return hipGetLastError();
+}
+
 // ---- measurement kernels ----
 __global__ __launch_bounds__(256) void probe_copy_kernel(uint4* __restrict__ dst,
                                                          const uint4* __restrict__ src, size_t n16) {

@@ -243,6 +243,8 @@ int select_chunk_rows(int E);
 hipError_t launch_select(const SelectParams& p, int B, int E, int step, hipStream_t st);
 hipError_t launch_block_max(const BlockMaxParams& p, int B, int Hkv, hipStream_t st);
 hipError_t launch_combine(const CombineParams& p, int n_heads_total, hipStream_t st);
+// n ints at p become zero (a kernel: safe to record into a HIP graph)
+hipError_t launch_fill_zero(int* p, int n, hipStream_t st);
 hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t st);
 
