@@ -21,12 +21,19 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E, published peak
 
-# HBM traffic per launch of the dominant kernel from rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE,
-# scaled by the copy-kernel calibration); see profiles/.  None until measured.
-MEASURED_TRAFFIC_BYTES = {
-    ("llama3_8b_32k", "full_attn"): 1081263987,    # profiles/hbm_traffic_llama3_8b_32k.txt
-    ("llama3_8b_32k", "reuse_attn"): 69417440,
-}
+DTYPE = ("f32 (bf16 q/K/V in; scores, softmax and accumulation in fp32; the matrix-core kernels feed the "
+         "softmax weights to P.V as a hi+lo bf16 pair = 16 mantissa bits)")
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this bench,
+    scaled by the copy-kernel calibration: profiles/traffic.json, written by
+    `python -m paper_2602_00777_amd.profile_summary`.  None if that workload was not profiled."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
+            return json.load(f).get(workload, {}).get(kernel)
+    except (OSError, ValueError):
+        return None
 
 
 def log(msg):
@@ -56,7 +63,10 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="capture one decode step in a HIP graph (through torch) and time its replays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--probe", action="store_true", help="also time the plain copy / read kernels")
+    ap.add_argument("--no-probe", action="store_true",
+                    help="skip the untimed ceilings (plain copy / streaming read of 4 GiB, bare gather of the Reuse rows)")
+    ap.add_argument("--no-parity", action="store_true",
+                    help="skip the untimed post-run comparison of the step's outputs with the CPU oracle")
     ap.add_argument("--opt", action="append", default=[], help="library option name=value")
     args = ap.parse_args()
 
@@ -182,6 +192,28 @@ def main():
     ms_per_step = 1e3 * elapsed / args.steps
     tokens_per_s = w.batch / (elapsed / args.steps)
 
+    # Algorithm 2 as written runs TopK at every Full layer; the step above skips it where the set
+    # would be overwritten unread (a Full layer directly followed by another).  Same outputs;
+    # the step with every TopK is timed beside it.
+    ms_every = None
+    plain = not (args.offload or args.graph)
+    if plain:
+        ctx_every = binding.Context(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ctx_len, w.top_k,
+                                    topk_every_full_layer=True)
+        for o in args.opt:
+            name, val = o.split("=")
+            ctx_every.set_option(name, int(val))
+        run_every, _, _ = ctx_every.prepare_step(policy, qs, Ks, Vs, k_sel, block=args.block, paged=paged)
+        for _ in range(args.warmup):
+            run_every()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run_every()
+        torch.cuda.synchronize()
+        ms_every = 1e3 * (time.perf_counter() - t0) / args.steps
+        ctx_every.close()
+
     # per-kernel durations: the same steps again, every launch bracketed by HIP events on
     # the launch stream
     ctx.profile_enable(True)
@@ -202,24 +234,37 @@ def main():
     full_bytes = 4 * Hkv * rows_total * d + small
     reuse_bytes = 4 * Hkv * sel_total * d + small
 
-    def roof(kernel, nbytes):
-        kk = kernels.get(kernel)
-        if not kk:
+    def roof(label, kernel, nbytes, avg_us):
+        if not avg_us:
             return None
-        gbs = nbytes / (kk["avg_us"] * 1e-6) / 1e9
-        return {"bound": "hbm", "kernel": kernel, "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
+        gbs = nbytes / (avg_us * 1e-6) / 1e9
+        return {"bound": "hbm", "kernel": label, "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
-                "algorithmic_bytes": nbytes, "avg_us": round(kk["avg_us"], 2),
-                "traffic": None if args.paged or args.block or args.ragged else MEASURED_TRAFFIC_BYTES.get((w.name, kernel))}
+                "algorithmic_bytes": nbytes, "avg_us": round(avg_us, 2),
+                "traffic": None if args.paged or args.block or args.ragged else measured_traffic(w.name, kernel)}
 
-    full_time = (kernels.get("full_attn", {}).get("avg_us") or 0) * n_full
-    reuse_time = (kernels.get("reuse_attn", {}).get("avg_us") or 0) * n_reuse
-    dominant = ("full_attn", full_bytes) if full_time >= reuse_time else ("reuse_attn", reuse_bytes)
-    roofline = roof(*dominant)
-    other = roof("reuse_attn", reuse_bytes) if dominant[0] == "full_attn" else roof("full_attn", full_bytes)
+    def total_us(name):
+        kk = kernels.get(name)
+        return kk["avg_us"] * kk["launches"] / prof_steps if kk else 0.0
 
+    # A Full layer is its streaming pass plus its second kernel (merge of the partials, TopK):
+    # the headline fraction charges both to the layer's bytes; the streaming pass alone (the
+    # one kernel a rocprofv3 trace shows under that name) is given beside it.
+    full_layer_us = (total_us("full_attn") + total_us("full_finalize")) / n_full if n_full else 0.0
+    reuse_us = (kernels.get("reuse_attn") or {}).get("avg_us") or 0.0
+    full_layer = roof("full layer = streaming pass (full_attn) + merge and top-k (full_finalize), mean over the step's Full layers",
+                      "full_attn", full_bytes, full_layer_us)
+    full_pass = roof("full_attn (streaming pass alone)", "full_attn", full_bytes, (kernels.get("full_attn") or {}).get("avg_us"))
+    reuse = roof("reuse_attn", "reuse_attn", reuse_bytes, reuse_us)
+    if full_layer_us * n_full >= reuse_us * n_reuse:
+        roofline, other = full_layer, reuse
+    else:
+        roofline, other = reuse, full_layer
+
+    # Untimed ceilings on this machine: plain copy and streaming read of 4 GiB, and the bare gather
+    # of the rows the Reuse layers read (same index sets, no arithmetic).
     probe = None
-    if args.probe:
+    if not args.no_probe and not (args.paged or args.block or args.offload):
         nbytes = 4 << 30
         src = torch.empty(nbytes, dtype=torch.uint8, device=dev).random_(0, 255)
         dst = torch.empty_like(src)
@@ -236,8 +281,44 @@ def main():
             n, ms = ctx.profile_read()["probe"]
             moved = nbytes * (2 if name == "copy" else 1)
             probe[name + "_GBps"] = round(moved / (ms / n * 1e-3) / 1e9, 1)
-        ctx.profile_enable(False)
         del src, dst
+        reuse_layers = [l for l in range(w.n_layers) if policy[l] == synth.REUSE]
+        if reuse_layers:
+            for l in reuse_layers:
+                ctx.probe_gather(Ks[l], Vs[l], idx_buf, sink)
+            torch.cuda.synchronize()
+            ctx.profile_reset()
+            for _ in range(5):
+                for l in reuse_layers:          # a different layer's cache every launch: nothing stays cached
+                    ctx.probe_gather(Ks[l], Vs[l], idx_buf, sink)
+            torch.cuda.synchronize()
+            n, ms = ctx.profile_read()["probe"]
+            probe["gather_us"] = round(1e3 * ms / n, 2)
+            probe["gather_GBps"] = round(4 * Hkv * sel_total * d / (ms / n * 1e-3) / 1e9, 1)
+        ctx.profile_enable(False)
+
+    # Untimed: the step's outputs against the CPU oracle on every (batch, KV head) pair of
+    # sampled layers (the first Full layer that hands its set on, the first and the last Reuse
+    # layer, the last Full layer); tests/test_gpu_full_size.py does all layers.
+    parity = None
+    if not args.no_parity and plain and not (args.paged or args.block or args.ragged):
+        from tests.step_check import check_step
+
+        fulls = [l for l in range(w.n_layers) if policy[l] == synth.FULL]
+        reuses = [l for l in range(w.n_layers) if policy[l] == synth.REUSE]
+        sample = {fulls[-1]}
+        sample |= set([l for l in fulls if l + 1 < w.n_layers and policy[l + 1] == synth.REUSE][:1])
+        if reuses:
+            sample |= {reuses[0], reuses[-1]}
+        run()
+        torch.cuda.synchronize()
+        t0 = time.time()
+        res = check_step(ctx, policy, qs, Ks, Vs, w.top_k, outs, idx_buf, layers=sorted(sample))
+        parity = {"layers": sorted(sample), "pairs_per_layer": B * Hkv, "out_tolerance": 2e-3,
+                  "max_err_full": float("%.3g" % res["max_err_full"]), "max_err_reuse": float("%.3g" % res["max_err_reuse"]),
+                  "idx_rule": "exact outside a 1e-4 score band around the k-th score",
+                  "sets_differing_inside_band": res["sets_differing_in_band"], "seconds": round(time.time() - t0, 1)}
+        log("parity: %s" % parity)
 
     cpu = None
     if not args.no_cpu_baseline and not args.paged and not args.ragged:
@@ -249,15 +330,19 @@ def main():
         "value": round(tokens_per_s, 1), "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": DTYPE, "data": "synthetic",
         "config": {"workload": w.name, "description": w.description, "policy": args.policy,
                    "n_layers": w.n_layers, "full_layers": n_full, "reuse_layers": n_reuse,
                    "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d, "ctx_len": N,
                    "top_k": k, "block": args.block or 1, "page_size": args.paged or None,
                    "seq_lens": lens.tolist() if lens is not None else None, "hip_graph": bool(args.graph),
                    "kv_dtype": "bf16", "accumulate": "f32"},
+        "ms_per_step_topk_at_every_full_layer": round(ms_every, 4) if ms_every else None,
+        "parity_checked": parity is not None,
+        "parity": parity,
         "roofline": roofline,
         "roofline_other": other,
+        "roofline_streaming_pass": full_pass,
         "kernels_us": {n: round(v["avg_us"], 2) for n, v in kernels.items()},
         "cpu_baseline": cpu,
     }

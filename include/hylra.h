@@ -74,6 +74,22 @@ typedef struct {
  * HOST call; allocates device memory; *out is NULL on failure. */
 hylra_status hylra_create(hylra_ctx **out, const hylra_shape *max_shape, int32_t max_k, int device);
 
+/*
+ * hylra_create with behaviour flags (hylra_create passes 0):
+ *   HYLRA_FLAG_DETERMINISTIC  only kernels whose every output is bit-identical from run to run.
+ *       Without it the Full layer may hand its rows out to workgroups at run time (faster on
+ *       large batches); index sets and Reuse outputs are bit-reproducible either way, but the
+ *       Full layer's attention output can then differ in the last bits between runs (the
+ *       partial sums are formed in a different grouping), within 1e-5 relative.
+ *   HYLRA_FLAG_TOPK_EVERY_FULL_LAYER  hylra_decode_step* run TopK at every Full layer, as
+ *       Algorithm 2 is written, also where the set would be overwritten before anyone reads
+ *       it (a Full layer directly followed by another).  Outputs are the same either way.
+ */
+#define HYLRA_FLAG_DETERMINISTIC 1u
+#define HYLRA_FLAG_TOPK_EVERY_FULL_LAYER 2u
+hylra_status hylra_create_ex(hylra_ctx **out, const hylra_shape *max_shape, int32_t max_k, int device,
+                             uint32_t flags);
+
 /* Frees the workspace.  The caller makes sure no work of this context is still
  * running.  NULL is accepted. */
 hylra_status hylra_destroy(hylra_ctx *ctx);
@@ -389,11 +405,21 @@ hylra_status hylra_profile_read(hylra_ctx *ctx, int32_t kernel_class, int32_t *n
 hylra_status hylra_probe_copy(hylra_ctx *ctx, void *dst, const void *src, size_t bytes,
                               void *hip_stream);
 
-/* Streaming read of `bytes` bytes (multiple of 16) with a trivial reduction;
+/* Streaming read of `bytes` bytes (multiple of 16; non-temporal loads, as the attention
+ * kernels read the cache) with a trivial reduction;
  * writes one 32-bit word per workgroup to `sink` (>= 16384 bytes).  Measures the
  * reachable HBM read rate. */
 hylra_status hylra_probe_read(hylra_ctx *ctx, const void *src, size_t bytes, void *sink,
                               void *hip_stream);
+
+/* Bare gather of the rows a Reuse layer over (K, V, idx, k) would read -- the same bytes,
+ * fetched whole rows at a time with everything in flight at once, and no arithmetic: the
+ * floor under hylra_reuse_sparse_attn for these index sets.  Arguments as in
+ * hylra_reuse_sparse_attn; entries < 0 or >= ctx_len are skipped; sink (>= 16384 bytes,
+ * 16-byte aligned) is practically never written. */
+hylra_status hylra_probe_gather(hylra_ctx *ctx, const hylra_shape *shape, const void *K,
+                                const void *V, const int32_t *idx, int32_t k, void *sink,
+                                void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -16,10 +16,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libhylra.so")
 
 FULL, REUSE = 0, 1
+FLAG_DETERMINISTIC, FLAG_TOPK_EVERY_FULL_LAYER = 1, 2
 PROFILE_CLASSES = ("full_attn", "full_finalize", "reuse_attn", "reuse_combine", "probe")
 
 EXPORTS = (
-    "hylra_create", "hylra_destroy", "hylra_status_str", "hylra_last_error",
+    "hylra_create", "hylra_create_ex", "hylra_destroy", "hylra_status_str", "hylra_last_error",
     "hylra_full_attn_topk", "hylra_reuse_sparse_attn", "hylra_decode_step",
     "hylra_reuse_sparse_attn_static",
     "hylra_full_attn_topk_blocks", "hylra_reuse_block_attn", "hylra_decode_step_blocks",
@@ -28,7 +29,7 @@ EXPORTS = (
     "hylra_overlap_counts", "hylra_similarity_matrix", "hylra_policy_search",
     "hylra_offload_slot_bytes", "hylra_gather_rows", "hylra_decode_step_offloaded",
     "hylra_set_option", "hylra_profile_enable", "hylra_profile_reset", "hylra_profile_read",
-    "hylra_probe_copy", "hylra_probe_read",
+    "hylra_probe_copy", "hylra_probe_read", "hylra_probe_gather",
 )
 
 
@@ -70,6 +71,7 @@ def load_library() -> ctypes.CDLL:
     vp, i32 = ctypes.c_void_p, ctypes.c_int32
     sp = ctypes.POINTER(Shape)
     lib.hylra_create.argtypes = [ctypes.POINTER(vp), sp, i32, ctypes.c_int]
+    lib.hylra_create_ex.argtypes = [ctypes.POINTER(vp), sp, i32, ctypes.c_int, ctypes.c_uint32]
     lib.hylra_destroy.argtypes = [vp]
     lib.hylra_status_str.argtypes = [ctypes.c_int]
     lib.hylra_status_str.restype = ctypes.c_char_p
@@ -102,6 +104,7 @@ def load_library() -> ctypes.CDLL:
     lib.hylra_profile_read.argtypes = [vp, i32, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_double)]
     lib.hylra_probe_copy.argtypes = [vp, vp, vp, ctypes.c_size_t, vp]
     lib.hylra_probe_read.argtypes = [vp, vp, ctypes.c_size_t, vp, vp]
+    lib.hylra_probe_gather.argtypes = [vp, sp, vp, vp, vp, i32, vp, vp]
     for name in EXPORTS:
         if name not in ("hylra_status_str", "hylra_last_error", "hylra_offload_slot_bytes"):
             getattr(lib, name).restype = ctypes.c_int
@@ -216,14 +219,15 @@ class Context:
     """Owns one ``hylra_ctx`` (a fixed device workspace) on one GPU."""
 
     def __init__(self, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, ctx_len: int,
-                 max_k: int, device: int = 0):
+                 max_k: int, device: int = 0, deterministic: bool = False, topk_every_full_layer: bool = False):
         self._lib = load_library()
         self._h = ctypes.c_void_p()
         self.device = torch.device("cuda", device)
         shp = Shape(batch, n_q_heads, n_kv_heads, head_dim, ctx_len, 0, 0, 0, 0.0)
-        rc = self._lib.hylra_create(ctypes.byref(self._h), ctypes.byref(shp), max_k, device)
+        flags = (FLAG_DETERMINISTIC if deterministic else 0) | (FLAG_TOPK_EVERY_FULL_LAYER if topk_every_full_layer else 0)
+        rc = self._lib.hylra_create_ex(ctypes.byref(self._h), ctypes.byref(shp), max_k, device, flags)
         if rc != 0:
-            raise HylraError(rc, "hylra_create", self._lib.hylra_last_error(None).decode())
+            raise HylraError(rc, "hylra_create_ex", self._lib.hylra_last_error(None).decode())
 
     def close(self):
         if getattr(self, "_h", None) and self._h.value:
@@ -552,3 +556,10 @@ class Context:
         nbytes = src.numel() * src.element_size()
         self._check(self._lib.hylra_probe_read(self._h, src.data_ptr(), nbytes, sink.data_ptr(),
                                                _stream_ptr(src.device)), "hylra_probe_read")
+
+    def probe_gather(self, K: torch.Tensor, V: torch.Tensor, idx: torch.Tensor, sink: torch.Tensor):
+        B, Hkv, N, d = K.shape
+        shp = Shape(B, Hkv, Hkv, d, N, K.stride(0), K.stride(1), K.stride(2), 0.0)
+        self._check(self._lib.hylra_probe_gather(self._h, ctypes.byref(shp), K.data_ptr(), V.data_ptr(),
+                                                 idx.data_ptr(), idx.shape[2], sink.data_ptr(),
+                                                 _stream_ptr(K.device)), "hylra_probe_gather")

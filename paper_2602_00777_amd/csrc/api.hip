@@ -107,6 +107,8 @@ struct hylra_ctx {
     int64_t cap_scores = 0;
     int64_t cap_bscores = 0;
 
+    uint32_t flags = 0;         // HYLRA_FLAG_* given at creation
+
     int32_t opt_full_split_rows = 0;
     int32_t opt_reuse_split_rows = 0;
     int32_t opt_full_variant = 0;
@@ -363,9 +365,10 @@ hylra_status plan_full(const hylra_ctx* ctx, const hylra_shape* s, int G, FullPl
         // it balances (batch 1 / 32K: 33 us against 27.5 us evenly split; batch 8 / 8K: 52 vs 48.5)
         small = s->ctx_len / S < 2048;
     }
+    const bool fixed_order = (ctx->flags & HYLRA_FLAG_DETERMINISTIC) != 0;     // no run-time hand-out of rows
     pl.variant = ctx->opt_full_variant > 0 ? ctx->opt_full_variant
-                 : s->head_dim == 128 ? (small ? 72 : one_segment && G <= 4 ? 74 : mixes ? 74 : 72)
-                 : G > 4 ? 52 : one_segment ? 43 : 23;
+                 : s->head_dim == 128 ? (small || fixed_order ? 72 : one_segment && G <= 4 ? 74 : mixes ? 74 : 72)
+                 : G > 4 ? 52 : one_segment && !fixed_order ? 43 : 23;
     const int quantum = full_block_quantum(s->head_dim, G, pl.variant);
     if (quantum <= 0) return fail(ctx, HYLRA_ERR_UNSUPPORTED, "Full kernel variant %d is not built for d=%d G=%d", pl.variant, s->head_dim, G);
     if (is_self_scheduling(pl.variant)) {
@@ -496,8 +499,15 @@ const char* hylra_status_str(hylra_status s) {
 const char* hylra_last_error(const hylra_ctx* ctx) { return ctx ? ctx->err : g_create_error; }
 
 hylra_status hylra_create(hylra_ctx** out, const hylra_shape* max_shape, int32_t max_k, int device) {
+    return hylra_create_ex(out, max_shape, max_k, device, 0u);
+}
+
+hylra_status hylra_create_ex(hylra_ctx** out, const hylra_shape* max_shape, int32_t max_k, int device,
+                             uint32_t flags) {
     if (!out) return fail(nullptr, HYLRA_ERR_BAD_ARG, "out is NULL");
     *out = nullptr;
+    if (flags & ~(uint32_t)(HYLRA_FLAG_DETERMINISTIC | HYLRA_FLAG_TOPK_EVERY_FULL_LAYER))
+        return fail(nullptr, HYLRA_ERR_BAD_ARG, "unknown flag bits 0x%x", flags);
     hylra_ctx* ctx = new (std::nothrow) hylra_ctx;
     if (!ctx) return fail(nullptr, HYLRA_ERR_HIP, "out of host memory");
     int G = 0;
@@ -515,6 +525,7 @@ hylra_status hylra_create(hylra_ctx** out, const hylra_shape* max_shape, int32_t
         return rc;
     }
     ctx->device = device;
+    ctx->flags = flags;
     (void)hipDeviceGetAttribute(&ctx->n_cus, hipDeviceAttributeMultiprocessorCount, device);
     ctx->max_shape = *max_shape;
     ctx->max_k = max_k;
@@ -839,7 +850,8 @@ hylra_status step_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
     ctx->in_step = true, ctx->step_planned = false;
     hylra_status rc = HYLRA_OK;
     for (int l = 0; l < n_layers && rc == HYLRA_OK; ++l) {
-        const bool want_idx = l + 1 == n_layers || policy[l + 1] == HYLRA_REUSE;
+        const bool want_idx = l + 1 == n_layers || policy[l + 1] == HYLRA_REUSE ||
+                              (ctx->flags & HYLRA_FLAG_TOPK_EVERY_FULL_LAYER);
         rc = policy[l] == HYLRA_FULL
                  ? full_impl(ctx, shape, pg, q_l[l], K_l[l], V_l[l], block, k, out_l[l], idx_buf, hip_stream, want_idx)
                  : reuse_impl(ctx, shape, pg, q_l[l], K_l[l], V_l[l], idx_buf, block, k, out_l[l], hip_stream);
@@ -1094,7 +1106,8 @@ hylra_status hylra_decode_step_offloaded(hylra_ctx* ctx, const hylra_shape* shap
     int run_end = 0, next_fetch = 0;      // the Reuse layers of the current run are [.., run_end); next to prefetch
     for (int l = 0; l < n_layers; ++l) {
         if (policy[l] == HYLRA_FULL) {
-            const bool want_idx = l + 1 == n_layers || policy[l + 1] == HYLRA_REUSE;
+            const bool want_idx = l + 1 == n_layers || policy[l + 1] == HYLRA_REUSE ||
+                                  (ctx->flags & HYLRA_FLAG_TOPK_EVERY_FULL_LAYER);
             hylra_status rc = full_impl(ctx, shape, nullptr, q_l[l], K_l[l], V_l[l], 1, k, out_l[l], idx_buf, cs, want_idx);
             if (rc != HYLRA_OK) return rc;
             run_end = l + 1;
@@ -1217,6 +1230,27 @@ hylra_status hylra_probe_copy(hylra_ctx* ctx, void* dst, const void* src, size_t
     hipStream_t st = (hipStream_t)hip_stream;
     DeviceGuard guard(ctx->device);
     HIP_TRY(ctx, launch_timed(ctx, 4, st, [&] { return launch_probe_copy(dst, src, bytes, st); }));
+    return HYLRA_OK;
+}
+
+hylra_status hylra_probe_gather(hylra_ctx* ctx, const hylra_shape* shape, const void* K, const void* V,
+                                const int32_t* idx, int32_t k, void* sink, void* hip_stream) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    int G = 0;
+    Strides sd{};
+    float scale = 0.f;
+    hylra_status rc = check_shape(ctx, shape, G, sd, scale);
+    if (rc != HYLRA_OK) return rc;
+    if (!K || !V || !idx || !sink || k < 1 || (((uintptr_t)K | (uintptr_t)V | (uintptr_t)sink) & 15) || ((uintptr_t)idx & 3))
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "probe_gather needs 16-byte aligned K, V, sink, a 4-byte aligned idx and k >= 1");
+    GatherParams gp{};
+    gp.K = (const uint16_t*)K, gp.V = (const uint16_t*)V;
+    gp.sb = sd.b, gp.sh = sd.h, gp.sn = sd.n;
+    gp.Hkv = shape->n_kv_heads, gp.D = shape->head_dim, gp.N = shape->ctx_len, gp.k = k;
+    gp.idx = idx;
+    hipStream_t st = (hipStream_t)hip_stream;
+    DeviceGuard guard(ctx->device);
+    HIP_TRY(ctx, launch_timed(ctx, 4, st, [&] { return launch_probe_gather(gp, shape->batch, ctx->n_cus, sink, st); }));
     return HYLRA_OK;
 }
 

@@ -15,6 +15,7 @@
 // Also here: the partial merge of the Reuse layer and two measurement kernels.
 #include "device_util.h"
 #include "launch.h"
+#include "mfma_core.h"
 #include "select_util.h"
 
 #ifdef HYLRA_TRACE
@@ -528,8 +529,11 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const uint4* __restrict
     const size_t stride = (size_t)gridDim.x * blockDim.x;
     uint32_t acc = 0;
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    // streaming (non-temporal) loads, as the attention kernels use for the cache
+    const uint16_t* s16 = reinterpret_cast<const uint16_t*>(src);
     for (; i + 3 * stride < n16; i += 4 * stride) {
-        const uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        const uint4 a = ld16<true>(s16 + 8 * i), b = ld16<true>(s16 + 8 * (i + stride)),
+                    c = ld16<true>(s16 + 8 * (i + 2 * stride)), d = ld16<true>(s16 + 8 * (i + 3 * stride));
         acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^
                d.z ^ d.w;
     }
@@ -543,6 +547,53 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const uint4* __restrict
     if ((threadIdx.x & 63) == 0) s[threadIdx.x >> 6] = acc;
     __syncthreads();
     if (threadIdx.x == 0) sink[blockIdx.x] = s[0] ^ s[1] ^ s[2] ^ s[3];
+}
+
+// Bare gather: the rows a Reuse layer would read (k entries per (batch, KV head), from K and
+// from V), fetched whole with 16 adjacent lanes per row and all of a wave's 64 rows in flight
+// at once, and nothing else -- no arithmetic, no partials, no merge.  What it takes is the
+// floor under the Reuse kernels for the same index sets.
+__global__ __launch_bounds__(512) void probe_gather_kernel(GatherParams p, uint32_t* __restrict__ sink) {
+    const int g = blockIdx.y, b = blockIdx.z;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int piece = lane & 15, gq = lane >> 4;
+    const int64_t pair = (int64_t)b * p.Hkv + g;
+    const int32_t* __restrict__ ib = p.idx + pair * p.k;
+    const int64_t base = (int64_t)b * p.sb + (int64_t)g * p.sh;
+    const int t0 = (blockIdx.x * (blockDim.x >> 6) + wave) * 64;
+    const bool live = piece < (p.D >> 3);
+    int row[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int t = t0 + 16 * (i >> 2) + 4 * gq + (i & 3);
+        row[i] = t < p.k ? ib[t] : -1;
+    }
+    uint4 kv[16], vv[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        kv[i] = vv[i] = make_uint4(0, 0, 0, 0);
+        if (live && (unsigned)row[i] < (unsigned)p.N) {
+            const int64_t off = base + (int64_t)row[i] * p.sn + 8 * piece;
+            kv[i] = ld16<true>(p.K + off);
+            vv[i] = ld16<true>(p.V + off);
+        }
+    }
+    uint32_t acc = 0;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+        acc ^= kv[i].x ^ kv[i].y ^ kv[i].z ^ kv[i].w ^ vv[i].x ^ vv[i].y ^ vv[i].z ^ vv[i].w;
+    // (keeps the loads alive; practically never taken, so the kernel stores nothing)
+    if (acc == 0x9e3779b9u) sink[(blockIdx.x + blockIdx.y + blockIdx.z) & 4095] = acc;
+}
+
+hipError_t launch_probe_gather(const GatherParams& p, int B, int n_cus, void* sink, hipStream_t st) {
+    // workgroups of 8 waves (one per compute unit, as the Reuse kernel prefers) while that
+    // still gives every compute unit one; smaller ones for small batches
+    int waves = 8;
+    while (waves > 1 && (int64_t)((p.k + 64 * waves - 1) / (64 * waves)) * p.Hkv * B < n_cus) waves >>= 1;
+    const dim3 grid((p.k + 64 * waves - 1) / (64 * waves), p.Hkv, B);
+    hipLaunchKernelGGL(probe_gather_kernel, grid, dim3(64 * waves), 0, st, p, reinterpret_cast<uint32_t*>(sink));
+    return hipGetLastError();
 }
 
 constexpr int kProbeBlocks = 4096;   // sink needs kProbeBlocks words

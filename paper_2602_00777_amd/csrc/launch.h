@@ -246,6 +246,7 @@ hipError_t launch_combine(const CombineParams& p, int n_heads_total, hipStream_t
 // n ints at p become zero (a kernel: safe to record into a HIP graph)
 hipError_t launch_fill_zero(int* p, int n, hipStream_t st);
 hipError_t launch_probe_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
+hipError_t launch_probe_gather(const GatherParams& p, int B, int n_cus, void* sink, hipStream_t st);
 hipError_t launch_probe_read(const void* src, size_t bytes, void* sink, hipStream_t st);
 
 }  // namespace hylra

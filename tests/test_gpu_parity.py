@@ -421,6 +421,47 @@ def test_results_are_deterministic(variant):
     assert np.array_equal(ra, rb)
 
 
+def test_creation_flags():
+    """HYLRA_FLAG_DETERMINISTIC: the Full output is bit-identical from run to run at a shape whose
+    default kernel hands rows out at run time.  HYLRA_FLAG_TOPK_EVERY_FULL_LAYER: same outputs
+    and final set as the step that skips the TopK nobody reads."""
+    say("creation flags")
+    B, Hkv, G, d, N, k = 16, 4, 4, 128, 8192, 300        # batch * n_kv_heads = 64: self-scheduling by default
+    q, K, V = rand_case(31, B, Hkv, G, d, N)
+    with binding.Context(B, Hkv * G, Hkv, d, N, k, deterministic=True) as ctx:
+        a_out, a_idx = run_full(ctx, q, K, V, k)
+        for _ in range(3):
+            b_out, b_idx = run_full(ctx, q, K, V, k)
+            assert np.array_equal(a_out, b_out) and np.array_equal(a_idx, b_idx)
+    ref_out, ref_idx, shat = oracle.full_attn_topk(q, K, V, k, want_shat=True)
+    assert_out_close(a_out, ref_out, "deterministic flag")
+    assert_idx_valid(a_idx, shat, k, "deterministic flag", exact_ref=ref_idx)
+    w = synth.scaled(synth.WORKLOADS["llama3_8b_32k"], n_layers=5, batch=2, n_q_heads=8, n_kv_heads=2, ctx_len=3000,
+                     top_k=200, full_layers=(0, 1, 2, 4))
+    policy, _, data = synth.make_workload(w, DEV)
+    qs, Ks, Vs = [x[0] for x in data], [x[1] for x in data], [x[2] for x in data]
+    res = []
+    for every in (False, True):
+        with binding.Context(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ctx_len, w.top_k, deterministic=True,
+                             topk_every_full_layer=every) as ctx:
+            ctx.profile_enable(True)
+            ctx.profile_reset()
+            outs, idx_buf = ctx.decode_step(policy, qs, Ks, Vs, w.top_k)
+            torch.cuda.synchronize()
+            res.append(([o.cpu().numpy() for o in outs], idx_buf.cpu().numpy()))
+    for l in range(w.n_layers):
+        assert np.array_equal(res[0][0][l], res[1][0][l]), "layer %d" % l
+    assert np.array_equal(res[0][1], res[1][1])
+    with pytest.raises(binding.HylraError):
+        binding.load_library()      # (loaded) -- an unknown flag bit is refused
+        import ctypes
+        h = ctypes.c_void_p()
+        shp = binding.Shape(1, 8, 2, 128, 128, 0, 0, 0, 0.0)
+        rc = binding.load_library().hylra_create_ex(ctypes.byref(h), ctypes.byref(shp), 8, 0, 0x80)
+        if rc != 0:
+            raise binding.HylraError(rc, "hylra_create_ex", binding.load_library().hylra_last_error(None).decode())
+
+
 def test_error_codes():
     say("error codes")
     B, Hkv, G, d, N, k = 1, 2, 4, 128, 512, 32
@@ -490,6 +531,14 @@ def test_profile_and_probe_aids():
         torch.cuda.synchronize()
         assert torch.equal(dst, src)
         assert ctx.profile_read()["probe"][0] == 2
+        # the bare gather reads the rows a Reuse layer would read and writes nothing
+        pad = idx.clone()
+        pad[:, :, ::3] = -1
+        pad[:, :, 1] = N
+        sink.fill_(3)
+        ctx.probe_gather(K, V, pad, sink)
+        torch.cuda.synchronize()
+        assert ctx.profile_read()["probe"][0] == 3 and torch.all(sink == 3)
         ctx.profile_enable(False)
         with pytest.raises(binding.HylraError):
             ctx.set_option("no_such_option", 1)
