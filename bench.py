@@ -60,6 +60,9 @@ def main():
     ap.add_argument("--offload", type=int, default=0,
                     help="index-guided prefetch: keep the Reuse layers' caches in pinned host memory and fetch only "
                          "the selected rows over PCIe into this many staging slots (0 = everything resident)")
+    ap.add_argument("--append", action="store_true",
+                    help="hylra_decode_step_append: every layer first writes the current token's key / value row into "
+                         "its cache (the last row; with --ragged, the row behind each sequence's length minus one)")
     ap.add_argument("--graph", action="store_true",
                     help="capture one decode step in a HIP graph (through torch) and time its replays")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -156,8 +159,8 @@ def main():
         n_reuse = int((policy == synth.REUSE).sum())
         del sets
     if args.offload:
-        if args.block or args.paged or args.ragged or args.graph:
-            print("bench.py: --offload runs on the contiguous token-level layout, launched eagerly", file=sys.stderr)
+        if args.graph or args.append:
+            print("bench.py: --offload is launched eagerly and without --append", file=sys.stderr)
             sys.exit(2)
         t0 = time.time()
         for l in range(w.n_layers):
@@ -167,7 +170,18 @@ def main():
                 data[l] = None
         log("offloaded %d Reuse layers (%.1f GiB) to pinned host memory in %.1f s" %
             (n_reuse, n_reuse * w.kv_bytes_per_layer() / 2**30, time.time() - t0))
-        run, outs, idx_buf, _copy_stream = ctx.prepare_step_offloaded(policy, qs, Ks, Vs, k_sel, n_slots=args.offload)
+        run, outs, idx_buf, _copy_stream = ctx.prepare_step_offloaded(policy, qs, Ks, Vs, k_sel, n_slots=args.offload,
+                                                                      block=args.block, paged=paged)
+    elif args.append:
+        if args.block:
+            print("bench.py: --append runs at token level", file=sys.stderr)
+            sys.exit(2)
+        gen = torch.Generator(device=dev).manual_seed(12345)
+        k_new = [torch.randn((w.batch, w.n_kv_heads, w.head_dim), generator=gen, device=dev).to(torch.bfloat16) for _ in range(w.n_layers)]
+        v_new = [torch.randn((w.batch, w.n_kv_heads, w.head_dim), generator=gen, device=dev).to(torch.bfloat16) for _ in range(w.n_layers)]
+        if lens is not None:        # lengths before the append: one row fewer, so that the step attends to `lens` rows
+            paged = binding.PagedCache(paged.block_table, paged.page_size, w.ctx_len, torch.from_numpy(lens - 1).to(dev))
+        run, outs, idx_buf = ctx.prepare_step_append(policy, qs, k_new, v_new, Ks, Vs, k_sel, paged=paged)
     else:
         run, outs, idx_buf = ctx.prepare_step(policy, qs, Ks, Vs, k_sel, block=args.block, paged=paged)
 
@@ -196,7 +210,7 @@ def main():
     # would be overwritten unread (a Full layer directly followed by another).  Same outputs;
     # the step with every TopK is timed beside it.
     ms_every = None
-    plain = not (args.offload or args.graph)
+    plain = not (args.offload or args.graph or args.append)
     if plain:
         ctx_every = binding.Context(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ctx_len, w.top_k,
                                     topk_every_full_layer=True)
@@ -336,6 +350,7 @@ def main():
                    "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv, "head_dim": d, "ctx_len": N,
                    "top_k": k, "block": args.block or 1, "page_size": args.paged or None,
                    "seq_lens": lens.tolist() if lens is not None else None, "hip_graph": bool(args.graph),
+                   "append": bool(args.append),
                    "kv_dtype": "bf16", "accumulate": "f32"},
         "ms_per_step_topk_at_every_full_layer": round(ms_every, 4) if ms_every else None,
         "parity_checked": parity is not None,

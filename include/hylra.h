@@ -294,6 +294,19 @@ hylra_status hylra_decode_step_blocks_paged(hylra_ctx *ctx, const hylra_shape *s
  * s slots up to s layers are prefetched ahead.  The streams may be the same (no
  * overlap then).  On return both streams have the work enqueued; results are
  * complete when compute_stream has drained.  n_layers <= 256.
+ *
+ * Block granularity and paged caches (the paper prefetches "only the critical KV blocks"):
+ * hylra_gather_blocks and hylra_decode_step_offloaded_blocks are the two calls above for the
+ * block-level variant (block rows per block, kb blocks per (batch, KV head); block = 1 is the
+ * token level) and for any cache layout (cache as in the *_paged calls: paged pools and / or
+ * per-sequence lengths; NULL = contiguous through shape's strides).  Slot t * block + r of the
+ * compact cache receives row bidx[b,g,t] * block + r of sequence b, or zeros and index entry -1
+ * where that is no row of the sequence (padding entry, block number out of range, row at or
+ * past the sequence's length); K_dst / V_dst are [B, Hkv, kb * block, d], idx_dst
+ * [B, Hkv, kb * block].  In the step, whole blocks (block * head_dim * 2 bytes of K and of V,
+ * contiguous in the source unless a block straddles pages) cross the slow link; the block
+ * table and the lengths are DEVICE arrays as always, only the Reuse layers' pools are in slow
+ * memory.  A slot holds hylra_offload_slot_bytes(shape, kb * block) bytes; kb * block <= max_k.
  */
 size_t hylra_offload_slot_bytes(const hylra_shape *shape, int32_t k);
 hylra_status hylra_gather_rows(hylra_ctx *ctx, const hylra_shape *shape, const void *K_src,
@@ -305,6 +318,53 @@ hylra_status hylra_decode_step_offloaded(hylra_ctx *ctx, const hylra_shape *shap
                                          float *const *out_l, int32_t *idx_buf, void *staging,
                                          size_t staging_bytes, void *compute_stream,
                                          void *copy_stream);
+
+hylra_status hylra_gather_blocks(hylra_ctx *ctx, const hylra_shape *shape, const hylra_paged *cache,
+                                 const void *K_src, const void *V_src, const int32_t *bidx,
+                                 int32_t block, int32_t kb, void *K_dst, void *V_dst,
+                                 int32_t *idx_dst, void *hip_stream);
+hylra_status hylra_decode_step_offloaded_blocks(hylra_ctx *ctx, const hylra_shape *shape,
+                                                const hylra_paged *cache, int32_t n_layers,
+                                                const uint8_t *policy, const void *const *q_l,
+                                                const void *const *K_l, const void *const *V_l,
+                                                int32_t block, int32_t kb, float *const *out_l,
+                                                int32_t *bidx_buf, void *staging, size_t staging_bytes,
+                                                void *compute_stream, void *copy_stream);
+
+/*
+ * Append, then attend: Algorithm 2 takes K^cache and V^cache with the current token already
+ * in them.  These calls first write the token's key and value, k_new / v_new (DEVICE, bf16
+ * [B, Hkv, d] contiguous, 16-byte aligned), into the cache and then run the attention of the
+ * same name over the cache including that row, as one launch sequence on the stream.
+ *   cache == NULL, or cache->seq_lens == NULL: every sequence has ctx_len - 1 rows before the
+ *     call; the token becomes row ctx_len - 1 and the attention covers ctx_len rows.
+ *   cache->seq_lens given: seq_lens[b] = n_b is the length BEFORE the call (clamped to
+ *     0 .. ctx_len - 1); the token becomes row n_b of sequence b -- through block_table[b] if
+ *     the cache is paged, whose page for that row the caller has allocated -- and sequence b
+ *     attends to and ranks n_b + 1 rows.  seq_lens itself is not written; the caller advances
+ *     its lengths after the step.
+ * K, V (pools if paged) are written: one row of each per (batch, KV head).  Everything else --
+ * arguments, selection rule, padding of short sequences, errors -- is as in
+ * hylra_full_attn_topk_paged / hylra_reuse_sparse_attn_paged / hylra_decode_step_paged.  In
+ * hylra_decode_step_append every layer l gets its own k_new_l[l], v_new_l[l] (HOST arrays of
+ * DEVICE pointers) written into its own cache before the layer's attention.  A Reuse layer
+ * attends to the inherited set as it is (the new row takes part if the set names it).
+ */
+hylra_status hylra_append_full_attn_topk(hylra_ctx *ctx, const hylra_shape *shape,
+                                         const hylra_paged *cache, const void *q,
+                                         const void *k_new, const void *v_new, void *K, void *V,
+                                         int32_t k, float *out, int32_t *idx, void *hip_stream);
+hylra_status hylra_append_reuse_sparse_attn(hylra_ctx *ctx, const hylra_shape *shape,
+                                            const hylra_paged *cache, const void *q,
+                                            const void *k_new, const void *v_new, void *K, void *V,
+                                            const int32_t *idx, int32_t k, float *out,
+                                            void *hip_stream);
+hylra_status hylra_decode_step_append(hylra_ctx *ctx, const hylra_shape *shape,
+                                      const hylra_paged *cache, int32_t n_layers,
+                                      const uint8_t *policy, const void *const *q_l,
+                                      const void *const *k_new_l, const void *const *v_new_l,
+                                      void *const *K_l, void *const *V_l, int32_t k,
+                                      float *const *out_l, int32_t *idx_buf, void *hip_stream);
 
 /*
  * Offline profiling: from the index sets of an all-Full run to the layer policy

@@ -28,6 +28,8 @@ EXPORTS = (
     "hylra_full_attn_topk_blocks_paged", "hylra_reuse_block_attn_paged", "hylra_decode_step_blocks_paged",
     "hylra_overlap_counts", "hylra_similarity_matrix", "hylra_policy_search",
     "hylra_offload_slot_bytes", "hylra_gather_rows", "hylra_decode_step_offloaded",
+    "hylra_gather_blocks", "hylra_decode_step_offloaded_blocks",
+    "hylra_append_full_attn_topk", "hylra_append_reuse_sparse_attn", "hylra_decode_step_append",
     "hylra_set_option", "hylra_profile_enable", "hylra_profile_reset", "hylra_profile_read",
     "hylra_probe_copy", "hylra_probe_read", "hylra_probe_gather",
 )
@@ -94,6 +96,12 @@ def load_library() -> ctypes.CDLL:
     lib.hylra_offload_slot_bytes.argtypes = [sp, i32]
     lib.hylra_gather_rows.argtypes = [vp, sp, vp, vp, vp, i32, vp, vp, vp, vp]
     lib.hylra_decode_step_offloaded.argtypes = [vp, sp, i32, vp, vp, vp, vp, i32, vp, vp, vp, ctypes.c_size_t, vp, vp]
+    lib.hylra_gather_blocks.argtypes = [vp, sp, pp, vp, vp, vp, i32, i32, vp, vp, vp, vp]
+    lib.hylra_decode_step_offloaded_blocks.argtypes = [vp, sp, pp, i32, vp, vp, vp, vp, i32, i32, vp, vp, vp,
+                                                       ctypes.c_size_t, vp, vp]
+    lib.hylra_append_full_attn_topk.argtypes = [vp, sp, pp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
+    lib.hylra_append_reuse_sparse_attn.argtypes = [vp, sp, pp, vp, vp, vp, vp, vp, vp, i32, vp, vp]
+    lib.hylra_decode_step_append.argtypes = [vp, sp, pp, i32, vp, vp, vp, vp, vp, vp, i32, vp, vp, vp]
     lib.hylra_overlap_counts.argtypes = [vp, i32, vp, i32, i32, i32, i32, vp, vp]
     lib.hylra_similarity_matrix.argtypes = [i32, vp, vp]
     lib.hylra_policy_search.argtypes = [vp, i32, vp, ctypes.c_double, vp, ctypes.POINTER(i32),
@@ -378,17 +386,112 @@ class Context:
         self._check(rc, "hylra_gather_rows")
         return Kd, Vd, idd
 
-    def prepare_step_offloaded(self, policy: Sequence[int], q_l, K_l, V_l, k: int, n_slots: int = 2,
-                               copy_stream: Optional[torch.cuda.Stream] = None, scale: float = 0.0):
-        """hylra_decode_step_offloaded: K_l[l] / V_l[l] of Reuse layers may be pinned host tensors.
-        Returns (run, outs, idx_buf, copy_stream); run() enqueues one step on the current stream
-        (attention) and the copy stream (gathers)."""
+    def gather_blocks(self, K_src, V_src, bidx, block: int, paged: Optional[PagedCache] = None, n_q_heads=None):
+        """hylra_gather_blocks: K_src / V_src a contiguous cache [B,Hkv,N,d] or (with a paged
+        ``paged``) pools, in device or pinned host memory; returns (K_dst, V_dst bf16
+        [B,Hkv,kb*block,d], idx_dst int32 [B,Hkv,kb*block]) on the GPU."""
+        dev = bidx.device
+        if not (K_src.is_cuda or K_src.is_pinned()) or not (V_src.is_cuda or V_src.is_pinned()):
+            raise TypeError("the source caches must be in device or pinned host memory")
+        B, Hkv, kb = bidx.shape
+        d = K_src.shape[3]
+        qlike = torch.empty((B, Hkv, d), dtype=torch.bfloat16, device="meta")
+        if paged is not None:
+            shp, pg = paged.describe(qlike, K_src)
+            pgp = ctypes.byref(pg)
+        else:
+            shp, pgp = make_shape(qlike, K_src), None
+        rows = kb * block
+        Kd = torch.empty((B, Hkv, rows, d), dtype=torch.bfloat16, device=dev)
+        Vd = torch.empty_like(Kd)
+        idd = torch.empty((B, Hkv, rows), dtype=torch.int32, device=dev)
+        rc = self._lib.hylra_gather_blocks(self._h, ctypes.byref(shp), pgp, K_src.data_ptr(), V_src.data_ptr(),
+                                           bidx.data_ptr(), block, kb, Kd.data_ptr(), Vd.data_ptr(), idd.data_ptr(),
+                                           _stream_ptr(dev))
+        self._check(rc, "hylra_gather_blocks")
+        return Kd, Vd, idd
+
+    # -- append the current token, then attend -------------------------------------------------
+    def append_full_attn_topk(self, q, k_new, v_new, K, V, k: int, paged: Optional[PagedCache] = None,
+                              out=None, idx=None, scale: float = 0.0):
+        """hylra_append_full_attn_topk: K / V (pools if paged) receive the new rows; returns (out, idx)."""
+        self._check_inputs(q, K, V)
+        shp, pgp, keep = self._describe(q, K, paged, scale)
+        if out is None:
+            out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+        if idx is None:
+            idx = torch.empty((shp.batch, shp.n_kv_heads, k), dtype=torch.int32, device=q.device)
+        rc = self._lib.hylra_append_full_attn_topk(self._h, ctypes.byref(shp), pgp, q.data_ptr(), k_new.data_ptr(),
+                                                   v_new.data_ptr(), K.data_ptr(), V.data_ptr(), k, out.data_ptr(),
+                                                   idx.data_ptr(), _stream_ptr(q.device))
+        self._check(rc, "hylra_append_full_attn_topk")
+        return out, idx
+
+    def append_reuse_sparse_attn(self, q, k_new, v_new, K, V, idx, paged: Optional[PagedCache] = None,
+                                 out=None, scale: float = 0.0):
+        """hylra_append_reuse_sparse_attn: returns out."""
+        self._check_inputs(q, K, V)
+        shp, pgp, keep = self._describe(q, K, paged, scale)
+        if out is None:
+            out = torch.empty(q.shape, dtype=torch.float32, device=q.device)
+        rc = self._lib.hylra_append_reuse_sparse_attn(self._h, ctypes.byref(shp), pgp, q.data_ptr(), k_new.data_ptr(),
+                                                      v_new.data_ptr(), K.data_ptr(), V.data_ptr(), idx.data_ptr(),
+                                                      idx.shape[2], out.data_ptr(), _stream_ptr(q.device))
+        self._check(rc, "hylra_append_reuse_sparse_attn")
+        return out
+
+    @staticmethod
+    def _describe(q, K, paged, scale):
+        if paged is None:
+            return make_shape(q, K, scale), None, None
+        shp, pg = paged.describe(q, K, scale)
+        return shp, ctypes.byref(pg), pg
+
+    def decode_step_append(self, policy: Sequence[int], q_l, k_new_l, v_new_l, K_l, V_l, k: int,
+                           paged: Optional[PagedCache] = None, scale: float = 0.0):
+        """hylra_decode_step_append: returns (outs, idx_buf)."""
+        run, outs, idx_buf = self.prepare_step_append(policy, q_l, k_new_l, v_new_l, K_l, V_l, k, paged, scale)
+        run()
+        return outs, idx_buf
+
+    def prepare_step_append(self, policy: Sequence[int], q_l, k_new_l, v_new_l, K_l, V_l, k: int,
+                            paged: Optional[PagedCache] = None, scale: float = 0.0):
+        """Marshals hylra_decode_step_append once; returns (run, outs, idx_buf)."""
         L = len(policy)
         dev = q_l[0].device
-        shp = make_shape(q_l[0], K_l[0], scale)
         for l in range(L):
-            o = make_shape(q_l[l], K_l[l], scale)
-            if bytes(o) != bytes(shp) or V_l[l].stride() != K_l[l].stride():
+            self._check_inputs(q_l[l], K_l[l], V_l[l])
+        shp, pgp, keep = self._describe(q_l[0], K_l[0], paged, scale)
+        outs = [torch.empty(q_l[l].shape, dtype=torch.float32, device=dev) for l in range(L)]
+        idx_buf = torch.empty((shp.batch, shp.n_kv_heads, k), dtype=torch.int32, device=dev)
+        arr = ctypes.c_void_p * L
+        pol = (ctypes.c_uint8 * L)(*[int(p) for p in policy])
+        ptrs = [arr(*[t.data_ptr() for t in ts]) for ts in (q_l, k_new_l, v_new_l, K_l, V_l, outs)]
+        held = (q_l, k_new_l, v_new_l, K_l, V_l, paged, keep)
+
+        def run():
+            rc = self._lib.hylra_decode_step_append(self._h, ctypes.byref(shp), pgp, L, pol, ptrs[0], ptrs[1], ptrs[2],
+                                                    ptrs[3], ptrs[4], k, ptrs[5], idx_buf.data_ptr(), _stream_ptr(dev))
+            self._check(rc, "hylra_decode_step_append")
+            return held is not None
+
+        return run, outs, idx_buf
+
+    def prepare_step_offloaded(self, policy: Sequence[int], q_l, K_l, V_l, k: int, n_slots: int = 2,
+                               copy_stream: Optional[torch.cuda.Stream] = None, scale: float = 0.0,
+                               block: int = 0, paged: Optional[PagedCache] = None):
+        """hylra_decode_step_offloaded (hylra_decode_step_offloaded_blocks with block > 0 or a
+        paged cache; k then counts blocks): K_l[l] / V_l[l] of Reuse layers may be pinned host
+        tensors.  Returns (run, outs, idx_buf, copy_stream); run() enqueues one step on the
+        current stream (attention) and the copy stream (gathers)."""
+        L = len(policy)
+        dev = q_l[0].device
+        general = block > 0 or paged is not None
+        blk = block if block > 0 else 1
+        shp, pgp, keep_pg = self._describe(q_l[0], K_l[0], paged, scale)
+        for l in range(L):
+            o, _, og = self._describe(q_l[l], K_l[l], paged, scale)
+            if bytes(o) != bytes(shp) or V_l[l].stride() != K_l[l].stride() or (og is not None and bytes(og) != bytes(keep_pg)):
                 raise ValueError("all layers must share one shape and stride set")
             if policy[l] == FULL and not K_l[l].is_cuda:
                 raise TypeError("the caches of Full layers must be in device memory")
@@ -396,7 +499,7 @@ class Context:
                 raise TypeError("offloaded caches must be in pinned host memory")
         outs = [torch.empty(q_l[l].shape, dtype=torch.float32, device=dev) for l in range(L)]
         idx_buf = torch.empty((shp.batch, shp.n_kv_heads, k), dtype=torch.int32, device=dev)
-        slot = self._lib.hylra_offload_slot_bytes(ctypes.byref(shp), k)
+        slot = self._lib.hylra_offload_slot_bytes(ctypes.byref(shp), k * blk)
         staging = torch.empty(slot * n_slots + 256, dtype=torch.uint8, device=dev)
         base = (staging.data_ptr() + 255) // 256 * 256
         if copy_stream is None:
@@ -405,13 +508,19 @@ class Context:
         pol = (ctypes.c_uint8 * L)(*[int(p) for p in policy])
         qa, Ka, Va = (arr(*[t.data_ptr() for t in ts]) for ts in (q_l, K_l, V_l))
         oa = arr(*[t.data_ptr() for t in outs])
-        keep = (q_l, K_l, V_l, staging)
+        keep = (q_l, K_l, V_l, staging, paged, keep_pg)
 
         def run():
-            rc = self._lib.hylra_decode_step_offloaded(self._h, ctypes.byref(shp), L, pol, qa, Ka, Va, k, oa,
-                                                       idx_buf.data_ptr(), base, slot * n_slots,
-                                                       _stream_ptr(dev), copy_stream.cuda_stream)
-            self._check(rc, "hylra_decode_step_offloaded")
+            if general:
+                rc = self._lib.hylra_decode_step_offloaded_blocks(self._h, ctypes.byref(shp), pgp, L, pol, qa, Ka, Va,
+                                                                  blk, k, oa, idx_buf.data_ptr(), base, slot * n_slots,
+                                                                  _stream_ptr(dev), copy_stream.cuda_stream)
+                self._check(rc, "hylra_decode_step_offloaded_blocks")
+            else:
+                rc = self._lib.hylra_decode_step_offloaded(self._h, ctypes.byref(shp), L, pol, qa, Ka, Va, k, oa,
+                                                           idx_buf.data_ptr(), base, slot * n_slots,
+                                                           _stream_ptr(dev), copy_stream.cuda_stream)
+                self._check(rc, "hylra_decode_step_offloaded")
             return keep is not None
 
         return run, outs, idx_buf, copy_stream

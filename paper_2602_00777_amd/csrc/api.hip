@@ -94,6 +94,7 @@ struct hylra_ctx {
     int* counters = nullptr;    // one arrival counter per (batch, KV head), zero between launches
     int* chunk_ctr = nullptr;   // chunk counters of the self-scheduling Full kernel (kCtrStride ints apart)
     int* sel_ws = nullptr;      // selection scratch: histogram, candidates, counts (see SelectParams)
+    int32_t* lens_plus = nullptr;   // [max batch] sequence lengths after an append (see append_impl)
     int4* wg_map = nullptr;     // deal of the Full kernel's workgroups to sequences of different lengths
     int2* pair_map = nullptr;   // (see RaggedPlanParams): `slots` and `pairs_cap` entries
     int n_cus = 0;              // compute units of the device
@@ -557,6 +558,7 @@ hylra_status hylra_create_ex(hylra_ctx** out, const hylra_shape* max_shape, int3
     if (e == hipSuccess) e = hipMemset(ctx->chunk_ctr, 0, ctx->slots * kCtrStride * sizeof(int));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->wg_map, ctx->slots * sizeof(int4));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->pair_map, pairs * sizeof(int2));
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->lens_plus, (size_t)max_shape->batch * sizeof(int32_t));
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         fail(nullptr, HYLRA_ERR_HIP, "workspace allocation failed: %s", hipGetErrorString(e));
@@ -590,6 +592,7 @@ hylra_status hylra_destroy(hylra_ctx* ctx) {
     if (ctx->sel_ws) (void)hipFree(ctx->sel_ws);
     if (ctx->wg_map) (void)hipFree(ctx->wg_map);
     if (ctx->pair_map) (void)hipFree(ctx->pair_map);
+    if (ctx->lens_plus) (void)hipFree(ctx->lens_plus);
     delete ctx;
     return HYLRA_OK;
 }
@@ -619,6 +622,10 @@ hylra_status hylra_set_option(hylra_ctx* ctx, const char* name, int32_t value) {
 }  // extern "C"
 
 namespace {
+
+hylra_status append_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* pg, const void* k_new,
+                         const void* v_new, const void* K, const void* V, hylra_paged& eff, const hylra_paged** use,
+                         void* hip_stream);
 
 // Full layer.  block == 1: idx receives the k best rows.  block >= 2: idx receives the k best
 // blocks of `block` rows (a block scores the maximum of its rows).
@@ -830,7 +837,8 @@ hylra_status reuse_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pa
 hylra_status step_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* pg, int32_t n_layers,
                        const uint8_t* policy, const void* const* q_l, const void* const* K_l,
                        const void* const* V_l, int32_t block, int32_t k, float* const* out_l,
-                       int32_t* idx_buf, void* hip_stream) {
+                       int32_t* idx_buf, void* hip_stream, const void* const* k_new_l = nullptr,
+                       const void* const* v_new_l = nullptr) {
     if (!ctx) return HYLRA_ERR_BAD_ARG;
     if (n_layers < 1 || !policy || !q_l || !K_l || !V_l || !out_l || !idx_buf)
         return fail(ctx, HYLRA_ERR_BAD_ARG, "n_layers < 1 or a NULL argument");
@@ -839,7 +847,7 @@ hylra_status step_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
     for (int l = 0; l < n_layers; ++l) {
         if (policy[l] != HYLRA_FULL && policy[l] != HYLRA_REUSE)
             return fail(ctx, HYLRA_ERR_POLICY, "policy[%d] = %d is neither Full (0) nor Reuse (1)", l, policy[l]);
-        if (!q_l[l] || !K_l[l] || !V_l[l] || !out_l[l])
+        if (!q_l[l] || !K_l[l] || !V_l[l] || !out_l[l] || (k_new_l && (!k_new_l[l] || !v_new_l[l])))
             return fail(ctx, HYLRA_ERR_BAD_ARG, "layer %d has a NULL tensor pointer", l);
     }
     // Layers run in order on one stream: a layer's query depends on the previous layer's
@@ -852,9 +860,15 @@ hylra_status step_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
     for (int l = 0; l < n_layers && rc == HYLRA_OK; ++l) {
         const bool want_idx = l + 1 == n_layers || policy[l + 1] == HYLRA_REUSE ||
                               (ctx->flags & HYLRA_FLAG_TOPK_EVERY_FULL_LAYER);
+        // with new rows: the layer's cache first receives the current token (every layer writes the
+        // same "length + 1" array, so the deal of workgroups made at the first layer stays valid)
+        hylra_paged eff{};
+        const hylra_paged* use = pg;
+        if (k_new_l && (rc = append_impl(ctx, shape, pg, k_new_l[l], v_new_l[l], K_l[l], V_l[l], eff, &use, hip_stream)) != HYLRA_OK)
+            break;
         rc = policy[l] == HYLRA_FULL
-                 ? full_impl(ctx, shape, pg, q_l[l], K_l[l], V_l[l], block, k, out_l[l], idx_buf, hip_stream, want_idx)
-                 : reuse_impl(ctx, shape, pg, q_l[l], K_l[l], V_l[l], idx_buf, block, k, out_l[l], hip_stream);
+                 ? full_impl(ctx, shape, use, q_l[l], K_l[l], V_l[l], block, k, out_l[l], idx_buf, hip_stream, want_idx)
+                 : reuse_impl(ctx, shape, use, q_l[l], K_l[l], V_l[l], idx_buf, block, k, out_l[l], hip_stream);
     }
     ctx->in_step = false;
     return rc;
@@ -1012,28 +1026,74 @@ Slot slot_at(void* staging, const hylra_shape* shape, int32_t k, int i) {
     return Slot{base, base + kv, (int32_t*)(base + 2 * kv)};
 }
 
-hylra_status gather_impl(hylra_ctx* ctx, const hylra_shape* shape, const void* K_src, const void* V_src,
-                         const int32_t* idx, int32_t k, void* K_dst, void* V_dst, int32_t* idx_dst,
-                         void* hip_stream) {
+// Selected rows (block == 1) or blocks of a cache the device can read into a compact cache of
+// n_idx * block rows per (batch, KV head); pg as in the attention calls (nullptr: contiguous).
+hylra_status gather_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* pg, const void* K_src,
+                         const void* V_src, const int32_t* idx, int32_t block, int32_t n_idx, void* K_dst,
+                         void* V_dst, int32_t* idx_dst, void* hip_stream) {
     int G = 0;
     Strides sd{};
     float scale = 0.f;
+    RowMap map{};
     hylra_status rc = check_shape(ctx, shape, G, sd, scale);
     if (rc != HYLRA_OK) return rc;
+    if ((rc = check_paged(ctx, shape, pg, sd, map)) != HYLRA_OK) return rc;
     if (!K_src || !V_src || !idx || !K_dst || !V_dst || !idx_dst)
         return fail(ctx, HYLRA_ERR_BAD_ARG, "a NULL argument");
     if ((((uintptr_t)K_src | (uintptr_t)V_src | (uintptr_t)K_dst | (uintptr_t)V_dst) & 15) ||
         (((uintptr_t)idx | (uintptr_t)idx_dst) & 3))
         return fail(ctx, HYLRA_ERR_BAD_ARG, "caches must be 16-byte aligned, index sets 4-byte aligned");
-    if (k < 1) return fail(ctx, HYLRA_ERR_BAD_ARG, "k = %d must be >= 1", k);
+    if (block < 1 || block > kMaxBlock) return fail(ctx, HYLRA_ERR_BAD_ARG, "block = %d is outside 1..%d", block, kMaxBlock);
+    if (n_idx < 1 || (int64_t)n_idx * block > kMaxCtx) return fail(ctx, HYLRA_ERR_BAD_ARG, "k = %d (x block %d) must be in 1..%d", n_idx, block, kMaxCtx);
     GatherParams gp{};
     gp.K = (const uint16_t*)K_src, gp.V = (const uint16_t*)V_src;
     gp.sb = sd.b, gp.sh = sd.h, gp.sn = sd.n;
-    gp.Hkv = shape->n_kv_heads, gp.D = shape->head_dim, gp.N = shape->ctx_len, gp.k = k;
+    gp.map = map;
+    gp.Hkv = shape->n_kv_heads, gp.D = shape->head_dim, gp.N = shape->ctx_len, gp.k = n_idx * block;
     gp.idx = idx;
+    gp.idx_stride = n_idx, gp.block = block;
+    gp.block_magic = block > 1 ? (uint32_t)((0x100000000ull + (uint32_t)block - 1) / (uint32_t)block) : 0u;
+    gp.n_blocks = (int)ceil_div(shape->ctx_len, block);
     gp.K_dst = (uint16_t*)K_dst, gp.V_dst = (uint16_t*)V_dst, gp.idx_dst = idx_dst;
     DeviceGuard guard(ctx->device);
     HIP_TRY(ctx, launch_timed(ctx, 3, (hipStream_t)hip_stream, [&] { return launch_gather_rows(gp, shape->batch, (hipStream_t)hip_stream); }));
+    return HYLRA_OK;
+}
+
+// The current token's key / value rows into the cache, behind the rows every sequence has.
+// Fills eff (and sets *use) with the cache description the attention that follows must use:
+// the caller's, with the lengths replaced by the context's own "length + 1" array.
+hylra_status append_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* pg, const void* k_new,
+                         const void* v_new, const void* K, const void* V, hylra_paged& eff, const hylra_paged** use,
+                         void* hip_stream) {
+    int G = 0;
+    Strides sd{};
+    float scale = 0.f;
+    RowMap map{};
+    hylra_status rc = check_shape(ctx, shape, G, sd, scale);
+    if (rc != HYLRA_OK) return rc;
+    if ((rc = check_paged(ctx, shape, pg, sd, map)) != HYLRA_OK) return rc;
+    if (!k_new || !v_new || !K || !V) return fail(ctx, HYLRA_ERR_BAD_ARG, "k_new, v_new, K and V must not be NULL");
+    if (((uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)K | (uintptr_t)V) & 15)
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "k_new, v_new, K and V must be 16-byte aligned");
+    if (shape->batch > ctx->max_shape.batch)
+        return fail(ctx, HYLRA_ERR_WORKSPACE, "batch = %d exceeds the context's %d", shape->batch, ctx->max_shape.batch);
+    AppendParams ap{};
+    ap.k_new = (const uint16_t*)k_new, ap.v_new = (const uint16_t*)v_new;
+    ap.K = (uint16_t*)K, ap.V = (uint16_t*)V;
+    ap.sb = sd.b, ap.sh = sd.h, ap.sn = sd.n;
+    ap.map = map;
+    ap.Hkv = shape->n_kv_heads, ap.D = shape->head_dim, ap.N = shape->ctx_len;
+    ap.lens_out = map.seq_lens ? ctx->lens_plus : nullptr;
+    DeviceGuard guard(ctx->device);
+    HIP_TRY(ctx, close_bracket(ctx));                    // (belongs to no profiling class)
+    HIP_TRY(ctx, launch_append_rows(ap, shape->batch, (hipStream_t)hip_stream));
+    *use = pg;
+    if (pg && pg->seq_lens) {
+        eff = *pg;
+        eff.seq_lens = ctx->lens_plus;
+        *use = &eff;
+    }
     return HYLRA_OK;
 }
 }  // namespace
@@ -1042,14 +1102,57 @@ hylra_status hylra_gather_rows(hylra_ctx* ctx, const hylra_shape* shape, const v
                                const int32_t* idx, int32_t k, void* K_dst, void* V_dst, int32_t* idx_dst,
                                void* hip_stream) {
     if (!ctx) return HYLRA_ERR_BAD_ARG;
-    return gather_impl(ctx, shape, K_src, V_src, idx, k, K_dst, V_dst, idx_dst, hip_stream);
+    return gather_impl(ctx, shape, nullptr, K_src, V_src, idx, 1, k, K_dst, V_dst, idx_dst, hip_stream);
 }
 
-hylra_status hylra_decode_step_offloaded(hylra_ctx* ctx, const hylra_shape* shape, int32_t n_layers,
-                                         const uint8_t* policy, const void* const* q_l, const void* const* K_l,
-                                         const void* const* V_l, int32_t k, float* const* out_l, int32_t* idx_buf,
-                                         void* staging, size_t staging_bytes, void* compute_stream,
-                                         void* copy_stream) {
+hylra_status hylra_gather_blocks(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* cache,
+                                 const void* K_src, const void* V_src, const int32_t* bidx, int32_t block,
+                                 int32_t kb, void* K_dst, void* V_dst, int32_t* idx_dst, void* hip_stream) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    return gather_impl(ctx, shape, cache, K_src, V_src, bidx, block, kb, K_dst, V_dst, idx_dst, hip_stream);
+}
+
+hylra_status hylra_append_full_attn_topk(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* cache,
+                                         const void* q, const void* k_new, const void* v_new, void* K, void* V,
+                                         int32_t k, float* out, int32_t* idx, void* hip_stream) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    hylra_paged eff{};
+    const hylra_paged* use = nullptr;
+    const hylra_status rc = append_impl(ctx, shape, cache, k_new, v_new, K, V, eff, &use, hip_stream);
+    if (rc != HYLRA_OK) return rc;
+    return full_impl(ctx, shape, use, q, K, V, 1, k, out, idx, hip_stream);
+}
+
+hylra_status hylra_append_reuse_sparse_attn(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* cache,
+                                            const void* q, const void* k_new, const void* v_new, void* K, void* V,
+                                            const int32_t* idx, int32_t k, float* out, void* hip_stream) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    hylra_paged eff{};
+    const hylra_paged* use = nullptr;
+    const hylra_status rc = append_impl(ctx, shape, cache, k_new, v_new, K, V, eff, &use, hip_stream);
+    if (rc != HYLRA_OK) return rc;
+    return reuse_impl(ctx, shape, use, q, K, V, idx, 1, k, out, hip_stream);
+}
+
+hylra_status hylra_decode_step_append(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* cache,
+                                      int32_t n_layers, const uint8_t* policy, const void* const* q_l,
+                                      const void* const* k_new_l, const void* const* v_new_l, void* const* K_l,
+                                      void* const* V_l, int32_t k, float* const* out_l, int32_t* idx_buf,
+                                      void* hip_stream) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    if (n_layers < 1 || !k_new_l || !v_new_l || !K_l || !V_l)
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "n_layers < 1 or a NULL argument");
+    return step_impl(ctx, shape, cache, n_layers, policy, q_l, (const void* const*)K_l, (const void* const*)V_l, 1, k,
+                     out_l, idx_buf, hip_stream, k_new_l, v_new_l);
+}
+
+namespace {
+// Algorithm 2 with the Reuse layers' caches in slow memory: their selected rows (block == 1) or
+// blocks are gathered ahead of time on the copy stream; pg as in the attention calls.
+hylra_status offloaded_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* pg, int32_t n_layers,
+                            const uint8_t* policy, const void* const* q_l, const void* const* K_l,
+                            const void* const* V_l, int32_t block, int32_t k, float* const* out_l, int32_t* idx_buf,
+                            void* staging, size_t staging_bytes, void* compute_stream, void* copy_stream) {
     if (!ctx) return HYLRA_ERR_BAD_ARG;
     if (n_layers < 1 || !policy || !q_l || !K_l || !V_l || !out_l || !idx_buf || !staging || !shape)
         return fail(ctx, HYLRA_ERR_BAD_ARG, "n_layers < 1 or a NULL argument");
@@ -1063,11 +1166,16 @@ hylra_status hylra_decode_step_offloaded(hylra_ctx* ctx, const hylra_shape* shap
             return fail(ctx, HYLRA_ERR_BAD_ARG, "layer %d has a NULL tensor pointer", l);
     }
     if ((uintptr_t)staging & 255) return fail(ctx, HYLRA_ERR_BAD_ARG, "staging must be 256-byte aligned");
-    const size_t slot_bytes = hylra_offload_slot_bytes(shape, k);
+    if (block < 1 || block > kMaxBlock) return fail(ctx, HYLRA_ERR_BAD_ARG, "block = %d is outside 1..%d", block, kMaxBlock);
+    if (k < 1 || (int64_t)k * block > ctx->max_k)
+        return fail(ctx, k < 1 ? HYLRA_ERR_BAD_ARG : HYLRA_ERR_WORKSPACE, "k = %d (x block %d) is outside 1..max_k = %d", k, block, ctx->max_k);
+    const int32_t rows = k * block;                     // rows of a compacted cache
+    const size_t slot_bytes = hylra_offload_slot_bytes(shape, rows);
     if (slot_bytes == 0 || staging_bytes < slot_bytes)
         return fail(ctx, HYLRA_ERR_WORKSPACE, "staging holds %zu bytes, one slot needs %zu", staging_bytes, slot_bytes);
     int n_slots = (int)(staging_bytes / slot_bytes < (size_t)kMaxOffloadLayers ? staging_bytes / slot_bytes : kMaxOffloadLayers);
-    if (k > shape->ctx_len) return fail(ctx, HYLRA_ERR_BAD_ARG, "k = %d exceeds ctx_len = %d", k, shape->ctx_len);
+    if ((int64_t)k > ceil_div(shape->ctx_len, block))
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "k = %d exceeds the %s of the cache", k, block == 1 ? "rows" : "blocks");
 
     DeviceGuard guard(ctx->device);
     if (!ctx->off_ev) {
@@ -1081,9 +1189,10 @@ hylra_status hylra_decode_step_offloaded(hylra_ctx* ctx, const hylra_shape* shap
     hipEvent_t* ev_consumed = ctx->off_ev + 1 + kMaxOffloadLayers;   // per slot
     hipStream_t cs = (hipStream_t)compute_stream, xs = (hipStream_t)copy_stream;
 
-    // the compacted cache of a Reuse layer: k rows per (batch, KV head), contiguous
+    // the compacted cache of a Reuse layer: `rows` rows per (batch, KV head), contiguous,
+    // every sequence the same (slots that hold no row are padding entries of its index set)
     hylra_shape compact = *shape;
-    compact.ctx_len = k;
+    compact.ctx_len = rows;
     compact.kv_stride_b = compact.kv_stride_h = compact.kv_stride_n = 0;
 
     std::vector<int> slot_of(n_layers, -1);
@@ -1094,8 +1203,8 @@ hylra_status hylra_decode_step_offloaded(hylra_ctx* ctx, const hylra_shape* shap
         const int s = next_slot;
         next_slot = (next_slot + 1) % n_slots;
         if (slot_used[s]) HIP_TRY(ctx, hipStreamWaitEvent(xs, ev_consumed[s], 0));
-        const Slot sl = slot_at(staging, shape, k, s);
-        hylra_status rc = gather_impl(ctx, shape, K_l[r], V_l[r], idx_buf, k, sl.K, sl.V, sl.idx, xs);
+        const Slot sl = slot_at(staging, shape, rows, s);
+        hylra_status rc = gather_impl(ctx, shape, pg, K_l[r], V_l[r], idx_buf, block, k, sl.K, sl.V, sl.idx, xs);
         if (rc != HYLRA_OK) return rc;
         HIP_TRY(ctx, hipEventRecord(ev_gathered[r], xs));
         slot_of[r] = s;
@@ -1108,7 +1217,7 @@ hylra_status hylra_decode_step_offloaded(hylra_ctx* ctx, const hylra_shape* shap
         if (policy[l] == HYLRA_FULL) {
             const bool want_idx = l + 1 == n_layers || policy[l + 1] == HYLRA_REUSE ||
                                   (ctx->flags & HYLRA_FLAG_TOPK_EVERY_FULL_LAYER);
-            hylra_status rc = full_impl(ctx, shape, nullptr, q_l[l], K_l[l], V_l[l], 1, k, out_l[l], idx_buf, cs, want_idx);
+            hylra_status rc = full_impl(ctx, shape, pg, q_l[l], K_l[l], V_l[l], block, k, out_l[l], idx_buf, cs, want_idx);
             if (rc != HYLRA_OK) return rc;
             run_end = l + 1;
             while (run_end < n_layers && policy[run_end] == HYLRA_REUSE) ++run_end;
@@ -1122,9 +1231,9 @@ hylra_status hylra_decode_step_offloaded(hylra_ctx* ctx, const hylra_shape* shap
             }
         } else {
             const int s = slot_of[l];
-            const Slot sl = slot_at(staging, shape, k, s);
+            const Slot sl = slot_at(staging, shape, rows, s);
             HIP_TRY(ctx, hipStreamWaitEvent(cs, ev_gathered[l], 0));
-            hylra_status rc = reuse_impl(ctx, &compact, nullptr, q_l[l], sl.K, sl.V, sl.idx, 1, k, out_l[l], cs);
+            hylra_status rc = reuse_impl(ctx, &compact, nullptr, q_l[l], sl.K, sl.V, sl.idx, 1, rows, out_l[l], cs);
             if (rc != HYLRA_OK) return rc;
             HIP_TRY(ctx, hipEventRecord(ev_consumed[s], cs));
             if (next_fetch < run_end) {
@@ -1134,6 +1243,25 @@ hylra_status hylra_decode_step_offloaded(hylra_ctx* ctx, const hylra_shape* shap
         }
     }
     return HYLRA_OK;
+}
+}  // namespace
+
+hylra_status hylra_decode_step_offloaded(hylra_ctx* ctx, const hylra_shape* shape, int32_t n_layers,
+                                         const uint8_t* policy, const void* const* q_l, const void* const* K_l,
+                                         const void* const* V_l, int32_t k, float* const* out_l, int32_t* idx_buf,
+                                         void* staging, size_t staging_bytes, void* compute_stream,
+                                         void* copy_stream) {
+    return offloaded_impl(ctx, shape, nullptr, n_layers, policy, q_l, K_l, V_l, 1, k, out_l, idx_buf, staging,
+                          staging_bytes, compute_stream, copy_stream);
+}
+
+hylra_status hylra_decode_step_offloaded_blocks(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* cache,
+                                                int32_t n_layers, const uint8_t* policy, const void* const* q_l,
+                                                const void* const* K_l, const void* const* V_l, int32_t block,
+                                                int32_t kb, float* const* out_l, int32_t* bidx_buf, void* staging,
+                                                size_t staging_bytes, void* compute_stream, void* copy_stream) {
+    return offloaded_impl(ctx, shape, cache, n_layers, policy, q_l, K_l, V_l, block, kb, out_l, bidx_buf, staging,
+                          staging_bytes, compute_stream, copy_stream);
 }
 
 hylra_status hylra_overlap_counts(hylra_ctx* ctx, int32_t n_layers, const int32_t* const* idx_l, int32_t batch,

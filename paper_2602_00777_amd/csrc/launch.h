@@ -167,15 +167,32 @@ struct OverlapParams {
 
 // Index-guided prefetch (offload.hip): selected rows of a (slow) cache into compact buffers.
 struct GatherParams {
-    const uint16_t* K;              // source cache, addressed through sb / sh / sn (elements)
-    const uint16_t* V;
+    const uint16_t* K;              // source cache, addressed through sb / sh / sn (elements), or
+    const uint16_t* V;              // through the page table of `map`
     int64_t sb, sh, sn;
-    int Hkv, D, N, k;
-    const int32_t* idx;             // [B][Hkv][k]
+    RowMap map;                     // zero: contiguous cache, every sequence N rows
+    int Hkv, D, N, k;               // k = row slots per (batch, KV head) = idx_stride * block
+    const int32_t* idx;             // [B][Hkv][idx_stride]: rows (block == 1) or block numbers
+    int idx_stride, block;
+    uint32_t block_magic;           // ceil(2^32 / block)
+    int n_blocks;                   // ceil(N / block)
     uint16_t* K_dst;                // [B][Hkv][k][D]
     uint16_t* V_dst;
-    int32_t* idx_dst;               // [B][Hkv][k]: t, or -1 where idx holds padding
+    int32_t* idx_dst;               // [B][Hkv][k]: the slot's own number, or -1 where it holds no row
 };
+
+// Cache update before the attention of a decode step: one new row per (batch, KV head).
+struct AppendParams {
+    const uint16_t* k_new;          // [B][Hkv][D]
+    const uint16_t* v_new;
+    uint16_t* K;                    // cache (or pools), addressed like the attention kernels do
+    uint16_t* V;
+    int64_t sb, sh, sn;
+    RowMap map;                     // seq_lens: rows before the call (nullptr: N - 1 everywhere)
+    int Hkv, D, N;
+    int32_t* lens_out;              // [B] rows after the call, or nullptr
+};
+hipError_t launch_append_rows(const AppendParams& p, int B, hipStream_t st);
 
 struct CombineParams {
     const float* part_ml;

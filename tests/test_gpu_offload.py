@@ -80,6 +80,95 @@ def test_offloaded_step_equals_resident_step(n_slots):
             assert_out_close(outs[l].cpu().numpy(), ref_outs[l], "offloaded step layer %d vs oracle.decode_step" % l)
 
 
+@pytest.mark.parametrize("block,page,ragged,pinned", [(4, 0, False, True), (16, 16, True, True), (5, 8, True, False),
+                                                         (1, 16, True, True), (128, 0, True, True)])
+def test_gather_blocks_is_exact(block, page, ragged, pinned):
+    """Whole blocks out of a contiguous or paged source, with per-sequence lengths: bit-exact
+    against the oracle's plain definition, and attention over the compact cache equals the
+    oracle's block attention over the source."""
+    say("gather blocks block=%d page=%d ragged=%s pinned=%s" % (block, page, ragged, pinned))
+    B, Hkv, G, d, N = 3, 2, 4, 128, 1000
+    nblk = -(-N // block)
+    kb = min(40, nblk)
+    gen = torch.Generator().manual_seed(block * 100 + page)
+    q = torch.randn((B, Hkv * G, d), generator=gen).to(torch.bfloat16)
+    K = torch.randn((B, Hkv, N, d), generator=gen).to(torch.bfloat16)
+    V = torch.randn((B, Hkv, N, d), generator=gen).to(torch.bfloat16)
+    rng = np.random.RandomState(block)
+    bidx = np.stack([[np.sort(rng.permutation(nblk)[:kb]) for _ in range(Hkv)] for _ in range(B)]).astype(np.int32)
+    bidx[:, :, 2] = -1
+    bidx[:, :, 5] = nblk + 1
+    bidx[0, 0, -1] = nblk - 1                      # the (possibly short) last block
+    lens = np.array([N, 1, 611], np.int32) if ragged else None
+    want_K, want_V, want_i = oracle.gather_blocks(K, V, bidx, block, lens=lens)
+    lens_d = torch.from_numpy(lens).to(DEV) if ragged else None
+    if page:
+        table = synth.page_table(B, N, page, 7)
+        Ks, Vs = synth.to_pool(K, table, page), synth.to_pool(V, table, page)
+        cache = binding.PagedCache(torch.from_numpy(table).to(DEV), page, N, lens_d)
+    else:
+        Ks, Vs = K, V
+        cache = binding.PagedCache(None, 0, N, lens_d) if ragged else None
+    Ks, Vs = (Ks.pin_memory(), Vs.pin_memory()) if pinned else (Ks.to(DEV), Vs.to(DEV))
+    with binding.Context(B, Hkv * G, Hkv, d, N, min(N, kb * block)) as ctx:
+        Kd, Vd, idd = ctx.gather_blocks(Ks, Vs, torch.from_numpy(bidx).to(DEV), block, paged=cache)
+        torch.cuda.synchronize()
+        assert np.array_equal(bits(Kd), want_K) and np.array_equal(bits(Vd), want_V)
+        assert np.array_equal(idd.cpu().numpy(), want_i)
+        if kb * block <= N:
+            got = ctx.reuse_sparse_attn(q.to(DEV), Kd, Vd, idd).cpu().numpy()
+            for b in range(B):
+                n = N if lens is None else int(lens[b])
+                ref = oracle.reuse_block_attn(q[b:b + 1], K[b:b + 1, :, :n], V[b:b + 1, :, :n],
+                                              np.where(bidx[b:b + 1] * block >= n, -1, bidx[b:b + 1]), block)
+                assert_out_close(got[b:b + 1], ref, "attention over the compact cache b=%d" % b)
+
+
+@pytest.mark.parametrize("block,page,ragged", [(16, 0, False), (16, 16, True), (8, 32, True), (1, 16, True)])
+def test_offloaded_step_blocks_and_pages(block, page, ragged):
+    """The offloaded step at block granularity and on paged / ragged caches: bit-equal to the
+    resident step of the same layout, which tests/test_gpu_blocks.py and tests/test_gpu_paged.py
+    hold against the oracle; plus the oracle directly on the Reuse layers here."""
+    say("offloaded step block=%d page=%d ragged=%s" % (block, page, ragged))
+    B, Hkv, G, d, N, L = 2, 2, 4, 128, 2400, 6
+    kb = 320 // block
+    w = synth.Workload("off", L, Hkv * G, Hkv, d, B, N, kb * block, (0, 3), 0.02, 3.0, 0.8, seed=11)
+    policy, _, data = synth.make_workload(w, DEV)
+    qs = [x[0] for x in data]
+    lens = np.array([N, 1500], np.int32) if ragged else None
+    lens_d = torch.from_numpy(lens).to(DEV) if ragged else None
+    if page:
+        table = synth.page_table(B, N, page, 11)
+        Ks = [synth.to_pool(x[1], table, page) for x in data]
+        Vs = [synth.to_pool(x[2], table, page) for x in data]
+        cache = binding.PagedCache(torch.from_numpy(table).to(DEV), page, N, lens_d)
+    else:
+        Ks, Vs = [x[1] for x in data], [x[2] for x in data]
+        cache = binding.PagedCache(None, 0, N, lens_d) if ragged else None
+    Ko = [K if policy[l] == synth.FULL else K.cpu().pin_memory() for l, K in enumerate(Ks)]
+    Vo = [V if policy[l] == synth.FULL else V.cpu().pin_memory() for l, V in enumerate(Vs)]
+    with binding.Context(B, Hkv * G, Hkv, d, N, kb * block, deterministic=True) as ctx:
+        want, want_idx = ctx.decode_step(policy, qs, Ks, Vs, kb, block=block if block > 1 else 0, paged=cache)
+        torch.cuda.synchronize()
+        run, outs, idx_buf, _ = ctx.prepare_step_offloaded(policy, qs, Ko, Vo, kb, n_slots=2, block=block, paged=cache)
+        for rep in range(2):
+            for o in outs:
+                o.fill_(float("nan"))
+            run()
+            torch.cuda.synchronize()
+            for l in range(L):
+                assert torch.equal(outs[l], want[l]), "layer %d differs from the resident step (run %d)" % (l, rep)
+            assert torch.equal(idx_buf, want_idx)
+    # the oracle on the Reuse layers, with the set the GPU selected at layer 3 (the last Full layer)
+    bidx = idx_buf.cpu().numpy()
+    for l in (4, 5):
+        for b in range(B):
+            n = N if lens is None else int(lens[b])
+            ref = oracle.reuse_block_attn(qs[l][b:b + 1].cpu(), data[l][1][b:b + 1, :, :n].cpu(), data[l][2][b:b + 1, :, :n].cpu(),
+                                          bidx[b:b + 1], block)
+            assert_out_close(outs[l][b:b + 1].cpu().numpy(), ref, "offloaded layer %d b=%d vs oracle" % (l, b))
+
+
 def test_offloaded_step_errors():
     say("offloaded step errors")
     w = synth.scaled(synth.WORKLOADS["toy"], n_layers=2, ctx_len=600, top_k=64)
