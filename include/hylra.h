@@ -424,13 +424,15 @@ hylra_status hylra_policy_search(hylra_ctx *ctx, int32_t n_layers, const double 
  *   "reuse_waves"       waves per workgroup of the matrix-core Reuse kernel: 4 or 8
  *   "reuse_unfused"     1 = merge the Reuse partials in a second kernel instead of in the
  *                       last-arriving workgroup of the Reuse kernel
- *   "finalize_variant"  how the Full layer is finalised (merge of partials + top-k):
- *                       1 = one launch, one workgroup per (batch, KV head), scores held in
- *                       registers when they fit (default up to 32768 rows of context);
- *                       2 = as 1 but re-reading the scores in every pass;
- *                       3 = three launches with several workgroups per (batch, KV head)
- *                       (default beyond 32768 rows)
- *   "finalize_groups"   rows per workgroup of the three-launch finalise, in units of 4096: 2 or 8
+ *   "finalize_variant"  the Full layer's second kernel (merge of partials + top-k):
+ *                       1 = its workgroups re-read the scores outside their own chunk in every
+ *                       pass instead of keeping all of a (batch, KV head)'s scores in registers
+ *                       (the default up to 65536 rows of context keeps them)
+ *   "finalize_groups"   rows of the (batch, KV head) per workgroup of that kernel: 2 = 8192, 8 =
+ *                       32768 (only beyond 65536 rows or with finalize_variant 1), 1 = all of
+ *                       them, i.e. one workgroup per (batch, KV head) (up to 65536 rows)
+ *   "hist_unfused"      1 = the first histogram of the top-k selection is made by a launch of
+ *                       its own instead of inside the Full layer's streaming kernel
  *   "full_unpaired"     1 = the self-scheduling Full kernels group their workgroups by number
  *                       instead of mixing early and late arrivals on the compute units
  *   "ragged_even"       1 = with seq_lens, give every (batch, KV head) the same number of

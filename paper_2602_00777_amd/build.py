@@ -16,7 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libhylra.so")
 SOURCES = ["api.hip", "full_attn_d64.hip", "full_attn_d128.hip", "reuse_attn_d64.hip",
-           "reuse_attn_d128.hip", "finalize.hip", "select.hip", "reuse_mfma.hip", "reuse_mfma2.hip", "full_mfma.hip", "full_mfma2.hip", "policy.hip", "ragged_plan.hip", "offload.hip"]
+           "reuse_attn_d128.hip", "finalize.hip", "topk.hip", "reuse_mfma.hip", "reuse_mfma2.hip", "full_mfma.hip", "full_mfma2.hip", "policy.hip", "ragged_plan.hip", "offload.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-FP32 code generation is switched off on purpose (device pass only)

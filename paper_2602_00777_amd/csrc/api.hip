@@ -88,12 +88,11 @@ struct hylra_ctx {
 
     float* part_ml = nullptr;
     float* part_acc = nullptr;
-    float* part_mm = nullptr;
     float* scores = nullptr;
     float* bscores = nullptr;   // block scores of the block-level variant (blocks of >= 2 rows)
     int* counters = nullptr;    // one arrival counter per (batch, KV head), zero between launches
     int* chunk_ctr = nullptr;   // chunk counters of the self-scheduling Full kernel (kCtrStride ints apart)
-    int* sel_ws = nullptr;      // selection scratch: histogram, candidates, counts (see SelectParams)
+    int* sel_ws = nullptr;      // selection scratch (see TopkParams): histograms [pairs_cap][4096], arrival counters [pairs_cap]
     int32_t* lens_plus = nullptr;   // [max batch] sequence lengths after an append (see append_impl)
     int4* wg_map = nullptr;     // deal of the Full kernel's workgroups to sequences of different lengths
     int2* pair_map = nullptr;   // (see RaggedPlanParams): `slots` and `pairs_cap` entries
@@ -101,7 +100,6 @@ struct hylra_ctx {
     bool in_step = false;       // inside hylra_decode_step*: the lengths are the same for every layer,
     bool step_planned = false;  // so the deal is made once per step
     int64_t pairs_cap = 0;      // (batch, KV head) pairs the selection scratch is sized for
-    int max_chunks = 0;         // chunks of 8192 rows per (batch, KV head) at the maximum context
     int64_t slots = 0;          // capacity in (batch, KV head, split) triples
     int64_t cap_acc = 0;        // floats
     int64_t cap_ml = 0;
@@ -122,6 +120,7 @@ struct hylra_ctx {
     int32_t opt_finalize_groups = 0;
     int32_t opt_ragged_even = 0;
     int32_t opt_full_unpaired = 0;
+    int32_t opt_hist_unfused = 0;
 
     bool prof_on = false;
     int prof_n = 0;
@@ -543,14 +542,12 @@ hylra_status hylra_create_ex(hylra_ctx** out, const hylra_shape* max_shape, int3
     DeviceGuard guard(device);
     hipError_t e = hipMalloc((void**)&ctx->part_acc, ctx->cap_acc * sizeof(float));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->part_ml, ctx->cap_ml * sizeof(float));
-    if (e == hipSuccess) e = hipMalloc((void**)&ctx->part_mm, ctx->slots * 2 * sizeof(float));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->scores, ctx->cap_scores * sizeof(float));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->bscores, ctx->cap_bscores * sizeof(float));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->counters, ctx->slots * sizeof(int));
     if (e == hipSuccess) e = hipMemset(ctx->counters, 0, ctx->slots * sizeof(int));
     ctx->pairs_cap = pairs;
-    ctx->max_chunks = (int)ceil_div(max_shape->ctx_len, select_chunk_rows(2));
-    const int64_t sel_ints = pairs * (4096 + 1 + 1024 + 1024 + 2 + ctx->max_chunks);
+    const int64_t sel_ints = pairs * (4096 + 1);          // level-1 histograms, then their readers' arrival counters
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->sel_ws, sel_ints * sizeof(int));
     if (e == hipSuccess) e = hipMemset(ctx->sel_ws, 0, sel_ints * sizeof(int));
     // one counter per (pair, segment); there are never more segments than partial slots
@@ -584,7 +581,6 @@ hylra_status hylra_destroy(hylra_ctx* ctx) {
     }
     if (ctx->part_acc) (void)hipFree(ctx->part_acc);
     if (ctx->part_ml) (void)hipFree(ctx->part_ml);
-    if (ctx->part_mm) (void)hipFree(ctx->part_mm);
     if (ctx->scores) (void)hipFree(ctx->scores);
     if (ctx->bscores) (void)hipFree(ctx->bscores);
     if (ctx->counters) (void)hipFree(ctx->counters);
@@ -611,8 +607,9 @@ hylra_status hylra_set_option(hylra_ctx* ctx, const char* name, int32_t value) {
     else if (!std::strcmp(name, "finalize_variant")) ctx->opt_finalize_variant = value;
     else if (!std::strcmp(name, "ragged_even")) ctx->opt_ragged_even = value;
     else if (!std::strcmp(name, "full_unpaired")) ctx->opt_full_unpaired = value;
+    else if (!std::strcmp(name, "hist_unfused")) ctx->opt_hist_unfused = value;
     else if (!std::strcmp(name, "finalize_groups")) {
-        if (value != 0 && value != 2 && value != 8) return fail(ctx, HYLRA_ERR_BAD_ARG, "finalize_groups must be 0, 2 or 8");
+        if (value != 0 && value != 1 && value != 2 && value != 8) return fail(ctx, HYLRA_ERR_BAD_ARG, "finalize_groups must be 0, 1, 2 or 8");
         ctx->opt_finalize_groups = value;
     }
     else return fail(ctx, HYLRA_ERR_BAD_ARG, "unknown option '%s'", name);
@@ -671,7 +668,12 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
     fp.split_rot = ctx->opt_full_split_rot % pl.n_splits;
     fp.scale_log2 = scale * LOG2E_HOST;
     fp.scale_mean = scale / (float)G;
-    fp.part_ml = ctx->part_ml, fp.part_acc = ctx->part_acc, fp.part_mm = ctx->part_mm;
+    fp.part_ml = ctx->part_ml, fp.part_acc = ctx->part_acc;
+    // the vector kernels and the second matrix-core kernel count their scores for the selection
+    // themselves (row level; block scores are counted by a launch of their own)
+    fp.ghist = want_idx && block == 1 && (pl.variant < 50 || pl.variant >= 70) && !ctx->opt_hist_unfused &&
+                       (int64_t)shape->batch * shape->n_kv_heads <= ctx->pairs_cap
+                   ? ctx->sel_ws : nullptr;
     // (the second matrix-core kernel leaves the scores out when the layer's index set is not wanted)
     fp.scores = !want_idx && pl.variant >= 70 ? nullptr : ctx->scores;
     fp.score_stride = round_up(shape->ctx_len, 4);
@@ -711,6 +713,7 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
             }));
 
     const int64_t pairs = (int64_t)shape->batch * shape->n_kv_heads;
+    const bool hist_in_kernel = fp.ghist != nullptr;
     const float* sel_scores = ctx->scores;
     int64_t sel_stride = fp.score_stride;
     if (block > 1 && want_idx) {
@@ -726,49 +729,29 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
         sel_scores = ctx->bscores;
         sel_stride = bp.bscore_stride;
     }
-    // One workgroup per (batch, KV head) keeps up to 32768 scores in registers and needs a
-    // single launch; beyond that the three-launch, several-workgroups form is faster.
-    // (The score range the streaming kernel recorded also bounds the block maxima.)
-    const bool multi = ctx->opt_finalize_variant == 3 ||
-                       (ctx->opt_finalize_variant == 0 && n_sel > 32768);
-    if (multi) {
-        // finalise spread over several workgroups per (batch, KV head): three launches
-        int E = 2;
-        if (pairs * ceil_div(n_sel, select_chunk_rows(2)) > 4096) E = 8;
-        if (ctx->opt_finalize_groups) E = ctx->opt_finalize_groups;
-        const int64_t chunks = ceil_div(n_sel, select_chunk_rows(E));
-        if (pairs > ctx->pairs_cap || chunks > ctx->max_chunks)
-            return fail(ctx, HYLRA_ERR_WORKSPACE, "batch*n_kv_heads = %lld or ctx_len = %d exceeds the selection workspace", (long long)pairs, shape->ctx_len);
-        SelectParams sp{};
-        sp.part_ml = ctx->part_ml, sp.part_acc = ctx->part_acc, sp.part_mm = ctx->part_mm;
-        sp.scores = sel_scores, sp.score_stride = sel_stride;
-        sp.n_splits = pl.n_splits, sp.Hq = shape->n_q_heads, sp.Hkv = shape->n_kv_heads;
-        sp.G = G, sp.D = shape->head_dim, sp.N = n_sel, sp.k = k;
-        sp.seq_lens = map.seq_lens, sp.sel_block = block;
-        sp.pair_map = pair_map;
-        sp.out = out, sp.idx = want_idx ? idx : nullptr;
-        int* w = ctx->sel_ws;
-        sp.ghist = w, w += ctx->pairs_cap * 4096;
-        sp.cand_n = w, w += ctx->pairs_cap;
-        sp.cand_key = (uint32_t*)w, w += ctx->pairs_cap * 1024;
-        sp.cand_pos = w, w += ctx->pairs_cap * 1024;
-        sp.sel_info = w, w += ctx->pairs_cap * 2;
-        sp.chunk_gt = w;
-        sp.max_chunks = ctx->max_chunks;
-        for (int step = 0; step < (want_idx ? 3 : 1); ++step)
-            HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_select(sp, shape->batch, E, step, st); }));
-        return HYLRA_OK;
+    // Merge of the partials and TopK: one launch, several workgroups per (batch, KV head).
+    // Its level-1 histogram comes from the streaming kernel where that bins its scores
+    // itself, else from a small launch in front.
+    if (pairs > ctx->pairs_cap)
+        return fail(ctx, HYLRA_ERR_WORKSPACE, "batch*n_kv_heads = %lld exceeds the selection workspace", (long long)pairs);
+    TopkParams tp{};
+    tp.part_ml = ctx->part_ml, tp.part_acc = ctx->part_acc;
+    tp.scores = sel_scores, tp.score_stride = sel_stride;
+    tp.n_splits = pl.n_splits, tp.Hq = shape->n_q_heads, tp.Hkv = shape->n_kv_heads;
+    tp.G = G, tp.D = shape->head_dim, tp.N = n_sel, tp.k = k;
+    tp.seq_lens = map.seq_lens, tp.sel_block = block;
+    tp.pair_map = pair_map;
+    tp.out = out, tp.idx = want_idx ? idx : nullptr;
+    tp.ghist = ctx->sel_ws, tp.arrive = ctx->sel_ws + ctx->pairs_cap * 4096;
+    if (want_idx && !hist_in_kernel)
+        HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_score_hist(tp, shape->batch, st); }));
+    int e_own = 2, e_all = 0;
+    topk_plan(n_sel, pairs, ctx->n_cus, ctx->opt_finalize_groups, e_own, e_all);
+    if (ctx->opt_finalize_variant == 1) {                 // rows outside the chunk re-read instead of kept in registers
+        e_all = 0;
+        if (e_own != 8) e_own = 2;
     }
-    FinalizeParams zp{};
-    zp.part_ml = ctx->part_ml, zp.part_acc = ctx->part_acc, zp.part_mm = ctx->part_mm;
-    zp.scores = sel_scores, zp.score_stride = sel_stride;
-    zp.n_splits = pl.n_splits, zp.Hq = shape->n_q_heads, zp.Hkv = shape->n_kv_heads;
-    zp.G = G, zp.D = shape->head_dim, zp.N = n_sel, zp.k = k;
-    zp.seq_lens = map.seq_lens, zp.sel_block = block;
-    zp.pair_map = pair_map;
-    zp.variant = ctx->opt_finalize_variant == 2 ? 1 : 0;
-    zp.out = out, zp.idx = want_idx ? idx : nullptr;
-    HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_full_finalize(zp, shape->batch, st); }));
+    HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_topk(tp, shape->batch, e_own, e_all, st); }));
     return HYLRA_OK;
 }
 

@@ -1,18 +1,5 @@
-// Full layer, second kernel: merge the split partials into the attention output
-// (Algorithm 2, "O <- Softmax(S) V") and select the k positions with the largest
-// group-mean score (Algorithm 2, "I <- TopK(S, B)"), ties to the lower position, written
-// in ascending order.  One workgroup of 1024 threads per (batch, KV head).
-//
-// Selection is exact and works on the fp32 scores the streaming kernel stored:
-//   1. histogram over 4096 equal-width bins spanning [min, max] of the scores (the bin
-//      index is a non-decreasing function of the score, so bins are ordered like keys);
-//   2. the bin T holding the k-th largest score and the count above it;
-//   3. the rows of bin T become candidates; if they fit in LDS their exact rank is
-//      counted pairwise (key descending, position ascending), otherwise a plain 4-pass
-//      radix select over all keys finds the threshold;
-//   4. one ordered sweep emits every row above the threshold key and the first r rows
-//      equal to it.
-// Also here: the partial merge of the Reuse layer and two measurement kernels.
+// Small kernels around the two layers: block maxima for the block-level TopK, the two-kernel
+// form of the Reuse merge, a zero fill, and the measurement kernels of the C ABI.
 #include "device_util.h"
 #include "launch.h"
 #include "mfma_core.h"
@@ -28,421 +15,6 @@ extern "C" int hylra_debug_set_trace(void* device_buffer) {
 #endif
 
 namespace hylra {
-
-// Where the finalise kernel gets the scores of its (batch, KV head) from.
-//
-// RegScores<E>: thread t keeps float4 groups t, t+1024, ..., t+1024*(E-1) in registers, so the
-// scores are read from memory exactly once (N <= 4096*E).  E = 0: nothing is kept and every
-// pass re-reads the scores (any N).
-template <int E>
-struct RegScores {
-    float4 v[E > 0 ? E : 1];
-    const float* sc;
-    int N, n4;
-    DEVI void init(const float* scores, int n) {
-        sc = scores;
-        N = n;
-        n4 = (n + 3) >> 2;     // float4 groups; the last may run past N inside the padding
-        if (E > 0) {
-#pragma unroll
-            for (int j = 0; j < E; ++j) {
-                const int i = j * SEL_THREADS + (int)threadIdx.x;
-                v[j] = i < n4 ? reinterpret_cast<const float4*>(sc)[i] : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-        }
-    }
-    // f(position, score) for every row this thread owns
-    template <class F>
-    DEVI void for_each(F&& f) const {
-        if (E > 0) {
-#pragma unroll
-            for (int j = 0; j < E; ++j) {
-                const int i = j * SEL_THREADS + (int)threadIdx.x;
-                const float x[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (4 * i + e < N) f(4 * i + e, x[e]);
-            }
-        } else {
-            // eight independent loads per trip, so the pass is not bound by one memory
-            // latency per float4
-            constexpr int U = 8;
-            for (int i0 = threadIdx.x; i0 < n4; i0 += U * SEL_THREADS) {
-                float4 q[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int i = i0 + u * SEL_THREADS;
-                    q[u] = i < n4 ? reinterpret_cast<const float4*>(sc)[i] : make_float4(0.f, 0.f, 0.f, 0.f);
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int i = i0 + u * SEL_THREADS;
-                    const float x[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (4 * i + e < N) f(4 * i + e, x[e]);
-                }
-            }
-        }
-    }
-};
-
-template <int E>
-__global__ __launch_bounds__(SEL_THREADS) void full_finalize_kernel(FinalizeParams p) {
-    __shared__ int s_hist[SEL_BINS];
-    __shared__ uint32_t s_ckey[SEL_CAP];
-    __shared__ int s_cpos[SEL_CAP];
-    __shared__ int s_wave[SEL_WAVES + 1];
-    __shared__ float s_red[2 * SEL_WAVES];
-    __shared__ float s_m[SEL_ML_CAP], s_l[SEL_ML_CAP];
-    __shared__ int s_tot[(E > 0 ? E : 4) * SEL_WAVES + 1];
-    __shared__ unsigned long long s_sel[E > 0 ? SEL_THREADS : 1];   // rows of bin T that made the cut
-    __shared__ int s_T, s_above, s_cand, s_gt, s_kr;
-    __shared__ uint32_t s_tau;
-
-    const int g = blockIdx.x, b = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int D = p.D, G = p.G;
-    // this sequence ranks its first N rows and selects k of them (all of them if it has fewer)
-    const int N = seq_units(p.seq_lens, b, p.N, p.sel_block), k = min(p.k, N);
-    const int64_t pair = (int64_t)b * p.Hkv + g;
-    const PartView pv = part_view(p.pair_map, pair, p.n_splits);
-    const int S = pv.S;
-    const int64_t hb = pv.first * G;              // first partial of the pair's first head
-    int32_t* __restrict__ dst = p.idx + pair * (int64_t)p.k;
-    if (p.idx)
-        for (int i = k + tid; i < p.k; i += SEL_THREADS) dst[i] = -1;  // entries beyond a short sequence
-
-    HYLRA_TS(0);
-    RegScores<E> src;
-    if (p.idx) src.init(p.scores + pair * p.score_stride, N);      // loads are in flight from here on
-
-    // ---- attention output: log-sum-exp merge of the S partials of each head ----
-    // (max, sum) pairs go through LDS so that all loads are issued at once; the accumulator
-    // columns are then read with independent loads.
-    const int64_t head0 = (int64_t)b * p.Hq + (int64_t)g * G;
-    const bool ml_in_lds = G * S <= SEL_ML_CAP;
-    if (ml_in_lds) {
-        for (int t = tid; t < G * S; t += SEL_THREADS) {
-            const float2 ml = reinterpret_cast<const float2*>(p.part_ml + hb * 2)[t];
-            s_m[t] = ml.x;
-            s_l[t] = ml.y;
-        }
-        __syncthreads();
-    }
-    for (int i = tid; i < G * D; i += SEL_THREADS) {
-        const int h = i / D, col = i - h * D;
-        const float* ml = p.part_ml + (hb + (int64_t)h * S) * 2;
-        const float* acc = p.part_acc + (hb + (int64_t)h * S) * D + col;
-        float M = NEG_BIG;
-        if (ml_in_lds) {
-            for (int s = 0; s < S; ++s) M = fmaxf(M, s_m[h * S + s]);
-        } else {
-#pragma unroll 8
-            for (int s = 0; s < S; ++s) M = fmaxf(M, ml[2 * s]);
-        }
-        float num = 0.f, den = 0.f;
-#pragma unroll 8
-        for (int s = 0; s < S; ++s) {
-            const float w = fast_exp2((ml_in_lds ? s_m[h * S + s] : ml[2 * s]) - M);
-            den = fmaf(w, ml_in_lds ? s_l[h * S + s] : ml[2 * s + 1], den);
-            num = fmaf(w, acc[(int64_t)s * D], num);
-        }
-        p.out[(head0 + h) * D + col] = den > 0.f ? num / den : 0.f;
-    }
-
-    HYLRA_TS(1);
-    if (!p.idx) return;         // merge only: nobody will read this layer's index set
-
-    // ---- range of the scores ----
-    float lo = 3.0e38f, hi = -3.0e38f;
-    for (int s = tid; s < S; s += SEL_THREADS) {
-        lo = fminf(lo, p.part_mm[(pv.first + s) * 2]);
-        hi = fmaxf(hi, p.part_mm[(pv.first + s) * 2 + 1]);
-    }
-#pragma unroll
-    for (int mask = 1; mask < 64; mask <<= 1) {
-        lo = fminf(lo, __shfl_xor(lo, mask, 64));
-        hi = fmaxf(hi, __shfl_xor(hi, mask, 64));
-    }
-    if (lane == 0) {
-        s_red[2 * wave] = lo;
-        s_red[2 * wave + 1] = hi;
-    }
-    for (int i = tid; i < SEL_BINS; i += SEL_THREADS) s_hist[i] = 0;
-    if (E > 0) s_sel[tid] = 0;
-    if (tid == 0) s_cand = 0, s_gt = 0, s_T = SEL_BINS, s_above = 0;      // (k = 0: nothing is selected)
-    __syncthreads();
-    lo = s_red[0];
-    hi = s_red[1];
-#pragma unroll
-    for (int w = 1; w < SEL_WAVES; ++w) {
-        lo = fminf(lo, s_red[2 * w]);
-        hi = fmaxf(hi, s_red[2 * w + 1]);
-    }
-    const float span = hi - lo;
-    const float inv_w = (span > 0.f && span < 3.0e38f) ? (float)SEL_BINS / span : 0.f;
-
-    HYLRA_TS(2);
-    // ---- 1. histogram ----
-    src.for_each([&](int, float x) { atomicAdd(&s_hist[score_bin(x, lo, inv_w)], 1); });
-    __syncthreads();
-
-    HYLRA_TS(3);
-    // ---- 2. threshold bin: thread t owns bins NB-1-4t ... NB-4-4t (top bins first) ----
-    {
-        int h4[4], local = 0;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            h4[e] = s_hist[SEL_BINS - 1 - (4 * tid + e)];
-            local += h4[e];
-        }
-        int total;
-        const int excl = block_excl_scan(local, s_wave, total);
-        if (excl < k && k <= excl + local) {
-            int c = excl;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (c < k && k <= c + h4[e]) {
-                    s_T = SEL_BINS - 1 - (4 * tid + e);
-                    s_above = c;
-                }
-                c += h4[e];
-            }
-        }
-    }
-    __syncthreads();
-    const int T = s_T;
-    const int kr = k - s_above;      // how many of bin T's rows are selected, 1 <= kr <= |bin T|
-
-    HYLRA_TS(4);
-    constexpr int EE = E > 0 ? E : 1;
-
-    // ---- 3. classify: rows in bins above T are selected, rows of bin T are candidates ----
-    // bit 4*j + e of a thread's mask stands for element e of its j-th float4 group
-    unsigned long long gt_mask = 0;
-    if (E > 0) {
-#pragma unroll
-        for (int j = 0; j < EE; ++j) {
-            const int i = j * SEL_THREADS + tid;
-            const float x[4] = {src.v[j].x, src.v[j].y, src.v[j].z, src.v[j].w};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (4 * i + e >= N) continue;
-                const int bn = score_bin(x[e], lo, inv_w);
-                if (bn > T) gt_mask |= 1ull << (4 * j + e);
-                else if (bn == T) {
-                    const int slot = atomicAdd(&s_cand, 1);
-                    if (slot < SEL_CAP) {
-                        s_ckey[slot] = ordered_key(x[e]);
-                        s_cpos[slot] = 4 * i + e;
-                    }
-                }
-            }
-        }
-    } else {
-        src.for_each([&](int pos, float x) {
-            if (score_bin(x, lo, inv_w) == T) {
-                const int slot = atomicAdd(&s_cand, 1);
-                if (slot < SEL_CAP) {
-                    s_ckey[slot] = ordered_key(x);
-                    s_cpos[slot] = pos;
-                }
-            }
-        });
-    }
-    __syncthreads();
-    const int n_cand = s_cand;
-
-    HYLRA_TS(5);
-    uint32_t tau = 0;
-    int r = 0;   // rows equal to tau that are selected (lowest positions first)
-    const bool ranked = n_cand <= SEL_CAP;
-    if (ranked) {
-        // exact rank of every candidate under (key descending, position ascending); the kr
-        // best are selected
-        for (int i = tid; i < n_cand; i += SEL_THREADS) {
-            const uint32_t key = s_ckey[i];
-            const int pos = s_cpos[i];
-            int rank = 0;
-            for (int j = 0; j < n_cand; ++j) {
-                const uint32_t kj = s_ckey[j];
-                rank += (kj > key) || (kj == key && s_cpos[j] < pos);
-            }
-            if (E > 0) {
-                if (rank < kr) {
-                    const int grp = pos >> 2;       // float4 group: owner thread grp % 1024, slot grp / 1024
-                    atomicOr(&s_sel[grp & (SEL_THREADS - 1)],
-                             1ull << (4 * (grp >> 10) + (pos & 3)));
-                }
-            } else if (rank == kr - 1) {
-                s_tau = key;
-            }
-        }
-        __syncthreads();
-        if (E == 0) {
-            tau = s_tau;
-            int gt = 0;
-            for (int i = tid; i < n_cand; i += SEL_THREADS) gt += s_ckey[i] > tau;
-            if (gt) atomicAdd(&s_gt, gt);
-            __syncthreads();
-            r = kr - s_gt;
-        }
-    } else {
-        // rare: too many rows share the threshold bin (e.g. massive ties).  Plain radix
-        // select over all keys, 8 bits per pass; s_hist[0..255] is the digit histogram.
-        uint32_t prefix = 0, mask = 0;
-        int want = k;
-        for (int shift = 24; shift >= 0; shift -= 8) {
-            __syncthreads();
-            for (int i = tid; i < 256; i += SEL_THREADS) s_hist[i] = 0;
-            __syncthreads();
-            src.for_each([&](int, float x) {
-                const uint32_t key = ordered_key(x);
-                if ((key & mask) == prefix) atomicAdd(&s_hist[(key >> shift) & 255], 1);
-            });
-            __syncthreads();
-            if (tid == 0) {
-                int c = 0, dg = 255;
-                for (; dg > 0; --dg) {
-                    if (c + s_hist[dg] >= want) break;
-                    c += s_hist[dg];
-                }
-                s_kr = want - c;
-                s_tau = prefix | ((uint32_t)dg << shift);
-            }
-            __syncthreads();
-            want = s_kr;
-            prefix = s_tau;
-            mask |= 0xffu << shift;
-        }
-        tau = prefix;
-        r = want;
-    }
-
-    HYLRA_TS(6);
-    // ---- 4. ordered emission ----
-    if (E > 0) {
-        unsigned long long sel;
-        if (ranked) {
-            sel = gt_mask | s_sel[tid];
-        } else {
-            // masks by key; the first r rows equal to tau (in row order) join the set
-            unsigned long long eq_mask = 0;
-            gt_mask = 0;
-            int eq_cnt[EE], eq_base[EE];
-#pragma unroll
-            for (int j = 0; j < EE; ++j) {
-                const int i = j * SEL_THREADS + tid;
-                const float x[4] = {src.v[j].x, src.v[j].y, src.v[j].z, src.v[j].w};
-                eq_cnt[j] = 0;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if (4 * i + e >= N) continue;
-                    const uint32_t key = ordered_key(x[e]);
-                    if (key > tau) gt_mask |= 1ull << (4 * j + e);
-                    else if (key == tau) eq_mask |= 1ull << (4 * j + e), ++eq_cnt[j];
-                }
-            }
-            multi_scan<EE>(eq_cnt, eq_base, s_tot);
-            sel = gt_mask;
-#pragma unroll
-            for (int j = 0; j < EE; ++j) {
-                int seen = eq_base[j];
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if ((eq_mask >> (4 * j + e)) & 1) {
-                        if (seen < r) sel |= 1ull << (4 * j + e);
-                        ++seen;
-                    }
-            }
-        }
-        int cnt[EE], base[EE];
-#pragma unroll
-        for (int j = 0; j < EE; ++j) cnt[j] = __popc((unsigned)(sel >> (4 * j)) & 0xFu);
-        multi_scan<EE>(cnt, base, s_tot);
-#pragma unroll
-        for (int j = 0; j < EE; ++j) {
-            unsigned nib = (unsigned)(sel >> (4 * j)) & 0xFu;
-            int o = base[j];
-            const int pos0 = 4 * (j * SEL_THREADS + tid);
-            while (nib) {
-                const int e = __ffs(nib) - 1;
-                nib &= nib - 1;
-                if (o < k) dst[o] = pos0 + e;
-                ++o;
-            }
-        }
-    } else {
-        // thread t owns 4 consecutive rows of each 4096-row tile; four tiles per trip, their
-        // (above tau, equal to tau) counts packed 16 + 16 bits and scanned together
-        constexpr int U = 4;
-        const float* __restrict__ sc = src.sc;
-        int base_gt = 0, base_eq = 0;
-        for (int tile0 = 0; tile0 < src.n4; tile0 += U * SEL_THREADS) {
-            uint32_t key[U][4];
-            int cnt[U], base[U];
-            float4 q[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int i = tile0 + u * SEL_THREADS + tid;
-                q[u] = i < src.n4 ? reinterpret_cast<const float4*>(sc)[i] : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int i = tile0 + u * SEL_THREADS + tid;
-                const float x[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
-                cnt[u] = 0;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    key[u][e] = ordered_key(x[e]);
-                    if (4 * i + e < N) cnt[u] += (key[u][e] > tau) ? 1 : ((key[u][e] == tau) ? 0x10000 : 0);
-                }
-            }
-            const int total = multi_scan<U>(cnt, base, s_tot);
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int i = tile0 + u * SEL_THREADS + tid;
-                int gt_before = base_gt + (base[u] & 0xffff);
-                int eq_before = base_eq + (base[u] >> 16);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if (4 * i + e >= N) continue;
-                    if (key[u][e] > tau) {
-                        const int o = gt_before + min(eq_before, r);
-                        if (o < k) dst[o] = 4 * i + e;
-                        ++gt_before;
-                    } else if (key[u][e] == tau) {
-                        if (eq_before < r) {
-                            const int o = gt_before + eq_before;
-                            if (o < k) dst[o] = 4 * i + e;
-                        }
-                        ++eq_before;
-                    }
-                }
-            }
-            base_gt += total & 0xffff;
-            base_eq += total >> 16;
-        }
-    }
-    HYLRA_TS(7);
-}
-
-hipError_t launch_full_finalize(const FinalizeParams& p, int B, hipStream_t st) {
-    const dim3 grid(p.Hkv, B), block(SEL_THREADS);
-    const int n4 = (p.N + 3) >> 2;
-    if (p.variant == 0 && n4 <= 2 * SEL_THREADS)
-        hipLaunchKernelGGL(full_finalize_kernel<2>, grid, block, 0, st, p);
-    else if (p.variant == 0 && n4 <= 4 * SEL_THREADS)
-        hipLaunchKernelGGL(full_finalize_kernel<4>, grid, block, 0, st, p);
-    else if (p.variant == 0 && n4 <= 8 * SEL_THREADS)
-        hipLaunchKernelGGL(full_finalize_kernel<8>, grid, block, 0, st, p);
-    else if (p.variant == 0 && n4 <= 16 * SEL_THREADS)
-        hipLaunchKernelGGL(full_finalize_kernel<16>, grid, block, 0, st, p);
-    else
-        hipLaunchKernelGGL(full_finalize_kernel<0>, grid, block, 0, st, p);
-    return hipGetLastError();
-}
 
 // ---- block-level TopK: score of a block = maximum of its rows' group-mean scores ----
 // A group of L lanes (L = largest power of two <= min(64, block)) reduces one block; a

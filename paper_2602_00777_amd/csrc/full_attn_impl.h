@@ -6,6 +6,7 @@
 #include "attend.h"
 #include "chunk_queue.h"
 #include "launch.h"
+#include "score_hist.h"
 
 #ifndef HYLRA_BUILD_D
 #error "define HYLRA_BUILD_D to 64 or 128"
@@ -39,7 +40,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     constexpr int TILE = R * GEO::RPG;
     constexpr bool NT = MODE >= 1;
     __shared__ float smem[merge_smem_floats<GEO, NW>()];
-    __shared__ float s_mm[2 * NW];
+    __shared__ int s_hist[kScoreBins];
     extern __shared__ float s_scores[];          // [rows_per_split]
 
     int split = (blockIdx.x + p.split_rot) % p.n_splits, g = blockIdx.y, b = blockIdx.z;
@@ -84,8 +85,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
                                          : (n_rows + p.n_splits * STEP - 1) / (p.n_splits * STEP) * STEP;
     const int row0 = DYN ? 0 : split * rps;
     const int row1 = DYN ? n_rows : min(n_rows, row0 + rps);
-    float smin = 3.0e38f, smax = -3.0e38f;
     float* __restrict__ srow = p.scores + ((int64_t)b * p.Hkv + g) * p.score_stride;
+    // the scores are also counted per top 12 bits of their key (score_hist.h); a barrier follows
+    // on every path before the first count
+    const bool bins = p.ghist != nullptr;
+    if (bins) hist_zero<NW * 64>(s_hist);
 
     // Paged cache: the part of the sequence's page table this workgroup can touch is staged in
     // LDS behind the score staging area (a lookup from memory in the loop would put a load
@@ -133,11 +137,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
             for (int r = 0; r < R; ++r) {
                 const float v = fminf(fmaxf(ms[r], -3.0e38f), 3.0e38f);   // also maps NaN to a number
                 if (chunk == 0) {
-                    if (DYN && st0 < 0) srow[t0 + r * GEO::RPG + slot] = v;
-                    else s_scores[st0 + r * GEO::RPG + slot] = v;
+                    if (DYN && st0 < 0) {
+                        srow[t0 + r * GEO::RPG + slot] = v;
+                        if (bins) hist_add(s_hist, v);
+                    } else {
+                        s_scores[st0 + r * GEO::RPG + slot] = v;
+                    }
                 }
-                smin = fminf(smin, v);
-                smax = fmaxf(smax, v);
             }
         } else {
 #pragma unroll
@@ -146,13 +152,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
 #pragma unroll
             for (int r = 0; r < R; ++r) {
                 const float v = fminf(fmaxf(ms[r], -3.0e38f), 3.0e38f);
-                if (valid[r]) {
-                    if (chunk == 0) {
-                        if (DYN && st0 < 0) srow[t0 + r * GEO::RPG + slot] = v;
-                        else s_scores[st0 + r * GEO::RPG + slot] = v;
+                if (valid[r] && chunk == 0) {
+                    if (DYN && st0 < 0) {
+                        srow[t0 + r * GEO::RPG + slot] = v;
+                        if (bins) hist_add(s_hist, v);
+                    } else {
+                        s_scores[st0 + r * GEO::RPG + slot] = v;
                     }
-                    smin = fminf(smin, v);
-                    smax = fmaxf(smax, v);
                 }
             }
         }
@@ -254,6 +260,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
                 } else {
                     for (int x = e; x < n; ++x) srow[r0 + x] = src[x];
                 }
+                if (bins)
+                    for (int x = e; x < min(e + 4, n); ++x) hist_add(s_hist, src[x]);
             }
         }
     } else if (DYN || row0 >= row1) {
@@ -288,25 +296,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     }
 
     HYLRA_TS(1);
-    // range of this split's group-mean scores (the finalise kernel bins on it)
-    smin = strided_minmax<1, false>(smin);
-    smax = strided_minmax<1, true>(smax);
-    if (lane == 0) {
-        s_mm[2 * wave] = smin;
-        s_mm[2 * wave + 1] = smax;
-    }
-    __syncthreads();                             // also: every score of the split is in LDS
-    if (tid == 0) {
-#pragma unroll
-        for (int w = 1; w < NW; ++w) {
-            smin = fminf(smin, s_mm[2 * w]);
-            smax = fmaxf(smax, s_mm[2 * w + 1]);
-        }
-        float* mm = p.part_mm + (slot0 + split) * 2;
-        mm[0] = smin;
-        mm[1] = smax;
-    }
     if (!DYN) {
+        __syncthreads();                         // every score of the split is in LDS
         // row0 and the score stride are multiples of 4 floats: 16-byte stores are aligned
         float* __restrict__ dst = srow + row0;
         const int n = max(row1 - row0, 0);
@@ -316,6 +307,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
             } else {
                 for (int e = i; e < n; ++e) dst[e] = s_scores[e];
             }
+            if (bins)
+                for (int e = i; e < min(i + 4, n); ++e) hist_add(s_hist, s_scores[e]);
         }
     }
 
@@ -323,6 +316,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     const int n_part = DYN ? my_wgs * p.n_segs : p.n_splits;
     block_merge_store<GEO, NW>(st, smem, p.part_ml + (slot0 * G + split) * 2, (int64_t)n_part * 2,
                                p.part_acc + (slot0 * G + split) * D, (int64_t)n_part * D);
+    __syncthreads();                             // between the last count and the flush
+    if (bins) hist_flush<NW * 64>(s_hist, p.ghist + ((int64_t)b * p.Hkv + g) * kScoreBins);
     HYLRA_TS(2);
 }
 

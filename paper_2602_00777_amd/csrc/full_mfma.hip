@@ -25,7 +25,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     __shared__ float s_m[NW][16];
     __shared__ float s_l[NW][16];
     __shared__ float s_acc[NW * G * D];
-    __shared__ float s_mm[2 * NW];
 
     const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -50,7 +49,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     const int row0 = split * rps;
     const int row1 = min(n_rows, row0 + rps);
     float* __restrict__ srow = p.scores + ((int64_t)b * p.Hkv + g) * p.score_stride;
-    float smin = 3.0e38f, smax = -3.0e38f;
 
     // paged cache: the split's part of the sequence's page table, staged in LDS
     extern __shared__ int s_tbl[];
@@ -100,19 +98,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
             }
             if (left >= 16) {
                 if (n == 0) *reinterpret_cast<float4*>(srow + r0 + 4 * gq) = make_float4(sj[0], sj[1], sj[2], sj[3]);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    smin = fminf(smin, sj[j]);
-                    smax = fmaxf(smax, sj[j]);
-                }
             } else {
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    if (4 * gq + j < left) {
-                        if (n == 0) srow[r0 + 4 * gq + j] = sj[j];
-                        smin = fminf(smin, sj[j]);
-                        smax = fmaxf(smax, sj[j]);
-                    }
+                    if (4 * gq + j < left && n == 0) srow[r0 + 4 * gq + j] = sj[j];
             }
         }
     };
@@ -138,27 +127,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         }
     }
 
-    // range of this split's group-mean scores (the finalise kernels bin on it)
-#pragma unroll
-    for (int mask = 1; mask < 64; mask <<= 1) {
-        smin = fminf(smin, __shfl_xor(smin, mask, 64));
-        smax = fmaxf(smax, __shfl_xor(smax, mask, 64));
-    }
-    if (lane == 0) {
-        s_mm[2 * wave] = smin;
-        s_mm[2 * wave + 1] = smax;
-    }
-    __syncthreads();
-    if (tid == 0) {
-#pragma unroll
-        for (int w = 1; w < NW; ++w) {
-            smin = fminf(smin, s_mm[2 * w]);
-            smax = fmaxf(smax, s_mm[2 * w + 1]);
-        }
-        float* mm = p.part_mm + (((int64_t)b * p.Hkv + g) * p.n_splits + split) * 2;
-        mm[0] = smin;
-        mm[1] = smax;
-    }
     mfma_block_merge_store<D, G, NW, false>(st, s_m, s_l, s_acc,
                                             p.part_ml + (head0 * p.n_splits + split) * 2,
                                             (int64_t)p.n_splits * 2,

@@ -12,6 +12,7 @@
 #include "chunk_queue.h"
 #include "launch.h"
 #include "mfma2_core.h"
+#include "score_hist.h"
 
 namespace hylra {
 
@@ -26,7 +27,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     __shared__ float s_m[NW][16];
     __shared__ float s_l[NW][16];
     __shared__ __attribute__((aligned(16))) float s_acc[NW * G * D];
-    __shared__ float s_mm[2 * NW];
+    __shared__ int s_hist[kScoreBins];
     extern __shared__ float s_scores[];          // [rows_per_split], then the staged page table
 
     int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
@@ -74,7 +75,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     // the group-mean scores are neither formed nor written, nor is their range
     const bool want_scores = p.scores != nullptr;
     float* __restrict__ srow = want_scores ? p.scores + ((int64_t)b * p.Hkv + g) * p.score_stride : nullptr;
-    float smin = 3.0e38f, smax = -3.0e38f;
+    // the scores are also counted per top 12 bits of their key (score_hist.h); a barrier follows
+    // on every path before the first count
+    const bool bins = want_scores && p.ghist != nullptr;
+    if (bins) hist_zero<NW * 64>(s_hist);
 
     // paged cache: the split's part of the sequence's page table, staged in LDS (read from
     // memory if it does not fit there)
@@ -155,13 +159,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
                 float v = group_sum<16>(blk ? Sb[j] : Sa[j]) * p.scale_mean;
                 v = fminf(fmaxf(v, -3.0e38f), 3.0e38f);      // also maps NaN to a number
                 const int r = 16 * blk + 4 * gq + j;
-                if (r < left) {
-                    if (n == 0) {
-                        if (DYN && st0 < 0) srow[t0 + r] = v;
-                        else s_scores[st0 + r] = v;
+                if (r < left && n == 0) {
+                    if (DYN && st0 < 0) {
+                        srow[t0 + r] = v;
+                        if (bins) hist_add(s_hist, v);
+                    } else {
+                        s_scores[st0 + r] = v;
                     }
-                    smin = fminf(smin, v);
-                    smax = fmaxf(smax, v);
                 }
             }
     };
@@ -263,6 +267,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
                 for (int x = 0; x < 4; ++x)
                     if (r + x < n_rows) srow[r + x] = src[x];
             }
+            if (bins)
+                for (int x = 0; x < 4; ++x)
+                    if (r + x < n_rows) hist_add(s_hist, src[x]);
         }
     } else if (!DYN && row0 < row1) {
         Tile32 bufA, bufB;
@@ -280,25 +287,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     }
 
     HYLRA_TS(3);
-    // range of this split's group-mean scores (the finalise kernels bin on it)
-    smin = strided_minmax<1, false>(smin);
-    smax = strided_minmax<1, true>(smax);
-    if (lane == 0) {
-        s_mm[2 * wave] = smin;
-        s_mm[2 * wave + 1] = smax;
-    }
-    __syncthreads();                             // also: every score of the split is in LDS
-    if (tid == 0 && want_scores) {
-#pragma unroll
-        for (int w = 1; w < NW; ++w) {
-            smin = fminf(smin, s_mm[2 * w]);
-            smax = fmaxf(smax, s_mm[2 * w + 1]);
-        }
-        float* mm = p.part_mm + (slot0 + split) * 2;
-        mm[0] = smin;
-        mm[1] = smax;
-    }
     if (!DYN) {
+        __syncthreads();                         // every score of the split is in LDS
         // row0 and the score stride are multiples of 4 floats: 16-byte stores are aligned
         float* __restrict__ dst = srow + row0;
         const int cnt = want_scores ? max(row1 - row0, 0) : 0;
@@ -308,6 +298,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
             } else {
                 for (int e = i; e < cnt; ++e) dst[e] = s_scores[e];
             }
+            if (bins)
+                for (int e = i; e < min(i + 4, cnt); ++e) hist_add(s_hist, s_scores[e]);
         }
     }
     // the pair's partials: [head of the group][partial] from slot0 * G on
@@ -315,6 +307,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     merge_store2<G, NW, false>(st, s_m, s_l, s_acc, p.part_ml + (slot0 * G + split) * 2,
                                (int64_t)n_part * 2, p.part_acc + (slot0 * G + split) * D,
                                (int64_t)n_part * D, n, gq);
+    // (the barrier inside the merge lies between the last count and the flush)
+    if (bins) hist_flush<NW * 64>(s_hist, p.ghist + ((int64_t)b * p.Hkv + g) * kScoreBins);
     HYLRA_TS(4);
 }
 

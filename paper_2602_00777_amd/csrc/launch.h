@@ -37,9 +37,10 @@ struct FullParams {
     float scale_mean;               // scale / G
     float* part_ml;                 // [B*Hq][S][2]   (max in log2 units, sum)
     float* part_acc;                // [B*Hq][S][D]
-    float* part_mm;                 // [B*Hkv][S][2]  (min, max of the group-mean scores)
+    int* ghist;                     // [B*Hkv][4096] or nullptr: where a kernel that bins its scores itself adds
+                                    // its counts per top-12-bits of the score's ordered key (see topk.hip)
     float* scores;                  // [B*Hkv][score_stride] group-mean scaled scores (second matrix-core
-                                    // kernel: nullptr = not wanted, then part_mm is not written either)
+                                    // kernel: nullptr = not wanted)
     int64_t score_stride;           // multiple of 4, >= N
     // self-scheduling mode only.  The wave tiles of a (batch, KV head) (a tile = the rows one
     // wave loads at a time) are cut into n_segs segments of equal length (to within one tile);
@@ -71,11 +72,11 @@ struct FullParams {
     int chunk_tile[kMaxChunks + 1];
 };
 
-struct FinalizeParams {
+// Merge of the partials + TopK in one launch (topk.hip).
+struct TopkParams {
     const float* part_ml;
     const float* part_acc;
-    const float* part_mm;
-    const float* scores;
+    const float* scores;            // [B*Hkv][score_stride] what is ranked: row scores, or block scores
     int64_t score_stride;
     int n_splits, Hq, Hkv, G, D, N, k;
     const int32_t* seq_lens;        // [B] or nullptr: sequence b ranks its first n_b rows and selects
@@ -83,34 +84,16 @@ struct FinalizeParams {
     int sel_block;                  // rows per ranked unit (N and k count units): n_b = ceil(len / sel_block)
     const int2* pair_map;           // [B*Hkv] {first partial slot, partials} of the pair; nullptr:
                                     // {pair * n_splits, n_splits}.  The pair's partials are laid out
-                                    // [head of the group][partial] from slot `first` on (see part_base).
-    int variant;                    // 0: scores kept in registers when they fit; 1: always re-read
+                                    // [head of the group][partial] from slot `first` on (see part_view).
     float* out;                     // [B][Hq][D]
-    int32_t* idx;                   // [B][Hkv][k]
+    int32_t* idx;                   // [B][Hkv][k]; nullptr: merge only
+    int* ghist;                     // [B*Hkv][4096] histogram of the top 12 key bits of the ranked scores:
+                                    // complete when the kernel starts, zero again when it ends
+    int* arrive;                    // [B*Hkv] readers of the histogram so far; zero between launches
 };
-
-// Multi-workgroup finalise (select.hip): same inputs as FinalizeParams plus per-(batch, KV
-// head) scratch that is zero between launches where noted.
-struct SelectParams {
-    const float* part_ml;
-    const float* part_acc;
-    const float* part_mm;
-    const float* scores;
-    int64_t score_stride;
-    int n_splits, Hq, Hkv, G, D, N, k;
-    const int32_t* seq_lens;        // as in FinalizeParams
-    int sel_block;
-    const int2* pair_map;
-    float* out;                     // [B][Hq][D]
-    int32_t* idx;                   // [B][Hkv][k]
-    int* ghist;                     // [B*Hkv][4096] score histogram; zero between launches
-    int* cand_n;                    // [B*Hkv] rows in the threshold bin found so far
-    uint32_t* cand_key;             // [B*Hkv][1024] their keys ...
-    int* cand_pos;                  // ... and positions (arrival order)
-    int* sel_info;                  // [B*Hkv][2] threshold bin, rows above it
-    int* chunk_gt;                  // [B*Hkv][max_chunks] rows above the threshold bin per chunk
-    int max_chunks;
-};
+hipError_t launch_score_hist(const TopkParams& p, int B, hipStream_t st);
+bool topk_plan(int N, int64_t pairs, int n_cus, int groups, int& e_own, int& e_all);
+hipError_t launch_topk(const TopkParams& p, int B, int e_own, int e_all, hipStream_t st);
 
 struct ReuseParams {
     const uint16_t* q;
@@ -254,10 +237,6 @@ hipError_t launch_gather_rows(const GatherParams& p, int B, hipStream_t st);
 hipError_t launch_overlap_counts(const OverlapParams& p, int B, hipStream_t st);
 int policy_search_host(int L, const double* M, double theta, uint8_t* policy, double* sum_sim);
 
-hipError_t launch_full_finalize(const FinalizeParams& p, int B, hipStream_t st);
-// step 0, 1, 2 = histogram, classify, emit; E = float4 groups per thread (2 or 8)
-int select_chunk_rows(int E);
-hipError_t launch_select(const SelectParams& p, int B, int E, int step, hipStream_t st);
 hipError_t launch_block_max(const BlockMaxParams& p, int B, int Hkv, hipStream_t st);
 hipError_t launch_combine(const CombineParams& p, int n_heads_total, hipStream_t st);
 // n ints at p become zero (a kernel: safe to record into a HIP graph)

@@ -97,8 +97,9 @@ def test_full_self_scheduling_kernel(B, Hkv, G, d, N, k, variant):
 
 @pytest.mark.parametrize("N,k", [(5003, 300), (20000, 1500), (40000, 3000)])
 def test_finalize_paths(N, k):
-    """Every finalise path (multi-workgroup; single workgroup with scores in registers / re-read
-    per pass), including the many-ties fallback, at sizes that span one to several chunks."""
+    """Every form of the merge + top-k kernel (one or several workgroups per (batch, KV head);
+    all scores in registers or re-read per pass), including the many-ties fallback, at sizes
+    that span one to several chunks."""
     say("finalize paths N=%d k=%d" % (N, k))
     B, Hkv, G, d = 1, 2, 4, 64
     q, K, V = rand_case(19 + N, B, Hkv, G, d, N)
@@ -110,7 +111,7 @@ def test_finalize_paths(N, k):
            oracle.full_attn_topk(qt, Kt, V, k, want_shat=True),
            oracle.full_attn_topk(q, Kz, V, k, want_shat=True)]
     with binding.Context(B, Hkv * G, Hkv, d, N, k) as ctx:
-        for variant, groups in ((3, 2), (3, 8), (1, 0), (2, 0), (0, 0)):
+        for variant, groups in ((0, 0), (0, 1), (0, 2), (1, 2), (1, 8)):
             ctx.set_option("finalize_variant", variant)
             ctx.set_option("finalize_groups", groups)
             for (qq, KK), (ro, ri, rs), exact in (((q, K), ref[0], False), ((qt, Kt), ref[1], True), ((q, Kz), ref[2], True)):
