@@ -424,13 +424,6 @@ hylra_status hylra_policy_search(hylra_ctx *ctx, int32_t n_layers, const double 
  *   "reuse_waves"       waves per workgroup of the matrix-core Reuse kernel: 4 or 8
  *   "reuse_unfused"     1 = merge the Reuse partials in a second kernel instead of in the
  *                       last-arriving workgroup of the Reuse kernel
- *   "finalize_variant"  the Full layer's second kernel (merge of partials + top-k):
- *                       1 = its workgroups re-read the scores outside their own chunk in every
- *                       pass instead of keeping all of a (batch, KV head)'s scores in registers
- *                       (the default up to 65536 rows of context keeps them)
- *   "finalize_groups"   rows of the (batch, KV head) per workgroup of that kernel: 2 = 8192, 8 =
- *                       32768 (only beyond 65536 rows or with finalize_variant 1), 1 = all of
- *                       them, i.e. one workgroup per (batch, KV head) (up to 65536 rows)
  *   "hist_unfused"      1 = the first histogram of the top-k selection is made by a launch of
  *                       its own instead of inside the Full layer's streaming kernel
  *   "full_unpaired"     1 = the self-scheduling Full kernels group their workgroups by number

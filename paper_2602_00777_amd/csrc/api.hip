@@ -92,7 +92,8 @@ struct hylra_ctx {
     float* bscores = nullptr;   // block scores of the block-level variant (blocks of >= 2 rows)
     int* counters = nullptr;    // one arrival counter per (batch, KV head), zero between launches
     int* chunk_ctr = nullptr;   // chunk counters of the self-scheduling Full kernel (kCtrStride ints apart)
-    int* sel_ws = nullptr;      // selection scratch (see TopkParams): histograms [pairs_cap][4096], arrival counters [pairs_cap]
+    int* sel_ws = nullptr;      // selection scratch (see TopkParams and hylra_create_ex)
+    int max_chunks = 0;         // chunks of 8192 rows per (batch, KV head) at the maximum context
     int32_t* lens_plus = nullptr;   // [max batch] sequence lengths after an append (see append_impl)
     int4* wg_map = nullptr;     // deal of the Full kernel's workgroups to sequences of different lengths
     int2* pair_map = nullptr;   // (see RaggedPlanParams): `slots` and `pairs_cap` entries
@@ -116,8 +117,6 @@ struct hylra_ctx {
     int32_t opt_reuse_unroll = 0;
     int32_t opt_reuse_waves = 0;
     int32_t opt_reuse_unfused = 0;
-    int32_t opt_finalize_variant = 0;
-    int32_t opt_finalize_groups = 0;
     int32_t opt_ragged_even = 0;
     int32_t opt_full_unpaired = 0;
     int32_t opt_hist_unfused = 0;
@@ -547,7 +546,10 @@ hylra_status hylra_create_ex(hylra_ctx** out, const hylra_shape* max_shape, int3
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->counters, ctx->slots * sizeof(int));
     if (e == hipSuccess) e = hipMemset(ctx->counters, 0, ctx->slots * sizeof(int));
     ctx->pairs_cap = pairs;
-    const int64_t sel_ints = pairs * (4096 + 1);          // level-1 histograms, then their readers' arrival counters
+    // selection scratch (see TopkParams): level-1 histograms; threshold per pair; per chunk of
+    // 8192 rows its counts and its list of rows in the threshold bin
+    ctx->max_chunks = (int)ceil_div(max_shape->ctx_len, kTopkChunkRows);
+    const int64_t sel_ints = pairs * (4096 + 2 + (int64_t)ctx->max_chunks * (2 + 2 * kTopkChunkList));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->sel_ws, sel_ints * sizeof(int));
     if (e == hipSuccess) e = hipMemset(ctx->sel_ws, 0, sel_ints * sizeof(int));
     // one counter per (pair, segment); there are never more segments than partial slots
@@ -604,14 +606,9 @@ hylra_status hylra_set_option(hylra_ctx* ctx, const char* name, int32_t value) {
     else if (!std::strcmp(name, "reuse_unroll")) ctx->opt_reuse_unroll = value;
     else if (!std::strcmp(name, "reuse_waves")) ctx->opt_reuse_waves = value;
     else if (!std::strcmp(name, "reuse_unfused")) ctx->opt_reuse_unfused = value;
-    else if (!std::strcmp(name, "finalize_variant")) ctx->opt_finalize_variant = value;
     else if (!std::strcmp(name, "ragged_even")) ctx->opt_ragged_even = value;
     else if (!std::strcmp(name, "full_unpaired")) ctx->opt_full_unpaired = value;
     else if (!std::strcmp(name, "hist_unfused")) ctx->opt_hist_unfused = value;
-    else if (!std::strcmp(name, "finalize_groups")) {
-        if (value != 0 && value != 1 && value != 2 && value != 8) return fail(ctx, HYLRA_ERR_BAD_ARG, "finalize_groups must be 0, 1, 2 or 8");
-        ctx->opt_finalize_groups = value;
-    }
     else return fail(ctx, HYLRA_ERR_BAD_ARG, "unknown option '%s'", name);
     return HYLRA_OK;
 }
@@ -742,16 +739,17 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
     tp.seq_lens = map.seq_lens, tp.sel_block = block;
     tp.pair_map = pair_map;
     tp.out = out, tp.idx = want_idx ? idx : nullptr;
-    tp.ghist = ctx->sel_ws, tp.arrive = ctx->sel_ws + ctx->pairs_cap * 4096;
+    tp.ghist = ctx->sel_ws;
+    tp.pair_info = reinterpret_cast<int2*>(ctx->sel_ws + ctx->pairs_cap * 4096);
+    tp.chunk_info = tp.pair_info + ctx->pairs_cap;
+    tp.chunk_list = tp.chunk_info + ctx->pairs_cap * ctx->max_chunks;
+    tp.max_chunks = ctx->max_chunks;
+    if (want_idx && ceil_div(n_sel, kTopkChunkRows) > ctx->max_chunks)
+        return fail(ctx, HYLRA_ERR_WORKSPACE, "ctx_len = %d exceeds the selection workspace", shape->ctx_len);
     if (want_idx && !hist_in_kernel)
         HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_score_hist(tp, shape->batch, st); }));
-    int e_own = 2, e_all = 0;
-    topk_plan(n_sel, pairs, ctx->n_cus, ctx->opt_finalize_groups, e_own, e_all);
-    if (ctx->opt_finalize_variant == 1) {                 // rows outside the chunk re-read instead of kept in registers
-        e_all = 0;
-        if (e_own != 8) e_own = 2;
-    }
-    HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_topk(tp, shape->batch, e_own, e_all, st); }));
+    for (int step = 0; step < (want_idx ? 2 : 1); ++step)
+        HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_topk(tp, shape->batch, step, ctx->n_cus, st); }));
     return HYLRA_OK;
 }
 

@@ -88,12 +88,20 @@ struct TopkParams {
     float* out;                     // [B][Hq][D]
     int32_t* idx;                   // [B][Hkv][k]; nullptr: merge only
     int* ghist;                     // [B*Hkv][4096] histogram of the top 12 key bits of the ranked scores:
-                                    // complete when the kernel starts, zero again when it ends
-    int* arrive;                    // [B*Hkv] readers of the histogram so far; zero between launches
+                                    // complete when step 0 starts, zero again when step 1 ends
+    int2* pair_info;                // [B*Hkv] {level-1 threshold bin, rows in the bins above it}
+    int2* chunk_info;               // [B*Hkv][max_chunks] {rows above the threshold bin, rows in it}
+    int2* chunk_list;               // [B*Hkv][max_chunks][kTopkChunkList] {key, position} of the rows in it
+    int max_chunks;
+    int merge_wgs, merge_lanes;     // workgroups per pair that merge the partials, lanes per output (set by launch_topk)
+    int chunks;                     // chunks per (batch, KV head) of this launch (set by launch_topk)
+    int64_t pairs;                  // B * Hkv (set by launch_topk)
 };
+constexpr int kTopkChunkRows = 8192;    // rows of a (batch, KV head) per selecting workgroup
+constexpr int kTopkChunkList = 512;     // rows of the level-1 threshold bin a chunk can list
 hipError_t launch_score_hist(const TopkParams& p, int B, hipStream_t st);
-bool topk_plan(int N, int64_t pairs, int n_cus, int groups, int& e_own, int& e_all);
-hipError_t launch_topk(const TopkParams& p, int B, int e_own, int e_all, hipStream_t st);
+// step 0: level-1 threshold, per-chunk counts and lists, merge of the partials; step 1: emission
+hipError_t launch_topk(const TopkParams& p, int B, int step, int n_cus, hipStream_t st);
 
 struct ReuseParams {
     const uint16_t* q;

@@ -1,43 +1,56 @@
 // Full layer, after the streaming pass: merge of the split partials into the attention
 // output (Algorithm 2, "O <- Softmax(S) V") and the EXACT selection of the k positions with
 // the largest group-mean score (Algorithm 2, "I <- TopK(S, B)"; ties to the lower position,
-// ascending order).  One launch, C workgroups of 1024 threads per (batch, KV head).
+// ascending order).
 //
 // Rows are ranked by (key descending, position ascending), key = the order-preserving 32-bit
-// image of the fp32 score.  The selection is a radix select on the key, 12 + 12 + 8 bits:
+// image of the fp32 score.  The selection is a radix select on the key, 12 + 12 + 8 bits, over
+// chunks of 8192 rows, one workgroup of 1024 threads per chunk holding its rows in registers:
 //   level 1  a histogram of the top 12 key bits over all of the pair's rows.  It is COMPLETE
-//            when this kernel starts: the streaming kernel bins the scores it has staged in
-//            LDS and adds its non-empty bins to the pair's histogram in memory (for the
+//            when the first kernel here starts: the streaming kernel bins the scores it has
+//            staged in LDS and adds its non-empty bins to the pair's histogram in memory (for the
 //            kernels that do not, score_hist_kernel below does it in a launch of its own).
-//            Every workgroup reads it and finds the bin T1 that holds the k-th best row.
-//   level 2  the rows of bin T1 (a few per cent of all rows) are binned on the next 12 bits
-//            in LDS, by every workgroup for itself; bin T2 holds the k-th best row.
-//   level 3  the rows whose top 24 bits equal (T1, T2) -- a handful unless scores tie -- are
-//            ranked pairwise in LDS; if they do not fit there (massive ties), one more
-//            histogram over the last 8 bits settles the threshold key and the rows equal to it
-//            are taken in position order.
-// Workgroup c of a pair emits the selected rows of chunk c (4096 * E_OWN consecutive rows, kept
-// in registers) at the place in the output that the selected rows of the chunks before it
-// leave; for that it counts those rows itself.  No workgroup waits for another one.  Rows
-// outside the own chunk are kept in registers too when the pair's rows fit there (E_ALL > 0,
-// up to 65536 rows), else they are re-read (from the L2 / memory-side cache) in each pass.
-// The histogram in memory is zeroed again by the workgroup of the pair that read it last (an
-// arrival counter), so the next Full layer finds it empty.
+//   topk_scan_kernel   every chunk finds the level-1 threshold bin T1 (the bin that holds the
+//            k-th best row), counts its rows in the bins above T1 (selected for sure) and lists
+//            its rows of bin T1 (key, position; about 1.5 % of the rows) in memory.  One more
+//            workgroup per (batch, KV head) merges the attention partials meanwhile.
+//   topk_emit_kernel   every chunk reads the lists of all the pair's chunks (a few KB), bins them
+//            on the next 12 key bits (level 2: bin T2), ranks the handful of rows whose top 24
+//            bits equal (T1, T2) pairwise (level 3; with massive ties: one more histogram over
+//            the last 8 bits, rows equal to the threshold key taken in position order), and
+//            emits the selected rows of its chunk at the place the chunks before it leave.
+// A workgroup reads its own chunk and those lists, nothing else: what bounds these kernels is
+// what ONE compute unit can pull from beyond its L2 (about 20 GB/s: a workgroup that scans all
+// 32768 rows of a pair spends 6 us on that alone, all 131072 rows 25 us -- measured with a
+// one-launch form of this selection, which lost for that reason), so the work is cut so that no
+// workgroup reads more than 32 KB of scores.  If a chunk has more rows in bin T1 than its list
+// holds (heavy ties), the second kernel falls back to scanning all rows of the pair itself.
 #include "launch.h"
 #include "select_util.h"
 
 namespace hylra {
 
 constexpr int kTopkFineBins = 4096;
+constexpr int kTopkList = 3072;       // rows of bin T1 (all chunks of a pair) a workgroup can hold in LDS
+constexpr int E_OWN = kTopkChunkRows / (4 * SEL_THREADS);      // float4 groups per thread = 2
+static_assert(E_OWN * 4 * SEL_THREADS == kTopkChunkRows, "a chunk is E_OWN float4 groups per thread");
 
 // Threshold bin of a histogram whose bins NB-1-4t .. NB-4-4t sit in h4[0..3] of thread t: the
 // bin T that holds the k-th largest row and the number of rows in the bins above it.  s_pick
-// must hold (SEL_BINS, 0) on entry (what comes back when k = 0).  Contains barriers.
+// must hold (SEL_BINS, 0) on entry (what comes back when k = 0).  Two barriers; once per kernel
+// (s_wave and s_pick are not reusable afterwards without another barrier).
 DEVI void threshold_pick(const int (&h4)[4], int k, int* s_wave, int* s_pick, int& T, int& above) {
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int local = h4[0] + h4[1] + h4[2] + h4[3];
-    int total;
-    const int excl = block_excl_scan(local, s_wave, total);
+    const int incl = wave_incl_scan_dpp(local);
+    if (lane == 63) s_wave[wave] = incl;
+    __syncthreads();
+    int excl = incl - local;
+#pragma unroll
+    for (int w = 0; w < SEL_WAVES; ++w) {
+        const int t = s_wave[w];                 // (one address for all lanes: a broadcast)
+        excl += w < wave ? t : 0;
+    }
     if (excl < k && k <= excl + local) {
         int c = excl;
 #pragma unroll
@@ -52,17 +65,173 @@ DEVI void threshold_pick(const int (&h4)[4], int k, int* s_wave, int* s_pick, in
     __syncthreads();
     T = s_pick[0];
     above = s_pick[1];
-    __syncthreads();                 // s_pick may be written again
 }
 
 DEVI float f4_at(const float4& v, int e) { return e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w; }
 
-template <int E_OWN, int E_ALL>
-__global__ __launch_bounds__(SEL_THREADS) void topk_kernel(TopkParams p) {
-    constexpr bool ALLREG = E_ALL > 0;
-    constexpr int NREG = ALLREG ? E_ALL : E_OWN;
-    static_assert(!ALLREG || E_ALL % E_OWN == 0, "chunks tile the register-resident rows");
-    static_assert(E_OWN <= 16, "selection masks hold 4 * E_OWN bits");
+// Workgroups are handed to the XCDs (each with an L2 of its own) in turn, by their number:
+// workgroup x runs on XCD x % 8.  The workgroups of a (batch, KV head) are numbered 8 apart, so
+// that they share one L2 (the lists one kernel writes and the other reads, the pair's
+// histogram).  Nothing but speed depends on where a workgroup really lands.  per_pair
+// workgroups per pair; returns false for the padding workgroups of the last eight pairs.
+DEVI bool xcd_pair_role(int per_pair, int64_t pairs, int64_t& pair, int& role) {
+    const int slot = blockIdx.x >> 3;
+    pair = (int64_t)(slot / per_pair) * 8 + (blockIdx.x & 7);
+    role = slot % per_pair;
+    return pair < pairs;
+}
+
+// The chunk's rows: register j of thread t holds float4 group first4 + j * 1024 + t.
+struct ChunkRows {
+    float4 v[E_OWN];
+    int first4;
+    DEVI void load(const float* sc, int n4, int c) {
+        first4 = c * E_OWN * SEL_THREADS;
+#pragma unroll
+        for (int j = 0; j < E_OWN; ++j) {
+            const int i = grp(j);
+            v[j] = i < n4 ? reinterpret_cast<const float4*>(sc)[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    }
+    DEVI int grp(int j) const { return first4 + j * SEL_THREADS + (int)threadIdx.x; }
+    DEVI uint32_t key(int j, int e) const { return ordered_key(f4_at(v[j], e)); }
+};
+
+// ---- first kernel: level-1 threshold, counts and lists per chunk; merge of the partials ----
+__global__ __launch_bounds__(SEL_THREADS) void topk_scan_kernel(TopkParams p) {
+    __shared__ int s_wave[SEL_WAVES + 1];
+    __shared__ int s_pick[2];
+    __shared__ int s_n, s_above;
+    __shared__ int2 s_list[kTopkChunkList];
+
+    const int C = p.chunks;
+    int64_t pair;
+    int c;
+    if (!xcd_pair_role(C + p.merge_wgs, p.pairs, pair, c)) return;
+    const int b = (int)(pair / p.Hkv), g = (int)(pair - (int64_t)b * p.Hkv);
+    const int tid = threadIdx.x, lane = tid & 63;
+
+    // ---- attention output (the pair's last merge_wgs workgroups): L lanes per output element,
+    // each lane merging every L-th partial with the loads of four partials in flight at once,
+    // then a log-sum-exp merge across the L lanes.  L and the number of workgroups are chosen
+    // on the host so that a lane has at most four partials and a workgroup one sweep (every
+    // further trip is another round to memory, and this is the kernel's longest chain). ----
+    // (merge_wgs = 0: few partials, no workgroups to spare -- chunk 0 merges before it scans)
+    if (c >= C || (p.merge_wgs == 0 && c == 0)) {
+        const int merge_wgs = max(p.merge_wgs, 1), merge_id = c >= C ? c - C : 0;
+        const PartView pv = part_view(p.pair_map, pair, p.n_splits);
+        const int S = pv.S, D = p.D, G = p.G;
+        const int64_t hb = pv.first * G;              // first partial of the pair's first head
+        const int L = p.merge_lanes;
+        const int64_t head0 = (int64_t)b * p.Hq + (int64_t)g * G;
+        const int sub = tid & (L - 1), per_sweep = SEL_THREADS / L;
+        const int share = (G * D + merge_wgs - 1) / merge_wgs;
+        const int begin = merge_id * share, end = min(G * D, begin + share);
+        for (int i0 = begin; i0 < end; i0 += per_sweep) {
+            const int i = i0 + tid / L;
+            const bool live = i < end;
+            const int h = live ? i / D : 0, col = live ? i - h * D : 0;
+            const float* ml = p.part_ml + (hb + (int64_t)h * S) * 2;
+            const float* acc = p.part_acc + (hb + (int64_t)h * S) * D + col;
+            float M = NEG_BIG, num = 0.f, den = 0.f;
+            for (int s0 = sub; s0 < S; s0 += 4 * L) {
+                float m_s[4], l_s[4], a_s[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int sx = min(s0 + u * L, S - 1);
+                    const float2 t = *reinterpret_cast<const float2*>(ml + 2 * sx);
+                    m_s[u] = s0 + u * L < S ? t.x : NEG_BIG;
+                    l_s[u] = t.y;
+                    a_s[u] = acc[(int64_t)sx * D];
+                }
+                const float M2 = fmaxf(fmaxf(fmaxf(m_s[0], m_s[1]), fmaxf(m_s[2], m_s[3])), M);
+                const float r = fast_exp2(M - M2);
+                num *= r, den *= r;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float w = s0 + u * L < S ? fast_exp2(m_s[u] - M2) : 0.f;
+                    den = fmaf(w, l_s[u], den);
+                    num = fmaf(w, a_s[u], num);
+                }
+                M = M2;
+            }
+            float Mg = M;
+            for (int m = 1; m < L; m <<= 1) Mg = fmaxf(Mg, __shfl_xor(Mg, m, 64));
+            const float r = fast_exp2(M - Mg);
+            num *= r, den *= r;
+            for (int m = 1; m < L; m <<= 1) {
+                num += __shfl_xor(num, m, 64);
+                den += __shfl_xor(den, m, 64);
+            }
+            if (live && sub == 0) p.out[(head0 + h) * D + col] = den > 0.f ? num / den : 0.f;
+        }
+        if (c >= C) return;
+    }
+
+    // this sequence ranks its first N rows and selects k of them
+    const int N = seq_units(p.seq_lens, b, p.N, p.sel_block), k = min(p.k, N);
+    const float* __restrict__ sc = p.scores + pair * p.score_stride;
+    ChunkRows rows;
+    rows.load(sc, (N + 3) >> 2, c);
+    int h4[4];
+    {
+        const int4 h = *reinterpret_cast<const int4*>(p.ghist + pair * SEL_BINS + SEL_BINS - 4 - 4 * tid);
+        h4[0] = h.w, h4[1] = h.z, h4[2] = h.y, h4[3] = h.x;
+    }
+    if (tid == 0) s_n = 0, s_above = 0, s_pick[0] = SEL_BINS, s_pick[1] = 0;
+    HYLRA_TS(4);
+
+    // ---- level 1: threshold bin of the complete histogram (the same in every chunk) ----
+    int T1, above1;
+    threshold_pick(h4, k, s_wave, s_pick, T1, above1);
+    HYLRA_TS(5);
+    if (c == 0 && tid == 0) p.pair_info[pair] = make_int2(T1, above1);
+
+    // ---- the chunk's rows: above bin T1 (counted), in it (listed) ----
+    const uint32_t lo_key = (uint32_t)T1 << 20, top_key = lo_key | 0xFFFFFu;      // bin T1 = [lo_key, top_key]
+    int above = 0, mine = 0;
+    uint32_t in_bin = 0;
+#pragma unroll
+    for (int j = 0; j < E_OWN; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (4 * rows.grp(j) + e >= N || T1 >= SEL_BINS) continue;
+            const uint32_t key = rows.key(j, e);
+            above += key > top_key;
+            if (key >= lo_key && key <= top_key) in_bin |= 1u << (4 * j + e), ++mine;
+        }
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) above += __shfl_xor(above, m, 64);
+    if (lane == 0 && above) atomicAdd(&s_above, above);
+    HYLRA_TS(2);
+    // list entries are reserved per wave: a prefix sum over the lanes and ONE atomic on the list's
+    // counter (an atomic per lane on that single LDS address is served lane by lane: 1024 of them
+    // took 2.6 us here)
+    const int incl = wave_incl_scan_dpp(mine);
+    int wave_base = 0;
+    if (lane == 63) wave_base = atomicAdd(&s_n, incl);
+    int slot = __shfl(wave_base, 63, 64) + incl - mine;
+#pragma unroll
+    for (int j = 0; j < E_OWN; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if ((in_bin >> (4 * j + e)) & 1u) {
+                if (slot < kTopkChunkList) s_list[slot] = make_int2((int)rows.key(j, e), 4 * rows.grp(j) + e);
+                ++slot;
+            }
+    HYLRA_TS(3);
+    __syncthreads();
+    HYLRA_TS(6);
+    const int n = s_n;                           // may exceed the list: the second kernel then scans all rows
+    const int64_t cslot = pair * p.max_chunks + c;
+    int2* __restrict__ gl = p.chunk_list + cslot * kTopkChunkList;
+    for (int i = tid; i < min(n, kTopkChunkList); i += SEL_THREADS) gl[i] = s_list[i];
+    if (tid == 0) p.chunk_info[cslot] = make_int2(s_above, n);
+    HYLRA_TS(7);
+}
+
+// ---- second kernel: levels 2 and 3, ordered emission ----
+__global__ __launch_bounds__(SEL_THREADS) void topk_emit_kernel(TopkParams p) {
     __shared__ int s_hist[kTopkFineBins];
     __shared__ uint32_t s_ckey[SEL_CAP];
     __shared__ int s_cpos[SEL_CAP];
@@ -70,141 +239,114 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(TopkParams p) {
     __shared__ int s_wave[SEL_WAVES + 1];
     __shared__ int s_tot[E_OWN * SEL_WAVES + 1];
     __shared__ int s_pick[2];
-    __shared__ int s_cand, s_before, s_before_eq, s_kr, s_last;
+    __shared__ uint32_t s_k1[kTopkList];               // the rows of bin T1: keys ...
+    __shared__ int s_p1[kTopkList];                    // ... and positions
+    __shared__ int s_n1, s_cand, s_before, s_before_eq, s_kr, s_overflow;
     __shared__ uint32_t s_tau;
 
-    const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z, C = gridDim.x;
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int64_t pair = (int64_t)b * p.Hkv + g;
-    const PartView pv = part_view(p.pair_map, pair, p.n_splits);
-    const int S = pv.S, D = p.D, G = p.G;
-    const int64_t hb = pv.first * G;              // first partial of the pair's first head
+    const int C = p.chunks;
+    int64_t pair;
+    int c;
+    if (!xcd_pair_role(C, p.pairs, pair, c)) return;
+    const int b = (int)(pair / p.Hkv);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-    // this sequence ranks its first N rows (none: merge only) and selects k of them
-    const int N = p.idx ? seq_units(p.seq_lens, b, p.N, p.sel_block) : 0, k = min(p.k, N);
+    const int N = seq_units(p.seq_lens, b, p.N, p.sel_block), k = min(p.k, N);
     const int n4 = (N + 3) >> 2;
     const float* __restrict__ sc = p.scores + pair * p.score_stride;
     const float4* __restrict__ sc4 = reinterpret_cast<const float4*>(sc);
     int32_t* __restrict__ dst = p.idx + pair * (int64_t)p.k;
-    const int first4 = c * E_OWN * SEL_THREADS;                   // the chunk's first float4 group
-    const int chunk_pos0 = 4 * first4, chunk_pos1 = chunk_pos0 + 4 * E_OWN * SEL_THREADS;
-    if (p.idx && c == 0)
+    if (c == 0)
         for (int i = k + tid; i < p.k; i += SEL_THREADS) dst[i] = -1;  // entries beyond a short sequence
 
-    // ---- loads first: the rows (the own chunk in registers 0 .. E_OWN - 1) and the histogram ----
-    // register j holds float4 group grp(j) of the pair
-    auto grp = [&](int j) {
-        return ALLREG ? ((j + c * E_OWN) & (E_ALL - 1)) * SEL_THREADS + tid : first4 + j * SEL_THREADS + tid;
-    };
-    float4 v[NREG];
-#pragma unroll
-    for (int j = 0; j < NREG; ++j) {
-        const int i = grp(j);
-        v[j] = i < n4 ? sc4[i] : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
-    int h4[4] = {0, 0, 0, 0};
-    int* __restrict__ gh = p.ghist + pair * SEL_BINS;
-    if (p.idx) {
-        const int4 h = *reinterpret_cast<const int4*>(gh + SEL_BINS - 4 - 4 * tid);
-        h4[0] = h.w, h4[1] = h.z, h4[2] = h.y, h4[3] = h.x;
-    }
+    ChunkRows rows;
+    rows.load(sc, n4, c);
+    const int first4 = rows.first4;
+    const int chunk_pos0 = 4 * first4, chunk_pos1 = chunk_pos0 + kTopkChunkRows;
+    const int2 info = p.pair_info[pair];
+    const int T1 = info.x, kr1 = k - info.y;     // level-1 threshold bin; rows of it that are selected
     for (int i = tid; i < kTopkFineBins; i += SEL_THREADS) s_hist[i] = 0;
     s_sel[tid] = 0;
-    if (tid == 0) s_cand = 0, s_before = 0, s_before_eq = 0, s_last = 0, s_pick[0] = SEL_BINS, s_pick[1] = 0;
+    if (tid == 0) s_n1 = 0, s_cand = 0, s_before = 0, s_before_eq = 0, s_overflow = 0, s_pick[0] = SEL_BINS, s_pick[1] = 0;
+    // the level-1 histogram has been read by every chunk (in the first kernel): leave it empty
+    if (c == 0) *reinterpret_cast<int4*>(p.ghist + pair * SEL_BINS + 4 * tid) = make_int4(0, 0, 0, 0);
+    __syncthreads();
+    HYLRA_TS(8);
 
-    // ---- attention output: this workgroup's share of the G*D outputs of the KV head.  16 lanes
-    // per output element, each merging every 16th partial. ----
-    {
-        constexpr int L = 16;
-        const int share = (G * D + C - 1) / C;
-        const int64_t head0 = (int64_t)b * p.Hq + (int64_t)g * G;
-        const int sub = tid & (L - 1), sgrp = tid / L;
-        const int end = min(G * D, (c + 1) * share);
-        for (int i = c * share + sgrp; i < end; i += SEL_THREADS / L) {
-            const int h = i / D, col = i - h * D;
-            const float* ml = p.part_ml + (hb + (int64_t)h * S) * 2;
-            const float* acc = p.part_acc + (hb + (int64_t)h * S) * D + col;
-            float M = NEG_BIG;
-            for (int s = sub; s < S; s += L) M = fmaxf(M, ml[2 * s]);
-#pragma unroll
-            for (int m = 1; m < L; m <<= 1) M = fmaxf(M, __shfl_xor(M, m, 64));
-            float num = 0.f, den = 0.f;
-            for (int s = sub; s < S; s += L) {
-                const float w = fast_exp2(ml[2 * s] - M);
-                den = fmaf(w, ml[2 * s + 1], den);
-                num = fmaf(w, acc[(int64_t)s * D], num);
+    // ---- the pair's rows of bin T1 from the chunks' lists into LDS (wave w takes chunks w,
+    // w + 16, ...), and the rows above T1 in the chunks before this one ----
+    int before = 0;                              // selected rows of the chunks before this one
+    for (int cc = wave; cc < C; cc += SEL_WAVES) {
+        const int64_t cslot = pair * p.max_chunks + cc;
+        const int2 ci = p.chunk_info[cslot];
+        if (ci.y > kTopkChunkList) {
+            if (lane == 0) s_overflow = 1;
+            continue;
+        }
+        if (lane == 0 && cc < c) before += ci.x;
+        int base = 0;
+        if (lane == 0) base = atomicAdd(&s_n1, ci.y);
+        base = __shfl(base, 0, 64);
+        const int2* __restrict__ gl = p.chunk_list + cslot * kTopkChunkList;
+        for (int i = lane; i < ci.y; i += 64) {
+            const int2 kp = gl[i];
+            if (base + i < kTopkList) {
+                s_k1[base + i] = (uint32_t)kp.x;
+                s_p1[base + i] = kp.y;
             }
-#pragma unroll
-            for (int m = 1; m < L; m <<= 1) {
-                num += __shfl_xor(num, m, 64);
-                den += __shfl_xor(den, m, 64);
-            }
-            if (sub == 0) p.out[(head0 + h) * D + col] = den > 0.f ? num / den : 0.f;
         }
     }
-    if (!p.idx) return;         // merge only: nobody will read this layer's index set
+    __syncthreads();
+    int n1 = s_n1;
+    const bool listed = !s_overflow && n1 <= kTopkList;
 
-    // f(position, key) for every row of the pair: from registers, or re-read from memory
-    // (eight independent loads per trip)
+    // g(regs, index) for every set of rows of the pair, re-read from memory eight independent
+    // loads at a time -- only when the lists do not hold bin T1 (heavy ties)
     auto for_all_rows = [&](auto&& f) {
-        if (ALLREG) {
+        constexpr int U = 8;
+        for (int i0 = tid; i0 < n4; i0 += U * SEL_THREADS) {
+            float4 q[U];
 #pragma unroll
-            for (int j = 0; j < NREG; ++j) {
-                const int i = grp(j);
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + u * SEL_THREADS;
+                q[u] = i < n4 ? sc4[i] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int i = i0 + u * SEL_THREADS;
 #pragma unroll
                 for (int e = 0; e < 4; ++e)
-                    if (4 * i + e < N) f(4 * i + e, ordered_key(f4_at(v[j], e)));
-            }
-        } else {
-            constexpr int U = 8;
-            for (int i0 = tid; i0 < n4; i0 += U * SEL_THREADS) {
-                float4 q[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int i = i0 + u * SEL_THREADS;
-                    q[u] = i < n4 ? sc4[i] : make_float4(0.f, 0.f, 0.f, 0.f);
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int i = i0 + u * SEL_THREADS;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (4 * i + e < N) f(4 * i + e, ordered_key(f4_at(q[u], e)));
-                }
+                    if (4 * i + e < N) f(4 * i + e, ordered_key(f4_at(q[u], e)));
             }
         }
     };
 
-    // ---- level 1: threshold bin of the complete histogram ----
-    int T1, above1;
-    threshold_pick(h4, k, s_wave, s_pick, T1, above1);
-    // every thread has consumed its part of the histogram: sign in as one of its C readers
-    // (the answer is looked at when the kernel is about to end)
-    int arrived = 0;
-    if (tid == 0) {
-        arrived = __hip_atomic_fetch_add(p.arrive + pair, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        s_pick[0] = SEL_BINS, s_pick[1] = 0;
-    }
-    const int kr1 = k - above1;                  // rows of bin T1 that are selected
-
     // ---- level 2: the rows of bin T1 by their next 12 bits ----
-    for_all_rows([&](int, uint32_t key) {
-        if ((int)(key >> 20) == T1) atomicAdd(&s_hist[(key >> 8) & (kTopkFineBins - 1)], 1);
-    });
-    __syncthreads();
-    {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) h4[e] = s_hist[kTopkFineBins - 1 - (4 * tid + e)];
+    if (listed) {
+        for (int i = tid; i < n1; i += SEL_THREADS) atomicAdd(&s_hist[(s_k1[i] >> 8) & (kTopkFineBins - 1)], 1);
+    } else {
+        before = 0;
+        for_all_rows([&](int pos, uint32_t key) {
+            const int b1 = (int)(key >> 20);
+            if (b1 > T1) before += pos < chunk_pos0;
+            else if (b1 == T1) atomicAdd(&s_hist[(key >> 8) & (kTopkFineBins - 1)], 1);
+        });
     }
+    __syncthreads();
+    HYLRA_TS(9);
+    int h4[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) h4[e] = s_hist[kTopkFineBins - 1 - (4 * tid + e)];
     int T2, above2;
     threshold_pick(h4, kr1, s_wave, s_pick, T2, above2);
+    HYLRA_TS(10);
     const int kr2 = kr1 - above2;                // rows with the top 24 bits (T1, T2) that are selected
     // (T1 = SEL_BINS when nothing is selected: thr24 is then above every 24-bit value)
     const uint32_t thr24 = ((uint32_t)T1 << 12) | (uint32_t)(T2 & (kTopkFineBins - 1));
 
-    // ---- level 3: rows above the 24-bit threshold are selected; rows equal to it are candidates ----
-    int before = 0;                              // selected rows of the chunks before this one
-    for_all_rows([&](int pos, uint32_t key) {
+    // ---- level 3: of the rows of bin T1, those above the 24-bit threshold are selected and those
+    // equal to it are candidates ----
+    auto classify = [&](int pos, uint32_t key) {
         const uint32_t k24 = key >> 8;
         if (k24 > thr24) {
             before += pos < chunk_pos0;
@@ -215,12 +357,20 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(TopkParams p) {
                 s_cpos[slot] = pos;
             }
         }
-    });
+    };
+    if (listed) {
+        for (int i = tid; i < n1; i += SEL_THREADS) classify(s_p1[i], s_k1[i]);
+    } else {
+        for_all_rows([&](int pos, uint32_t key) {
+            if ((int)(key >> 20) == T1) classify(pos, key);
+        });
+    }
 #pragma unroll
     for (int m = 1; m < 64; m <<= 1) before += __shfl_xor(before, m, 64);
     if (lane == 0 && before) atomicAdd(&s_before, before);
     __syncthreads();
     const int n_cand = s_cand;
+    HYLRA_TS(11);
 
     unsigned long long sel = 0;                  // bit 4 j + e: element e of own register j is selected
     if (n_cand <= SEL_CAP) {
@@ -246,7 +396,7 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(TopkParams p) {
         for (int j = 0; j < E_OWN; ++j)
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                if (4 * grp(j) + e < N && (ordered_key(f4_at(v[j], e)) >> 8) > thr24) sel |= 1ull << (4 * j + e);
+                if (4 * rows.grp(j) + e < N && (rows.key(j, e) >> 8) > thr24) sel |= 1ull << (4 * j + e);
         sel |= s_sel[tid];
     } else {
         // rare: more rows share the top 24 key bits than the candidate list holds (massive
@@ -297,8 +447,8 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(TopkParams p) {
             eq_cnt[j] = 0;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                if (4 * grp(j) + e >= N) continue;
-                const uint32_t key = ordered_key(f4_at(v[j], e));
+                if (4 * rows.grp(j) + e >= N) continue;
+                const uint32_t key = rows.key(j, e);
                 if (key > tau) sel |= 1ull << (4 * j + e);
                 else if (key == tau) eq_mask |= 1ull << (4 * j + e), ++eq_cnt[j];
             }
@@ -318,6 +468,7 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(TopkParams p) {
         __syncthreads();
     }
     const int base0 = s_before;
+    HYLRA_TS(12);
 
     // ---- ordered emission of the chunk's selected rows ----
     int cnt[E_OWN], base[E_OWN];
@@ -328,7 +479,7 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(TopkParams p) {
     for (int j = 0; j < E_OWN; ++j) {
         unsigned nib = (unsigned)(sel >> (4 * j)) & 0xFu;
         int o = base0 + base[j];
-        const int pos0 = 4 * grp(j);
+        const int pos0 = 4 * rows.grp(j);
         while (nib) {
             const int e = __ffs(nib) - 1;
             nib &= nib - 1;
@@ -336,14 +487,7 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_kernel(TopkParams p) {
             ++o;
         }
     }
-
-    // ---- the last reader of the pair's histogram leaves it empty ----
-    if (tid == 0 && arrived == C - 1) s_last = 1;
-    __syncthreads();
-    if (s_last) {
-        *reinterpret_cast<int4*>(gh + 4 * tid) = make_int4(0, 0, 0, 0);
-        if (tid == 0) __hip_atomic_store(p.arrive + pair, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
+    HYLRA_TS(13);
 }
 
 // ---- level-1 histogram in a launch of its own, for the streaming kernels that do not bin ----
@@ -354,21 +498,15 @@ __global__ __launch_bounds__(SEL_THREADS) void score_hist_kernel(TopkParams p) {
     const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z, tid = threadIdx.x;
     const int64_t pair = (int64_t)b * p.Hkv + g;
     const int N = seq_units(p.seq_lens, b, p.N, p.sel_block);
-    const int n4 = (N + 3) >> 2;
-    const float4* __restrict__ sc4 = reinterpret_cast<const float4*>(p.scores + pair * p.score_stride);
-    float4 v[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int i = (2 * c + j) * SEL_THREADS + tid;
-        v[j] = i < n4 ? sc4[i] : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
+    ChunkRows rows;
+    rows.load(p.scores + pair * p.score_stride, (N + 3) >> 2, c);
     for (int i = tid; i < SEL_BINS; i += SEL_THREADS) s_hist[i] = 0;
     __syncthreads();
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < E_OWN; ++j)
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            if (4 * ((2 * c + j) * SEL_THREADS + tid) + e < N) atomicAdd(&s_hist[ordered_key(f4_at(v[j], e)) >> 20], 1);
+            if (4 * rows.grp(j) + e < N) atomicAdd(&s_hist[rows.key(j, e) >> 20], 1);
     __syncthreads();
     int* gh = p.ghist + pair * SEL_BINS;
     for (int i = tid; i < SEL_BINS; i += SEL_THREADS) {
@@ -378,42 +516,33 @@ __global__ __launch_bounds__(SEL_THREADS) void score_hist_kernel(TopkParams p) {
 }
 
 hipError_t launch_score_hist(const TopkParams& p, int B, hipStream_t st) {
-    const dim3 grid((p.N + 8 * SEL_THREADS - 1) / (8 * SEL_THREADS), p.Hkv, B);
+    const dim3 grid((p.N + kTopkChunkRows - 1) / kTopkChunkRows, p.Hkv, B);
     hipLaunchKernelGGL(score_hist_kernel, grid, dim3(SEL_THREADS), 0, st, p);
     return hipGetLastError();
 }
 
-// Rows per chunk are 4096 * e_own; e_all = 0 or the power of two >= ceil(N / 4096) (at most 16)
-bool topk_plan(int N, int64_t pairs, int n_cus, int groups, int& e_own, int& e_all) {
-    const int64_t n4k = ((int64_t)N + 4095) / 4096;        // float4 groups per thread if one workgroup held all rows
-    e_all = 0;
-    for (int e = 2; e <= 16; e *= 2)
-        if (n4k <= e) {
-            e_all = e;
-            break;
-        }
-    if (e_all) {
-        // chunks of 8192 rows while that does not launch more than two workgroups per compute
-        // unit; else one workgroup per pair
-        e_own = (groups == 1 || (groups == 0 && pairs * (e_all / 2) > 2 * (int64_t)n_cus)) ? e_all : 2;
-    } else {
-        e_own = (groups == 8 || (groups == 0 && pairs * ((n4k + 1) / 2) > 4 * (int64_t)n_cus)) ? 8 : 2;
-    }
-    return true;
-}
-
-hipError_t launch_topk(const TopkParams& p, int B, int e_own, int e_all, hipStream_t st) {
-    const int C = (p.N + 4096 * e_own - 1) / (4096 * e_own);
-    const dim3 grid(C, p.Hkv, B), block(SEL_THREADS);
-#define HYLRA_TOPK(EO, EA)                                                        \
-    if (e_own == EO && e_all == EA) {                                             \
-        hipLaunchKernelGGL((topk_kernel<EO, EA>), grid, block, 0, st, p);         \
-        return hipGetLastError();                                                 \
-    }
-    HYLRA_TOPK(2, 2) HYLRA_TOPK(2, 4) HYLRA_TOPK(4, 4) HYLRA_TOPK(2, 8) HYLRA_TOPK(8, 8)
-    HYLRA_TOPK(2, 16) HYLRA_TOPK(16, 16) HYLRA_TOPK(2, 0) HYLRA_TOPK(8, 0)
-#undef HYLRA_TOPK
-    return hipErrorInvalidValue;
+// step 0: scan (+ merge of the partials); step 1: emit.  p.idx == nullptr: merge only (step 0).
+hipError_t launch_topk(const TopkParams& p, int B, int step, int n_cus, hipStream_t st) {
+    TopkParams q = p;
+    q.chunks = p.idx ? (p.N + kTopkChunkRows - 1) / kTopkChunkRows : 0;
+    q.pairs = (int64_t)B * p.Hkv;
+    if (q.chunks > p.max_chunks) return hipErrorInvalidValue;
+    // merge of the partials: lanes per output so that a lane has at most four partials (up to 16
+    // lanes), workgroups so that one sweep covers the pair's outputs (up to 16 workgroups)
+    q.merge_lanes = 1;
+    while (q.merge_lanes < 16 && 4 * q.merge_lanes < p.n_splits) q.merge_lanes *= 2;
+    q.merge_wgs = (p.G * p.D * q.merge_lanes + SEL_THREADS - 1) / SEL_THREADS;
+    if (q.merge_wgs > 16) q.merge_wgs = 16;
+    // few partials and already more workgroups than can be resident at once (two per compute
+    // unit): the pair's first chunk does the merge in passing
+    if (q.chunks > 0 && q.merge_lanes == 1 && q.merge_wgs == 1 && q.pairs * (q.chunks + 1) > 2 * (int64_t)n_cus) q.merge_wgs = 0;
+    const int per_pair = step == 0 ? q.chunks + q.merge_wgs : q.chunks;
+    const int64_t wgs = (q.pairs + 7) / 8 * 8 * per_pair;
+    if (wgs > 0x7fffffff) return hipErrorInvalidValue;
+    if (wgs == 0) return hipSuccess;
+    if (step == 0) hipLaunchKernelGGL(topk_scan_kernel, dim3((unsigned)wgs), dim3(SEL_THREADS), 0, st, q);
+    else hipLaunchKernelGGL(topk_emit_kernel, dim3((unsigned)wgs), dim3(SEL_THREADS), 0, st, q);
+    return hipGetLastError();
 }
 
 }  // namespace hylra

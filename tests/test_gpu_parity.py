@@ -97,9 +97,9 @@ def test_full_self_scheduling_kernel(B, Hkv, G, d, N, k, variant):
 
 @pytest.mark.parametrize("N,k", [(5003, 300), (20000, 1500), (40000, 3000)])
 def test_finalize_paths(N, k):
-    """Every form of the merge + top-k kernel (one or several workgroups per (batch, KV head);
-    all scores in registers or re-read per pass), including the many-ties fallback, at sizes
-    that span one to several chunks."""
+    """The selection kernels with the first histogram made inside the streaming kernel or by a
+    launch of its own, including the many-ties fallbacks (a chunk's list overflowing; more
+    tied candidates than can be ranked), at sizes that span one to several chunks."""
     say("finalize paths N=%d k=%d" % (N, k))
     B, Hkv, G, d = 1, 2, 4, 64
     q, K, V = rand_case(19 + N, B, Hkv, G, d, N)
@@ -111,9 +111,8 @@ def test_finalize_paths(N, k):
            oracle.full_attn_topk(qt, Kt, V, k, want_shat=True),
            oracle.full_attn_topk(q, Kz, V, k, want_shat=True)]
     with binding.Context(B, Hkv * G, Hkv, d, N, k) as ctx:
-        for variant, groups in ((0, 0), (0, 1), (0, 2), (1, 2), (1, 8)):
-            ctx.set_option("finalize_variant", variant)
-            ctx.set_option("finalize_groups", groups)
+        for unfused in (0, 1):
+            ctx.set_option("hist_unfused", unfused)
             for (qq, KK), (ro, ri, rs), exact in (((q, K), ref[0], False), ((qt, Kt), ref[1], True), ((q, Kz), ref[2], True)):
                 out, idx = run_full(ctx, qq, KK, V, k)
                 assert_out_close(out, ro, "out")
@@ -518,7 +517,7 @@ def test_profile_and_probe_aids():
             ctx.reuse_sparse_attn(q, K, V, idx)
         torch.cuda.synchronize()
         prof = ctx.profile_read()
-        assert prof["full_attn"][0] == 1 and prof["full_finalize"][0] == 1
+        assert prof["full_attn"][0] == 1 and prof["full_finalize"][0] == 2      # streaming pass; scan + emit of the selection
         assert prof["reuse_attn"][0] == 3 and prof["reuse_combine"][0] == 0
         for name in ("full_attn", "full_finalize", "reuse_attn"):
             assert 0.0 < prof[name][1] < 50.0          # milliseconds
