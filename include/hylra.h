@@ -94,6 +94,14 @@ hylra_status hylra_create_ex(hylra_ctx **out, const hylra_shape *max_shape, int3
  * running.  NULL is accepted. */
 hylra_status hylra_destroy(hylra_ctx *ctx);
 
+/* Puts the context's workspace back into its initial state: synchronises the device, zeroes the
+ * counters and histograms the kernels keep between launches, clears the sticky error below.
+ * HOST call.  Needed only after a call failed with the text "gave up waiting": the Full
+ * kernels that hand rows out at run time bound every wait; should such a wait ever run out
+ * (it cannot unless the device is failing), the launch leaves rows out, the context records
+ * it, and every later call on the context fails with HYLRA_ERR_HIP until hylra_reset. */
+hylra_status hylra_reset(hylra_ctx *ctx);
+
 /* Static, never NULL. */
 const char *hylra_status_str(hylra_status s);
 
@@ -403,19 +411,16 @@ hylra_status hylra_policy_search(hylra_ctx *ctx, int32_t n_layers, const double 
  *   "full_split_rows"   rows of the cache per workgroup of the Full kernel (the vector-ALU
  *                       kernels take at most 8192 and clamp larger values)
  *   "reuse_split_rows"  index entries per workgroup of the Reuse kernel
- *   "full_variant"      Full streaming kernel.  Vector-ALU kernels, 10*mode + unroll: 4 (plain
- *                       loads), 14 (streaming loads), 23 / 22 (streaming loads, two-deep register
- *                       pipeline), 43 / 42 (as 23 / 22 with the rows handed out at run time).
- *                       First matrix-core kernel: 54, 52, 62, 61 (pipelined).  Second
- *                       matrix-core kernel (head_dim 128): 72 (even splits), 74 (rows handed
- *                       out at run time).  Defaults: head_dim 128: 74 while batch * n_kv_heads
- *                       >= 64 (up to 4 heads per KV head) or whenever the launch has exactly two
- *                       workgroups per compute unit, 72 otherwise and for small problems (under
- *                       2048 rows per workgroup); head_dim 64: 52 from 5 heads per KV head, else
- *                       43 while batch * n_kv_heads >= 64 and 23 below that.  The kernels that
- *                       hand out rows at run time give outputs that can differ in the last
- *                       bits from run to run (index sets never do); the others are
- *                       bit-reproducible.
+ *   "full_variant"      Full streaming kernel.  Vector-ALU kernel (two-deep register pipeline,
+ *                       streaming loads): 23 = even splits, 43 = rows handed out at run time.
+ *                       First matrix-core kernel: 52.  Second matrix-core kernel (head_dim 128):
+ *                       72 = even splits, 74 = rows handed out at run time.  Defaults: head_dim
+ *                       128: 74 while batch * n_kv_heads >= 64 (up to 4 heads per KV head) or
+ *                       whenever the launch has exactly two workgroups per compute unit, 72
+ *                       otherwise and for small problems (under 2048 rows per workgroup);
+ *                       head_dim 64: 52 from 5 heads per KV head, else 43 while batch *
+ *                       n_kv_heads >= 64 and 23 below that.  HYLRA_FLAG_DETERMINISTIC rules out
+ *                       43 and 74 as defaults (see hylra_create_ex).
  *   "reuse_variant"     Reuse gather kernel: 1 / 2 = vector-ALU kernel with streaming / plain
  *                       loads, 3 / 4 = first matrix-core kernel with streaming / plain loads
  *                       (default for head_dim 64: 4), 5 / 6 = second matrix-core kernel
@@ -424,6 +429,8 @@ hylra_status hylra_policy_search(hylra_ctx *ctx, int32_t n_layers, const double 
  *   "reuse_waves"       waves per workgroup of the matrix-core Reuse kernel: 4 or 8
  *   "reuse_unfused"     1 = merge the Reuse partials in a second kernel instead of in the
  *                       last-arriving workgroup of the Reuse kernel
+ *   "simulate_give_up"  1 = mark the context as if a kernel had given up a bounded wait (for
+ *                       tests of that error path; see hylra_reset)
  *   "hist_unfused"      1 = the first histogram of the top-k selection is made by a launch of
  *                       its own instead of inside the Full layer's streaming kernel
  *   "full_unpaired"     1 = the self-scheduling Full kernels group their workgroups by number

@@ -39,8 +39,13 @@ def _load():
     global _lib
     with _lock:
         if _lib is None:
-            build(force=False)
-            lib = ctypes.CDLL(_LIB)
+            # HYLRA_ORACLE_LIB: a library built elsewhere from the same source (the sanitizer
+            # test builds one with -fsanitize=address,undefined)
+            path = os.environ.get("HYLRA_ORACLE_LIB")
+            if not path:
+                build(force=False)
+                path = _LIB
+            lib = ctypes.CDLL(path)
             vp, i32, i64, f64 = ctypes.c_void_p, ctypes.c_int, ctypes.c_long, ctypes.c_double
             lib.hylra_oracle_full_attn_topk.argtypes = [i32, i32, i32, i32, i32, i64, i32, f64,
                                                         vp, vp, vp, vp, vp, vp]

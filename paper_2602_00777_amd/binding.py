@@ -20,7 +20,7 @@ FLAG_DETERMINISTIC, FLAG_TOPK_EVERY_FULL_LAYER = 1, 2
 PROFILE_CLASSES = ("full_attn", "full_finalize", "reuse_attn", "reuse_combine", "probe")
 
 EXPORTS = (
-    "hylra_create", "hylra_create_ex", "hylra_destroy", "hylra_status_str", "hylra_last_error",
+    "hylra_create", "hylra_create_ex", "hylra_destroy", "hylra_reset", "hylra_status_str", "hylra_last_error",
     "hylra_full_attn_topk", "hylra_reuse_sparse_attn", "hylra_decode_step",
     "hylra_reuse_sparse_attn_static",
     "hylra_full_attn_topk_blocks", "hylra_reuse_block_attn", "hylra_decode_step_blocks",
@@ -75,6 +75,7 @@ def load_library() -> ctypes.CDLL:
     lib.hylra_create.argtypes = [ctypes.POINTER(vp), sp, i32, ctypes.c_int]
     lib.hylra_create_ex.argtypes = [ctypes.POINTER(vp), sp, i32, ctypes.c_int, ctypes.c_uint32]
     lib.hylra_destroy.argtypes = [vp]
+    lib.hylra_reset.argtypes = [vp]
     lib.hylra_status_str.argtypes = [ctypes.c_int]
     lib.hylra_status_str.restype = ctypes.c_char_p
     lib.hylra_last_error.argtypes = [vp]
@@ -638,6 +639,9 @@ class Context:
         return outs, idx_buf
 
     # -- knobs and measurement aids ----------------------------------------------------------
+    def reset(self):
+        self._check(self._lib.hylra_reset(self._h), "hylra_reset")
+
     def set_option(self, name: str, value: int):
         self._check(self._lib.hylra_set_option(self._h, name.encode(), int(value)), "hylra_set_option")
 

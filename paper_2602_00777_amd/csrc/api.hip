@@ -92,8 +92,11 @@ struct hylra_ctx {
     float* bscores = nullptr;   // block scores of the block-level variant (blocks of >= 2 rows)
     int* counters = nullptr;    // one arrival counter per (batch, KV head), zero between launches
     int* chunk_ctr = nullptr;   // chunk counters of the self-scheduling Full kernel (kCtrStride ints apart)
+    int* err_word = nullptr;    // pinned host memory the kernels can write: non-zero = a launch of this context
+                                // gave up a bounded wait; its results and the counters cannot be trusted
     int* sel_ws = nullptr;      // selection scratch (see TopkParams and hylra_create_ex)
     int max_chunks = 0;         // chunks of 8192 rows per (batch, KV head) at the maximum context
+    int64_t sel_ints = 0;       // ints in sel_ws
     int32_t* lens_plus = nullptr;   // [max batch] sequence lengths after an append (see append_impl)
     int4* wg_map = nullptr;     // deal of the Full kernel's workgroups to sequences of different lengths
     int2* pair_map = nullptr;   // (see RaggedPlanParams): `slots` and `pairs_cap` entries
@@ -112,7 +115,6 @@ struct hylra_ctx {
     int32_t opt_full_split_rows = 0;
     int32_t opt_reuse_split_rows = 0;
     int32_t opt_full_variant = 0;
-    int32_t opt_full_split_rot = 0;
     int32_t opt_reuse_variant = 0;
     int32_t opt_reuse_unroll = 0;
     int32_t opt_reuse_waves = 0;
@@ -172,6 +174,9 @@ struct Strides {
 // Shape checks shared by every entry point.  Fills G and the effective strides.
 hylra_status check_shape(const hylra_ctx* ctx, const hylra_shape* s, int& G, Strides& st, float& scale) {
     if (!ctx) return HYLRA_ERR_BAD_ARG;
+    if (ctx->err_word && *(volatile int*)ctx->err_word)
+        return fail(ctx, HYLRA_ERR_HIP, "an earlier launch of this context gave up waiting for rows to be handed out: "
+                                        "its results are incomplete; call hylra_reset");
     if (!s) return fail(ctx, HYLRA_ERR_BAD_ARG, "shape is NULL");
     if (s->batch < 1 || s->n_q_heads < 1 || s->n_kv_heads < 1 || s->ctx_len < 1)
         return fail(ctx, HYLRA_ERR_BAD_ARG, "batch, head counts and ctx_len must be >= 1");
@@ -294,27 +299,6 @@ struct FullPlan {
     int rows_per_split, n_splits, variant;
     int n_segs, wgs_per_seg;        // self-scheduling kernel: n_splits = n_segs * wgs_per_seg
 };
-
-// Chunk table of the self-scheduling Full kernel (guided self-scheduling): with `remaining`
-// tiles left, the next chunk takes remaining / (2 * S) of them, never fewer than min_tiles
-// (one tile per wave), so chunks shrink towards the end and the S workgroups of a (batch,
-// KV head) finish within about one small chunk of each other.  Returns the number of chunks.
-int make_chunk_table(int total_tiles, int S, int (&chunk_tile)[kMaxChunks + 1]) {
-    for (int min_tiles = 4;; min_tiles *= 2) {
-        int n = 0, at = 0;
-        while (at < total_tiles && n < kMaxChunks) {
-            int take = (int)ceil_div(total_tiles - at, 2 * (int64_t)S);
-            if (take < min_tiles) take = min_tiles;
-            if (take > total_tiles - at) take = total_tiles - at;
-            chunk_tile[n++] = at;
-            at += take;
-        }
-        if (at == total_tiles) {
-            chunk_tile[n] = total_tiles;
-            return n;
-        }
-    }
-}
 
 // Workgroups per (batch, KV head) of a self-scheduling Full kernel whose wave tile has `tile`
 // rows, and the segments they form.  Only the number of workgroups is planned (rows are handed
@@ -550,11 +534,14 @@ hylra_status hylra_create_ex(hylra_ctx** out, const hylra_shape* max_shape, int3
     // 8192 rows its counts and its list of rows in the threshold bin
     ctx->max_chunks = (int)ceil_div(max_shape->ctx_len, kTopkChunkRows);
     const int64_t sel_ints = pairs * (4096 + 2 + (int64_t)ctx->max_chunks * (2 + 2 * kTopkChunkList));
+    ctx->sel_ints = sel_ints;
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->sel_ws, sel_ints * sizeof(int));
     if (e == hipSuccess) e = hipMemset(ctx->sel_ws, 0, sel_ints * sizeof(int));
     // one counter per (pair, segment); there are never more segments than partial slots
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->chunk_ctr, ctx->slots * kCtrStride * sizeof(int));
     if (e == hipSuccess) e = hipMemset(ctx->chunk_ctr, 0, ctx->slots * kCtrStride * sizeof(int));
+    if (e == hipSuccess) e = hipHostMalloc((void**)&ctx->err_word, 64, hipHostMallocDefault);
+    if (e == hipSuccess) *ctx->err_word = 0;
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->wg_map, ctx->slots * sizeof(int4));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->pair_map, pairs * sizeof(int2));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->lens_plus, (size_t)max_shape->batch * sizeof(int32_t));
@@ -587,11 +574,25 @@ hylra_status hylra_destroy(hylra_ctx* ctx) {
     if (ctx->bscores) (void)hipFree(ctx->bscores);
     if (ctx->counters) (void)hipFree(ctx->counters);
     if (ctx->chunk_ctr) (void)hipFree(ctx->chunk_ctr);
+    if (ctx->err_word) (void)hipHostFree(ctx->err_word);
     if (ctx->sel_ws) (void)hipFree(ctx->sel_ws);
     if (ctx->wg_map) (void)hipFree(ctx->wg_map);
     if (ctx->pair_map) (void)hipFree(ctx->pair_map);
     if (ctx->lens_plus) (void)hipFree(ctx->lens_plus);
     delete ctx;
+    return HYLRA_OK;
+}
+
+hylra_status hylra_reset(hylra_ctx* ctx) {
+    if (!ctx) return HYLRA_ERR_BAD_ARG;
+    DeviceGuard guard(ctx->device);
+    HIP_TRY(ctx, hipDeviceSynchronize());
+    HIP_TRY(ctx, hipMemset(ctx->counters, 0, ctx->slots * sizeof(int)));
+    HIP_TRY(ctx, hipMemset(ctx->chunk_ctr, 0, ctx->slots * kCtrStride * sizeof(int)));
+    HIP_TRY(ctx, hipMemset(ctx->sel_ws, 0, ctx->sel_ints * sizeof(int)));
+    HIP_TRY(ctx, hipDeviceSynchronize());
+    ctx->in_step = false, ctx->step_planned = false;
+    if (ctx->err_word) *ctx->err_word = 0;
     return HYLRA_OK;
 }
 
@@ -601,7 +602,6 @@ hylra_status hylra_set_option(hylra_ctx* ctx, const char* name, int32_t value) {
     if (!std::strcmp(name, "full_split_rows")) ctx->opt_full_split_rows = value;
     else if (!std::strcmp(name, "reuse_split_rows")) ctx->opt_reuse_split_rows = value;
     else if (!std::strcmp(name, "full_variant")) ctx->opt_full_variant = value;
-    else if (!std::strcmp(name, "full_split_rot")) ctx->opt_full_split_rot = value;
     else if (!std::strcmp(name, "reuse_variant")) ctx->opt_reuse_variant = value;
     else if (!std::strcmp(name, "reuse_unroll")) ctx->opt_reuse_unroll = value;
     else if (!std::strcmp(name, "reuse_waves")) ctx->opt_reuse_waves = value;
@@ -609,6 +609,9 @@ hylra_status hylra_set_option(hylra_ctx* ctx, const char* name, int32_t value) {
     else if (!std::strcmp(name, "ragged_even")) ctx->opt_ragged_even = value;
     else if (!std::strcmp(name, "full_unpaired")) ctx->opt_full_unpaired = value;
     else if (!std::strcmp(name, "hist_unfused")) ctx->opt_hist_unfused = value;
+    else if (!std::strcmp(name, "simulate_give_up")) {      // what a kernel whose bounded wait ran out would report
+        if (ctx->err_word) *ctx->err_word = value ? 1 : 0;
+    }
     else return fail(ctx, HYLRA_ERR_BAD_ARG, "unknown option '%s'", name);
     return HYLRA_OK;
 }
@@ -662,7 +665,6 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
     // rows whose pages one workgroup can touch: its split, or (self-scheduling) its segment
     fp.tbl_cap = table_capacity(map, is_self_scheduling(pl.variant) ? ceil_div(shape->ctx_len, pl.n_segs) + 64 : pl.rows_per_split,
                                 pl.variant >= 50 && pl.variant < 70 ? 0 : (int64_t)pl.rows_per_split * 4);
-    fp.split_rot = ctx->opt_full_split_rot % pl.n_splits;
     fp.scale_log2 = scale * LOG2E_HOST;
     fp.scale_mean = scale / (float)G;
     fp.part_ml = ctx->part_ml, fp.part_acc = ctx->part_acc;
@@ -676,6 +678,7 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
     fp.score_stride = round_up(shape->ctx_len, 4);
     if (is_self_scheduling(pl.variant)) {
         fp.chunk_ctr = ctx->chunk_ctr;
+        fp.err_word = ctx->err_word;
         const int tile = full_block_quantum(shape->head_dim, G, pl.variant) / 4;     // rows of one wave tile
         fp.total_tiles = (int)ceil_div(shape->ctx_len, tile);
         fp.n_segs = pl.n_segs, fp.wgs_per_seg = pl.wgs_per_seg;
@@ -1270,12 +1273,7 @@ hylra_status hylra_overlap_counts(hylra_ctx* ctx, int32_t n_layers, const int32_
 
 hylra_status hylra_similarity_matrix(int32_t n_layers, const int64_t* counts, double* M) {
     if (n_layers < 1 || !counts || !M) return HYLRA_ERR_BAD_ARG;
-    const int64_t L = n_layers;
-    for (int64_t i = 0; i < L; ++i)
-        for (int64_t j = 0; j < L; ++j) {
-            const int64_t d = counts[j * L + j];
-            M[i * L + j] = i > j ? 0.0 : i == j ? 1.0 : d > 0 ? (double)counts[i * L + j] / (double)d : 0.0;
-        }
+    similarity_from_counts(n_layers, counts, M);
     return HYLRA_OK;
 }
 

@@ -26,6 +26,7 @@ struct ChunkQueue {
     int ticket;                     // next tile ticket of the workgroup
     int n_ready;                    // published slots
     int done;                       // no further slot will be published
+    int gave_up;                    // a wave's bounded wait for a slot ran out (reported to the host, see FullParams::err_word)
     int first[kMaxChunks + 2];      // first[i] = first ticket of slot i; first[n_ready] = end
     int tile0[kMaxChunks + 1];      // first tile (of the pair's tiles) of slot i
 };
@@ -68,6 +69,15 @@ struct QueueCursor {
     int slot, first, next, tile0;   // tickets first .. next - 1 are tiles tile0 .. of slot `slot`
 };
 
+// After the streaming loop (and a barrier): a workgroup in which a wave gave up waiting has
+// left rows out, and its segment's counter may not return to zero -- nothing of the launch can
+// be trusted.  The host is told through a word in pinned host memory that every later call on
+// the context looks at (hylra_reset clears it and the counters).
+DEVI void report_give_up(const ChunkQueue& cq, int* err_word) {
+    if (threadIdx.x == 0 && cq.gave_up && err_word)
+        __hip_atomic_store(err_word, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 // Next tile of the pair for the calling wave (every lane gets the same answer), or -1 when
 // the workgroup has none left.  Every wait here ends: a slot is published by a running wave
 // of this workgroup that waits for nothing but its own memory operations, and the spin is
@@ -92,6 +102,8 @@ DEVI TileRef next_tile(ChunkQueue& cq, int* __restrict__ ctr, QueueCursor& cur, 
             if (done) break;
             __builtin_amdgcn_s_sleep(2);
         }
+        if (!have && !lds_load(&cq.done) && lane == 0)
+            __hip_atomic_store(&cq.gave_up, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
         if (have) {
             while (T >= cur.next) {
                 ++cur.slot;
@@ -118,72 +130,10 @@ DEVI TileRef next_tile(ChunkQueue& cq, int* __restrict__ ctr, QueueCursor& cur, 
     return r;
 }
 
-// The workgroup's segment for its sequence: first tile, number of tiles, and the number of
-// tiles the host's chunk table was made for.  A full-length sequence has that many or one more
-// (the last chunk then runs to the segment's end).  A shorter one uses the end of the table:
-// guided self-scheduling cuts the next chunk from what remains, so the table's chunks from the
-// one that holds tile `off` = made_for - tiles on are the table of a segment of `tiles` tiles
-// (its first chunk clipped), with the same smallest chunk; the segment has n_eff chunks,
-// table entries c0 .. n_chunks - 1.
-struct SegInfo {
-    int tile0, tiles, made_for;
-    int wgs;                        // workgroups that serve the segment
-    int off, c0, n_eff;             // set by seg_chunks()
-};
-
-// Every thread calls this (the result is the same for all and lives in scalar registers).
-DEVI void seg_chunks(const FullParams& p, SegInfo& sg) {
-    sg.off = max(sg.made_for - sg.tiles, 0);
-    int lo = 0, hi = sg.off ? p.n_chunks : 0;       // largest c with chunk_tile[c] <= off (0 for a full-length sequence)
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (p.chunk_tile[mid] <= sg.off) lo = mid;
-        else hi = mid - 1;
-    }
-    sg.c0 = lo;
-    sg.n_eff = p.n_chunks - lo;
-}
-
-// Workgroup x of a grid of 2 * half workgroups -> the group of S workgroups (S even) it belongs
-// to and its rank there: group u is made of the S / 2 workgroups u * S / 2 .. of the first half
-// and of the S / 2 workgroups of the second half that sit one group further on (so that its
-// workgroups of the second half land on other XCDs than those of the first half).
-DEVI void paired_unit(int x, int half, int S, int& unit, int& w) {
-    const int h = S >> 1;
-    const int late = x >= half;
-    int r = x - (late ? half : 0);
-    if (late) r = r >= h ? r - h : r - h + half;
-    unit = r / h;
-    w = (late ? h : 0) + (r - unit * h);
-}
-
-// A pair that was dealt n workgroups of its own (sequences of different lengths): they form
-// max(1, n / S) segments of S .. 2 S - 1 workgroups each (fewer than S only when n < S), S being
-// the number of workgroups the chunk table was made for, so that a workgroup's first chunk
-// (1 / (2 S) of its segment) stays below its fair share.  For workgroup w of the pair: its
-// segment, its rank in it, the segment's workgroups and the rank of the segment's first one.
-struct PairSeg {
-    int seg, w, wgs, wg0;
-};
-DEVI PairSeg pair_segment(int n, int S, int w) {
-    const int n_seg = max(1, n / S), base = n / n_seg, extra = n - base * n_seg;   // `extra` segments have one more
-    PairSeg r;
-    if (w < extra * (base + 1)) {
-        r.seg = w / (base + 1), r.wgs = base + 1, r.wg0 = r.seg * (base + 1);
-    } else {
-        const int v = w - extra * (base + 1);
-        r.seg = extra + v / base, r.wgs = base, r.wg0 = extra * (base + 1) + (r.seg - extra) * base;
-    }
-    r.w = w - r.wg0;
-    return r;
-}
-
-// First tile (within the segment) of the segment's chunk c (0 .. n_eff - 1); chunk c is
-// [chunk_bound(c), chunk_bound(c + 1)).
-DEVI int chunk_bound(const FullParams& p, const SegInfo& sg, int c) {
-    if (c >= sg.n_eff) return sg.tiles;
-    return max(p.chunk_tile[sg.c0 + c] - sg.off, 0);
-}
+// Segment and chunk arithmetic: host_logic.h (SegInfo, seg_chunks, chunk_bound, pair_segment,
+// paired_unit), here bound to the launch's table.
+DEVI void seg_chunks(const FullParams& p, SegInfo& sg) { seg_chunks(p.chunk_tile, p.n_chunks, sg); }
+DEVI int chunk_bound(const FullParams& p, const SegInfo& sg, int c) { return chunk_bound(p.chunk_tile, sg, c); }
 
 // One lane only.  raw: what the segment's counter returned to a claim of this workgroup.
 // Returns the claimed chunk and its bounds, or -1 if the counter has run out.  Should a chunk

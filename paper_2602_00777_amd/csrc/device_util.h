@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "trace.h"
+
 #define DEVI __device__ __forceinline__
 
 namespace hylra {
@@ -90,8 +92,13 @@ DEVI void coherent_store(float* p, float v) {
 DEVI float coherent_load(const float* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// Wait until every vector memory operation this wave has issued is complete.
-DEVI void wait_vmem() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+// Wait until every vector memory operation this wave has issued is complete: s_waitcnt with
+// vmcnt = 0 and the other counters left alone.  The immediate's fields on gfx9: vmcnt low four
+// bits in [3:0] and its two high bits in [15:14]; expcnt in [6:4] (7 = do not wait); lgkmcnt in
+// [11:8] (15 = do not wait).
+constexpr int kWaitcntVm0 = (0 << 0) | (0 << 14) | (7 << 4) | (15 << 8);
+static_assert(kWaitcntVm0 == 0x0F70, "vmcnt(0), expcnt and lgkmcnt at their no-wait maxima");
+DEVI void wait_vmem() { __builtin_amdgcn_s_waitcnt(kWaitcntVm0); }
 
 // Rows of sequence b (see RowMap): clamped to 0..N.
 template <class MAP>
@@ -130,20 +137,6 @@ template <class MAP>
 DEVI int64_t paged_row_offset(const MAP& m, const int32_t* tbl, int row, int64_t sn) {
     return (int64_t)tbl[row >> m.page_shift] * m.stride_page + (int64_t)(row & ((1 << m.page_shift) - 1)) * sn;
 }
-
-// Phase timestamps for kernel tuning; compiled in only with -DHYLRA_TRACE (never in the
-// product build).  Slot s of workgroup w lands in trace[w * 16 + s] (100 MHz wall clock).
-#ifdef HYLRA_TRACE
-extern __device__ long long* g_trace;
-#define HYLRA_TS(slot)                                                                       \
-    do {                                                                                     \
-        if (threadIdx.x == 0 && g_trace)                                                     \
-            g_trace[((blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * 16 +  \
-                    (slot)] = wall_clock64();                                                \
-    } while (0)
-#else
-#define HYLRA_TS(slot) do { } while (0)
-#endif
 
 constexpr float NEG_BIG = -1.0e30f;   // "minus infinity" that stays finite under subtraction
 constexpr float LOG2E = 1.4426950408889634f;

@@ -1,18 +1,11 @@
 // Small kernels around the two layers: block maxima for the block-level TopK, the two-kernel
 // form of the Reuse merge, a zero fill, and the measurement kernels of the C ABI.
+#define HYLRA_TRACE_OWNER
 #include "device_util.h"
 #include "launch.h"
 #include "mfma_core.h"
 #include "select_util.h"
 
-#ifdef HYLRA_TRACE
-namespace hylra {
-__device__ long long* g_trace = nullptr;
-}
-extern "C" int hylra_debug_set_trace(void* device_buffer) {
-    return (int)hipMemcpyToSymbol(HIP_SYMBOL(hylra::g_trace), &device_buffer, sizeof(void*));
-}
-#endif
 
 namespace hylra {
 

@@ -14,9 +14,8 @@
 
 namespace hylra {
 
-// MODE 0: plain loads, one tile at a time.  MODE 1: streaming (non-temporal) loads.
-// MODE 2: streaming loads and a two-deep register pipeline -- the loads of tile i+1 are
-// issued before tile i is consumed, so every wave always has one to two tiles in flight.
+// MODE 2: streaming (non-temporal) loads and a two-deep register pipeline -- the loads of tile
+// i+1 are issued before tile i is consumed, so every wave always has one to two tiles in flight.
 //
 // The group-mean scores of the split are staged in LDS (rows_per_split floats of dynamic
 // shared memory) and written out once, after the loop.  Besides turning them into full
@@ -38,12 +37,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     using GEO = Geo<D, G, CH>;
     constexpr int NW = 4;
     constexpr int TILE = R * GEO::RPG;
-    constexpr bool NT = MODE >= 1;
+    constexpr bool NT = true;
     __shared__ float smem[merge_smem_floats<GEO, NW>()];
     __shared__ int s_hist[kScoreBins];
     extern __shared__ float s_scores[];          // [rows_per_split]
 
-    int split = (blockIdx.x + p.split_rot) % p.n_splits, g = blockIdx.y, b = blockIdx.z;
+    int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     int my_wgs = p.wgs_per_seg;                              // workgroups of this pair (self-scheduling mode)
     int64_t slot0 = ((int64_t)b * p.Hkv + g) * p.n_splits;   // the pair's first partial slot
     int mapped_rows = -1;
@@ -213,6 +212,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
             cq.tile0[0] = has ? sg.tile0 + lo : 0;
             cq.n_ready = 1;
             cq.done = has ? 0 : 1;
+            cq.gave_up = 0;
         }
         __syncthreads();
         QueueCursor qslot;
@@ -245,6 +245,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         }
         publish_claim(cq, p, ctr, pc, lane, sg);
         __syncthreads();
+        report_give_up(cq, p.err_word);
         // write the staged scores out: slot i of the queue is tiles tile0[i] .. of the pair,
         // tickets first[i] .. first[i + 1] - 1 (tile starts and the score stride are multiples
         // of 4 floats, so the 16-byte stores are aligned)
@@ -266,15 +267,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         }
     } else if (DYN || row0 >= row1) {
         // nothing to stream: an empty sequence, or a split past the end of a short one
-    } else if (MODE < 2) {
-        if (paged) stage_table(row0, row1 - 1);
-        for (int t0 = row0 + wave * TILE; t0 < row1; t0 += STEP) {
-            int64_t off[R];
-            TileBuf<GEO, R> buf;
-            offsets(t0, off);
-            load_tile<GEO, R, NT>(buf, Kb, Vb, off);
-            consume(buf, t0, t0 - row0);
-        }
     } else {
         if (paged) stage_table(row0, row1 - 1);
         TileBuf<GEO, R> bufA, bufB;
@@ -329,7 +321,7 @@ struct FullCfg {
 };
 
 // variant = 10 * MODE + R  (R = row groups per tile)
-#define HYLRA_FULL_VARIANTS(X) X(0, 4) X(1, 4) X(2, 3) X(4, 3) X(4, 2) X(2, 2)
+#define HYLRA_FULL_VARIANTS(X) X(2, 3) X(4, 3)
 constexpr int kDefaultFullVariant = 23;
 
 template <int D, int G>

@@ -135,7 +135,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
 }
 
 // variant = 10 * mode + NB: mode 5 = one tile at a time, mode 6 = two-deep register pipeline
-#define HYLRA_FULL_MFMA_VARIANTS(X) X(5, 4, false) X(5, 2, false) X(6, 2, true) X(6, 1, true)
+#define HYLRA_FULL_MFMA_VARIANTS(X) X(5, 2, false)
 
 template <int D, int G>
 static hipError_t launch_g(const FullParams& p, int B, int variant, hipStream_t st) {

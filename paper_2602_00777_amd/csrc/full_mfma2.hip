@@ -219,6 +219,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
             cq.tile0[0] = has ? sg.tile0 + lo : 0;
             cq.n_ready = 1;
             cq.done = has ? 0 : 1;
+            cq.gave_up = 0;
         }
         __syncthreads();
         QueueCursor cur;
@@ -253,6 +254,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         publish_claim(cq, p, ctr, pc, lane, sg);
         HYLRA_TS(1);
         __syncthreads();
+        report_give_up(cq, p.err_word);
         HYLRA_TS(2);
         // write the staged scores out: 8 threads per staged tile, 16 bytes each (tile starts and
         // the score stride are multiples of 4 floats, so the stores are aligned)

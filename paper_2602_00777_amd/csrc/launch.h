@@ -3,12 +3,13 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "host_logic.h"
+
 namespace hylra {
 
 constexpr int kMaxGroup = 8;        // query heads per KV head
 constexpr int kMaxSplits = 1024;    // partials per (batch, KV head) the finalise kernels accept
 constexpr int kMaxFullSplitRows = 8192;   // rows per workgroup of the vector Full kernel (its scores sit in LDS)
-constexpr int kMaxChunks = 480;     // chunks of rows per (batch, KV head) in the self-scheduling Full kernel
 constexpr int kCtrStride = 64;      // ints between the chunk counters of two (batch, KV head) pairs
 
 // Where the rows of the cache live and how many a sequence has (paged caches and
@@ -32,7 +33,6 @@ struct FullParams {
     int tbl_cap;                    // page-table entries a workgroup can stage in LDS (0 if not paged)
     int Hq, Hkv, N;
     int rows_per_split, n_splits;
-    int split_rot;                  // workgroup x handles split (x + split_rot) % n_splits
     float scale_log2;               // scale * log2(e)
     float scale_mean;               // scale / G
     float* part_ml;                 // [B*Hq][S][2]   (max in log2 units, sum)
@@ -49,6 +49,7 @@ struct FullParams {
     // workgroup w of the segment starts on chunk w, further chunks are claimed from the
     // segment's counter.
     int* chunk_ctr;                 // [B*Hkv][n_segs] counters, kCtrStride ints apart, zero between launches
+    int* err_word;                  // pinned host memory (or nullptr): set to 1 if a wave's bounded wait ran out
     int n_segs, wgs_per_seg, total_tiles;
     // Sequences of different lengths (n_segs == 1 only): the workgroups of the launch are
     // dealt out to the (batch, KV head) pairs in proportion to their rows by a small kernel
@@ -205,7 +206,7 @@ int reuse_block_quantum_d128(int G, int variant, int R);
 hipError_t launch_reuse_split_d64(const ReuseParams& p, int B, int G, int variant, int R, hipStream_t st);
 hipError_t launch_reuse_split_d128(const ReuseParams& p, int B, int G, int variant, int R, hipStream_t st);
 
-// Matrix-core Full kernel (full_mfma.hip): variants 54, 52 (one tile at a time), 62, 61 (pipelined)
+// Matrix-core Full kernel (full_mfma.hip): variant 52
 int full_mfma_quantum(int variant);
 hipError_t launch_full_mfma(const FullParams& p, int B, int D, int G, int variant, hipStream_t st);
 
@@ -243,7 +244,6 @@ hipError_t launch_reuse_mfma2(const ReuseParams& p, int B, int G, bool nt, int N
 
 hipError_t launch_gather_rows(const GatherParams& p, int B, hipStream_t st);
 hipError_t launch_overlap_counts(const OverlapParams& p, int B, hipStream_t st);
-int policy_search_host(int L, const double* M, double theta, uint8_t* policy, double* sum_sim);
 
 hipError_t launch_block_max(const BlockMaxParams& p, int B, int Hkv, hipStream_t st);
 hipError_t launch_combine(const CombineParams& p, int n_heads_total, hipStream_t st);

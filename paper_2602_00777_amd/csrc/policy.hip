@@ -64,49 +64,4 @@ hipError_t launch_overlap_counts(const OverlapParams& p, int B, hipStream_t st) 
     return hipGetLastError();
 }
 
-// Algorithm 1.  A state (i, j), i <= j: layer j uses the index set of layer i (i == j: full
-// attention at layer j).  Layer by layer, every state keeps the best value of a path that
-// reaches it: fewest Full layers first, then the largest sum of similarities; a later candidate
-// replaces it only if strictly better (candidates arrive in the order of the algorithm's
-// loops).  Returns the number of Full layers of the best path.
-int policy_search_host(int L, const double* M, double theta, uint8_t* policy, double* sum_sim) {
-    struct Val {
-        int full = -1;          // -1: not reachable
-        double sim = 0.0;
-        int from = -1;          // source layer of the state this one was reached from
-        bool better_than(const Val& o) const { return o.full < 0 || full < o.full || (full == o.full && sim > o.sim); }
-    };
-    // column j of the state grid: states (0..j, j)
-    std::vector<std::vector<Val>> col(L);
-    col[0].resize(1);
-    col[0][0].full = 1, col[0][0].sim = M[0];
-    for (int j = 1; j < L; ++j) {
-        col[j].resize(j + 1);
-        const double diag = M[(size_t)j * L + j];
-        for (int i = 0; i < j; ++i) {
-            const Val& v = col[j - 1][i];
-            if (v.full < 0) continue;
-            const double m = M[(size_t)i * L + j];
-            if (m >= theta) {                               // index reuse: (i, j-1) -> (i, j)
-                Val c;
-                c.full = v.full, c.sim = v.sim + m, c.from = i;
-                if (c.better_than(col[j][i])) col[j][i] = c;
-            }
-            Val c;                                          // full attention: (i, j-1) -> (j, j)
-            c.full = v.full + 1, c.sim = v.sim + diag, c.from = i;
-            if (c.better_than(col[j][j])) col[j][j] = c;
-        }
-    }
-    int best = -1;
-    for (int i = 0; i < L; ++i)
-        if (col[L - 1][i].full >= 0 && (best < 0 || col[L - 1][i].better_than(col[L - 1][best]))) best = i;
-    if (sum_sim) *sum_sim = col[L - 1][best].sim;
-    const int n_full = col[L - 1][best].full;
-    for (int j = L - 1, i = best; j >= 0; --j) {
-        policy[j] = i == j ? 0 : 1;
-        i = col[j][i].from;
-    }
-    return n_full;
-}
-
 }  // namespace hylra

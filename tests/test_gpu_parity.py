@@ -59,7 +59,7 @@ def test_full_attn_topk_matches_oracle(B, Hkv, G, d, N, k):
     assert_idx_valid(idx, shat, k, "full idx", exact_ref=ref_idx)
 
 
-@pytest.mark.parametrize("variant", [4, 14, 23, 22, 43, 42, 54, 52, 62, 61, 72, 74])
+@pytest.mark.parametrize("variant", [23, 43, 52, 72, 74])
 def test_full_kernel_variants(variant):
     say("full variant=%d" % variant)
     B, Hkv, G, d, N, k = 2, 2, 4, 128, 5003, 300
@@ -491,6 +491,13 @@ def test_error_codes():
         with pytest.raises(binding.HylraError) as e:
             ctx.full_attn_topk(q2, K2, V2, k)
         assert e.value.status == 3
+        # a launch that gave up a bounded wait (simulated from the host): every call fails until reset
+        ctx.set_option("simulate_give_up", 1)
+        for call in (lambda: ctx.full_attn_topk(q, K, V, k), lambda: ctx.reuse_sparse_attn(q, K, V, torch.zeros((B, Hkv, k), dtype=torch.int32, device=DEV))):
+            with pytest.raises(binding.HylraError) as e:
+                call()
+            assert e.value.status == 5 and "hylra_reset" in str(e.value)
+        ctx.reset()
         # the context still works after failed calls
         out, idx = run_full(ctx, q, K, V, k)
     ref_out, ref_idx, shat = oracle.full_attn_topk(q, K, V, k, want_shat=True)
