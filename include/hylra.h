@@ -357,6 +357,10 @@ hylra_status hylra_decode_step_offloaded_blocks(hylra_ctx *ctx, const hylra_shap
  * hylra_decode_step_append every layer l gets its own k_new_l[l], v_new_l[l] (HOST arrays of
  * DEVICE pointers) written into its own cache before the layer's attention.  A Reuse layer
  * attends to the inherited set as it is (the new row takes part if the set names it).
+ * Launches: the Reuse form is ONE launch -- the matrix-core Reuse kernels read the new row from
+ * k_new / v_new wherever the set names it and write it into the cache themselves (option
+ * "append_unfused" = 1, and the vector Reuse kernel always: a small launch writes the rows
+ * first); the Full form is that small launch followed by the Full layer's own launches.
  */
 hylra_status hylra_append_full_attn_topk(hylra_ctx *ctx, const hylra_shape *shape,
                                          const hylra_paged *cache, const void *q,
@@ -431,6 +435,9 @@ hylra_status hylra_policy_search(hylra_ctx *ctx, int32_t n_layers, const double 
  *                       last-arriving workgroup of the Reuse kernel
  *   "simulate_give_up"  1 = mark the context as if a kernel had given up a bounded wait (for
  *                       tests of that error path; see hylra_reset)
+ *   "append_unfused"    1 = hylra_append_reuse_sparse_attn and the Reuse layers of
+ *                       hylra_decode_step_append write the new rows with a launch of their own
+ *                       instead of inside the Reuse kernel
  *   "hist_unfused"      1 = the first histogram of the top-k selection is made by a launch of
  *                       its own instead of inside the Full layer's streaming kernel
  *   "full_unpaired"     1 = the self-scheduling Full kernels group their workgroups by number

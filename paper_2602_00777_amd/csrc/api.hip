@@ -122,6 +122,7 @@ struct hylra_ctx {
     int32_t opt_ragged_even = 0;
     int32_t opt_full_unpaired = 0;
     int32_t opt_hist_unfused = 0;
+    int32_t opt_append_unfused = 0;
 
     bool prof_on = false;
     int prof_n = 0;
@@ -609,6 +610,7 @@ hylra_status hylra_set_option(hylra_ctx* ctx, const char* name, int32_t value) {
     else if (!std::strcmp(name, "ragged_even")) ctx->opt_ragged_even = value;
     else if (!std::strcmp(name, "full_unpaired")) ctx->opt_full_unpaired = value;
     else if (!std::strcmp(name, "hist_unfused")) ctx->opt_hist_unfused = value;
+    else if (!std::strcmp(name, "append_unfused")) ctx->opt_append_unfused = value;
     else if (!std::strcmp(name, "simulate_give_up")) {      // what a kernel whose bounded wait ran out would report
         if (ctx->err_word) *ctx->err_word = value ? 1 : 0;
     }
@@ -623,6 +625,7 @@ namespace {
 hylra_status append_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* pg, const void* k_new,
                          const void* v_new, const void* K, const void* V, hylra_paged& eff, const hylra_paged** use,
                          void* hip_stream);
+hylra_status check_append_args(hylra_ctx* ctx, const void* k_new, const void* v_new, const void* K, const void* V);
 
 // Full layer.  block == 1: idx receives the k best rows.  block >= 2: idx receives the k best
 // blocks of `block` rows (a block scores the maximum of its rows).
@@ -759,7 +762,8 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
 // Reuse layer over n_idx inherited entries per (batch, KV head): rows (block == 1) or blocks.
 hylra_status reuse_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* pg, const void* q,
                         const void* K, const void* V, const int32_t* idx, int32_t block, int32_t n_idx,
-                        float* out, void* hip_stream, bool clear_counters = false) {
+                        float* out, void* hip_stream, bool clear_counters = false, const void* k_new = nullptr,
+                        const void* v_new = nullptr) {
     int G = 0;
     Strides sd{};
     float scale = 0.f;
@@ -777,10 +781,22 @@ hylra_status reuse_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pa
     ReusePlan pl{};
     if ((rc = plan_reuse(ctx, shape, G, k, pl)) != HYLRA_OK) return rc;
     if ((rc = check_workspace(ctx, shape, pl.n_splits, false)) != HYLRA_OK) return rc;
+    // k_new: the current token's rows go into the cache first.  The matrix-core kernels do that
+    // themselves (pg's lengths are then those before the call); for the vector kernel a launch of
+    // its own writes the rows and the "length + 1" array the attention then uses.
+    const bool append_fused = k_new && pl.variant >= 2 && ctx->opt_append_unfused == 0;
+    if (k_new && !append_fused) {
+        hylra_paged eff{};
+        const hylra_paged* use = nullptr;
+        if ((rc = append_impl(ctx, shape, pg, k_new, v_new, K, V, eff, &use, hip_stream)) != HYLRA_OK) return rc;
+        if (use && use->seq_lens) map.seq_lens = use->seq_lens;
+    }
+    if (append_fused && (rc = check_append_args(ctx, k_new, v_new, K, V)) != HYLRA_OK) return rc;
 
     hipStream_t st = (hipStream_t)hip_stream;
     DeviceGuard guard(ctx->device);
     ReuseParams rp{};
+    if (append_fused) rp.k_new = (const uint16_t*)k_new, rp.v_new = (const uint16_t*)v_new;
     rp.q = (const uint16_t*)q;
     rp.K = (const uint16_t*)K;
     rp.V = (const uint16_t*)V;
@@ -846,13 +862,16 @@ hylra_status step_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
                               (ctx->flags & HYLRA_FLAG_TOPK_EVERY_FULL_LAYER);
         // with new rows: the layer's cache first receives the current token (every layer writes the
         // same "length + 1" array, so the deal of workgroups made at the first layer stays valid)
+        // (a Reuse layer takes the rows along in its own launch: see reuse_impl)
         hylra_paged eff{};
         const hylra_paged* use = pg;
-        if (k_new_l && (rc = append_impl(ctx, shape, pg, k_new_l[l], v_new_l[l], K_l[l], V_l[l], eff, &use, hip_stream)) != HYLRA_OK)
+        if (k_new_l && policy[l] == HYLRA_FULL &&
+            (rc = append_impl(ctx, shape, pg, k_new_l[l], v_new_l[l], K_l[l], V_l[l], eff, &use, hip_stream)) != HYLRA_OK)
             break;
         rc = policy[l] == HYLRA_FULL
                  ? full_impl(ctx, shape, use, q_l[l], K_l[l], V_l[l], block, k, out_l[l], idx_buf, hip_stream, want_idx)
-                 : reuse_impl(ctx, shape, use, q_l[l], K_l[l], V_l[l], idx_buf, block, k, out_l[l], hip_stream);
+                 : reuse_impl(ctx, shape, pg, q_l[l], K_l[l], V_l[l], idx_buf, block, k, out_l[l], hip_stream, false,
+                              k_new_l ? k_new_l[l] : nullptr, k_new_l ? v_new_l[l] : nullptr);
     }
     ctx->in_step = false;
     return rc;
@@ -1044,6 +1063,13 @@ hylra_status gather_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_p
     return HYLRA_OK;
 }
 
+hylra_status check_append_args(hylra_ctx* ctx, const void* k_new, const void* v_new, const void* K, const void* V) {
+    if (!k_new || !v_new || !K || !V) return fail(ctx, HYLRA_ERR_BAD_ARG, "k_new, v_new, K and V must not be NULL");
+    if (((uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)K | (uintptr_t)V) & 15)
+        return fail(ctx, HYLRA_ERR_BAD_ARG, "k_new, v_new, K and V must be 16-byte aligned");
+    return HYLRA_OK;
+}
+
 // The current token's key / value rows into the cache, behind the rows every sequence has.
 // Fills eff (and sets *use) with the cache description the attention that follows must use:
 // the caller's, with the lengths replaced by the context's own "length + 1" array.
@@ -1057,9 +1083,7 @@ hylra_status append_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_p
     hylra_status rc = check_shape(ctx, shape, G, sd, scale);
     if (rc != HYLRA_OK) return rc;
     if ((rc = check_paged(ctx, shape, pg, sd, map)) != HYLRA_OK) return rc;
-    if (!k_new || !v_new || !K || !V) return fail(ctx, HYLRA_ERR_BAD_ARG, "k_new, v_new, K and V must not be NULL");
-    if (((uintptr_t)k_new | (uintptr_t)v_new | (uintptr_t)K | (uintptr_t)V) & 15)
-        return fail(ctx, HYLRA_ERR_BAD_ARG, "k_new, v_new, K and V must be 16-byte aligned");
+    if ((rc = check_append_args(ctx, k_new, v_new, K, V)) != HYLRA_OK) return rc;
     if (shape->batch > ctx->max_shape.batch)
         return fail(ctx, HYLRA_ERR_WORKSPACE, "batch = %d exceeds the context's %d", shape->batch, ctx->max_shape.batch);
     AppendParams ap{};
@@ -1111,11 +1135,8 @@ hylra_status hylra_append_reuse_sparse_attn(hylra_ctx* ctx, const hylra_shape* s
                                             const void* q, const void* k_new, const void* v_new, void* K, void* V,
                                             const int32_t* idx, int32_t k, float* out, void* hip_stream) {
     if (!ctx) return HYLRA_ERR_BAD_ARG;
-    hylra_paged eff{};
-    const hylra_paged* use = nullptr;
-    const hylra_status rc = append_impl(ctx, shape, cache, k_new, v_new, K, V, eff, &use, hip_stream);
-    if (rc != HYLRA_OK) return rc;
-    return reuse_impl(ctx, shape, use, q, K, V, idx, 1, k, out, hip_stream);
+    if (!k_new || !v_new) return fail(ctx, HYLRA_ERR_BAD_ARG, "k_new, v_new, K and V must not be NULL");
+    return reuse_impl(ctx, shape, cache, q, K, V, idx, 1, k, out, hip_stream, false, k_new, v_new);
 }
 
 hylra_status hylra_decode_step_append(hylra_ctx* ctx, const hylra_shape* shape, const hylra_paged* cache,

@@ -123,6 +123,11 @@ struct ReuseParams {
     int* counters;                  // [B*Hkv] arrival counters, all zero between launches;
                                     // nullptr: do not merge in this kernel
     float* out;                     // [B][Hq][D], written by the merging workgroup
+    // Append-then-attend in one launch (matrix-core kernels only; see reuse_tail.h): the current
+    // token's rows [B][Hkv][D], or nullptr.  Then map.seq_lens holds the lengths BEFORE the call
+    // (nullptr: N - 1 everywhere) and K, V receive one row per (batch, KV head).
+    const uint16_t* k_new;
+    const uint16_t* v_new;
 };
 
 // Block-level TopK: scores of blocks of `block` consecutive rows = maximum of the rows' scores.

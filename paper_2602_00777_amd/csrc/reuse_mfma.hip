@@ -44,16 +44,19 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 
     // rows of this sequence (entries that name a row beyond them are padding); with none,
     // nothing is loaded
-    const int n_rows = seq_rows(p.map, b, p.N);
+    int n_rows = seq_rows(p.map, b, p.N);
+    const int64_t pair = (int64_t)b * p.Hkv + g;
+    const NewRow nr = reuse_new_row<D>(p, b, pair, n_rows);
     const int i0 = split * p.rows_per_split;
     const int i1 = n_rows > 0 ? min(p.k, i0 + p.rows_per_split) : i0;
-    const int64_t pair = (int64_t)b * p.Hkv + g;
     const int64_t head0 = (int64_t)b * p.Hq + (int64_t)g * G;
     const int32_t* __restrict__ ib = p.idx + pair * p.idx_stride;
     const int32_t* __restrict__ tbl = p.map.table ? p.map.table + (int64_t)b * p.map.table_stride : nullptr;
     const int64_t base = (tbl ? 0 : (int64_t)b * p.sb) + (int64_t)g * p.sh;
     const uint16_t* __restrict__ Kb = p.K + base;
     const uint16_t* __restrict__ Vb = p.V + base;
+
+    reuse_store_new_row<D>(p, nr, tbl, Kb, Vb, split, tid);
 
     HYLRA_TS(0);
     // the index loads head the longest dependent chain (index -> row -> softmax): issue first
@@ -77,11 +80,15 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 #pragma unroll
         for (int blk = 0; blk < NB; ++blk) {
             valid[blk] = (unsigned)row[blk] < (unsigned)n_rows;    // negative or past the sequence: padding
-            const int64_t off = reuse_row_offset(p, tbl, valid[blk] ? row[blk] : 0) + 8 * gq;
+            const int r = valid[blk] ? row[blk] : 0;
+            const int64_t off = reuse_row_offset(p, tbl, r);
+            // (the token being appended is not in the cache yet)
+            const uint16_t* kp = (r == nr.row ? nr.k : Kb + off) + 8 * gq;
+            const uint16_t* vp = (r == nr.row ? nr.v : Vb + off) + 8 * gq;
 #pragma unroll
-            for (int i = 0; i < KI; ++i) kb[blk][i] = ld16<NT>(Kb + off + 32 * i);
+            for (int i = 0; i < KI; ++i) kb[blk][i] = ld16<NT>(kp + 32 * i);
 #pragma unroll
-            for (int i = 0; i < KI; ++i) vb[blk][i] = ld16<NT>(Vb + off + 32 * i);
+            for (int i = 0; i < KI; ++i) vb[blk][i] = ld16<NT>(vp + 32 * i);
         }
         t0 += NW * ROWS_W;
         if (t0 < i1) {

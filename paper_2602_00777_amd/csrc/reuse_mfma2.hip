@@ -23,10 +23,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 
     // rows of this sequence (entries that name a row beyond them are padding); with none,
     // nothing is loaded
-    const int n_rows = seq_rows(p.map, b, p.N);
+    int n_rows = seq_rows(p.map, b, p.N);
+    const int64_t pair = (int64_t)b * p.Hkv + g;
+    const NewRow nr = reuse_new_row<D>(p, b, pair, n_rows);
     const int i0 = split * p.rows_per_split;
     const int i1 = n_rows > 0 ? min(p.k, i0 + p.rows_per_split) : i0;
-    const int64_t pair = (int64_t)b * p.Hkv + g;
     const int64_t head0 = (int64_t)b * p.Hq + (int64_t)g * G;
     const int32_t* __restrict__ ib = p.idx + pair * p.idx_stride;
     const int32_t* __restrict__ tbl = p.map.table ? p.map.table + (int64_t)b * p.map.table_stride : nullptr;
@@ -40,6 +41,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
         return tbl ? (int64_t)(pr >> p.map.page_shift) * p.map.stride_page + (int64_t)(pr & page_mask) * p.sn
                    : (int64_t)pr * p.sn;
     };
+    // a negative place stands for the token being appended, whose rows are not in the cache yet
+    auto k_at = [&](int pr) -> const uint16_t* { return pr < 0 ? nr.k : Kb + place(pr); };
+    auto v_at = [&](int pr) -> const uint16_t* { return pr < 0 ? nr.v : Vb + place(pr); };
+    reuse_store_new_row<D>(p, nr, tbl, Kb, Vb, split, tid);
 
     HYLRA_TS(0);
     // the index loads head the longest dependent chain (index -> row -> softmax): issue first
@@ -66,25 +71,25 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
             // slot in a paged one (one page-table lookup per row; the lanes below that fetch
             // pieces of other lanes' rows get this number from them, not from the table).
             const int r = valid[blk] ? row[blk] : 0;
-            const int pr = tbl ? (tbl[r >> p.map.page_shift] << p.map.page_shift) | (r & page_mask) : r;
+            const int pr = r == nr.row ? -1 : tbl ? (tbl[r >> p.map.page_shift] << p.map.page_shift) | (r & page_mask) : r;
             // K: lanes n and n ^ 8 read the two halves of a 128-byte line of one row (row n & 7
             // of the block in the first load of a line, row 8 + (n & 7) in the second), so that
             // eight lanes cover a whole line; own_row() afterwards hands every lane the pieces of
             // its own row n.
             const int ra = rotate_in<0xC>(pr, pr);                  // lanes 8..15: from lane n - 8
             const int rb = rotate_in<0x3>(pr, pr);                  // lanes 0..7: from lane n + 8
-            const int64_t offa = place(ra) + 32 * (n >> 3) + 8 * gq;
-            const int64_t offb = place(rb) + 32 * (n >> 3) + 8 * gq;
+            const uint16_t* pa = k_at(ra) + 32 * (n >> 3) + 8 * gq;
+            const uint16_t* pb = k_at(rb) + 32 * (n >> 3) + 8 * gq;
 #pragma unroll
             for (int L = 0; L < 2; ++L) {
-                kb[blk][2 * L] = ld16<NT>(Kb + offa + 64 * L);
-                kb[blk][2 * L + 1] = ld16<NT>(Kb + offb + 64 * L);
+                kb[blk][2 * L] = ld16<NT>(pa + 64 * L);
+                kb[blk][2 * L + 1] = ld16<NT>(pb + 64 * L);
             }
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 // row 4 gq + j of the block: its place sits in lane 4 gq + j
                 const int rv = __shfl(pr, 4 * gq + j, 64);
-                vb[blk][j] = ld16<NT>(Vb + place(rv) + 8 * n);
+                vb[blk][j] = ld16<NT>(v_at(rv) + 8 * n);
             }
         }
         t0 += NW * ROWS_W;

@@ -58,6 +58,42 @@ DEVI int64_t reuse_row_offset(const ReuseParams& p, const int32_t* __restrict__ 
     return tbl ? paged_row_offset(p.map, tbl, row, p.sn) : (int64_t)row * p.sn;
 }
 
+// Append-then-attend in one launch (Algorithm 2 takes the caches with the current token in
+// them).  The token's key / value rows, one per (batch, KV head), are not in the cache when
+// the launch starts: every lane whose entry names the token's position reads k_new / v_new
+// instead of the cache, and the pair's first workgroup writes the two rows into the cache for
+// the launches that follow -- nothing in this launch reads what it writes.  row: the token's
+// position = the sequence's length before the call, clamped to 0 .. N - 1 (-1: no append).
+struct NewRow {
+    int row;
+    const uint16_t* k;      // the pair's new key / value row
+    const uint16_t* v;
+};
+// n_rows: in, the rows of the sequence by p.map; out, the rows the attention covers.
+template <int D>
+DEVI NewRow reuse_new_row(const ReuseParams& p, int b, int64_t pair, int& n_rows) {
+    NewRow nr;
+    nr.row = -1, nr.k = nullptr, nr.v = nullptr;
+    if (p.k_new) {
+        nr.row = min(p.map.seq_lens ? n_rows : p.N - 1, p.N - 1);
+        nr.k = p.k_new + pair * D, nr.v = p.v_new + pair * D;
+        n_rows = nr.row + 1;
+    }
+    return nr;
+}
+// Kb / Vb: the kernel's K / V base of this (batch, KV head); threads 0 .. D/4 - 1 of the pair's
+// first workgroup copy 16 bytes each.
+template <int D>
+DEVI void reuse_store_new_row(const ReuseParams& p, const NewRow& nr, const int32_t* __restrict__ tbl,
+                              const uint16_t* Kb, const uint16_t* Vb, int split, int tid) {
+    if (nr.row < 0 || split != 0 || tid >= D / 4) return;
+    const int piece = tid % (D / 8);
+    const bool is_v = tid >= D / 8;
+    const int64_t off = reuse_row_offset(p, tbl, nr.row) + 8 * piece;
+    uint16_t* dst = const_cast<uint16_t*>(is_v ? Vb : Kb) + off;
+    *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>((is_v ? nr.v : nr.k) + 8 * piece);
+}
+
 // Every thread of the workgroup (NT threads) calls this after its partial stores were issued.
 template <int G, int D, int NT>
 DEVI void reuse_merge_tail(const ReuseParams& p, int64_t pair, int64_t head0, int* s_last) {

@@ -68,13 +68,18 @@ def test_append_contiguous_equal_lengths(B, Hkv, G, d, N, k):
         check_full(out, idx, refs, k, "append full")
         # the new row is among the selected ones (its key was pushed along the query)
         assert np.all((idx == N - 1).any(axis=2))
-        # Reuse on a restored cache: same append, attention over the set just selected
-        Kc2, Vc2 = K.clone(), V.clone()
-        sparse = ctx.append_reuse_sparse_attn(q, k_new, v_new, Kc2, Vc2, torch.from_numpy(idx).to(DEV))
-        torch.cuda.synchronize()
-        assert np.array_equal(bits(Kc2), refs[0]) and np.array_equal(bits(Vc2), refs[1])
-    ref = oracle.reuse_sparse_attn(q.cpu(), refs[0], refs[1], idx)
-    assert_out_close(sparse.cpu().numpy(), ref, "append reuse")
+        # Reuse on a restored cache: same append, attention over the set just selected (which
+        # names the new row: it must be read from k_new / v_new, the restored cache holds another
+        # row there).  Once with the row written by the Reuse kernel itself, once by a launch of
+        # its own before it.
+        ref = oracle.reuse_sparse_attn(q.cpu(), refs[0], refs[1], idx)
+        for unfused in (0, 1):
+            ctx.set_option("append_unfused", unfused)
+            Kc2, Vc2 = K.clone(), V.clone()
+            sparse = ctx.append_reuse_sparse_attn(q, k_new, v_new, Kc2, Vc2, torch.from_numpy(idx).to(DEV))
+            torch.cuda.synchronize()
+            assert np.array_equal(bits(Kc2), refs[0]) and np.array_equal(bits(Vc2), refs[1])
+            assert_out_close(sparse.cpu().numpy(), ref, "append reuse, append_unfused=%d" % unfused)
 
 
 @pytest.mark.parametrize("page", [0, 16, 1])
@@ -108,11 +113,34 @@ def test_append_with_sequence_lengths(page):
             assert torch.equal(Vp.view(torch.int16), want_V.view(torch.int16))
         else:
             assert np.array_equal(bits(Kp), refs[0]) and np.array_equal(bits(Vp), refs[1])
+        # Reuse with the same append on restored caches, over the set just selected (sequence 1 was
+        # empty: its only row is the new one; the set of every sequence names its new row)
+        idx_d = idx
+        idx_h = idx.cpu().numpy()
+        for b in range(B):
+            assert np.all((idx_h[b] == lens[b]).any(axis=1)), "the new row of sequence %d is not selected" % b
+        for unfused in (0, 1):
+            ctx.set_option("append_unfused", unfused)
+            if page:
+                Kq, Vq = synth.to_pool(K, table, page), synth.to_pool(V, table, page)
+            else:
+                Kq, Vq = K.clone(), V.clone()
+            sparse = ctx.append_reuse_sparse_attn(q, k_new, v_new, Kq, Vq, idx_d, paged=cache)
+            torch.cuda.synchronize()
+            assert np.array_equal(lens_d.cpu().numpy(), lens), "the caller's lengths must not be written"
+            assert torch.equal(Kq.view(torch.int16), Kp.view(torch.int16)), "cache after append (K), append_unfused=%d" % unfused
+            assert torch.equal(Vq.view(torch.int16), Vp.view(torch.int16)), "cache after append (V), append_unfused=%d" % unfused
+            for b in range(B):
+                n = int(lens[b]) + 1
+                ref = oracle.reuse_sparse_attn(q[b:b + 1].cpu(), refs[0][b:b + 1, :, :n], refs[1][b:b + 1, :, :n], idx_h[b:b + 1])
+                assert_out_close(sparse[b:b + 1].cpu().numpy(), ref, "append reuse page=%d b=%d unfused=%d" % (page, b, unfused))
 
 
-def test_decode_step_append_chain():
-    """Algorithm 2 with every layer's cache receiving its own new row first (paged, ragged)."""
-    say("decode step with append")
+@pytest.mark.parametrize("unfused", [0, 1])
+def test_decode_step_append_chain(unfused):
+    """Algorithm 2 with every layer's cache receiving its own new row first (paged, ragged); the
+    Reuse layers write their row themselves (0) or a launch before them does (1)."""
+    say("decode step with append, append_unfused=%d" % unfused)
     B, Hkv, G, d, N, k, page, L = 3, 2, 4, 128, 3000, 256, 16, 5
     policy = np.array([0, 1, 1, 0, 1], np.uint8)
     lens = np.array([N - 1, 700, 2011], np.int32)
@@ -122,6 +150,7 @@ def test_decode_step_append_chain():
     pools = [(synth.to_pool(x[1], table, page), synth.to_pool(x[2], table, page)) for x in layers]
     cache = binding.PagedCache(torch.from_numpy(table).to(DEV), page, N, torch.from_numpy(lens).to(DEV))
     with binding.Context(B, Hkv * G, Hkv, d, N, k) as ctx:
+        ctx.set_option("append_unfused", unfused)
         outs, idx_buf = ctx.decode_step_append(policy, qs, [x[3] for x in layers], [x[4] for x in layers],
                                                [p[0] for p in pools], [p[1] for p in pools], k, paged=cache)
         torch.cuda.synchronize()
@@ -129,6 +158,9 @@ def test_decode_step_append_chain():
         for l in range(L):
             q, K, V, k_new, v_new = layers[l]
             refs = oracle_after_append(q, K, V, k_new, v_new, lens, k)
+            for which in (0, 1):         # the layer's pools: exactly the appended rows changed
+                want = synth.to_pool(torch.from_numpy(refs[which].view(np.int16)).view(torch.bfloat16).to(DEV), table, page)
+                assert torch.equal(pools[l][which].view(torch.int16), want.view(torch.int16)), "layer %d pool %d" % (l, which)
             if policy[l] == 0:
                 # the set in force: read by running the layer alone on the (already appended) pools
                 _, gidx = ctx.full_attn_topk_paged(q, pools[l][0], pools[l][1],
