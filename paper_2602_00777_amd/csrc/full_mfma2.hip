@@ -75,10 +75,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
     // the group-mean scores are neither formed nor written, nor is their range
     const bool want_scores = p.scores != nullptr;
     float* __restrict__ srow = want_scores ? p.scores + ((int64_t)b * p.Hkv + g) * p.score_stride : nullptr;
-    // the scores are also counted per top 12 bits of their key (score_hist.h); a barrier follows
-    // on every path before the first count
+    // the scores are also counted, as they are formed, per top 12 bits of their key
+    // (score_hist.h)
     const bool bins = want_scores && p.ghist != nullptr;
     if (bins) hist_zero<NW * 64>(s_hist);
+    if (!DYN && bins) __syncthreads();           // (the other form meets at a barrier before its first tile anyway)
 
     // paged cache: the split's part of the sequence's page table, staged in LDS (read from
     // memory if it does not fit there)
@@ -151,23 +152,22 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         group32<G>(st, buf.k[0], buf.k[1], buf.v, qb, mask_a, mask_b, p.scale_log2, n, gq, Sa, Sb);
         if (!want_scores) return;
         // group-mean score of rows 4 gq + j of each block: sum over the 16 head lanes (padding
-        // heads hold 0); staged in LDS at the row's place in the split
+        // heads hold 0), which leaves every lane of a 16-lane row with the row's eight values.
+        // Lane n < 8 keeps value n (block n >> 2, row 4 gq + (n & 3) of it): one LDS store and one
+        // histogram count per tile for 32 lanes.  Staged in LDS at the row's place in the split.
+        float mine = 0.f;
 #pragma unroll
-        for (int blk = 0; blk < 2; ++blk)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                float v = group_sum<16>(blk ? Sb[j] : Sa[j]) * p.scale_mean;
-                v = fminf(fmaxf(v, -3.0e38f), 3.0e38f);      // also maps NaN to a number
-                const int r = 16 * blk + 4 * gq + j;
-                if (r < left && n == 0) {
-                    if (DYN && st0 < 0) {
-                        srow[t0 + r] = v;
-                        if (bins) hist_add(s_hist, v);
-                    } else {
-                        s_scores[st0 + r] = v;
-                    }
-                }
-            }
+        for (int c = 0; c < 8; ++c) {
+            float v = group_sum<16>((c >> 2) ? Sb[c & 3] : Sa[c & 3]) * p.scale_mean;
+            v = fminf(fmaxf(v, -3.0e38f), 3.0e38f);          // also maps NaN to a number
+            mine = n == c ? v : mine;
+        }
+        const int r = 16 * (n >> 2) + 4 * gq + (n & 3);
+        if (n < 8 && r < left) {
+            if (DYN && st0 < 0) srow[t0 + r] = mine;
+            else s_scores[st0 + r] = mine;
+            if (bins) hist_add(s_hist, mine);
+        }
     };
 
     if (DYN && n_rows > 0) {
@@ -201,19 +201,34 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
         // (all of them at this one row: the rows after it may lie outside the staged table)
         const int idle_row = min(sg.tile0 * TILE, n_rows - 1);
         if (paged) stage_table(idle_row, max(idle_row, min((sg.tile0 + sg.tiles) * TILE, n_rows) - 1));
-        if (tid == 0) {
-            int lo = 0, hi = 0;
-            bool has = false;
-            if (w < sg.n_eff) {
-                lo = chunk_bound(p, sg, w);
-                hi = chunk_bound(p, sg, w + 1);
-                has = hi > lo;
-                if (!has) {
-                    const int raw = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    has = settle_claim(p, sg, ctr, raw, lo, hi) >= 0;
-                }
+        // The chunk the workgroup starts on is known without the queue: wave v takes its tile v
+        // and has the loads under way while thread 0 sets the queue up (the draw of a chunk's
+        // first tile also claims the workgroup's next chunk: wave 0 does that first, so that the
+        // claim's answer is not queued behind the tile).
+        int lo0 = 0, hi0 = 0;
+        if (w < sg.n_eff) lo0 = chunk_bound(p, sg, w), hi0 = chunk_bound(p, sg, w + 1);
+        const bool early = wave < hi0 - lo0;
+        PendingClaim pc;
+        pc.raw = 0, pc.slot = -1, pc.first = 0;
+        Tile32 bufA, bufB;
+        TileRef ta;
+        ta.tile = -1, ta.ticket = wave;
+        if (early) {
+            if (wave == 0) {
+                if (lane == 0) pc.raw = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                pc.slot = 1, pc.first = hi0 - lo0;
             }
-            cq.ticket = 0;
+            ta.tile = sg.tile0 + lo0 + wave;
+            issue(bufA, ta.tile * TILE);
+        }
+        if (tid == 0) {
+            int lo = lo0, hi = hi0;
+            bool has = hi0 > lo0;
+            if (w < sg.n_eff && !has) {
+                const int raw = __hip_atomic_fetch_add(ctr, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                has = settle_claim(p, sg, ctr, raw, lo, hi) >= 0;
+            }
+            cq.ticket = min(max(hi0 - lo0, 0), NW);          // the tiles taken above
             cq.first[0] = 0;
             cq.first[1] = has ? hi - lo : 0;
             cq.tile0[0] = has ? sg.tile0 + lo : 0;
@@ -233,12 +248,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
             if (lane == 0) s_tile_of[t.ticket] = t.tile;
             return t.ticket * TILE;
         };
-        PendingClaim pc;
-        pc.raw = 0, pc.slot = -1, pc.first = 0;
-        Tile32 bufA, bufB;
-        TileRef ta = next_tile(cq, ctr, cur, pc, lane);
+        if (!early) {
+            ta = next_tile(cq, ctr, cur, pc, lane);
+            issue(bufA, ta.tile >= 0 ? ta.tile * TILE : idle_row, ta.tile >= 0 ? -1 : idle_row);
+        }
         HYLRA_TS(5);
-        issue(bufA, ta.tile >= 0 ? ta.tile * TILE : idle_row, ta.tile >= 0 ? -1 : idle_row);
         while (ta.tile >= 0) {
             publish_claim(cq, p, ctr, pc, lane, sg);                  // (first pass only)
             const TileRef tb = next_tile(cq, ctr, cur, pc, lane);
@@ -269,9 +283,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
                 for (int x = 0; x < 4; ++x)
                     if (r + x < n_rows) srow[r + x] = src[x];
             }
-            if (bins)
-                for (int x = 0; x < 4; ++x)
-                    if (r + x < n_rows) hist_add(s_hist, src[x]);
         }
     } else if (!DYN && row0 < row1) {
         Tile32 bufA, bufB;
@@ -300,8 +311,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void f
             } else {
                 for (int e = i; e < cnt; ++e) dst[e] = s_scores[e];
             }
-            if (bins)
-                for (int e = i; e < min(i + 4, cnt); ++e) hist_add(s_hist, s_scores[e]);
         }
     }
     // the pair's partials: [head of the group][partial] from slot0 * G on

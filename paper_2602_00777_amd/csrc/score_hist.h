@@ -14,17 +14,22 @@ constexpr int kScoreBins = 4096;
 DEVI void hist_add(int* s_hist, float score) { atomicAdd(&s_hist[ordered_key(score) >> 20], 1); }
 
 // NT threads clear / flush; a thread flushes the bins it cleared, so only the additions in
-// between need a barrier on either side.
+// between need a barrier on either side.  The flush reads all of a thread's bins before its
+// first conditional add, so that the LDS reads are in flight together.
 template <int NT>
 DEVI void hist_zero(int* s_hist) {
-    for (int i = threadIdx.x; i < kScoreBins; i += NT) s_hist[i] = 0;
+    static_assert(kScoreBins % NT == 0, "bins per thread");
+#pragma unroll
+    for (int j = 0; j < kScoreBins / NT; ++j) s_hist[threadIdx.x + j * NT] = 0;
 }
 template <int NT>
 DEVI void hist_flush(const int* s_hist, int* __restrict__ ghist) {
-    for (int i = threadIdx.x; i < kScoreBins; i += NT) {
-        const int n = s_hist[i];
-        if (n) atomicAdd(ghist + i, n);
-    }
+    int n[kScoreBins / NT];
+#pragma unroll
+    for (int j = 0; j < kScoreBins / NT; ++j) n[j] = s_hist[threadIdx.x + j * NT];
+#pragma unroll
+    for (int j = 0; j < kScoreBins / NT; ++j)
+        if (n[j]) atomicAdd(ghist + threadIdx.x + j * NT, n[j]);
 }
 
 }  // namespace hylra
