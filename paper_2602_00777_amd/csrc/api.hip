@@ -98,6 +98,8 @@ struct hylra_ctx {
     int max_chunks = 0;         // chunks of 8192 rows per (batch, KV head) at the maximum context
     int64_t sel_ints = 0;       // ints in sel_ws
     int32_t* lens_plus = nullptr;   // [max batch] sequence lengths after an append (see append_impl)
+    uint64_t* packets = nullptr;    // packets of the Reuse kernels' merge (reuse_tail.h), all zero between launches
+    int64_t cap_packets = 0;        // 64-bit units
     int4* wg_map = nullptr;     // deal of the Full kernel's workgroups to sequences of different lengths
     int2* pair_map = nullptr;   // (see RaggedPlanParams): `slots` and `pairs_cap` entries
     int n_cus = 0;              // compute units of the device
@@ -123,6 +125,7 @@ struct hylra_ctx {
     int32_t opt_full_unpaired = 0;
     int32_t opt_hist_unfused = 0;
     int32_t opt_append_unfused = 0;
+    int32_t opt_reuse_merge = 0;
 
     bool prof_on = false;
     int prof_n = 0;
@@ -396,6 +399,7 @@ hylra_status plan_full(const hylra_ctx* ctx, const hylra_shape* s, int G, FullPl
 
 struct ReusePlan {
     int rows_per_split, n_splits, variant, R, NW;
+    bool packets;               // merge by packets instead of by arrival counter (reuse_tail.h)
 };
 
 hylra_status plan_reuse(const hylra_ctx* ctx, const hylra_shape* s, int G, int k, ReusePlan& pl) {
@@ -414,7 +418,7 @@ hylra_status plan_reuse(const hylra_ctx* ctx, const hylra_shape* s, int G, int k
     pl.R = ctx->opt_reuse_unroll > 0 ? ctx->opt_reuse_unroll : 8;
     const bool mfma = pl.variant >= 2;
     const bool mfma2 = pl.variant >= 4;
-    if (mfma2) pl.R = 8;
+    if (mfma2) pl.R = ctx->opt_reuse_unroll == 4 ? 4 : 8;     // (wave tiles of 32 or 64 rows)
     // matrix-core kernels: workgroups of 8 waves when asked for, or when k fills them and there
     // are enough of them for every compute unit (below that, twice as many workgroups of 4
     // waves spread the gather wider: 12.0 instead of 12.7 us at batch 1 / k = 4096)
@@ -423,7 +427,7 @@ hylra_status plan_reuse(const hylra_ctx* ctx, const hylra_shape* s, int G, int k
                               (ctx->opt_reuse_waves == 0 && k >= 512 && k % 512 == 0 && pairs * (k / 512) >= 256)))
         pl.NW = 8;
     auto quantum_of = [&](int R) {
-        if (mfma2) return R == 8 ? reuse_mfma2_quantum(s->head_dim, pl.NW) : 0;
+        if (mfma2) return reuse_mfma2_quantum(s->head_dim, pl.NW, R / 2);
         return mfma ? reuse_mfma_quantum(R / 2, pl.NW) : reuse_block_quantum(s->head_dim, G, pl.variant, R);
     };
     while (ctx->opt_reuse_unroll == 0 && !mfma2 && pl.R > (mfma ? 2 : 1) && quantum_of(pl.R / 2) >= k) pl.R /= 2;
@@ -447,6 +451,27 @@ hylra_status plan_reuse(const hylra_ctx* ctx, const hylra_shape* s, int G, int k
         return fail(ctx, HYLRA_ERR_WORKSPACE, "batch*n_kv_heads = %lld exceeds the workspace", (long long)pairs);
     pl.rows_per_split = (int)rps;
     pl.n_splits = (int)S;
+    // Merge by packets: second matrix-core kernel, every workgroup resident at once (at most
+    // one per compute unit), a power-of-two number of partials that divides the 128 columns,
+    // and what a workgroup receives within what its threads poll.  From 8 partials on: with 4
+    // the arrival counter is as fast (config 2: 16.1 against 16.5 us), its merging workgroup
+    // then loads only 8 KB.
+    auto packets_ok = [&](int NW, int64_t n) {
+        const int64_t units = n * (2 * G * n + (int64_t)G * 128);       // per (batch, KV head)
+        return mfma2 && ctx->packets && ctx->opt_reuse_unfused == 0 && ctx->opt_reuse_merge != 1 && n >= (ctx->opt_reuse_merge == 2 ? kMergeBlock : 8) && n <= 128 &&
+               (n & (n - 1)) == 0 && pairs * n <= ctx->n_cus && units / n <= (int64_t)kPacketUnitsPerThread * NW * 64 &&
+               pairs * units <= ctx->cap_packets;
+    };
+    // With few (batch, KV head) pairs the gather is spread over twice as many workgroups (wave
+    // tiles of 32 rows, 128 entries per workgroup) if the packets can carry the merge: the
+    // arrival-counter merge by one compute unit does not keep up with that many partials.
+    const bool free_choice = ctx->opt_reuse_unroll == 0 && ctx->opt_reuse_waves == 0 && ctx->opt_reuse_split_rows == 0;
+    if (mfma2 && free_choice && pl.NW == 4 && k % 128 == 0 && packets_ok(4, k / 128)) {
+        pl.R = 4;
+        pl.rows_per_split = 128;
+        pl.n_splits = k / 128;
+    }
+    pl.packets = packets_ok(pl.NW, pl.n_splits);
     return HYLRA_OK;
 }
 
@@ -546,6 +571,11 @@ hylra_status hylra_create_ex(hylra_ctx** out, const hylra_shape* max_shape, int3
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->wg_map, ctx->slots * sizeof(int4));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->pair_map, pairs * sizeof(int2));
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->lens_plus, (size_t)max_shape->batch * sizeof(int32_t));
+    // packets: used only by launches of at most one workgroup per compute unit, each of which
+    // receives at most kPacketUnitsPerThread units per thread
+    ctx->cap_packets = (int64_t)std::max(ctx->n_cus, 1) * kPacketUnitsPerThread * 512;
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->packets, ctx->cap_packets * sizeof(uint64_t));
+    if (e == hipSuccess) e = hipMemset(ctx->packets, 0, ctx->cap_packets * sizeof(uint64_t));
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         fail(nullptr, HYLRA_ERR_HIP, "workspace allocation failed: %s", hipGetErrorString(e));
@@ -580,6 +610,7 @@ hylra_status hylra_destroy(hylra_ctx* ctx) {
     if (ctx->wg_map) (void)hipFree(ctx->wg_map);
     if (ctx->pair_map) (void)hipFree(ctx->pair_map);
     if (ctx->lens_plus) (void)hipFree(ctx->lens_plus);
+    if (ctx->packets) (void)hipFree(ctx->packets);
     delete ctx;
     return HYLRA_OK;
 }
@@ -591,6 +622,7 @@ hylra_status hylra_reset(hylra_ctx* ctx) {
     HIP_TRY(ctx, hipMemset(ctx->counters, 0, ctx->slots * sizeof(int)));
     HIP_TRY(ctx, hipMemset(ctx->chunk_ctr, 0, ctx->slots * kCtrStride * sizeof(int)));
     HIP_TRY(ctx, hipMemset(ctx->sel_ws, 0, ctx->sel_ints * sizeof(int)));
+    HIP_TRY(ctx, hipMemset(ctx->packets, 0, ctx->cap_packets * sizeof(uint64_t)));
     HIP_TRY(ctx, hipDeviceSynchronize());
     ctx->in_step = false, ctx->step_planned = false;
     if (ctx->err_word) *ctx->err_word = 0;
@@ -611,6 +643,7 @@ hylra_status hylra_set_option(hylra_ctx* ctx, const char* name, int32_t value) {
     else if (!std::strcmp(name, "full_unpaired")) ctx->opt_full_unpaired = value;
     else if (!std::strcmp(name, "hist_unfused")) ctx->opt_hist_unfused = value;
     else if (!std::strcmp(name, "append_unfused")) ctx->opt_append_unfused = value;
+    else if (!std::strcmp(name, "reuse_merge")) ctx->opt_reuse_merge = value;
     else if (!std::strcmp(name, "simulate_give_up")) {      // what a kernel whose bounded wait ran out would report
         if (ctx->err_word) *ctx->err_word = value ? 1 : 0;
     }
@@ -812,13 +845,15 @@ hylra_status reuse_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pa
     rp.part_ml = ctx->part_ml, rp.part_acc = ctx->part_acc;
     const bool fused = ctx->opt_reuse_unfused == 0;
     rp.counters = fused ? ctx->counters : nullptr;
+    rp.packets = pl.packets ? ctx->packets : nullptr;
+    rp.err_word = ctx->err_word;
     rp.out = out;
     // (a workspace that other calls may have left in any state: the arrival counters must start
     // at zero; a fill kernel, not a memset, since the caller may be capturing the stream)
     if (clear_counters && fused) HIP_TRY(ctx, launch_fill_zero(ctx->counters, shape->batch * shape->n_kv_heads, st));
     HIP_TRY(ctx, launch_timed(ctx, 2, st, [&] {
                 if (pl.variant >= 4)
-                    return launch_reuse_mfma2(rp, shape->batch, G, pl.variant == 4, pl.NW, st);
+                    return launch_reuse_mfma2(rp, shape->batch, G, pl.variant == 4, pl.NW, pl.R / 2, st);
                 if (pl.variant >= 2)
                     return launch_reuse_mfma(rp, shape->batch, shape->head_dim, G, pl.R / 2, pl.variant == 2, pl.NW, st);
                 return launch_reuse_split(rp, shape->batch, shape->head_dim, G, pl.variant, pl.R, st);

@@ -53,14 +53,10 @@ __global__ __launch_bounds__(128) void combine_kernel(CombineParams p) {
     for (int s = 0; s < S; ++s) M = fmaxf(M, ml[2 * s]);
     for (int col = threadIdx.x; col < D; col += blockDim.x) {
         const float* acc = p.part_acc + head * S * D + col;
-        float num = 0.f, den = 0.f;
+        MergeSum sum;
 #pragma unroll 16
-        for (int s = 0; s < S; ++s) {
-            const float w = fast_exp2(ml[2 * s] - M);
-            den = fmaf(w, ml[2 * s + 1], den);
-            num = fmaf(w, acc[(int64_t)s * D], num);
-        }
-        p.out[head * D + col] = den > 0.f ? num / den : 0.f;
+        for (int s = 0; s < S; ++s) sum.add(s, fast_exp2(ml[2 * s] - M), ml[2 * s + 1], acc[(int64_t)s * D]);
+        p.out[head * D + col] = sum.result();
     }
 }
 

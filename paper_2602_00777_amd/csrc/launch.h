@@ -104,6 +104,13 @@ hipError_t launch_score_hist(const TopkParams& p, int B, hipStream_t st);
 // step 0: level-1 threshold, per-chunk counts and lists, merge of the partials; step 1: emission
 hipError_t launch_topk(const TopkParams& p, int B, int step, int n_cus, hipStream_t st);
 
+// Partials per block of the common merge order (MergeSum, device_util.h).
+constexpr int kMergeBlock = 4;
+
+// Merge by packets (reuse_tail.h): 64-bit units a thread of a consuming workgroup polls at most,
+// i.e. a workgroup of T threads receives at most kPacketUnitsPerThread * T units.
+constexpr int kPacketUnitsPerThread = 6;
+
 struct ReuseParams {
     const uint16_t* q;
     const uint16_t* K;
@@ -128,6 +135,11 @@ struct ReuseParams {
     // (nullptr: N - 1 everywhere) and K, V receive one row per (batch, KV head).
     const uint16_t* k_new;
     const uint16_t* v_new;
+    // Merge by packets (reuse_tail.h): [B*Hkv][S][S][units] 64-bit units, all zero between
+    // launches, or nullptr: merge by arrival counter.  err_word: pinned host word set if a
+    // bounded wait runs out.
+    uint64_t* packets;
+    int* err_word;
 };
 
 // Block-level TopK: scores of blocks of `block` consecutive rows = maximum of the rows' scores.
@@ -244,8 +256,8 @@ int reuse_mfma_quantum(int NB, int NW);
 hipError_t launch_reuse_mfma(const ReuseParams& p, int B, int D, int G, int NB, bool nt, int NW, hipStream_t st);
 
 // Second matrix-core Reuse kernel (head_dim 128): 64 index entries per wave, NW = 4 or 8 waves
-int reuse_mfma2_quantum(int D, int NW);
-hipError_t launch_reuse_mfma2(const ReuseParams& p, int B, int G, bool nt, int NW, hipStream_t st);
+int reuse_mfma2_quantum(int D, int NW, int NB);
+hipError_t launch_reuse_mfma2(const ReuseParams& p, int B, int G, bool nt, int NW, int NB, hipStream_t st);
 
 hipError_t launch_gather_rows(const GatherParams& p, int B, hipStream_t st);
 hipError_t launch_overlap_counts(const OverlapParams& p, int B, hipStream_t st);

@@ -135,14 +135,12 @@ DEVI void group32(State2& st, const uint4 (&ka)[4], const uint4 (&kb)[4], const 
     }
 }
 
-// Merge the wave states of a workgroup into one partial per head, as mfma_block_merge_store
-// does for the first form (only the accumulator layout differs).  s_acc: [NW][G][128].
-template <int G, int NW, bool COHERENT>
-DEVI void merge_store2(State2& st, float (*s_m)[16], float (*s_l)[16], float* s_acc,
-                       float* __restrict__ part_ml, int64_t ml_stride, float* __restrict__ part_acc,
-                       int64_t acc_stride, int n, int gq) {
+// The wave states of a workgroup into LDS (s_m, s_l: [NW][16]; s_acc: [NW][G][128]); ends with
+// the barrier after which every thread may read them.
+template <int G, int NW>
+DEVI void stage_states2(State2& st, float (*s_m)[16], float (*s_l)[16], float* s_acc, int n, int gq) {
     constexpr int D = 128;
-    const int tid = threadIdx.x, wave = tid >> 6;
+    const int wave = threadIdx.x >> 6;
     float l = st.l;
     l += __shfl_xor(l, 16, 64);
     l += __shfl_xor(l, 32, 64);
@@ -160,24 +158,48 @@ DEVI void merge_store2(State2& st, float (*s_m)[16], float (*s_l)[16], float* s_
         }
     }
     __syncthreads();
+}
+// Head h of the workgroup after stage_states2: its maximum, its sum, its accumulator column.
+template <int NW>
+DEVI float staged_max(const float (*s_m)[16], int h) {
+    float M = s_m[0][h];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) M = fmaxf(M, s_m[w][h]);
+    return M;
+}
+template <int NW>
+DEVI float staged_sum(const float (*s_m)[16], const float (*s_l)[16], int h, float M) {
+    float ls = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) ls = fmaf(fast_exp2(s_m[w][h] - M), s_l[w][h], ls);
+    return ls;
+}
+template <int G, int NW>
+DEVI float staged_acc(const float (*s_m)[16], const float* s_acc, int h, int col, float M) {
+    float a = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) a = fmaf(fast_exp2(s_m[w][h] - M), s_acc[(w * G + h) * 128 + col], a);
+    return a;
+}
+
+// Merge the wave states of a workgroup into one partial per head, as mfma_block_merge_store
+// does for the first form (only the accumulator layout differs).
+template <int G, int NW, bool COHERENT>
+DEVI void merge_store2(State2& st, float (*s_m)[16], float (*s_l)[16], float* s_acc,
+                       float* __restrict__ part_ml, int64_t ml_stride, float* __restrict__ part_acc,
+                       int64_t acc_stride, int n, int gq) {
+    constexpr int D = 128;
+    const int tid = threadIdx.x;
+    stage_states2<G, NW>(st, s_m, s_l, s_acc, n, gq);
     for (int i = tid; i < G * D; i += NW * 64) {
         const int h = i / D, col = i - h * D;
-        float M = s_m[0][h];
-#pragma unroll
-        for (int w = 1; w < NW; ++w) M = fmaxf(M, s_m[w][h]);
-        float a = 0.f;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) a = fmaf(fast_exp2(s_m[w][h] - M), s_acc[(w * G + h) * D + col], a);
+        const float a = staged_acc<G, NW>(s_m, s_acc, h, col, staged_max<NW>(s_m, h));
         if (COHERENT) coherent_store(part_acc + h * acc_stride + col, a);
         else part_acc[h * acc_stride + col] = a;
     }
     if (tid < G) {
-        float M = s_m[0][tid];
-#pragma unroll
-        for (int w = 1; w < NW; ++w) M = fmaxf(M, s_m[w][tid]);
-        float ls = 0.f;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) ls = fmaf(fast_exp2(s_m[w][tid] - M), s_l[w][tid], ls);
+        const float M = staged_max<NW>(s_m, tid);
+        const float ls = staged_sum<NW>(s_m, s_l, tid, M);
         if (COHERENT) {
             coherent_store(part_ml + tid * ml_stride, M);
             coherent_store(part_ml + tid * ml_stride + 1, ls);

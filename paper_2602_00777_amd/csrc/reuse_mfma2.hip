@@ -7,11 +7,11 @@
 
 namespace hylra {
 
-// A wave takes 64 index entries (4 blocks of 16 = 2 groups of 32) per sweep; NW waves per
+// A wave takes NB blocks of 16 index entries (= NB / 2 groups of 32) per sweep; NW waves per
 // workgroup.
-template <int G, bool NT, int NW>
+template <int G, bool NT, int NW, int NB>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) void reuse_mfma2_kernel(ReuseParams p) {
-    constexpr int D = 128, NB = 4, ROWS_W = 16 * NB;
+    constexpr int D = 128, ROWS_W = 16 * NB;
     __shared__ float s_m[NW][16];
     __shared__ float s_l[NW][16];
     __shared__ __attribute__((aligned(16))) float s_acc[NW * G * D];
@@ -122,6 +122,18 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     float* const my_ml = p.part_ml + (head0 * p.n_splits + split) * 2;
     float* const my_acc = p.part_acc + (head0 * p.n_splits + split) * D;
     const int64_t ml_stride = (int64_t)p.n_splits * 2, acc_stride = (int64_t)p.n_splits * D;
+    if (p.packets) {                        // every workgroup merges its slice of the columns
+        __shared__ float s_pk[kPacketUnitsPerThread * NW * 64];
+        HYLRA_TS(3);
+        stage_states2<G, NW>(st, s_m, s_l, s_acc, n, gq);
+        uint64_t* pk_pair = p.packets + pair * p.n_splits * p.n_splits * packet_units<G, D>(p.n_splits);
+        send_packets<G, D, NW * 64>(
+            pk_pair, p.n_splits, split, [&](int h) { return staged_max<NW>(s_m, h); },
+            [&](int h, float M) { return staged_sum<NW>(s_m, s_l, h, M); },
+            [&](int h, int col, float M) { return staged_acc<G, NW>(s_m, s_acc, h, col, M); });
+        reuse_packet_tail<G, D, NW * 64>(p, pk_pair, head0, split, s_pk);
+        return;
+    }
     if (p.counters == nullptr) {            // unfused: a separate kernel merges the partials
         merge_store2<G, NW, false>(st, s_m, s_l, s_acc, my_ml, ml_stride, my_acc, acc_stride, n, gq);
         return;
@@ -131,26 +143,29 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
 }
 
 template <int G>
-static hipError_t launch2_g(const ReuseParams& p, int B, bool nt, int NW, hipStream_t st) {
+static hipError_t launch2_g(const ReuseParams& p, int B, bool nt, int NW, int NB, hipStream_t st) {
     dim3 grid(p.n_splits, p.Hkv, B);
-#define HYLRA_CASE(NWV)                                                                              \
-    if (NW == NWV) {                                                                                 \
-        if (nt) hipLaunchKernelGGL((reuse_mfma2_kernel<G, true, NWV>), grid, dim3(NWV * 64), 0, st, p); \
-        else hipLaunchKernelGGL((reuse_mfma2_kernel<G, false, NWV>), grid, dim3(NWV * 64), 0, st, p);   \
-        return hipGetLastError();                                                                    \
+#define HYLRA_CASE(NWV, NBV)                                                                              \
+    if (NW == NWV && NB == NBV) {                                                                         \
+        if (nt) hipLaunchKernelGGL((reuse_mfma2_kernel<G, true, NWV, NBV>), grid, dim3(NWV * 64), 0, st, p); \
+        else hipLaunchKernelGGL((reuse_mfma2_kernel<G, false, NWV, NBV>), grid, dim3(NWV * 64), 0, st, p);   \
+        return hipGetLastError();                                                                         \
     }
-    HYLRA_CASE(4)
-    HYLRA_CASE(8)
+    HYLRA_CASE(4, 4)
+    HYLRA_CASE(8, 4)
+    HYLRA_CASE(4, 2)
 #undef HYLRA_CASE
     return hipErrorInvalidValue;
 }
 
-// index entries per workgroup sweep; 0 if the shape is not built
-int reuse_mfma2_quantum(int D, int NW) { return (D == 128 && (NW == 4 || NW == 8)) ? NW * 64 : 0; }
+// index entries per workgroup sweep (NW waves of NB blocks of 16); 0 if the shape is not built
+int reuse_mfma2_quantum(int D, int NW, int NB) {
+    return (D == 128 && ((NB == 4 && (NW == 4 || NW == 8)) || (NB == 2 && NW == 4))) ? NW * NB * 16 : 0;
+}
 
-hipError_t launch_reuse_mfma2(const ReuseParams& p, int B, int G, bool nt, int NW, hipStream_t st) {
+hipError_t launch_reuse_mfma2(const ReuseParams& p, int B, int G, bool nt, int NW, int NB, hipStream_t st) {
 #define HYLRA_G(GG) \
-    if (G == GG) return launch2_g<GG>(p, B, nt, NW, st);
+    if (G == GG) return launch2_g<GG>(p, B, nt, NW, NB, st);
     HYLRA_G(1) HYLRA_G(2) HYLRA_G(3) HYLRA_G(4) HYLRA_G(5) HYLRA_G(6) HYLRA_G(7) HYLRA_G(8)
 #undef HYLRA_G
     return hipErrorInvalidValue;

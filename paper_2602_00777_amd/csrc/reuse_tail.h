@@ -39,16 +39,14 @@ DEVI float merge_partials(const ReuseParams& p, int64_t head0, int i, int S) {
         l_s[s] = coherent_load(ml + 2 * sc + 1);
         a_s[s] = coherent_load(acc + (int64_t)sc * D);
     }
-    float M = NEG_BIG, num = 0.f, den = 0.f;
+    float M = NEG_BIG;
 #pragma unroll
     for (int s = 0; s < SB; ++s) M = fmaxf(M, m_s[s]);
+    MergeSum sum;
 #pragma unroll
-    for (int s = 0; s < SB; ++s) {
-        const float w = s < S ? fast_exp2(m_s[s] - M) : 0.f;
-        den = fmaf(w, l_s[s], den);
-        num = fmaf(w, a_s[s], num);
-    }
-    return den > 0.f ? num / den : 0.f;
+    for (int s = 0; s < SB; ++s)
+        if (s < S) sum.add(s, fast_exp2(m_s[s] - M), l_s[s], a_s[s]);
+    return sum.result();
 }
 
 // Element offset of cache row `row` of the workgroup's sequence from the kernel's K / V base
@@ -132,20 +130,137 @@ DEVI void reuse_merge_tail(const ReuseParams& p, int64_t pair, int64_t head0, in
             const int h = i / D, col = i - h * D;
             const float* ml = p.part_ml + (head0 + h) * S * 2;
             const float* acc = p.part_acc + (head0 + h) * S * D + col;
-            float M = NEG_BIG, num = 0.f, den = 0.f;
+            float M = NEG_BIG;
 #pragma unroll 8
             for (int s = 0; s < S; ++s) M = fmaxf(M, coherent_load(ml + 2 * s));
+            MergeSum sum;
 #pragma unroll 8
-            for (int s = 0; s < S; ++s) {
-                const float w = fast_exp2(coherent_load(ml + 2 * s) - M);
-                den = fmaf(w, coherent_load(ml + 2 * s + 1), den);
-                num = fmaf(w, coherent_load(acc + (int64_t)s * D), num);
-            }
-            p.out[(head0 + h) * D + col] = den > 0.f ? num / den : 0.f;
+            for (int s = 0; s < S; ++s)
+                sum.add(s, fast_exp2(coherent_load(ml + 2 * s) - M), coherent_load(ml + 2 * s + 1),
+                        coherent_load(acc + (int64_t)s * D));
+            p.out[(head0 + h) * D + col] = sum.result();
         }
     }
     HYLRA_TS(6);
     if (tid == 0) __hip_atomic_store(p.counters + pair, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// ---- Merge by packets ------------------------------------------------------------------------
+// A second way across workgroups, for launches whose workgroups are all resident at once (the
+// host checks: no more workgroups than compute units).  Instead of "store the partial, count
+// the arrival, the last one merges everything" -- three dependent trips to memory after the
+// last row, and a merge by ONE compute unit -- every workgroup of a (batch, KV head) is also
+// the consumer of one slice of the output columns: workgroup c merges columns c D/S .. of all
+// heads.  A producer sends consumer c a packet [G][2] (max, sum) + [G][D/S] (its accumulator's
+// columns of c); every float travels in a 64-bit unit {value, tag} written and read with one
+// 64-bit agent-scope atomic access, so a unit that reads tag = 1 carries its value: nothing
+// else has to be ordered, no counter, no wait for stores to be acknowledged.  The consumer
+// polls the S packets addressed to it (contiguous), keeps what is tagged, and writes zero over
+// every unit it has taken, which is the state the next launch expects (a launch ends before
+// the next one starts, so these stores are complete by then; every unit has one writer and
+// one reader per launch).  The poll is bounded; if it runs out (which takes a fault elsewhere)
+// the host is told through err_word and the context has to be reset.  The merge itself runs
+// in partial order 0 .. S - 1 with the arithmetic of combine_kernel, bit for bit.
+constexpr uint32_t kPacketFull = 1u;
+constexpr int kPacketSpins = 1 << 18;
+
+// units of a packet for S partials
+template <int G, int D>
+DEVI int packet_units(int S) { return G * (2 + D / S); }
+
+// Producer.  pk_pair: the pair's packets [consumer][producer][units]; max_of(h), sum_of(h, M),
+// acc_of(h, col, M): the workgroup's merged state.  Every thread calls.
+template <int G, int D, int NT, class FM, class FS, class FA>
+DEVI void send_packets(uint64_t* __restrict__ pk_pair, int S, int split, FM max_of, FS sum_of, FA acc_of) {
+    const int tid = threadIdx.x;
+    const int W = D / S, PK = G * (2 + W);
+    const int lw = 31 - __clz(W);                 // S divides D = 2^x: W is a power of two
+    auto put = [](uint64_t* p, float v) {
+        __hip_atomic_store(p, ((uint64_t)kPacketFull << 32) | __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    };
+    for (int i = tid; i < G * D; i += NT) {
+        const int h = i / D, col = i - h * D;
+        const int c = col >> lw, j = col & (W - 1);
+        put(pk_pair + ((int64_t)c * S + split) * PK + 2 * G + h * W + j, acc_of(h, col, max_of(h)));
+    }
+    for (int i = tid; i < S * G; i += NT) {
+        const int c = i / G, h = i - c * G;
+        const float M = max_of(h);
+        uint64_t* dst = pk_pair + ((int64_t)c * S + split) * PK + 2 * h;
+        put(dst, M);
+        put(dst + 1, sum_of(h, M));
+    }
+}
+
+// Consumer.  s_pk: kPacketUnitsPerThread * NT floats of LDS.  Every thread calls.
+template <int G, int D, int NT>
+DEVI void reuse_packet_tail(const ReuseParams& p, uint64_t* __restrict__ pk_pair, int64_t head0, int split,
+                            float* s_pk) {
+    constexpr int U = kPacketUnitsPerThread;
+    const int tid = threadIdx.x;
+    const int S = p.n_splits, W = D / S, PK = G * (2 + W), total = S * PK;
+    const int nu = (total + NT - 1) / NT;                   // units per thread (<= U: the host checks)
+    uint64_t* __restrict__ mine = pk_pair + (int64_t)split * S * PK;
+    HYLRA_TS(4);
+    // Every round reads all of the thread's units again, without branches, so that the loads of
+    // a round are in flight together (a unit that was full stays full until this thread clears
+    // it below; a place past the end loads the last unit and ignores it -- that unit's owner
+    // may have cleared it already).
+    uint64_t v[U];
+    bool ok = false;
+    for (int spin = 0; spin < kPacketSpins && !ok; ++spin) {
+        if (spin) __builtin_amdgcn_s_sleep(1);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (u < nu) v[u] = __hip_atomic_load(mine + min(tid + u * NT, total - 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ok = true;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (u < nu) ok = ok && (tid + u * NT >= total || (uint32_t)(v[u] >> 32) == kPacketFull);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+        if (u < nu && tid + u * NT < total) {
+            s_pk[tid + u * NT] = __uint_as_float((uint32_t)v[u]);
+            __hip_atomic_store(mine + tid + u * NT, (uint64_t)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    if (!ok && p.err_word) __hip_atomic_store(p.err_word, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    __syncthreads();
+    HYLRA_TS(5);
+    // The merge, in the common order (MergeSum): S / 4 lanes per output element, one block of
+    // four partials each; their maxima meet by exchange, their block sums are added in block
+    // order by the element's first lane.  G W elements of S / 4 lanes = G D / 4 <= NT threads.
+    static_assert(G * D / kMergeBlock <= NT, "one pass of the workgroup covers every element");
+    const int L = S / kMergeBlock, ll = 31 - __clz(L), lw = 31 - __clz(W);      // (powers of two; S >= 4)
+    const int e = tid >> ll, blk = tid & (L - 1);
+    if (e < G * W) {                                    // (whole groups of L <= 32 lanes, inside one wave)
+        const int h = e >> lw, j = e & (W - 1);
+        const float* pk = s_pk + blk * kMergeBlock * PK;
+        float m4[kMergeBlock], l4[kMergeBlock], a4[kMergeBlock];
+#pragma unroll
+        for (int i = 0; i < kMergeBlock; ++i) {
+            m4[i] = pk[i * PK + 2 * h];
+            l4[i] = pk[i * PK + 2 * h + 1];
+            a4[i] = pk[i * PK + 2 * G + h * W + j];
+        }
+        float M = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
+        for (int x = 1; x < L; x <<= 1) M = fmaxf(M, __shfl_xor(M, x, 64));
+        float db = 0.f, nb = 0.f;
+#pragma unroll
+        for (int i = 0; i < kMergeBlock; ++i) {
+            const float w = fast_exp2(m4[i] - M);
+            db = fmaf(w, l4[i], db);
+            nb = fmaf(w, a4[i], nb);
+        }
+        float den = 0.f, num = 0.f;
+        const int first = threadIdx.x & 63 & ~(L - 1);
+        for (int x = 0; x < L; ++x) {
+            den += __shfl(db, first + x, 64);
+            num += __shfl(nb, first + x, 64);
+        }
+        if (blk == 0) p.out[(head0 + h) * D + split * W + j] = den > 0.f ? num / den : 0.f;
+    }
+    HYLRA_TS(6);
 }
 
 }  // namespace hylra

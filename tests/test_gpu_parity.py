@@ -268,6 +268,49 @@ def test_reuse_fused_merge_equals_two_kernel_merge(B, Hkv, G, d, N, k):
     assert_out_close(two.cpu().numpy(), oracle.reuse_sparse_attn(q, K, V, idx), "reuse out")
 
 
+@pytest.mark.parametrize("B,Hkv,G,k,unroll", [(1, 8, 4, 4096, 0), (2, 8, 7, 2048, 0), (4, 8, 4, 2048, 8), (1, 4, 1, 1024, 4),
+                                              (1, 2, 8, 4096, 0), (3, 5, 3, 512, 4)])
+def test_reuse_packet_merge_equals_two_kernel_merge(B, Hkv, G, k, unroll):
+    """The merge by packets (every workgroup of a (batch, KV head) merges a slice of the columns
+    from 64-bit {value, tag} units it polls) must give bit-identical results to the separate
+    merge kernel over the same partials, launch after launch (the units are cleared by their
+    readers), also when launches of another shape run in between."""
+    say("reuse packet merge B=%d Hkv=%d G=%d k=%d unroll=%d" % (B, Hkv, G, k, unroll))
+    d, N = 128, 8192
+    q, K, V = rand_case(310 + G, B, Hkv, G, d, N)
+    rng = np.random.RandomState(k)
+    idx = np.stack([[np.sort(rng.permutation(N)[:k]) for _ in range(Hkv)] for _ in range(B)]).astype(np.int32)
+    idx[:, :, k // 3] = -1                       # a padding entry
+    gidx = torch.from_numpy(idx).to(DEV)
+    other = gidx[:, :, :256].contiguous()
+    with binding.Context(B, Hkv * G, Hkv, d, N, k) as ctx:
+        # same split both times: wave tiles of 32 rows (unroll 4: 128 entries per workgroup) or of 64
+        ctx.set_option("reuse_unroll", unroll if unroll else 4)
+        if unroll == 8:
+            ctx.set_option("reuse_waves", 8)
+        ctx.set_option("reuse_unfused", 1)
+        two = ctx.reuse_sparse_attn(q, K, V, gidx).clone()
+        ctx.set_option("reuse_unfused", 0)
+        ctx.set_option("reuse_merge", 2)         # packets whenever the launch allows them
+        if unroll == 0:                          # the automatic choice must be this very split
+            ctx.set_option("reuse_unroll", 0)
+            ctx.set_option("reuse_merge", 0)
+        ctx.profile_enable(True)
+        outs = []
+        for it in range(30):
+            o = torch.full(q.shape, float("nan"), dtype=torch.float32, device=DEV)
+            ctx.reuse_sparse_attn(q, K, V, gidx, out=o)
+            outs.append(o)
+            if it % 7 == 3:
+                ctx.reuse_sparse_attn(q, K, V, other)
+        torch.cuda.synchronize()
+        prof = ctx.profile_read()
+        assert prof["reuse_combine"][0] == 0
+    for it, o in enumerate(outs):
+        assert torch.equal(o, two), "packet merge differs at launch %d" % it
+    assert_out_close(two.cpu().numpy(), oracle.reuse_sparse_attn(q, K, V, idx), "reuse out")
+
+
 def test_reuse_padding_order_and_out_of_range_entries():
     say("reuse padding")
     B, Hkv, G, d, N, k = 1, 2, 4, 128, 1000, 200
