@@ -429,8 +429,17 @@ hylra_status hylra_policy_search(hylra_ctx *ctx, int32_t n_layers, const double 
  *                       loads, 3 / 4 = first matrix-core kernel with streaming / plain loads
  *                       (default for head_dim 64: 4), 5 / 6 = second matrix-core kernel
  *                       (head_dim 128 only; default there: 5)
- *   "reuse_unroll"      row groups per wave tile of the Reuse kernel: 1, 2, 4 or 8
+ *   "reuse_unroll"      row groups per wave tile of the Reuse kernel: 1, 2, 4 or 8 (the second
+ *                       matrix-core kernel: 4 = wave tiles of 32 rows, otherwise of 64)
  *   "reuse_waves"       waves per workgroup of the matrix-core Reuse kernel: 4 or 8
+ *   "reuse_merge"       how the Reuse kernel merges the partials of a (batch, KV head) across
+ *                       workgroups.  0 = automatic; 1 = always by arrival counter (the last
+ *                       workgroup to arrive merges everything); 2 = by packets (every workgroup
+ *                       merges a slice of the columns) whenever the launch allows it: head_dim
+ *                       128, 4 .. 128 partials per pair and a power of two, no more workgroups
+ *                       than compute units.  Automatic: packets from 8 partials on, and with
+ *                       few (batch, KV head) pairs twice as many workgroups with wave tiles of
+ *                       32 rows.
  *   "reuse_unfused"     1 = merge the Reuse partials in a second kernel instead of in the
  *                       last-arriving workgroup of the Reuse kernel
  *   "simulate_give_up"  1 = mark the context as if a kernel had given up a bounded wait (for
