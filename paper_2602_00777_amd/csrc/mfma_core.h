@@ -151,26 +151,37 @@ DEVI float4_t mfma_block(MfmaState<D>& st, const uint4 (&kb)[D / 32], const uint
 // Merge the wave states of a workgroup of NW waves into one partial per head:
 // (max, sum) to part_ml[h * ml_stride + {0,1}], accumulator to part_acc[h * acc_stride + col].
 // s_m, s_l: [NW][16]; s_acc: [NW][G][D].  Every thread must call it.
+template <int D, int G, int NW>
+DEVI void mfma_stage_states(MfmaState<D>& st, float (*s_m)[16], float (*s_l)[16], float* s_acc, int n, int gq);
+
+// A (batch, KV head) that ONE workgroup covers: its output straight from the staged wave states
+// (s_m, s_l: [NW][16]; s_acc: [NW][G][D]; after the staging barrier), out: [G][D].  The same
+// bits as the partial followed by a merge of one partial: there the weight is 2^0 = 1, and
+// fma(1, x, 0) and 0 + x are x.
+template <int D, int G, int NW>
+DEVI void staged_to_output(const float (*s_m)[16], const float (*s_l)[16], const float* s_acc, float* __restrict__ out) {
+    for (int i = threadIdx.x; i < G * D; i += NW * 64) {
+        const int h = i / D, col = i - h * D;
+        float M = s_m[0][h];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) M = fmaxf(M, s_m[w][h]);
+        float a = 0.f, ls = 0.f;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) {
+            const float f = fast_exp2(s_m[w][h] - M);
+            a = fmaf(f, s_acc[(w * G + h) * D + col], a);
+            ls = fmaf(f, s_l[w][h], ls);
+        }
+        out[i] = ls > 0.f ? a / ls : 0.f;
+    }
+}
+
 template <int D, int G, int NW, bool COHERENT>
 DEVI void mfma_block_merge_store(MfmaState<D>& st, float (*s_m)[16], float (*s_l)[16],
                                  float* s_acc, float* __restrict__ part_ml, int64_t ml_stride,
                                  float* __restrict__ part_acc, int64_t acc_stride, int n, int gq) {
-    const int tid = threadIdx.x, wave = tid >> 6;
-    float l = st.l;
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
-    if (gq == 0) {
-        s_m[wave][n] = st.m;
-        s_l[wave][n] = l;
-    }
-#pragma unroll
-    for (int tl = 0; tl < D / 16; ++tl)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int h = 4 * gq + j;
-            if (h < G) s_acc[(wave * G + h) * D + 16 * tl + n] = st.acc[tl][j];
-        }
-    __syncthreads();
+    const int tid = threadIdx.x;
+    mfma_stage_states<D, G, NW>(st, s_m, s_l, s_acc, n, gq);
     for (int i = tid; i < G * D; i += NW * 64) {
         const int h = i / D, col = i - h * D;
         float M = s_m[0][h];
@@ -197,6 +208,28 @@ DEVI void mfma_block_merge_store(MfmaState<D>& st, float (*s_m)[16], float (*s_l
             part_ml[tid * ml_stride + 1] = ls;
         }
     }
+}
+
+// The wave states of a workgroup into LDS; ends with the barrier after which every thread may
+// read them.
+template <int D, int G, int NW>
+DEVI void mfma_stage_states(MfmaState<D>& st, float (*s_m)[16], float (*s_l)[16], float* s_acc, int n, int gq) {
+    const int wave = threadIdx.x >> 6;
+    float l = st.l;
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    if (gq == 0) {
+        s_m[wave][n] = st.m;
+        s_l[wave][n] = l;
+    }
+#pragma unroll
+    for (int tl = 0; tl < D / 16; ++tl)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int h = 4 * gq + j;
+            if (h < G) s_acc[(wave * G + h) * D + 16 * tl + n] = st.acc[tl][j];
+        }
+    __syncthreads();
 }
 
 }  // namespace hylra

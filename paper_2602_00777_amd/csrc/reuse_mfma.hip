@@ -110,6 +110,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     float* const my_ml = p.part_ml + (head0 * p.n_splits + split) * 2;
     float* const my_acc = p.part_acc + (head0 * p.n_splits + split) * D;
     const int64_t ml_stride = (int64_t)p.n_splits * 2, acc_stride = (int64_t)p.n_splits * D;
+    if (p.n_splits == 1 && p.counters) {    // nothing crosses workgroups: no partial, no counter
+        mfma_stage_states<D, G, NW>(st, s_m, s_l, s_acc, n, gq);
+        staged_to_output<D, G, NW>(s_m, s_l, s_acc, p.out + head0 * D);
+        return;
+    }
     if (p.counters == nullptr) {            // unfused: a separate kernel merges the partials
         mfma_block_merge_store<D, G, NW, false>(st, s_m, s_l, s_acc, my_ml, ml_stride, my_acc, acc_stride, n, gq);
         return;

@@ -122,6 +122,11 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
     float* const my_ml = p.part_ml + (head0 * p.n_splits + split) * 2;
     float* const my_acc = p.part_acc + (head0 * p.n_splits + split) * D;
     const int64_t ml_stride = (int64_t)p.n_splits * 2, acc_stride = (int64_t)p.n_splits * D;
+    if (p.n_splits == 1 && p.counters) {    // nothing crosses workgroups: no partial, no counter
+        stage_states2<G, NW>(st, s_m, s_l, s_acc, n, gq);
+        staged_to_output<D, G, NW>(s_m, s_l, s_acc, p.out + head0 * D);
+        return;
+    }
     if (p.packets) {                        // every workgroup merges its slice of the columns
         __shared__ float s_pk[kPacketUnitsPerThread * NW * 64];
         HYLRA_TS(3);

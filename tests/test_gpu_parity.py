@@ -244,10 +244,12 @@ def test_reuse_sparse_attn_matches_oracle(B, Hkv, G, d, N, k):
     assert_out_close(out.cpu().numpy(), oracle.reuse_sparse_attn(q, K, V, idx), "reuse out")
 
 
-@pytest.mark.parametrize("B,Hkv,G,d,N,k", [(4, 8, 4, 128, 8192, 2048), (2, 4, 7, 128, 6000, 1000), (8, 2, 4, 64, 4096, 1024)])
+@pytest.mark.parametrize("B,Hkv,G,d,N,k", [(4, 8, 4, 128, 8192, 2048), (2, 4, 7, 128, 6000, 1000), (8, 2, 4, 64, 4096, 1024),
+                                          (2, 2, 4, 128, 3000, 200), (1, 3, 5, 64, 2000, 100), (32, 8, 4, 128, 2048, 1024)])
 def test_reuse_fused_merge_equals_two_kernel_merge(B, Hkv, G, d, N, k):
-    """The in-kernel merge (last-arriving workgroup) must give bit-identical results to the
-    separate merge kernel, launch after launch (the arrival counters reset themselves)."""
+    """The in-kernel merge (last-arriving workgroup; with one workgroup per (batch, KV head) the
+    output straight from that workgroup) must give bit-identical results to the separate merge
+    kernel, launch after launch (the arrival counters reset themselves)."""
     say("reuse fused merge B=%d Hkv=%d G=%d d=%d N=%d k=%d" % (B, Hkv, G, d, N, k))
     q, K, V = rand_case(300 + G, B, Hkv, G, d, N)
     rng = np.random.RandomState(k)
