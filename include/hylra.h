@@ -458,6 +458,17 @@ hylra_status hylra_policy_search(hylra_ctx *ctx, int32_t n_layers, const double 
 hylra_status hylra_set_option(hylra_ctx *ctx, const char *name, int32_t value);
 
 /*
+ * What the library decided for the most recent Reuse-layer launch of the context ("Sparse
+ * Attention", Algorithm 2's Reuse branch), for tests and for tuning.  *value (HOST) receives:
+ *   "last_reuse_splits"     workgroups (= partials) per (batch, KV head)
+ *   "last_reuse_wave_rows"  index entries a wave takes per sweep (matrix-core kernels: 32 or 64)
+ *   "last_reuse_merge"      how the partials met: 0 = a second kernel, 1 = arrival counter,
+ *                           2 = packets, 3 = one workgroup per pair, nothing to merge
+ * 0 everywhere before the first such launch.  An unknown name is HYLRA_ERR_BAD_ARG.
+ */
+hylra_status hylra_get_info(const hylra_ctx *ctx, const char *name, int32_t *value);
+
+/*
  * Measurement aids (not on the hot path).
  *
  * hylra_profile_enable(ctx, 1) makes every later kernel launch of this context

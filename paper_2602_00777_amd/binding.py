@@ -30,7 +30,7 @@ EXPORTS = (
     "hylra_offload_slot_bytes", "hylra_gather_rows", "hylra_decode_step_offloaded",
     "hylra_gather_blocks", "hylra_decode_step_offloaded_blocks",
     "hylra_append_full_attn_topk", "hylra_append_reuse_sparse_attn", "hylra_decode_step_append",
-    "hylra_set_option", "hylra_profile_enable", "hylra_profile_reset", "hylra_profile_read",
+    "hylra_set_option", "hylra_get_info", "hylra_profile_enable", "hylra_profile_reset", "hylra_profile_read",
     "hylra_probe_copy", "hylra_probe_read", "hylra_probe_gather",
 )
 
@@ -108,6 +108,7 @@ def load_library() -> ctypes.CDLL:
     lib.hylra_policy_search.argtypes = [vp, i32, vp, ctypes.c_double, vp, ctypes.POINTER(i32),
                                         ctypes.POINTER(ctypes.c_double)]
     lib.hylra_set_option.argtypes = [vp, ctypes.c_char_p, i32]
+    lib.hylra_get_info.argtypes = [vp, ctypes.c_char_p, ctypes.POINTER(i32)]
     lib.hylra_profile_enable.argtypes = [vp, i32]
     lib.hylra_profile_reset.argtypes = [vp]
     lib.hylra_profile_read.argtypes = [vp, i32, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_double)]
@@ -644,6 +645,11 @@ class Context:
 
     def set_option(self, name: str, value: int):
         self._check(self._lib.hylra_set_option(self._h, name.encode(), int(value)), "hylra_set_option")
+
+    def get_info(self, name: str) -> int:
+        v = ctypes.c_int32()
+        self._check(self._lib.hylra_get_info(self._h, name.encode(), ctypes.byref(v)), "hylra_get_info")
+        return v.value
 
     def profile_enable(self, on: bool = True):
         self._check(self._lib.hylra_profile_enable(self._h, 1 if on else 0), "hylra_profile_enable")

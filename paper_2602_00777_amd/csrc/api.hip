@@ -126,6 +126,7 @@ struct hylra_ctx {
     int32_t opt_hist_unfused = 0;
     int32_t opt_append_unfused = 0;
     int32_t opt_reuse_merge = 0;
+    int32_t last_reuse_splits = 0, last_reuse_wave_rows = 0, last_reuse_merge = 0;   // see hylra_get_info
 
     bool prof_on = false;
     int prof_n = 0;
@@ -629,6 +630,15 @@ hylra_status hylra_reset(hylra_ctx* ctx) {
     return HYLRA_OK;
 }
 
+hylra_status hylra_get_info(const hylra_ctx* ctx, const char* name, int32_t* value) {
+    if (!ctx || !name || !value) return HYLRA_ERR_BAD_ARG;
+    if (!std::strcmp(name, "last_reuse_splits")) *value = ctx->last_reuse_splits;
+    else if (!std::strcmp(name, "last_reuse_wave_rows")) *value = ctx->last_reuse_wave_rows;
+    else if (!std::strcmp(name, "last_reuse_merge")) *value = ctx->last_reuse_merge;
+    else return HYLRA_ERR_BAD_ARG;
+    return HYLRA_OK;
+}
+
 hylra_status hylra_set_option(hylra_ctx* ctx, const char* name, int32_t value) {
     if (!ctx) return HYLRA_ERR_BAD_ARG;
     if (!name || value < 0) return fail(ctx, HYLRA_ERR_BAD_ARG, "option name is NULL or value negative");
@@ -847,6 +857,9 @@ hylra_status reuse_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pa
     rp.counters = fused ? ctx->counters : nullptr;
     rp.packets = pl.packets ? ctx->packets : nullptr;
     rp.err_word = ctx->err_word;
+    ctx->last_reuse_splits = pl.n_splits;
+    ctx->last_reuse_wave_rows = pl.variant >= 2 ? 8 * pl.R : 0;
+    ctx->last_reuse_merge = !fused ? 0 : pl.n_splits == 1 && pl.variant >= 2 ? 3 : pl.packets ? 2 : 1;
     rp.out = out;
     // (a workspace that other calls may have left in any state: the arrival counters must start
     // at zero; a fill kernel, not a memset, since the caller may be capturing the stream)

@@ -52,7 +52,8 @@ def check_full(out, idx, refs, k, what):
         assert_idx_valid(idx[b:b + 1, :, :kb], shats[b][None], kb, "%s idx b=%d" % (what, b), exact_ref=idxs[b][None])
 
 
-@pytest.mark.parametrize("B,Hkv,G,d,N,k", [(2, 2, 4, 128, 3000, 200), (1, 2, 4, 64, 1500, 64), (3, 1, 7, 128, 2049, 300)])
+@pytest.mark.parametrize("B,Hkv,G,d,N,k", [(2, 2, 4, 128, 3000, 200), (1, 2, 4, 64, 1500, 64), (3, 1, 7, 128, 2049, 300),
+                                          (1, 2, 4, 128, 5000, 1024)])       # (the last: Reuse merge by packets)
 def test_append_contiguous_equal_lengths(B, Hkv, G, d, N, k):
     """cache == NULL: the token becomes row N - 1 of every sequence."""
     say("append contiguous B=%d Hkv=%d G=%d d=%d N=%d k=%d" % (B, Hkv, G, d, N, k))
@@ -80,6 +81,8 @@ def test_append_contiguous_equal_lengths(B, Hkv, G, d, N, k):
             torch.cuda.synchronize()
             assert np.array_equal(bits(Kc2), refs[0]) and np.array_equal(bits(Vc2), refs[1])
             assert_out_close(sparse.cpu().numpy(), ref, "append reuse, append_unfused=%d" % unfused)
+            if k == 1024:
+                assert ctx.get_info("last_reuse_merge") == 2
 
 
 @pytest.mark.parametrize("page", [0, 16, 1])

@@ -102,7 +102,7 @@ def test_paged_full_kernel_variants(variant):
             check_full(out.cpu().numpy(), idx.cpu().numpy(), refs, lens, k, "variant %d split %d" % (variant, split_rows))
 
 
-@pytest.mark.parametrize("variant,waves", [(1, 4), (4, 4), (4, 8), (5, 8), (6, 4)])
+@pytest.mark.parametrize("variant,waves", [(1, 4), (4, 4), (4, 8), (5, 8), (6, 4), (5, 0)])    # (5, 0): merge by packets
 def test_paged_reuse_kernel_variants(variant, waves):
     say("paged reuse variant=%d waves=%d" % (variant, waves))
     B, Hkv, G, d, N, k, page = 3, 2, 4, 128, 4000, 1024, 16
@@ -116,6 +116,7 @@ def test_paged_reuse_kernel_variants(variant, waves):
         out = ctx.reuse_sparse_attn_paged(q, Kp, Vp, cache, torch.from_numpy(idx).to(DEV))
         torch.cuda.synchronize()
         out = out.cpu().numpy()
+        assert ctx.get_info("last_reuse_merge") == (2 if waves == 0 else 1)
     for b in range(B):
         n = int(lens[b])
         ref = oracle.reuse_sparse_attn(q[b:b + 1], K[b:b + 1, :, :n], V[b:b + 1, :, :n],

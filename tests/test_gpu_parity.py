@@ -265,6 +265,9 @@ def test_reuse_fused_merge_equals_two_kernel_merge(B, Hkv, G, d, N, k):
             ctx.reuse_sparse_attn(q, K, V, gidx, out=o)
             outs.append(o)
         torch.cuda.synchronize()
+        # the shapes with k <= 256 or many pairs are covered by one workgroup per pair
+        assert ctx.get_info("last_reuse_merge") in ((3,) if ctx.get_info("last_reuse_splits") == 1 else (1, 2))
+        assert (ctx.get_info("last_reuse_splits") == 1) == ((B, k) in ((2, 200), (1, 100), (32, 1024)))
     for it, o in enumerate(outs):
         assert torch.equal(o, two), "fused merge differs at launch %d" % it
     assert_out_close(two.cpu().numpy(), oracle.reuse_sparse_attn(q, K, V, idx), "reuse out")
@@ -308,6 +311,10 @@ def test_reuse_packet_merge_equals_two_kernel_merge(B, Hkv, G, k, unroll):
         torch.cuda.synchronize()
         prof = ctx.profile_read()
         assert prof["reuse_combine"][0] == 0
+        ctx.reuse_sparse_attn(q, K, V, gidx)
+        assert ctx.get_info("last_reuse_merge") == 2, "the launch did not merge by packets"
+        assert ctx.get_info("last_reuse_splits") == k // (512 if unroll == 8 else 128)
+        assert ctx.get_info("last_reuse_wave_rows") == (64 if unroll == 8 else 32)
     for it, o in enumerate(outs):
         assert torch.equal(o, two), "packet merge differs at launch %d" % it
     assert_out_close(two.cpu().numpy(), oracle.reuse_sparse_attn(q, K, V, idx), "reuse out")
@@ -406,16 +413,20 @@ def test_decode_step_longer_chain_and_baseline_policies():
                              top_k=150, full_layers=(0, 1)))              # group of 7, sink prefix
 
 
-def test_decode_step_replayed_from_a_hip_graph():
+@pytest.mark.parametrize("batch,ctx_len,top_k", [(16, 3000, 512), (1, 6000, 2048)])
+def test_decode_step_replayed_from_a_hip_graph(batch, ctx_len, top_k):
     """hylra_decode_step only launches kernels on the caller's stream, so a caller may capture
     it in a HIP graph.  Replays (with eager launches and synchronisations in between) must give
     the eager result: this covers the counters the kernels reset themselves.  Index sets and the
     Reuse layers' outputs must be bit-identical; a Full layer's output may differ in the last
     bits, because the self-scheduling kernel groups the rows into partial sums differently from
-    run to run (the row scores, and hence the index sets, do not depend on the grouping)."""
-    say("decode step under graph capture")
-    w = synth.scaled(synth.WORKLOADS["toy"], n_layers=6, full_layers=(0, 3), batch=16, n_q_heads=32, n_kv_heads=8,
-                     head_dim=128, ctx_len=3000, top_k=512)      # batch * n_kv_heads >= 64: the self-scheduling Full kernel
+    run to run (the row scores, and hence the index sets, do not depend on the grouping).
+    Batch 16: the self-scheduling Full kernel (batch * n_kv_heads >= 64) and the Reuse merge by
+    arrival counter; batch 1 with k = 2048: the Reuse merge by packets, whose units the
+    consumers clear themselves and which takes no launch number from the host."""
+    say("decode step under graph capture, batch %d" % batch)
+    w = synth.scaled(synth.WORKLOADS["toy"], n_layers=6, full_layers=(0, 3), batch=batch, n_q_heads=32, n_kv_heads=8,
+                     head_dim=128, ctx_len=ctx_len, top_k=top_k)
     policy, _, data = synth.make_workload(w, DEV)
     qs, Ks, Vs = [x[0] for x in data], [x[1] for x in data], [x[2] for x in data]
     with binding.Context(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ctx_len, w.top_k) as ctx:
