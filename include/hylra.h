@@ -97,9 +97,10 @@ hylra_status hylra_destroy(hylra_ctx *ctx);
 /* Puts the context's workspace back into its initial state: synchronises the device, zeroes the
  * counters and histograms the kernels keep between launches, clears the sticky error below.
  * HOST call.  Needed only after a call failed with the text "gave up waiting": the Full
- * kernels that hand rows out at run time bound every wait; should such a wait ever run out
- * (it cannot unless the device is failing), the launch leaves rows out, the context records
- * it, and every later call on the context fails with HYLRA_ERR_HIP until hylra_reset. */
+ * kernels that hand rows out at run time and the Reuse kernels that merge by packets bound
+ * every wait; should such a wait ever run out (it cannot unless the device is failing or
+ * two calls on one context overlapped), the launch's results are incomplete, the context
+ * records it, and every later call on the context fails with HYLRA_ERR_HIP until hylra_reset. */
 hylra_status hylra_reset(hylra_ctx *ctx);
 
 /* Static, never NULL. */

@@ -180,7 +180,7 @@ struct Strides {
 hylra_status check_shape(const hylra_ctx* ctx, const hylra_shape* s, int& G, Strides& st, float& scale) {
     if (!ctx) return HYLRA_ERR_BAD_ARG;
     if (ctx->err_word && *(volatile int*)ctx->err_word)
-        return fail(ctx, HYLRA_ERR_HIP, "an earlier launch of this context gave up waiting for rows to be handed out: "
+        return fail(ctx, HYLRA_ERR_HIP, "an earlier launch of this context gave up waiting (for rows to be handed out, or for another workgroup's partial results): "
                                         "its results are incomplete; call hylra_reset");
     if (!s) return fail(ctx, HYLRA_ERR_BAD_ARG, "shape is NULL");
     if (s->batch < 1 || s->n_q_heads < 1 || s->n_kv_heads < 1 || s->ctx_len < 1)
@@ -458,10 +458,9 @@ hylra_status plan_reuse(const hylra_ctx* ctx, const hylra_shape* s, int G, int k
     // the arrival counter is as fast (config 2: 16.1 against 16.5 us), its merging workgroup
     // then loads only 8 KB.
     auto packets_ok = [&](int NW, int64_t n) {
-        const int64_t units = n * (2 * G * n + (int64_t)G * 128);       // per (batch, KV head)
-        return mfma2 && ctx->packets && ctx->opt_reuse_unfused == 0 && ctx->opt_reuse_merge != 1 && n >= (ctx->opt_reuse_merge == 2 ? kMergeBlock : 8) && n <= 128 &&
-               (n & (n - 1)) == 0 && pairs * n <= ctx->n_cus && units / n <= (int64_t)kPacketUnitsPerThread * NW * 64 &&
-               pairs * units <= ctx->cap_packets;
+        return mfma2 && ctx->packets && ctx->opt_reuse_unfused == 0 && ctx->opt_reuse_merge != 1 &&
+               packets_fit(pairs, n, G, 128, NW * 64, kPacketUnitsPerThread, ctx->n_cus, ctx->cap_packets,
+                           ctx->opt_reuse_merge == 2 ? kMergeBlock : 8);
     };
     // With few (batch, KV head) pairs the gather is spread over twice as many workgroups (wave
     // tiles of 32 rows, 128 entries per workgroup) if the packets can carry the merge: the

@@ -93,29 +93,6 @@ DEVI void coherent_store(float* p, float v) {
 DEVI float coherent_load(const float* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// Merge of S online-softmax partials (max m_s in log2 units, sum l_s, accumulator a_s) into
-// out = sum_s w_s a_s / sum_s w_s l_s with w_s = 2^(m_s - max m).  Every merge in this library
-// adds in ONE order, so that they agree bit for bit whichever kernel runs it: blocks of four
-// consecutive partials are accumulated from zero with fused multiply-adds, and the block sums
-// are added to the total in block order (a lane per block can then share one element's merge).
-struct MergeSum {
-    float num = 0.f, den = 0.f;     // totals
-    float nb = 0.f, db = 0.f;       // the block under way
-    DEVI void add(int s, float w, float l, float a) {       // s = 0, 1, 2, ... in order
-        if (s % kMergeBlock == 0 && s) close_block();
-        db = fmaf(w, l, db);
-        nb = fmaf(w, a, nb);
-    }
-    DEVI void close_block() {
-        num += nb, den += db;
-        nb = 0.f, db = 0.f;
-    }
-    DEVI float result() {
-        close_block();
-        return den > 0.f ? num / den : 0.f;
-    }
-};
-
 // Wait until every vector memory operation this wave has issued is complete: s_waitcnt with
 // vmcnt = 0 and the other counters left alone.  The immediate's fields on gfx9: vmcnt low four
 // bits in [3:0] and its two high bits in [15:14]; expcnt in [6:4] (7 = do not wait); lgkmcnt in

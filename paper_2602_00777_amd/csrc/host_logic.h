@@ -1,10 +1,11 @@
 // The library's integer and host-side logic that needs no GPU: the chunk tables and segment
 // arithmetic of the self-scheduling Full kernels (used on the host to build the tables and on
-// the device to read them), the workgroup-to-group maps, and the offline policy search
-// (Algorithm 1; similarity matrix as in Eq. 2).  Plain C++ with no HIP types, so that it also
+// the device to read them), the workgroup-to-group maps, the layout of the Reuse layer's merge
+// packets, and the offline policy search (Algorithm 1; similarity matrix as in Eq. 2).  Plain C++ with no HIP types, so that it also
 // compiles with the host compiler alone: tests/host_logic_check.cpp runs it under the address
 // and undefined-behaviour sanitizers.
 #pragma once
+#include <math.h>
 #include <stdint.h>
 
 #include <vector>
@@ -108,6 +109,65 @@ HYLRA_HD PairSeg pair_segment(int n, int S, int w) {
     }
     r.w = w - r.wg0;
     return r;
+}
+
+// ---- the one merge order ---------------------------------------------------------------------
+constexpr int kMergeBlock = 4;      // partials per block
+// Merge of S online-softmax partials (max m_s in log2 units, sum l_s, accumulator a_s) into
+// out = sum_s w_s a_s / sum_s w_s l_s with w_s = 2^(m_s - max m).  Every merge in this library
+// adds in ONE order, so that they agree bit for bit whichever kernel runs it: blocks of four
+// consecutive partials are accumulated from zero with fused multiply-adds, and the block sums
+// are added to the total in block order (a lane per block can then share one element's merge).
+struct MergeSum {
+    float num = 0.f, den = 0.f;     // totals
+    float nb = 0.f, db = 0.f;       // the block under way
+    HYLRA_HD void add(int s, float w, float l, float a) {       // s = 0, 1, 2, ... in order
+        if (s % kMergeBlock == 0 && s) close_block();
+        db = fmaf(w, l, db);
+        nb = fmaf(w, a, nb);
+    }
+    HYLRA_HD void close_block() {
+        num += nb, den += db;
+        nb = 0.f, db = 0.f;
+    }
+    HYLRA_HD float result() {
+        close_block();
+        return den > 0.f ? num / den : 0.f;
+    }
+};
+
+// ---- merge by packets (Reuse layer): layout and limits ---------------------------------------
+// The S workgroups of a (batch, KV head) each merge D / S output columns of all G heads.
+// Producer s sends consumer c one packet of G (2 + D / S) units: [G][2] (max, sum) and then
+// [G][D / S] (its accumulator's columns c D / S ..).  The packets of a pair are laid out
+// [consumer][producer][unit], so that what a consumer polls is contiguous.
+struct PacketShape {
+    int S, W, PK;                   // partials per pair, columns per consumer, units per packet
+};
+HYLRA_HD PacketShape packet_shape(int G, int D, int S) {
+    PacketShape ps;
+    ps.S = S, ps.W = D / S, ps.PK = G * (2 + D / S);
+    return ps;
+}
+// unit (within the pair's S * S * PK) of head h's max (which = 0) or sum (1) from producer s to consumer c
+HYLRA_HD int64_t packet_ml_unit(const PacketShape& ps, int c, int s, int h, int which) {
+    return ((int64_t)c * ps.S + s) * ps.PK + 2 * h + which;
+}
+// unit of accumulator element (h, col) of producer s; G: heads per pair
+HYLRA_HD int64_t packet_acc_unit(const PacketShape& ps, int G, int s, int h, int col) {
+    const int c = col / ps.W, j = col - c * ps.W;
+    return ((int64_t)c * ps.S + s) * ps.PK + 2 * G + h * ps.W + j;
+}
+// Whether a launch of `pairs` pairs with n partials each may merge by packets: every workgroup
+// resident at once (at most one per compute unit), n a power of two between min_n and D (so
+// that it divides the D columns and groups of n / 4 lanes line up), what a workgroup of
+// `threads` threads receives within units_per_thread units per thread, everything within the
+// buffer of cap_units units.
+HYLRA_HD bool packets_fit(int64_t pairs, int64_t n, int G, int D, int threads, int units_per_thread, int n_cus,
+                          int64_t cap_units, int min_n) {
+    if (n < min_n || n < 4 || n > D || (n & (n - 1)) != 0 || D % n != 0) return false;
+    const int64_t per_consumer = n * (int64_t)G * (2 + D / n);
+    return pairs * n <= n_cus && per_consumer <= (int64_t)units_per_thread * threads && pairs * n * per_consumer <= cap_units;
 }
 
 // ---- offline profiling (host only) -----------------------------------------------------------

@@ -104,9 +104,6 @@ hipError_t launch_score_hist(const TopkParams& p, int B, hipStream_t st);
 // step 0: level-1 threshold, per-chunk counts and lists, merge of the partials; step 1: emission
 hipError_t launch_topk(const TopkParams& p, int B, int step, int n_cus, hipStream_t st);
 
-// Partials per block of the common merge order (MergeSum, device_util.h).
-constexpr int kMergeBlock = 4;
-
 // Merge by packets (reuse_tail.h): 64-bit units a thread of a consuming workgroup polls at most,
 // i.e. a workgroup of T threads receives at most kPacketUnitsPerThread * T units.
 constexpr int kPacketUnitsPerThread = 6;

@@ -131,7 +131,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2))) vo
         __shared__ float s_pk[kPacketUnitsPerThread * NW * 64];
         HYLRA_TS(3);
         stage_states2<G, NW>(st, s_m, s_l, s_acc, n, gq);
-        uint64_t* pk_pair = p.packets + pair * p.n_splits * p.n_splits * packet_units<G, D>(p.n_splits);
+        uint64_t* pk_pair = p.packets + pair * p.n_splits * p.n_splits * packet_shape(G, D, p.n_splits).PK;
         send_packets<G, D, NW * 64>(
             pk_pair, p.n_splits, split, [&](int h) { return staged_max<NW>(s_m, h); },
             [&](int h, float M) { return staged_sum<NW>(s_m, s_l, h, M); },

@@ -164,31 +164,24 @@ DEVI void reuse_merge_tail(const ReuseParams& p, int64_t pair, int64_t head0, in
 constexpr uint32_t kPacketFull = 1u;
 constexpr int kPacketSpins = 1 << 18;
 
-// units of a packet for S partials
-template <int G, int D>
-DEVI int packet_units(int S) { return G * (2 + D / S); }
-
-// Producer.  pk_pair: the pair's packets [consumer][producer][units]; max_of(h), sum_of(h, M),
-// acc_of(h, col, M): the workgroup's merged state.  Every thread calls.
+// Producer.  pk_pair: the pair's packets (layout: host_logic.h, PacketShape); max_of(h),
+// sum_of(h, M), acc_of(h, col, M): the workgroup's merged state.  Every thread calls.
 template <int G, int D, int NT, class FM, class FS, class FA>
 DEVI void send_packets(uint64_t* __restrict__ pk_pair, int S, int split, FM max_of, FS sum_of, FA acc_of) {
     const int tid = threadIdx.x;
-    const int W = D / S, PK = G * (2 + W);
-    const int lw = 31 - __clz(W);                 // S divides D = 2^x: W is a power of two
+    const PacketShape ps = packet_shape(G, D, S);
     auto put = [](uint64_t* p, float v) {
         __hip_atomic_store(p, ((uint64_t)kPacketFull << 32) | __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     };
     for (int i = tid; i < G * D; i += NT) {
         const int h = i / D, col = i - h * D;
-        const int c = col >> lw, j = col & (W - 1);
-        put(pk_pair + ((int64_t)c * S + split) * PK + 2 * G + h * W + j, acc_of(h, col, max_of(h)));
+        put(pk_pair + packet_acc_unit(ps, G, split, h, col), acc_of(h, col, max_of(h)));
     }
     for (int i = tid; i < S * G; i += NT) {
         const int c = i / G, h = i - c * G;
         const float M = max_of(h);
-        uint64_t* dst = pk_pair + ((int64_t)c * S + split) * PK + 2 * h;
-        put(dst, M);
-        put(dst + 1, sum_of(h, M));
+        put(pk_pair + packet_ml_unit(ps, c, split, h, 0), M);
+        put(pk_pair + packet_ml_unit(ps, c, split, h, 1), sum_of(h, M));
     }
 }
 
@@ -198,9 +191,10 @@ DEVI void reuse_packet_tail(const ReuseParams& p, uint64_t* __restrict__ pk_pair
                             float* s_pk) {
     constexpr int U = kPacketUnitsPerThread;
     const int tid = threadIdx.x;
-    const int S = p.n_splits, W = D / S, PK = G * (2 + W), total = S * PK;
+    const PacketShape ps = packet_shape(G, D, p.n_splits);
+    const int S = ps.S, W = ps.W, PK = ps.PK, total = S * PK;
     const int nu = (total + NT - 1) / NT;                   // units per thread (<= U: the host checks)
-    uint64_t* __restrict__ mine = pk_pair + (int64_t)split * S * PK;
+    uint64_t* __restrict__ mine = pk_pair + packet_ml_unit(ps, split, 0, 0, 0);      // S packets, contiguous
     HYLRA_TS(4);
     // Every round reads all of the thread's units again, without branches, so that the loads of
     // a round are in flight together (a unit that was full stays full until this thread clears

@@ -5,11 +5,17 @@
 //      whichever workgroup claims when, every workgroup ends with exactly one failed claim (none
 //      if it never had a chunk to start on), and the claim counter is back at zero afterwards;
 //   2. the workgroup-to-group maps (paired_unit, pair_segment) are bijections;
-//   3. the policy search against exhaustive search over all policies on small matrices.
+//   3. the policy search against exhaustive search over all policies on small matrices;
+//   4. the layout of the Reuse layer's merge packets (every unit has one writer and one reader, a
+//      consumer's units are contiguous), the limits under which a launch may merge that way, and
+//      the one merge order (blocks of four partials) against a merge in double precision, run
+//      through the packets for several launches in a row with the readers clearing what they took.
 // The device code reads the tables through the same functions; what is modelled here in plain
 // C++ is only the order of the claims (a seeded random interleaving of the workgroups).
+#include <cmath>
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
 #include <random>
 #include <vector>
 
@@ -179,6 +185,101 @@ static void check_policy(std::mt19937& rng) {
     }
 }
 
+// Packets: the producers' unit numbers (as send_packets forms them) against the consumers'
+// (consumer c polls units [c S PK, (c + 1) S PK) and finds partial s's head-h values at
+// s PK + 2 h, + 1 and its element (h, j) at s PK + 2 G + h W + j of that range), over several
+// launches on one buffer that starts all empty and that the readers clear.
+static void check_packets(std::mt19937& rng) {
+    const int D = 128;
+    std::uniform_real_distribution<float> val(-3.f, 3.f), pos(0.1f, 50.f);
+    for (int G = 1; G <= 8; ++G)
+        for (int S : {4, 8, 16, 32, 64, 128}) {
+            const PacketShape ps = packet_shape(G, D, S);
+            CHECK(ps.W * S == D && ps.PK == G * (2 + ps.W), "shape G=%d S=%d", G, S);
+            const int64_t total = (int64_t)S * S * ps.PK;
+            std::vector<uint64_t> buf(total, 0);                 // {value, tag} units, tag 0 = empty
+            for (int launch = 0; launch < 3; ++launch) {
+                std::vector<float> m(S * G), l(S * G), acc((size_t)S * G * D);
+                for (auto& x : m) x = val(rng);
+                for (auto& x : l) x = pos(rng);
+                for (auto& x : acc) x = val(rng);
+                if (launch == 1)                                  // a producer that saw no rows
+                    for (int h = 0; h < G; ++h) m[h] = -1.0e30f, l[h] = 0.f;
+                auto put = [&](int64_t u, float v) {
+                    CHECK(u >= 0 && u < total, "unit %lld outside the pair's %lld", (long long)u, (long long)total);
+                    CHECK((buf[u] >> 32) == 0, "unit %lld written twice (G=%d S=%d)", (long long)u, G, S);
+                    uint32_t bits;
+                    std::memcpy(&bits, &v, 4);
+                    buf[u] = ((uint64_t)1 << 32) | bits;
+                };
+                for (int s = 0; s < S; ++s) {
+                    for (int h = 0; h < G; ++h)
+                        for (int col = 0; col < D; ++col) put(packet_acc_unit(ps, G, s, h, col), acc[((size_t)s * G + h) * D + col]);
+                    for (int c = 0; c < S; ++c)
+                        for (int h = 0; h < G; ++h) {
+                            put(packet_ml_unit(ps, c, s, h, 0), m[s * G + h]);
+                            put(packet_ml_unit(ps, c, s, h, 1), l[s * G + h]);
+                        }
+                }
+                for (int64_t u = 0; u < total; ++u) CHECK((buf[u] >> 32) == 1, "unit %lld never written (G=%d S=%d)", (long long)u, G, S);
+                for (int c = 0; c < S; ++c) {
+                    const int64_t first = packet_ml_unit(ps, c, 0, 0, 0);
+                    CHECK(first == (int64_t)c * S * ps.PK, "consumer %d starts at %lld", c, (long long)first);
+                    std::vector<float> pk((size_t)S * ps.PK);
+                    for (int i = 0; i < S * ps.PK; ++i) {
+                        const uint32_t bits = (uint32_t)buf[first + i];
+                        std::memcpy(&pk[i], &bits, 4);
+                        buf[first + i] = 0;                       // the reader clears what it took
+                    }
+                    for (int h = 0; h < G; ++h)
+                        for (int j = 0; j < ps.W; ++j) {
+                            float M = -1.0e30f;
+                            for (int s = 0; s < S; ++s) M = std::fmax(M, pk[s * ps.PK + 2 * h]);
+                            // as the consumer's lanes do it: one block of four per lane, block sums in block order
+                            float den = 0.f, num = 0.f;
+                            for (int blk = 0; blk < S / kMergeBlock; ++blk) {
+                                float db = 0.f, nb = 0.f;
+                                for (int i = 0; i < kMergeBlock; ++i) {
+                                    const int s = blk * kMergeBlock + i;
+                                    const float w = std::exp2(pk[s * ps.PK + 2 * h] - M);
+                                    db = std::fmaf(w, pk[s * ps.PK + 2 * h + 1], db);
+                                    nb = std::fmaf(w, pk[s * ps.PK + 2 * G + h * ps.W + j], nb);
+                                }
+                                den += db, num += nb;
+                            }
+                            const float got = den > 0.f ? num / den : 0.f;
+                            // the sequential form of the same order, fed straight from the producers' values
+                            MergeSum sum;
+                            double dn = 0.0, dd = 0.0;
+                            const int col = c * ps.W + j;
+                            for (int s = 0; s < S; ++s) {
+                                const float w = std::exp2(m[s * G + h] - M);
+                                sum.add(s, w, l[s * G + h], acc[((size_t)s * G + h) * D + col]);
+                                dn += (double)w * acc[((size_t)s * G + h) * D + col];
+                                dd += (double)w * l[s * G + h];
+                            }
+                            const float want = sum.result();
+                            CHECK(std::memcmp(&got, &want, 4) == 0 || (got == 0.f && want == 0.f), "merge order differs: %g vs %g (G=%d S=%d)", got, want, G, S);
+                            CHECK(std::fabs(got - dn / dd) <= 1e-5 * (1.0 + std::fabs(dn / dd)), "merge value %g vs %g", got, dn / dd);
+                        }
+                }
+                for (int64_t u = 0; u < total; ++u) CHECK(buf[u] == 0, "unit %lld left full after the launch", (long long)u);
+            }
+        }
+    // the limits: what the benchmark shapes choose, and what must be refused
+    const int64_t cap = 256 * 6 * 512;
+    CHECK(packets_fit(8, 32, 4, 128, 256, 6, 256, cap, 8), "batch 1, 8 KV heads, k = 4096");
+    CHECK(packets_fit(16, 16, 7, 128, 256, 6, 256, cap, 8), "batch 4, 4 KV heads of 7, k = 2048");
+    CHECK(packets_fit(2, 32, 8, 128, 256, 6, 256, cap, 8), "G = 8 with 32 partials just fits 6 units per thread");
+    CHECK(!packets_fit(1, 64, 8, 128, 256, 6, 256, cap, 8), "G = 8 with 64 partials: more than a thread polls");
+    CHECK(!packets_fit(64, 4, 4, 128, 512, 6, 256, cap, 8), "4 partials: below the automatic minimum");
+    CHECK(packets_fit(64, 4, 4, 128, 512, 6, 256, cap, 4), "4 partials when asked for");
+    CHECK(!packets_fit(64, 8, 4, 128, 256, 6, 256, cap, 8), "more workgroups than compute units");
+    CHECK(!packets_fit(8, 24, 4, 128, 256, 6, 256, cap, 8) && !packets_fit(8, 2, 4, 128, 256, 6, 256, cap, 2) && !packets_fit(1, 256, 1, 128, 256, 6, 256, cap, 8),
+          "not a power of two, fewer than a merge block, more partials than columns");
+    CHECK(!packets_fit(8, 32, 4, 128, 256, 6, 256, 1000, 8), "buffer too small");
+}
+
 int main() {
     std::mt19937 rng(12345);
     int cases = 0;
@@ -195,6 +296,7 @@ int main() {
         }
     check_maps();
     check_policy(rng);
+    check_packets(rng);
     std::printf("host logic ok: %d segment cases\n", cases);
     return 0;
 }
