@@ -442,9 +442,9 @@ hylra_status hylra_policy_search(hylra_ctx *ctx, int32_t n_layers, const double 
  *                       few (batch, KV head) pairs twice as many workgroups with wave tiles of
  *                       32 rows.  The workgroups of such a launch wait for one another (bounded:
  *                       see hylra_reset), which needs all of them resident at once: a launch
- *                       takes at most a quarter of a wave slot per compute unit, so several can
- *                       share the device, but a device kept full by other long-running work is a
- *                       reason to set 1.
+ *                       puts at most one workgroup of 4 or 8 waves on a compute unit (which holds
+ *                       32), so several can share the device, but a device kept full by other
+ *                       long-running work is a reason to set 1.
  *   "reuse_unfused"     1 = merge the Reuse partials in a second kernel instead of in the
  *                       last-arriving workgroup of the Reuse kernel
  *   "simulate_give_up"  1 = mark the context as if a kernel had given up a bounded wait (for
