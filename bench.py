@@ -351,7 +351,12 @@ def main():
                    "top_k": k, "block": args.block or 1, "page_size": args.paged or None,
                    "seq_lens": lens.tolist() if lens is not None else None, "hip_graph": bool(args.graph),
                    "append": bool(args.append),
-                   "kv_dtype": "bf16", "accumulate": "f32"},
+                   "kv_dtype": "bf16", "accumulate": "f32",
+                   # what the library chose for the Reuse layers (hylra_get_info)
+                   "reuse_launch": {"partials_per_pair": ctx.get_info("last_reuse_splits"),
+                                    "wave_rows": ctx.get_info("last_reuse_wave_rows"),
+                                    "merge": ("second kernel", "arrival counter", "packets", "one workgroup per pair")[
+                                        ctx.get_info("last_reuse_merge")]} if n_reuse else None},
         "ms_per_step_topk_at_every_full_layer": round(ms_every, 4) if ms_every else None,
         "parity_checked": parity is not None,
         "parity": parity,
