@@ -40,6 +40,48 @@ def test_full_size_decode_step_all_pairs(name):
     assert res["layers"] == w.n_layers and res["pairs"] == w.n_layers * w.batch * w.n_kv_heads
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name", ["llama3_8b_32k", "long_131k", "qwen25_7b_64k"])
+def test_full_size_decode_step_append_all_pairs(name):
+    """hylra_decode_step_append at full shape: the caches start with another row at position
+    N - 1, the step receives the true rows as k_new / v_new (every layer its own), and must leave
+    the caches exactly as they were drawn and give the outputs of a step over them -- every
+    layer and every pair against the oracle.  The Reuse layers write their row inside their own
+    launch (merging by packets at the small-batch shapes), the Full layers with a launch before."""
+    from tests.step_check import check_step
+
+    print("[case] full size decode step with append, all layers, all pairs: %s" % name, flush=True)
+    w = synth.WORKLOADS[name]
+    policy = w.policy()
+    planted = synth.planted_positions(w)
+    N = w.ctx_len
+    qs, Ks, Vs, k_new, v_new = [], [], [], [], []
+    for l in range(w.n_layers):
+        q, K, V = synth.make_layer(w, l, planted[l], DEV)
+        # the token's key is pushed along the group's mean query, so that every set names row N - 1
+        qm = q.view(w.batch, w.n_kv_heads, w.group, w.head_dim).float().mean(2)
+        K[:, :, N - 1, :] = (K[:, :, N - 1, :].float() + 3.0 * qm).to(torch.bfloat16)
+        k_new.append(K[:, :, N - 1, :].clone()), v_new.append(V[:, :, N - 1, :].clone())
+        K[:, :, N - 1, :] = 7.0                    # what the append must replace
+        V[:, :, N - 1, :] = -3.0
+        qs.append(q), Ks.append(K), Vs.append(V)
+    with binding.Context(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, N, w.top_k) as ctx:
+        run, outs, idx_buf = ctx.prepare_step_append(policy, qs, k_new, v_new, Ks, Vs, w.top_k)
+        run()
+        run()
+        torch.cuda.synchronize()
+        for l in range(w.n_layers):
+            assert torch.equal(Ks[l][:, :, N - 1, :].view(torch.int16), k_new[l].view(torch.int16)), "layer %d: K row" % l
+            assert torch.equal(Vs[l][:, :, N - 1, :].view(torch.int16), v_new[l].view(torch.int16)), "layer %d: V row" % l
+        if w.batch * w.n_kv_heads <= 16:
+            assert ctx.get_info("last_reuse_merge") == 2
+        assert bool((idx_buf == N - 1).any(dim=2).all()), "the new row is not in every index set"
+        res = check_step(ctx, policy, qs, Ks, Vs, w.top_k, outs, idx_buf,
+                         say=lambda m: print("  " + m, flush=True))
+    print("  %s" % res, flush=True)
+    assert res["layers"] == w.n_layers and res["pairs"] == w.n_layers * w.batch * w.n_kv_heads
+
+
 def sample_pairs(B, Hkv):
     pairs = {(0, 0), (B - 1, Hkv - 1), (B // 2, Hkv // 2), (0, Hkv - 1)}
     return sorted(pairs)
