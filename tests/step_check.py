@@ -36,10 +36,12 @@ class _Stage:
         return self.buf[key]
 
 
-def check_step(ctx, policy, qs, Ks, Vs, k, outs, idx_buf, layers=None, say=None):
+def check_step(ctx, policy, qs, Ks, Vs, k, outs, idx_buf, layers=None, say=None, lens=None):
     """Compares the outputs of one hylra_decode_step (outs, idx_buf; contiguous token-level
-    layout) with the oracle on every pair of the layers in `layers` (None: all).  Raises
-    AssertionError on the first violation; returns a summary dict."""
+    layout) with the oracle on every pair of the layers in `layers` (None: all).  lens: the
+    per-sequence lengths the step ran with (hylra_decode_step_paged without a block table);
+    sequence b is then checked on its first lens[b] rows, its set holds min(k, lens[b]) entries
+    and -1 behind them.  Raises AssertionError on the first violation; returns a summary dict."""
     L = len(policy)
     want = set(range(L)) if layers is None else set(int(l) for l in layers)
     src_of = {}
@@ -57,6 +59,9 @@ def check_step(ctx, policy, qs, Ks, Vs, k, outs, idx_buf, layers=None, say=None)
     summary = {"layers": 0, "pairs": 0, "max_err_full": 0.0, "max_err_reuse": 0.0, "sets_differing_in_band": 0,
                "oracle_s": 0.0}
     B, Hkv = Ks[0].shape[0], Ks[0].shape[1]
+    if lens is not None:
+        return _check_step_lens(ctx, policy, qs, Ks, Vs, k, outs, idx_buf, lens, want, need_idx, src_of, last_full,
+                                layers is None, stage, summary, say)
     for l in sorted(want | need_idx):
         if policy[l] == REUSE and l not in want:
             continue
@@ -85,5 +90,56 @@ def check_step(ctx, policy, qs, Ks, Vs, k, outs, idx_buf, layers=None, say=None)
         if say:
             say("layer %d %s checked on %d pairs" % (l, "Full" if policy[l] == FULL else "Reuse", B * Hkv))
     if layers is None:
+        assert np.array_equal(idx_buf.cpu().numpy(), gpu_idx[last_full]), "idx_buf is not the last Full layer's set"
+    return summary
+
+
+def _check_step_lens(ctx, policy, qs, Ks, Vs, k, outs, idx_buf, lens, want, need_idx, src_of, last_full, whole,
+                     stage, summary, say):
+    """check_step for a step that ran with per-sequence lengths: the oracle is called per
+    sequence on the rows that sequence has."""
+    from paper_2602_00777_amd import binding
+
+    B, Hkv, N = Ks[0].shape[0], Ks[0].shape[1], Ks[0].shape[2]
+    cache = binding.PagedCache(None, 0, N, torch.from_numpy(np.asarray(lens, np.int32)).to(qs[0].device))
+    gpu_idx = {}
+    for l in sorted(want | need_idx):
+        if policy[l] == REUSE and l not in want:
+            continue
+        q, K, V = qs[l].cpu(), stage.fetch(Ks[l], "K"), stage.fetch(Vs[l], "V")
+        got = outs[l].cpu().numpy()
+        if policy[l] == FULL and l in need_idx:
+            _, g = ctx.full_attn_topk_paged(qs[l], Ks[l], Vs[l], cache, k)
+            torch.cuda.synchronize()
+            gpu_idx[l] = g.cpu().numpy()
+        t0 = time.perf_counter()
+        for b in range(B):
+            n = int(lens[b])
+            kb = min(k, n)
+            if n == 0:
+                assert np.all(got[b] == 0.0), "layer %d: a sequence without rows must give zeros" % l
+                continue
+            qb, Kb, Vb = q[b:b + 1], K[b:b + 1, :, :n], V[b:b + 1, :, :n]
+            if policy[l] == FULL:
+                sel = l in need_idx
+                ref_out, ref_idx, shat = oracle.full_attn_topk(qb, Kb, Vb, kb, want_out=l in want, want_idx=sel, want_shat=sel)
+                if sel:
+                    assert np.all(gpu_idx[l][b, :, kb:] == -1), "layer %d b=%d: entries behind the set" % (l, b)
+                    summary["sets_differing_in_band"] += assert_idx_valid(gpu_idx[l][b:b + 1, :, :kb], shat, kb,
+                                                                          "layer %d b=%d idx" % (l, b), exact_ref=ref_idx)
+                if l in want:
+                    err = assert_out_close(got[b:b + 1], ref_out, "layer %d (Full) b=%d out" % (l, b))
+                    summary["max_err_full"] = max(summary["max_err_full"], err)
+            else:
+                ref_out = oracle.reuse_sparse_attn(qb, Kb, Vb, gpu_idx[src_of[l]][b:b + 1])
+                err = assert_out_close(got[b:b + 1], ref_out, "layer %d (Reuse of %d) b=%d out" % (l, src_of[l], b))
+                summary["max_err_reuse"] = max(summary["max_err_reuse"], err)
+        summary["oracle_s"] += time.perf_counter() - t0
+        if l in want:
+            summary["layers"] += 1
+            summary["pairs"] += B * Hkv
+        if say:
+            say("layer %d %s checked on %d pairs" % (l, "Full" if policy[l] == FULL else "Reuse", B * Hkv))
+    if whole:
         assert np.array_equal(idx_buf.cpu().numpy(), gpu_idx[last_full]), "idx_buf is not the last Full layer's set"
     return summary

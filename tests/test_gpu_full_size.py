@@ -82,6 +82,54 @@ def test_full_size_decode_step_append_all_pairs(name):
     assert res["layers"] == w.n_layers and res["pairs"] == w.n_layers * w.batch * w.n_kv_heads
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("name,page,ragged", [("llama3_8b_32k", 16, False), ("llama3_8b_32k", 16, True), ("long_131k", 64, False)])
+def test_full_size_paged_step_against_contiguous_step(name, page, ragged):
+    """hylra_decode_step_paged at full shape on pools scattered by a random block table (and with
+    per-sequence lengths): with equal lengths it must select the sets of the contiguous step
+    (which the test above checks against the oracle on every pair) and give its Reuse outputs
+    bit for bit and its Full outputs to the last bits; with lengths, the step over the
+    contiguous cache with the same lengths is the reference, and is itself checked against the
+    oracle on every layer and pair, each sequence on the rows it has."""
+    print("[case] full size paged step %s page=%d ragged=%s" % (name, page, ragged), flush=True)
+    w = synth.WORKLOADS[name]
+    policy = w.policy()
+    planted = synth.planted_positions(w)
+    N = w.ctx_len
+    table = synth.page_table(w.batch, N, page, w.seed)
+    lens = synth.ragged_lengths(w.batch, N, w.seed) if ragged else None
+    lens_d = torch.from_numpy(lens).to(DEV) if ragged else None
+    qs, Ks, Vs, Kp, Vp = [], [], [], [], []
+    for l in range(w.n_layers):
+        q, K, V = synth.make_layer(w, l, planted[l], DEV)
+        qs.append(q), Ks.append(K), Vs.append(V)
+        Kp.append(synth.to_pool(K, table, page)), Vp.append(synth.to_pool(V, table, page))
+    flat = binding.PagedCache(None, 0, N, lens_d) if ragged else None
+    paged = binding.PagedCache(torch.from_numpy(table).to(DEV), page, N, lens_d)
+    with binding.Context(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, N, w.top_k) as ctx:
+        run, outs, idx_buf = ctx.prepare_step(policy, qs, Ks, Vs, w.top_k, paged=flat)
+        run()
+        torch.cuda.synchronize()
+        if ragged:               # the reference step itself, every layer and pair against the oracle
+            from tests.step_check import check_step
+            res = check_step(ctx, policy, qs, Ks, Vs, w.top_k, outs, idx_buf, lens=lens)
+            print("  %s" % res, flush=True)
+            assert res["layers"] == w.n_layers
+        want = [o.clone() for o in outs]
+        want_idx = idx_buf.clone()
+        run, outs, idx_buf = ctx.prepare_step(policy, qs, Kp, Vp, w.top_k, paged=paged)
+        run()
+        run()
+        torch.cuda.synchronize()
+    assert torch.equal(idx_buf, want_idx), "index sets differ"
+    for l in range(w.n_layers):
+        if policy[l] == synth.REUSE:
+            assert torch.equal(outs[l], want[l]), "Reuse layer %d differs" % l
+        else:
+            err = (outs[l] - want[l]).abs().max().item() / want[l].abs().max().item()
+            assert err < 1e-5, "Full layer %d differs by %.2e" % (l, err)
+
+
 def sample_pairs(B, Hkv):
     pairs = {(0, 0), (B - 1, Hkv - 1), (B // 2, Hkv // 2), (0, Hkv - 1)}
     return sorted(pairs)
