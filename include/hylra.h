@@ -144,7 +144,7 @@ hylra_status hylra_reuse_sparse_attn(hylra_ctx *ctx, const hylra_shape *shape,
  * CURRENT HIP device; hip_stream must belong to it.  Arguments, results and numerics are those
  * of hylra_reuse_sparse_attn (same kernels, same split plan).
  * Limits: batch * n_kv_heads <= 2048 and batch * n_q_heads * splits <= 4096, where splits is
- * the number of workgroups the plan gives one (batch, KV head) (every BASELINE shape fits);
+ * the number of workgroups the plan gives one (batch, KV head) (every benchmark shape fits);
  * anything larger fails with HYLRA_ERR_WORKSPACE before a kernel is launched.  Failures leave
  * their text in hylra_last_error(NULL) (per thread).
  * All calls on one GPU share the one array: calls that overlap in time on one GPU (two

@@ -3,8 +3,8 @@
 ``roofline.traffic`` field.
 
     python -m paper_2602_00777_amd.profile_summary --workload llama3_8b_32k \\
-        --stats gpurun_out/prof_stats_llama3_8b_32k \\
-        --fetch gpurun_out/prof_fetch_llama3_8b_32k --write gpurun_out/prof_write_llama3_8b_32k
+        --stats out/prof_stats_llama3_8b_32k \\
+        --fetch out/prof_fetch_llama3_8b_32k --write out/prof_write_llama3_8b_32k
 
 The three directories come from (run from /tmp with TMPDIR=/tmp, one counter per run):
 

@@ -393,7 +393,7 @@ def check_chain(w, ctx=None):
 
 
 def test_decode_step_toy_config():
-    """BASELINE config 1: 2-layer toy, policy [full, reuse]."""
+    """The smallest benchmark configuration: 2-layer toy, policy [full, reuse]."""
     say("decode_step toy")
     w = synth.WORKLOADS["toy"]
     planted, idx = check_chain(w)
