@@ -97,8 +97,8 @@ hylra_status hylra_destroy(hylra_ctx *ctx);
 /* Puts the context's workspace back into its initial state: synchronises the device, zeroes the
  * counters and histograms the kernels keep between launches, clears the sticky error below.
  * HOST call.  Needed only after a call failed with the text "gave up waiting": the Full
- * kernels that hand rows out at run time and the Reuse kernels that merge by packets bound
- * every wait; should such a wait ever run out (it cannot unless the device is failing or
+ * kernels that hand rows out at run time, the one-launch top-k selection and the Reuse kernels
+ * that merge by packets bound every wait; should such a wait ever run out (it cannot unless the device is failing or
  * two calls on one context overlapped), the launch's results are incomplete, the context
  * records it, and every later call on the context fails with HYLRA_ERR_HIP until hylra_reset. */
 hylra_status hylra_reset(hylra_ctx *ctx);
@@ -452,6 +452,10 @@ hylra_status hylra_policy_search(hylra_ctx *ctx, int32_t n_layers, const double 
  *   "append_unfused"    1 = hylra_append_reuse_sparse_attn and the Reuse layers of
  *                       hylra_decode_step_append write the new rows with a launch of their own
  *                       instead of inside the Reuse kernel
+ *   "topk_two_launches" 1 = the top-k selection after the streaming pass always runs as two
+ *                       launches (scan, emit).  Default: one launch when it has no more
+ *                       workgroups than the device has compute units (its workgroups wait for one
+ *                       another's counts, bounded: see hylra_reset), two otherwise.
  *   "hist_unfused"      1 = the first histogram of the top-k selection is made by a launch of
  *                       its own instead of inside the Full layer's streaming kernel
  *   "full_unpaired"     1 = the self-scheduling Full kernels group their workgroups by number
@@ -463,12 +467,16 @@ hylra_status hylra_policy_search(hylra_ctx *ctx, int32_t n_layers, const double 
 hylra_status hylra_set_option(hylra_ctx *ctx, const char *name, int32_t value);
 
 /*
- * What the library decided for the most recent Reuse-layer launch of the context ("Sparse
- * Attention", Algorithm 2's Reuse branch), for tests and for tuning.  *value (HOST) receives:
+ * What the library decided for the most recent launches of the context, for tests and for
+ * tuning.  *value (HOST) receives, for the most recent Reuse-layer launch ("Sparse Attention",
+ * Algorithm 2's Reuse branch):
  *   "last_reuse_splits"     workgroups (= partials) per (batch, KV head)
  *   "last_reuse_wave_rows"  index entries a wave takes per sweep (matrix-core kernels: 32 or 64)
  *   "last_reuse_merge"      how the partials met: 0 = a second kernel, 1 = arrival counter,
  *                           2 = packets, 3 = one workgroup per pair, nothing to merge
+ * and for the most recent Full-layer call ("TopK", Algorithm 2's Full branch):
+ *   "last_topk_launches"    launches of the selection after the streaming pass: 1, 2, or 0 if
+ *                           the layer's index set was not wanted
  * 0 everywhere before the first such launch.  An unknown name is HYLRA_ERR_BAD_ARG.
  */
 hylra_status hylra_get_info(const hylra_ctx *ctx, const char *name, int32_t *value);

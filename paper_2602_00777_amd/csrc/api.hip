@@ -100,6 +100,9 @@ struct hylra_ctx {
     int32_t* lens_plus = nullptr;   // [max batch] sequence lengths after an append (see append_impl)
     uint64_t* packets = nullptr;    // packets of the Reuse kernels' merge (reuse_tail.h), all zero between launches
     int64_t cap_packets = 0;        // 64-bit units
+    uint64_t* topk_headers = nullptr;   // [pairs][max_chunks][max_chunks] headers of the one-launch selection, zero between launches
+    int64_t n_topk_headers = 0;
+    int topk_occupancy = 0;         // workgroups of the one-launch selection a compute unit holds
     int4* wg_map = nullptr;     // deal of the Full kernel's workgroups to sequences of different lengths
     int2* pair_map = nullptr;   // (see RaggedPlanParams): `slots` and `pairs_cap` entries
     int n_cus = 0;              // compute units of the device
@@ -126,6 +129,8 @@ struct hylra_ctx {
     int32_t opt_hist_unfused = 0;
     int32_t opt_append_unfused = 0;
     int32_t opt_reuse_merge = 0;
+    int32_t opt_topk_two_launches = 0;
+    int32_t last_topk_launches = 0;
     int32_t last_reuse_splits = 0, last_reuse_wave_rows = 0, last_reuse_merge = 0;   // see hylra_get_info
 
     bool prof_on = false;
@@ -576,6 +581,13 @@ hylra_status hylra_create_ex(hylra_ctx** out, const hylra_shape* max_shape, int3
     ctx->cap_packets = (int64_t)std::max(ctx->n_cus, 1) * kPacketUnitsPerThread * 512;
     if (e == hipSuccess) e = hipMalloc((void**)&ctx->packets, ctx->cap_packets * sizeof(uint64_t));
     if (e == hipSuccess) e = hipMemset(ctx->packets, 0, ctx->cap_packets * sizeof(uint64_t));
+    // headers of the one-launch selection (left out for contexts whose lengths would need more than 64 MiB of them)
+    ctx->n_topk_headers = pairs * ctx->max_chunks * ctx->max_chunks;
+    if (ctx->n_topk_headers <= (8 << 20)) {
+        if (e == hipSuccess) e = hipMalloc((void**)&ctx->topk_headers, ctx->n_topk_headers * sizeof(uint64_t));
+        if (e == hipSuccess) e = hipMemset(ctx->topk_headers, 0, ctx->n_topk_headers * sizeof(uint64_t));
+        ctx->topk_occupancy = topk_one_launch_occupancy();
+    }
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) {
         fail(nullptr, HYLRA_ERR_HIP, "workspace allocation failed: %s", hipGetErrorString(e));
@@ -611,6 +623,7 @@ hylra_status hylra_destroy(hylra_ctx* ctx) {
     if (ctx->pair_map) (void)hipFree(ctx->pair_map);
     if (ctx->lens_plus) (void)hipFree(ctx->lens_plus);
     if (ctx->packets) (void)hipFree(ctx->packets);
+    if (ctx->topk_headers) (void)hipFree(ctx->topk_headers);
     delete ctx;
     return HYLRA_OK;
 }
@@ -623,6 +636,7 @@ hylra_status hylra_reset(hylra_ctx* ctx) {
     HIP_TRY(ctx, hipMemset(ctx->chunk_ctr, 0, ctx->slots * kCtrStride * sizeof(int)));
     HIP_TRY(ctx, hipMemset(ctx->sel_ws, 0, ctx->sel_ints * sizeof(int)));
     HIP_TRY(ctx, hipMemset(ctx->packets, 0, ctx->cap_packets * sizeof(uint64_t)));
+    if (ctx->topk_headers) HIP_TRY(ctx, hipMemset(ctx->topk_headers, 0, ctx->n_topk_headers * sizeof(uint64_t)));
     HIP_TRY(ctx, hipDeviceSynchronize());
     ctx->in_step = false, ctx->step_planned = false;
     if (ctx->err_word) *ctx->err_word = 0;
@@ -634,6 +648,7 @@ hylra_status hylra_get_info(const hylra_ctx* ctx, const char* name, int32_t* val
     if (!std::strcmp(name, "last_reuse_splits")) *value = ctx->last_reuse_splits;
     else if (!std::strcmp(name, "last_reuse_wave_rows")) *value = ctx->last_reuse_wave_rows;
     else if (!std::strcmp(name, "last_reuse_merge")) *value = ctx->last_reuse_merge;
+    else if (!std::strcmp(name, "last_topk_launches")) *value = ctx->last_topk_launches;
     else return HYLRA_ERR_BAD_ARG;
     return HYLRA_OK;
 }
@@ -653,6 +668,7 @@ hylra_status hylra_set_option(hylra_ctx* ctx, const char* name, int32_t value) {
     else if (!std::strcmp(name, "hist_unfused")) ctx->opt_hist_unfused = value;
     else if (!std::strcmp(name, "append_unfused")) ctx->opt_append_unfused = value;
     else if (!std::strcmp(name, "reuse_merge")) ctx->opt_reuse_merge = value;
+    else if (!std::strcmp(name, "topk_two_launches")) ctx->opt_topk_two_launches = value;
     else if (!std::strcmp(name, "simulate_give_up")) {      // what a kernel whose bounded wait ran out would report
         if (ctx->err_word) *ctx->err_word = value ? 1 : 0;
     }
@@ -792,10 +808,20 @@ hylra_status full_impl(hylra_ctx* ctx, const hylra_shape* shape, const hylra_pag
     tp.chunk_info = tp.pair_info + ctx->pairs_cap;
     tp.chunk_list = tp.chunk_info + ctx->pairs_cap * ctx->max_chunks;
     tp.max_chunks = ctx->max_chunks;
+    tp.headers = ctx->topk_headers, tp.err_word = ctx->err_word;
     if (want_idx && ceil_div(n_sel, kTopkChunkRows) > ctx->max_chunks)
         return fail(ctx, HYLRA_ERR_WORKSPACE, "ctx_len = %d exceeds the selection workspace", shape->ctx_len);
     if (want_idx && !hist_in_kernel)
         HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_score_hist(tp, shape->batch, st); }));
+    // The selection in one launch when all its workgroups are resident at once (they wait for
+    // one another's counts), else in two.
+    const bool one = want_idx && ctx->opt_topk_two_launches == 0 &&
+                     topk_one_launch_fits(tp, shape->batch, ctx->n_cus, ctx->topk_occupancy);
+    ctx->last_topk_launches = !want_idx ? 0 : one ? 1 : 2;
+    if (one) {
+        HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_topk(tp, shape->batch, 2, ctx->n_cus, st); }));
+        return HYLRA_OK;
+    }
     for (int step = 0; step < (want_idx ? 2 : 1); ++step)
         HIP_TRY(ctx, launch_timed(ctx, 1, st, [&] { return launch_topk(tp, shape->batch, step, ctx->n_cus, st); }));
     return HYLRA_OK;

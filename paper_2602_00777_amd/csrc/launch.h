@@ -94,6 +94,9 @@ struct TopkParams {
     int2* chunk_info;               // [B*Hkv][max_chunks] {rows above the threshold bin, rows in it}
     int2* chunk_list;               // [B*Hkv][max_chunks][kTopkChunkList] {key, position} of the rows in it
     int max_chunks;
+    uint64_t* headers;              // one-launch form: [B*Hkv][max_chunks][max_chunks] 64-bit {counts, tag} units
+                                    // (receiver, sender), all zero between launches; nullptr: not available
+    int* err_word;                  // pinned host word set if a bounded wait runs out
     int merge_wgs, merge_lanes;     // workgroups per pair that merge the partials, lanes per output (set by launch_topk)
     int chunks;                     // chunks per (batch, KV head) of this launch (set by launch_topk)
     int64_t pairs;                  // B * Hkv (set by launch_topk)
@@ -101,8 +104,13 @@ struct TopkParams {
 constexpr int kTopkChunkRows = 8192;    // rows of a (batch, KV head) per selecting workgroup
 constexpr int kTopkChunkList = 512;     // rows of the level-1 threshold bin a chunk can list
 hipError_t launch_score_hist(const TopkParams& p, int B, hipStream_t st);
-// step 0: level-1 threshold, per-chunk counts and lists, merge of the partials; step 1: emission
+// step 0: level-1 threshold, per-chunk counts and lists, merge of the partials; step 1: emission;
+// step 2: both in one launch (only if topk_one_launch_fits)
 hipError_t launch_topk(const TopkParams& p, int B, int step, int n_cus, hipStream_t st);
+// Workgroups of the one-launch kernel a compute unit holds at once (a host-side query; 0 on failure).
+int topk_one_launch_occupancy();
+// Whether every workgroup of the one-launch form would be resident at once (they wait for one another).
+bool topk_one_launch_fits(const TopkParams& p, int B, int n_cus, int occupancy);
 
 // Merge by packets (reuse_tail.h): 64-bit units a thread of a consuming workgroup polls at most,
 // i.e. a workgroup of T threads receives at most kPacketUnitsPerThread * T units.

@@ -97,20 +97,98 @@ struct ChunkRows {
     DEVI uint32_t key(int j, int e) const { return ordered_key(f4_at(v[j], e)); }
 };
 
-// ---- first kernel: level-1 threshold, counts and lists per chunk; merge of the partials ----
-__global__ __launch_bounds__(SEL_THREADS) void topk_scan_kernel(TopkParams p) {
+// ---- scan: level-1 threshold, the chunk's count and list ----
+// ONE: the one-launch form (topk_one_kernel): the list leaves with agent-scope stores, and once
+// they are acknowledged a header {rows above T1, rows in T1} goes to every chunk of the pair.
+constexpr int kTopkHdrBits = 14;        // both header fields are <= 8192
+constexpr uint32_t kTopkHdrFull = 1u;
+constexpr int kTopkHdrSpins = 1 << 18;
+constexpr int kTopkOneMaxChunks = 256;  // chunks per pair the one-launch form is built for
+
+template <bool ONE>
+DEVI void scan_part(const TopkParams& p, int64_t pair, int c, const ChunkRows& rows, int N, int k, int& T1, int& above1) {
     __shared__ int s_wave[SEL_WAVES + 1];
     __shared__ int s_pick[2];
     __shared__ int s_n, s_above;
     __shared__ int2 s_list[kTopkChunkList];
-
-    const int C = p.chunks;
-    int64_t pair;
-    int c;
-    if (!xcd_pair_role(C + p.merge_wgs, p.pairs, pair, c)) return;
-    const int b = (int)(pair / p.Hkv), g = (int)(pair - (int64_t)b * p.Hkv);
     const int tid = threadIdx.x, lane = tid & 63;
+    int h4[4];
+    {
+        const int4 h = *reinterpret_cast<const int4*>(p.ghist + pair * SEL_BINS + SEL_BINS - 4 - 4 * tid);
+        h4[0] = h.w, h4[1] = h.z, h4[2] = h.y, h4[3] = h.x;
+    }
+    if (tid == 0) s_n = 0, s_above = 0, s_pick[0] = SEL_BINS, s_pick[1] = 0;
+    HYLRA_TS(4);
 
+    // ---- level 1: threshold bin of the complete histogram (the same in every chunk) ----
+    threshold_pick(h4, k, s_wave, s_pick, T1, above1);
+    HYLRA_TS(5);
+    if (!ONE && c == 0 && tid == 0) p.pair_info[pair] = make_int2(T1, above1);
+
+    // ---- the chunk's rows: above bin T1 (counted), in it (listed) ----
+    const uint32_t lo_key = (uint32_t)T1 << 20, top_key = lo_key | 0xFFFFFu;      // bin T1 = [lo_key, top_key]
+    int above = 0, mine = 0;
+    uint32_t in_bin = 0;
+#pragma unroll
+    for (int j = 0; j < E_OWN; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (4 * rows.grp(j) + e >= N || T1 >= SEL_BINS) continue;
+            const uint32_t key = rows.key(j, e);
+            above += key > top_key;
+            if (key >= lo_key && key <= top_key) in_bin |= 1u << (4 * j + e), ++mine;
+        }
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) above += __shfl_xor(above, m, 64);
+    if (lane == 0 && above) atomicAdd(&s_above, above);
+    HYLRA_TS(2);
+    // list entries are reserved per wave: a prefix sum over the lanes and ONE atomic on the list's
+    // counter (an atomic per lane on that single LDS address is served lane by lane: 1024 of them
+    // took 2.6 us here)
+    const int incl = wave_incl_scan_dpp(mine);
+    int wave_base = 0;
+    if (lane == 63) wave_base = atomicAdd(&s_n, incl);
+    int slot = __shfl(wave_base, 63, 64) + incl - mine;
+#pragma unroll
+    for (int j = 0; j < E_OWN; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if ((in_bin >> (4 * j + e)) & 1u) {
+                if (slot < kTopkChunkList) s_list[slot] = make_int2((int)rows.key(j, e), 4 * rows.grp(j) + e);
+                ++slot;
+            }
+    HYLRA_TS(3);
+    __syncthreads();
+    HYLRA_TS(6);
+    const int n = s_n;                           // may exceed the list: the emission then scans all rows
+    const int64_t cslot = pair * p.max_chunks + c;
+    int2* __restrict__ gl = p.chunk_list + cslot * kTopkChunkList;
+    if (!ONE) {
+        for (int i = tid; i < min(n, kTopkChunkList); i += SEL_THREADS) gl[i] = s_list[i];
+        if (tid == 0) p.chunk_info[cslot] = make_int2(s_above, n);
+    } else {
+        // (entries as 64-bit agent-scope stores: the readers are other workgroups of this launch)
+        for (int i = tid; i < min(n, kTopkChunkList); i += SEL_THREADS) {
+            const int2 e = s_list[i];
+            __hip_atomic_store(reinterpret_cast<uint64_t*>(gl + i), ((uint64_t)(uint32_t)e.y << 32) | (uint32_t)e.x,
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        wait_vmem();
+        __syncthreads();                         // every entry of the list has been acknowledged
+        const uint64_t hdr = ((uint64_t)kTopkHdrFull << 32) | ((uint32_t)s_above << kTopkHdrBits) | (uint32_t)n;
+        const int MC = p.max_chunks;
+        for (int t = tid; t < p.chunks; t += SEL_THREADS)
+            __hip_atomic_store(p.headers + ((pair * MC + t) * MC + c), hdr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    HYLRA_TS(7);
+}
+
+// ---- merge of the attention partials (the pair's workgroups C .. C + merge_wgs - 1, or its
+// chunk 0 in passing when merge_wgs = 0).  Returns true for a workgroup that has nothing else
+// to do. ----
+DEVI bool merge_part(const TopkParams& p, int64_t pair, int b, int g, int c) {
+    const int C = p.chunks;
+    const int tid = threadIdx.x;
     // ---- attention output (the pair's last merge_wgs workgroups): L lanes per output element,
     // each lane merging every L-th partial with the loads of four partials in flight at once,
     // then a log-sum-exp merge across the L lanes.  L and the number of workgroups are chosen
@@ -165,73 +243,34 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_scan_kernel(TopkParams p) {
             }
             if (live && sub == 0) p.out[(head0 + h) * D + col] = den > 0.f ? num / den : 0.f;
         }
-        if (c >= C) return;
     }
+    return c >= C;
+
+}
+
+// ---- first kernel: level-1 threshold, counts and lists per chunk; merge of the partials ----
+__global__ __launch_bounds__(SEL_THREADS) void topk_scan_kernel(TopkParams p) {
+    const int C = p.chunks;
+    int64_t pair;
+    int c;
+    if (!xcd_pair_role(C + p.merge_wgs, p.pairs, pair, c)) return;
+    const int b = (int)(pair / p.Hkv), g = (int)(pair - (int64_t)b * p.Hkv);
+    if (merge_part(p, pair, b, g, c)) return;
 
     // this sequence ranks its first N rows and selects k of them
     const int N = seq_units(p.seq_lens, b, p.N, p.sel_block), k = min(p.k, N);
-    const float* __restrict__ sc = p.scores + pair * p.score_stride;
     ChunkRows rows;
-    rows.load(sc, (N + 3) >> 2, c);
-    int h4[4];
-    {
-        const int4 h = *reinterpret_cast<const int4*>(p.ghist + pair * SEL_BINS + SEL_BINS - 4 - 4 * tid);
-        h4[0] = h.w, h4[1] = h.z, h4[2] = h.y, h4[3] = h.x;
-    }
-    if (tid == 0) s_n = 0, s_above = 0, s_pick[0] = SEL_BINS, s_pick[1] = 0;
-    HYLRA_TS(4);
-
-    // ---- level 1: threshold bin of the complete histogram (the same in every chunk) ----
+    rows.load(p.scores + pair * p.score_stride, (N + 3) >> 2, c);
     int T1, above1;
-    threshold_pick(h4, k, s_wave, s_pick, T1, above1);
-    HYLRA_TS(5);
-    if (c == 0 && tid == 0) p.pair_info[pair] = make_int2(T1, above1);
-
-    // ---- the chunk's rows: above bin T1 (counted), in it (listed) ----
-    const uint32_t lo_key = (uint32_t)T1 << 20, top_key = lo_key | 0xFFFFFu;      // bin T1 = [lo_key, top_key]
-    int above = 0, mine = 0;
-    uint32_t in_bin = 0;
-#pragma unroll
-    for (int j = 0; j < E_OWN; ++j)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            if (4 * rows.grp(j) + e >= N || T1 >= SEL_BINS) continue;
-            const uint32_t key = rows.key(j, e);
-            above += key > top_key;
-            if (key >= lo_key && key <= top_key) in_bin |= 1u << (4 * j + e), ++mine;
-        }
-#pragma unroll
-    for (int m = 1; m < 64; m <<= 1) above += __shfl_xor(above, m, 64);
-    if (lane == 0 && above) atomicAdd(&s_above, above);
-    HYLRA_TS(2);
-    // list entries are reserved per wave: a prefix sum over the lanes and ONE atomic on the list's
-    // counter (an atomic per lane on that single LDS address is served lane by lane: 1024 of them
-    // took 2.6 us here)
-    const int incl = wave_incl_scan_dpp(mine);
-    int wave_base = 0;
-    if (lane == 63) wave_base = atomicAdd(&s_n, incl);
-    int slot = __shfl(wave_base, 63, 64) + incl - mine;
-#pragma unroll
-    for (int j = 0; j < E_OWN; ++j)
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if ((in_bin >> (4 * j + e)) & 1u) {
-                if (slot < kTopkChunkList) s_list[slot] = make_int2((int)rows.key(j, e), 4 * rows.grp(j) + e);
-                ++slot;
-            }
-    HYLRA_TS(3);
-    __syncthreads();
-    HYLRA_TS(6);
-    const int n = s_n;                           // may exceed the list: the second kernel then scans all rows
-    const int64_t cslot = pair * p.max_chunks + c;
-    int2* __restrict__ gl = p.chunk_list + cslot * kTopkChunkList;
-    for (int i = tid; i < min(n, kTopkChunkList); i += SEL_THREADS) gl[i] = s_list[i];
-    if (tid == 0) p.chunk_info[cslot] = make_int2(s_above, n);
-    HYLRA_TS(7);
+    scan_part<false>(p, pair, c, rows, N, k, T1, above1);
 }
 
-// ---- second kernel: levels 2 and 3, ordered emission ----
-__global__ __launch_bounds__(SEL_THREADS) void topk_emit_kernel(TopkParams p) {
+// ---- emission: levels 2 and 3, ordered output of the chunk's selected rows ----
+// rows: the chunk's rows (first4 set); T1, kr1: level-1 threshold bin and the rows of it that
+// are selected.  ONE: the one-launch form -- the chunks' counts come from the headers this
+// workgroup polls, their lists through agent-scope loads.
+template <bool ONE>
+DEVI void emit_part(const TopkParams& p, int64_t pair, int c, const ChunkRows& rows, int N, int k, int T1, int kr1) {
     __shared__ int s_hist[kTopkFineBins];
     __shared__ uint32_t s_ckey[SEL_CAP];
     __shared__ int s_cpos[SEL_CAP];
@@ -243,34 +282,43 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_emit_kernel(TopkParams p) {
     __shared__ int s_p1[kTopkList];                    // ... and positions
     __shared__ int s_n1, s_cand, s_before, s_before_eq, s_kr, s_overflow;
     __shared__ uint32_t s_tau;
+    __shared__ uint32_t s_hdr[ONE ? kTopkOneMaxChunks : 1];
 
     const int C = p.chunks;
-    int64_t pair;
-    int c;
-    if (!xcd_pair_role(C, p.pairs, pair, c)) return;
-    const int b = (int)(pair / p.Hkv);
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-
-    const int N = seq_units(p.seq_lens, b, p.N, p.sel_block), k = min(p.k, N);
     const int n4 = (N + 3) >> 2;
     const float* __restrict__ sc = p.scores + pair * p.score_stride;
     const float4* __restrict__ sc4 = reinterpret_cast<const float4*>(sc);
     int32_t* __restrict__ dst = p.idx + pair * (int64_t)p.k;
     if (c == 0)
         for (int i = k + tid; i < p.k; i += SEL_THREADS) dst[i] = -1;  // entries beyond a short sequence
-
-    ChunkRows rows;
-    rows.load(sc, n4, c);
     const int first4 = rows.first4;
     const int chunk_pos0 = 4 * first4, chunk_pos1 = chunk_pos0 + kTopkChunkRows;
-    const int2 info = p.pair_info[pair];
-    const int T1 = info.x, kr1 = k - info.y;     // level-1 threshold bin; rows of it that are selected
     for (int i = tid; i < kTopkFineBins; i += SEL_THREADS) s_hist[i] = 0;
     s_sel[tid] = 0;
     if (tid == 0) s_n1 = 0, s_cand = 0, s_before = 0, s_before_eq = 0, s_overflow = 0, s_pick[0] = SEL_BINS, s_pick[1] = 0;
-    // the level-1 histogram has been read by every chunk (in the first kernel): leave it empty
-    if (c == 0) *reinterpret_cast<int4*>(p.ghist + pair * SEL_BINS + 4 * tid) = make_int4(0, 0, 0, 0);
+    if (ONE) {
+        // the headers of the pair's chunks, this one's included: one thread each polls (bounded),
+        // keeps the value and leaves the unit empty for the next launch
+        const int MC = p.max_chunks;
+        for (int t = tid; t < C; t += SEL_THREADS) {
+            uint64_t* u = p.headers + ((pair * MC + c) * MC + t);
+            uint64_t v = 0;
+            bool ok = false;
+            for (int spin = 0; spin < kTopkHdrSpins && !ok; ++spin) {
+                if (spin) __builtin_amdgcn_s_sleep(1);
+                v = __hip_atomic_load(u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ok = (uint32_t)(v >> 32) == kTopkHdrFull;
+            }
+            s_hdr[t] = ok ? (uint32_t)v : 0u;
+            __hip_atomic_store(u, (uint64_t)0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (!ok && p.err_word) __hip_atomic_store(p.err_word, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        }
+    }
     __syncthreads();
+    // every chunk of the pair has read the level-1 histogram (in the first kernel, or -- one
+    // launch -- before it sent the header this workgroup now holds): leave it empty
+    if (c == 0) *reinterpret_cast<int4*>(p.ghist + pair * SEL_BINS + 4 * tid) = make_int4(0, 0, 0, 0);
     HYLRA_TS(8);
 
     // ---- the pair's rows of bin T1 from the chunks' lists into LDS (wave w takes chunks w,
@@ -278,7 +326,8 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_emit_kernel(TopkParams p) {
     int before = 0;                              // selected rows of the chunks before this one
     for (int cc = wave; cc < C; cc += SEL_WAVES) {
         const int64_t cslot = pair * p.max_chunks + cc;
-        const int2 ci = p.chunk_info[cslot];
+        const int2 ci = ONE ? make_int2((int)(s_hdr[cc] >> kTopkHdrBits), (int)(s_hdr[cc] & ((1u << kTopkHdrBits) - 1u)))
+                            : p.chunk_info[cslot];
         if (ci.y > kTopkChunkList) {
             if (lane == 0) s_overflow = 1;
             continue;
@@ -289,7 +338,13 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_emit_kernel(TopkParams p) {
         base = __shfl(base, 0, 64);
         const int2* __restrict__ gl = p.chunk_list + cslot * kTopkChunkList;
         for (int i = lane; i < ci.y; i += 64) {
-            const int2 kp = gl[i];
+            int2 kp;
+            if (ONE) {
+                const uint64_t e = __hip_atomic_load(reinterpret_cast<const uint64_t*>(gl + i), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                kp = make_int2((int)(uint32_t)e, (int)(uint32_t)(e >> 32));
+            } else {
+                kp = gl[i];
+            }
             if (base + i < kTopkList) {
                 s_k1[base + i] = (uint32_t)kp.x;
                 s_p1[base + i] = kp.y;
@@ -490,6 +545,39 @@ __global__ __launch_bounds__(SEL_THREADS) void topk_emit_kernel(TopkParams p) {
     HYLRA_TS(13);
 }
 
+// ---- second kernel: levels 2 and 3, ordered emission ----
+__global__ __launch_bounds__(SEL_THREADS) void topk_emit_kernel(TopkParams p) {
+    int64_t pair;
+    int c;
+    if (!xcd_pair_role(p.chunks, p.pairs, pair, c)) return;
+    const int b = (int)(pair / p.Hkv);
+    const int N = seq_units(p.seq_lens, b, p.N, p.sel_block), k = min(p.k, N);
+    ChunkRows rows;
+    rows.load(p.scores + pair * p.score_stride, (N + 3) >> 2, c);
+    const int2 info = p.pair_info[pair];         // level-1 threshold bin; rows in the bins above it
+    emit_part<false>(p, pair, c, rows, N, k, info.x, k - info.y);
+}
+
+// ---- both in one launch, for launches whose workgroups are all resident at once (the host
+// checks).  What crosses workgroups between the two parts -- every chunk's count and list --
+// travels as in the Reuse layer's merge by packets: the list with agent-scope stores, and once
+// those are acknowledged a 64-bit header {counts, tag} to every chunk of the pair, which the
+// receiver polls (bounded), takes and clears.  The chunk's rows stay in registers across the two
+// parts, so the scores are read once; one launch and its gap are saved. ----
+__global__ __launch_bounds__(SEL_THREADS) void topk_one_kernel(TopkParams p) {
+    int64_t pair;
+    int c;
+    if (!xcd_pair_role(p.chunks + p.merge_wgs, p.pairs, pair, c)) return;
+    const int b = (int)(pair / p.Hkv), g = (int)(pair - (int64_t)b * p.Hkv);
+    if (merge_part(p, pair, b, g, c)) return;
+    const int N = seq_units(p.seq_lens, b, p.N, p.sel_block), k = min(p.k, N);
+    ChunkRows rows;
+    rows.load(p.scores + pair * p.score_stride, (N + 3) >> 2, c);
+    int T1, above1;
+    scan_part<true>(p, pair, c, rows, N, k, T1, above1);
+    emit_part<true>(p, pair, c, rows, N, k, T1, k - above1);
+}
+
 // ---- level-1 histogram in a launch of its own, for the streaming kernels that do not bin ----
 // grid (chunks of 8192 rows, Hkv, B); the non-empty bins of a chunk are added to the pair's
 // histogram with device-scope atomics.
@@ -521,12 +609,12 @@ hipError_t launch_score_hist(const TopkParams& p, int B, hipStream_t st) {
     return hipGetLastError();
 }
 
-// step 0: scan (+ merge of the partials); step 1: emit.  p.idx == nullptr: merge only (step 0).
-hipError_t launch_topk(const TopkParams& p, int B, int step, int n_cus, hipStream_t st) {
-    TopkParams q = p;
+// chunks, pairs, merge lanes and merge workgroups of a launch
+static bool plan_topk(const TopkParams& p, int B, int n_cus, TopkParams& q) {
+    q = p;
     q.chunks = p.idx ? (p.N + kTopkChunkRows - 1) / kTopkChunkRows : 0;
     q.pairs = (int64_t)B * p.Hkv;
-    if (q.chunks > p.max_chunks) return hipErrorInvalidValue;
+    if (q.chunks > p.max_chunks) return false;
     // merge of the partials: lanes per output so that a lane has at most four partials (up to 16
     // lanes), workgroups so that one sweep covers the pair's outputs (up to 16 workgroups)
     q.merge_lanes = 1;
@@ -536,12 +624,38 @@ hipError_t launch_topk(const TopkParams& p, int B, int step, int n_cus, hipStrea
     // few partials and already more workgroups than can be resident at once (two per compute
     // unit): the pair's first chunk does the merge in passing
     if (q.chunks > 0 && q.merge_lanes == 1 && q.merge_wgs == 1 && q.pairs * (q.chunks + 1) > 2 * (int64_t)n_cus) q.merge_wgs = 0;
-    const int per_pair = step == 0 ? q.chunks + q.merge_wgs : q.chunks;
+    return true;
+}
+
+int topk_one_launch_occupancy() {
+    int occ = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&occ, topk_one_kernel, SEL_THREADS, 0) != hipSuccess) return 0;
+    return occ;
+}
+
+bool topk_one_launch_fits(const TopkParams& p, int B, int n_cus, int occupancy) {
+    TopkParams q;
+    if (!p.idx || !p.headers || !plan_topk(p, B, n_cus, q)) return false;
+    const int64_t wgs = (q.pairs + 7) / 8 * 8 * (q.chunks + q.merge_wgs);
+    // (no more workgroups than compute units, although a unit holds `occupancy` of them: that is
+    // where one launch wins -- with two workgroups per unit, config 2's 320 and config 4's 512,
+    // it only ties with scan + emit -- and it leaves room for whatever else is running)
+    return q.chunks >= 1 && q.chunks <= kTopkOneMaxChunks && occupancy >= 1 && wgs <= (int64_t)n_cus;
+}
+
+// step 0: scan (+ merge of the partials); step 1: emit; step 2: both in one launch.
+// p.idx == nullptr: merge only (step 0).
+hipError_t launch_topk(const TopkParams& p, int B, int step, int n_cus, hipStream_t st) {
+    TopkParams q;
+    if (!plan_topk(p, B, n_cus, q)) return hipErrorInvalidValue;
+    if (step == 2 && (!p.headers || q.chunks < 1 || q.chunks > kTopkOneMaxChunks)) return hipErrorInvalidValue;
+    const int per_pair = step == 1 ? q.chunks : q.chunks + q.merge_wgs;
     const int64_t wgs = (q.pairs + 7) / 8 * 8 * per_pair;
     if (wgs > 0x7fffffff) return hipErrorInvalidValue;
     if (wgs == 0) return hipSuccess;
     if (step == 0) hipLaunchKernelGGL(topk_scan_kernel, dim3((unsigned)wgs), dim3(SEL_THREADS), 0, st, q);
-    else hipLaunchKernelGGL(topk_emit_kernel, dim3((unsigned)wgs), dim3(SEL_THREADS), 0, st, q);
+    else if (step == 1) hipLaunchKernelGGL(topk_emit_kernel, dim3((unsigned)wgs), dim3(SEL_THREADS), 0, st, q);
+    else hipLaunchKernelGGL(topk_one_kernel, dim3((unsigned)wgs), dim3(SEL_THREADS), 0, st, q);
     return hipGetLastError();
 }
 

@@ -97,8 +97,8 @@ def test_full_self_scheduling_kernel(B, Hkv, G, d, N, k, variant):
 
 @pytest.mark.parametrize("N,k", [(5003, 300), (20000, 1500), (40000, 3000)])
 def test_finalize_paths(N, k):
-    """The selection kernels with the first histogram made inside the streaming kernel or by a
-    launch of its own, including the many-ties fallbacks (a chunk's list overflowing; more
+    """The selection, in one launch and in two, with the first histogram made inside the streaming
+    kernel or by a launch of its own, including the many-ties fallbacks (a chunk's list overflowing; more
     tied candidates than can be ranked), at sizes that span one to several chunks."""
     say("finalize paths N=%d k=%d" % (N, k))
     B, Hkv, G, d = 1, 2, 4, 64
@@ -111,14 +111,17 @@ def test_finalize_paths(N, k):
            oracle.full_attn_topk(qt, Kt, V, k, want_shat=True),
            oracle.full_attn_topk(q, Kz, V, k, want_shat=True)]
     with binding.Context(B, Hkv * G, Hkv, d, N, k) as ctx:
-        for unfused in (0, 1):
+        for unfused, two in ((0, 0), (1, 0), (0, 1), (1, 1)):
             ctx.set_option("hist_unfused", unfused)
-            for (qq, KK), (ro, ri, rs), exact in (((q, K), ref[0], False), ((qt, Kt), ref[1], True), ((q, Kz), ref[2], True)):
-                out, idx = run_full(ctx, qq, KK, V, k)
-                assert_out_close(out, ro, "out")
-                assert_idx_valid(idx, rs, k, "idx", exact_ref=ri)
-                if exact:      # d = 64 and integer inputs: scores are exact, sets must be equal
-                    assert np.array_equal(idx, ri)
+            ctx.set_option("topk_two_launches", two)     # the selection in one launch, or as scan + emit
+            for rep in range(2):                         # (launch after launch: the headers are left empty)
+                for (qq, KK), (ro, ri, rs), exact in (((q, K), ref[0], False), ((qt, Kt), ref[1], True), ((q, Kz), ref[2], True)):
+                    out, idx = run_full(ctx, qq, KK, V, k)
+                    assert ctx.get_info("last_topk_launches") == 1 + two
+                    assert_out_close(out, ro, "out")
+                    assert_idx_valid(idx, rs, k, "idx", exact_ref=ri)
+                    if exact:      # d = 64 and integer inputs: scores are exact, sets must be equal
+                        assert np.array_equal(idx, ri)
 
 
 @pytest.mark.parametrize("unroll", [1, 2, 4, 8])
@@ -580,7 +583,21 @@ def test_profile_and_probe_aids():
             ctx.reuse_sparse_attn(q, K, V, idx)
         torch.cuda.synchronize()
         prof = ctx.profile_read()
-        assert prof["full_attn"][0] == 1 and prof["full_finalize"][0] == 2      # streaming pass; scan + emit of the selection
+        assert prof["full_attn"][0] == 1 and prof["full_finalize"][0] == 1      # streaming pass; the selection in one launch
+        assert ctx.get_info("last_topk_launches") == 1
+        ctx.set_option("topk_two_launches", 1)
+        ctx.profile_reset()
+        out2, idx2 = ctx.full_attn_topk(q, K, V, k)
+        torch.cuda.synchronize()
+        assert ctx.profile_read()["full_finalize"][0] == 2 and ctx.get_info("last_topk_launches") == 2   # scan + emit
+        assert torch.equal(idx2, idx)
+        ctx.set_option("topk_two_launches", 0)
+        ctx.profile_reset()
+        ctx.full_attn_topk(q, K, V, k)
+        for _ in range(3):
+            ctx.reuse_sparse_attn(q, K, V, idx)
+        torch.cuda.synchronize()
+        prof = ctx.profile_read()
         assert prof["reuse_attn"][0] == 3 and prof["reuse_combine"][0] == 0
         for name in ("full_attn", "full_finalize", "reuse_attn"):
             assert 0.0 < prof[name][1] < 50.0          # milliseconds
