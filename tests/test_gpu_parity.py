@@ -323,6 +323,41 @@ def test_reuse_packet_merge_equals_two_kernel_merge(B, Hkv, G, k, unroll):
     assert_out_close(two.cpu().numpy(), oracle.reuse_sparse_attn(q, K, V, idx), "reuse out")
 
 
+def test_two_contexts_on_two_streams_share_the_device():
+    """Two contexts, each on a stream of its own, run launches whose workgroups wait for one
+    another (Reuse merge by packets, one-launch selection) at the same time: each launch holds
+    at most one workgroup per compute unit, so both fit, and the results are those of running
+    them one after the other."""
+    say("two contexts on two streams")
+    B, Hkv, G, d, N, k = 1, 8, 4, 128, 8192, 2048
+    cases = [rand_case(330 + i, B, Hkv, G, d, N) for i in range(2)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    with binding.Context(B, Hkv * G, Hkv, d, N, k) as c0, binding.Context(B, Hkv * G, Hkv, d, N, k) as c1:
+        ctxs = [c0, c1]
+        want = []
+        for ctx, (q, K, V) in zip(ctxs, cases):
+            out, idx = ctx.full_attn_topk(q, K, V, k)
+            sparse = ctx.reuse_sparse_attn(q, K, V, idx)
+            torch.cuda.synchronize()
+            assert ctx.get_info("last_reuse_merge") == 2 and ctx.get_info("last_topk_launches") == 1
+            want.append((out.clone(), idx.clone(), sparse.clone()))
+        got = [[], []]
+        torch.cuda.synchronize()
+        for rep in range(10):
+            for i, (ctx, (q, K, V)) in enumerate(zip(ctxs, cases)):
+                with torch.cuda.stream(streams[i]):
+                    out, idx = ctx.full_attn_topk(q, K, V, k)
+                    sparse = ctx.reuse_sparse_attn(q, K, V, idx)
+                    got[i].append((out, idx, sparse))
+        torch.cuda.synchronize()
+    for i in range(2):
+        for rep, (out, idx, sparse) in enumerate(got[i]):
+            assert torch.equal(idx, want[i][1]), "context %d launch %d: index set" % (i, rep)
+            assert torch.equal(sparse, want[i][2]), "context %d launch %d: Reuse output" % (i, rep)
+            err = (out - want[i][0]).abs().max().item() / want[i][0].abs().max().item()
+            assert err < 1e-5, "context %d launch %d: Full output differs by %.2e" % (i, rep, err)
+
+
 def test_reuse_padding_order_and_out_of_range_entries():
     say("reuse padding")
     B, Hkv, G, d, N, k = 1, 2, 4, 128, 1000, 200
