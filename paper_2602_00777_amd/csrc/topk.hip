@@ -118,11 +118,11 @@ DEVI void scan_part(const TopkParams& p, int64_t pair, int c, const ChunkRows& r
         h4[0] = h.w, h4[1] = h.z, h4[2] = h.y, h4[3] = h.x;
     }
     if (tid == 0) s_n = 0, s_above = 0, s_pick[0] = SEL_BINS, s_pick[1] = 0;
-    HYLRA_TS(4);
+    HYLRA_TS_SEL(4);
 
     // ---- level 1: threshold bin of the complete histogram (the same in every chunk) ----
     threshold_pick(h4, k, s_wave, s_pick, T1, above1);
-    HYLRA_TS(5);
+    HYLRA_TS_SEL(5);
     if (!ONE && c == 0 && tid == 0) p.pair_info[pair] = make_int2(T1, above1);
 
     // ---- the chunk's rows: above bin T1 (counted), in it (listed) ----
@@ -141,7 +141,7 @@ DEVI void scan_part(const TopkParams& p, int64_t pair, int c, const ChunkRows& r
 #pragma unroll
     for (int m = 1; m < 64; m <<= 1) above += __shfl_xor(above, m, 64);
     if (lane == 0 && above) atomicAdd(&s_above, above);
-    HYLRA_TS(2);
+    HYLRA_TS_SEL(2);
     // list entries are reserved per wave: a prefix sum over the lanes and ONE atomic on the list's
     // counter (an atomic per lane on that single LDS address is served lane by lane: 1024 of them
     // took 2.6 us here)
@@ -157,9 +157,9 @@ DEVI void scan_part(const TopkParams& p, int64_t pair, int c, const ChunkRows& r
                 if (slot < kTopkChunkList) s_list[slot] = make_int2((int)rows.key(j, e), 4 * rows.grp(j) + e);
                 ++slot;
             }
-    HYLRA_TS(3);
+    HYLRA_TS_SEL(3);
     __syncthreads();
-    HYLRA_TS(6);
+    HYLRA_TS_SEL(6);
     const int n = s_n;                           // may exceed the list: the emission then scans all rows
     const int64_t cslot = pair * p.max_chunks + c;
     int2* __restrict__ gl = p.chunk_list + cslot * kTopkChunkList;
@@ -180,7 +180,7 @@ DEVI void scan_part(const TopkParams& p, int64_t pair, int c, const ChunkRows& r
         for (int t = tid; t < p.chunks; t += SEL_THREADS)
             __hip_atomic_store(p.headers + ((pair * MC + t) * MC + c), hdr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    HYLRA_TS(7);
+    HYLRA_TS_SEL(7);
 }
 
 // ---- merge of the attention partials (the pair's workgroups C .. C + merge_wgs - 1, or its
@@ -319,7 +319,7 @@ DEVI void emit_part(const TopkParams& p, int64_t pair, int c, const ChunkRows& r
     // every chunk of the pair has read the level-1 histogram (in the first kernel, or -- one
     // launch -- before it sent the header this workgroup now holds): leave it empty
     if (c == 0) *reinterpret_cast<int4*>(p.ghist + pair * SEL_BINS + 4 * tid) = make_int4(0, 0, 0, 0);
-    HYLRA_TS(8);
+    HYLRA_TS_SEL(8);
 
     // ---- the pair's rows of bin T1 from the chunks' lists into LDS (wave w takes chunks w,
     // w + 16, ...), and the rows above T1 in the chunks before this one ----
@@ -388,13 +388,13 @@ DEVI void emit_part(const TopkParams& p, int64_t pair, int c, const ChunkRows& r
         });
     }
     __syncthreads();
-    HYLRA_TS(9);
+    HYLRA_TS_SEL(9);
     int h4[4];
 #pragma unroll
     for (int e = 0; e < 4; ++e) h4[e] = s_hist[kTopkFineBins - 1 - (4 * tid + e)];
     int T2, above2;
     threshold_pick(h4, kr1, s_wave, s_pick, T2, above2);
-    HYLRA_TS(10);
+    HYLRA_TS_SEL(10);
     const int kr2 = kr1 - above2;                // rows with the top 24 bits (T1, T2) that are selected
     // (T1 = SEL_BINS when nothing is selected: thr24 is then above every 24-bit value)
     const uint32_t thr24 = ((uint32_t)T1 << 12) | (uint32_t)(T2 & (kTopkFineBins - 1));
@@ -425,7 +425,7 @@ DEVI void emit_part(const TopkParams& p, int64_t pair, int c, const ChunkRows& r
     if (lane == 0 && before) atomicAdd(&s_before, before);
     __syncthreads();
     const int n_cand = s_cand;
-    HYLRA_TS(11);
+    HYLRA_TS_SEL(11);
 
     unsigned long long sel = 0;                  // bit 4 j + e: element e of own register j is selected
     if (n_cand <= SEL_CAP) {
@@ -523,7 +523,7 @@ DEVI void emit_part(const TopkParams& p, int64_t pair, int c, const ChunkRows& r
         __syncthreads();
     }
     const int base0 = s_before;
-    HYLRA_TS(12);
+    HYLRA_TS_SEL(12);
 
     // ---- ordered emission of the chunk's selected rows ----
     int cnt[E_OWN], base[E_OWN];
@@ -542,7 +542,7 @@ DEVI void emit_part(const TopkParams& p, int64_t pair, int c, const ChunkRows& r
             ++o;
         }
     }
-    HYLRA_TS(13);
+    HYLRA_TS_SEL(13);
 }
 
 // ---- second kernel: levels 2 and 3, ordered emission ----
